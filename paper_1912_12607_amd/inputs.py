@@ -1,0 +1,126 @@
+"""Seeded synthetic inputs shaped like the paper's workloads.
+
+This module holds *no arithmetic of the method*: it only names the benchmark
+layers and draws x / w / dy from fixed distributions.  It is the one module
+that both the CPU oracle's tests and the GPU path's tests / benchmark use, so
+that both sides see identical arrays.
+
+Shapes follow the networks the paper trains (ResNet-18/50, MobileNetV2,
+InceptionV3; Tables 6-7).  The paper's datasets are not available, so the
+value distributions are stand-ins: activations are (clipped) normal, weights
+Kaiming-normal, output gradients heavy-tailed Student-t with a few large
+outliers -- the "sharp and wide" shape of Sec.3.2, characteristic C1.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, List, Tuple
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class Layer:
+    name: str
+    N: int
+    C: int
+    H: int
+    W: int
+    K: int
+    R: int
+    S: int
+    stride: Tuple[int, int] = (1, 1)
+    pad: Tuple[int, int] = (0, 0)
+    groups: int = 1
+    x_dist: str = "normal"        # normal | relu | relu6
+    dy_df: float = 3.0            # Student-t degrees of freedom
+    dy_scale: float = 1e-3
+    dy_outliers: bool = True      # 0.01 % of entries multiplied by 100
+
+    @property
+    def P(self) -> int:
+        return (self.H + 2 * self.pad[0] - self.R) // self.stride[0] + 1
+
+    @property
+    def Q(self) -> int:
+        return (self.W + 2 * self.pad[1] - self.S) // self.stride[1] + 1
+
+    @property
+    def x_shape(self):
+        return (self.N, self.C, self.H, self.W)
+
+    @property
+    def w_shape(self):
+        return (self.K, self.C // self.groups, self.R, self.S)
+
+    @property
+    def y_shape(self):
+        return (self.N, self.K, self.P, self.Q)
+
+    @property
+    def macs(self) -> int:
+        """Multiply-accumulates of one of the three convolution passes."""
+        return self.N * self.K * self.P * self.Q * (self.C // self.groups) * self.R * self.S
+
+
+# Index = position in the benchmark's config list.
+CONFIGS: Dict[int, List[Layer]] = {
+    0: [Layer("tiny3x3", 2, 16, 16, 16, 32, 3, 3, pad=(1, 1), x_dist="normal", dy_scale=1e-3)],
+    1: [Layer("resnet18_3x3", 64, 64, 56, 56, 64, 3, 3, pad=(1, 1), x_dist="relu", dy_scale=1e-4)],
+    2: [Layer("r50_1x1_reduce", 128, 1024, 14, 14, 256, 1, 1),
+        Layer("r50_3x3", 128, 256, 14, 14, 256, 3, 3, pad=(1, 1)),
+        Layer("r50_1x1_expand", 128, 256, 14, 14, 1024, 1, 1)],
+    3: [Layer("mbv2_expand", 64, 24, 56, 56, 144, 1, 1, x_dist="relu6", dy_df=2.0, dy_scale=1e-4,
+              dy_outliers=False),
+        Layer("mbv2_depthwise", 64, 144, 56, 56, 144, 3, 3, pad=(1, 1), groups=144, x_dist="relu6",
+              dy_df=2.0, dy_scale=1e-4, dy_outliers=False),
+        Layer("mbv2_project", 64, 144, 56, 56, 24, 1, 1, x_dist="relu6", dy_df=2.0, dy_scale=1e-4,
+              dy_outliers=False)],
+    4: [Layer("inc_1x7", 64, 768, 17, 17, 768, 1, 7, pad=(0, 3)),
+        Layer("inc_7x1", 64, 768, 17, 17, 768, 7, 1, pad=(3, 0)),
+        Layer("inc_3x3_s2", 64, 768, 17, 17, 192, 3, 3, stride=(2, 2), pad=(0, 0))],
+}
+
+# Default clip candidates of the search: ratio_j = 2^(-j/4), j = 0..31 (j = 0 is "no clipping").
+def default_ratios(n_cand: int = 32) -> np.ndarray:
+    return np.exp2(-np.arange(n_cand, dtype=np.float64) / 4.0).astype(np.float32)
+
+
+def _rng(seed: int, cfg: int, layer: int, tensor: int) -> np.random.Generator:
+    return np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, cfg, layer, tensor])))
+
+
+def make_x(L: Layer, cfg: int, li: int, seed: int = 0) -> np.ndarray:
+    r = _rng(seed, cfg, li, 0)
+    x = r.standard_normal(L.x_shape, dtype=np.float32)
+    if L.x_dist == "relu":
+        np.maximum(x, 0.0, out=x)
+    elif L.x_dist == "relu6":
+        np.clip(x, 0.0, 6.0, out=x)
+    return x
+
+
+def make_w(L: Layer, cfg: int, li: int, seed: int = 0) -> np.ndarray:
+    r = _rng(seed, cfg, li, 1)
+    fan_in = (L.C // L.groups) * L.R * L.S
+    w = r.standard_normal(L.w_shape, dtype=np.float32)
+    w *= np.float32(np.sqrt(2.0 / fan_in))
+    return w
+
+
+def make_dy(L: Layer, cfg: int, li: int, seed: int = 0) -> np.ndarray:
+    r = _rng(seed, cfg, li, 2)
+    n = int(np.prod(L.y_shape))
+    dy = r.standard_t(L.dy_df, size=n).astype(np.float32)
+    dy *= np.float32(L.dy_scale)
+    if L.dy_outliers:
+        k = int(round(1e-4 * n))
+        if k > 0:
+            pos = r.choice(n, size=k, replace=False)
+            dy[pos] *= np.float32(100.0)
+    return dy.reshape(L.y_shape)
+
+
+def make_layer_inputs(cfg: int, li: int, seed: int = 0):
+    L = CONFIGS[cfg][li]
+    return L, make_x(L, cfg, li, seed), make_w(L, cfg, li, seed), make_dy(L, cfg, li, seed)
