@@ -1,0 +1,195 @@
+/*
+ * int8t.h -- C ABI of the MI355X (gfx950) INT8 training-convolution library.
+ *
+ * The calls are the per-layer steps of "Towards Unified INT8 Training for
+ * Convolutional Neural Network":
+ *
+ *   int8t_quantize         Eq.1 (symmetric uniform quantizer, s = c/127) with
+ *                          round-to-nearest for activations / weights and the
+ *                          stochastic rounding of Eq.3 for output gradients;
+ *                          optionally reports the direction deviation of Eq.6.
+ *   int8t_dsgc_clip        Direction Sensitive Gradient Clipping (Sec.3.4): picks
+ *                          the clip value of the output gradient that minimises
+ *                          the cosine deviation d_c of Eq.6, as a search over
+ *                          caller-supplied candidates; also returns d_c, the
+ *                          scalar Eq.7 consumes.
+ *   int8t_conv_fwd         z  = q_a (*) q_W          int8 x int8 -> int32, then Eq.2
+ *   int8t_conv_bwd_data    g_a = q_gz (*)^T q_W      (Sec.3.4; Suppl. "INT8 Convolution")
+ *   int8t_conv_bwd_weight  g_W = q_gz^T q_a          (Sec.3.4)
+ *   int8t_dclr_scale       Eq.7, phi(d_c) = max(exp(-alpha d_c), beta)   (host)
+ *
+ * General conventions
+ *   - Every pointer named *_dev is DEVICE memory owned by the caller.  The library
+ *     never allocates, frees or keeps device memory between calls.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
+ *     work is enqueued asynchronously on it; no call synchronises with the host.
+ *   - Scalars that flow between calls (clip, scale, deviation) stay in device
+ *     memory, so the calls of one layer step chain without a host round trip.
+ *   - fp32 tensors are dense, in PyTorch's logical order: activations and
+ *     gradients N,C,H,W; weights K,C/groups,R,S.  They must be 16-byte aligned.
+ *   - Errors are return codes.  Argument errors are detected before anything is
+ *     launched; in that case no output is touched.
+ *   - `ws_dev` is scratch the caller provides; ask int8t_workspace_bytes() how
+ *     much a call needs.  Its contents need no initialisation and are
+ *     unspecified afterwards.  Two calls that run concurrently (different
+ *     streams) must not share scratch.
+ *   - Inputs must be finite.  NaN quantizes to code 0; results derived from
+ *     non-finite inputs are otherwise unspecified (but memory safe).
+ *
+ * Layout of int8 code tensors (the library's own; Suppl. "INT8 Convolution"
+ * packs the reduction dimension innermost for the dot-product instruction, and
+ * so do we, in granules of 16 bytes for the int8 MFMA):
+ *   INT8T_ACT         dims {N,C,H,W}: codes[((n*H + h)*W + w)*Cp + c], Cp = C rounded up
+ *                     to a multiple of 16, bytes c >= C are zero.  N*H*W*Cp bytes.
+ *   INT8T_ACT_PLANAR  dims {N,C,H,W}: codes in logical N,C,H,W order (depthwise layers).
+ *   INT8T_WGT         dims {K,Cg,R,S} (Cg = C/groups, groups == 1): two copies,
+ *                       [0, K*R*S*Cp):             codes[((k*R + r)*S + s)*Cp + c]
+ *                       [align256(K*R*S*Cp), ...): codes[((c*R + r)*S + s)*Kp + k]
+ *                     (the second serves backward-data), Cp/Kp rounded up to 16, pad zero.
+ *   INT8T_WGT_PLANAR  dims {K,Cg,R,S}: codes in logical order (depthwise layers).
+ * int8t_code_bytes() returns the size of each.
+ *
+ * The stochastic draw of element i is a function of (seed, i) only, where i is
+ * the element's linear index in LOGICAL order, so codes do not depend on the
+ * code layout, the launch geometry or the clip search.
+ */
+#ifndef INT8T_H
+#define INT8T_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    INT8T_OK = 0,
+    INT8T_ERR_NULL = 1,       /* a required pointer is NULL */
+    INT8T_ERR_SHAPE = 2,      /* non-positive or unsupported dimensions */
+    INT8T_ERR_ARG = 3,        /* bad enum value, misaligned pointer, too many candidates */
+    INT8T_ERR_WORKSPACE = 4,  /* ws_bytes smaller than int8t_workspace_bytes() */
+    INT8T_ERR_RUNTIME = 5     /* a HIP launch failed */
+} int8t_status;
+
+typedef enum { INT8T_ROUND_NEAREST_EVEN = 0, INT8T_ROUND_STOCHASTIC = 1 } int8t_round;
+
+typedef enum {
+    INT8T_ACT = 0,
+    INT8T_WGT = 1,
+    INT8T_ACT_PLANAR = 2,
+    INT8T_WGT_PLANAR = 3
+} int8t_kind;
+
+typedef enum {
+    INT8T_OP_QUANTIZE = 0,
+    INT8T_OP_DSGC = 1,
+    INT8T_OP_CONV_FWD = 2,
+    INT8T_OP_CONV_BWD_DATA = 3,
+    INT8T_OP_CONV_BWD_WEIGHT = 4
+} int8t_op;
+
+/* Convolution geometry, PyTorch conventions: cross-correlation, zero padding,
+ * P = floor((H + 2 pad_h - R)/stride_h) + 1, dilation 1.  groups must be 1
+ * (dense; code layouts INT8T_ACT / INT8T_WGT) or C == K == groups (depthwise;
+ * INT8T_ACT_PLANAR / INT8T_WGT_PLANAR). */
+typedef struct {
+    int N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups;
+} int8t_conv_desc;
+
+#define INT8T_MAX_CANDIDATES 64
+
+const char *int8t_status_string(int8t_status s);
+
+/* Bytes of the int8 code tensor of `kind` for logical dims; 0 on bad input. */
+size_t int8t_code_bytes(const int dims[4], int8t_kind kind);
+
+/* Scratch a call needs.  DSGC: n = element count, n_cand = number of candidates, desc ignored.
+ * CONV_*: desc required, n / n_cand ignored.  QUANTIZE: use int8t_quantize_workspace_bytes()
+ * (this function returns 0 for it).  0 also means "bad arguments" for the CONV ops whose
+ * descriptor is invalid; the call itself then reports the error. */
+size_t int8t_workspace_bytes(int8t_op op, const int8t_conv_desc *desc, size_t n, int n_cand);
+
+/* Scratch of int8t_quantize for a tensor of logical dims and code layout `kind`; covers both the
+ * absmax pass (clip_dev == NULL) and the deviation output.  0 on bad input. */
+size_t int8t_quantize_workspace_bytes(const int dims[4], int8t_kind kind);
+
+/*
+ * Eq.1 / Eq.3.  Per element (fp32, each operation rounded once, no fused multiply-add):
+ *     inv = 127 / c;   t = min(max(x * inv, -127), 127)
+ *     nearest:    q = rint(t)                (ties to even)
+ *     stochastic: q = floor((floor(t * 2^24) + u) / 2^24),  u = 24 uniform bits drawn from
+ *                 (seed, logical index)  ==> q = floor(t) + 1 with probability frac(t).
+ *   x_dev          fp32 tensor, logical order, dims[0]*dims[1]*dims[2]*dims[3] elements
+ *   clip_dev       clip value c (1 float), or NULL: c = max|x| is computed first
+ *   q_dev          out: int8 codes in the layout of `kind`, int8t_code_bytes() bytes
+ *   scale_dev      out: 1 float, s = c / 127 (0 when c == 0, and then all codes are 0)
+ *   deviation_dev  NULL, or out: 1 double, d_c of Eq.6 between x and q*s
+ *                  (0 when x is all zero; 1 when every code is 0 but x is not)
+ */
+int8t_status int8t_quantize(const float *x_dev, const int dims[4], int8t_kind kind,
+                            const float *clip_dev, int8t_round mode, uint64_t seed,
+                            int8_t *q_dev, float *scale_dev, double *deviation_dev,
+                            void *ws_dev, size_t ws_bytes, void *stream);
+
+/*
+ * Clip search of Sec.3.4.  Candidates c_j = fl32(max|g| * ratios[j]), j < n_cand
+ * (1 <= n_cand <= INT8T_MAX_CANDIDATES).  For each, the tensor is quantized exactly
+ * as int8t_quantize(mode, seed) would, and d_j = 1 - cos(g, q*s) (Eq.6) is evaluated;
+ * the smallest d_j wins, ties go to the smallest j.
+ *   g_dev              fp32 tensor, n elements (n < 2^31), logical order
+ *   ratios_dev         n_cand floats in (0, 1]
+ *   clip_dev           out: 1 float, the winning c_j
+ *   deviation_dev      out: 1 double, its d_j
+ *   deviation_all_dev  NULL, or out: n_cand doubles, every d_j
+ */
+int8t_status int8t_dsgc_clip(const float *g_dev, size_t n, const float *ratios_dev, int n_cand,
+                             int8t_round mode, uint64_t seed,
+                             float *clip_dev, double *deviation_dev, double *deviation_all_dev,
+                             void *ws_dev, size_t ws_bytes, void *stream);
+
+/*
+ * Forward convolution on codes: acc[n,k,p,q] = sum_{c,r,s} xq[n,c,p*sh+r-ph,q*sw+s-pw] * wq[k,c,r,s]
+ * in int32 (two's-complement wrap), then Eq.2: y = (float)acc * (sx * sw).
+ *   xq_dev   INT8T_ACT codes of dims {N,C,H,W}   (INT8T_ACT_PLANAR when depthwise)
+ *   wq_dev   INT8T_WGT codes of dims {K,C/g,R,S} (INT8T_WGT_PLANAR when depthwise)
+ *   sx_dev, sw_dev   1 float each (the scales int8t_quantize wrote)
+ *   y_dev    out: fp32 N,K,P,Q
+ *   acc_dev  NULL, or out: int32 N,K,P,Q, the raw accumulators
+ */
+int8t_status int8t_conv_fwd(const int8t_conv_desc *desc,
+                            const int8_t *xq_dev, const float *sx_dev,
+                            const int8_t *wq_dev, const float *sw_dev,
+                            float *y_dev, int32_t *acc_dev,
+                            void *ws_dev, size_t ws_bytes, void *stream);
+
+/*
+ * Backward-data: acc[n,c,h,w] = sum over (k,r,s,p,q) with p*sh+r-ph = h, q*sw+s-pw = w of
+ * dyq[n,k,p,q] * wq[k,c,r,s];  dx = (float)acc * (sdy * sw).
+ *   dyq_dev  INT8T_ACT codes of dims {N,K,P,Q} (planar when depthwise);  wq_dev as in forward
+ *   dx_dev   out: fp32 N,C,H,W;   acc_dev NULL or int32 N,C,H,W
+ */
+int8t_status int8t_conv_bwd_data(const int8t_conv_desc *desc,
+                                 const int8_t *dyq_dev, const float *sdy_dev,
+                                 const int8_t *wq_dev, const float *sw_dev,
+                                 float *dx_dev, int32_t *acc_dev,
+                                 void *ws_dev, size_t ws_bytes, void *stream);
+
+/*
+ * Backward-weight: acc[k,c,r,s] = sum_{n,p,q} dyq[n,k,p,q] * xq[n,c,p*sh+r-ph,q*sw+s-pw];
+ * dw = (float)acc * (sdy * sx).  The forward's codes of x are re-used.
+ *   dw_dev   out: fp32 K,C/g,R,S;   acc_dev NULL or int32 K,C/g,R,S
+ */
+int8t_status int8t_conv_bwd_weight(const int8t_conv_desc *desc,
+                                   const int8_t *xq_dev, const float *sx_dev,
+                                   const int8_t *dyq_dev, const float *sdy_dev,
+                                   float *dw_dev, int32_t *acc_dev,
+                                   void *ws_dev, size_t ws_bytes, void *stream);
+
+/* Eq.7 on the host: max(exp(-alpha * d_c), beta).  The paper uses alpha = 20, beta = 0.1. */
+double int8t_dclr_scale(double d_c, double alpha, double beta);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* INT8T_H */

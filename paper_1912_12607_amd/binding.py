@@ -1,0 +1,147 @@
+"""Thin ctypes binding of csrc/libint8t.so: same names as the C ABI (include/int8t.h), argument
+marshalling only.  Tensors are torch CUDA(ROCm) tensors used purely as device memory; every step
+of the path runs inside the library's HIP kernels.  There is no CPU fallback: if the library is
+missing or fails to load, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "csrc", "libint8t.so")
+
+OK = 0
+ROUND_NEAREST_EVEN, ROUND_STOCHASTIC = 0, 1
+ACT, WGT, ACT_PLANAR, WGT_PLANAR = 0, 1, 2, 3
+OP_QUANTIZE, OP_DSGC, OP_CONV_FWD, OP_CONV_BWD_DATA, OP_CONV_BWD_WEIGHT = range(5)
+MAX_CANDIDATES = 64
+
+EXPORTS = ["int8t_status_string", "int8t_code_bytes", "int8t_workspace_bytes",
+           "int8t_quantize_workspace_bytes", "int8t_quantize", "int8t_dsgc_clip", "int8t_conv_fwd",
+           "int8t_conv_bwd_data", "int8t_conv_bwd_weight", "int8t_dclr_scale"]
+
+
+class ConvDesc(C.Structure):
+    _fields_ = [(n, C.c_int) for n in
+                ("N", "C", "H", "W", "K", "R", "S", "stride_h", "stride_w", "pad_h", "pad_w", "groups")]
+
+
+def make_desc(N, Cin, H, W, K, R, S, stride=(1, 1), pad=(0, 0), groups=1) -> ConvDesc:
+    return ConvDesc(N, Cin, H, W, K, R, S, stride[0], stride[1], pad[0], pad[1], groups)
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built: run `python -m paper_1912_12607_amd.build` "
+                          "(or __graft_entry__.build()) first; there is no fallback path")
+    L = C.CDLL(LIB_PATH)
+    vp, sz, u64, i32 = C.c_void_p, C.c_size_t, C.c_uint64, C.c_int
+    dims = C.POINTER(C.c_int)
+    dp = C.POINTER(ConvDesc)
+    L.int8t_status_string.restype = C.c_char_p
+    L.int8t_status_string.argtypes = [i32]
+    L.int8t_code_bytes.restype = sz
+    L.int8t_code_bytes.argtypes = [dims, i32]
+    L.int8t_workspace_bytes.restype = sz
+    L.int8t_workspace_bytes.argtypes = [i32, dp, sz, i32]
+    L.int8t_quantize_workspace_bytes.restype = sz
+    L.int8t_quantize_workspace_bytes.argtypes = [dims, i32]
+    L.int8t_quantize.restype = i32
+    L.int8t_quantize.argtypes = [vp, dims, i32, vp, i32, u64, vp, vp, vp, vp, sz, vp]
+    L.int8t_dsgc_clip.restype = i32
+    L.int8t_dsgc_clip.argtypes = [vp, sz, vp, i32, i32, u64, vp, vp, vp, vp, sz, vp]
+    for name in ("int8t_conv_fwd", "int8t_conv_bwd_data", "int8t_conv_bwd_weight"):
+        f = getattr(L, name)
+        f.restype = i32
+        f.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.int8t_dclr_scale.restype = C.c_double
+    L.int8t_dclr_scale.argtypes = [C.c_double, C.c_double, C.c_double]
+    return L
+
+
+lib = _load()
+
+
+class Int8tError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"int8t status {status}: {lib.int8t_status_string(status).decode()}")
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return C.c_void_p(t)
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensors only"
+    return C.c_void_p(t.data_ptr())
+
+
+def _nbytes(t):
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def _stream(stream):
+    if stream is None:
+        return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return C.c_void_p(stream)
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _dims(d):
+    return (C.c_int * 4)(*[int(v) for v in d])
+
+
+def _check(status: int):
+    if status != OK:
+        raise Int8tError(status)
+
+
+def int8t_status_string(status: int) -> str:
+    return lib.int8t_status_string(status).decode()
+
+
+def int8t_code_bytes(dims, kind: int) -> int:
+    return int(lib.int8t_code_bytes(_dims(dims), kind))
+
+
+def int8t_workspace_bytes(op: int, desc: ConvDesc | None = None, n: int = 0, n_cand: int = 0) -> int:
+    return int(lib.int8t_workspace_bytes(op, C.byref(desc) if desc is not None else None, n, n_cand))
+
+
+def int8t_quantize_workspace_bytes(dims, kind: int) -> int:
+    return int(lib.int8t_quantize_workspace_bytes(_dims(dims), kind))
+
+
+def int8t_quantize(x, dims, kind, clip, mode, seed, q, scale, deviation=None, ws=None, stream=None):
+    _check(lib.int8t_quantize(_ptr(x), _dims(dims), kind, _ptr(clip), mode, seed, _ptr(q), _ptr(scale),
+                              _ptr(deviation), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def int8t_dsgc_clip(g, n, ratios, n_cand, mode, seed, clip, deviation, deviation_all=None, ws=None,
+                    stream=None):
+    _check(lib.int8t_dsgc_clip(_ptr(g), n, _ptr(ratios), n_cand, mode, seed, _ptr(clip), _ptr(deviation),
+                               _ptr(deviation_all), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def int8t_conv_fwd(desc, xq, sx, wq, sw, y, acc=None, ws=None, stream=None):
+    _check(lib.int8t_conv_fwd(C.byref(desc), _ptr(xq), _ptr(sx), _ptr(wq), _ptr(sw), _ptr(y), _ptr(acc),
+                              _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def int8t_conv_bwd_data(desc, dyq, sdy, wq, sw, dx, acc=None, ws=None, stream=None):
+    _check(lib.int8t_conv_bwd_data(C.byref(desc), _ptr(dyq), _ptr(sdy), _ptr(wq), _ptr(sw), _ptr(dx),
+                                   _ptr(acc), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def int8t_conv_bwd_weight(desc, xq, sx, dyq, sdy, dw, acc=None, ws=None, stream=None):
+    _check(lib.int8t_conv_bwd_weight(C.byref(desc), _ptr(xq), _ptr(sx), _ptr(dyq), _ptr(sdy), _ptr(dw),
+                                     _ptr(acc), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def int8t_dclr_scale(d_c: float, alpha: float = 20.0, beta: float = 0.1) -> float:
+    return float(lib.int8t_dclr_scale(d_c, alpha, beta))

@@ -1,0 +1,301 @@
+// C ABI of the library (see include/int8t.h): argument validation, scratch carving, dispatch.
+// No device memory is allocated here and nothing synchronises with the host.
+#include <math.h>
+
+#include "../../include/int8t.h"
+#include "kernels.h"
+
+using namespace int8t;
+
+namespace {
+
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+inline int pad16(int v) { return (v + 15) & ~15; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+inline bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3) == 0; }
+
+constexpr size_t kMaxElems = 0x7FFFFFFFull;   // 32-bit indices inside the kernels
+
+bool dims_ok(const int d[4], size_t* n) {
+    if (!d) return false;
+    size_t t = 1;
+    for (int i = 0; i < 4; ++i) {
+        if (d[i] <= 0) return false;
+        t *= (size_t)d[i];
+        if (t > kMaxElems) return false;
+    }
+    *n = t;
+    return true;
+}
+
+struct Geo {
+    int P, Q;
+    bool depthwise;
+};
+
+int8t_status desc_ok(const int8t_conv_desc* d, Geo* g) {
+    if (!d) return INT8T_ERR_NULL;
+    if (d->N <= 0 || d->C <= 0 || d->H <= 0 || d->W <= 0 || d->K <= 0 || d->R <= 0 || d->S <= 0 ||
+        d->stride_h <= 0 || d->stride_w <= 0 || d->pad_h < 0 || d->pad_w < 0 || d->groups <= 0)
+        return INT8T_ERR_SHAPE;
+    if (d->H + 2 * d->pad_h < d->R || d->W + 2 * d->pad_w < d->S) return INT8T_ERR_SHAPE;
+    g->P = (d->H + 2 * d->pad_h - d->R) / d->stride_h + 1;
+    g->Q = (d->W + 2 * d->pad_w - d->S) / d->stride_w + 1;
+    if (d->groups == 1) g->depthwise = false;
+    else if (d->groups == d->C && d->K == d->C) g->depthwise = true;
+    else return INT8T_ERR_SHAPE;
+    // element counts must fit the kernels' 32-bit indices (padded channel pitch included)
+    const size_t nx = (size_t)d->N * pad16(d->C) * d->H * d->W;
+    const size_t ny = (size_t)d->N * pad16(d->K) * g->P * g->Q;
+    const size_t nw = (size_t)pad16(d->K) * pad16(d->C / d->groups) * d->R * d->S;
+    if (nx > kMaxElems || ny > kMaxElems || nw > kMaxElems) return INT8T_ERR_SHAPE;
+    if ((size_t)g->P * g->Q > (1u << 22) || (size_t)d->H * d->W > (1u << 22)) return INT8T_ERR_SHAPE;
+    if (g->depthwise) {
+        if (d->R * d->S > 64) return INT8T_ERR_SHAPE;
+        if ((size_t)d->H * d->W + (size_t)g->P * g->Q > 48000) return INT8T_ERR_SHAPE;   // LDS planes
+    }
+    return INT8T_OK;
+}
+
+// scratch of int8t_quantize: [absmax partials][deviation partials]
+size_t quant_ws_bytes(int blocks) { return align256(kMaxPartials * sizeof(float)) + align256((size_t)blocks * sizeof(DevPartial)); }
+
+int quant_blocks(const int d[4], int8t_kind kind) {
+    switch (kind) {
+        case INT8T_ACT: return quant_blocks_act(d[0], pad16(d[1]), d[2] * d[3]);
+        case INT8T_WGT: return quant_blocks_wgt(d[0], d[1], d[2], d[3]);
+        default: return quant_blocks_planar((size_t)d[0] * d[1] * d[2] * d[3]);
+    }
+}
+
+size_t dsgc_ws_bytes(size_t n) {
+    const size_t nb = (size_t)dsgc_blocks(n);
+    return align256(kMaxPartials * sizeof(float)) + 256 + align256(nb * 64 * sizeof(double)) +
+           align256(nb * 64 * sizeof(unsigned long long)) + align256(nb * sizeof(double));
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* int8t_status_string(int8t_status s) {
+    switch (s) {
+        case INT8T_OK: return "ok";
+        case INT8T_ERR_NULL: return "required pointer is NULL";
+        case INT8T_ERR_SHAPE: return "bad or unsupported shape";
+        case INT8T_ERR_ARG: return "bad argument (enum value, alignment, candidate count)";
+        case INT8T_ERR_WORKSPACE: return "workspace too small";
+        case INT8T_ERR_RUNTIME: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+size_t int8t_code_bytes(const int dims[4], int8t_kind kind) {
+    size_t n;
+    if (!dims_ok(dims, &n)) return 0;
+    switch (kind) {
+        case INT8T_ACT: return (size_t)dims[0] * dims[2] * dims[3] * pad16(dims[1]);
+        case INT8T_WGT:
+            return align256((size_t)dims[0] * dims[2] * dims[3] * pad16(dims[1])) +
+                   (size_t)dims[1] * dims[2] * dims[3] * pad16(dims[0]);
+        case INT8T_ACT_PLANAR:
+        case INT8T_WGT_PLANAR: return n;
+    }
+    return 0;
+}
+
+size_t int8t_workspace_bytes(int8t_op op, const int8t_conv_desc* desc, size_t n, int n_cand) {
+    (void)n_cand;
+    switch (op) {
+        case INT8T_OP_QUANTIZE: return 0;
+        case INT8T_OP_DSGC: return dsgc_ws_bytes(n);
+        case INT8T_OP_CONV_FWD:
+        case INT8T_OP_CONV_BWD_DATA: return 0;
+        case INT8T_OP_CONV_BWD_WEIGHT: {
+            Geo g;
+            if (desc_ok(desc, &g) != INT8T_OK) return 0;
+            if (g.depthwise)
+                return align256((size_t)dw_wgrad_chunks(desc->N, desc->C) * desc->C * desc->R * desc->S * 4);
+            const size_t splits = (size_t)wgrad_splits(desc->N, desc->C, desc->K, g.P, g.Q, desc->R, desc->S);
+            return align256(splits * desc->K * desc->R * desc->S * pad16(desc->C) * 4);
+        }
+    }
+    return 0;
+}
+
+size_t int8t_quantize_workspace_bytes(const int dims[4], int8t_kind kind) {
+    size_t n;
+    if (!dims_ok(dims, &n)) return 0;
+    if (kind != INT8T_ACT && kind != INT8T_WGT && kind != INT8T_ACT_PLANAR && kind != INT8T_WGT_PLANAR) return 0;
+    return quant_ws_bytes(quant_blocks(dims, kind));
+}
+
+int8t_status int8t_quantize(const float* x_dev, const int dims[4], int8t_kind kind,
+                            const float* clip_dev, int8t_round mode, uint64_t seed, int8_t* q_dev,
+                            float* scale_dev, double* deviation_dev, void* ws_dev, size_t ws_bytes,
+                            void* stream) {
+    if (!x_dev || !dims || !q_dev || !scale_dev) return INT8T_ERR_NULL;
+    size_t n;
+    if (!dims_ok(dims, &n)) return INT8T_ERR_SHAPE;
+    if (kind != INT8T_ACT && kind != INT8T_WGT && kind != INT8T_ACT_PLANAR && kind != INT8T_WGT_PLANAR)
+        return INT8T_ERR_ARG;
+    if (mode != INT8T_ROUND_NEAREST_EVEN && mode != INT8T_ROUND_STOCHASTIC) return INT8T_ERR_ARG;
+    if (!aligned16(x_dev) || !aligned16(q_dev) || !aligned4(scale_dev)) return INT8T_ERR_ARG;
+    if (kind == INT8T_ACT && (size_t)dims[0] * pad16(dims[1]) * dims[2] * dims[3] > kMaxElems) return INT8T_ERR_SHAPE;
+    if (kind == INT8T_ACT && dims[0] > 65535) return INT8T_ERR_SHAPE;   // grid.z
+    const bool need_absmax = (clip_dev == nullptr);
+    const bool need_dev = (deviation_dev != nullptr);
+    const int blocks = quant_blocks(dims, kind);
+    if (need_absmax || need_dev) {
+        if (!ws_dev) return INT8T_ERR_NULL;
+        if (ws_bytes < quant_ws_bytes(need_dev ? blocks : 0)) return INT8T_ERR_WORKSPACE;
+        if (!aligned16(ws_dev)) return INT8T_ERR_ARG;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    char* ws = (char*)ws_dev;
+    float* absmax_part = (float*)ws;
+    DevPartial* devpart = need_dev ? (DevPartial*)(ws + align256(kMaxPartials * sizeof(float))) : nullptr;
+
+    int nparts = 0;
+    if (need_absmax && launch_absmax(x_dev, n, absmax_part, &nparts, st) != hipSuccess) return INT8T_ERR_RUNTIME;
+    QuantArgs a;
+    a.x = x_dev;
+    a.d0 = dims[0]; a.d1 = dims[1]; a.d2 = dims[2]; a.d3 = dims[3];
+    a.clip = clip_dev;
+    a.absmax_part = absmax_part;
+    a.nparts = nparts;
+    a.stochastic = (mode == INT8T_ROUND_STOCHASTIC);
+    a.seed = seed;
+    a.q = q_dev;
+    a.scale = scale_dev;
+    a.devpart = devpart;
+    hipError_t e;
+    if (kind == INT8T_ACT) e = launch_quantize_act(a, st);
+    else if (kind == INT8T_WGT) e = launch_quantize_wgt(a, st);
+    else e = launch_quantize_planar(a, st);
+    if (e != hipSuccess) return INT8T_ERR_RUNTIME;
+    if (need_dev && launch_deviation_finish(devpart, blocks, deviation_dev, st) != hipSuccess) return INT8T_ERR_RUNTIME;
+    return INT8T_OK;
+}
+
+int8t_status int8t_dsgc_clip(const float* g_dev, size_t n, const float* ratios_dev, int n_cand,
+                             int8t_round mode, uint64_t seed, float* clip_dev, double* deviation_dev,
+                             double* deviation_all_dev, void* ws_dev, size_t ws_bytes, void* stream) {
+    if (!g_dev || !ratios_dev || !clip_dev || !deviation_dev || !ws_dev) return INT8T_ERR_NULL;
+    if (n == 0 || n > kMaxElems) return INT8T_ERR_SHAPE;
+    if (n_cand < 1 || n_cand > INT8T_MAX_CANDIDATES) return INT8T_ERR_ARG;
+    if (mode != INT8T_ROUND_NEAREST_EVEN && mode != INT8T_ROUND_STOCHASTIC) return INT8T_ERR_ARG;
+    if (!aligned16(g_dev) || !aligned16(ws_dev) || !aligned4(ratios_dev) || !aligned4(clip_dev) ||
+        (reinterpret_cast<uintptr_t>(deviation_dev) & 7) || (reinterpret_cast<uintptr_t>(deviation_all_dev) & 7))
+        return INT8T_ERR_ARG;
+    if (ws_bytes < dsgc_ws_bytes(n)) return INT8T_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    const size_t nb = (size_t)dsgc_blocks(n);
+    char* p = (char*)ws_dev;
+    DsgcWs ws;
+    ws.absmax_part = (float*)p;                 p += align256(kMaxPartials * sizeof(float));
+    ws.absmax = (float*)p;                      p += 256;
+    ws.partA = (double*)p;                      p += align256(nb * 64 * sizeof(double));
+    ws.partB = (unsigned long long*)p;          p += align256(nb * 64 * sizeof(unsigned long long));
+    ws.partG = (double*)p;
+    int nparts = 0;
+    if (launch_absmax(g_dev, n, ws.absmax_part, &nparts, st) != hipSuccess) return INT8T_ERR_RUNTIME;
+    if (launch_dsgc(g_dev, n, ratios_dev, n_cand, mode == INT8T_ROUND_STOCHASTIC, seed, ws, nparts, clip_dev,
+                    deviation_dev, deviation_all_dev, st) != hipSuccess)
+        return INT8T_ERR_RUNTIME;
+    return INT8T_OK;
+}
+
+int8t_status int8t_conv_fwd(const int8t_conv_desc* desc, const int8_t* xq_dev, const float* sx_dev,
+                            const int8_t* wq_dev, const float* sw_dev, float* y_dev, int32_t* acc_dev,
+                            void* ws_dev, size_t ws_bytes, void* stream) {
+    (void)ws_dev; (void)ws_bytes;
+    Geo g;
+    int8t_status s = desc_ok(desc, &g);
+    if (s != INT8T_OK) return s;
+    if (!xq_dev || !sx_dev || !wq_dev || !sw_dev || !y_dev) return INT8T_ERR_NULL;
+    if (!aligned16(xq_dev) || !aligned16(wq_dev) || !aligned16(y_dev) || !aligned4(acc_dev)) return INT8T_ERR_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    if (g.depthwise) {
+        DwArgs a{};
+        a.a = xq_dev; a.b = wq_dev; a.sa = sx_dev; a.sb = sw_dev; a.out = y_dev; a.acc = acc_dev;
+        a.N = desc->N; a.C = desc->C; a.IH = desc->H; a.IW = desc->W; a.OH = g.P; a.OW = g.Q;
+        a.R = desc->R; a.S = desc->S; a.stride_h = desc->stride_h; a.stride_w = desc->stride_w;
+        a.pad_h = desc->pad_h; a.pad_w = desc->pad_w; a.dgrad = 0;
+        return launch_dw_conv(a, st) == hipSuccess ? INT8T_OK : INT8T_ERR_RUNTIME;
+    }
+    IgemmArgs a{};
+    a.act = xq_dev; a.wgt = wq_dev; a.sa = sx_dev; a.sb = sw_dev; a.out = y_dev; a.acc = acc_dev;
+    a.N = desc->N; a.rows = desc->K; a.Ca = pad16(desc->C);
+    a.IH = desc->H; a.IW = desc->W; a.OH = g.P; a.OW = g.Q; a.R = desc->R; a.S = desc->S;
+    a.stride_h = desc->stride_h; a.stride_w = desc->stride_w; a.pad_h = desc->pad_h; a.pad_w = desc->pad_w;
+    a.dgrad = 0;
+    return launch_igemm(a, st) == hipSuccess ? INT8T_OK : INT8T_ERR_RUNTIME;
+}
+
+int8t_status int8t_conv_bwd_data(const int8t_conv_desc* desc, const int8_t* dyq_dev, const float* sdy_dev,
+                                 const int8_t* wq_dev, const float* sw_dev, float* dx_dev, int32_t* acc_dev,
+                                 void* ws_dev, size_t ws_bytes, void* stream) {
+    (void)ws_dev; (void)ws_bytes;
+    Geo g;
+    int8t_status s = desc_ok(desc, &g);
+    if (s != INT8T_OK) return s;
+    if (!dyq_dev || !sdy_dev || !wq_dev || !sw_dev || !dx_dev) return INT8T_ERR_NULL;
+    if (!aligned16(dyq_dev) || !aligned16(wq_dev) || !aligned16(dx_dev) || !aligned4(acc_dev)) return INT8T_ERR_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    if (g.depthwise) {
+        DwArgs a{};
+        a.a = dyq_dev; a.b = wq_dev; a.sa = sdy_dev; a.sb = sw_dev; a.out = dx_dev; a.acc = acc_dev;
+        a.N = desc->N; a.C = desc->C; a.IH = g.P; a.IW = g.Q; a.OH = desc->H; a.OW = desc->W;
+        a.R = desc->R; a.S = desc->S; a.stride_h = desc->stride_h; a.stride_w = desc->stride_w;
+        a.pad_h = desc->pad_h; a.pad_w = desc->pad_w; a.dgrad = 1;
+        return launch_dw_conv(a, st) == hipSuccess ? INT8T_OK : INT8T_ERR_RUNTIME;
+    }
+    IgemmArgs a{};
+    a.act = dyq_dev;
+    // second copy of the weight codes: [C][R][S][Kp]
+    a.wgt = wq_dev + align256((size_t)desc->K * desc->R * desc->S * pad16(desc->C));
+    a.sa = sdy_dev; a.sb = sw_dev; a.out = dx_dev; a.acc = acc_dev;
+    a.N = desc->N; a.rows = desc->C; a.Ca = pad16(desc->K);
+    a.IH = g.P; a.IW = g.Q; a.OH = desc->H; a.OW = desc->W; a.R = desc->R; a.S = desc->S;
+    a.stride_h = desc->stride_h; a.stride_w = desc->stride_w; a.pad_h = desc->pad_h; a.pad_w = desc->pad_w;
+    a.dgrad = 1;
+    return launch_igemm(a, st) == hipSuccess ? INT8T_OK : INT8T_ERR_RUNTIME;
+}
+
+int8t_status int8t_conv_bwd_weight(const int8t_conv_desc* desc, const int8_t* xq_dev, const float* sx_dev,
+                                   const int8_t* dyq_dev, const float* sdy_dev, float* dw_dev, int32_t* acc_dev,
+                                   void* ws_dev, size_t ws_bytes, void* stream) {
+    Geo g;
+    int8t_status s = desc_ok(desc, &g);
+    if (s != INT8T_OK) return s;
+    if (!xq_dev || !sx_dev || !dyq_dev || !sdy_dev || !dw_dev || !ws_dev) return INT8T_ERR_NULL;
+    if (!aligned16(xq_dev) || !aligned16(dyq_dev) || !aligned16(dw_dev) || !aligned4(acc_dev) || !aligned16(ws_dev))
+        return INT8T_ERR_ARG;
+    if (ws_bytes < int8t_workspace_bytes(INT8T_OP_CONV_BWD_WEIGHT, desc, 0, 0)) return INT8T_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    if (g.depthwise) {
+        DwArgs a{};
+        a.a = xq_dev; a.b = dyq_dev; a.sa = sx_dev; a.sb = sdy_dev; a.out = dw_dev; a.acc = acc_dev;
+        a.partial = (int32_t*)ws_dev; a.chunks = dw_wgrad_chunks(desc->N, desc->C);
+        a.N = desc->N; a.C = desc->C; a.IH = desc->H; a.IW = desc->W; a.OH = g.P; a.OW = g.Q;
+        a.R = desc->R; a.S = desc->S; a.stride_h = desc->stride_h; a.stride_w = desc->stride_w;
+        a.pad_h = desc->pad_h; a.pad_w = desc->pad_w; a.dgrad = 0;
+        return launch_dw_wgrad(a, st) == hipSuccess ? INT8T_OK : INT8T_ERR_RUNTIME;
+    }
+    WgradArgs a{};
+    a.x = xq_dev; a.dy = dyq_dev; a.sa = sx_dev; a.sb = sdy_dev; a.dw = dw_dev; a.acc = acc_dev;
+    a.partial = (int32_t*)ws_dev;
+    a.splits = wgrad_splits(desc->N, desc->C, desc->K, g.P, g.Q, desc->R, desc->S);
+    a.N = desc->N; a.C = desc->C; a.Cp = pad16(desc->C); a.H = desc->H; a.W = desc->W;
+    a.K = desc->K; a.Kp = pad16(desc->K); a.P = g.P; a.Q = g.Q; a.R = desc->R; a.S = desc->S;
+    a.stride_h = desc->stride_h; a.stride_w = desc->stride_w; a.pad_h = desc->pad_h; a.pad_w = desc->pad_w;
+    return launch_wgrad(a, st) == hipSuccess ? INT8T_OK : INT8T_ERR_RUNTIME;
+}
+
+double int8t_dclr_scale(double d_c, double alpha, double beta) {
+    const double e = exp(-alpha * d_c);
+    return e > beta ? e : beta;
+}
+
+}  // extern "C"

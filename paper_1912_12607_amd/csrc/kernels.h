@@ -1,0 +1,105 @@
+// Internal launch interface between the C-ABI layer (api.hip) and the kernel files.
+// Every launcher enqueues on `st` and returns the hipError_t of its last launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace int8t {
+
+constexpr int kMaxPartials = 1024;   // per-block partial results of an absmax pass
+
+// Partial sums of Eq.6 left by one block: A = sum g*q, G = sum g^2, B = sum q^2.
+struct DevPartial {
+    double A;
+    double G;
+    unsigned long long B;
+};
+
+// ---- quantize.hip ---------------------------------------------------------------------------
+// max|x| per block -> part[0..nparts); returns the number of partials through *nparts.
+hipError_t launch_absmax(const float* x, size_t n, float* part, int* nparts, hipStream_t st);
+
+struct QuantArgs {
+    const float* x;
+    int d0, d1, d2, d3;          // logical dims: N,C,H,W or K,Cg,R,S
+    const float* clip;           // device scalar or nullptr (then absmax partials are reduced)
+    const float* absmax_part;
+    int nparts;
+    int stochastic;
+    uint64_t seed;
+    int8_t* q;
+    float* scale;
+    DevPartial* devpart;         // nullptr: no deviation
+};
+int quant_blocks_act(int N, int Cp, int HW);
+int quant_blocks_planar(size_t n);
+int quant_blocks_wgt(int K, int Cg, int R, int S);
+hipError_t launch_quantize_act(const QuantArgs& a, hipStream_t st);
+hipError_t launch_quantize_planar(const QuantArgs& a, hipStream_t st);
+hipError_t launch_quantize_wgt(const QuantArgs& a, hipStream_t st);
+hipError_t launch_deviation_finish(const DevPartial* part, int nparts, double* dev_out, hipStream_t st);
+
+// ---- dsgc.hip -------------------------------------------------------------------------------
+struct DsgcWs {
+    float* absmax_part;          // kMaxPartials floats
+    float* absmax;               // 1 float (written by the sweep)
+    double* partA;               // [nblocks][jpad]
+    unsigned long long* partB;   // [nblocks][jpad]
+    double* partG;               // [nblocks]
+};
+int dsgc_blocks(size_t n);
+hipError_t launch_dsgc(const float* g, size_t n, const float* ratios, int n_cand, int stochastic,
+                       uint64_t seed, const DsgcWs& ws, int nparts_absmax, float* clip_out,
+                       double* dev_out, double* dev_all_out, hipStream_t st);
+
+// ---- conv_igemm.hip (dense forward and backward-data) -----------------------------------------
+struct IgemmArgs {
+    const int8_t* act;           // NHWC codes, channel pitch Ca
+    const int8_t* wgt;           // [rows][R][S][Ca]
+    const float* sa;
+    const float* sb;
+    float* out;                  // [N][rows][OH*OW]
+    int32_t* acc;                // nullable, same order
+    int N, rows, Ca;             // Ca: padded reduction channels (multiple of 16)
+    int IH, IW, OH, OW, R, S;
+    int stride_h, stride_w, pad_h, pad_w;
+    int dgrad;                   // 0: ih = oh*stride + r - pad;  1: ih = (oh + pad - r)/stride
+};
+hipError_t launch_igemm(const IgemmArgs& a, hipStream_t st);
+
+// ---- conv_wgrad.hip (dense backward-weight) ---------------------------------------------------
+struct WgradArgs {
+    const int8_t* x;             // NHWC codes of a, pitch Cp
+    const int8_t* dy;            // NHWC codes of g_z, pitch Kp
+    const float* sa;
+    const float* sb;
+    float* dw;                   // [K][C][R][S]
+    int32_t* acc;                // nullable
+    int32_t* partial;            // scratch [splits][K][R*S*Cp]
+    int splits;
+    int N, C, Cp, H, W, K, Kp, P, Q, R, S;
+    int stride_h, stride_w, pad_h, pad_w;
+};
+int wgrad_splits(int N, int C, int K, int P, int Q, int R, int S);
+hipError_t launch_wgrad(const WgradArgs& a, hipStream_t st);
+
+// ---- conv_dw.hip (depthwise, planar codes) ----------------------------------------------------
+struct DwArgs {
+    const int8_t* a;             // planar codes, input of the gather ([N][C][IH][IW])
+    const int8_t* b;             // fwd/bwd-data: weights [C][R][S]; bwd-weight: dy codes [N][C][P][Q]
+    const float* sa;
+    const float* sb;
+    float* out;
+    int32_t* acc;                // nullable
+    int32_t* partial;            // bwd-weight scratch [chunks][C*R*S]
+    int chunks;
+    int N, C, IH, IW, OH, OW, R, S;
+    int stride_h, stride_w, pad_h, pad_w;
+    int dgrad;
+};
+int dw_wgrad_chunks(int N, int C);
+hipError_t launch_dw_conv(const DwArgs& a, hipStream_t st);
+hipError_t launch_dw_wgrad(const DwArgs& a, hipStream_t st);
+
+}  // namespace int8t

@@ -1,0 +1,384 @@
+// Quantize passes (Eq.1 / Eq.3 of the paper), the absmax reduction that supplies the default
+// clip value, and the scalar finish of the direction deviation (Eq.6).
+//
+// All of these are HBM-bandwidth bound: each fp32 element is read once and one code byte is
+// written.  The layout change fp32 N,C,H,W -> int8 N,H,W,C (reduction dimension innermost, the
+// analogue of the paper's NC4HW transposition) happens inside the quantize pass through an LDS
+// tile, so it costs no extra HBM traffic.
+#include "device_common.h"
+#include "kernels.h"
+
+namespace int8t {
+
+// ---------------------------------------------------------------------------------------------
+// absmax: grid-stride float4 sweep, one partial per block.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void absmax_kernel(const float* __restrict__ x, size_t n,
+                                                     float* __restrict__ part) {
+    __shared__ float lds4[4];
+    const size_t n4 = n >> 2;
+    const float4* __restrict__ x4 = reinterpret_cast<const float4*>(x);
+    float m = 0.0f;
+    const size_t stride = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    // four independent 16-byte loads in flight per thread
+    for (; i + 3 * stride < n4; i += 4 * stride) {
+        float4 a = x4[i], b = x4[i + stride], c = x4[i + 2 * stride], d = x4[i + 3 * stride];
+        m = fmaxf(m, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
+        m = fmaxf(m, fmaxf(fmaxf(fabsf(b.x), fabsf(b.y)), fmaxf(fabsf(b.z), fabsf(b.w))));
+        m = fmaxf(m, fmaxf(fmaxf(fabsf(c.x), fabsf(c.y)), fmaxf(fabsf(c.z), fabsf(c.w))));
+        m = fmaxf(m, fmaxf(fmaxf(fabsf(d.x), fabsf(d.y)), fmaxf(fabsf(d.z), fabsf(d.w))));
+    }
+    for (; i < n4; i += stride) {
+        float4 a = x4[i];
+        m = fmaxf(m, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (n & 3)) m = fmaxf(m, fabsf(x[(n4 << 2) + threadIdx.x]));
+    m = block_max_256(m, lds4);
+    if (threadIdx.x == 0) part[blockIdx.x] = m;
+}
+
+hipError_t launch_absmax(const float* x, size_t n, float* part, int* nparts, hipStream_t st) {
+    size_t want = (n / 4 + 256 * 8 - 1) / (256 * 8);   // >= 8 float4 per thread before adding blocks
+    int blocks = (int)(want < 1 ? 1 : (want > (size_t)kMaxPartials ? (size_t)kMaxPartials : want));
+    *nparts = blocks;
+    hipLaunchKernelGGL(absmax_kernel, dim3(blocks), dim3(256), 0, st, x, n, part);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Block-level reduction of the Eq.6 partial sums, one DevPartial per block.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void block_store_devpartial(double A, double G, unsigned long long B,
+                                                       DevPartial* __restrict__ out) {
+    __shared__ double ldsA[4], ldsG[4];
+    __shared__ unsigned long long ldsB[4];
+    A = wave_sum(A);
+    G = wave_sum(G);
+    B = wave_sum(B);
+    const int w = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) {
+        ldsA[w] = A;
+        ldsG[w] = G;
+        ldsB[w] = B;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        DevPartial p;
+        p.A = (ldsA[0] + ldsA[1]) + (ldsA[2] + ldsA[3]);
+        p.G = (ldsG[0] + ldsG[1]) + (ldsG[2] + ldsG[3]);
+        p.B = ldsB[0] + ldsB[1] + ldsB[2] + ldsB[3];
+        *out = p;
+    }
+}
+
+__device__ __forceinline__ float resolve_clip(const float* __restrict__ clip,
+                                              const float* __restrict__ part, int nparts, float* lds4) {
+    if (clip) return *clip;
+    return reduce_absmax_partials(part, nparts, lds4);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Activations / gradients: fp32 N,C,H,W -> int8 N,H,W,Cp.
+// One block = 64 pixels x 64 channels of one image.  Loads walk pixels (contiguous in the
+// source), each thread owns four consecutive channels of its pixel and packs them to one
+// dword; the store phase walks channels (contiguous in the destination) in 16-byte pieces.
+// ---------------------------------------------------------------------------------------------
+constexpr int QA_PIX = 64;
+constexpr int QA_CH = 64;
+
+template <bool STOCH, bool DEV>
+__global__ __launch_bounds__(256) void quantize_act_kernel(
+    const float* __restrict__ x, int C, int Cp, int HW, const float* __restrict__ clip,
+    const float* __restrict__ absmax_part, int nparts, uint32_t seed_lo, uint32_t seed_hi_mul,
+    int8_t* __restrict__ q, float* __restrict__ scale_out, DevPartial* __restrict__ devpart) {
+    __shared__ float lds4[4];
+    __shared__ uint32_t tile[QA_PIX][QA_CH / 4 + 1];
+
+    const int n = blockIdx.z;
+    const int c0 = blockIdx.y * QA_CH;
+    const int p0 = blockIdx.x * QA_PIX;
+    const int lane = threadIdx.x & 63;
+    const int wv = threadIdx.x >> 6;
+    const int p = p0 + lane;
+    const bool pv = p < HW;
+
+    // issue every global load of this thread before anything depends on them
+    float v[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int c = c0 + 4 * (wv + 4 * i) + j;
+            v[i][j] = (pv && c < C) ? x[((size_t)n * C + c) * HW + p] : 0.0f;
+        }
+    }
+
+    const float cval = resolve_clip(clip, absmax_part, nparts, lds4);
+    const float inv = inv_scale_of(cval);
+    if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) *scale_out = scale_of(cval);
+
+    double A = 0.0, G = 0.0;
+    unsigned long long B = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int code[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int c = c0 + 4 * (wv + 4 * i) + j;
+            const uint32_t idx = (uint32_t)(((size_t)n * C + c) * HW + p);
+            code[j] = quantize_one<STOCH>(v[i][j], inv, seed_lo, seed_hi_mul, idx);
+            if (DEV) {
+                const double g = (double)v[i][j];
+                A = fma(g, (double)code[j], A);
+                G = fma(g, g, G);
+                B += (unsigned)(code[j] * code[j]);
+            }
+        }
+        tile[lane][wv + 4 * i] = pack4(code[0], code[1], code[2], code[3]);
+    }
+    __syncthreads();
+
+    const int pl = threadIdx.x >> 2;
+    const int chunk = threadIdx.x & 3;
+    if (p0 + pl < HW && c0 + chunk * 16 < Cp) {
+        uint4 o;
+        o.x = tile[pl][chunk * 4 + 0];
+        o.y = tile[pl][chunk * 4 + 1];
+        o.z = tile[pl][chunk * 4 + 2];
+        o.w = tile[pl][chunk * 4 + 3];
+        *reinterpret_cast<uint4*>(q + ((size_t)n * HW + p0 + pl) * Cp + c0 + chunk * 16) = o;
+    }
+    if (DEV) {
+        const int b = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
+        block_store_devpartial(A, G, B, devpart + b);
+    }
+}
+
+int quant_blocks_act(int N, int Cp, int HW) {
+    return ((HW + QA_PIX - 1) / QA_PIX) * ((Cp + QA_CH - 1) / QA_CH) * N;
+}
+
+hipError_t launch_quantize_act(const QuantArgs& a, hipStream_t st) {
+    const int N = a.d0, C = a.d1, HW = a.d2 * a.d3, Cp = (C + 15) & ~15;
+    dim3 grid((HW + QA_PIX - 1) / QA_PIX, (Cp + QA_CH - 1) / QA_CH, N);
+    const uint32_t slo = (uint32_t)a.seed, shi = seed_hi_term(a.seed);
+#define LAUNCH(ST, DV)                                                                               \
+    hipLaunchKernelGGL((quantize_act_kernel<ST, DV>), grid, dim3(256), 0, st, a.x, C, Cp, HW, a.clip, \
+                       a.absmax_part, a.nparts, slo, shi, a.q, a.scale, a.devpart)
+    if (a.stochastic) {
+        if (a.devpart) LAUNCH(true, true); else LAUNCH(true, false);
+    } else {
+        if (a.devpart) LAUNCH(false, true); else LAUNCH(false, false);
+    }
+#undef LAUNCH
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Planar codes (depthwise layers): element-wise, logical order kept.
+// ---------------------------------------------------------------------------------------------
+constexpr int QP_BLOCKS_MAX = 4096;
+
+template <bool STOCH, bool DEV>
+__global__ __launch_bounds__(256) void quantize_planar_kernel(
+    const float* __restrict__ x, size_t n, const float* __restrict__ clip,
+    const float* __restrict__ absmax_part, int nparts, uint32_t seed_lo, uint32_t seed_hi_mul,
+    int8_t* __restrict__ q, float* __restrict__ scale_out, DevPartial* __restrict__ devpart) {
+    __shared__ float lds4[4];
+    const float cval = resolve_clip(clip, absmax_part, nparts, lds4);
+    const float inv = inv_scale_of(cval);
+    if (blockIdx.x == 0 && threadIdx.x == 0) *scale_out = scale_of(cval);
+
+    double A = 0.0, G = 0.0;
+    unsigned long long B = 0;
+    const size_t n4 = n >> 2;
+    const float4* __restrict__ x4 = reinterpret_cast<const float4*>(x);
+    uint32_t* __restrict__ q4 = reinterpret_cast<uint32_t*>(q);
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
+        const float4 f = x4[i];
+        const float vv[4] = {f.x, f.y, f.z, f.w};
+        int code[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            code[j] = quantize_one<STOCH>(vv[j], inv, seed_lo, seed_hi_mul, (uint32_t)(4 * i + j));
+            if (DEV) {
+                const double g = (double)vv[j];
+                A = fma(g, (double)code[j], A);
+                G = fma(g, g, G);
+                B += (unsigned)(code[j] * code[j]);
+            }
+        }
+        q4[i] = pack4(code[0], code[1], code[2], code[3]);
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
+        const size_t i = (n4 << 2) + threadIdx.x;
+        const float g32 = x[i];
+        const int code = quantize_one<STOCH>(g32, inv, seed_lo, seed_hi_mul, (uint32_t)i);
+        q[i] = (int8_t)code;
+        if (DEV) {
+            const double g = (double)g32;
+            A = fma(g, (double)code, A);
+            G = fma(g, g, G);
+            B += (unsigned)(code * code);
+        }
+    }
+    if (DEV) block_store_devpartial(A, G, B, devpart + blockIdx.x);
+}
+
+int quant_blocks_planar(size_t n) {
+    size_t want = (n / 4 + 256 * 4 - 1) / (256 * 4);
+    return (int)(want < 1 ? 1 : (want > (size_t)QP_BLOCKS_MAX ? (size_t)QP_BLOCKS_MAX : want));
+}
+
+hipError_t launch_quantize_planar(const QuantArgs& a, hipStream_t st) {
+    const size_t n = (size_t)a.d0 * a.d1 * a.d2 * a.d3;
+    const int blocks = quant_blocks_planar(n);
+    const uint32_t slo = (uint32_t)a.seed, shi = seed_hi_term(a.seed);
+#define LAUNCH(ST, DV)                                                                              \
+    hipLaunchKernelGGL((quantize_planar_kernel<ST, DV>), dim3(blocks), dim3(256), 0, st, a.x, n,    \
+                       a.clip, a.absmax_part, a.nparts, slo, shi, a.q, a.scale, a.devpart)
+    if (a.stochastic) {
+        if (a.devpart) LAUNCH(true, true); else LAUNCH(true, false);
+    } else {
+        if (a.devpart) LAUNCH(false, true); else LAUNCH(false, false);
+    }
+#undef LAUNCH
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Weights: fp32 K,Cg,R,S -> two int8 copies, [K][R][S][Cp] (forward / backward-weight view) and
+// [Cg][R][S][Kp] (backward-data view).  One thread per output dword; the tensors are small
+// (a few MB at most) and the strided reads hit L2.
+// ---------------------------------------------------------------------------------------------
+template <bool STOCH, bool DEV>
+__global__ __launch_bounds__(256) void quantize_wgt_kernel(
+    const float* __restrict__ w, int K, int Cg, int R, int S, int Cp, int Kp, size_t off2,
+    const float* __restrict__ clip, const float* __restrict__ absmax_part, int nparts,
+    uint32_t seed_lo, uint32_t seed_hi_mul, int8_t* __restrict__ q, float* __restrict__ scale_out,
+    DevPartial* __restrict__ devpart) {
+    __shared__ float lds4[4];
+    const float cval = resolve_clip(clip, absmax_part, nparts, lds4);
+    const float inv = inv_scale_of(cval);
+    if (blockIdx.x == 0 && threadIdx.x == 0) *scale_out = scale_of(cval);
+
+    const int RS = R * S;
+    const size_t nd1 = (size_t)K * RS * (Cp / 4);
+    const size_t nd2 = (size_t)Cg * RS * (Kp / 4);
+    double A = 0.0, G = 0.0;
+    unsigned long long B = 0;
+    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (t < nd1) {
+        const int c4 = (int)(t % (Cp / 4));
+        size_t rest = t / (Cp / 4);
+        const int rs = (int)(rest % RS);
+        const int k = (int)(rest / RS);
+        int code[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int c = 4 * c4 + j;
+            code[j] = 0;
+            if (c < Cg) {
+                const size_t idx = ((size_t)k * Cg + c) * RS + rs;
+                const float g32 = w[idx];
+                code[j] = quantize_one<STOCH>(g32, inv, seed_lo, seed_hi_mul, (uint32_t)idx);
+                if (DEV) {
+                    const double g = (double)g32;
+                    A = fma(g, (double)code[j], A);
+                    G = fma(g, g, G);
+                    B += (unsigned)(code[j] * code[j]);
+                }
+            }
+        }
+        reinterpret_cast<uint32_t*>(q)[t] = pack4(code[0], code[1], code[2], code[3]);
+    } else if (t < nd1 + nd2) {
+        const size_t u = t - nd1;
+        const int k4 = (int)(u % (Kp / 4));
+        size_t rest = u / (Kp / 4);
+        const int rs = (int)(rest % RS);
+        const int c = (int)(rest / RS);
+        int code[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int k = 4 * k4 + j;
+            code[j] = 0;
+            if (k < K) {
+                const size_t idx = ((size_t)k * Cg + c) * RS + rs;
+                code[j] = quantize_one<STOCH>(w[idx], inv, seed_lo, seed_hi_mul, (uint32_t)idx);
+            }
+        }
+        reinterpret_cast<uint32_t*>(q + off2)[u] = pack4(code[0], code[1], code[2], code[3]);
+    }
+    if (DEV) block_store_devpartial(A, G, B, devpart + blockIdx.x);
+}
+
+int quant_blocks_wgt(int K, int Cg, int R, int S) {
+    const int Cp = (Cg + 15) & ~15, Kp = (K + 15) & ~15;
+    const size_t nd = (size_t)K * R * S * (Cp / 4) + (size_t)Cg * R * S * (Kp / 4);
+    return (int)((nd + 255) / 256);
+}
+
+hipError_t launch_quantize_wgt(const QuantArgs& a, hipStream_t st) {
+    const int K = a.d0, Cg = a.d1, R = a.d2, S = a.d3;
+    const int Cp = (Cg + 15) & ~15, Kp = (K + 15) & ~15;
+    const size_t off2 = (((size_t)K * R * S * Cp) + 255) & ~(size_t)255;
+    const int blocks = quant_blocks_wgt(K, Cg, R, S);
+    const uint32_t slo = (uint32_t)a.seed, shi = seed_hi_term(a.seed);
+#define LAUNCH(ST, DV)                                                                              \
+    hipLaunchKernelGGL((quantize_wgt_kernel<ST, DV>), dim3(blocks), dim3(256), 0, st, a.x, K, Cg, R, \
+                       S, Cp, Kp, off2, a.clip, a.absmax_part, a.nparts, slo, shi, a.q, a.scale,    \
+                       a.devpart)
+    if (a.stochastic) {
+        if (a.devpart) LAUNCH(true, true); else LAUNCH(true, false);
+    } else {
+        if (a.devpart) LAUNCH(false, true); else LAUNCH(false, false);
+    }
+#undef LAUNCH
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Eq.6 finish: d = 1 - A / sqrt(G * B)  (the scale s cancels between numerator and |ghat|).
+// Partials are summed in a fixed tree order, so the result is deterministic.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void deviation_finish_kernel(const DevPartial* __restrict__ part,
+                                                               int nparts, double* __restrict__ out) {
+    __shared__ double sA[256], sG[256];
+    __shared__ unsigned long long sB[256];
+    double A = 0.0, G = 0.0;
+    unsigned long long B = 0;
+    for (int i = threadIdx.x; i < nparts; i += 256) {
+        A += part[i].A;
+        G += part[i].G;
+        B += part[i].B;
+    }
+    sA[threadIdx.x] = A;
+    sG[threadIdx.x] = G;
+    sB[threadIdx.x] = B;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) {
+            sA[threadIdx.x] += sA[threadIdx.x + s];
+            sG[threadIdx.x] += sG[threadIdx.x + s];
+            sB[threadIdx.x] += sB[threadIdx.x + s];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const double g = sG[0], b = (double)sB[0];
+        double d;
+        if (g == 0.0) d = 0.0;
+        else if (b == 0.0) d = 1.0;
+        else d = 1.0 - sA[0] / (sqrt(g) * sqrt(b));
+        *out = d;
+    }
+}
+
+hipError_t launch_deviation_finish(const DevPartial* part, int nparts, double* dev_out, hipStream_t st) {
+    hipLaunchKernelGGL(deviation_finish_kernel, dim3(1), dim3(256), 0, st, part, nparts, dev_out);
+    return hipGetLastError();
+}
+
+}  // namespace int8t

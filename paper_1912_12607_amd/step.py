@@ -1,0 +1,141 @@
+"""One conv-layer training step of the INT8 path as a sequence of C-ABI calls.
+
+Pure plumbing: allocates device buffers with torch, uploads the fp32 tensors once, and chains
+    quantize(a) -> quantize(W) -> dsgc_clip(g_z) -> quantize(g_z; clip, stochastic, d_c)
+    -> conv_fwd -> conv_bwd_data -> conv_bwd_weight
+on one stream with no host synchronisation in between (scales, clip and deviation stay in device
+memory).  Used by the tests, the smoke check and the benchmark.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as B
+from .inputs import Layer
+
+
+def pad16(v: int) -> int:
+    return (v + 15) & ~15
+
+
+def align256(v: int) -> int:
+    return (v + 255) & ~255
+
+
+class LayerStep:
+    def __init__(self, L: Layer, n_cand: int = 32, keep_acc: bool = False, device: str = "cuda:0"):
+        self.L, self.n_cand, self.dev = L, n_cand, torch.device(device)
+        self.depthwise = L.groups != 1
+        self.desc = B.make_desc(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad, L.groups)
+        self.act_kind = B.ACT_PLANAR if self.depthwise else B.ACT
+        self.wgt_kind = B.WGT_PLANAR if self.depthwise else B.WGT
+        d = self.dev
+        f32, i8, i32, f64 = torch.float32, torch.int8, torch.int32, torch.float64
+        self.x = torch.empty(L.x_shape, dtype=f32, device=d)
+        self.w = torch.empty(L.w_shape, dtype=f32, device=d)
+        self.dy = torch.empty(L.y_shape, dtype=f32, device=d)
+        self.ratios = torch.empty(n_cand, dtype=f32, device=d)
+        self.xq = torch.empty(B.int8t_code_bytes(L.x_shape, self.act_kind), dtype=i8, device=d)
+        self.wq = torch.empty(B.int8t_code_bytes(L.w_shape, self.wgt_kind), dtype=i8, device=d)
+        self.dyq = torch.empty(B.int8t_code_bytes(L.y_shape, self.act_kind), dtype=i8, device=d)
+        self.sx = torch.empty(1, dtype=f32, device=d)
+        self.sw = torch.empty(1, dtype=f32, device=d)
+        self.sdy = torch.empty(1, dtype=f32, device=d)
+        self.clip = torch.empty(1, dtype=f32, device=d)
+        self.dev_search = torch.empty(1, dtype=f64, device=d)
+        self.dev_all = torch.empty(n_cand, dtype=f64, device=d)
+        self.dev_final = torch.empty(1, dtype=f64, device=d)
+        self.y = torch.empty(L.y_shape, dtype=f32, device=d)
+        self.dx = torch.empty(L.x_shape, dtype=f32, device=d)
+        self.dw = torch.empty(L.w_shape, dtype=f32, device=d)
+        self.y_acc = torch.empty(L.y_shape, dtype=i32, device=d) if keep_acc else None
+        self.dx_acc = torch.empty(L.x_shape, dtype=i32, device=d) if keep_acc else None
+        self.dw_acc = torch.empty(L.w_shape, dtype=i32, device=d) if keep_acc else None
+        n_y = int(np.prod(L.y_shape))
+        ws = max(B.int8t_quantize_workspace_bytes(L.x_shape, self.act_kind),
+                 B.int8t_quantize_workspace_bytes(L.w_shape, self.wgt_kind),
+                 B.int8t_quantize_workspace_bytes(L.y_shape, self.act_kind),
+                 B.int8t_workspace_bytes(B.OP_DSGC, None, n_y, n_cand),
+                 B.int8t_workspace_bytes(B.OP_CONV_BWD_WEIGHT, self.desc), 256)
+        self.ws = torch.empty(ws, dtype=torch.uint8, device=d)
+
+    def upload(self, x: np.ndarray, w: np.ndarray, dy: np.ndarray, ratios: np.ndarray):
+        self.x.copy_(torch.from_numpy(np.ascontiguousarray(x)))
+        self.w.copy_(torch.from_numpy(np.ascontiguousarray(w)))
+        self.dy.copy_(torch.from_numpy(np.ascontiguousarray(dy)))
+        self.ratios.copy_(torch.from_numpy(np.ascontiguousarray(ratios, dtype=np.float32)))
+
+    # -- the individual calls -------------------------------------------------------------------
+    def quantize_x(self, stream=None):
+        B.int8t_quantize(self.x, self.L.x_shape, self.act_kind, None, B.ROUND_NEAREST_EVEN, 0,
+                         self.xq, self.sx, None, self.ws, stream)
+
+    def quantize_w(self, stream=None):
+        B.int8t_quantize(self.w, self.L.w_shape, self.wgt_kind, None, B.ROUND_NEAREST_EVEN, 0,
+                         self.wq, self.sw, None, self.ws, stream)
+
+    def dsgc(self, seed: int, stream=None):
+        B.int8t_dsgc_clip(self.dy, self.dy.numel(), self.ratios, self.n_cand, B.ROUND_STOCHASTIC, seed,
+                          self.clip, self.dev_search, self.dev_all, self.ws, stream)
+
+    def quantize_dy(self, seed: int, stream=None):
+        B.int8t_quantize(self.dy, self.L.y_shape, self.act_kind, self.clip, B.ROUND_STOCHASTIC, seed,
+                         self.dyq, self.sdy, self.dev_final, self.ws, stream)
+
+    def fwd(self, stream=None):
+        B.int8t_conv_fwd(self.desc, self.xq, self.sx, self.wq, self.sw, self.y, self.y_acc, None, stream)
+
+    def bwd_data(self, stream=None):
+        B.int8t_conv_bwd_data(self.desc, self.dyq, self.sdy, self.wq, self.sw, self.dx, self.dx_acc, None,
+                              stream)
+
+    def bwd_weight(self, stream=None):
+        B.int8t_conv_bwd_weight(self.desc, self.xq, self.sx, self.dyq, self.sdy, self.dw, self.dw_acc,
+                                self.ws, stream)
+
+    def run(self, seed: int = 0, stream=None):
+        """The whole hot path once."""
+        self.quantize_x(stream)
+        self.quantize_w(stream)
+        self.dsgc(seed, stream)
+        self.quantize_dy(seed, stream)
+        self.fwd(stream)
+        self.bwd_data(stream)
+        self.bwd_weight(stream)
+
+    # -- host views of the library's code layouts (tests only need numpy reshapes) -----------------
+    def codes_x(self) -> np.ndarray:
+        return unpack_act(self.xq.cpu().numpy(), self.L.x_shape, self.depthwise)
+
+    def codes_dy(self) -> np.ndarray:
+        return unpack_act(self.dyq.cpu().numpy(), self.L.y_shape, self.depthwise)
+
+    def codes_w(self):
+        return unpack_wgt(self.wq.cpu().numpy(), self.L.w_shape, self.depthwise)
+
+
+def unpack_act(q: np.ndarray, shape, planar: bool) -> np.ndarray:
+    """Library layout -> logical N,C,H,W codes.  Checks that channel padding is zero."""
+    N, Cc, H, W = shape
+    if planar:
+        return q.reshape(N, Cc, H, W)
+    Cp = pad16(Cc)
+    v = q.reshape(N, H, W, Cp)
+    assert not v[..., Cc:].any(), "channel padding of the code tensor must be zero"
+    return np.ascontiguousarray(v[..., :Cc].transpose(0, 3, 1, 2))
+
+
+def unpack_wgt(q: np.ndarray, shape, planar: bool):
+    """Library layout -> (logical K,Cg,R,S codes, same from the backward-data copy or None)."""
+    K, Cg, R, S = shape
+    if planar:
+        return q.reshape(K, Cg, R, S), None
+    Cp, Kp = pad16(Cg), pad16(K)
+    n1 = K * R * S * Cp
+    a = q[:n1].reshape(K, R, S, Cp)
+    off = align256(n1)
+    b = q[off:off + Cg * R * S * Kp].reshape(Cg, R, S, Kp)
+    assert not a[..., Cg:].any() and not b[..., K:].any(), "padding of the weight codes must be zero"
+    return (np.ascontiguousarray(a[..., :Cg].transpose(0, 3, 1, 2)),
+            np.ascontiguousarray(b[..., :K].transpose(3, 0, 1, 2)))

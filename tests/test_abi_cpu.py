@@ -1,0 +1,120 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every function the
+header declares, sizes layouts and scratch as documented, and rejects bad arguments before any
+launch."""
+import ctypes as C
+import math
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_1912_12607_amd", "csrc", "libint8t.so")
+HDR = os.path.join(ROOT, "include", "int8t.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_1912_12607_amd import build
+        build.build(force=False)
+    L = C.CDLL(LIB)
+    L.int8t_code_bytes.restype = C.c_size_t
+    L.int8t_workspace_bytes.restype = C.c_size_t
+    L.int8t_quantize_workspace_bytes.restype = C.c_size_t
+    L.int8t_status_string.restype = C.c_char_p
+    L.int8t_dclr_scale.restype = C.c_double
+    L.int8t_dclr_scale.argtypes = [C.c_double] * 3
+    return L
+
+
+class Desc(C.Structure):
+    _fields_ = [(n, C.c_int) for n in
+                ("N", "C", "H", "W", "K", "R", "S", "stride_h", "stride_w", "pad_h", "pad_w", "groups")]
+
+
+def dims(*v):
+    return (C.c_int * 4)(*v)
+
+
+def test_every_declared_symbol_is_exported(lib):
+    text = open(HDR).read()
+    names = set(re.findall(r"\b(int8t_[a-z_0-9]+)\s*\(", text))
+    assert {"int8t_quantize", "int8t_dsgc_clip", "int8t_conv_fwd", "int8t_conv_bwd_data",
+            "int8t_conv_bwd_weight"} <= names
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_binding_names_match_header():
+    text = open(os.path.join(ROOT, "paper_1912_12607_amd", "binding.py")).read()
+    hdr = set(re.findall(r"\b(int8t_[a-z_0-9]+)\s*\(", open(HDR).read()))
+    for n in hdr:
+        assert f"def {n}(" in text, n
+
+
+def test_code_bytes(lib):
+    assert lib.int8t_code_bytes(dims(2, 16, 16, 16), 0) == 2 * 16 * 16 * 16
+    assert lib.int8t_code_bytes(dims(64, 24, 56, 56), 0) == 64 * 56 * 56 * 32      # C padded to 32
+    assert lib.int8t_code_bytes(dims(64, 24, 56, 56), 2) == 64 * 24 * 56 * 56      # planar
+    k, c, r, s = 70, 33, 3, 3
+    n1 = k * r * s * 48
+    assert lib.int8t_code_bytes(dims(k, c, r, s), 1) == ((n1 + 255) // 256) * 256 + c * r * s * 80
+    assert lib.int8t_code_bytes(dims(k, c, r, s), 3) == k * c * r * s
+    assert lib.int8t_code_bytes(dims(0, 1, 1, 1), 0) == 0
+    assert lib.int8t_code_bytes(dims(2, 2, 2, 2), 7) == 0
+
+
+def test_workspace_sizes(lib):
+    assert lib.int8t_quantize_workspace_bytes(dims(2, 16, 16, 16), 0) >= 4096 + 8 * 24
+    assert lib.int8t_quantize_workspace_bytes(dims(2, 16, 16, -1), 0) == 0
+    assert lib.int8t_workspace_bytes(1, None, C.c_size_t(1 << 20), 32) > 512 * 64 * 16
+    d = Desc(64, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1, 1)
+    assert lib.int8t_workspace_bytes(4, C.byref(d), C.c_size_t(0), 0) >= 64 * 9 * 64 * 4
+    assert lib.int8t_workspace_bytes(2, C.byref(d), C.c_size_t(0), 0) == 0
+    bad = Desc(64, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1, 2)     # grouped but not depthwise
+    assert lib.int8t_workspace_bytes(4, C.byref(bad), C.c_size_t(0), 0) == 0
+
+
+def test_dclr_scale_eq7(lib):
+    assert lib.int8t_dclr_scale(0.0, 20.0, 0.1) == 1.0
+    assert lib.int8t_dclr_scale(0.05, 20.0, 0.1) == pytest.approx(math.exp(-1.0), rel=1e-15)
+    assert lib.int8t_dclr_scale(0.5, 20.0, 0.1) == 0.1
+
+
+def test_argument_errors_before_any_launch(lib):
+    vp = C.c_void_p
+    fake = vp(0x1000)            # aligned, never dereferenced on these paths
+    odd = vp(0x1004)
+    q = lib.int8t_quantize
+    q.restype = C.c_int
+    q.argtypes = [vp, C.POINTER(C.c_int), C.c_int, vp, C.c_int, C.c_uint64, vp, vp, vp, vp, C.c_size_t, vp]
+    assert q(None, dims(1, 1, 1, 1), 0, None, 0, 0, fake, fake, None, fake, 1 << 20, None) == 1
+    assert q(fake, dims(1, 0, 1, 1), 0, None, 0, 0, fake, fake, None, fake, 1 << 20, None) == 2
+    assert q(fake, dims(1, 1, 1, 1), 5, None, 0, 0, fake, fake, None, fake, 1 << 20, None) == 3
+    assert q(fake, dims(1, 1, 1, 1), 0, None, 2, 0, fake, fake, None, fake, 1 << 20, None) == 3
+    assert q(odd, dims(1, 1, 1, 1), 0, None, 0, 0, fake, fake, None, fake, 1 << 20, None) == 3
+    assert q(fake, dims(1, 1, 1, 1), 0, None, 0, 0, fake, fake, None, fake, 16, None) == 4
+    assert q(fake, dims(1, 1, 1, 1), 0, None, 0, 0, fake, fake, None, None, 0, None) == 1
+    g = lib.int8t_dsgc_clip
+    g.restype = C.c_int
+    g.argtypes = [vp, C.c_size_t, vp, C.c_int, C.c_int, C.c_uint64, vp, vp, vp, vp, C.c_size_t, vp]
+    assert g(fake, 100, fake, 0, 1, 0, fake, fake, None, fake, 1 << 24, None) == 3
+    assert g(fake, 100, fake, 65, 1, 0, fake, fake, None, fake, 1 << 24, None) == 3
+    assert g(fake, 0, fake, 4, 1, 0, fake, fake, None, fake, 1 << 24, None) == 2
+    assert g(fake, 100, None, 4, 1, 0, fake, fake, None, fake, 1 << 24, None) == 1
+    assert g(fake, 100, fake, 4, 1, 0, fake, fake, None, fake, 64, None) == 4
+    for name in ("int8t_conv_fwd", "int8t_conv_bwd_data", "int8t_conv_bwd_weight"):
+        f = getattr(lib, name)
+        f.restype = C.c_int
+        f.argtypes = [C.POINTER(Desc), vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        good = Desc(1, 4, 5, 5, 4, 3, 3, 1, 1, 1, 1, 1)
+        assert f(None, fake, fake, fake, fake, fake, None, fake, 1 << 20, None) == 1
+        assert f(C.byref(Desc(1, 4, 5, 5, 4, 3, 3, 0, 1, 1, 1, 1)), fake, fake, fake, fake, fake, None, fake, 1 << 20, None) == 2
+        assert f(C.byref(Desc(1, 4, 5, 5, 6, 3, 3, 1, 1, 1, 1, 2)), fake, fake, fake, fake, fake, None, fake, 1 << 20, None) == 2
+        assert f(C.byref(Desc(1, 4, 2, 2, 4, 7, 7, 1, 1, 0, 0, 1)), fake, fake, fake, fake, fake, None, fake, 1 << 20, None) == 2
+        assert f(C.byref(good), None, fake, fake, fake, fake, None, fake, 1 << 20, None) == 1
+        assert f(C.byref(good), odd, fake, fake, fake, fake, None, fake, 1 << 20, None) == 3
+    f = lib.int8t_conv_bwd_weight
+    assert f(C.byref(Desc(1, 4, 5, 5, 4, 3, 3, 1, 1, 1, 1, 1)), fake, fake, fake, fake, fake, None, fake, 8, None) == 4
+    assert lib.int8t_status_string(4) == b"workspace too small"

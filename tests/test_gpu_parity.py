@@ -1,0 +1,364 @@
+"""GPU parity: every C-ABI call against the CPU oracle, element by element, on seeded inputs.
+
+Bars: int8 codes and int32 accumulators bit-exact; dequantized fp32 outputs within 1e-6 relative
+(three fp32 roundings on the GPU -- int32->fp32, s_a*s_b, the product -- against one rounding of
+the exact double product in the oracle: <= 3 * 2^-24 = 1.8e-7); direction deviations within 1e-9
+absolute (both sides sum in fp64, only the order differs: error <= n * 2^-53 relative to sums
+whose ratio is <= 1).
+"""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+if not torch.cuda.is_available():
+    pytest.skip("no GPU", allow_module_level=True)
+
+import oracle  # noqa: E402
+from paper_1912_12607_amd import binding as B  # noqa: E402
+from paper_1912_12607_amd import inputs  # noqa: E402
+from paper_1912_12607_amd.step import LayerStep, align256, pad16, unpack_act, unpack_wgt  # noqa: E402
+
+DEV = torch.device("cuda:0")
+RTN, STO = B.ROUND_NEAREST_EVEN, B.ROUND_STOCHASTIC
+DEV_TOL = 1e-9
+REL_TOL = 1e-6
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def pack_act(q):
+    N, C, H, W = q.shape
+    out = np.zeros((N, H, W, pad16(C)), np.int8)
+    out[..., :C] = q.transpose(0, 2, 3, 1)
+    return out.reshape(-1)
+
+
+def pack_wgt(w):
+    K, Cg, R, S = w.shape
+    Cp, Kp = pad16(Cg), pad16(K)
+    n1 = K * R * S * Cp
+    buf = np.zeros(align256(n1) + Cg * R * S * Kp, np.int8)
+    a = np.zeros((K, R, S, Cp), np.int8)
+    a[..., :Cg] = w.transpose(0, 2, 3, 1)
+    b = np.zeros((Cg, R, S, Kp), np.int8)
+    b[..., :K] = w.transpose(1, 2, 3, 0)
+    buf[:n1] = a.reshape(-1)
+    buf[align256(n1):] = b.reshape(-1)
+    return buf
+
+
+def gpu_quantize(x, kind, clip=None, mode=RTN, seed=0, want_dev=False):
+    x = np.ascontiguousarray(x, np.float32)
+    dims = x.shape
+    xd = dev(x)
+    q = torch.full((B.int8t_code_bytes(dims, kind),), 77, dtype=torch.int8, device=DEV)
+    s = torch.zeros(1, dtype=torch.float32, device=DEV)
+    d = torch.zeros(1, dtype=torch.float64, device=DEV) if want_dev else None
+    ws = torch.empty(max(B.int8t_quantize_workspace_bytes(dims, kind), 256), dtype=torch.uint8, device=DEV)
+    cd = dev(np.array([clip], np.float32)) if clip is not None else None
+    B.int8t_quantize(xd, dims, kind, cd, mode, seed, q, s, d, ws)
+    torch.cuda.synchronize()
+    return q.cpu().numpy(), np.float32(s.item()), (d.item() if want_dev else None)
+
+
+ACT_SHAPES = [(2, 16, 16, 16), (1, 3, 5, 7), (3, 24, 14, 14), (2, 70, 17, 17), (1, 144, 9, 3),
+              (2, 64, 8, 8), (1, 1, 1, 1), (5, 130, 1, 66)]
+
+
+@pytest.mark.parametrize("shape", ACT_SHAPES)
+@pytest.mark.parametrize("mode", [RTN, STO])
+def test_quantize_act_bit_exact(shape, mode):
+    r = np.random.RandomState(hash(shape) % 1000)
+    x = r.standard_normal(shape).astype(np.float32) * 3
+    for clip in (None, 2.5):
+        q, s, d = gpu_quantize(x, B.ACT, clip, mode, seed=11, want_dev=True)
+        qo, so = oracle.quantize(x, c=clip, mode=mode, seed=11)
+        assert s == so
+        assert np.array_equal(unpack_act(q, shape, False), qo)
+        assert abs(d - oracle.deviation(x, qo, so)) < DEV_TOL
+
+
+def test_quantize_act_ties_and_representable():
+    k = np.arange(-127, 128, dtype=np.int32)
+    x = np.zeros((1, 5, 17, 15), np.float32)
+    x.reshape(-1)[:255] = k * 0.5
+    x.reshape(-1)[300:308] = [0.5, 1.5, 2.5, 3.5, -0.5, -1.5, -2.5, 62.5]
+    q, s, _ = gpu_quantize(x, B.ACT, clip=127.0)
+    qo, so = oracle.quantize(x, c=127.0)
+    assert np.array_equal(unpack_act(q, x.shape, False), qo) and s == so == 1.0
+
+
+@pytest.mark.parametrize("shape", [(32, 16, 3, 3), (5, 3, 1, 7), (24, 144, 1, 1), (70, 33, 3, 3)])
+@pytest.mark.parametrize("mode", [RTN, STO])
+def test_quantize_wgt_both_copies(shape, mode):
+    w = (np.random.RandomState(3).standard_normal(shape) * 0.1).astype(np.float32)
+    q, s, d = gpu_quantize(w, B.WGT, None, mode, seed=5, want_dev=True)
+    qo, so = oracle.quantize(w, mode=mode, seed=5)
+    a, b = unpack_wgt(q, shape, False)
+    assert s == so and np.array_equal(a, qo) and np.array_equal(b, qo)
+    assert abs(d - oracle.deviation(w, qo, so)) < DEV_TOL
+
+
+@pytest.mark.parametrize("shape", [(2, 4, 5, 5), (1, 3, 7, 9), (3, 144, 14, 14), (1, 1, 1, 3)])
+@pytest.mark.parametrize("mode", [RTN, STO])
+def test_quantize_planar(shape, mode):
+    x = np.random.RandomState(4).standard_normal(shape).astype(np.float32)
+    for kind in (B.ACT_PLANAR, B.WGT_PLANAR):
+        q, s, d = gpu_quantize(x, kind, None, mode, seed=2 ** 40 + 9, want_dev=True)
+        qo, so = oracle.quantize(x, mode=mode, seed=2 ** 40 + 9)
+        assert s == so and np.array_equal(q.reshape(shape), qo)
+        assert abs(d - oracle.deviation(x, qo, so)) < DEV_TOL
+
+
+def test_quantize_zero_tensor_and_nan():
+    z = np.zeros((2, 5, 4, 4), np.float32)
+    for mode in (RTN, STO):
+        q, s, d = gpu_quantize(z, B.ACT, None, mode, seed=1, want_dev=True)
+        assert not q.any() and s == 0.0 and d == 0.0
+    x = np.random.RandomState(1).standard_normal((1, 16, 4, 4)).astype(np.float32)
+    x[0, 3, 2, 1] = np.nan
+    q, s, _ = gpu_quantize(x, B.ACT)
+    qo, so = oracle.quantize(x)
+    assert s == so and np.array_equal(unpack_act(q, x.shape, False), qo) and qo[0, 3, 2, 1] == 0
+
+
+def gpu_dsgc(g, ratios, mode, seed):
+    g = np.ascontiguousarray(g, np.float32).reshape(-1)
+    J = len(ratios)
+    clip = torch.zeros(1, dtype=torch.float32, device=DEV)
+    d = torch.zeros(1, dtype=torch.float64, device=DEV)
+    da = torch.zeros(J, dtype=torch.float64, device=DEV)
+    ws = torch.empty(B.int8t_workspace_bytes(B.OP_DSGC, None, g.size, J), dtype=torch.uint8, device=DEV)
+    B.int8t_dsgc_clip(dev(g), g.size, dev(np.asarray(ratios, np.float32)), J, mode, seed, clip, d, da, ws)
+    torch.cuda.synchronize()
+    return np.float32(clip.item()), d.item(), da.cpu().numpy()
+
+
+def check_dsgc(g, ratios, mode, seed):
+    clip, d, da = gpu_dsgc(g, ratios, mode, seed)
+    o = oracle.dsgc(np.asarray(g, np.float32).reshape(-1), ratios, mode=mode, seed=seed)
+    assert np.all(np.abs(da - o["dev"]) < DEV_TOL)
+    # several candidates may tie within rounding of the fp64 sums: accept the GPU's winner iff the
+    # oracle's deviation at it is within tolerance of the oracle's minimum, and the clip is that candidate's
+    j = int(np.argmin(np.abs(o["clips"] - clip)))
+    assert clip == o["clips"][j]
+    assert o["dev"][j] - o["deviation"] <= 2 * DEV_TOL
+    assert abs(d - o["dev"][j]) < DEV_TOL
+    return o, j
+
+
+@pytest.mark.parametrize("n", [1, 3, 1000, 16384, 100003])
+@pytest.mark.parametrize("mode", [RTN, STO])
+def test_dsgc_small(n, mode):
+    r = np.random.RandomState(n % 97)
+    g = (r.standard_t(3, size=n) * 1e-3).astype(np.float32)
+    if n > 100:
+        g[r.choice(n, max(1, n // 10000), replace=False)] *= 100
+    check_dsgc(g, inputs.default_ratios(32), mode, seed=n)
+
+
+def test_dsgc_candidate_counts_and_degenerate():
+    r = np.random.RandomState(5)
+    g = (r.standard_t(3, size=50000) * 1e-3).astype(np.float32)
+    for J in (1, 7, 33, 64):
+        ratios = np.exp2(-np.arange(J) / 8.0).astype(np.float32)
+        check_dsgc(g, ratios, STO, seed=3)
+    clip, d, da = gpu_dsgc(np.zeros(1000, np.float32), [1.0, 0.5], STO, 1)
+    assert clip == 0.0 and d == 0.0 and not da.any()
+    # representable inputs, ratio 1: zero deviation
+    k = r.randint(-127, 128, size=4096)
+    k[0] = 127
+    g = (k * 2.0 ** -12).astype(np.float32)
+    clip, d, da = gpu_dsgc(g, [1.0, 0.5], STO, 9)
+    assert clip == np.float32(127 * 2.0 ** -12) and abs(d) < 1e-15
+
+
+# (N, C, H, W, K, R, S, stride, pad, groups)
+CONV_SHAPES = [
+    (2, 16, 16, 16, 32, 3, 3, (1, 1), (1, 1), 1),
+    (1, 3, 5, 5, 4, 3, 3, (1, 1), (1, 1), 1),
+    (2, 24, 9, 9, 144, 1, 1, (1, 1), (0, 0), 1),
+    (2, 144, 7, 7, 24, 1, 1, (1, 1), (0, 0), 1),
+    (1, 20, 11, 13, 70, 3, 3, (2, 2), (0, 0), 1),
+    (2, 33, 8, 9, 17, 3, 3, (2, 1), (1, 0), 1),
+    (1, 48, 9, 17, 40, 1, 7, (1, 1), (0, 3), 1),
+    (1, 48, 17, 9, 40, 7, 1, (1, 1), (3, 0), 1),
+    (3, 64, 14, 14, 130, 3, 3, (1, 1), (1, 1), 1),
+    (2, 130, 6, 6, 200, 3, 3, (1, 1), (1, 1), 1),
+    (1, 8, 12, 12, 8, 5, 5, (3, 2), (2, 2), 1),
+    (2, 12, 9, 9, 12, 3, 3, (1, 1), (1, 1), 12),      # depthwise
+    (1, 5, 11, 8, 5, 3, 3, (2, 2), (1, 1), 5),        # depthwise stride 2
+    (2, 7, 6, 9, 7, 5, 3, (1, 2), (2, 0), 7),         # depthwise odd filter
+]
+
+
+@pytest.mark.parametrize("shape", CONV_SHAPES)
+def test_conv_three_passes_bit_exact(shape):
+    N, C, H, W, K, R, S, st, pd, g = shape
+    od = oracle.make_desc(N, C, H, W, K, R, S, st, pd, g)
+    gd = B.make_desc(N, C, H, W, K, R, S, st, pd, g)
+    P, Q = oracle.out_hw(od)
+    r = np.random.RandomState(abs(hash(shape)) % 2 ** 31)
+    x = r.randint(-127, 128, size=(N, C, H, W)).astype(np.int8)
+    w = r.randint(-127, 128, size=(K, C // g, R, S)).astype(np.int8)
+    dy = r.randint(-127, 128, size=(N, K, P, Q)).astype(np.int8)
+    dwise = g != 1
+    xq = dev(x.reshape(-1) if dwise else pack_act(x))
+    dyq = dev(dy.reshape(-1) if dwise else pack_act(dy))
+    wq = dev(w.reshape(-1) if dwise else pack_wgt(w))
+    sx, sw, sdy = (dev(np.array([v], np.float32)) for v in (0.0123, 3.3e-3, 7.7e-6))
+    ws = torch.empty(max(256, B.int8t_workspace_bytes(B.OP_CONV_BWD_WEIGHT, gd)), dtype=torch.uint8, device=DEV)
+
+    def run(fn, a, sa, b, sb, shape_out):
+        out = torch.full(shape_out, float("nan"), dtype=torch.float32, device=DEV)
+        acc = torch.full(shape_out, -12345, dtype=torch.int32, device=DEV)
+        fn(gd, a, sa, b, sb, out, acc, ws)
+        torch.cuda.synchronize()
+        return out.cpu().numpy(), acc.cpu().numpy()
+
+    for name, got, want64, s1, s2 in (
+        ("fwd", run(B.int8t_conv_fwd, xq, sx, wq, sw, (N, K, P, Q)), oracle.conv_fwd(od, x, w), 0.0123, 3.3e-3),
+        ("bwd_data", run(B.int8t_conv_bwd_data, dyq, sdy, wq, sw, (N, C, H, W)),
+         oracle.conv_bwd_data(od, dy, w), 7.7e-6, 3.3e-3),
+        ("bwd_weight", run(B.int8t_conv_bwd_weight, xq, sx, dyq, sdy, (K, C // g, R, S)),
+         oracle.conv_bwd_weight(od, x, dy), 0.0123, 7.7e-6),
+    ):
+        out, acc = got
+        want32, ov = oracle.wrap32(want64)
+        assert ov == 0
+        assert np.array_equal(acc, want32), name
+        ref = oracle.dequant(want32, np.float32(s1), np.float32(s2))
+        assert np.all(np.abs(out - ref) <= REL_TOL * np.abs(ref)), name
+
+
+def test_bwd_weight_int32_wrap():
+    # 133145 products of 127*127 exceed 2^31: the accumulator wraps to a known value
+    N, P, Q = 5, 31, 859
+    od = oracle.make_desc(N, 1, P, Q, 1, 1, 1)
+    gd = B.make_desc(N, 1, P, Q, 1, 1, 1)
+    x = np.full((N, 1, P, Q), 127, np.int8)
+    ws = torch.empty(max(256, B.int8t_workspace_bytes(B.OP_CONV_BWD_WEIGHT, gd)), dtype=torch.uint8, device=DEV)
+    out = torch.zeros((1, 1, 1, 1), dtype=torch.float32, device=DEV)
+    acc = torch.zeros((1, 1, 1, 1), dtype=torch.int32, device=DEV)
+    one = dev(np.array([1.0], np.float32))
+    xq = dev(pack_act(x))
+    B.int8t_conv_bwd_weight(gd, xq, one, xq, one, out, acc, ws)
+    torch.cuda.synchronize()
+    want32, ov = oracle.wrap32(oracle.conv_bwd_weight(od, x, x))
+    assert ov == 1 and acc.item() == want32.item() == -2147471591
+    assert out.item() == np.float32(-2147471591)
+
+
+def run_layer(cfg, li, keep_acc=True):
+    L, x, w, dy = inputs.make_layer_inputs(cfg, li)
+    st = LayerStep(L, n_cand=32, keep_acc=keep_acc)
+    st.upload(x, w, dy, inputs.default_ratios(32))
+    st.run(seed=0)
+    torch.cuda.synchronize()
+    return L, x, w, dy, st
+
+
+def test_config0_full_step_elementwise():
+    L, x, w, dy, st = run_layer(0, 0)
+    od = oracle.make_desc(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad, L.groups)
+    xq, sx = oracle.quantize(x)
+    wq, sw = oracle.quantize(w)
+    o = oracle.dsgc(dy.reshape(-1), inputs.default_ratios(32), mode=STO, seed=0)
+    assert np.all(np.abs(st.dev_all.cpu().numpy() - o["dev"]) < DEV_TOL)
+    assert st.clip.item() == o["clip"]
+    dyq, sdy = oracle.quantize(dy, c=o["clip"], mode=STO, seed=0)
+    assert np.array_equal(st.codes_x(), xq) and st.sx.item() == sx
+    a, b = st.codes_w()
+    assert np.array_equal(a, wq) and np.array_equal(b, wq) and st.sw.item() == sw
+    assert np.array_equal(st.codes_dy(), dyq) and st.sdy.item() == sdy
+    assert abs(st.dev_final.item() - oracle.deviation(dy, dyq, sdy)) < DEV_TOL
+    assert abs(st.dev_final.item() - st.dev_search.item()) < DEV_TOL
+    for got, acc, want64, s1, s2 in (
+        (st.y, st.y_acc, oracle.conv_fwd(od, xq, wq), sx, sw),
+        (st.dx, st.dx_acc, oracle.conv_bwd_data(od, dyq, wq), sdy, sw),
+        (st.dw, st.dw_acc, oracle.conv_bwd_weight(od, xq, dyq), sx, sdy),
+    ):
+        want32, ov = oracle.wrap32(want64)
+        assert ov == 0 and np.array_equal(acc.cpu().numpy(), want32)
+        ref = oracle.dequant(want32, s1, s2)
+        assert np.all(np.abs(got.cpu().numpy() - ref) <= REL_TOL * np.abs(ref))
+    phi = B.int8t_dclr_scale(st.dev_final.item())
+    assert phi == oracle.dclr(st.dev_final.item())
+
+
+FULL_LAYERS = [(1, 0), (2, 0), (2, 1), (2, 2), (3, 0), (3, 1), (3, 2), (4, 0), (4, 1), (4, 2)]
+
+
+@pytest.mark.parametrize("cfg,li", FULL_LAYERS)
+def test_full_size_layers(cfg, li):
+    """Benchmark-size layers in the benchmark's launch configuration: quantizers compared in
+    full, the clip search in full, convolutions on sampled outputs the oracle computes one by one."""
+    L, x, w, dy, st = run_layer(cfg, li)
+    od = oracle.make_desc(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad, L.groups)
+    xq, sx = oracle.quantize(x)
+    wq, sw = oracle.quantize(w)
+    assert np.array_equal(st.codes_x(), xq) and st.sx.item() == sx
+    a, b = st.codes_w()
+    assert np.array_equal(a, wq) and st.sw.item() == sw and (b is None or np.array_equal(b, wq))
+    o = oracle.dsgc(dy.reshape(-1), inputs.default_ratios(32), mode=STO, seed=0)
+    assert np.all(np.abs(st.dev_all.cpu().numpy() - o["dev"]) < DEV_TOL)
+    clip = np.float32(st.clip.item())
+    j = int(np.argmin(np.abs(o["clips"] - clip)))
+    assert clip == o["clips"][j] and o["dev"][j] - o["deviation"] <= 2 * DEV_TOL
+    dyq, sdy = oracle.quantize(dy, c=clip, mode=STO, seed=0)
+    assert np.array_equal(st.codes_dy(), dyq) and st.sdy.item() == sdy
+    assert abs(st.dev_final.item() - o["dev"][j]) < DEV_TOL
+
+    r = np.random.RandomState(cfg * 10 + li)
+    y_acc, dx_acc, dw_acc = st.y_acc.cpu().numpy(), st.dx_acc.cpu().numpy(), st.dw_acc.cpu().numpy()
+    y, dx, dw = st.y.cpu().numpy(), st.dx.cpu().numpy(), st.dw.cpu().numpy()
+
+    def sample(shape, count):
+        pts = [tuple(int(r.randint(0, s)) for s in shape) for _ in range(count)]
+        corners = [tuple(0 for _ in shape), tuple(s - 1 for s in shape)]
+        return pts + corners
+
+    def cmp(acc, out, idx, want, s1, s2):
+        want32, _ = oracle.wrap32(np.array([want], np.int64))
+        assert acc[idx] == want32[0], (idx, acc[idx], want32[0])
+        ref = oracle.dequant(want32, s1, s2)[0]
+        assert abs(out[idx] - ref) <= REL_TOL * abs(ref)
+
+    for idx in sample(y_acc.shape, 600):
+        cmp(y_acc, y, idx, oracle.conv_fwd_at(od, xq, wq, *idx), sx, sw)
+    for idx in sample(dx_acc.shape, 600):
+        cmp(dx_acc, dx, idx, oracle.conv_bwd_data_at(od, dyq, wq, *idx), sdy, sw)
+    nw = 60 if L.N * L.P * L.Q > 100000 else 200
+    for idx in sample(dw_acc.shape, nw):
+        cmp(dw_acc, dw, idx, oracle.conv_bwd_weight_at(od, xq, dyq, *idx), sx, sdy)
+    # property that holds at any size: the exact adjoint identity on the int32 accumulators
+    if np.abs(y_acc).max() < 2 ** 31 - 1:
+        lhs = int((dyq.astype(np.int64) * y_acc).sum())
+        assert lhs == int((dx_acc.astype(np.int64) * xq).sum()) == int((dw_acc.astype(np.int64) * wq).sum())
+
+
+def test_same_seed_same_codes_different_seed_differs():
+    L, x, w, dy = inputs.make_layer_inputs(0, 0)
+    a, _, _ = gpu_quantize(dy, B.ACT, 0.01, STO, seed=42)
+    b, _, _ = gpu_quantize(dy, B.ACT, 0.01, STO, seed=42)
+    c, _, _ = gpu_quantize(dy, B.ACT, 0.01, STO, seed=43)
+    assert np.array_equal(a, b) and not np.array_equal(a, c)
+    # layout independence: planar and channels-last layouts hold the same logical codes
+    p, _, _ = gpu_quantize(dy, B.ACT_PLANAR, 0.01, STO, seed=42)
+    assert np.array_equal(unpack_act(a, dy.shape, False), p.reshape(dy.shape))
+
+
+def test_error_paths_on_device():
+    x = torch.zeros(64, dtype=torch.float32, device=DEV)
+    q = torch.zeros(1024, dtype=torch.int8, device=DEV)
+    s = torch.zeros(1, dtype=torch.float32, device=DEV)
+    with pytest.raises(B.Int8tError) as e:
+        B.int8t_quantize(x, (1, 4, 4, 4), B.ACT, None, RTN, 0, q, s, None, torch.zeros(16, dtype=torch.uint8, device=DEV))
+    assert e.value.status == 4
+    with pytest.raises(B.Int8tError) as e:
+        B.int8t_quantize(x, (1, 4, 4, 4), 9, None, RTN, 0, q, s, None, None)
+    assert e.value.status == 3
