@@ -72,16 +72,19 @@ uint32_t orc_rng24(uint64_t seed, uint64_t index)
 
 /* ------------------------------------------------------------------ */
 /* Eq.1 / Eq.3 for one element.                                        */
-/*   inv = 127/c          one fp32 division                            */
-/*   t   = clip(x*inv, 127)  fp32; clip(x,c)/s == clip(x/s, 127) for   */
-/*         s > 0, evaluated on the scaled value so that |t| <= 127     */
-/*         holds exactly and codes never leave [-127,127]              */
-/*   mode 0: q = rint(t), ties to even                                 */
-/*   mode 1: Eq.3 with 24-bit probabilities:                           */
-/*         X = floor(t * 2^24)  (exact: power-of-two scaling)          */
+/*   inv = 127/c          one fp32 division (= 1/s)                    */
+/*   mode 0: t = clip(x*inv, 127) in fp32; clip(x,c)/s == clip(x/s,    */
+/*         127) for s > 0, evaluated on the scaled value so that       */
+/*         |t| <= 127 holds exactly and codes never leave [-127,127];  */
+/*         q = rint(t), ties to even                                   */
+/*   mode 1: Eq.3 with 24-bit probabilities.  The scaled value is      */
+/*         carried with 24 fraction bits:                              */
+/*         T = clip(x * (inv*2^24), 127*2^24)   one fp32 product; the  */
+/*             factor inv*2^24 is an exact power-of-two scaling        */
+/*         X = floor(T)                                                */
 /*         q = floor((X + u) / 2^24),  u = rng24(seed, index)          */
 /*         => q = floor(t)+1 with probability floor(frac*2^24)/2^24    */
-/* c <= 0 (all-zero tensor): every code is 0.                          */
+/* c <= 0 (all-zero tensor): every code is 0.  NaN -> code 0.          */
 /* ------------------------------------------------------------------ */
 static inline float orc_inv_scale(float c)
 {
@@ -90,15 +93,19 @@ static inline float orc_inv_scale(float c)
 
 static inline int orc_quantize_one(float x, float inv, int mode, uint64_t seed, uint64_t index)
 {
-    float t = x * inv;
-    if (t > 127.0f) t = 127.0f;
-    if (t < -127.0f) t = -127.0f;
-    if (t != t) t = 0.0f; /* NaN input: code 0 */
     if (mode == 0) {
+        float t = x * inv;
+        if (t > 127.0f) t = 127.0f;
+        if (t < -127.0f) t = -127.0f;
+        if (t != t) t = 0.0f;
         return (int)rintf(t); /* default rounding mode: nearest, ties to even */
     } else {
-        double T = (double)t * 16777216.0; /* exact */
-        int64_t X = (int64_t)floor(T);
+        float inv24 = inv * 16777216.0f;
+        float T = x * inv24;
+        if (T > 2130706432.0f) T = 2130706432.0f;   /* 127 * 2^24 */
+        if (T < -2130706432.0f) T = -2130706432.0f;
+        if (T != T) T = 0.0f;
+        int64_t X = (int64_t)floor((double)T);
         int64_t u = (int64_t)orc_rng24(seed, index);
         int64_t s = X + u;
         /* floor division by 2^24 */

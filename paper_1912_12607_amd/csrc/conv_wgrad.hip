@@ -23,7 +23,12 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 constexpr int WG_BN = 128;   // columns (r,s,c) per block
 constexpr int WG_BK = 64;    // pixels per reduction step
 
-__device__ __forceinline__ int wg_slot(int row, int g) { return row * 4 + (g ^ ((row >> 1) & 3)); }
+// LDS tile [row][64 pixel bytes] with an 80-byte row pitch (20 dwords).  wg_slot() is the index of
+// the 16-byte granule g of `row` in 16-byte units.  Eight consecutive rows at one granule land in
+// eight different 16-byte bank groups (the MFMA operand reads are conflict free); the xor with
+// row bits 3-4 spreads the loader's transposed stores, which walk rows with a stride of four.
+constexpr int WG_PITCH16 = 5;
+__device__ __forceinline__ int wg_slot(int row, int g) { return row * WG_PITCH16 + (g ^ ((row >> 3) & 3)); }
 
 // 4x4 byte transpose: in d[i] = 4 channels of pixel i; out o[c] = channel c of pixels 0..3.
 __device__ __forceinline__ void transpose4x4(const uint32_t d[4], uint32_t o[4]) {
@@ -41,8 +46,8 @@ __device__ __forceinline__ void transpose4x4(const uint32_t d[4], uint32_t o[4])
 template <int BM>
 __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
     constexpr int MI = BM / 64;
-    __shared__ __attribute__((aligned(16))) uint32_t sA[BM * 16];      // [k][64 pixel bytes], granule-swizzled
-    __shared__ __attribute__((aligned(16))) uint32_t sB[WG_BN * 16];   // [col][64 pixel bytes]
+    __shared__ __attribute__((aligned(16))) uint32_t sA[BM * WG_PITCH16 * 4];      // [k][64 pixel bytes]
+    __shared__ __attribute__((aligned(16))) uint32_t sB[WG_BN * WG_PITCH16 * 4];   // [col][64 pixel bytes]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -59,8 +64,8 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
 
     // ---- A loader (g_z): k-quad = tid % 16, pixel-quad = tid / 16, MI row halves --------------
     const int a_kq = tid & 15, a_pq = tid >> 4;
-    // ---- B loader (a): column-quad = tid % 32, pixel-quads tid/32 and tid/32 + 8 --------------
-    const int b_cq = tid & 31, b_pq = tid >> 5;
+    // ---- B loader (a): column-quad = tid % 32, pixel octet = tid / 32 ---------------------------
+    const int b_cq = tid & 31, b_po = tid >> 5;
     const int bcol = colbase + 4 * b_cq;
     const bool bcol_ok = bcol < ncolsp;
     int b_tr, b_ts, b_c;
@@ -88,23 +93,22 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
                     ra[h][i] = *reinterpret_cast<const uint32_t*>(a.dy + ((size_t)n * PQ + rem) * a.Kp + k);
             }
         }
-        // B: x[((n*H + ih)*W + iw)*Cp + c .. c+3] at this thread's filter tap
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int rem_first = rem0 + 4 * (b_pq + 8 * h);
+        // B: x[((n*H + ih)*W + iw)*Cp + c .. c+3] at this thread's filter tap, 8 consecutive pixels
+        {
+            const int rem_first = rem0 + 8 * b_po;
             // (p,q) of the first pixel: float estimate, then exact correction
             int p = (int)((float)rem_first * invQ);
             int q = rem_first - p * a.Q;
             if (q < 0) { --p; q += a.Q; }
             if (q >= a.Q) { ++p; q -= a.Q; }
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < 8; ++i) {
                 const int ih = p * a.stride_h - a.pad_h + b_tr;
                 const int iw = q * a.stride_w - a.pad_w + b_ts;
-                rb[h][i] = 0;
+                rb[i >> 2][i & 3] = 0;
                 if (bcol_ok && (rem_first + i) < PQ && (unsigned)ih < (unsigned)a.H &&
                     (unsigned)iw < (unsigned)a.W)
-                    rb[h][i] = *reinterpret_cast<const uint32_t*>(
+                    rb[i >> 2][i & 3] = *reinterpret_cast<const uint32_t*>(
                         a.x + (((size_t)n * a.H + ih) * a.W + iw) * a.Cp + b_c);
                 if (++q == a.Q) { q = 0; ++p; }
             }
@@ -131,13 +135,18 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
             for (int c = 0; c < 4; ++c)
                 sA[wg_slot(h * 64 + 4 * a_kq + c, a_pq >> 2) * 4 + (a_pq & 3)] = o[c];
         }
+        {
+            uint32_t o0[4], o1[4];
+            transpose4x4(rb[0], o0);
+            transpose4x4(rb[1], o1);
+            // pixel octet b_po = dwords 2*b_po, 2*b_po+1 of the row: granule b_po/2, 8-byte half b_po%2
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            uint32_t o[4];
-            transpose4x4(rb[h], o);
-            const int pq = b_pq + 8 * h;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) sB[wg_slot(4 * b_cq + c, pq >> 2) * 4 + (pq & 3)] = o[c];
+            for (int c = 0; c < 4; ++c) {
+                uint2 v;
+                v.x = o0[c];
+                v.y = o1[c];
+                *reinterpret_cast<uint2*>(&sB[wg_slot(4 * b_cq + c, b_po >> 1) * 4 + (b_po & 1) * 2]) = v;
+            }
         }
         __syncthreads();
         if (t + 1 < t_end) load_step(t + 1);
@@ -185,8 +194,14 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const WgradArgs a) {
     const int col = (int)(t - (size_t)k * ncolsp);
     const int rs = col / a.Cp, c = col - rs * a.Cp;
     if (c >= a.C) return;
-    int sum = 0;
-    for (int z = 0; z < a.splits; ++z) sum += a.partial[(size_t)z * total + t];
+    int s4[4] = {0, 0, 0, 0};
+    int z = 0;
+    for (; z + 3 < a.splits; z += 4) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) s4[u] += a.partial[(size_t)(z + u) * total + t];
+    }
+    for (; z < a.splits; ++z) s4[0] += a.partial[(size_t)z * total + t];
+    const int sum = (s4[0] + s4[1]) + (s4[2] + s4[3]);
     const size_t o = ((size_t)k * a.C + c) * (a.R * a.S) + rs;
     a.dw[o] = __fmul_rn((float)sum, __fmul_rn(a.sa[0], a.sb[0]));
     if (a.acc) a.acc[o] = sum;
@@ -197,8 +212,8 @@ int wgrad_splits(int N, int C, int K, int P, int Q, int R, int S) {
     const int BM = (K <= 64) ? 64 : 128;
     const int tiles = ((K + BM - 1) / BM) * ((R * S * Cp + WG_BN - 1) / WG_BN);
     const int chunks = N * ((P * Q + WG_BK - 1) / WG_BK);
-    int splits = (512 + tiles - 1) / tiles;
-    if (splits > chunks) splits = chunks;
+    int splits = (512 + tiles - 1) / tiles;          // about two blocks per compute unit
+    if (splits > chunks / 4) splits = chunks / 4;     // at least four reduction steps per block
     if (splits < 1) splits = 1;
     return splits;
 }

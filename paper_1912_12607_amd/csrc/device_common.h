@@ -70,25 +70,43 @@ __host__ __device__ __forceinline__ uint32_t seed_hi_term(uint64_t seed) {
 __device__ __forceinline__ float inv_scale_of(float c) { return (c > 0.0f) ? __fdiv_rn(127.0f, c) : 0.0f; }
 __device__ __forceinline__ float scale_of(float c) { return (c > 0.0f) ? __fdiv_rn(c, 127.0f) : 0.0f; }
 
-// Eq.1 on the scaled value: t = clip(x * inv, 127), |t| <= 127 exactly.
-__device__ __forceinline__ float scaled_clipped(float x, float inv) {
-    float t = __fmul_rn(x, inv);
-    return fminf(fmaxf(t, -127.0f), 127.0f);
+// floor(x) as int32 in one instruction (saturating).
+__device__ __forceinline__ int floor_to_int(float x) {
+    int r;
+    asm("v_cvt_flr_i32_f32 %0, %1" : "=v"(r) : "v"(x));
+    return r;
 }
 
-// One code.  STOCH: Eq.3 with 24-bit probabilities, q = floor((floor(t*2^24) + u) / 2^24).
+constexpr float kTwo24 = 16777216.0f;
+constexpr float kCodeMax24 = 2130706432.0f;   // 127 * 2^24
+
+// Eq.1 on the scaled value, nearest rounding: t = clip(x * inv, 127), |t| <= 127 exactly.
+__device__ __forceinline__ int round_nearest_code(float x, float inv) {
+    const float t = fminf(fmaxf(__fmul_rn(x, inv), -127.0f), 127.0f);
+    return (int)rintf(t);
+}
+// Eq.3 with 24-bit probabilities on the scaled value carried with 24 fraction bits:
+// T = clip(x * inv24, 127*2^24), inv24 = inv * 2^24;  q = floor((floor(T) + u) / 2^24).
+// floor(T) + u <= 2^31 - 1, so the 32-bit sum cannot overflow and q stays in [-127, 127].
+__device__ __forceinline__ int stochastic_sum(float x, float inv24, int u) {
+    const float T = fminf(fmaxf(__fmul_rn(x, inv24), -kCodeMax24), kCodeMax24);
+    return floor_to_int(T) + u;   // the code is this sum >> 24 (its signed top byte)
+}
+
+// One code, with NaN -> 0.
 template <bool STOCH>
 __device__ __forceinline__ int quantize_one(float x, float inv, uint32_t seed_lo, uint32_t seed_hi_mul,
                                             uint32_t index) {
-    float t = __fmul_rn(x, inv);
-    t = (t != t) ? 0.0f : t;                                 // NaN -> code 0
-    t = fminf(fmaxf(t, -127.0f), 127.0f);
     if (STOCH) {
-        const float T = __fmul_rn(t, 16777216.0f);          // exact
-        const int X = (int)floorf(T);                        // |X| <= 127 * 2^24
+        float T = __fmul_rn(x, __fmul_rn(inv, kTwo24));
+        T = (T != T) ? 0.0f : T;
+        T = fminf(fmaxf(T, -kCodeMax24), kCodeMax24);
         const int u = (int)rng24(seed_lo, seed_hi_mul, index);
-        return (X + u) >> 24;                                // X + u <= 2^31 - 1: no overflow
+        return (floor_to_int(T) + u) >> 24;
     } else {
+        float t = __fmul_rn(x, inv);
+        t = (t != t) ? 0.0f : t;
+        t = fminf(fmaxf(t, -127.0f), 127.0f);
         return (int)rintf(t);
     }
 }

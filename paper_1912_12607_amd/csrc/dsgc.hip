@@ -35,7 +35,8 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
     if (threadIdx.x < JC) {
         const int j = threadIdx.x;
         const float c = (j < jn) ? __fmul_rn(M, ratios[j0 + j]) : 0.0f;
-        s_inv[j] = inv_scale_of(c);
+        // stochastic mode carries the scaled value with 24 fraction bits (exact power-of-two factor)
+        s_inv[j] = STOCH ? __fmul_rn(inv_scale_of(c), kTwo24) : inv_scale_of(c);
     }
     __syncthreads();
     float inv[JC];
@@ -67,14 +68,7 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
             if (STOCH) u = (int)rng24(seed_lo, seed_hi_mul, (uint32_t)(4 * i + e));
 #pragma unroll
             for (int j = 0; j < JC; ++j) {
-                const float t = scaled_clipped(x, inv[j]);
-                int r;
-                if (STOCH) {
-                    const int X = (int)floorf(__fmul_rn(t, 16777216.0f));
-                    r = (X + u) >> 24;
-                } else {
-                    r = (int)rintf(t);
-                }
+                const int r = STOCH ? (stochastic_sum(x, inv[j], u) >> 24) : round_nearest_code(x, inv[j]);
                 A[j] = fma(xd, (double)r, A[j]);
                 B[j] += (unsigned)(r * r);
             }
@@ -89,14 +83,7 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
         if (STOCH) u = (int)rng24(seed_lo, seed_hi_mul, (uint32_t)i);
 #pragma unroll
         for (int j = 0; j < JC; ++j) {
-            const float t = scaled_clipped(x, inv[j]);
-            int r;
-            if (STOCH) {
-                const int X = (int)floorf(__fmul_rn(t, 16777216.0f));
-                r = (X + u) >> 24;
-            } else {
-                r = (int)rintf(t);
-            }
+            const int r = STOCH ? (stochastic_sum(x, inv[j], u) >> 24) : round_nearest_code(x, inv[j]);
             A[j] = fma(xd, (double)r, A[j]);
             B[j] += (unsigned)(r * r);
         }
@@ -131,38 +118,61 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
 
 // Sums the per-block partials in a fixed order, evaluates Eq.6 for every candidate and picks the
 // smallest deviation (ties: smallest j, i.e. the largest clip value for decreasing ratios).
-__global__ __launch_bounds__(256) void dsgc_finish_kernel(
+// 1024 threads = 64 candidates x 16 block segments; the order of the additions depends on
+// (nblocks, n_cand) only, so results are reproducible run to run.
+constexpr int DSGC_SEGS = 16;
+
+__global__ __launch_bounds__(1024) void dsgc_finish_kernel(
     const double* __restrict__ partA, const unsigned long long* __restrict__ partB,
     const double* __restrict__ partG, int nblocks, const float* __restrict__ ratios, int n_cand,
     const float* __restrict__ absmax, float* __restrict__ clip_out, double* __restrict__ dev_out,
     double* __restrict__ dev_all_out) {
-    __shared__ double sA[4][DSGC_JPAD];
-    __shared__ unsigned long long sB[4][DSGC_JPAD];
-    __shared__ double sG[4];
+    __shared__ double sA[DSGC_SEGS][DSGC_JPAD];
+    __shared__ unsigned long long sB[DSGC_SEGS][DSGC_JPAD];
+    __shared__ double sG[DSGC_SEGS];
     __shared__ double sD[DSGC_JPAD];
     const int j = threadIdx.x & 63, seg = threadIdx.x >> 6;
-    const int b0 = (int)(((long long)nblocks * seg) / 4), b1 = (int)(((long long)nblocks * (seg + 1)) / 4);
-    double a = 0.0;
-    unsigned long long b = 0;
-    if (j < n_cand)
-        for (int i = b0; i < b1; ++i) {
-            a += partA[(size_t)i * DSGC_JPAD + j];
-            b += partB[(size_t)i * DSGC_JPAD + j];
+    const int b0 = (int)(((long long)nblocks * seg) / DSGC_SEGS);
+    const int b1 = (int)(((long long)nblocks * (seg + 1)) / DSGC_SEGS);
+    // four independent running sums per thread keep several loads in flight
+    double a[4] = {0.0, 0.0, 0.0, 0.0};
+    unsigned long long b[4] = {0, 0, 0, 0};
+    if (j < n_cand) {
+        int i = b0;
+        for (; i + 3 < b1; i += 4) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                a[k] += partA[(size_t)(i + k) * DSGC_JPAD + j];
+                b[k] += partB[(size_t)(i + k) * DSGC_JPAD + j];
+            }
         }
-    sA[seg][j] = a;
-    sB[seg][j] = b;
-    if (j == 0) {
-        double gsum = 0.0;
-        for (int i = b0; i < b1; ++i) gsum += partG[i];
-        sG[seg] = gsum;
+        for (; i < b1; ++i) {
+            a[0] += partA[(size_t)i * DSGC_JPAD + j];
+            b[0] += partB[(size_t)i * DSGC_JPAD + j];
+        }
+    }
+    sA[seg][j] = (a[0] + a[1]) + (a[2] + a[3]);
+    sB[seg][j] = b[0] + b[1] + b[2] + b[3];
+    {
+        // G: each segment's wave sums its blocks, lane-strided, then a shuffle tree
+        double g = 0.0;
+        for (int i = b0 + j; i < b1; i += 64) g += partG[i];
+        g = wave_sum(g);
+        if (j == 0) sG[seg] = g;
     }
     __syncthreads();
     if (threadIdx.x < 64) {
         double d = 0.0;
         if (j < n_cand) {
-            const double At = (sA[0][j] + sA[1][j]) + (sA[2][j] + sA[3][j]);
-            const double Bt = (double)(sB[0][j] + sB[1][j] + sB[2][j] + sB[3][j]);
-            const double Gt = (sG[0] + sG[1]) + (sG[2] + sG[3]);
+            double At = 0.0, Gt = 0.0;
+            unsigned long long Bi = 0;
+#pragma unroll
+            for (int k = 0; k < DSGC_SEGS; ++k) {
+                At += sA[k][j];
+                Bi += sB[k][j];
+                Gt += sG[k];
+            }
+            const double Bt = (double)Bi;
             if (Gt == 0.0) d = 0.0;
             else if (Bt == 0.0) d = 1.0;
             else d = 1.0 - At / (sqrt(Gt) * sqrt(Bt));
@@ -205,7 +215,7 @@ hipError_t launch_dsgc(const float* g, size_t n, const float* ratios, int n_cand
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(dsgc_finish_kernel, dim3(1), dim3(256), 0, st, ws.partA, ws.partB, ws.partG,
+    hipLaunchKernelGGL(dsgc_finish_kernel, dim3(1), dim3(1024), 0, st, ws.partA, ws.partB, ws.partG,
                        blocks, ratios, n_cand, ws.absmax, clip_out, dev_out, dev_all_out);
     return hipGetLastError();
 }
