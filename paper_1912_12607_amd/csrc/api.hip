@@ -74,6 +74,12 @@ size_t dsgc_ws_bytes(size_t n) {
            align256(nb * 64 * sizeof(unsigned long long)) + align256(nb * sizeof(double));
 }
 
+void fill_wgrad_geometry(WgradArgs* a, const int8t_conv_desc* d, const Geo& g) {
+    a->N = d->N; a->C = d->C; a->Cp = pad16(d->C); a->H = d->H; a->W = d->W;
+    a->K = d->K; a->Kp = pad16(d->K); a->P = g.P; a->Q = g.Q; a->R = d->R; a->S = d->S;
+    a->stride_h = d->stride_h; a->stride_w = d->stride_w; a->pad_h = d->pad_h; a->pad_w = d->pad_w;
+}
+
 }  // namespace
 
 extern "C" {
@@ -116,8 +122,10 @@ size_t int8t_workspace_bytes(int8t_op op, const int8t_conv_desc* desc, size_t n,
             if (desc_ok(desc, &g) != INT8T_OK) return 0;
             if (g.depthwise)
                 return align256((size_t)dw_wgrad_chunks(desc->N, desc->C) * desc->C * desc->R * desc->S * 4);
-            const size_t splits = (size_t)wgrad_splits(desc->N, desc->C, desc->K, g.P, g.Q, desc->R, desc->S);
-            return align256(splits * desc->K * desc->R * desc->S * pad16(desc->C) * 4);
+            WgradArgs a{};
+            fill_wgrad_geometry(&a, desc, g);
+            wgrad_plan(&a);
+            return align256((size_t)a.splits * desc->K * desc->R * desc->S * pad16(desc->C) * 4);
         }
     }
     return 0;
@@ -284,12 +292,10 @@ int8t_status int8t_conv_bwd_weight(const int8t_conv_desc* desc, const int8_t* xq
         return launch_dw_wgrad(a, st) == hipSuccess ? INT8T_OK : INT8T_ERR_RUNTIME;
     }
     WgradArgs a{};
+    fill_wgrad_geometry(&a, desc, g);
+    wgrad_plan(&a);
     a.x = xq_dev; a.dy = dyq_dev; a.sa = sx_dev; a.sb = sdy_dev; a.dw = dw_dev; a.acc = acc_dev;
     a.partial = (int32_t*)ws_dev;
-    a.splits = wgrad_splits(desc->N, desc->C, desc->K, g.P, g.Q, desc->R, desc->S);
-    a.N = desc->N; a.C = desc->C; a.Cp = pad16(desc->C); a.H = desc->H; a.W = desc->W;
-    a.K = desc->K; a.Kp = pad16(desc->K); a.P = g.P; a.Q = g.Q; a.R = desc->R; a.S = desc->S;
-    a.stride_h = desc->stride_h; a.stride_w = desc->stride_w; a.pad_h = desc->pad_h; a.pad_w = desc->pad_w;
     return launch_wgrad(a, st) == hipSuccess ? INT8T_OK : INT8T_ERR_RUNTIME;
 }
 

@@ -1,17 +1,21 @@
 // Dense backward-weight convolution on int8 codes (Sec.3.4: g_W = g_z^T a), int8 MFMA with int32
 // accumulation, Eq.2 fused into the final reduction.
 //
-// GEMM view:  D[k][col] = sum_pix  Gz^T[k][pix] * A^T[pix][col],   col = (r,s,c),  pix = (n,p,q)
-// The reduction runs over output pixels, which are the OUTERMOST index of the channels-last code
-// tensors, while the MFMA wants 16 consecutive reduction bytes per lane.  The loader therefore
-// transposes on the fly: a thread fetches 4 pixels x 4 channels (four dwords), swaps them to
-// 4 channels x 4 pixels with byte permutes -- the 4x4 int8 block transpose of the paper's Suppl.
-// "INT8 Convolution" (its Fig. "4x4 8-bit integer block transpose"), here feeding LDS tiles laid
-// out [channel][64 pixels] -- and the MFMA operand reads are then plain 16-byte LDS loads.
+// GEMM view:  D[k][(tap,c)] = sum over (n,p,q) of  Gz[(n,p,q)][k] * A[(n, p*sh+r-ph, q*sw+s-pw)][c]
+// The reduction runs over images and output pixels, but the channels-last code tensors keep the
+// channel innermost, while the MFMA wants 16 consecutive reduction bytes per lane.  Any order of
+// the reduction index is as good as any other, so the 16 bytes of a lane are made 16 different
+// IMAGES at one pixel: the loader fetches, for one pixel and four channels, one dword from each of
+// 16 images, swaps the 4x4 byte blocks with byte permutes -- the "4x4 8-bit integer block
+// transpose" of the paper's Suppl. "INT8 Convolution" -- and stores [pixel][channel][16 images]
+// granules to LDS.  A filter tap is then just a different PIXEL of the staged input window, i.e. a
+// different, always 16-byte aligned LDS row: no im2col buffer, no unaligned operand reads, zero
+// padding is written once by the loader.
 //
-// The pixel reduction is long (N*P*Q) and the output small, so the reduction is split across
-// blocks (grid.z); every split writes an int32 partial tile and a second kernel sums the
-// partials (integer addition: exact in any order), applies Eq.2 and scatters to K,C,R,S.
+// One block owns an output tile of 64 filters x CT channels x TB taps and a share of the
+// reduction (split-K over image groups and output-pixel tiles); it writes an int32 partial tile.
+// A second kernel sums the partials (integer addition: exact in any order, hence deterministic),
+// applies Eq.2 and scatters [k][(tap,c)] to the K,C,R,S result.
 #include "device_common.h"
 #include "kernels.h"
 
@@ -20,17 +24,11 @@ namespace int8t {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr int WG_BN = 128;   // columns (r,s,c) per block
-constexpr int WG_BK = 64;    // pixels per reduction step
+constexpr int W2_BM = 64;              // filters per block
+constexpr int W2_LDS_BUDGET = 64 * 1024;
+constexpr int W2_TARGET_BLOCKS = 512;  // about two blocks per compute unit
 
-// LDS tile [row][64 pixel bytes] with an 80-byte row pitch (20 dwords).  wg_slot() is the index of
-// the 16-byte granule g of `row` in 16-byte units.  Eight consecutive rows at one granule land in
-// eight different 16-byte bank groups (the MFMA operand reads are conflict free); the xor with
-// row bits 3-4 spreads the loader's transposed stores, which walk rows with a stride of four.
-constexpr int WG_PITCH16 = 5;
-__device__ __forceinline__ int wg_slot(int row, int g) { return row * WG_PITCH16 + (g ^ ((row >> 3) & 3)); }
-
-// 4x4 byte transpose: in d[i] = 4 channels of pixel i; out o[c] = channel c of pixels 0..3.
+// 4x4 byte transpose: in d[i] = 4 channels of image i; out o[c] = channel c of images 0..3.
 __device__ __forceinline__ void transpose4x4(const uint32_t d[4], uint32_t o[4]) {
     // v_perm_b32 picks 4 bytes out of the 8 bytes {hi, lo}; selector byte 0-3 = lo, 4-7 = hi
     const uint32_t t0 = __builtin_amdgcn_perm(d[1], d[0], 0x05010400u);  // d0.b0 d1.b0 d0.b1 d1.b1
@@ -43,144 +41,161 @@ __device__ __forceinline__ void transpose4x4(const uint32_t d[4], uint32_t o[4])
     o[3] = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
 }
 
-template <int BM>
+// Position of channel c inside a [channel][16 bytes] LDS row block.  MFMA operand reads walk 32
+// consecutive channels, the loader's stores walk channels with a stride of four; the xor keeps
+// both spread over all bank groups.
+__device__ __forceinline__ int ch_slot(int c) { return c ^ ((c >> 3) & 3); }
+
+// 16 images x 4 channels -> four [channel][16 images] granules.
+__device__ __forceinline__ void transpose_store(const uint32_t d[16], uint4* __restrict__ row, int c4) {
+    uint32_t o[4][4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) transpose4x4(d + 4 * g, o[g]);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) row[ch_slot(c4 + j)] = make_uint4(o[0][j], o[1][j], o[2][j], o[3][j]);
+}
+
+// Extent of the taps [t0, t0+nt) of an R x S filter (taps numbered r*S + s).
+__host__ __device__ inline void tap_extent(int t0, int nt, int S, int* rmin, int* rmax, int* smin, int* smax) {
+    *rmin = t0 / S;
+    *rmax = (t0 + nt - 1) / S;
+    if (*rmin == *rmax) {
+        *smin = t0 % S;
+        *smax = (t0 + nt - 1) % S;
+    } else {
+        *smin = 0;
+        *smax = S - 1;
+    }
+}
+
+template <int TB, int CS>
 __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
-    constexpr int MI = BM / 64;
-    __shared__ __attribute__((aligned(16))) uint32_t sA[BM * WG_PITCH16 * 4];      // [k][64 pixel bytes]
-    __shared__ __attribute__((aligned(16))) uint32_t sB[WG_BN * WG_PITCH16 * 4];   // [col][64 pixel bytes]
+    constexpr int CT = 64 * CS;   // channels per block
+    extern __shared__ __attribute__((aligned(16))) uint4 lds[];
+    uint4* __restrict__ xT = lds;                   // [window pixel][CT channels] granules
+    uint4* __restrict__ dyT = lds + a.xt_slots;     // [tile pixel][64 filters] granules
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave & 1, wn = wave >> 1;
+    const int mt = wave & 1, ch = wave >> 1, half = lane >> 5, l32 = lane & 31;
 
-    const int PQ = a.P * a.Q;
-    const int ncolsp = a.R * a.S * a.Cp;
-    const int rowbase = blockIdx.y * BM;
-    const int colbase = blockIdx.x * WG_BN;
-    const int cpi = (PQ + WG_BK - 1) / WG_BK;          // reduction chunks per image
-    const int total = a.N * cpi;
-    const int t_begin = (int)(((long long)total * blockIdx.z) / gridDim.z);
-    const int t_end = (int)(((long long)total * (blockIdx.z + 1)) / gridDim.z);
-
-    // ---- A loader (g_z): k-quad = tid % 16, pixel-quad = tid / 16, MI row halves --------------
-    const int a_kq = tid & 15, a_pq = tid >> 4;
-    // ---- B loader (a): column-quad = tid % 32, pixel octet = tid / 32 ---------------------------
-    const int b_cq = tid & 31, b_po = tid >> 5;
-    const int bcol = colbase + 4 * b_cq;
-    const bool bcol_ok = bcol < ncolsp;
-    int b_tr, b_ts, b_c;
-    {
-        const int tap = (bcol_ok ? bcol : 0) / a.Cp;
-        b_c = (bcol_ok ? bcol : 0) - tap * a.Cp;
-        b_tr = tap / a.S;
-        b_ts = tap - b_tr * a.S;
+    int ot = blockIdx.x;
+    const int tg = ot % a.tapgroups;
+    ot /= a.tapgroups;
+    const int ct = ot % a.ctiles;
+    const int kt = ot / a.ctiles;
+    const int RS = a.R * a.S;
+    const int t0 = tg * TB;
+    const int nt = (RS - t0 < TB) ? (RS - t0) : TB;
+    int rmin, rmax, smin, smax;
+    tap_extent(t0, nt, a.S, &rmin, &rmax, &smin, &smax);
+    const int WH = (a.BP - 1) * a.stride_h + (rmax - rmin) + 1;
+    const int WW = (a.BQ - 1) * a.stride_w + (smax - smin) + 1;
+    int toff[TB];
+#pragma unroll
+    for (int j = 0; j < TB; ++j) {
+        const int t = t0 + ((j < nt) ? j : 0);
+        toff[j] = ((t / a.S - rmin) * WW + (t % a.S - smin)) * CT;
     }
-    const float invQ = 1.0f / (float)a.Q;
+    const int units = a.BP * a.BQ;
+    const int nsteps = (units + 1) >> 1;
+    const size_t ximg = (size_t)a.H * a.W * a.Cp;     // image strides in bytes
+    const size_t yimg = (size_t)a.P * a.Q * a.Kp;
 
-    uint32_t ra[MI][4], rb[2][4];
-    auto load_step = [&](int t) {
-        const int n = t / cpi;
-        const int rem0 = (t - n * cpi) * WG_BK;
-        // A: dy[(n*PQ + rem)*Kp + k .. k+3]
+    v16i acc[TB][CS];
 #pragma unroll
-        for (int h = 0; h < MI; ++h) {
-            const int k = rowbase + h * 64 + 4 * a_kq;
+    for (int j = 0; j < TB; ++j)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int rem = rem0 + 4 * a_pq + i;
-                ra[h][i] = 0;
-                if (rem < PQ && k < a.Kp)
-                    ra[h][i] = *reinterpret_cast<const uint32_t*>(a.dy + ((size_t)n * PQ + rem) * a.Kp + k);
-            }
-        }
-        // B: x[((n*H + ih)*W + iw)*Cp + c .. c+3] at this thread's filter tap, 8 consecutive pixels
-        {
-            const int rem_first = rem0 + 8 * b_po;
-            // (p,q) of the first pixel: float estimate, then exact correction
-            int p = (int)((float)rem_first * invQ);
-            int q = rem_first - p * a.Q;
-            if (q < 0) { --p; q += a.Q; }
-            if (q >= a.Q) { ++p; q -= a.Q; }
+        for (int i = 0; i < CS; ++i)
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int ih = p * a.stride_h - a.pad_h + b_tr;
-                const int iw = q * a.stride_w - a.pad_w + b_ts;
-                rb[i >> 2][i & 3] = 0;
-                if (bcol_ok && (rem_first + i) < PQ && (unsigned)ih < (unsigned)a.H &&
-                    (unsigned)iw < (unsigned)a.W)
-                    rb[i >> 2][i & 3] = *reinterpret_cast<const uint32_t*>(
-                        a.x + (((size_t)n * a.H + ih) * a.W + iw) * a.Cp + b_c);
-                if (++q == a.Q) { q = 0; ++p; }
-            }
-        }
-    };
+            for (int v = 0; v < 16; ++v) acc[j][i][v] = 0;
 
-    v16i acc[MI][2];
-#pragma unroll
-    for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+    const int c_begin = (int)(((long long)a.chunks * blockIdx.y) / gridDim.y);
+    const int c_end = (int)(((long long)a.chunks * (blockIdx.y + 1)) / gridDim.y);
+    const int tiles_per_group = a.ntp * a.ntq;
+    for (int chunk = c_begin; chunk < c_end; ++chunk) {
+        const int ng = chunk / tiles_per_group;
+        const int trem = chunk - ng * tiles_per_group;
+        const int tp = trem / a.ntq, tq = trem - tp * a.ntq;
+        const int p0 = tp * a.BP, q0 = tq * a.BQ;
+        const int ih0 = p0 * a.stride_h - a.pad_h + rmin, iw0 = q0 * a.stride_w - a.pad_w + smin;
+        const int n0 = ng * 16;
+        const int nimg = (a.N - n0 < 16) ? (a.N - n0) : 16;
 
-    if (t_begin < t_end) load_step(t_begin);
-    for (int t = t_begin; t < t_end; ++t) {
-        __syncthreads();
-        // transpose in registers, then [channel][pixel] dwords into LDS
+        __syncthreads();   // the previous chunk's MFMA reads are done
+        // ---- stage the input window: 16 images x 4 channels per task ---------------------------
+        const int ntask_x = WH * WW * (CT / 4);
+        for (int task = tid; task < ntask_x; task += 256) {
+            const int cq = task % (CT / 4), wp = task / (CT / 4);
+            const int wy = wp / WW, wx = wp - wy * WW;
+            const int ih = ih0 + wy, iw = iw0 + wx, c = ct * CT + 4 * cq;
+            const bool ok = (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W && c < a.Cp;
+            const int8_t* src = a.x + ((size_t)n0 * a.H * a.W + (size_t)(ok ? ih : 0) * a.W + (ok ? iw : 0)) * a.Cp +
+                                (ok ? c : 0);
+            uint32_t d[16];
 #pragma unroll
-        for (int h = 0; h < MI; ++h) {
-            uint32_t o[4];
-            transpose4x4(ra[h], o);
-#pragma unroll
-            for (int c = 0; c < 4; ++c)
-                sA[wg_slot(h * 64 + 4 * a_kq + c, a_pq >> 2) * 4 + (a_pq & 3)] = o[c];
+            for (int i = 0; i < 16; ++i)
+                d[i] = (ok && i < nimg) ? *reinterpret_cast<const uint32_t*>(src + (size_t)i * ximg) : 0u;
+            transpose_store(d, xT + (size_t)wp * CT, 4 * cq);
         }
-        {
-            uint32_t o0[4], o1[4];
-            transpose4x4(rb[0], o0);
-            transpose4x4(rb[1], o1);
-            // pixel octet b_po = dwords 2*b_po, 2*b_po+1 of the row: granule b_po/2, 8-byte half b_po%2
+        // ---- stage the gradient tile ---------------------------------------------------------
+        const int ntask_y = units * 16;
+        for (int task = tid; task < ntask_y; task += 256) {
+            const int kq = task & 15, u = task >> 4;
+            const int pl = u / a.BQ, ql = u - pl * a.BQ;
+            const int p = p0 + pl, q = q0 + ql, k = kt * W2_BM + 4 * kq;
+            const bool ok = p < a.P && q < a.Q && k < a.Kp;
+            const int8_t* src = a.dy + ((size_t)n0 * a.P * a.Q + (size_t)(ok ? p : 0) * a.Q + (ok ? q : 0)) * a.Kp +
+                                (ok ? k : 0);
+            uint32_t d[16];
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                uint2 v;
-                v.x = o0[c];
-                v.y = o1[c];
-                *reinterpret_cast<uint2*>(&sB[wg_slot(4 * b_cq + c, b_po >> 1) * 4 + (b_po & 1) * 2]) = v;
-            }
+            for (int i = 0; i < 16; ++i)
+                d[i] = (ok && i < nimg) ? *reinterpret_cast<const uint32_t*>(src + (size_t)i * yimg) : 0u;
+            transpose_store(d, dyT + (size_t)u * W2_BM, 4 * kq);
         }
         __syncthreads();
-        if (t + 1 < t_end) load_step(t + 1);
+
+        // ---- MFMA: one step = two tile pixels (one per half-wave) x 16 images ------------------
+        for (int step = 0; step < nsteps; ++step) {
+            const int u = 2 * step + half;
+            const bool uv = u < units;
+            const int uu = uv ? u : 0;
+            const int pl = uu / a.BQ, ql = uu - pl * a.BQ;
+            const uint4 ta = dyT[uu * W2_BM + ch_slot(mt * 32 + l32)];
+            v4i fa = v4i{(int)ta.x, (int)ta.y, (int)ta.z, (int)ta.w};
+            if (!uv) fa = v4i{0, 0, 0, 0};
+            const uint4* __restrict__ xrow = xT + (pl * a.stride_h * WW + ql * a.stride_w) * CT;
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            const int g = kk * 2 + (lane >> 5);
-            v4i fa[MI], fb[2];
+            for (int j = 0; j < TB; ++j) {
+                if (j < nt) {
 #pragma unroll
-            for (int i = 0; i < MI; ++i)
-                fa[i] = *reinterpret_cast<const v4i*>(&sA[wg_slot(wm * (BM / 2) + i * 32 + (lane & 31), g) * 4]);
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-                fb[j] = *reinterpret_cast<const v4i*>(&sB[wg_slot(wn * 64 + j * 32 + (lane & 31), g) * 4]);
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                    for (int i = 0; i < CS; ++i) {
+                        const uint4 tb = xrow[toff[j] + ch_slot((ch * CS + i) * 32 + l32)];
+                        const v4i fb = v4i{(int)tb.x, (int)tb.y, (int)tb.z, (int)tb.w};
+                        acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa, fb, acc[j][i], 0, 0, 0);
+                    }
+                }
+            }
         }
     }
 
-    // partial[z][k][col], col fastest: 32 consecutive columns per store instruction
-    int32_t* __restrict__ part = a.partial + (size_t)blockIdx.z * a.K * ncolsp;
+    // partial[z][k][(tap,c)], channel fastest: 32 consecutive columns per store instruction
+    const int ncolsp = RS * a.Cp;
+    int32_t* __restrict__ part = a.partial + (size_t)blockIdx.y * a.K * ncolsp;
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int col = colbase + wn * 64 + j * 32 + (lane & 31);
-        if (col >= ncolsp) continue;
+    for (int j = 0; j < TB; ++j) {
+        if (j >= nt) continue;
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
+        for (int i = 0; i < CS; ++i) {
+            const int c = ct * CT + (ch * CS + i) * 32 + l32;
+            if (c >= a.Cp) continue;
+            const int col = (t0 + j) * a.Cp + c;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int k = rowbase + wm * (BM / 2) + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                if (k < a.K) part[(size_t)k * ncolsp + col] = acc[i][j][v];
+                const int k = kt * W2_BM + mt * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+                if (k < a.K) part[(size_t)k * ncolsp + col] = acc[j][i][v];
             }
+        }
     }
 }
 
@@ -207,29 +222,72 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const WgradArgs a) {
     if (a.acc) a.acc[o] = sum;
 }
 
-int wgrad_splits(int N, int C, int K, int P, int Q, int R, int S) {
-    const int Cp = (C + 15) & ~15;
-    const int BM = (K <= 64) ? 64 : 128;
-    const int tiles = ((K + BM - 1) / BM) * ((R * S * Cp + WG_BN - 1) / WG_BN);
-    const int chunks = N * ((P * Q + WG_BK - 1) / WG_BK);
-    int splits = (512 + tiles - 1) / tiles;          // about two blocks per compute unit
-    if (splits > chunks / 4) splits = chunks / 4;     // at least four reduction steps per block
+// ---------------------------------------------------------------------------------------------
+// Host-side plan: tile shapes, tap grouping, split count.  Shared by the workspace query and the
+// launch so that both see the same numbers.
+// ---------------------------------------------------------------------------------------------
+void wgrad_plan(WgradArgs* a) {
+    const int RS = a->R * a->S;
+    // taps per block / channel slabs per wave: one filter row of a 3-wide filter, a whole 1x7 or
+    // 7x1 filter, a wide channel tile for 1x1, one tap at a time otherwise
+    if (RS == 1) { a->TB = 1; a->CS = (a->Cp >= 256) ? 4 : 1; }
+    else if (a->S == 3) { a->TB = 3; a->CS = 1; }
+    else if (RS == 7) { a->TB = 7; a->CS = 1; }
+    else { a->TB = 1; a->CS = 1; }
+    const int CT = 64 * a->CS;
+    a->tapgroups = (RS + a->TB - 1) / a->TB;
+    a->ktiles = (a->K + W2_BM - 1) / W2_BM;
+    a->ctiles = (a->Cp + CT - 1) / CT;
+    // output-pixel tile: about 16 pixels, split evenly, shrunk until the staged window fits
+    int nq = (a->Q + 7) / 8;
+    int BQ = (a->Q + nq - 1) / nq;
+    int BP = 16 / BQ;
+    if (BP < 1) BP = 1;
+    if (BP > a->P) BP = a->P;
+    for (;;) {
+        int maxwin = 0;
+        for (int g = 0; g < a->tapgroups; ++g) {
+            const int t0 = g * a->TB, nt = (RS - t0 < a->TB) ? (RS - t0) : a->TB;
+            int rmin, rmax, smin, smax;
+            tap_extent(t0, nt, a->S, &rmin, &rmax, &smin, &smax);
+            const int WH = (BP - 1) * a->stride_h + (rmax - rmin) + 1;
+            const int WW = (BQ - 1) * a->stride_w + (smax - smin) + 1;
+            if (WH * WW > maxwin) maxwin = WH * WW;
+        }
+        a->xt_slots = maxwin * CT;
+        a->lds_bytes = (size_t)(a->xt_slots + BP * BQ * W2_BM) * 16;
+        if (a->lds_bytes <= (size_t)W2_LDS_BUDGET || (BP == 1 && BQ == 1)) break;
+        if (BP > 1) BP = (BP + 1) / 2;
+        else BQ = (BQ + 1) / 2;
+    }
+    const int np = (a->P + BP - 1) / BP;
+    nq = (a->Q + BQ - 1) / BQ;
+    a->BP = BP;
+    a->BQ = BQ;
+    a->ntp = np;
+    a->ntq = nq;
+    a->ngrp = (a->N + 15) / 16;
+    a->chunks = a->ngrp * np * nq;
+    const int out_tiles = a->ktiles * a->ctiles * a->tapgroups;
+    int splits = (W2_TARGET_BLOCKS + out_tiles - 1) / out_tiles;
+    if (splits > a->chunks) splits = a->chunks;
     if (splits < 1) splits = 1;
-    return splits;
+    a->splits = splits;
 }
 
 hipError_t launch_wgrad(const WgradArgs& a, hipStream_t st) {
-    const int ncolsp = a.R * a.S * a.Cp;
-    if (a.K <= 64) {
-        dim3 grid((ncolsp + WG_BN - 1) / WG_BN, 1, a.splits);
-        hipLaunchKernelGGL((wgrad_kernel<64>), grid, dim3(256), 0, st, a);
-    } else {
-        dim3 grid((ncolsp + WG_BN - 1) / WG_BN, (a.K + 127) / 128, a.splits);
-        hipLaunchKernelGGL((wgrad_kernel<128>), grid, dim3(256), 0, st, a);
-    }
+    dim3 grid(a.ktiles * a.ctiles * a.tapgroups, a.splits);
+#define LAUNCH(TBv, CSv) \
+    hipLaunchKernelGGL((wgrad_kernel<TBv, CSv>), grid, dim3(256), a.lds_bytes, st, a)
+    if (a.TB == 1 && a.CS == 1) LAUNCH(1, 1);
+    else if (a.TB == 1 && a.CS == 4) LAUNCH(1, 4);
+    else if (a.TB == 3) LAUNCH(3, 1);
+    else if (a.TB == 7) LAUNCH(7, 1);
+    else return hipErrorInvalidValue;
+#undef LAUNCH
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const size_t total = (size_t)a.K * ncolsp;
+    const size_t total = (size_t)a.K * a.R * a.S * a.Cp;
     hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a);
     return hipGetLastError();
 }

@@ -77,11 +77,17 @@ struct WgradArgs {
     float* dw;                   // [K][C][R][S]
     int32_t* acc;                // nullable
     int32_t* partial;            // scratch [splits][K][R*S*Cp]
-    int splits;
     int N, C, Cp, H, W, K, Kp, P, Q, R, S;
     int stride_h, stride_w, pad_h, pad_w;
+    // filled by wgrad_plan():
+    int TB, CS;                  // taps per block, 32-channel slabs per wave
+    int BP, BQ, ntp, ntq;        // output-pixel tile and tiles per image
+    int ngrp, chunks, splits;    // groups of 16 images, reduction chunks, split-K factor
+    int ktiles, ctiles, tapgroups;
+    int xt_slots;                // 16-byte granules of the staged input window
+    size_t lds_bytes;
 };
-int wgrad_splits(int N, int C, int K, int P, int Q, int R, int S);
+void wgrad_plan(WgradArgs* a);   // needs the geometry fields above the comment
 hipError_t launch_wgrad(const WgradArgs& a, hipStream_t st);
 
 // ---- conv_dw.hip (depthwise, planar codes) ----------------------------------------------------
