@@ -27,6 +27,7 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 constexpr int W2_BM = 64;              // filters per block
 constexpr int W2_LDS_BUDGET = 64 * 1024;
 constexpr int W2_TARGET_BLOCKS = 512;  // about two blocks per compute unit
+constexpr int W2_TPT = 3;              // loader tasks per thread and reduction chunk (prefetched in registers)
 
 // 4x4 byte transpose: in d[i] = 4 channels of image i; out o[c] = channel c of images 0..3.
 __device__ __forceinline__ void transpose4x4(const uint32_t d[4], uint32_t o[4]) {
@@ -68,12 +69,14 @@ __host__ __device__ inline void tap_extent(int t0, int nt, int S, int* rmin, int
     }
 }
 
+constexpr int W2_MAXSTEPS = 8;         // MFMA steps per chunk: at most 16 tile pixels
+
 template <int TB, int CS>
 __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
     constexpr int CT = 64 * CS;   // channels per block
     extern __shared__ __attribute__((aligned(16))) uint4 lds[];
     uint4* __restrict__ xT = lds;                   // [window pixel][CT channels] granules
-    uint4* __restrict__ dyT = lds + a.xt_slots;     // [tile pixel][64 filters] granules
+    uint4* __restrict__ dyT = lds + a.xt_slots;     // [tile pixel][64 filters] granules, then one zero granule
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -91,16 +94,29 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
     tap_extent(t0, nt, a.S, &rmin, &rmax, &smin, &smax);
     const int WH = (a.BP - 1) * a.stride_h + (rmax - rmin) + 1;
     const int WW = (a.BQ - 1) * a.stride_w + (smax - smin) + 1;
-    int toff[TB];
+    int toff[TB];   // uniform: LDS offset of each tap inside the staged window
 #pragma unroll
     for (int j = 0; j < TB; ++j) {
         const int t = t0 + ((j < nt) ? j : 0);
-        toff[j] = ((t / a.S - rmin) * WW + (t % a.S - smin)) * CT;
+        toff[j] = __builtin_amdgcn_readfirstlane(((t / a.S - rmin) * WW + (t % a.S - smin)) * CT);
     }
     const int units = a.BP * a.BQ;
     const int nsteps = (units + 1) >> 1;
-    const size_t ximg = (size_t)a.H * a.W * a.Cp;     // image strides in bytes
-    const size_t yimg = (size_t)a.P * a.Q * a.Kp;
+    const int zero_slot = units * W2_BM;            // in dyT
+    if (tid == 0) dyT[zero_slot] = make_uint4(0, 0, 0, 0);
+
+    // LDS operand positions of every MFMA step; they depend on the tile geometry only.  A step
+    // feeds two tile pixels, one per half-wave, each with 16 images.
+    int a_off[W2_MAXSTEPS], x_off[W2_MAXSTEPS];
+#pragma unroll
+    for (int s = 0; s < W2_MAXSTEPS; ++s) {
+        const int u = 2 * s + half;
+        const bool uv = u < units;
+        const int uu = uv ? u : 0;
+        const int pl = uu / a.BQ, ql = uu - pl * a.BQ;
+        a_off[s] = uv ? (uu * W2_BM + ch_slot(mt * 32 + l32)) : zero_slot;
+        x_off[s] = (pl * a.stride_h * WW + ql * a.stride_w) * CT + ch * CS * 32 + ch_slot(l32);
+    }
 
     v16i acc[TB][CS];
 #pragma unroll
@@ -113,7 +129,43 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
     const int c_begin = (int)(((long long)a.chunks * blockIdx.y) / gridDim.y);
     const int c_end = (int)(((long long)a.chunks * (blockIdx.y + 1)) / gridDim.y);
     const int tiles_per_group = a.ntp * a.ntq;
-    for (int chunk = c_begin; chunk < c_end; ++chunk) {
+    const int ntask_x = WH * WW * (CT / 4);     // input window: (window pixel, channel quad)
+    const int ntask = ntask_x + units * 16;     // + gradient tile: (tile pixel, filter quad)
+    const uint32_t ximg = (uint32_t)a.H * a.W * a.Cp;     // image strides in bytes
+    const uint32_t yimg = (uint32_t)a.P * a.Q * a.Kp;
+
+    // Loader tasks of this thread (task = tid + 256*i): everything that does not depend on the
+    // chunk is worked out once.  A task fetches one dword from each of 16 images.
+    int t_kind[W2_TPT], t_c[W2_TPT], t_a[W2_TPT], t_b[W2_TPT], t_dst[W2_TPT];   // kind: 0 input, 1 gradient, 2 none
+#pragma unroll
+    for (int i = 0; i < W2_TPT; ++i) {
+        const int task = tid + 256 * i;
+        t_kind[i] = 2;
+        t_a[i] = t_b[i] = t_c[i] = t_dst[i] = 0;
+        if (task < ntask_x) {
+            const int cq = task % (CT / 4), wp = task / (CT / 4);
+            t_kind[i] = 0;
+            t_a[i] = wp / WW;                 // window row
+            t_b[i] = wp - t_a[i] * WW;        // window column
+            t_c[i] = ct * CT + 4 * cq;        // >= Cp: nothing to fetch, zeros are staged
+            t_dst[i] = wp * CT + 4 * cq;      // granule index in xT (before the channel swizzle)
+        } else if (task < ntask) {
+            const int kq = (task - ntask_x) & 15, u = (task - ntask_x) >> 4;
+            t_kind[i] = 1;
+            t_a[i] = u / a.BQ;                // tile row
+            t_b[i] = u - t_a[i] * a.BQ;       // tile column
+            t_c[i] = kt * W2_BM + 4 * kq;
+            t_dst[i] = u * W2_BM + 4 * kq;
+        }
+    }
+
+    // Prefetch registers.  Loads are unconditional: a task with nothing to fetch (padding, ragged
+    // tile edge, channel beyond the tensor) reads offset 0 of its tensor and is zeroed when it is
+    // staged; images beyond N re-read the group's last image and are zeroed the same way.
+    uint32_t pre[W2_TPT][16];
+    bool pre_ok[W2_TPT];
+    int pre_nimg = 16;
+    auto issue = [&](int chunk) {
         const int ng = chunk / tiles_per_group;
         const int trem = chunk - ng * tiles_per_group;
         const int tp = trem / a.ntq, tq = trem - tp * a.ntq;
@@ -121,58 +173,61 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
         const int ih0 = p0 * a.stride_h - a.pad_h + rmin, iw0 = q0 * a.stride_w - a.pad_w + smin;
         const int n0 = ng * 16;
         const int nimg = (a.N - n0 < 16) ? (a.N - n0) : 16;
-
-        __syncthreads();   // the previous chunk's MFMA reads are done
-        // ---- stage the input window: 16 images x 4 channels per task ---------------------------
-        const int ntask_x = WH * WW * (CT / 4);
-        for (int task = tid; task < ntask_x; task += 256) {
-            const int cq = task % (CT / 4), wp = task / (CT / 4);
-            const int wy = wp / WW, wx = wp - wy * WW;
-            const int ih = ih0 + wy, iw = iw0 + wx, c = ct * CT + 4 * cq;
-            const bool ok = (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W && c < a.Cp;
-            const int8_t* src = a.x + ((size_t)n0 * a.H * a.W + (size_t)(ok ? ih : 0) * a.W + (ok ? iw : 0)) * a.Cp +
-                                (ok ? c : 0);
-            uint32_t d[16];
+        pre_nimg = nimg;
 #pragma unroll
-            for (int i = 0; i < 16; ++i)
-                d[i] = (ok && i < nimg) ? *reinterpret_cast<const uint32_t*>(src + (size_t)i * ximg) : 0u;
-            transpose_store(d, xT + (size_t)wp * CT, 4 * cq);
+        for (int i = 0; i < W2_TPT; ++i) {
+            if (t_kind[i] == 2) continue;
+            const bool isx = t_kind[i] == 0;
+            const int yy = (isx ? ih0 : p0) + t_a[i], xx = (isx ? iw0 : q0) + t_b[i];
+            const int hh = isx ? a.H : a.P, ww = isx ? a.W : a.Q, cc = isx ? a.Cp : a.Kp;
+            const bool ok = (unsigned)yy < (unsigned)hh && (unsigned)xx < (unsigned)ww && t_c[i] < cc;
+            pre_ok[i] = ok;
+            const uint32_t stride = isx ? ximg : yimg;
+            const int8_t* base = isx ? a.x : a.dy;
+            uint32_t off = ok ? (((uint32_t)n0 * hh + yy) * ww + xx) * cc + t_c[i] : (uint32_t)n0 * stride;
+#pragma unroll
+            for (int im = 0; im < 16; ++im) {
+                pre[i][im] = *reinterpret_cast<const uint32_t*>(base + off);
+                if (im + 1 < nimg) off += stride;
+            }
         }
-        // ---- stage the gradient tile ---------------------------------------------------------
-        const int ntask_y = units * 16;
-        for (int task = tid; task < ntask_y; task += 256) {
-            const int kq = task & 15, u = task >> 4;
-            const int pl = u / a.BQ, ql = u - pl * a.BQ;
-            const int p = p0 + pl, q = q0 + ql, k = kt * W2_BM + 4 * kq;
-            const bool ok = p < a.P && q < a.Q && k < a.Kp;
-            const int8_t* src = a.dy + ((size_t)n0 * a.P * a.Q + (size_t)(ok ? p : 0) * a.Q + (ok ? q : 0)) * a.Kp +
-                                (ok ? k : 0);
-            uint32_t d[16];
+    };
+
+    if (c_begin < c_end) issue(c_begin);
+    for (int chunk = c_begin; chunk < c_end; ++chunk) {
+        __syncthreads();   // the previous chunk's MFMA reads are done
 #pragma unroll
-            for (int i = 0; i < 16; ++i)
-                d[i] = (ok && i < nimg) ? *reinterpret_cast<const uint32_t*>(src + (size_t)i * yimg) : 0u;
-            transpose_store(d, dyT + (size_t)u * W2_BM, 4 * kq);
+        for (int i = 0; i < W2_TPT; ++i) {
+            if (t_kind[i] == 2) continue;
+            if (!pre_ok[i]) {
+#pragma unroll
+                for (int im = 0; im < 16; ++im) pre[i][im] = 0u;
+            } else if (pre_nimg < 16) {
+#pragma unroll
+                for (int im = 0; im < 16; ++im)
+                    if (im >= pre_nimg) pre[i][im] = 0u;
+            }
+            // t_dst = 64-granule row block + channel offset; the swizzle acts on the low bits only
+            uint4* __restrict__ row = ((t_kind[i] == 1) ? dyT : xT) + (t_dst[i] & ~63);
+            transpose_store(pre[i], row, t_dst[i] & 63);
         }
         __syncthreads();
+        if (chunk + 1 < c_end) issue(chunk + 1);   // in flight while this chunk's MFMAs run
 
-        // ---- MFMA: one step = two tile pixels (one per half-wave) x 16 images ------------------
-        for (int step = 0; step < nsteps; ++step) {
-            const int u = 2 * step + half;
-            const bool uv = u < units;
-            const int uu = uv ? u : 0;
-            const int pl = uu / a.BQ, ql = uu - pl * a.BQ;
-            const uint4 ta = dyT[uu * W2_BM + ch_slot(mt * 32 + l32)];
-            v4i fa = v4i{(int)ta.x, (int)ta.y, (int)ta.z, (int)ta.w};
-            if (!uv) fa = v4i{0, 0, 0, 0};
-            const uint4* __restrict__ xrow = xT + (pl * a.stride_h * WW + ql * a.stride_w) * CT;
 #pragma unroll
-            for (int j = 0; j < TB; ++j) {
-                if (j < nt) {
+        for (int s = 0; s < W2_MAXSTEPS; ++s) {
+            if (s < nsteps) {
+                const uint4 ta = dyT[a_off[s]];
+                const v4i fa = v4i{(int)ta.x, (int)ta.y, (int)ta.z, (int)ta.w};
 #pragma unroll
-                    for (int i = 0; i < CS; ++i) {
-                        const uint4 tb = xrow[toff[j] + ch_slot((ch * CS + i) * 32 + l32)];
-                        const v4i fb = v4i{(int)tb.x, (int)tb.y, (int)tb.z, (int)tb.w};
-                        acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa, fb, acc[j][i], 0, 0, 0);
+                for (int j = 0; j < TB; ++j) {
+                    if (j < nt) {
+#pragma unroll
+                        for (int i = 0; i < CS; ++i) {
+                            const uint4 tb = xT[x_off[s] + toff[j] + i * 32];
+                            const v4i fb = v4i{(int)tb.x, (int)tb.y, (int)tb.z, (int)tb.w};
+                            acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa, fb, acc[j][i], 0, 0, 0);
+                        }
                     }
                 }
             }
@@ -255,8 +310,11 @@ void wgrad_plan(WgradArgs* a) {
             if (WH * WW > maxwin) maxwin = WH * WW;
         }
         a->xt_slots = maxwin * CT;
-        a->lds_bytes = (size_t)(a->xt_slots + BP * BQ * W2_BM) * 16;
-        if (a->lds_bytes <= (size_t)W2_LDS_BUDGET || (BP == 1 && BQ == 1)) break;
+        a->lds_bytes = (size_t)(a->xt_slots + BP * BQ * W2_BM + 1) * 16;
+        const int ntask = maxwin * (CT / 4) + BP * BQ * 16;
+        if ((a->lds_bytes <= (size_t)W2_LDS_BUDGET && ntask <= 256 * W2_TPT && BP * BQ <= 2 * W2_MAXSTEPS) ||
+            (BP == 1 && BQ == 1))
+            break;
         if (BP > 1) BP = (BP + 1) / 2;
         else BQ = (BQ + 1) / 2;
     }

@@ -134,23 +134,29 @@ __global__ __launch_bounds__(1024) void dsgc_finish_kernel(
     const int j = threadIdx.x & 63, seg = threadIdx.x >> 6;
     const int b0 = (int)(((long long)nblocks * seg) / DSGC_SEGS);
     const int b1 = (int)(((long long)nblocks * (seg + 1)) / DSGC_SEGS);
-    // four independent running sums per thread keep several loads in flight
-    double a[4] = {0.0, 0.0, 0.0, 0.0};
-    unsigned long long b[4] = {0, 0, 0, 0};
-    if (j < n_cand) {
-        int i = b0;
-        for (; i + 3 < b1; i += 4) {
+    // eight independent running sums per thread keep sixteen loads in flight
+    double a[8];
+    unsigned long long b[8];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                a[k] += partA[(size_t)(i + k) * DSGC_JPAD + j];
-                b[k] += partB[(size_t)(i + k) * DSGC_JPAD + j];
+    for (int k = 0; k < 8; ++k) {
+        a[k] = 0.0;
+        b[k] = 0;
+    }
+    if (j < n_cand) {
+        for (int i = b0; i < b1; i += 8) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const bool in = i + k < b1;
+                const size_t idx = (size_t)(in ? i + k : b0) * DSGC_JPAD + j;
+                const double av = partA[idx];
+                const unsigned long long bv = partB[idx];
+                a[k] += in ? av : 0.0;
+                b[k] += in ? bv : 0ull;
             }
         }
-        for (; i < b1; ++i) {
-            a[0] += partA[(size_t)i * DSGC_JPAD + j];
-            b[0] += partB[(size_t)i * DSGC_JPAD + j];
-        }
     }
+    a[0] = (a[0] + a[4]); a[1] = (a[1] + a[5]); a[2] = (a[2] + a[6]); a[3] = (a[3] + a[7]);
+    b[0] += b[4]; b[1] += b[5]; b[2] += b[6]; b[3] += b[7];
     sA[seg][j] = (a[0] + a[1]) + (a[2] + a[3]);
     sB[seg][j] = b[0] + b[1] + b[2] + b[3];
     {
