@@ -41,9 +41,10 @@ def algorithmic(L, n_cand):
     return {
         "quantize_x": dict(bytes=4 * n_x + 4 * n_x + n_x, ops=0),          # absmax read + read + code write
         "quantize_w": dict(bytes=9 * n_w, ops=0),
-        # absmax pass (4 B/elem) + one sweep (4 B/elem); 10 vector-ALU operations per element and
-        # candidate (scale, clip, 2^24 scale, floor+convert, add draw, shift, q*q, int->fp64, fp64 fma, int add)
-        "dsgc": dict(bytes=8 * n_y, ops=10 * n_cand * n_y),
+        # absmax pass (4 B/elem) + one sweep (4 B/elem).  Vector-ALU work of the sweep: 8 operations per
+        # element and candidate (scale, clamp, floor-convert, add draw, 0.75 byte gather, 1.75 int8
+        # dot-product accumulates) + 25 per element and 16-candidate chunk (draw, fixed point, digits)
+        "dsgc": dict(bytes=8 * n_y, ops=(8 * n_cand + 25 * ((n_cand + 15) // 16)) * n_y),
         "quantize_dy": dict(bytes=5 * n_y, ops=0),
         "fwd": dict(bytes=n_x + n_w + 4 * n_y, ops=2 * macs),
         "bwd_data": dict(bytes=n_y + n_w + 4 * n_x, ops=2 * macs),
@@ -152,9 +153,12 @@ def main():
         roof = dict(bound="hbm", achieved=a["bytes"] / t_dom / 1e9, peak=HBM_PEAK_GBS, unit="GB/s")
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = None
-    roof["kernel"] = "int8t_" + {"dsgc": "dsgc_clip", "quantize_x": "quantize", "quantize_w": "quantize",
-                                 "quantize_dy": "quantize", "fwd": "conv_fwd", "bwd_data": "conv_bwd_data",
-                                 "bwd_weight": "conv_bwd_weight"}[dom] + f" ({dom})"
+    roof["kernel"] = {"dsgc": "int8t_dsgc_clip = absmax_kernel + dsgc_sweep_kernel + dsgc_finish_kernel",
+                      "quantize_x": "int8t_quantize(a) = absmax_kernel + quantize_act_kernel",
+                      "quantize_w": "int8t_quantize(W) = absmax_kernel + quantize_wgt_kernel",
+                      "quantize_dy": "int8t_quantize(g_z) = quantize_act_kernel + deviation_finish_kernel",
+                      "fwd": "int8t_conv_fwd = igemm_kernel", "bwd_data": "int8t_conv_bwd_data = igemm_kernel",
+                      "bwd_weight": "int8t_conv_bwd_weight = wgrad_kernel + wgrad_reduce_kernel"}[dom]
     roof["us_per_launch"] = per_call[dom]
 
     out = {

@@ -1,37 +1,78 @@
 // Direction Sensitive Gradient Clipping (Sec.3.4 of the paper) as a candidate search.
 //
-// One sweep over the gradient evaluates every candidate clip value at once: each thread keeps,
-// per candidate j, A_j = sum g*q_j (fp64) and B_j = sum q_j^2 (integer) in registers, and G =
-// sum g^2 once.  The deviation of Eq.6 is then d_j = 1 - A_j / sqrt(G * B_j): the scale s_j
-// cancels between the numerator and |ghat|, so no dequantized tensor is ever formed.  The
-// uniform draw of the stochastic rounding (Eq.3) is taken once per element and shared by all
-// candidates -- the same draw the later quantize call uses, so the search scores exactly the
-// codes that will be produced.
+// One sweep over the gradient evaluates the candidate clip values side by side.  Per candidate j
+// it needs A_j = sum g*q_j and B_j = sum q_j^2 (and G = sum g^2 once); the deviation of Eq.6 is
+// then d_j = 1 - A_j / sqrt(G * B_j): the scale s_j cancels between the numerator and |ghat|, so no
+// dequantized tensor is ever formed.  The uniform draw of the stochastic rounding (Eq.3) is taken
+// once per element and shared by all candidates -- the same draw the later quantize call uses,
+// so the search scores exactly the codes that will be produced.
 //
-// The sweep reads 4 bytes per element and spends ~10 vector-ALU operations per element and
-// candidate: it is bound by the plain vector ALUs, not by HBM.
+// The sweep is bound by the plain vector ALUs, not by HBM (4 bytes per element against several
+// operations per element AND candidate), so the arithmetic is arranged to need few instructions:
+//   * the code of (element, candidate) is the signed top byte of floor(T) + u, T the scaled value
+//     with 24 fraction bits; four elements' codes are gathered into one dword by byte permutes;
+//   * g is turned, once per element, into a 46-bit fixed-point integer relative to max|g|
+//     (H * 2^23 + L, |H|,|L| <= 2^22), and both halves into three balanced signed byte digits;
+//   * A_j and B_j are then sums of int8 x int8 products, accumulated four at a time by the 4-way
+//     int8 dot-product instruction into int32 registers: 6 digit sums + 1 square sum per candidate.
+// The integer sums are exact and order independent; the only error against an fp64 evaluation is
+// the fixed-point rounding of g, |delta| <= max|g| * 2^-45 per element, i.e. at most
+// 2^-45 * sqrt(n) in d_j (Cauchy-Schwarz), far below the resolution the search needs.
 #include "device_common.h"
 #include "kernels.h"
 
 namespace int8t {
 
-constexpr int DSGC_JC = 32;       // candidates per sweep (register accumulators)
+constexpr int DSGC_JC = 16;       // candidates per block (7 int32 accumulators each)
 constexpr int DSGC_JPAD = 64;     // row pitch of the partial arrays (= INT8T_MAX_CANDIDATES)
 constexpr int DSGC_MAX_BLOCKS = 512;
 
-template <int JC, bool STOCH>
+// bytes [a.b3, b.b3, c.b3, d.b3]: the signed top bytes of four 32-bit sums
+__device__ __forceinline__ uint32_t top_bytes(int a, int b, int c, int d) {
+    const uint32_t lo = __builtin_amdgcn_perm((uint32_t)b, (uint32_t)a, 0x0c0c0703u);   // a.b3 b.b3 0 0
+    const uint32_t hi = __builtin_amdgcn_perm((uint32_t)d, (uint32_t)c, 0x07030c0cu);   // 0 0 c.b3 d.b3
+    return lo | hi;
+}
+// bytes [a.b0, b.b0, c.b0, d.b0]
+__device__ __forceinline__ uint32_t low_bytes(int a, int b, int c, int d) {
+    const uint32_t lo = __builtin_amdgcn_perm((uint32_t)b, (uint32_t)a, 0x0c0c0400u);
+    const uint32_t hi = __builtin_amdgcn_perm((uint32_t)d, (uint32_t)c, 0x04000c0cu);
+    return lo | hi;
+}
+
+// Balanced signed byte digits of four integers |v| <= 2^22:  v = d0 + 256 d1 + 65536 d2.
+// Adding 0x808080 makes the three low bytes the digits plus 128; the xor turns each back into a
+// signed byte.  plane[b] packs digit b of the four values.
+__device__ __forceinline__ void digit_planes(const int v[4], uint32_t plane[3]) {
+    uint32_t y[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) y[e] = ((uint32_t)(v[e] + 0x00808080)) ^ 0x00808080u;
+    const uint32_t t0 = __builtin_amdgcn_perm(y[1], y[0], 0x05010400u);  // y0.b0 y1.b0 y0.b1 y1.b1
+    const uint32_t t1 = __builtin_amdgcn_perm(y[1], y[0], 0x0c0c0602u);  // y0.b2 y1.b2 0 0
+    const uint32_t t2 = __builtin_amdgcn_perm(y[3], y[2], 0x05010400u);
+    const uint32_t t3 = __builtin_amdgcn_perm(y[3], y[2], 0x06020c0cu);  // 0 0 y2.b2 y3.b2
+    plane[0] = __builtin_amdgcn_perm(t2, t0, 0x05040100u);
+    plane[1] = __builtin_amdgcn_perm(t2, t0, 0x07060302u);
+    plane[2] = t1 | t3;
+}
+
+template <bool STOCH>
 __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
-    const float* __restrict__ g, size_t n, const float* __restrict__ ratios, int j0, int jn,
+    const float* __restrict__ g, size_t n, const float* __restrict__ ratios, int n_cand,
     const float* __restrict__ absmax_part, int nparts, uint32_t seed_lo, uint32_t seed_hi_mul,
     float* __restrict__ absmax_out, double* __restrict__ partA, unsigned long long* __restrict__ partB,
     double* __restrict__ partG) {
+    constexpr int JC = DSGC_JC;
     __shared__ float lds4[4];
     __shared__ float s_inv[JC];
     __shared__ double s_red[4][JC + 1];
     __shared__ unsigned long long s_redB[4][JC];
 
+    const int j0 = blockIdx.y * JC;
+    const int jn = (n_cand - j0 < JC) ? (n_cand - j0) : JC;
+    const bool want_g = blockIdx.y == 0;
     const float M = reduce_absmax_partials(absmax_part, nparts, lds4);
-    if (blockIdx.x == 0 && threadIdx.x == 0) *absmax_out = M;
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *absmax_out = M;
     if (threadIdx.x < JC) {
         const int j = threadIdx.x;
         const float c = (j < jn) ? __fmul_rn(M, ratios[j0 + j]) : 0.0f;
@@ -43,61 +84,95 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
 #pragma unroll
     for (int j = 0; j < JC; ++j)
         inv[j] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(s_inv[j])));
+    // fixed point: max|g| < 2^e, g * 2^(22-e) has magnitude <= 2^22
+    int e2 = 0;
+    (void)frexpf(M, &e2);
+    const int shift = 22 - e2;
 
-    double A[JC];
-    unsigned B[JC];
+    int accA[JC][6];
+    int accB[JC];
 #pragma unroll
     for (int j = 0; j < JC; ++j) {
-        A[j] = 0.0;
-        B[j] = 0u;
+        accB[j] = 0;
+#pragma unroll
+        for (int b = 0; b < 6; ++b) accA[j][b] = 0;
     }
     double G = 0.0;
+
+    auto group = [&](const float x[4], uint32_t index0, int nvalid) {
+        int u[4] = {0, 0, 0, 0};
+        int H[4], L[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (STOCH) u[e] = (int)rng24(seed_lo, seed_hi_mul, index0 + e);
+            const float xs = ldexpf(x[e], shift);
+            const float h = rintf(xs);
+            H[e] = (int)h;
+            L[e] = (int)rintf(__fmul_rn(xs - h, 8388608.0f));   // remainder * 2^23, exact before rint
+            if (want_g) {
+                const double xd = (double)x[e];
+                G = fma(xd, xd, G);
+            }
+        }
+        (void)nvalid;
+        uint32_t pH[3], pL[3];
+        digit_planes(H, pH);
+        digit_planes(L, pL);
+#pragma unroll
+        for (int j = 0; j < JC; ++j) {
+            uint32_t rp;
+            if (STOCH) {
+                rp = top_bytes(stochastic_sum(x[0], inv[j], u[0]), stochastic_sum(x[1], inv[j], u[1]),
+                               stochastic_sum(x[2], inv[j], u[2]), stochastic_sum(x[3], inv[j], u[3]));
+            } else {
+                rp = low_bytes(round_nearest_code(x[0], inv[j]), round_nearest_code(x[1], inv[j]),
+                               round_nearest_code(x[2], inv[j]), round_nearest_code(x[3], inv[j]));
+            }
+            accB[j] = __builtin_amdgcn_sdot4((int)rp, (int)rp, accB[j], false);
+#pragma unroll
+            for (int b = 0; b < 3; ++b) {
+                accA[j][b] = __builtin_amdgcn_sdot4((int)pH[b], (int)rp, accA[j][b], false);
+                accA[j][3 + b] = __builtin_amdgcn_sdot4((int)pL[b], (int)rp, accA[j][3 + b], false);
+            }
+        }
+    };
 
     const size_t n4 = n >> 2;
     const float4* __restrict__ g4 = reinterpret_cast<const float4*>(g);
     const size_t stride = (size_t)gridDim.x * 256;
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
-        const float4 f = g4[i];
-        const float vv[4] = {f.x, f.y, f.z, f.w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const float x = vv[e];
-            const double xd = (double)x;
-            G = fma(xd, xd, G);
-            int u = 0;
-            if (STOCH) u = (int)rng24(seed_lo, seed_hi_mul, (uint32_t)(4 * i + e));
-#pragma unroll
-            for (int j = 0; j < JC; ++j) {
-                const int r = STOCH ? (stochastic_sum(x, inv[j], u) >> 24) : round_nearest_code(x, inv[j]);
-                A[j] = fma(xd, (double)r, A[j]);
-                B[j] += (unsigned)(r * r);
-            }
+    {
+        // the next iteration's 16 bytes are requested before this iteration's arithmetic starts
+        size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+        float4 f = (i < n4) ? g4[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+        while (i < n4) {
+            const size_t inext = i + stride;
+            const float4 fn = (inext < n4) ? g4[inext] : make_float4(0.f, 0.f, 0.f, 0.f);
+            const float vv[4] = {f.x, f.y, f.z, f.w};
+            group(vv, (uint32_t)(4 * i), 4);
+            f = fn;
+            i = inext;
         }
     }
-    if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
-        const size_t i = (n4 << 2) + threadIdx.x;
-        const float x = g[i];
-        const double xd = (double)x;
-        G = fma(xd, xd, G);
-        int u = 0;
-        if (STOCH) u = (int)rng24(seed_lo, seed_hi_mul, (uint32_t)i);
-#pragma unroll
-        for (int j = 0; j < JC; ++j) {
-            const int r = STOCH ? (stochastic_sum(x, inv[j], u) >> 24) : round_nearest_code(x, inv[j]);
-            A[j] = fma(xd, (double)r, A[j]);
-            B[j] += (unsigned)(r * r);
-        }
+    if (blockIdx.x == 0 && threadIdx.x == 0 && (n & 3)) {
+        // ragged tail: missing elements are zeros (zero contributes nothing to A, B or G)
+        float vv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        for (int e = 0; e < (int)(n & 3); ++e) vv[e] = g[(n4 << 2) + e];
+        group(vv, (uint32_t)(n4 << 2), (int)(n & 3));
     }
 
-    // block reduction: shuffles inside a wave, then the four waves through LDS in fixed order
+    // per-thread totals: A = (2^23 * sum_b 256^b aH_b + sum_b 256^b aL_b) * 2^(e-45); the digit
+    // sums are exact integers below 2^48 in double, the last additions round like any fp64 sum
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
     G = wave_sum(G);
 #pragma unroll
     for (int j = 0; j < JC; ++j) {
-        const double a = wave_sum(A[j]);
-        const unsigned long long b = wave_sum((unsigned long long)B[j]);
+        const double dH = (double)accA[j][0] + 256.0 * (double)accA[j][1] + 65536.0 * (double)accA[j][2];
+        const double dL = (double)accA[j][3] + 256.0 * (double)accA[j][4] + 65536.0 * (double)accA[j][5];
+        const double at = ldexp(dH * 8388608.0 + dL, e2 - 45);
+        const double asum = wave_sum(at);
+        const unsigned long long b = wave_sum((unsigned long long)(unsigned)accB[j]);
         if (lane == 0) {
-            s_red[w][j] = a;
+            s_red[w][j] = asum;
             s_redB[w][j] = b;
         }
     }
@@ -112,7 +187,7 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
                 s_redB[0][j] + s_redB[1][j] + s_redB[2][j] + s_redB[3][j];
         }
     }
-    if (threadIdx.x == 0 && j0 == 0)
+    if (threadIdx.x == 0 && want_g)
         partG[blockIdx.x] = (s_red[0][JC] + s_red[1][JC]) + (s_red[2][JC] + s_red[3][JC]);
 }
 
@@ -134,29 +209,29 @@ __global__ __launch_bounds__(1024) void dsgc_finish_kernel(
     const int j = threadIdx.x & 63, seg = threadIdx.x >> 6;
     const int b0 = (int)(((long long)nblocks * seg) / DSGC_SEGS);
     const int b1 = (int)(((long long)nblocks * (seg + 1)) / DSGC_SEGS);
-    // eight independent running sums per thread keep sixteen loads in flight
-    double a[8];
-    unsigned long long b[8];
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        a[k] = 0.0;
-        b[k] = 0;
-    }
+    // every partial of this thread's segment is requested before the first one is used
+    // (at most DSGC_MAX_BLOCKS / DSGC_SEGS = 32 per segment, in two batches of 16)
+    const float M = *absmax;
+    double a[4] = {0.0, 0.0, 0.0, 0.0};
+    unsigned long long b[4] = {0, 0, 0, 0};
     if (j < n_cand) {
-        for (int i = b0; i < b1; i += 8) {
+        for (int i = b0; i < b1; i += 16) {
+            double av[16];
+            unsigned long long bv[16];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
+            for (int k = 0; k < 16; ++k) {
+                const size_t idx = (size_t)((i + k < b1) ? i + k : b0) * DSGC_JPAD + j;
+                av[k] = partA[idx];
+                bv[k] = partB[idx];
+            }
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
                 const bool in = i + k < b1;
-                const size_t idx = (size_t)(in ? i + k : b0) * DSGC_JPAD + j;
-                const double av = partA[idx];
-                const unsigned long long bv = partB[idx];
-                a[k] += in ? av : 0.0;
-                b[k] += in ? bv : 0ull;
+                a[k & 3] += in ? av[k] : 0.0;
+                b[k & 3] += in ? bv[k] : 0ull;
             }
         }
     }
-    a[0] = (a[0] + a[4]); a[1] = (a[1] + a[5]); a[2] = (a[2] + a[6]); a[3] = (a[3] + a[7]);
-    b[0] += b[4]; b[1] += b[5]; b[2] += b[6]; b[3] += b[7];
     sA[seg][j] = (a[0] + a[1]) + (a[2] + a[3]);
     sB[seg][j] = b[0] + b[1] + b[2] + b[3];
     {
@@ -191,7 +266,6 @@ __global__ __launch_bounds__(1024) void dsgc_finish_kernel(
         int best = 0;
         for (int k = 1; k < n_cand; ++k)
             if (sD[k] < sD[best]) best = k;
-        const float M = *absmax;
         if (M == 0.0f) best = 0;
         *clip_out = __fmul_rn(M, ratios[best]);
         *dev_out = sD[best];
@@ -206,21 +280,22 @@ int dsgc_blocks(size_t n) {
 hipError_t launch_dsgc(const float* g, size_t n, const float* ratios, int n_cand, int stochastic,
                        uint64_t seed, const DsgcWs& ws, int nparts_absmax, float* clip_out,
                        double* dev_out, double* dev_all_out, hipStream_t st) {
-    const int blocks = dsgc_blocks(n);
+    const int nchunks = (n_cand + DSGC_JC - 1) / DSGC_JC;
+    // about two blocks per compute unit in total; every candidate chunk uses the same x-grid so
+    // that the partial arrays have one row per x-block
+    int blocks = dsgc_blocks(n);
+    const int cap = (DSGC_MAX_BLOCKS + nchunks - 1) / nchunks;
+    if (blocks > cap) blocks = cap;
     const uint32_t slo = (uint32_t)seed, shi = seed_hi_term(seed);
-    for (int j0 = 0; j0 < n_cand; j0 += DSGC_JC) {
-        const int jn = (n_cand - j0 < DSGC_JC) ? (n_cand - j0) : DSGC_JC;
-        if (stochastic)
-            hipLaunchKernelGGL((dsgc_sweep_kernel<DSGC_JC, true>), dim3(blocks), dim3(256), 0, st, g, n,
-                               ratios, j0, jn, ws.absmax_part, nparts_absmax, slo, shi, ws.absmax,
-                               ws.partA, ws.partB, ws.partG);
-        else
-            hipLaunchKernelGGL((dsgc_sweep_kernel<DSGC_JC, false>), dim3(blocks), dim3(256), 0, st, g, n,
-                               ratios, j0, jn, ws.absmax_part, nparts_absmax, slo, shi, ws.absmax,
-                               ws.partA, ws.partB, ws.partG);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-    }
+    dim3 grid(blocks, nchunks);
+    if (stochastic)
+        hipLaunchKernelGGL((dsgc_sweep_kernel<true>), grid, dim3(256), 0, st, g, n, ratios, n_cand,
+                           ws.absmax_part, nparts_absmax, slo, shi, ws.absmax, ws.partA, ws.partB, ws.partG);
+    else
+        hipLaunchKernelGGL((dsgc_sweep_kernel<false>), grid, dim3(256), 0, st, g, n, ratios, n_cand,
+                           ws.absmax_part, nparts_absmax, slo, shi, ws.absmax, ws.partA, ws.partB, ws.partG);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(dsgc_finish_kernel, dim3(1), dim3(1024), 0, st, ws.partA, ws.partB, ws.partG,
                        blocks, ratios, n_cand, ws.absmax, clip_out, dev_out, dev_all_out);
     return hipGetLastError();
