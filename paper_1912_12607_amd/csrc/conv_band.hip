@@ -1,0 +1,249 @@
+// Dense forward / backward-data convolution for layers whose whole filter bank is small
+// (at most 64 output rows and a few tens of KB of weight codes): the ResNet-18 3x3 layer, the
+// MobileNetV2 1x1 layers.  Same arithmetic as conv_igemm.hip (int8 MFMA, int32 accumulators, Eq.2
+// in the epilogue), different staging: such layers have a reduction of only a few hundred bytes
+// per output, so a tile-by-tile pipeline spends its time waiting for memory.  Here a block keeps
+// the complete weight matrix in LDS for its lifetime and, per band of output rows, stages the
+// input rows it needs ONCE (with their zero padding); every filter tap is then a shifted view of
+// that LDS window -- pixel-granular, so always 16-byte aligned -- and the whole reduction runs
+// out of LDS without touching global memory again.
+//
+//   forward        rows = K, act = codes of a   (N,H,W,Cp), input pixel = (oh + r - ph, ow + s - pw)
+//   backward-data  rows = C, act = codes of g_z (N,P,Q,Kp), input pixel = (oh + ph - r, ow + pw - s)
+// (stride 1 only; other shapes go through the implicit-GEMM kernel.)
+#include "device_common.h"
+#include "kernels.h"
+
+namespace int8t {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int BAND_NTW = 2;                  // 32-pixel tiles per wave (x 2 row tiles of 32)
+constexpr int BAND_PIX = 4 * BAND_NTW * 32;  // output pixels per band (256)
+constexpr size_t BAND_LDS_MAX = 80 * 1024;   // two blocks per compute unit
+constexpr int BAND_STAGE = 12;               // staged 16-byte granules per thread and band, at most
+constexpr int BAND_MAXK = 512;               // MFMA k-steps (pairs of granules), at most
+
+// odd pitch (in 16-byte granules): rows of a tile read at one granule index land in distinct banks
+__host__ __device__ inline int odd_pitch(int granules) { return (granules & 1) ? granules : granules + 1; }
+
+// The kernel is written to keep the vector-ALU instruction count per MFMA small: everything that
+// does not depend on the band (which granule a thread stages, the LDS offsets of every k-step,
+// the output offsets of a lane) is worked out once per block.
+template <bool DGRAD, int MT>   // MT: 32-row tiles of output rows (1 or 2)
+__global__ __launch_bounds__(256) void band_kernel(const IgemmArgs a, int BP, int nbands_h, int nbands) {
+    extern __shared__ __attribute__((aligned(16))) uint4 lds[];
+    const int Cg16 = a.Ca >> 4;
+    const int G = a.R * a.S * Cg16;          // reduction granules
+    const int GP = odd_pitch(G);
+    const int PG = odd_pitch(Cg16);
+    const int WH = BP + a.R - 1, WW = a.OW + a.S - 1;
+    const int nksteps = (G + 1) >> 1;
+    uint4* __restrict__ wT = lds;                       // [64 rows][GP]
+    uint4* __restrict__ xW = lds + 64 * GP;             // [WH*WW pixels][PG]
+    uint4* __restrict__ zero = xW + WH * WW * PG;       // one zero granule
+    int2* __restrict__ ktab = reinterpret_cast<int2*>(zero + 1);   // [nksteps][2 halves]: {A offset, B offset}
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
+    // smallest input offset over the taps (rows / columns)
+    const int drmin = DGRAD ? (a.pad_h - (a.R - 1)) : -a.pad_h;
+    const int dsmin = DGRAD ? (a.pad_w - (a.S - 1)) : -a.pad_w;
+
+    // ---- weights: once per block, loads issued in batches of eight before any is stored ---------
+    for (int base = 0; base < 64 * G; base += 256 * 8) {
+        uint4 v[8];
+        int dst[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int idx = base + tid + 256 * k;
+            const bool in = idx < 64 * G;
+            const int row = (in ? idx : 0) / G, g = (in ? idx : 0) - row * G;
+            dst[k] = in ? (row * GP + g) : -1;
+            v[k] = make_uint4(0, 0, 0, 0);
+            if (in && row < a.rows) v[k] = *reinterpret_cast<const uint4*>(a.wgt + ((size_t)row * G + g) * 16);
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            if (dst[k] >= 0) wT[dst[k]] = v[k];
+    }
+    if (tid == 0) *zero = make_uint4(0, 0, 0, 0);
+    // ---- k-step table: granule g = 2*ks + half -> {offset of the weight granule, offset of the
+    // tap's pixel shift + channel granule}; granules past the end read the zero granule ------------
+    for (int e = tid; e < 2 * nksteps; e += 256) {
+        const int g = e;                       // e = 2*ks + half
+        int2 t;
+        if (g < G) {
+            const int tap = g / Cg16, cg = g - tap * Cg16;
+            const int r = tap / a.S, s = tap - r * a.S;
+            const int dr = DGRAD ? (a.pad_h - r) : (r - a.pad_h);
+            const int ds = DGRAD ? (a.pad_w - s) : (s - a.pad_w);
+            t.x = g;
+            t.y = ((dr - drmin) * WW + (ds - dsmin)) * PG + cg;
+        } else {
+            t.x = -1;
+            t.y = 0;
+        }
+        ktab[e] = t;
+    }
+
+    // ---- band-independent staging plan: slot k of this thread covers granule (wx, cg) of window
+    // row wy, with k = wy * kw + j and j-th column granule tid + 256*j ------------------------------
+    const int rowgran = WW * Cg16;
+    const int kw = (rowgran + 255) >> 8;
+    int s_goff[BAND_STAGE], s_ldst[BAND_STAGE], s_wy[BAND_STAGE];
+#pragma unroll
+    for (int k = 0; k < BAND_STAGE; ++k) {
+        const int wy = k / kw, j = k - wy * kw;
+        const int col = tid + 256 * j;
+        s_wy[k] = -1;
+        s_goff[k] = 0;
+        s_ldst[k] = 0;
+        if (wy < WH && col < rowgran) {
+            const int wx = col / Cg16, cg = col - wx * Cg16;
+            const int iw = dsmin + wx;
+            s_ldst[k] = (wy * WW + wx) * PG + cg;
+            s_wy[k] = wy;
+            if ((unsigned)iw < (unsigned)a.IW) s_goff[k] = iw * a.Ca + cg * 16;
+            else s_goff[k] = -1;               // padding column: zeros
+        }
+    }
+
+    // ---- per-lane output bookkeeping of the wave's n-tiles (pixel index inside the band) ---------
+    const int npix = BP * a.OW;
+    const int OHW = a.OH * a.OW;
+    int pbase[BAND_NTW], pl[BAND_NTW], obase[BAND_NTW];
+    bool pvalid[BAND_NTW];
+#pragma unroll
+    for (int i = 0; i < BAND_NTW; ++i) {
+        const int p = (wave + 4 * i) * 32 + l32;
+        pvalid[i] = p < npix;
+        const int pp = pvalid[i] ? p : 0;
+        pl[i] = pp / a.OW;
+        const int ql = pp - pl[i] * a.OW;
+        pbase[i] = (pl[i] * WW + ql) * PG;
+        obase[i] = (4 * half) * OHW + pl[i] * a.OW + ql;   // + (n*rows)*OHW + oh0*OW + row term
+    }
+    const float scale = __fmul_rn(a.sa[0], a.sb[0]);
+    const int aoff0 = l32 * GP, aoff1 = (32 + l32) * GP;
+
+    for (int band = blockIdx.x; band < nbands; band += gridDim.x) {
+        const int n = band / nbands_h;
+        const int oh0 = (band - n * nbands_h) * BP;
+        __syncthreads();   // previous band's reads are done (and weights / tables are in place)
+        // ---- stage the input window with its zero padding: all loads first, then all stores ------
+        {
+            const int8_t* __restrict__ img = a.act + (size_t)n * a.IH * a.IW * a.Ca;
+            uint4 v[BAND_STAGE];
+#pragma unroll
+            for (int k = 0; k < BAND_STAGE; ++k) {
+                v[k] = make_uint4(0, 0, 0, 0);
+                const int ih = oh0 + drmin + s_wy[k];
+                if (s_wy[k] >= 0 && s_goff[k] >= 0 && (unsigned)ih < (unsigned)a.IH)
+                    v[k] = *reinterpret_cast<const uint4*>(img + (size_t)ih * a.IW * a.Ca + s_goff[k]);
+            }
+#pragma unroll
+            for (int k = 0; k < BAND_STAGE; ++k)
+                if (s_wy[k] >= 0) xW[s_ldst[k]] = v[k];
+        }
+        __syncthreads();
+
+        v16i acc[MT][BAND_NTW];
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+#pragma unroll
+            for (int i = 0; i < BAND_NTW; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[m][i][v] = 0;
+
+        for (int ks = 0; ks < nksteps; ++ks) {
+            const int2 t = ktab[2 * ks + half];
+            const bool gv = t.x >= 0;
+            v4i fa[MT];
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+                const uint4 tw = gv ? wT[(m ? aoff1 : aoff0) + t.x] : *zero;
+                fa[m] = v4i{(int)tw.x, (int)tw.y, (int)tw.z, (int)tw.w};
+            }
+            v4i fb[BAND_NTW];
+#pragma unroll
+            for (int i = 0; i < BAND_NTW; ++i) {
+                const uint4 tb = xW[pbase[i] + t.y];
+                fb[i] = v4i{(int)tb.x, (int)tb.y, (int)tb.z, (int)tb.w};
+            }
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+#pragma unroll
+                for (int i = 0; i < BAND_NTW; ++i)
+                    acc[m][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[m], fb[i], acc[m][i], 0, 0, 0);
+        }
+
+        // ---- epilogue: Eq.2, 32 consecutive pixels of one output row per store -------------------
+        const int bandoff = n * a.rows * OHW + oh0 * a.OW;   // output elements < 2^31 (checked on the host)
+#pragma unroll
+        for (int i = 0; i < BAND_NTW; ++i) {
+            if (!pvalid[i] || oh0 + pl[i] >= a.OH) continue;
+            float* __restrict__ outp = a.out + bandoff + obase[i];
+            int32_t* __restrict__ accp = a.acc ? a.acc + bandoff + obase[i] : nullptr;
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int rowu = m * 32 + 8 * (v >> 2) + (v & 3);   // + 4*half, already in obase
+                    if (rowu + 4 * half < a.rows) {
+                        const int val = acc[m][i][v];
+                        outp[rowu * OHW] = __fmul_rn((float)val, scale);
+                        if (accp) accp[rowu * OHW] = val;
+                    }
+                }
+            }
+        }
+    }
+}
+
+// Returns true (and launches) when the layer fits this kernel; false: use the implicit GEMM.
+bool launch_band(const IgemmArgs& a, hipStream_t st, hipError_t* err) {
+    if (a.stride_h != 1 || a.stride_w != 1 || a.rows > 64 || a.OW > BAND_PIX) return false;
+    if (a.dgrad ? (a.pad_h > a.R - 1 || a.pad_w > a.S - 1) : false) return false;
+    const int Cg16 = a.Ca >> 4;
+    const int G = a.R * a.S * Cg16;
+    if ((G + 1) / 2 > BAND_MAXK) return false;
+    if ((size_t)a.N * a.rows * a.OH * a.OW > 0x7FFFFFFFull) return false;
+    int BP = BAND_PIX / a.OW;
+    if (BP > a.OH) BP = a.OH;
+    const int WW = a.OW + a.S - 1;
+    const int kw = (WW * Cg16 + 255) / 256;
+    while (BP > 1 && (BP + a.R - 1) * kw > BAND_STAGE) --BP;
+    const int WH = BP + a.R - 1;
+    if (WH * kw > BAND_STAGE) return false;
+    const size_t lds = ((size_t)64 * odd_pitch(G) + (size_t)WH * WW * odd_pitch(Cg16) + 1) * 16 +
+                       (size_t)(G + 2) * sizeof(int2);
+    if (lds > BAND_LDS_MAX) return false;
+    const int nbands_h = (a.OH + BP - 1) / BP;
+    const int nbands = a.N * nbands_h;
+    const int grid = nbands < 512 ? nbands : 512;
+    const int mt = a.rows > 32 ? 2 : 1;
+    const void* fn = a.dgrad ? (mt == 2 ? reinterpret_cast<const void*>(&band_kernel<true, 2>)
+                                        : reinterpret_cast<const void*>(&band_kernel<true, 1>))
+                             : (mt == 2 ? reinterpret_cast<const void*>(&band_kernel<false, 2>)
+                                        : reinterpret_cast<const void*>(&band_kernel<false, 1>));
+    static bool attr_done[4] = {false, false, false, false};
+    const int slot = (a.dgrad ? 2 : 0) + (mt - 1);
+    if (!attr_done[slot]) {
+        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)BAND_LDS_MAX);
+        if (e != hipSuccess) { *err = e; return true; }
+        attr_done[slot] = true;
+    }
+    if (a.dgrad) {
+        if (mt == 2) hipLaunchKernelGGL((band_kernel<true, 2>), dim3(grid), dim3(256), lds, st, a, BP, nbands_h, nbands);
+        else hipLaunchKernelGGL((band_kernel<true, 1>), dim3(grid), dim3(256), lds, st, a, BP, nbands_h, nbands);
+    } else {
+        if (mt == 2) hipLaunchKernelGGL((band_kernel<false, 2>), dim3(grid), dim3(256), lds, st, a, BP, nbands_h, nbands);
+        else hipLaunchKernelGGL((band_kernel<false, 1>), dim3(grid), dim3(256), lds, st, a, BP, nbands_h, nbands);
+    }
+    *err = hipGetLastError();
+    return true;
+}
+
+}  // namespace int8t

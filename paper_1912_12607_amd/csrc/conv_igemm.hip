@@ -189,6 +189,8 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
 }
 
 hipError_t launch_igemm(const IgemmArgs& a, hipStream_t st) {
+    hipError_t berr = hipSuccess;
+    if (launch_band(a, st, &berr)) return berr;   // small filter bank: LDS-resident kernel
     const int ncols = a.N * a.OH * a.OW;
     const int ctiles = (ncols + IG_BN - 1) / IG_BN;
     if (a.rows <= 64) {

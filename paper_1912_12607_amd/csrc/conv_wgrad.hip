@@ -220,14 +220,12 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
                 const uint4 ta = dyT[a_off[s]];
                 const v4i fa = v4i{(int)ta.x, (int)ta.y, (int)ta.z, (int)ta.w};
 #pragma unroll
-                for (int j = 0; j < TB; ++j) {
-                    if (j < nt) {
+                for (int j = 0; j < TB; ++j) {   // TB divides R*S: every tap of the group exists
 #pragma unroll
-                        for (int i = 0; i < CS; ++i) {
-                            const uint4 tb = xT[x_off[s] + toff[j] + i * 32];
-                            const v4i fb = v4i{(int)tb.x, (int)tb.y, (int)tb.z, (int)tb.w};
-                            acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa, fb, acc[j][i], 0, 0, 0);
-                        }
+                    for (int i = 0; i < CS; ++i) {
+                        const uint4 tb = xT[x_off[s] + toff[j] + i * 32];
+                        const v4i fb = v4i{(int)tb.x, (int)tb.y, (int)tb.z, (int)tb.w};
+                        acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa, fb, acc[j][i], 0, 0, 0);
                     }
                 }
             }
@@ -286,9 +284,10 @@ void wgrad_plan(WgradArgs* a) {
     // taps per block / channel slabs per wave: one filter row of a 3-wide filter, a whole 1x7 or
     // 7x1 filter, a wide channel tile for 1x1, one tap at a time otherwise
     if (RS == 1) { a->TB = 1; a->CS = (a->Cp >= 256) ? 4 : 1; }
-    else if (a->S == 3) { a->TB = 3; a->CS = 1; }
+    else if (RS % 3 == 0 && a->S == 3) { a->TB = 3; a->CS = 1; }
     else if (RS == 7) { a->TB = 7; a->CS = 1; }
     else { a->TB = 1; a->CS = 1; }
+    // TB divides R*S in every case, so a tap group is never ragged
     const int CT = 64 * a->CS;
     a->tapgroups = (RS + a->TB - 1) / a->TB;
     a->ktiles = (a->K + W2_BM - 1) / W2_BM;

@@ -67,6 +67,8 @@ struct IgemmArgs {
     int dgrad;                   // 0: ih = oh*stride + r - pad;  1: ih = (oh + pad - r)/stride
 };
 hipError_t launch_igemm(const IgemmArgs& a, hipStream_t st);
+// conv_band.hip: LDS-resident variant for small filter banks; false = shape not covered
+bool launch_band(const IgemmArgs& a, hipStream_t st, hipError_t* err);
 
 // ---- conv_wgrad.hip (dense backward-weight) ---------------------------------------------------
 struct WgradArgs {
