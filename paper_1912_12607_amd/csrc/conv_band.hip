@@ -19,8 +19,7 @@ namespace int8t {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr int BAND_NTW = 2;                  // 32-pixel tiles per wave (x 2 row tiles of 32)
-constexpr int BAND_PIX = 4 * BAND_NTW * 32;  // output pixels per band (256)
+constexpr int BAND_MAXPIX = 256;             // output pixels per band, at most (NTW = 2: 8 tiles of 32)
 constexpr size_t BAND_LDS_MAX = 80 * 1024;   // two blocks per compute unit
 constexpr int BAND_STAGE = 12;               // staged 16-byte granules per thread and band, at most
 constexpr int BAND_MAXK = 512;               // MFMA k-steps (pairs of granules), at most
@@ -31,7 +30,7 @@ __host__ __device__ inline int odd_pitch(int granules) { return (granules & 1) ?
 // The kernel is written to keep the vector-ALU instruction count per MFMA small: everything that
 // does not depend on the band (which granule a thread stages, the LDS offsets of every k-step,
 // the output offsets of a lane) is worked out once per block.
-template <bool DGRAD, int MT>   // MT: 32-row tiles of output rows (1 or 2)
+template <bool DGRAD, int MT, int BAND_NTW>   // MT: 32-row tiles of output rows; BAND_NTW: 32-pixel tiles per wave
 __global__ __launch_bounds__(256) void band_kernel(const IgemmArgs a, int BP, int nbands_h, int nbands) {
     extern __shared__ __attribute__((aligned(16))) uint4 lds[];
     const int Cg16 = a.Ca >> 4;
@@ -128,26 +127,31 @@ __global__ __launch_bounds__(256) void band_kernel(const IgemmArgs a, int BP, in
     const float scale = __fmul_rn(a.sa[0], a.sb[0]);
     const int aoff0 = l32 * GP, aoff1 = (32 + l32) * GP;
 
+    // Window loads of the NEXT band are in flight (in registers) while the current band computes.
+    uint4 pre[BAND_STAGE];
+    auto issue = [&](int band) {
+        const int n = band / nbands_h;
+        const int oh0 = (band - n * nbands_h) * BP;
+        const int8_t* __restrict__ img = a.act + (size_t)n * a.IH * a.IW * a.Ca;
+#pragma unroll
+        for (int k = 0; k < BAND_STAGE; ++k) {
+            pre[k] = make_uint4(0, 0, 0, 0);
+            const int ih = oh0 + drmin + s_wy[k];
+            if (s_wy[k] >= 0 && s_goff[k] >= 0 && (unsigned)ih < (unsigned)a.IH)
+                pre[k] = *reinterpret_cast<const uint4*>(img + (size_t)ih * a.IW * a.Ca + s_goff[k]);
+        }
+    };
+    if ((int)blockIdx.x < nbands) issue(blockIdx.x);
+
     for (int band = blockIdx.x; band < nbands; band += gridDim.x) {
         const int n = band / nbands_h;
         const int oh0 = (band - n * nbands_h) * BP;
         __syncthreads();   // previous band's reads are done (and weights / tables are in place)
-        // ---- stage the input window with its zero padding: all loads first, then all stores ------
-        {
-            const int8_t* __restrict__ img = a.act + (size_t)n * a.IH * a.IW * a.Ca;
-            uint4 v[BAND_STAGE];
 #pragma unroll
-            for (int k = 0; k < BAND_STAGE; ++k) {
-                v[k] = make_uint4(0, 0, 0, 0);
-                const int ih = oh0 + drmin + s_wy[k];
-                if (s_wy[k] >= 0 && s_goff[k] >= 0 && (unsigned)ih < (unsigned)a.IH)
-                    v[k] = *reinterpret_cast<const uint4*>(img + (size_t)ih * a.IW * a.Ca + s_goff[k]);
-            }
-#pragma unroll
-            for (int k = 0; k < BAND_STAGE; ++k)
-                if (s_wy[k] >= 0) xW[s_ldst[k]] = v[k];
-        }
+        for (int k = 0; k < BAND_STAGE; ++k)
+            if (s_wy[k] >= 0) xW[s_ldst[k]] = pre[k];
         __syncthreads();
+        if (band + (int)gridDim.x < nbands) issue(band + gridDim.x);
 
         v16i acc[MT][BAND_NTW];
 #pragma unroll
@@ -204,13 +208,15 @@ __global__ __launch_bounds__(256) void band_kernel(const IgemmArgs a, int BP, in
 
 // Returns true (and launches) when the layer fits this kernel; false: use the implicit GEMM.
 bool launch_band(const IgemmArgs& a, hipStream_t st, hipError_t* err) {
-    if (a.stride_h != 1 || a.stride_w != 1 || a.rows > 64 || a.OW > BAND_PIX) return false;
-    if (a.dgrad ? (a.pad_h > a.R - 1 || a.pad_w > a.S - 1) : false) return false;
+    if (a.stride_h != 1 || a.stride_w != 1 || a.rows > 64 || a.OW > BAND_MAXPIX) return false;
     const int Cg16 = a.Ca >> 4;
     const int G = a.R * a.S * Cg16;
     if ((G + 1) / 2 > BAND_MAXK) return false;
     if ((size_t)a.N * a.rows * a.OH * a.OW > 0x7FFFFFFFull) return false;
-    int BP = BAND_PIX / a.OW;
+    // band height: as many output rows as fit 128 pixels (one 32-pixel tile per wave), or 256
+    // (two tiles per wave) when a single row is already wider than 128
+    int ntw = (a.OW > 128) ? 2 : 1;
+    int BP = (128 * ntw) / a.OW;
     if (BP > a.OH) BP = a.OH;
     const int WW = a.OW + a.S - 1;
     const int kw = (WW * Cg16 + 255) / 256;
@@ -224,24 +230,19 @@ bool launch_band(const IgemmArgs& a, hipStream_t st, hipError_t* err) {
     const int nbands = a.N * nbands_h;
     const int grid = nbands < 512 ? nbands : 512;
     const int mt = a.rows > 32 ? 2 : 1;
-    const void* fn = a.dgrad ? (mt == 2 ? reinterpret_cast<const void*>(&band_kernel<true, 2>)
-                                        : reinterpret_cast<const void*>(&band_kernel<true, 1>))
-                             : (mt == 2 ? reinterpret_cast<const void*>(&band_kernel<false, 2>)
-                                        : reinterpret_cast<const void*>(&band_kernel<false, 1>));
-    static bool attr_done[4] = {false, false, false, false};
-    const int slot = (a.dgrad ? 2 : 0) + (mt - 1);
-    if (!attr_done[slot]) {
-        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)BAND_LDS_MAX);
+    const int variant = (a.dgrad ? 4 : 0) + (mt - 1) * 2 + (ntw - 1);
+    typedef void (*kern_t)(const IgemmArgs, int, int, int);
+    static const kern_t kerns[8] = {
+        band_kernel<false, 1, 1>, band_kernel<false, 1, 2>, band_kernel<false, 2, 1>, band_kernel<false, 2, 2>,
+        band_kernel<true, 1, 1>,  band_kernel<true, 1, 2>,  band_kernel<true, 2, 1>,  band_kernel<true, 2, 2>};
+    static bool attr_done[8] = {false, false, false, false, false, false, false, false};
+    if (!attr_done[variant]) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kerns[variant]),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)BAND_LDS_MAX);
         if (e != hipSuccess) { *err = e; return true; }
-        attr_done[slot] = true;
+        attr_done[variant] = true;
     }
-    if (a.dgrad) {
-        if (mt == 2) hipLaunchKernelGGL((band_kernel<true, 2>), dim3(grid), dim3(256), lds, st, a, BP, nbands_h, nbands);
-        else hipLaunchKernelGGL((band_kernel<true, 1>), dim3(grid), dim3(256), lds, st, a, BP, nbands_h, nbands);
-    } else {
-        if (mt == 2) hipLaunchKernelGGL((band_kernel<false, 2>), dim3(grid), dim3(256), lds, st, a, BP, nbands_h, nbands);
-        else hipLaunchKernelGGL((band_kernel<false, 1>), dim3(grid), dim3(256), lds, st, a, BP, nbands_h, nbands);
-    }
+    hipLaunchKernelGGL(kerns[variant], dim3(grid), dim3(256), lds, st, a, BP, nbands_h, nbands);
     *err = hipGetLastError();
     return true;
 }
