@@ -22,7 +22,8 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 constexpr int BAND_MAXPIX = 256;             // output pixels per band, at most (NTW = 2: 8 tiles of 32)
 constexpr size_t BAND_LDS_MAX = 80 * 1024;   // two blocks per compute unit
 constexpr int BAND_STAGE = 12;               // staged 16-byte granules per thread and band, at most
-constexpr int BAND_MAXK = 512;               // MFMA k-steps (pairs of granules), at most
+constexpr int BAND_MAXG = 64;                // reduction granules (16 bytes each) per output row, at most
+constexpr int BAND_WJ = BAND_MAXG / 4;       // weight granules per thread
 
 // odd pitch (in 16-byte granules): rows of a tile read at one granule index land in distinct banks
 __host__ __device__ inline int odd_pitch(int granules) { return (granules & 1) ? granules : granules + 1; }
@@ -30,7 +31,9 @@ __host__ __device__ inline int odd_pitch(int granules) { return (granules & 1) ?
 // The kernel is written to keep the vector-ALU instruction count per MFMA small: everything that
 // does not depend on the band (which granule a thread stages, the LDS offsets of every k-step,
 // the output offsets of a lane) is worked out once per block.
-template <bool DGRAD, int MT, int BAND_NTW>   // MT: 32-row tiles of output rows; BAND_NTW: 32-pixel tiles per wave
+// MT: 32-row tiles of output rows; NTW: 32-pixel tiles per wave; UNI: rows is a multiple of 8, so
+// the "row exists" test of the epilogue is the same for every lane.
+template <bool DGRAD, int MT, int NTW, bool UNI>
 __global__ __launch_bounds__(256) void band_kernel(const IgemmArgs a, int BP, int nbands_h, int nbands) {
     extern __shared__ __attribute__((aligned(16))) uint4 lds[];
     const int Cg16 = a.Ca >> 4;
@@ -42,7 +45,7 @@ __global__ __launch_bounds__(256) void band_kernel(const IgemmArgs a, int BP, in
     uint4* __restrict__ wT = lds;                       // [64 rows][GP]
     uint4* __restrict__ xW = lds + 64 * GP;             // [WH*WW pixels][PG]
     uint4* __restrict__ zero = xW + WH * WW * PG;       // one zero granule
-    int2* __restrict__ ktab = reinterpret_cast<int2*>(zero + 1);   // [nksteps][2 halves]: {A offset, B offset}
+    int2* __restrict__ ktab = reinterpret_cast<int2*>(zero + 1);   // [nksteps + 1][2 halves]: {A offset, B offset}
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
@@ -50,29 +53,33 @@ __global__ __launch_bounds__(256) void band_kernel(const IgemmArgs a, int BP, in
     const int drmin = DGRAD ? (a.pad_h - (a.R - 1)) : -a.pad_h;
     const int dsmin = DGRAD ? (a.pad_w - (a.S - 1)) : -a.pad_w;
 
-    // ---- weights: once per block, loads issued in batches of eight before any is stored ---------
-    for (int base = 0; base < 64 * G; base += 256 * 8) {
-        uint4 v[8];
-        int dst[8];
+    // ---- weights, once per block: thread = (row, granule mod 4); every load is issued before the
+    // first store, so the whole matrix costs one memory round trip -------------------------------
+    {
+        const int row = tid >> 2, gq = tid & 3;
+        const bool rv = row < a.rows;
+        const int8_t* __restrict__ src = a.wgt + (size_t)(rv ? row : 0) * G * 16;
+        uint4 v[BAND_WJ];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const int idx = base + tid + 256 * k;
-            const bool in = idx < 64 * G;
-            const int row = (in ? idx : 0) / G, g = (in ? idx : 0) - row * G;
-            dst[k] = in ? (row * GP + g) : -1;
-            v[k] = make_uint4(0, 0, 0, 0);
-            if (in && row < a.rows) v[k] = *reinterpret_cast<const uint4*>(a.wgt + ((size_t)row * G + g) * 16);
+        for (int j = 0; j < BAND_WJ; ++j) {
+            const int g = gq + 4 * j;
+            v[j] = make_uint4(0, 0, 0, 0);
+            if (rv && g < G) v[j] = *reinterpret_cast<const uint4*>(src + g * 16);
         }
 #pragma unroll
-        for (int k = 0; k < 8; ++k)
-            if (dst[k] >= 0) wT[dst[k]] = v[k];
+        for (int j = 0; j < BAND_WJ; ++j) {
+            const int g = gq + 4 * j;
+            if (g < G) wT[row * GP + g] = v[j];
+        }
     }
     if (tid == 0) *zero = make_uint4(0, 0, 0, 0);
-    // ---- k-step table: granule g = 2*ks + half -> {offset of the weight granule, offset of the
-    // tap's pixel shift + channel granule}; granules past the end read the zero granule ------------
-    for (int e = tid; e < 2 * nksteps; e += 256) {
-        const int g = e;                       // e = 2*ks + half
+    // ---- k-step table: granule g = 2*ks + half -> {weight granule index or -1, LDS offset of the
+    // tap's pixel shift + channel granule}; one spare k-step so that the pipeline may read ahead ----
+    if (tid < 2 * (nksteps + 1)) {
+        const int g = tid;                       // = 2*ks + half
         int2 t;
+        t.x = -1;
+        t.y = 0;
         if (g < G) {
             const int tap = g / Cg16, cg = g - tap * Cg16;
             const int r = tap / a.S, s = tap - r * a.S;
@@ -80,49 +87,52 @@ __global__ __launch_bounds__(256) void band_kernel(const IgemmArgs a, int BP, in
             const int ds = DGRAD ? (a.pad_w - s) : (s - a.pad_w);
             t.x = g;
             t.y = ((dr - drmin) * WW + (ds - dsmin)) * PG + cg;
-        } else {
-            t.x = -1;
-            t.y = 0;
         }
-        ktab[e] = t;
+        ktab[tid] = t;
     }
 
-    // ---- band-independent staging plan: slot k of this thread covers granule (wx, cg) of window
-    // row wy, with k = wy * kw + j and j-th column granule tid + 256*j ------------------------------
+    // ---- band-independent staging plan: slot k of this thread covers column granule
+    // tid + 256*j of window row wy, k = wy * kw + j ----------------------------------------------------
     const int rowgran = WW * Cg16;
     const int kw = (rowgran + 255) >> 8;
     int s_goff[BAND_STAGE], s_ldst[BAND_STAGE], s_wy[BAND_STAGE];
+    {
+        int wy = 0, j = 0;
 #pragma unroll
-    for (int k = 0; k < BAND_STAGE; ++k) {
-        const int wy = k / kw, j = k - wy * kw;
-        const int col = tid + 256 * j;
-        s_wy[k] = -1;
-        s_goff[k] = 0;
-        s_ldst[k] = 0;
-        if (wy < WH && col < rowgran) {
-            const int wx = col / Cg16, cg = col - wx * Cg16;
-            const int iw = dsmin + wx;
-            s_ldst[k] = (wy * WW + wx) * PG + cg;
-            s_wy[k] = wy;
-            if ((unsigned)iw < (unsigned)a.IW) s_goff[k] = iw * a.Ca + cg * 16;
-            else s_goff[k] = -1;               // padding column: zeros
+        for (int k = 0; k < BAND_STAGE; ++k) {
+            const int col = tid + 256 * j;
+            s_wy[k] = -1;
+            s_goff[k] = 0;
+            s_ldst[k] = 0;
+            if (wy < WH && col < rowgran) {
+                const int wx = col / Cg16, cg = col - wx * Cg16;
+                const int iw = dsmin + wx;
+                s_ldst[k] = (wy * WW + wx) * PG + cg;
+                s_wy[k] = wy;
+                s_goff[k] = ((unsigned)iw < (unsigned)a.IW) ? (iw * a.Ca + cg * 16) : -1;   // -1: padding column
+            }
+            if (++j == kw) {
+                j = 0;
+                ++wy;
+            }
         }
     }
 
     // ---- per-lane output bookkeeping of the wave's n-tiles (pixel index inside the band) ---------
     const int npix = BP * a.OW;
     const int OHW = a.OH * a.OW;
-    int pbase[BAND_NTW], pl[BAND_NTW], obase[BAND_NTW];
-    bool pvalid[BAND_NTW];
+    int pbase[NTW], pl[NTW];
+    uint32_t obase[NTW];
+    bool pvalid[NTW];
 #pragma unroll
-    for (int i = 0; i < BAND_NTW; ++i) {
+    for (int i = 0; i < NTW; ++i) {
         const int p = (wave + 4 * i) * 32 + l32;
         pvalid[i] = p < npix;
         const int pp = pvalid[i] ? p : 0;
         pl[i] = pp / a.OW;
         const int ql = pp - pl[i] * a.OW;
         pbase[i] = (pl[i] * WW + ql) * PG;
-        obase[i] = (4 * half) * OHW + pl[i] * a.OW + ql;   // + (n*rows)*OHW + oh0*OW + row term
+        obase[i] = (uint32_t)((4 * half) * OHW + pl[i] * a.OW + ql);   // + (n*rows)*OHW + oh0*OW + row term
     }
     const float scale = __fmul_rn(a.sa[0], a.sb[0]);
     const int aoff0 = l32 * GP, aoff1 = (32 + l32) * GP;
@@ -143,6 +153,22 @@ __global__ __launch_bounds__(256) void band_kernel(const IgemmArgs a, int BP, in
     };
     if ((int)blockIdx.x < nbands) issue(blockIdx.x);
 
+    // operand fetch of one k-step: weight fragments of the MT row tiles, pixel fragments of the NTW tiles
+    auto fetch = [&](int ks, v4i (&fa)[MT], v4i (&fb)[NTW]) {
+        const int2 t = ktab[2 * ks + half];
+        const bool gv = t.x >= 0;
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+            const uint4 tw = gv ? wT[(m ? aoff1 : aoff0) + t.x] : *zero;
+            fa[m] = v4i{(int)tw.x, (int)tw.y, (int)tw.z, (int)tw.w};
+        }
+#pragma unroll
+        for (int i = 0; i < NTW; ++i) {
+            const uint4 tb = xW[pbase[i] + t.y];
+            fb[i] = v4i{(int)tb.x, (int)tb.y, (int)tb.z, (int)tb.w};
+        }
+    };
+
     for (int band = blockIdx.x; band < nbands; band += gridDim.x) {
         const int n = band / nbands_h;
         const int oh0 = (band - n * nbands_h) * BP;
@@ -153,52 +179,51 @@ __global__ __launch_bounds__(256) void band_kernel(const IgemmArgs a, int BP, in
         __syncthreads();
         if (band + (int)gridDim.x < nbands) issue(band + gridDim.x);
 
-        v16i acc[MT][BAND_NTW];
+        v16i acc[MT][NTW];
 #pragma unroll
         for (int m = 0; m < MT; ++m)
 #pragma unroll
-            for (int i = 0; i < BAND_NTW; ++i)
+            for (int i = 0; i < NTW; ++i)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[m][i][v] = 0;
 
-        for (int ks = 0; ks < nksteps; ++ks) {
-            const int2 t = ktab[2 * ks + half];
-            const bool gv = t.x >= 0;
-            v4i fa[MT];
-#pragma unroll
-            for (int m = 0; m < MT; ++m) {
-                const uint4 tw = gv ? wT[(m ? aoff1 : aoff0) + t.x] : *zero;
-                fa[m] = v4i{(int)tw.x, (int)tw.y, (int)tw.z, (int)tw.w};
-            }
-            v4i fb[BAND_NTW];
-#pragma unroll
-            for (int i = 0; i < BAND_NTW; ++i) {
-                const uint4 tb = xW[pbase[i] + t.y];
-                fb[i] = v4i{(int)tb.x, (int)tb.y, (int)tb.z, (int)tb.w};
-            }
+        // k-loop, two steps per iteration with the operands of the following step requested before
+        // the current step's MFMAs are issued (LDS latency hides behind the matrix pipeline)
+        v4i fa0[MT], fb0[NTW], fa1[MT], fb1[NTW];
+        fetch(0, fa0, fb0);
+        for (int ks = 0; ks < nksteps; ks += 2) {
+            fetch(ks + 1, fa1, fb1);             // ks + 1 <= nksteps: the spare table entry reads zeros
 #pragma unroll
             for (int m = 0; m < MT; ++m)
 #pragma unroll
-                for (int i = 0; i < BAND_NTW; ++i)
-                    acc[m][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[m], fb[i], acc[m][i], 0, 0, 0);
+                for (int i = 0; i < NTW; ++i)
+                    acc[m][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa0[m], fb0[i], acc[m][i], 0, 0, 0);
+            if (ks + 2 < nksteps) fetch(ks + 2, fa0, fb0);
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+#pragma unroll
+                for (int i = 0; i < NTW; ++i)
+                    acc[m][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa1[m], fb1[i], acc[m][i], 0, 0, 0);
         }
 
         // ---- epilogue: Eq.2, 32 consecutive pixels of one output row per store -------------------
-        const int bandoff = n * a.rows * OHW + oh0 * a.OW;   // output elements < 2^31 (checked on the host)
+        const size_t bandoff = (size_t)n * a.rows * OHW + (size_t)oh0 * a.OW;
+        float* __restrict__ outb = a.out + bandoff;
+        int32_t* __restrict__ accb = a.acc ? a.acc + bandoff : nullptr;
 #pragma unroll
-        for (int i = 0; i < BAND_NTW; ++i) {
+        for (int i = 0; i < NTW; ++i) {
             if (!pvalid[i] || oh0 + pl[i] >= a.OH) continue;
-            float* __restrict__ outp = a.out + bandoff + obase[i];
-            int32_t* __restrict__ accp = a.acc ? a.acc + bandoff + obase[i] : nullptr;
 #pragma unroll
             for (int m = 0; m < MT; ++m) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int rowu = m * 32 + 8 * (v >> 2) + (v & 3);   // + 4*half, already in obase
-                    if (rowu + 4 * half < a.rows) {
+                    const bool ok = UNI ? (m * 32 + 8 * (v >> 2) < a.rows) : (rowu + 4 * half < a.rows);
+                    if (ok) {
+                        const uint32_t o = obase[i] + (uint32_t)(rowu * OHW);
                         const int val = acc[m][i][v];
-                        outp[rowu * OHW] = __fmul_rn((float)val, scale);
-                        if (accp) accp[rowu * OHW] = val;
+                        outb[o] = __fmul_rn((float)val, scale);
+                        if (accb) accb[o] = val;
                     }
                 }
             }
@@ -211,12 +236,14 @@ bool launch_band(const IgemmArgs& a, hipStream_t st, hipError_t* err) {
     if (a.stride_h != 1 || a.stride_w != 1 || a.rows > 64 || a.OW > BAND_MAXPIX) return false;
     const int Cg16 = a.Ca >> 4;
     const int G = a.R * a.S * Cg16;
-    if ((G + 1) / 2 > BAND_MAXK) return false;
+    if (G > BAND_MAXG) return false;
     if ((size_t)a.N * a.rows * a.OH * a.OW > 0x7FFFFFFFull) return false;
-    // band height: as many output rows as fit 128 pixels (one 32-pixel tile per wave), or 256
-    // (two tiles per wave) when a single row is already wider than 128
-    int ntw = (a.OW > 128) ? 2 : 1;
-    int BP = (128 * ntw) / a.OW;
+    // band height: as many output rows as fit 128 pixels (one 32-pixel tile per wave; smaller bands
+    // balance better over the persistent blocks than 256-pixel ones); one row of up to 256 pixels
+    // (two tiles per wave) when a single row is wider than 128
+    int ntw = 1;
+    int BP = 128 / a.OW;
+    if (BP < 1) { ntw = 2; BP = 1; }
     if (BP > a.OH) BP = a.OH;
     const int WW = a.OW + a.S - 1;
     const int kw = (WW * Cg16 + 255) / 256;
@@ -224,18 +251,20 @@ bool launch_band(const IgemmArgs& a, hipStream_t st, hipError_t* err) {
     const int WH = BP + a.R - 1;
     if (WH * kw > BAND_STAGE) return false;
     const size_t lds = ((size_t)64 * odd_pitch(G) + (size_t)WH * WW * odd_pitch(Cg16) + 1) * 16 +
-                       (size_t)(G + 2) * sizeof(int2);
+                       (size_t)(G + 4) * sizeof(int2);
     if (lds > BAND_LDS_MAX) return false;
     const int nbands_h = (a.OH + BP - 1) / BP;
     const int nbands = a.N * nbands_h;
     const int grid = nbands < 512 ? nbands : 512;
     const int mt = a.rows > 32 ? 2 : 1;
-    const int variant = (a.dgrad ? 4 : 0) + (mt - 1) * 2 + (ntw - 1);
+    const int uni = (a.rows % 8 == 0) ? 1 : 0;
+    const int variant = (a.dgrad ? 8 : 0) + (mt - 1) * 4 + (ntw - 1) * 2 + uni;
     typedef void (*kern_t)(const IgemmArgs, int, int, int);
-    static const kern_t kerns[8] = {
-        band_kernel<false, 1, 1>, band_kernel<false, 1, 2>, band_kernel<false, 2, 1>, band_kernel<false, 2, 2>,
-        band_kernel<true, 1, 1>,  band_kernel<true, 1, 2>,  band_kernel<true, 2, 1>,  band_kernel<true, 2, 2>};
-    static bool attr_done[8] = {false, false, false, false, false, false, false, false};
+#define BK(D, M, N) band_kernel<D, M, N, false>, band_kernel<D, M, N, true>
+    static const kern_t kerns[16] = {BK(false, 1, 1), BK(false, 1, 2), BK(false, 2, 1), BK(false, 2, 2),
+                                     BK(true, 1, 1),  BK(true, 1, 2),  BK(true, 2, 1),  BK(true, 2, 2)};
+#undef BK
+    static bool attr_done[16] = {};
     if (!attr_done[variant]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kerns[variant]),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)BAND_LDS_MAX);
