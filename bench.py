@@ -41,10 +41,10 @@ def algorithmic(L, n_cand):
     return {
         "quantize_x": dict(bytes=4 * n_x + 4 * n_x + n_x, ops=0),          # absmax read + read + code write
         "quantize_w": dict(bytes=9 * n_w, ops=0),
-        # absmax pass (4 B/elem) + one sweep (4 B/elem).  Vector-ALU work of the sweep: 8 operations per
-        # element and candidate (scale, clamp, floor-convert, add draw, 0.75 byte gather, 1.75 int8
-        # dot-product accumulates) + 25 per element and 16-candidate chunk (draw, fixed point, digits)
-        "dsgc": dict(bytes=8 * n_y, ops=(8 * n_cand + 25 * ((n_cand + 15) // 16)) * n_y),
+        # absmax pass (4 B/elem) + one sweep (4 B/elem).  Vector-ALU work of the sweep: 4.5 operations per
+        # element and candidate (fused multiply-add, convert, 0.75 byte gather, 1.75 uint8 dot-product
+        # accumulates) + 25 per element and 16-candidate chunk (draw, fixed point, digit planes)
+        "dsgc": dict(bytes=8 * n_y, ops=(4.5 * n_cand + 25 * ((n_cand + 15) // 16)) * n_y),
         "quantize_dy": dict(bytes=5 * n_y, ops=0),
         "fwd": dict(bytes=n_x + n_w + 4 * n_y, ops=2 * macs),
         "bwd_data": dict(bytes=n_y + n_w + 4 * n_x, ops=2 * macs),

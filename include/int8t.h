@@ -118,10 +118,11 @@ size_t int8t_quantize_workspace_bytes(const int dims[4], int8t_kind kind);
  * Eq.1 / Eq.3.  Per element (fp32, each operation rounded once, no fused multiply-add):
  *     inv = 127 / c
  *     nearest:    q = rint(min(max(x * inv, -127), 127))                 (ties to even)
- *     stochastic: T = min(max(x * (inv * 2^24), -127 * 2^24), 127 * 2^24)
- *                 q = floor((floor(T) + u) / 2^24),  u = 24 uniform bits drawn from
- *                 (seed, logical index)  ==> q = floor(x/s) + 1 with probability frac(x/s),
- *                 resolved to 2^-24.
+ *     stochastic: m = min(127, floor((|x| * (inv * 2^24) + u) / 2^24)) in exact arithmetic,
+ *                 q = sign(x) * m,  u = 24 uniform bits drawn from (seed, logical index)
+ *                 ==> |q| = floor(|x|/s) + 1 with probability frac(|x|/s), resolved to 2^-24:
+ *                 the distribution of Eq.3 (rounding the magnitude and restoring the sign keeps
+ *                 the probabilities of floor and floor + 1 also for negative values).
  *   x_dev          fp32 tensor, logical order, dims[0]*dims[1]*dims[2]*dims[3] elements
  *   clip_dev       clip value c (1 float), or NULL: c = max|x| is computed first
  *   q_dev          out: int8 codes in the layout of `kind`, int8t_code_bytes() bytes

@@ -77,13 +77,16 @@ uint32_t orc_rng24(uint64_t seed, uint64_t index)
 /*         127) for s > 0, evaluated on the scaled value so that       */
 /*         |t| <= 127 holds exactly and codes never leave [-127,127];  */
 /*         q = rint(t), ties to even                                   */
-/*   mode 1: Eq.3 with 24-bit probabilities.  The scaled value is      */
-/*         carried with 24 fraction bits:                              */
-/*         T = clip(x * (inv*2^24), 127*2^24)   one fp32 product; the  */
-/*             factor inv*2^24 is an exact power-of-two scaling        */
-/*         X = floor(T)                                                */
-/*         q = floor((X + u) / 2^24),  u = rng24(seed, index)          */
-/*         => q = floor(t)+1 with probability floor(frac*2^24)/2^24    */
+/*   mode 1: Eq.3 with 24-bit probabilities, applied to the magnitude  */
+/*         and the sign restored (floor(t) and floor(t)+1 keep exactly */
+/*         the probabilities of Eq.3, also for negative t):            */
+/*         P = |x| * (inv*2^24)      exact real product (both factors  */
+/*             are fp32, so it fits a double; inv*2^24 is an exact     */
+/*             power-of-two scaling of inv)                            */
+/*         m = min(127, floor((P + u) / 2^24)),  u = rng24(seed,index) */
+/*         q = sign(x) * m                                             */
+/*         => |q| = floor(|t|)+1 with probability frac(|t|), resolved  */
+/*            to 2^-24; integer t are fixed points                     */
 /* c <= 0 (all-zero tensor): every code is 0.  NaN -> code 0.          */
 /* ------------------------------------------------------------------ */
 static inline float orc_inv_scale(float c)
@@ -101,16 +104,17 @@ static inline int orc_quantize_one(float x, float inv, int mode, uint64_t seed, 
         return (int)rintf(t); /* default rounding mode: nearest, ties to even */
     } else {
         float inv24 = inv * 16777216.0f;
-        float T = x * inv24;
-        if (T > 2130706432.0f) T = 2130706432.0f;   /* 127 * 2^24 */
-        if (T < -2130706432.0f) T = -2130706432.0f;
-        if (T != T) T = 0.0f;
-        int64_t X = (int64_t)floor((double)T);
-        int64_t u = (int64_t)orc_rng24(seed, index);
-        int64_t s = X + u;
-        /* floor division by 2^24 */
-        int64_t q = (s >= 0) ? (s >> 24) : -((-s + 16777215) >> 24);
-        return (int)q;
+        double P = (double)fabsf(x) * (double)inv24; /* exact: 24 x 24 significant bits */
+        int m;
+        if (P != P) {
+            m = 0; /* NaN input, or 0 * inf */
+        } else if (P >= 2147483648.0) {
+            m = 127;
+        } else {
+            int64_t S = (int64_t)floor(P) + (int64_t)orc_rng24(seed, index); /* floor(P + u), u integer */
+            m = (S >= 2147483648LL) ? 127 : (int)(S >> 24);
+        }
+        return (x < 0.0f) ? -m : m;
     }
 }
 

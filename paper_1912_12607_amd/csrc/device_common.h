@@ -70,39 +70,53 @@ __host__ __device__ __forceinline__ uint32_t seed_hi_term(uint64_t seed) {
 __device__ __forceinline__ float inv_scale_of(float c) { return (c > 0.0f) ? __fdiv_rn(127.0f, c) : 0.0f; }
 __device__ __forceinline__ float scale_of(float c) { return (c > 0.0f) ? __fdiv_rn(c, 127.0f) : 0.0f; }
 
-// floor(x) as int32 in one instruction (saturating).
-__device__ __forceinline__ int floor_to_int(float x) {
-    int r;
-    asm("v_cvt_flr_i32_f32 %0, %1" : "=v"(r) : "v"(x));
-    return r;
-}
-
 constexpr float kTwo24 = 16777216.0f;
-constexpr float kCodeMax24 = 2130706432.0f;   // 127 * 2^24
 
 // Eq.1 on the scaled value, nearest rounding: t = clip(x * inv, 127), |t| <= 127 exactly.
 __device__ __forceinline__ int round_nearest_code(float x, float inv) {
     const float t = fminf(fmaxf(__fmul_rn(x, inv), -127.0f), 127.0f);
     return (int)rintf(t);
 }
-// Eq.3 with 24-bit probabilities on the scaled value carried with 24 fraction bits:
-// T = clip(x * inv24, 127*2^24), inv24 = inv * 2^24;  q = floor((floor(T) + u) / 2^24).
-// floor(T) + u <= 2^31 - 1, so the 32-bit sum cannot overflow and q stays in [-127, 127].
-__device__ __forceinline__ int stochastic_sum(float x, float inv24, int u) {
-    const float T = fminf(fmaxf(__fmul_rn(x, inv24), -kCodeMax24), kCodeMax24);
-    return floor_to_int(T) + u;   // the code is this sum >> 24 (its signed top byte)
+
+// ---------------------------------------------------------------------------
+// Stochastic rounding (Eq.3) on the magnitude:  m = min(127, floor((|x| * inv24 + u) / 2^24)),
+// inv24 = inv * 2^24, u a 24-bit draw; the code is sign(x) * m.  floor((P + u)/2^24) of the EXACT
+// product P is obtained from one fp32 fused multiply-add evaluated with rounding toward minus
+// infinity: every multiple of 2^24 below 2^31 is representable, so rounding the sum down never
+// moves it across one, and the saturating float->int32 conversion caps the result at 2^31 - 1,
+// whose top byte is 127.  Two instructions per code, no clamp.
+// The wave's fp32 rounding mode is switched once; values that must have been computed in the
+// default mode are passed through the switch so that the compiler cannot move their
+// computation behind it.  fp64 arithmetic has its own mode bits and is not affected.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void fp32_round_down_mode(float& keep0, float& keep1) {
+    asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 2\n\ts_nop 3" : "+v"(keep0), "+v"(keep1));
+}
+// floor(|x| * inv24 + uf) as int32, saturated at 2^31 - 1 (needs the round-down mode).
+__device__ __forceinline__ int stoch_fixed(float x, float inv24, float uf) {
+    float t;
+    int X;
+    asm volatile("v_fma_f32 %0, |%1|, %2, %3" : "=v"(t) : "v"(x), "v"(inv24), "v"(uf));
+    asm("v_cvt_i32_f32 %0, %1" : "=v"(X) : "v"(t));
+    return X;
+}
+// same with the scale in a scalar register
+__device__ __forceinline__ int stoch_fixed_s(float x, float inv24_uniform, float uf) {
+    float t;
+    int X;
+    asm volatile("v_fma_f32 %0, |%1|, %2, %3" : "=v"(t) : "v"(x), "s"(inv24_uniform), "v"(uf));
+    asm("v_cvt_i32_f32 %0, %1" : "=v"(X) : "v"(t));
+    return X;
 }
 
-// One code, with NaN -> 0.
+// One code, with NaN -> 0.  STOCH needs fp32_round_down_mode() and inv = inv24.
 template <bool STOCH>
 __device__ __forceinline__ int quantize_one(float x, float inv, uint32_t seed_lo, uint32_t seed_hi_mul,
                                             uint32_t index) {
     if (STOCH) {
-        float T = __fmul_rn(x, __fmul_rn(inv, kTwo24));
-        T = (T != T) ? 0.0f : T;
-        T = fminf(fmaxf(T, -kCodeMax24), kCodeMax24);
-        const int u = (int)rng24(seed_lo, seed_hi_mul, index);
-        return (floor_to_int(T) + u) >> 24;
+        const float uf = (float)rng24(seed_lo, seed_hi_mul, index);   // exact: 24 bits
+        const int m = stoch_fixed(x, inv, uf) >> 24;                  // NaN converts to 0
+        return (x < 0.0f) ? -m : m;
     } else {
         float t = __fmul_rn(x, inv);
         t = (t != t) ? 0.0f : t;

@@ -9,25 +9,28 @@
 //
 // The sweep is bound by the plain vector ALUs, not by HBM (4 bytes per element against several
 // operations per element AND candidate), so the arithmetic is arranged to need few instructions:
-//   * the code of (element, candidate) is the signed top byte of floor(T) + u, T the scaled value
-//     with 24 fraction bits; four elements' codes are gathered into one dword by byte permutes;
-//   * g is turned, once per element, into a 46-bit fixed-point integer relative to max|g|
-//     (H * 2^23 + L, |H|,|L| <= 2^22), and both halves into three balanced signed byte digits;
-//   * A_j and B_j are then sums of int8 x int8 products, accumulated four at a time by the 4-way
-//     int8 dot-product instruction into int32 registers: 6 digit sums + 1 square sum per candidate.
+//   * codes are sign(g) * m with m the rounded magnitude, so g*q = |g|*m and q^2 = m^2: the whole
+//     search runs on magnitudes and never looks at a sign;
+//   * m is the top byte of floor(|g| * inv24 + u), one round-down fused multiply-add and one
+//     saturating convert (see device_common.h); four elements' bytes are gathered into one dword
+//     by byte permutes;
+//   * |g| is turned, once per element, into a 46-bit fixed-point integer relative to max|g|
+//     (H * 2^23 + L, H <= 2^22, L <= 2^23), and both halves into three byte digits;
+//   * A_j and B_j are then sums of uint8 x uint8 products, accumulated four at a time by the 4-way
+//     dot-product instruction into 32-bit registers: 6 digit sums + 1 square sum per candidate.
 // The integer sums are exact and order independent; the only error against an fp64 evaluation is
-// the fixed-point rounding of g, |delta| <= max|g| * 2^-45 per element, i.e. at most
+// the fixed-point rounding of |g|, |delta| <= max|g| * 2^-45 per element, i.e. at most
 // 2^-45 * sqrt(n) in d_j (Cauchy-Schwarz), far below the resolution the search needs.
 #include "device_common.h"
 #include "kernels.h"
 
 namespace int8t {
 
-constexpr int DSGC_JC = 16;       // candidates per block (7 int32 accumulators each)
+constexpr int DSGC_JC = 16;       // candidates per block (7 32-bit accumulators each)
 constexpr int DSGC_JPAD = 64;     // row pitch of the partial arrays (= INT8T_MAX_CANDIDATES)
 constexpr int DSGC_MAX_BLOCKS = 512;
 
-// bytes [a.b3, b.b3, c.b3, d.b3]: the signed top bytes of four 32-bit sums
+// bytes [a.b3, b.b3, c.b3, d.b3]: the top bytes of four 32-bit values
 __device__ __forceinline__ uint32_t top_bytes(int a, int b, int c, int d) {
     const uint32_t lo = __builtin_amdgcn_perm((uint32_t)b, (uint32_t)a, 0x0c0c0703u);   // a.b3 b.b3 0 0
     const uint32_t hi = __builtin_amdgcn_perm((uint32_t)d, (uint32_t)c, 0x07030c0cu);   // 0 0 c.b3 d.b3
@@ -40,13 +43,9 @@ __device__ __forceinline__ uint32_t low_bytes(int a, int b, int c, int d) {
     return lo | hi;
 }
 
-// Balanced signed byte digits of four integers |v| <= 2^22:  v = d0 + 256 d1 + 65536 d2.
-// Adding 0x808080 makes the three low bytes the digits plus 128; the xor turns each back into a
-// signed byte.  plane[b] packs digit b of the four values.
-__device__ __forceinline__ void digit_planes(const int v[4], uint32_t plane[3]) {
-    uint32_t y[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) y[e] = ((uint32_t)(v[e] + 0x00808080)) ^ 0x00808080u;
+// Byte digits of four integers 0 <= v < 2^24:  v = d0 + 256 d1 + 65536 d2.
+// plane[b] packs digit b of the four values.
+__device__ __forceinline__ void digit_planes(const uint32_t y[4], uint32_t plane[3]) {
     const uint32_t t0 = __builtin_amdgcn_perm(y[1], y[0], 0x05010400u);  // y0.b0 y1.b0 y0.b1 y1.b1
     const uint32_t t1 = __builtin_amdgcn_perm(y[1], y[0], 0x0c0c0602u);  // y0.b2 y1.b2 0 0
     const uint32_t t2 = __builtin_amdgcn_perm(y[3], y[2], 0x05010400u);
@@ -80,17 +79,22 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
         s_inv[j] = STOCH ? __fmul_rn(inv_scale_of(c), kTwo24) : inv_scale_of(c);
     }
     __syncthreads();
+    // fixed point: max|g| < 2^e, |g| * 2^(22-e) <= 2^22
+    int e2 = 0;
+    float mant = frexpf(M, &e2);
+    float e2f = (float)e2;
+    // From here on every fp32 operation of the stochastic sweep is either exact or the one
+    // round-down multiply-add; the candidates' scales above were computed (by other lanes, before
+    // the barrier) in the default mode.
+    if (STOCH) fp32_round_down_mode(mant, e2f);
+    const int shift = 22 - (int)e2f;
     float inv[JC];
 #pragma unroll
     for (int j = 0; j < JC; ++j)
         inv[j] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(s_inv[j])));
-    // fixed point: max|g| < 2^e, g * 2^(22-e) has magnitude <= 2^22
-    int e2 = 0;
-    (void)frexpf(M, &e2);
-    const int shift = 22 - e2;
 
-    int accA[JC][6];
-    int accB[JC];
+    unsigned accA[JC][6];
+    unsigned accB[JC];
 #pragma unroll
     for (int j = 0; j < JC; ++j) {
         accB[j] = 0;
@@ -99,22 +103,21 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
     }
     double G = 0.0;
 
-    auto group = [&](const float x[4], uint32_t index0, int nvalid) {
-        int u[4] = {0, 0, 0, 0};
-        int H[4], L[4];
+    auto group = [&](const float x[4], uint32_t index0) {
+        float uf[4] = {0.f, 0.f, 0.f, 0.f};
+        uint32_t H[4], L[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            if (STOCH) u[e] = (int)rng24(seed_lo, seed_hi_mul, index0 + e);
-            const float xs = ldexpf(x[e], shift);
-            const float h = rintf(xs);
-            H[e] = (int)h;
-            L[e] = (int)rintf(__fmul_rn(xs - h, 8388608.0f));   // remainder * 2^23, exact before rint
+            if (STOCH) uf[e] = (float)rng24(seed_lo, seed_hi_mul, index0 + e);   // exact: 24 bits
+            const float xs = ldexpf(fabsf(x[e]), shift);     // exact, 0 .. 2^22
+            const float h = floorf(xs);
+            H[e] = (uint32_t)h;
+            L[e] = (uint32_t)rintf((xs - h) * 8388608.0f);   // remainder * 2^23: exact before rint
             if (want_g) {
                 const double xd = (double)x[e];
                 G = fma(xd, xd, G);
             }
         }
-        (void)nvalid;
         uint32_t pH[3], pL[3];
         digit_planes(H, pH);
         digit_planes(L, pL);
@@ -122,17 +125,17 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
         for (int j = 0; j < JC; ++j) {
             uint32_t rp;
             if (STOCH) {
-                rp = top_bytes(stochastic_sum(x[0], inv[j], u[0]), stochastic_sum(x[1], inv[j], u[1]),
-                               stochastic_sum(x[2], inv[j], u[2]), stochastic_sum(x[3], inv[j], u[3]));
+                rp = top_bytes(stoch_fixed_s(x[0], inv[j], uf[0]), stoch_fixed_s(x[1], inv[j], uf[1]),
+                               stoch_fixed_s(x[2], inv[j], uf[2]), stoch_fixed_s(x[3], inv[j], uf[3]));
             } else {
-                rp = low_bytes(round_nearest_code(x[0], inv[j]), round_nearest_code(x[1], inv[j]),
-                               round_nearest_code(x[2], inv[j]), round_nearest_code(x[3], inv[j]));
+                rp = low_bytes(round_nearest_code(fabsf(x[0]), inv[j]), round_nearest_code(fabsf(x[1]), inv[j]),
+                               round_nearest_code(fabsf(x[2]), inv[j]), round_nearest_code(fabsf(x[3]), inv[j]));
             }
-            accB[j] = __builtin_amdgcn_sdot4((int)rp, (int)rp, accB[j], false);
+            accB[j] = __builtin_amdgcn_udot4(rp, rp, accB[j], false);
 #pragma unroll
             for (int b = 0; b < 3; ++b) {
-                accA[j][b] = __builtin_amdgcn_sdot4((int)pH[b], (int)rp, accA[j][b], false);
-                accA[j][3 + b] = __builtin_amdgcn_sdot4((int)pL[b], (int)rp, accA[j][3 + b], false);
+                accA[j][b] = __builtin_amdgcn_udot4(pH[b], rp, accA[j][b], false);
+                accA[j][3 + b] = __builtin_amdgcn_udot4(pL[b], rp, accA[j][3 + b], false);
             }
         }
     };
@@ -148,7 +151,7 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
             const size_t inext = i + stride;
             const float4 fn = (inext < n4) ? g4[inext] : make_float4(0.f, 0.f, 0.f, 0.f);
             const float vv[4] = {f.x, f.y, f.z, f.w};
-            group(vv, (uint32_t)(4 * i), 4);
+            group(vv, (uint32_t)(4 * i));
             f = fn;
             i = inext;
         }
@@ -157,11 +160,11 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
         // ragged tail: missing elements are zeros (zero contributes nothing to A, B or G)
         float vv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
         for (int e = 0; e < (int)(n & 3); ++e) vv[e] = g[(n4 << 2) + e];
-        group(vv, (uint32_t)(n4 << 2), (int)(n & 3));
+        group(vv, (uint32_t)(n4 << 2));
     }
 
     // per-thread totals: A = (2^23 * sum_b 256^b aH_b + sum_b 256^b aL_b) * 2^(e-45); the digit
-    // sums are exact integers below 2^48 in double, the last additions round like any fp64 sum
+    // sums are exact integers below 2^49 in double, the last additions round like any fp64 sum
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
     G = wave_sum(G);
 #pragma unroll
@@ -170,7 +173,7 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
         const double dL = (double)accA[j][3] + 256.0 * (double)accA[j][4] + 65536.0 * (double)accA[j][5];
         const double at = ldexp(dH * 8388608.0 + dL, e2 - 45);
         const double asum = wave_sum(at);
-        const unsigned long long b = wave_sum((unsigned long long)(unsigned)accB[j]);
+        const unsigned long long b = wave_sum((unsigned long long)accB[j]);
         if (lane == 0) {
             s_red[w][j] = asum;
             s_redB[w][j] = b;

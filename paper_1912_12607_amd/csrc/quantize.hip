@@ -115,8 +115,13 @@ __global__ __launch_bounds__(256) void quantize_act_kernel(
     }
 
     const float cval = resolve_clip(clip, absmax_part, nparts, lds4);
-    const float inv = inv_scale_of(cval);
-    if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) *scale_out = scale_of(cval);
+    float inv = inv_scale_of(cval);
+    float sc = scale_of(cval);
+    if (STOCH) {
+        inv = __fmul_rn(inv, kTwo24);        // the scaled value carries 24 fraction bits
+        fp32_round_down_mode(inv, sc);
+    }
+    if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) *scale_out = sc;
 
     double A = 0.0, G = 0.0;
     unsigned long long B = 0;
@@ -187,8 +192,13 @@ __global__ __launch_bounds__(256) void quantize_planar_kernel(
     int8_t* __restrict__ q, float* __restrict__ scale_out, DevPartial* __restrict__ devpart) {
     __shared__ float lds4[4];
     const float cval = resolve_clip(clip, absmax_part, nparts, lds4);
-    const float inv = inv_scale_of(cval);
-    if (blockIdx.x == 0 && threadIdx.x == 0) *scale_out = scale_of(cval);
+    float inv = inv_scale_of(cval);
+    float sc = scale_of(cval);
+    if (STOCH) {
+        inv = __fmul_rn(inv, kTwo24);        // the scaled value carries 24 fraction bits
+        fp32_round_down_mode(inv, sc);
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) *scale_out = sc;
 
     double A = 0.0, G = 0.0;
     unsigned long long B = 0;
@@ -261,8 +271,13 @@ __global__ __launch_bounds__(256) void quantize_wgt_kernel(
     DevPartial* __restrict__ devpart) {
     __shared__ float lds4[4];
     const float cval = resolve_clip(clip, absmax_part, nparts, lds4);
-    const float inv = inv_scale_of(cval);
-    if (blockIdx.x == 0 && threadIdx.x == 0) *scale_out = scale_of(cval);
+    float inv = inv_scale_of(cval);
+    float sc = scale_of(cval);
+    if (STOCH) {
+        inv = __fmul_rn(inv, kTwo24);        // the scaled value carries 24 fraction bits
+        fp32_round_down_mode(inv, sc);
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) *scale_out = sc;
 
     const int RS = R * S;
     const size_t nd1 = (size_t)K * RS * (Cp / 4);
