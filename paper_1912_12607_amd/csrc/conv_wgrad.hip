@@ -5,12 +5,12 @@
 // The reduction runs over images and output pixels, but the channels-last code tensors keep the
 // channel innermost, while the MFMA wants 16 consecutive reduction bytes per lane.  Any order of
 // the reduction index is as good as any other, so the 16 bytes of a lane are made 16 different
-// IMAGES at one pixel: the loader fetches, for one pixel and four channels, one dword from each of
-// 16 images, swaps the 4x4 byte blocks with byte permutes -- the "4x4 8-bit integer block
-// transpose" of the paper's Suppl. "INT8 Convolution" -- and stores [pixel][channel][16 images]
-// granules to LDS.  A filter tap is then just a different PIXEL of the staged input window, i.e. a
-// different, always 16-byte aligned LDS row: no im2col buffer, no unaligned operand reads, zero
-// padding is written once by the loader.
+// IMAGES at one pixel: a loader task fetches, for one pixel, the 16-channel granule of each of 16
+// images (sixteen 16-byte loads), transposes the 16x16 byte block in registers with byte permutes
+// -- built from the "4x4 8-bit integer block transpose" of the paper's Suppl. "INT8 Convolution"
+// -- and stores [pixel][channel][16 images] granules to LDS.  A filter tap is then just a different
+// PIXEL of the staged input window, i.e. a different, always 16-byte aligned LDS row: no im2col
+// buffer, no unaligned operand reads, zero padding is written once by the loader.
 //
 // One block owns an output tile of 64 filters x CT channels x TB taps and a share of the
 // reduction (split-K over image groups and output-pixel tiles); it writes an int32 partial tile.
@@ -26,9 +26,6 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int W2_BM = 64;              // filters per block
 constexpr int W2_LDS_BUDGET = 64 * 1024;
-constexpr int W2_TARGET_BLOCKS = 512;  // about two blocks per compute unit
-constexpr int W2_TPT = 3;              // loader tasks per thread and reduction chunk (prefetched in registers)
-
 // 4x4 byte transpose: in d[i] = 4 channels of image i; out o[c] = channel c of images 0..3.
 __device__ __forceinline__ void transpose4x4(const uint32_t d[4], uint32_t o[4]) {
     // v_perm_b32 picks 4 bytes out of the 8 bytes {hi, lo}; selector byte 0-3 = lo, 4-7 = hi
@@ -42,19 +39,18 @@ __device__ __forceinline__ void transpose4x4(const uint32_t d[4], uint32_t o[4])
     o[3] = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
 }
 
-// Position of channel c inside a [channel][16 bytes] LDS row block.  MFMA operand reads walk 32
-// consecutive channels, the loader's stores walk channels with a stride of four; the xor keeps
-// both spread over all bank groups.
-__device__ __forceinline__ int ch_slot(int c) { return c ^ ((c >> 3) & 3); }
-
-// 16 images x 4 channels -> four [channel][16 images] granules.
-__device__ __forceinline__ void transpose_store(const uint32_t d[16], uint4* __restrict__ row, int c4) {
-    uint32_t o[4][4];
-#pragma unroll
-    for (int g = 0; g < 4; ++g) transpose4x4(d + 4 * g, o[g]);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) row[ch_slot(c4 + j)] = make_uint4(o[0][j], o[1][j], o[2][j], o[3][j]);
+// Granule index of channel c at pixel `pix` in a [pixel][2^LOGW channels] LDS tile.  Inside each
+// aligned group of 16 channels the position is xor-ed with a number that differs between the 16
+// consecutive loader lanes (4 or 16 channel granules per pixel, consecutive pixels), so the
+// loader's stores (same channel-in-granule from every lane) and the MFMA operand reads (32
+// consecutive channels of one pixel) both spread over all banks.
+template <int LOGW>
+__device__ __forceinline__ int swz(int pix, int c) {
+    return (pix << LOGW) + (c & ~15) + ((c & 15) ^ (((c >> 4) + 4 * pix) & 15));
 }
+
+// Component q of a 16-byte register granule.
+__device__ __forceinline__ uint32_t comp(const uint4& v, int q) { return q == 0 ? v.x : q == 1 ? v.y : q == 2 ? v.z : v.w; }
 
 // Extent of the taps [t0, t0+nt) of an R x S filter (taps numbered r*S + s).
 __host__ __device__ inline void tap_extent(int t0, int nt, int S, int* rmin, int* rmax, int* smin, int* smax) {
@@ -73,7 +69,9 @@ constexpr int W2_MAXSTEPS = 8;         // MFMA steps per chunk: at most 16 tile 
 
 template <int TB, int CS>
 __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
-    constexpr int CT = 64 * CS;   // channels per block
+    constexpr int CT = 64 * CS;                   // channels per block
+    constexpr int LOGCT = (CS == 1) ? 6 : 8;
+    static_assert(CS == 1 || CS == 4, "channel tile is 64 or 256");
     extern __shared__ __attribute__((aligned(16))) uint4 lds[];
     uint4* __restrict__ xT = lds;                   // [window pixel][CT channels] granules
     uint4* __restrict__ dyT = lds + a.xt_slots;     // [tile pixel][64 filters] granules, then one zero granule
@@ -94,11 +92,11 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
     tap_extent(t0, nt, a.S, &rmin, &rmax, &smin, &smax);
     const int WH = (a.BP - 1) * a.stride_h + (rmax - rmin) + 1;
     const int WW = (a.BQ - 1) * a.stride_w + (smax - smin) + 1;
-    int toff[TB];   // uniform: LDS offset of each tap inside the staged window
+    int tpix[TB];   // uniform: window pixel offset of each tap
 #pragma unroll
     for (int j = 0; j < TB; ++j) {
         const int t = t0 + ((j < nt) ? j : 0);
-        toff[j] = __builtin_amdgcn_readfirstlane(((t / a.S - rmin) * WW + (t % a.S - smin)) * CT);
+        tpix[j] = __builtin_amdgcn_readfirstlane((t / a.S - rmin) * WW + (t % a.S - smin));
     }
     const int units = a.BP * a.BQ;
     const int nsteps = (units + 1) >> 1;
@@ -107,16 +105,17 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
 
     // LDS operand positions of every MFMA step; they depend on the tile geometry only.  A step
     // feeds two tile pixels, one per half-wave, each with 16 images.
-    int a_off[W2_MAXSTEPS], x_off[W2_MAXSTEPS];
+    int a_off[W2_MAXSTEPS], x_pix[W2_MAXSTEPS];
 #pragma unroll
     for (int s = 0; s < W2_MAXSTEPS; ++s) {
         const int u = 2 * s + half;
         const bool uv = u < units;
         const int uu = uv ? u : 0;
         const int pl = uu / a.BQ, ql = uu - pl * a.BQ;
-        a_off[s] = uv ? (uu * W2_BM + ch_slot(mt * 32 + l32)) : zero_slot;
-        x_off[s] = (pl * a.stride_h * WW + ql * a.stride_w) * CT + ch * CS * 32 + ch_slot(l32);
+        a_off[s] = uv ? swz<6>(uu, mt * 32 + l32) : zero_slot;
+        x_pix[s] = pl * a.stride_h * WW + ql * a.stride_w;
     }
+    const int xc0 = ch * CS * 32 + l32;             // this lane's channel inside the block's tile (slab 0)
 
     v16i acc[TB][CS];
 #pragma unroll
@@ -126,44 +125,46 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[j][i][v] = 0;
 
-    const int c_begin = (int)(((long long)a.chunks * blockIdx.y) / gridDim.y);
-    const int c_end = (int)(((long long)a.chunks * (blockIdx.y + 1)) / gridDim.y);
+    const int c_begin = (int)(((uint32_t)a.chunks * blockIdx.y) / gridDim.y);   // chunks * splits < 2^31 (host)
+    const int c_end = (int)(((uint32_t)a.chunks * (blockIdx.y + 1)) / gridDim.y);
     const int tiles_per_group = a.ntp * a.ntq;
-    const int ntask_x = WH * WW * (CT / 4);     // input window: (window pixel, channel quad)
-    const int ntask = ntask_x + units * 16;     // + gradient tile: (tile pixel, filter quad)
+    const int ntask_x = WH * WW * (CT / 16);    // input window: (window pixel, 16-channel granule)
+    const int ntask = ntask_x + units * 4;      // + gradient tile: (tile pixel, 16-filter granule)
     const uint32_t ximg = (uint32_t)a.H * a.W * a.Cp;     // image strides in bytes
     const uint32_t yimg = (uint32_t)a.P * a.Q * a.Kp;
 
-    // Loader tasks of this thread (task = tid + 256*i): everything that does not depend on the
-    // chunk is worked out once.  A task fetches one dword from each of 16 images.
-    int t_kind[W2_TPT], t_c[W2_TPT], t_a[W2_TPT], t_b[W2_TPT], t_dst[W2_TPT];   // kind: 0 input, 1 gradient, 2 none
-#pragma unroll
-    for (int i = 0; i < W2_TPT; ++i) {
-        const int task = tid + 256 * i;
-        t_kind[i] = 2;
-        t_a[i] = t_b[i] = t_c[i] = t_dst[i] = 0;
+    // The loader task of this thread; tasks are dealt evenly to the four waves.  Everything that
+    // does not depend on the chunk is worked out once.  A task fetches 16 bytes from each of 16
+    // images.  kind: 0 input, 1 gradient, 2 none
+    int t_kind = 2, t_a = 0, t_b = 0, t_c = 0, t_pix = 0, t_g = 0;
+    {
+        const int per_wave = (ntask + 3) >> 2;
+        const int task = (lane < per_wave) ? wave * per_wave + lane : ntask;
         if (task < ntask_x) {
-            const int cq = task % (CT / 4), wp = task / (CT / 4);
-            t_kind[i] = 0;
-            t_a[i] = wp / WW;                 // window row
-            t_b[i] = wp - t_a[i] * WW;        // window column
-            t_c[i] = ct * CT + 4 * cq;        // >= Cp: nothing to fetch, zeros are staged
-            t_dst[i] = wp * CT + 4 * cq;      // granule index in xT (before the channel swizzle)
+            t_g = task % (CT / 16);
+            t_pix = task / (CT / 16);
+            t_kind = 0;
+            t_a = t_pix / WW;                 // window row
+            t_b = t_pix - t_a * WW;           // window column
+            t_c = ct * CT + 16 * t_g;         // >= Cp: nothing to fetch, zeros are staged
         } else if (task < ntask) {
-            const int kq = (task - ntask_x) & 15, u = (task - ntask_x) >> 4;
-            t_kind[i] = 1;
-            t_a[i] = u / a.BQ;                // tile row
-            t_b[i] = u - t_a[i] * a.BQ;       // tile column
-            t_c[i] = kt * W2_BM + 4 * kq;
-            t_dst[i] = u * W2_BM + 4 * kq;
+            t_g = (task - ntask_x) & 3;
+            t_pix = (task - ntask_x) >> 2;
+            t_kind = 1;
+            t_a = t_pix / a.BQ;               // tile row
+            t_b = t_pix - t_a * a.BQ;         // tile column
+            t_c = kt * W2_BM + 16 * t_g;
         }
     }
+    // first granule of the task's 16 in LDS and the xor of swz() for them
+    uint4* __restrict__ const t_row = (t_kind == 1) ? (dyT + (t_pix << 6) + 16 * t_g) : (xT + (t_pix << LOGCT) + 16 * t_g);
+    const int t_xor = (t_g + 4 * t_pix) & 15;
 
     // Prefetch registers.  Loads are unconditional: a task with nothing to fetch (padding, ragged
     // tile edge, channel beyond the tensor) reads offset 0 of its tensor and is zeroed when it is
     // staged; images beyond N re-read the group's last image and are zeroed the same way.
-    uint32_t pre[W2_TPT][16];
-    bool pre_ok[W2_TPT];
+    uint4 pre[16];
+    bool pre_ok = false;
     int pre_nimg = 16;
     auto issue = [&](int chunk) {
         const int ng = chunk / tiles_per_group;
@@ -174,42 +175,47 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
         const int n0 = ng * 16;
         const int nimg = (a.N - n0 < 16) ? (a.N - n0) : 16;
         pre_nimg = nimg;
+        if (t_kind == 2) return;
+        const bool isx = t_kind == 0;
+        const int yy = (isx ? ih0 : p0) + t_a, xx = (isx ? iw0 : q0) + t_b;
+        const int hh = isx ? a.H : a.P, ww = isx ? a.W : a.Q, cc = isx ? a.Cp : a.Kp;
+        const bool ok = (unsigned)yy < (unsigned)hh && (unsigned)xx < (unsigned)ww && t_c < cc;
+        pre_ok = ok;
+        const uint32_t stride = isx ? ximg : yimg;
+        const int8_t* base = isx ? a.x : a.dy;
+        uint32_t off = ok ? (((uint32_t)n0 * hh + yy) * ww + xx) * cc + t_c : (uint32_t)n0 * stride;
 #pragma unroll
-        for (int i = 0; i < W2_TPT; ++i) {
-            if (t_kind[i] == 2) continue;
-            const bool isx = t_kind[i] == 0;
-            const int yy = (isx ? ih0 : p0) + t_a[i], xx = (isx ? iw0 : q0) + t_b[i];
-            const int hh = isx ? a.H : a.P, ww = isx ? a.W : a.Q, cc = isx ? a.Cp : a.Kp;
-            const bool ok = (unsigned)yy < (unsigned)hh && (unsigned)xx < (unsigned)ww && t_c[i] < cc;
-            pre_ok[i] = ok;
-            const uint32_t stride = isx ? ximg : yimg;
-            const int8_t* base = isx ? a.x : a.dy;
-            uint32_t off = ok ? (((uint32_t)n0 * hh + yy) * ww + xx) * cc + t_c[i] : (uint32_t)n0 * stride;
-#pragma unroll
-            for (int im = 0; im < 16; ++im) {
-                pre[i][im] = *reinterpret_cast<const uint32_t*>(base + off);
-                if (im + 1 < nimg) off += stride;
-            }
+        for (int im = 0; im < 16; ++im) {
+            pre[im] = *reinterpret_cast<const uint4*>(base + off);
+            if (im + 1 < nimg) off += stride;
         }
     };
 
     if (c_begin < c_end) issue(c_begin);
     for (int chunk = c_begin; chunk < c_end; ++chunk) {
         __syncthreads();   // the previous chunk's MFMA reads are done
+        if (t_kind != 2) {
+            if (!pre_ok) {
 #pragma unroll
-        for (int i = 0; i < W2_TPT; ++i) {
-            if (t_kind[i] == 2) continue;
-            if (!pre_ok[i]) {
-#pragma unroll
-                for (int im = 0; im < 16; ++im) pre[i][im] = 0u;
+                for (int im = 0; im < 16; ++im) pre[im] = make_uint4(0, 0, 0, 0);
             } else if (pre_nimg < 16) {
 #pragma unroll
                 for (int im = 0; im < 16; ++im)
-                    if (im >= pre_nimg) pre[i][im] = 0u;
+                    if (im >= pre_nimg) pre[im] = make_uint4(0, 0, 0, 0);
             }
-            // t_dst = 64-granule row block + channel offset; the swizzle acts on the low bits only
-            uint4* __restrict__ row = ((t_kind[i] == 1) ? dyT : xT) + (t_dst[i] & ~63);
-            transpose_store(pre[i], row, t_dst[i] & 63);
+            // 16 images x 16 channels -> sixteen [channel][16 images] granules, four channels at a time
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                uint32_t o[4][4];
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const uint32_t d[4] = {comp(pre[4 * g], q), comp(pre[4 * g + 1], q), comp(pre[4 * g + 2], q),
+                                           comp(pre[4 * g + 3], q)};
+                    transpose4x4(d, o[g]);
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) t_row[(4 * q + j) ^ t_xor] = make_uint4(o[0][j], o[1][j], o[2][j], o[3][j]);
+            }
         }
         __syncthreads();
         if (chunk + 1 < c_end) issue(chunk + 1);   // in flight while this chunk's MFMAs run
@@ -221,9 +227,10 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
                 const v4i fa = v4i{(int)ta.x, (int)ta.y, (int)ta.z, (int)ta.w};
 #pragma unroll
                 for (int j = 0; j < TB; ++j) {   // TB divides R*S: every tap of the group exists
+                    const int pix = x_pix[s] + tpix[j];
 #pragma unroll
                     for (int i = 0; i < CS; ++i) {
-                        const uint4 tb = xT[x_off[s] + toff[j] + i * 32];
+                        const uint4 tb = xT[swz<LOGCT>(pix, xc0 + 32 * i)];
                         const v4i fb = v4i{(int)tb.x, (int)tb.y, (int)tb.z, (int)tb.w};
                         acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa, fb, acc[j][i], 0, 0, 0);
                     }
@@ -252,24 +259,44 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
     }
 }
 
-// Sum the split partials, apply Eq.2 and scatter [k][(r,s,c)] -> K,C,R,S.
+// Sum the split partials, apply Eq.2 and scatter [k][(r,s,c)] -> K,C,R,S.  A block owns 64
+// consecutive partial columns; its 256 threads are 16 split lanes x 16 column quads, every thread
+// adds up the splits z = lane, lane+16, ... with independent 16-byte loads, and the 16 lanes are
+// combined through LDS.  (K*R*S*Cp is a multiple of 16, so a quad never straddles the end.)
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const WgradArgs a) {
+    __shared__ int4 sred[16][17];
     const int ncolsp = a.R * a.S * a.Cp;
     const size_t total = (size_t)a.K * ncolsp;
-    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const int zl = threadIdx.x >> 4, quad = threadIdx.x & 15;
+    const size_t t4 = (size_t)blockIdx.x * 64 + 4 * quad;
+    int4 s4 = make_int4(0, 0, 0, 0);
+    if (t4 < total) {
+        const int32_t* __restrict__ p = a.partial + t4;
+        int z = zl;
+        for (; z + 48 < a.splits; z += 64) {
+            int4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const int4*>(p + (size_t)(z + 16 * u) * total);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { s4.x += v[u].x; s4.y += v[u].y; s4.z += v[u].z; s4.w += v[u].w; }
+        }
+        for (; z < a.splits; z += 16) {
+            const int4 v = *reinterpret_cast<const int4*>(p + (size_t)z * total);
+            s4.x += v.x; s4.y += v.y; s4.z += v.z; s4.w += v.w;
+        }
+    }
+    sred[zl][quad] = s4;
+    __syncthreads();
+    if (threadIdx.x >= 64) return;
+    const size_t t = (size_t)blockIdx.x * 64 + threadIdx.x;
     if (t >= total) return;
+    int sum = 0;
+#pragma unroll
+    for (int l = 0; l < 16; ++l) sum += reinterpret_cast<const int*>(&sred[l][threadIdx.x >> 2])[threadIdx.x & 3];
     const int k = (int)(t / ncolsp);
     const int col = (int)(t - (size_t)k * ncolsp);
     const int rs = col / a.Cp, c = col - rs * a.Cp;
     if (c >= a.C) return;
-    int s4[4] = {0, 0, 0, 0};
-    int z = 0;
-    for (; z + 3 < a.splits; z += 4) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) s4[u] += a.partial[(size_t)(z + u) * total + t];
-    }
-    for (; z < a.splits; ++z) s4[0] += a.partial[(size_t)z * total + t];
-    const int sum = (s4[0] + s4[1]) + (s4[2] + s4[3]);
     const size_t o = ((size_t)k * a.C + c) * (a.R * a.S) + rs;
     a.dw[o] = __fmul_rn((float)sum, __fmul_rn(a.sa[0], a.sb[0]));
     if (a.acc) a.acc[o] = sum;
@@ -310,8 +337,8 @@ void wgrad_plan(WgradArgs* a) {
         }
         a->xt_slots = maxwin * CT;
         a->lds_bytes = (size_t)(a->xt_slots + BP * BQ * W2_BM + 1) * 16;
-        const int ntask = maxwin * (CT / 4) + BP * BQ * 16;
-        if ((a->lds_bytes <= (size_t)W2_LDS_BUDGET && ntask <= 256 * W2_TPT && BP * BQ <= 2 * W2_MAXSTEPS) ||
+        const int ntask = maxwin * (CT / 16) + BP * BQ * 4;   // one loader task per thread
+        if ((a->lds_bytes <= (size_t)W2_LDS_BUDGET && ntask <= 256 && BP * BQ <= 2 * W2_MAXSTEPS) ||
             (BP == 1 && BQ == 1))
             break;
         if (BP > 1) BP = (BP + 1) / 2;
@@ -326,9 +353,25 @@ void wgrad_plan(WgradArgs* a) {
     a->ngrp = (a->N + 15) / 16;
     a->chunks = a->ngrp * np * nq;
     const int out_tiles = a->ktiles * a->ctiles * a->tapgroups;
-    int splits = (W2_TARGET_BLOCKS + out_tiles - 1) / out_tiles;
-    if (splits > a->chunks) splits = a->chunks;
-    if (splits < 1) splits = 1;
+    // Split count: the one with the smallest estimated time.  Blocks run in rounds of `slots`
+    // (blocks resident on the chip: registers allow two per compute unit for the narrow tiles, one
+    // for the wide ones); a block pays a prologue plus its chunks; every split adds one write and
+    // one read of the int32 partial tile set.  The constants are rough measurements in microseconds.
+    const int per_cu_regs = (a->TB == 7 || a->CS == 4) ? 1 : 2;
+    int per_cu_lds = (int)((160 * 1024) / a->lds_bytes);
+    if (per_cu_lds < 1) per_cu_lds = 1;
+    const int slots = 256 * (per_cu_regs < per_cu_lds ? per_cu_regs : per_cu_lds);
+    const double t_chunk = 1.2 * per_cu_regs + 0.014 * (BP * BQ + 1) / 2 * a->TB * a->CS;
+    const double t_partial = (double)a->K * RS * a->Cp * 8.0 / 4.0e6;
+    int splits = 1;
+    double best = 1e30;
+    for (int sp = 1; sp <= a->chunks && sp <= 4096; ++sp) {
+        const long long blocks = (long long)out_tiles * sp;
+        const double rounds = (double)((blocks + slots - 1) / slots);
+        const double t = rounds * (3.0 + ((a->chunks + sp - 1) / sp) * t_chunk) + sp * t_partial;
+        if (t < best) { best = t; splits = sp; }
+        if (blocks > 8LL * slots || (long long)a->chunks * (sp + 2) >= (1LL << 31)) break;
+    }
     a->splits = splits;
 }
 
@@ -345,7 +388,7 @@ hipError_t launch_wgrad(const WgradArgs& a, hipStream_t st) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const size_t total = (size_t)a.K * a.R * a.S * a.Cp;
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((total + 63) / 64)), dim3(256), 0, st, a);
     return hipGetLastError();
 }
 
