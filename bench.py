@@ -29,26 +29,33 @@ INT8_MFMA_PEAK_TOPS = 5000.0
 # plain (unpacked) vector ALU: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, one operation per lane per issue
 VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 
-CALLS = ["quantize_x", "quantize_w", "dsgc", "quantize_dy", "fwd", "bwd_data", "bwd_weight"]
-
+# HBM bytes per launch from rocprofv3 counter runs (FETCH_SIZE + WRITE_SIZE, each scaled by what the same
+# counter reads for a copy kernel of known size); keyed by (config, layer, kernel).  See profiles/.
+TRAFFIC = {(1, 0, "dsgc_sweep_kernel"): 56887 * 1024}
 
 def algorithmic(L, n_cand):
-    """Algorithmic HBM bytes and arithmetic per call (what the method must move / compute)."""
+    """Algorithmic HBM bytes and arithmetic of one step, per kernel name (what the method must move
+    and compute, summed over that kernel's launches in the step; scratch traffic is not counted)."""
     n_x = L.N * L.C * L.H * L.W
     n_w = L.K * (L.C // L.groups) * L.R * L.S
     n_y = L.N * L.K * L.P * L.Q
     macs = L.macs
+    conv2 = dict(bytes=(n_x + n_w + 4 * n_y) + (n_y + n_w + 4 * n_x), ops=4 * macs)   # forward + backward-data
+    wg = dict(bytes=n_x + n_y + 4 * n_w, ops=2 * macs)
     return {
-        "quantize_x": dict(bytes=4 * n_x + 4 * n_x + n_x, ops=0),          # absmax read + read + code write
-        "quantize_w": dict(bytes=9 * n_w, ops=0),
-        # absmax pass (4 B/elem) + one sweep (4 B/elem).  Vector-ALU work of the sweep: 4.5 operations per
-        # element and candidate (fused multiply-add, convert, 0.75 byte gather, 1.75 uint8 dot-product
-        # accumulates) + 25 per element and 16-candidate chunk (draw, fixed point, digit planes)
-        "dsgc": dict(bytes=8 * n_y, ops=(4.5 * n_cand + 25 * ((n_cand + 15) // 16)) * n_y),
-        "quantize_dy": dict(bytes=5 * n_y, ops=0),
-        "fwd": dict(bytes=n_x + n_w + 4 * n_y, ops=2 * macs),
-        "bwd_data": dict(bytes=n_y + n_w + 4 * n_x, ops=2 * macs),
-        "bwd_weight": dict(bytes=n_x + n_y + 4 * n_w, ops=2 * macs),
+        "absmax_kernel": dict(bytes=4 * (n_x + n_w + n_y), ops=0),               # a, W, g_z: one read each
+        "quantize_act_kernel": dict(bytes=5 * (n_x + n_y), ops=0),                # fp32 read + code write, a and g_z
+        "quantize_planar_kernel": dict(bytes=5 * (n_x + n_y), ops=0),
+        "quantize_wgt_kernel": dict(bytes=6 * n_w, ops=0),                        # fp32 read + two code copies
+        "deviation_finish_kernel": dict(bytes=0, ops=0),
+        # one read of g_z.  Vector-ALU work of the sweep: 4.5 operations per element and candidate (fused
+        # multiply-add, convert, 0.75 byte gather, 1.75 uint8 dot-product accumulates) + 25 per element
+        # and 16-candidate chunk (draw, fixed point, digit planes)
+        "dsgc_sweep_kernel": dict(bytes=4 * n_y, ops=(4.5 * n_cand + 25 * ((n_cand + 15) // 16)) * n_y),
+        "dsgc_finish_kernel": dict(bytes=0, ops=0),
+        "igemm_kernel": conv2, "band_kernel": conv2, "dw_conv_kernel": conv2,
+        "wgrad_kernel": wg, "dw_wgrad_kernel": wg,
+        "wgrad_reduce_kernel": dict(bytes=4 * n_w, ops=0), "dw_wgrad_reduce_kernel": dict(bytes=4 * n_w, ops=0),
     }
 
 
@@ -87,6 +94,9 @@ def main():
     ap.add_argument("--layer", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-images", type=int, default=64)
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="after the steps, run a plain elementwise copy of this many MiB three times "
+                         "(reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--all-layers", action="store_true", help="also print a per-layer table for every config (stderr)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -98,6 +108,7 @@ def main():
     import numpy as np
     import torch
 
+    from paper_1912_12607_amd import binding as B
     from paper_1912_12607_amd import inputs
     from paper_1912_12607_amd.step import LayerStep
 
@@ -106,6 +117,9 @@ def main():
     ratios = inputs.default_ratios(n_cand)
 
     def bench_layer(cfg, li, steps, warmup):
+        """Returns layer, host tensors, seconds per step, {kernel: (launches per step, us per launch)} of
+        an untimed pass with every kernel bracketed by events, and the dominant kernel's
+        (name, us per launch) measured by events inside the timed region itself."""
         L, x, w, dy = inputs.make_layer_inputs(cfg, li)
         st = LayerStep(L, n_cand=n_cand, keep_acc=False)
         st.upload(x, w, dy, ratios)
@@ -113,53 +127,43 @@ def main():
         for i in range(warmup):
             st.run(seed=i)
         torch.cuda.synchronize()
-        # per-call HIP events on the launch stream (torch's current stream is the one the binding uses)
-        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(CALLS) + 1)] for _ in range(steps)]
+        # pass 1 (untimed): HIP events around every kernel launch, on the launch stream, inside the library
+        nprof = max(3, min(10, steps))
+        B.int8t_profile_start(None)
+        for i in range(nprof):
+            st.run(seed=i)
+        torch.cuda.synchronize()
+        prof = B.int8t_profile_stop()
+        per_kernel = {k: (n / nprof, ms * 1e3 / n) for k, (n, ms) in prof.items()}
+        dom = max(prof, key=lambda k: prof[k][1])
+        # pass 2 (the timed region): only the dominant kernel carries events
+        B.int8t_profile_start(dom)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(steps):
-            e = ev[i]
-            e[0].record()
-            st.quantize_x(); e[1].record()
-            st.quantize_w(); e[2].record()
-            st.dsgc(i); e[3].record()
-            st.quantize_dy(i); e[4].record()
-            st.fwd(); e[5].record()
-            st.bwd_data(); e[6].record()
-            st.bwd_weight(); e[7].record()
+            st.run(seed=i)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
-        per_call = {c: float(np.mean([ev[i][k].elapsed_time(ev[i][k + 1]) for i in range(steps)])) * 1e3
-                    for k, c in enumerate(CALLS)}          # microseconds
-        return L, (x, w, dy), dt / steps, per_call
+        n, ms = B.int8t_profile_stop()[dom]
+        return L, (x, w, dy), dt / steps, per_kernel, (dom, n / steps, ms * 1e3 / n)
 
-    L, host, t_step, per_call = bench_layer(args.config, args.layer, args.steps, args.warmup)
+    L, host, t_step, per_kernel, (dom, dom_launches, dom_us) = bench_layer(args.config, args.layer, args.steps, args.warmup)
     tops = 6 * L.macs / t_step / 1e12
-    alg = algorithmic(L, n_cand)
-    dom = max(per_call, key=per_call.get)
-    t_dom = per_call[dom] * 1e-6
-    a = alg[dom]
-    # which roofline bounds the dominant call
+    a = algorithmic(L, n_cand)[dom]
+    t_dom = dom_us * 1e-6 * dom_launches           # the kernel's time per step
+    # which roofline bounds the dominant kernel
     t_hbm = a["bytes"] / (HBM_PEAK_GBS * 1e9)
-    if dom == "dsgc":
-        t_alu = a["ops"] / (VALU_PEAK_TOPS * 1e12)
-        if t_alu > t_hbm:
-            roof = dict(bound="alu", achieved=a["ops"] / t_dom / 1e12, peak=VALU_PEAK_TOPS, unit="TOP/s")
-        else:
-            roof = dict(bound="hbm", achieved=a["bytes"] / t_dom / 1e9, peak=HBM_PEAK_GBS, unit="GB/s")
-    elif a["ops"] / (INT8_MFMA_PEAK_TOPS * 1e12) > t_hbm:
+    if dom == "dsgc_sweep_kernel" and a["ops"] / (VALU_PEAK_TOPS * 1e12) > t_hbm:
+        roof = dict(bound="alu", achieved=a["ops"] / t_dom / 1e12, peak=VALU_PEAK_TOPS, unit="TOP/s")
+    elif dom != "dsgc_sweep_kernel" and a["ops"] / (INT8_MFMA_PEAK_TOPS * 1e12) > t_hbm:
         roof = dict(bound="mfma", achieved=a["ops"] / t_dom / 1e12, peak=INT8_MFMA_PEAK_TOPS, unit="TOP/s")
     else:
         roof = dict(bound="hbm", achieved=a["bytes"] / t_dom / 1e9, peak=HBM_PEAK_GBS, unit="GB/s")
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
-    roof["kernel"] = {"dsgc": "int8t_dsgc_clip = absmax_kernel + dsgc_sweep_kernel + dsgc_finish_kernel",
-                      "quantize_x": "int8t_quantize(a) = absmax_kernel + quantize_act_kernel",
-                      "quantize_w": "int8t_quantize(W) = absmax_kernel + quantize_wgt_kernel",
-                      "quantize_dy": "int8t_quantize(g_z) = quantize_act_kernel + deviation_finish_kernel",
-                      "fwd": "int8t_conv_fwd = igemm_kernel", "bwd_data": "int8t_conv_bwd_data = igemm_kernel",
-                      "bwd_weight": "int8t_conv_bwd_weight = wgrad_kernel + wgrad_reduce_kernel"}[dom]
-    roof["us_per_launch"] = per_call[dom]
+    roof["traffic"] = TRAFFIC.get((args.config, args.layer, dom))
+    roof["kernel"] = dom
+    roof["launches_per_step"] = dom_launches
+    roof["us_per_launch"] = dom_us
 
     out = {
         "metric": "INT8 conv TOPS (fwd+bwd-data+bwd-weight incl. quantize); % int8 MFMA peak",
@@ -170,27 +174,35 @@ def main():
                                f"H=W={L.H}x{L.W} K={L.K} {L.R}x{L.S} stride {L.stride[0]} pad {L.pad} "
                                f"groups {L.groups}; DSGC 32 candidates every step",
                    "pct_int8_mfma_peak": 100.0 * tops / INT8_MFMA_PEAK_TOPS,
-                   "us_per_call": per_call,
-                   "sum_calls_us": sum(per_call.values())},
+                   "us_per_kernel": {k: {"launches_per_step": v[0], "us_per_launch": round(v[1], 2)}
+                                     for k, v in sorted(per_kernel.items(), key=lambda kv: -kv[1][0] * kv[1][1])},
+                   "sum_kernels_us": sum(v[0] * v[1] for v in per_kernel.values())},
         "roofline": roof,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(L, *host, ratios, args.cpu_images)
 
+    if args.copy_calibration > 0:
+        src = torch.ones(args.copy_calibration * (1 << 20) // 4, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)       # one elementwise kernel: reads and writes the stated size once
+        torch.cuda.synchronize()
+
     if args.all_layers:
         for cfg in sorted(inputs.CONFIGS):
             for li in range(len(inputs.CONFIGS[cfg])):
                 if (cfg, li) == (args.config, args.layer):
-                    Lx, ts, pc = L, t_step, per_call
+                    Lx, ts, pk = L, t_step, per_kernel
                 else:
-                    Lx, _, ts, pc = bench_layer(cfg, li, max(5, args.steps // 2), 3)
+                    Lx, _, ts, pk, _ = bench_layer(cfg, li, max(5, args.steps // 2), 3)
                 al = algorithmic(Lx, n_cand)
                 row = {"layer": f"{cfg}.{li} {Lx.name}", "ms_per_step": round(ts * 1e3, 4),
                        "TOPS": round(6 * Lx.macs / ts / 1e12, 2)}
-                for c in CALLS:
-                    t = pc[c] * 1e-6
-                    row[c] = {"us": round(pc[c], 2), "GB/s": round(al[c]["bytes"] / t / 1e9, 1),
-                              "TOP/s": round(al[c]["ops"] / t / 1e12, 2)}
+                for k, (n, us) in sorted(pk.items(), key=lambda kv: -kv[1][0] * kv[1][1]):
+                    t = n * us * 1e-6
+                    row[k] = {"us_per_step": round(n * us, 2), "GB/s": round(al[k]["bytes"] / t / 1e9, 1),
+                              "TOP/s": round(al[k]["ops"] / t / 1e12, 2)}
                 print(json.dumps(row), file=sys.stderr, flush=True)
 
     print(json.dumps(out), flush=True)

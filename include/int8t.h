@@ -189,6 +189,30 @@ int8t_status int8t_conv_bwd_weight(const int8t_conv_desc *desc,
                                    float *dw_dev, int32_t *acc_dev,
                                    void *ws_dev, size_t ws_bytes, void *stream);
 
+/*
+ * Kernel timing (measurement aid, not part of the method).  Between int8t_profile_start and
+ * int8t_profile_stop the library records a pair of HIP events on the launch stream around
+ * every launch of the selected kernel.
+ *   kernel   host string: the kernel's name ("dsgc_sweep_kernel", "absmax_kernel",
+ *            "quantize_act_kernel", "quantize_planar_kernel", "quantize_wgt_kernel",
+ *            "deviation_finish_kernel", "dsgc_finish_kernel", "igemm_kernel", "band_kernel",
+ *            "wgrad_kernel", "wgrad_reduce_kernel", "dw_conv_kernel", "dw_wgrad_kernel",
+ *            "dw_wgrad_reduce_kernel"); NULL or "" selects every kernel.
+ *            An unknown name returns INT8T_ERR_ARG and leaves timing off.
+ * int8t_profile_stop waits for the recorded events, writes one entry per kernel that was
+ * launched (name: static string owned by the library; launches; summed duration in ms) into
+ * out[0..capacity), stores the number of kernels seen in *count (which may exceed capacity) and
+ * switches timing off.  Host pointers throughout.  Not thread-safe; event objects are created
+ * while timing is on, so keep it off under stream capture.
+ */
+typedef struct int8t_kernel_time {
+    const char *name;
+    int launches;
+    double total_ms;
+} int8t_kernel_time;
+int8t_status int8t_profile_start(const char *kernel);
+int8t_status int8t_profile_stop(int8t_kernel_time *out, int capacity, int *count);
+
 /* Eq.7 on the host: max(exp(-alpha * d_c), beta).  The paper uses alpha = 20, beta = 0.1. */
 double int8t_dclr_scale(double d_c, double alpha, double beta);
 

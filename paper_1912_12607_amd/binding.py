@@ -21,7 +21,12 @@ MAX_CANDIDATES = 64
 
 EXPORTS = ["int8t_status_string", "int8t_code_bytes", "int8t_workspace_bytes",
            "int8t_quantize_workspace_bytes", "int8t_quantize", "int8t_dsgc_clip", "int8t_conv_fwd",
-           "int8t_conv_bwd_data", "int8t_conv_bwd_weight", "int8t_dclr_scale"]
+           "int8t_conv_bwd_data", "int8t_conv_bwd_weight", "int8t_dclr_scale",
+           "int8t_profile_start", "int8t_profile_stop"]
+
+
+class KernelTime(C.Structure):
+    _fields_ = [("name", C.c_char_p), ("launches", C.c_int), ("total_ms", C.c_double)]
 
 
 class ConvDesc(C.Structure):
@@ -59,6 +64,10 @@ def _load():
         f.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.int8t_dclr_scale.restype = C.c_double
     L.int8t_dclr_scale.argtypes = [C.c_double, C.c_double, C.c_double]
+    L.int8t_profile_start.restype = i32
+    L.int8t_profile_start.argtypes = [C.c_char_p]
+    L.int8t_profile_stop.restype = i32
+    L.int8t_profile_stop.argtypes = [C.POINTER(KernelTime), i32, C.POINTER(i32)]
     return L
 
 
@@ -145,3 +154,15 @@ def int8t_conv_bwd_weight(desc, xq, sx, dyq, sdy, dw, acc=None, ws=None, stream=
 
 def int8t_dclr_scale(d_c: float, alpha: float = 20.0, beta: float = 0.1) -> float:
     return float(lib.int8t_dclr_scale(d_c, alpha, beta))
+
+
+def int8t_profile_start(kernel: str | None = None):
+    _check(lib.int8t_profile_start(None if kernel is None else kernel.encode()))
+
+
+def int8t_profile_stop() -> dict:
+    """{kernel name: (launches, total milliseconds)} of the launches since int8t_profile_start."""
+    buf = (KernelTime * 32)()
+    n = C.c_int(0)
+    _check(lib.int8t_profile_stop(buf, 32, C.byref(n)))
+    return {buf[i].name.decode(): (int(buf[i].launches), float(buf[i].total_ms)) for i in range(min(n.value, 32))}

@@ -271,7 +271,10 @@ bool launch_band(const IgemmArgs& a, hipStream_t st, hipError_t* err) {
         if (e != hipSuccess) { *err = e; return true; }
         attr_done[variant] = true;
     }
-    hipLaunchKernelGGL(kerns[variant], dim3(grid), dim3(256), lds, st, a, BP, nbands_h, nbands);
+    {
+        KernelTimer kt(KID_BAND, st);
+        hipLaunchKernelGGL(kerns[variant], dim3(grid), dim3(256), lds, st, a, BP, nbands_h, nbands);
+    }
     *err = hipGetLastError();
     return true;
 }

@@ -156,19 +156,19 @@ int dw_wgrad_chunks(int N, int C) {
 hipError_t launch_dw_conv(const DwArgs& a, hipStream_t st) {
     const size_t lds = ((size_t)a.IH * a.IW + 15) & ~(size_t)15;
     if (a.dgrad)
-        hipLaunchKernelGGL((dw_conv_kernel<true>), dim3(a.N * a.C), dim3(256), lds, st, a);
+        { KernelTimer kt(KID_DW_CONV, st); hipLaunchKernelGGL((dw_conv_kernel<true>), dim3(a.N * a.C), dim3(256), lds, st, a); }
     else
-        hipLaunchKernelGGL((dw_conv_kernel<false>), dim3(a.N * a.C), dim3(256), lds, st, a);
+        { KernelTimer kt(KID_DW_CONV, st); hipLaunchKernelGGL((dw_conv_kernel<false>), dim3(a.N * a.C), dim3(256), lds, st, a); }
     return hipGetLastError();
 }
 
 hipError_t launch_dw_wgrad(const DwArgs& a, hipStream_t st) {
     const size_t lds = (((size_t)a.IH * a.IW + 15) & ~(size_t)15) + (((size_t)a.OH * a.OW + 15) & ~(size_t)15);
-    hipLaunchKernelGGL(dw_wgrad_kernel, dim3(a.C, a.chunks), dim3(256), lds, st, a);
+    { KernelTimer kt(KID_DW_WGRAD, st); hipLaunchKernelGGL(dw_wgrad_kernel, dim3(a.C, a.chunks), dim3(256), lds, st, a); }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int total = a.C * a.R * a.S;
-    hipLaunchKernelGGL(dw_wgrad_reduce_kernel, dim3((total + 255) / 256), dim3(256), 0, st, a);
+    { KernelTimer kt(KID_DW_WGRAD_REDUCE, st); hipLaunchKernelGGL(dw_wgrad_reduce_kernel, dim3((total + 255) / 256), dim3(256), 0, st, a); }
     return hipGetLastError();
 }
 

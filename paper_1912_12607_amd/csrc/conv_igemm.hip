@@ -193,6 +193,7 @@ hipError_t launch_igemm(const IgemmArgs& a, hipStream_t st) {
     if (launch_band(a, st, &berr)) return berr;   // small filter bank: LDS-resident kernel
     const int ncols = a.N * a.OH * a.OW;
     const int ctiles = (ncols + IG_BN - 1) / IG_BN;
+    KernelTimer kt(KID_IGEMM, st);
     if (a.rows <= 64) {
         dim3 grid(ctiles, 1);
         if (a.dgrad) hipLaunchKernelGGL((igemm_kernel<64, true>), grid, dim3(256), 0, st, a);

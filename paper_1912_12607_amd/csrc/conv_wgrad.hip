@@ -379,16 +379,22 @@ hipError_t launch_wgrad(const WgradArgs& a, hipStream_t st) {
     dim3 grid(a.ktiles * a.ctiles * a.tapgroups, a.splits);
 #define LAUNCH(TBv, CSv) \
     hipLaunchKernelGGL((wgrad_kernel<TBv, CSv>), grid, dim3(256), a.lds_bytes, st, a)
-    if (a.TB == 1 && a.CS == 1) LAUNCH(1, 1);
-    else if (a.TB == 1 && a.CS == 4) LAUNCH(1, 4);
-    else if (a.TB == 3) LAUNCH(3, 1);
-    else if (a.TB == 7) LAUNCH(7, 1);
-    else return hipErrorInvalidValue;
+    {
+        KernelTimer kt(KID_WGRAD, st);
+        if (a.TB == 1 && a.CS == 1) LAUNCH(1, 1);
+        else if (a.TB == 1 && a.CS == 4) LAUNCH(1, 4);
+        else if (a.TB == 3) LAUNCH(3, 1);
+        else if (a.TB == 7) LAUNCH(7, 1);
+        else return hipErrorInvalidValue;
+    }
 #undef LAUNCH
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const size_t total = (size_t)a.K * a.R * a.S * a.Cp;
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((total + 63) / 64)), dim3(256), 0, st, a);
+    {
+        KernelTimer kt(KID_WGRAD_REDUCE, st);
+        hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((total + 63) / 64)), dim3(256), 0, st, a);
+    }
     return hipGetLastError();
 }
 

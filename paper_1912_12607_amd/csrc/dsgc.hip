@@ -291,14 +291,18 @@ hipError_t launch_dsgc(const float* g, size_t n, const float* ratios, int n_cand
     if (blocks > cap) blocks = cap;
     const uint32_t slo = (uint32_t)seed, shi = seed_hi_term(seed);
     dim3 grid(blocks, nchunks);
+    {
+    KernelTimer kt(KID_DSGC_SWEEP, st);
     if (stochastic)
         hipLaunchKernelGGL((dsgc_sweep_kernel<true>), grid, dim3(256), 0, st, g, n, ratios, n_cand,
                            ws.absmax_part, nparts_absmax, slo, shi, ws.absmax, ws.partA, ws.partB, ws.partG);
     else
         hipLaunchKernelGGL((dsgc_sweep_kernel<false>), grid, dim3(256), 0, st, g, n, ratios, n_cand,
                            ws.absmax_part, nparts_absmax, slo, shi, ws.absmax, ws.partA, ws.partB, ws.partG);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    KernelTimer kt(KID_DSGC_FINISH, st);
     hipLaunchKernelGGL(dsgc_finish_kernel, dim3(1), dim3(1024), 0, st, ws.partA, ws.partB, ws.partG,
                        blocks, ratios, n_cand, ws.absmax, clip_out, dev_out, dev_all_out);
     return hipGetLastError();

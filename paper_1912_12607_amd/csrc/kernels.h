@@ -1,6 +1,7 @@
 // Internal launch interface between the C-ABI layer (api.hip) and the kernel files.
 // Every launcher enqueues on `st` and returns the hipError_t of its last launch.
 #pragma once
+#include "profile.h"
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>

@@ -1,0 +1,111 @@
+// Per-kernel timing with HIP events on the launch stream (see profile.h).
+#include "profile.h"
+
+#include <cstring>
+#include <vector>
+
+#include "../../include/int8t.h"
+
+namespace int8t {
+
+int g_profile_select = -2;
+
+namespace {
+struct Rec {
+    int kid;
+    hipEvent_t a, b;
+    bool closed;
+};
+std::vector<Rec> g_recs;
+
+const char* const kNames[KID_COUNT] = {
+    "absmax_kernel",       "quantize_act_kernel", "quantize_planar_kernel", "quantize_wgt_kernel",
+    "deviation_finish_kernel", "dsgc_sweep_kernel",   "dsgc_finish_kernel",     "igemm_kernel",
+    "band_kernel",         "wgrad_kernel",        "wgrad_reduce_kernel",    "dw_conv_kernel",
+    "dw_wgrad_kernel",     "dw_wgrad_reduce_kernel"};
+
+void drop_all() {
+    for (Rec& r : g_recs) {
+        (void)hipEventDestroy(r.a);
+        (void)hipEventDestroy(r.b);
+    }
+    g_recs.clear();
+}
+}  // namespace
+
+void KernelTimer::begin(int kid) {
+    Rec r;
+    r.kid = kid;
+    r.closed = false;
+    if (hipEventCreate(&r.a) != hipSuccess) return;
+    if (hipEventCreate(&r.b) != hipSuccess) {
+        (void)hipEventDestroy(r.a);
+        return;
+    }
+    if (hipEventRecord(r.a, st_) != hipSuccess) {
+        (void)hipEventDestroy(r.a);
+        (void)hipEventDestroy(r.b);
+        return;
+    }
+    g_recs.push_back(r);
+    slot_ = (int)g_recs.size() - 1;
+}
+
+void KernelTimer::end() {
+    Rec& r = g_recs[(size_t)slot_];
+    r.closed = hipEventRecord(r.b, st_) == hipSuccess;
+}
+
+}  // namespace int8t
+
+using namespace int8t;
+
+extern "C" int8t_status int8t_profile_start(const char* kernel) {
+    drop_all();
+    if (kernel == nullptr || kernel[0] == '\0') {
+        g_profile_select = -1;
+        return INT8T_OK;
+    }
+    for (int k = 0; k < KID_COUNT; ++k) {
+        if (std::strcmp(kernel, kNames[k]) == 0) {
+            g_profile_select = k;
+            return INT8T_OK;
+        }
+    }
+    g_profile_select = -2;
+    return INT8T_ERR_ARG;
+}
+
+extern "C" int8t_status int8t_profile_stop(int8t_kernel_time* out, int capacity, int* count) {
+    g_profile_select = -2;
+    if (count == nullptr || capacity < 0 || (capacity > 0 && out == nullptr)) {
+        drop_all();
+        return INT8T_ERR_ARG;
+    }
+    int launches[KID_COUNT] = {0};
+    double total[KID_COUNT] = {0.0};
+    int8t_status status = INT8T_OK;
+    for (Rec& r : g_recs) {
+        if (!r.closed) continue;
+        float ms = 0.f;
+        if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) {
+            status = INT8T_ERR_RUNTIME;
+            continue;
+        }
+        launches[r.kid] += 1;
+        total[r.kid] += (double)ms;
+    }
+    drop_all();
+    int n = 0;
+    for (int k = 0; k < KID_COUNT; ++k) {
+        if (launches[k] == 0) continue;
+        if (n < capacity) {
+            out[n].name = kNames[k];
+            out[n].launches = launches[k];
+            out[n].total_ms = total[k];
+        }
+        ++n;
+    }
+    *count = n;
+    return status;
+}

@@ -42,6 +42,7 @@ hipError_t launch_absmax(const float* x, size_t n, float* part, int* nparts, hip
     size_t want = (n / 4 + 256 * 8 - 1) / (256 * 8);   // >= 8 float4 per thread before adding blocks
     int blocks = (int)(want < 1 ? 1 : (want > (size_t)kMaxPartials ? (size_t)kMaxPartials : want));
     *nparts = blocks;
+    KernelTimer kt(KID_ABSMAX, st);
     hipLaunchKernelGGL(absmax_kernel, dim3(blocks), dim3(256), 0, st, x, n, part);
     return hipGetLastError();
 }
@@ -168,6 +169,7 @@ hipError_t launch_quantize_act(const QuantArgs& a, hipStream_t st) {
     const int N = a.d0, C = a.d1, HW = a.d2 * a.d3, Cp = (C + 15) & ~15;
     dim3 grid((HW + QA_PIX - 1) / QA_PIX, (Cp + QA_CH - 1) / QA_CH, N);
     const uint32_t slo = (uint32_t)a.seed, shi = seed_hi_term(a.seed);
+    KernelTimer kt(KID_QUANTIZE_ACT, st);
 #define LAUNCH(ST, DV)                                                                               \
     hipLaunchKernelGGL((quantize_act_kernel<ST, DV>), grid, dim3(256), 0, st, a.x, C, Cp, HW, a.clip, \
                        a.absmax_part, a.nparts, slo, shi, a.q, a.scale, a.devpart)
@@ -246,6 +248,7 @@ hipError_t launch_quantize_planar(const QuantArgs& a, hipStream_t st) {
     const size_t n = (size_t)a.d0 * a.d1 * a.d2 * a.d3;
     const int blocks = quant_blocks_planar(n);
     const uint32_t slo = (uint32_t)a.seed, shi = seed_hi_term(a.seed);
+    KernelTimer kt(KID_QUANTIZE_PLANAR, st);
 #define LAUNCH(ST, DV)                                                                              \
     hipLaunchKernelGGL((quantize_planar_kernel<ST, DV>), dim3(blocks), dim3(256), 0, st, a.x, n,    \
                        a.clip, a.absmax_part, a.nparts, slo, shi, a.q, a.scale, a.devpart)
@@ -341,6 +344,7 @@ hipError_t launch_quantize_wgt(const QuantArgs& a, hipStream_t st) {
     const size_t off2 = (((size_t)K * R * S * Cp) + 255) & ~(size_t)255;
     const int blocks = quant_blocks_wgt(K, Cg, R, S);
     const uint32_t slo = (uint32_t)a.seed, shi = seed_hi_term(a.seed);
+    KernelTimer kt(KID_QUANTIZE_WGT, st);
 #define LAUNCH(ST, DV)                                                                              \
     hipLaunchKernelGGL((quantize_wgt_kernel<ST, DV>), dim3(blocks), dim3(256), 0, st, a.x, K, Cg, R, \
                        S, Cp, Kp, off2, a.clip, a.absmax_part, a.nparts, slo, shi, a.q, a.scale,    \
@@ -392,6 +396,7 @@ __global__ __launch_bounds__(256) void deviation_finish_kernel(const DevPartial*
 }
 
 hipError_t launch_deviation_finish(const DevPartial* part, int nparts, double* dev_out, hipStream_t st) {
+    KernelTimer kt(KID_DEVIATION_FINISH, st);
     hipLaunchKernelGGL(deviation_finish_kernel, dim3(1), dim3(256), 0, st, part, nparts, dev_out);
     return hipGetLastError();
 }

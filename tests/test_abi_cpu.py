@@ -118,3 +118,16 @@ def test_argument_errors_before_any_launch(lib):
     f = lib.int8t_conv_bwd_weight
     assert f(C.byref(Desc(1, 4, 5, 5, 4, 3, 3, 1, 1, 1, 1, 1)), fake, fake, fake, fake, fake, None, fake, 8, None) == 4
     assert lib.int8t_status_string(4) == b"workspace too small"
+
+
+def test_profile_entry_points_without_launches(lib):
+    class KT(C.Structure):
+        _fields_ = [("name", C.c_char_p), ("launches", C.c_int), ("total_ms", C.c_double)]
+    assert lib.int8t_profile_start(b"no_such_kernel") == 3          # INT8T_ERR_ARG, timing stays off
+    assert lib.int8t_profile_start(b"dsgc_sweep_kernel") == 0
+    n = C.c_int(-1)
+    buf = (KT * 4)()
+    assert lib.int8t_profile_stop(buf, 4, C.byref(n)) == 0 and n.value == 0
+    assert lib.int8t_profile_start(None) == 0
+    assert lib.int8t_profile_stop(None, 0, C.byref(n)) == 0 and n.value == 0
+    assert lib.int8t_profile_stop(None, 4, C.byref(n)) == 3          # capacity without a buffer
