@@ -5,6 +5,7 @@ A "step" is one pass of the whole path over one layer's synthetic tensors, all r
 before the timed region starts:
     quantize(a) + quantize(W) + DSGC clip search(g_z) + quantize(g_z; stochastic, d_c)
     + conv forward + conv backward-data + conv backward-weight.
+The clip search returns d_c (the input of Eq.7); the quantizer's optional second Eq.6 report is off.
 The workload is the ResNet-18-style 3x3 layer (N=64, C=K=64, 56x56, stride 1, pad 1).
 Metric: INT8 conv TOPS = 3 * 2 * N*K*P*Q*C*R*S / step time  (the three convolutions' integer
 operations over the time of the whole step, quantizers and clip search included).
@@ -48,11 +49,10 @@ def algorithmic(L, n_cand):
         "quantize_planar_kernel": dict(bytes=5 * (n_x + n_y), ops=0),
         "quantize_wgt_kernel": dict(bytes=6 * n_w, ops=0),                        # fp32 read + two code copies
         "deviation_finish_kernel": dict(bytes=0, ops=0),
-        # one read of g_z.  Vector-ALU work of the sweep: 4.5 operations per element and candidate (fused
-        # multiply-add, convert, 0.75 byte gather, 1.75 uint8 dot-product accumulates) + 25 per element
-        # and 16-candidate chunk (draw, fixed point, digit planes)
-        "dsgc_sweep_kernel": dict(bytes=4 * n_y, ops=(4.5 * n_cand + 25 * ((n_cand + 15) // 16)) * n_y),
-        "dsgc_finish_kernel": dict(bytes=0, ops=0),
+        # one read of g_z.  Vector-ALU work of the sweep: 2.75 operations per element and candidate (round-down
+        # fused multiply-add, convert, 0.75 byte gather) + 30 per element and 32-candidate chunk (draw, fixed
+        # point, digit planes, LDS traffic); the products and sums themselves run on the matrix cores
+        "dsgc_sweep_kernel": dict(bytes=4 * n_y, ops=(2.75 * n_cand + 30 * ((n_cand + 31) // 32)) * n_y),
         "igemm_kernel": conv2, "band_kernel": conv2, "dw_conv_kernel": conv2,
         "wgrad_kernel": wg, "dw_wgrad_kernel": wg,
         "wgrad_reduce_kernel": dict(bytes=4 * n_w, ops=0), "dw_wgrad_reduce_kernel": dict(bytes=4 * n_w, ops=0),
@@ -121,7 +121,7 @@ def main():
         an untimed pass with every kernel bracketed by events, and the dominant kernel's
         (name, us per launch) measured by events inside the timed region itself."""
         L, x, w, dy = inputs.make_layer_inputs(cfg, li)
-        st = LayerStep(L, n_cand=n_cand, keep_acc=False)
+        st = LayerStep(L, n_cand=n_cand, keep_acc=False, requantize_deviation=False)
         st.upload(x, w, dy, ratios)
         torch.cuda.synchronize()
         for i in range(warmup):

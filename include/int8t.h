@@ -195,7 +195,7 @@ int8t_status int8t_conv_bwd_weight(const int8t_conv_desc *desc,
  * every launch of the selected kernel.
  *   kernel   host string: the kernel's name ("dsgc_sweep_kernel", "absmax_kernel",
  *            "quantize_act_kernel", "quantize_planar_kernel", "quantize_wgt_kernel",
- *            "deviation_finish_kernel", "dsgc_finish_kernel", "igemm_kernel", "band_kernel",
+ *            "deviation_finish_kernel", "igemm_kernel", "band_kernel",
  *            "wgrad_kernel", "wgrad_reduce_kernel", "dw_conv_kernel", "dw_wgrad_kernel",
  *            "dw_wgrad_reduce_kernel"); NULL or "" selects every kernel.
  *            An unknown name returns INT8T_ERR_ARG and leaves timing off.

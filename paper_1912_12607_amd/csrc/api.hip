@@ -69,9 +69,9 @@ int quant_blocks(const int d[4], int8t_kind kind) {
 }
 
 size_t dsgc_ws_bytes(size_t n) {
-    const size_t nb = (size_t)dsgc_blocks(n);
-    return align256(kMaxPartials * sizeof(float)) + 256 + align256(nb * 64 * sizeof(double)) +
-           align256(nb * 64 * sizeof(unsigned long long)) + align256(nb * sizeof(double));
+    (void)n;
+    return align256(kMaxPartials * sizeof(float)) + align256((dsgc_acc_words() + 1) * sizeof(unsigned long long)) +
+           align256(kMaxPartials * sizeof(double));
 }
 
 void fill_wgrad_geometry(WgradArgs* a, const int8t_conv_desc* d, const Geo& g) {
@@ -198,16 +198,16 @@ int8t_status int8t_dsgc_clip(const float* g_dev, size_t n, const float* ratios_d
         return INT8T_ERR_ARG;
     if (ws_bytes < dsgc_ws_bytes(n)) return INT8T_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    const size_t nb = (size_t)dsgc_blocks(n);
     char* p = (char*)ws_dev;
     DsgcWs ws;
+    const size_t nacc = dsgc_acc_words();
     ws.absmax_part = (float*)p;                 p += align256(kMaxPartials * sizeof(float));
-    ws.absmax = (float*)p;                      p += 256;
-    ws.partA = (double*)p;                      p += align256(nb * 64 * sizeof(double));
-    ws.partB = (unsigned long long*)p;          p += align256(nb * 64 * sizeof(unsigned long long));
+    ws.acc = (unsigned long long*)p;
+    ws.ticket = (unsigned int*)(ws.acc + nacc);  p += align256((nacc + 1) * sizeof(unsigned long long));
     ws.partG = (double*)p;
     int nparts = 0;
-    if (launch_absmax(g_dev, n, ws.absmax_part, &nparts, st) != hipSuccess) return INT8T_ERR_RUNTIME;
+    if (launch_absmax(g_dev, n, ws.absmax_part, &nparts, st, ws.partG, ws.acc, (int)nacc + 1) != hipSuccess)
+        return INT8T_ERR_RUNTIME;
     if (launch_dsgc(g_dev, n, ratios_dev, n_cand, mode == INT8T_ROUND_STOCHASTIC, seed, ws, nparts, clip_dev,
                     deviation_dev, deviation_all_dev, st) != hipSuccess)
         return INT8T_ERR_RUNTIME;

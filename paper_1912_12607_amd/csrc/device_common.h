@@ -92,6 +92,10 @@ __device__ __forceinline__ int round_nearest_code(float x, float inv) {
 __device__ __forceinline__ void fp32_round_down_mode(float& keep0, float& keep1) {
     asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 2\n\ts_nop 3" : "+v"(keep0), "+v"(keep1));
 }
+// back to round-to-nearest-even (the default) for the fp32 operations that follow
+__device__ __forceinline__ void fp32_round_nearest_mode(float& keep0) {
+    asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 0\n\ts_nop 3" : "+v"(keep0));
+}
 // floor(|x| * inv24 + uf) as int32, saturated at 2^31 - 1 (needs the round-down mode).
 __device__ __forceinline__ int stoch_fixed(float x, float inv24, float uf) {
     float t;

@@ -13,22 +13,43 @@
 //     search runs on magnitudes and never looks at a sign;
 //   * m is the top byte of floor(|g| * inv24 + u), one round-down fused multiply-add and one
 //     saturating convert (see device_common.h); four elements' bytes are gathered into one dword
-//     by byte permutes;
-//   * |g| is turned, once per element, into a 46-bit fixed-point integer relative to max|g|
-//     (H * 2^23 + L, H <= 2^22, L <= 2^23), and both halves into three byte digits;
-//   * A_j and B_j are then sums of uint8 x uint8 products, accumulated four at a time by the 4-way
-//     dot-product instruction into 32-bit registers: 6 digit sums + 1 square sum per candidate.
+//     by byte permutes.  These 2.75 instructions per element and candidate are all the vector ALU
+//     does per evaluation;
+//   * |g| is turned, once per element, into a 44-bit fixed-point integer relative to max|g|
+//     (H * 2^22 + L, H, L <= 2^22), and both halves into three balanced (signed) byte digits;
+//   * the sums A_j = sum |g| m_j (six digit sums) and B_j = sum m_j^2 are int8 x int8 products
+//     with int32 accumulation, i.e. matrix products [digits x elements] * [elements x candidates]
+//     and [candidates x elements] * [elements x candidates] (diagonal): they go to the matrix
+//     cores.  A lane computes the codes of ITS four elements for all candidates, but an MFMA
+//     operand wants one candidate's codes of 16 elements in a lane, so the code dwords take a trip
+//     through a wave-private LDS tile (one byte per evaluation), which is cheap next to the ALU
+//     work.  No barriers: a wave only reads what it wrote itself, and LDS serves a wave's
+//     instructions in order.
 // The integer sums are exact and order independent; the only error against an fp64 evaluation is
-// the fixed-point rounding of |g|, |delta| <= max|g| * 2^-45 per element, i.e. at most
-// 2^-45 * sqrt(n) in d_j (Cauchy-Schwarz), far below the resolution the search needs.
+// the fixed-point rounding of |g|, |delta| <= max|g| * 2^-44 per element, i.e. at most
+// 2^-44 * sqrt(n) in d_j (Cauchy-Schwarz), far below the resolution the search needs.
+//
+// Blocks add their 64-bit integer totals (sum H*m, sum L*m, sum m^2 per candidate) into one of
+// DSGC_GROUPS accumulator sets with device-scope atomics -- integer addition, so the result does
+// not depend on the order -- and take a ticket; the block that draws the last ticket sums the
+// sets, evaluates Eq.6 for every candidate and picks the clip value.  The accumulators and the
+// ticket are cleared by the absmax pass that always precedes the sweep.
 #include "device_common.h"
 #include "kernels.h"
 
 namespace int8t {
 
-constexpr int DSGC_JC = 16;       // candidates per block (7 32-bit accumulators each)
-constexpr int DSGC_JPAD = 64;     // row pitch of the partial arrays (= INT8T_MAX_CANDIDATES)
-constexpr int DSGC_MAX_BLOCKS = 512;
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int DSGC_JC = 32;        // candidates per block: the 32 columns of one MFMA tile
+constexpr int DSGC_JPAD = 64;      // row pitch of the partial arrays (= INT8T_MAX_CANDIDATES)
+constexpr int DSGC_MAX_BLOCKS = 768;
+constexpr int DSGC_GROUPS = 32;     // accumulator sets the blocks spread their atomics over
+constexpr int DSGC_PITCH = 272;    // bytes per LDS row: a wave's 256 elements + 16 (spreads the operand reads over the banks)
+constexpr int DSGC_ROWS = DSGC_JC + 6;   // 32 code rows, then the 6 digit rows
+// int32 accumulators: |digit * code| <= 128 * 127 per element and lane sum; flushed well before 2^31
+constexpr int DSGC_FLUSH_ITERS = 256;    // 256 iterations x 256 elements x 16256 < 2^31
 
 // bytes [a.b3, b.b3, c.b3, d.b3]: the top bytes of four 32-bit values
 __device__ __forceinline__ uint32_t top_bytes(int a, int b, int c, int d) {
@@ -43,35 +64,38 @@ __device__ __forceinline__ uint32_t low_bytes(int a, int b, int c, int d) {
     return lo | hi;
 }
 
-// Byte digits of four integers 0 <= v < 2^24:  v = d0 + 256 d1 + 65536 d2.
-// plane[b] packs digit b of the four values.
-__device__ __forceinline__ void digit_planes(const uint32_t y[4], uint32_t plane[3]) {
+// Balanced byte digits of four integers 0 <= v <= 2^22:  v = d0 + 256 d1 + 65536 d2 with
+// -128 <= d < 128 (the bytes of v + 0x808080, each minus 128).  plane[b] packs digit b of the
+// four values as signed bytes.
+__device__ __forceinline__ void digit_planes(const uint32_t v[4], uint32_t plane[3]) {
+    uint32_t y[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) y[e] = v[e] + 0x808080u;
     const uint32_t t0 = __builtin_amdgcn_perm(y[1], y[0], 0x05010400u);  // y0.b0 y1.b0 y0.b1 y1.b1
     const uint32_t t1 = __builtin_amdgcn_perm(y[1], y[0], 0x0c0c0602u);  // y0.b2 y1.b2 0 0
     const uint32_t t2 = __builtin_amdgcn_perm(y[3], y[2], 0x05010400u);
     const uint32_t t3 = __builtin_amdgcn_perm(y[3], y[2], 0x06020c0cu);  // 0 0 y2.b2 y3.b2
-    plane[0] = __builtin_amdgcn_perm(t2, t0, 0x05040100u);
-    plane[1] = __builtin_amdgcn_perm(t2, t0, 0x07060302u);
-    plane[2] = t1 | t3;
+    plane[0] = __builtin_amdgcn_perm(t2, t0, 0x05040100u) ^ 0x80808080u;
+    plane[1] = __builtin_amdgcn_perm(t2, t0, 0x07060302u) ^ 0x80808080u;
+    plane[2] = (t1 | t3) ^ 0x80808080u;
 }
 
 template <bool STOCH>
 __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
     const float* __restrict__ g, size_t n, const float* __restrict__ ratios, int n_cand,
     const float* __restrict__ absmax_part, int nparts, uint32_t seed_lo, uint32_t seed_hi_mul,
-    float* __restrict__ absmax_out, double* __restrict__ partA, unsigned long long* __restrict__ partB,
-    double* __restrict__ partG) {
+    unsigned long long* __restrict__ acc, unsigned int* __restrict__ ticket, const double* __restrict__ partG,
+    float* __restrict__ clip_out, double* __restrict__ dev_out, double* __restrict__ dev_all_out) {
     constexpr int JC = DSGC_JC;
     __shared__ float lds4[4];
     __shared__ float s_inv[JC];
-    __shared__ double s_red[4][JC + 1];
-    __shared__ unsigned long long s_redB[4][JC];
+    __shared__ long long s_red[4][JC][3];
+    __shared__ unsigned int s_last;
+    __shared__ __attribute__((aligned(16))) unsigned char s_tile[4][DSGC_ROWS * DSGC_PITCH];
 
     const int j0 = blockIdx.y * JC;
     const int jn = (n_cand - j0 < JC) ? (n_cand - j0) : JC;
-    const bool want_g = blockIdx.y == 0;
     const float M = reduce_absmax_partials(absmax_part, nparts, lds4);
-    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *absmax_out = M;
     if (threadIdx.x < JC) {
         const int j = threadIdx.x;
         const float c = (j < jn) ? __fmul_rn(M, ratios[j0 + j]) : 0.0f;
@@ -93,16 +117,49 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
     for (int j = 0; j < JC; ++j)
         inv[j] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(s_inv[j])));
 
-    unsigned accA[JC][6];
-    unsigned accB[JC];
-#pragma unroll
-    for (int j = 0; j < JC; ++j) {
-        accB[j] = 0;
-#pragma unroll
-        for (int b = 0; b < 6; ++b) accA[j][b] = 0;
-    }
-    double G = 0.0;
+    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int l32 = lane & 31, kh = lane >> 5;
+    unsigned char* __restrict__ const tile = s_tile[w];
+    uint32_t* __restrict__ const wr = reinterpret_cast<uint32_t*>(tile + 4 * lane);         // + row * PITCH
+    // MFMA operands of this lane: candidate l32's codes / digit row min(l32, 5), 16 elements from 16*kh
+    const unsigned char* __restrict__ const rd_code = tile + l32 * DSGC_PITCH + 16 * kh;
+    const unsigned char* __restrict__ const rd_dig = tile + (JC + (l32 < 5 ? l32 : 5)) * DSGC_PITCH + 16 * kh;
 
+    v16i accA, accB;      // [digit row][candidate] (rows 0..5 used) and [candidate][candidate] (diagonal used)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) accA[v] = accB[v] = 0;
+    // lanes 0..31: candidate l32's totals so far (flushed part): sum H*m, sum L*m, sum m^2
+    long long runH = 0, runL = 0, runB = 0;
+
+    // int32 tiles -> 64-bit per-candidate totals in lanes 0..31, accumulators cleared
+    auto flush = [&]() {
+        // accA: lane (col, kh), register v holds row 8*(v/4) + 4*kh + (v%4): rows 0..3 (the H digits
+        // and L digit 0) sit in the lower half's registers 0..3, rows 4..5 (L digits 1, 2) in the
+        // upper half's registers 0..1
+        long long ph, pl;
+        if (kh == 0) {
+            ph = (long long)accA[0] + 256LL * accA[1] + 65536LL * accA[2];
+            pl = (long long)accA[3];
+        } else {
+            ph = 0;
+            pl = 256LL * accA[0] + 65536LL * accA[1];
+        }
+        pl += __shfl_xor(pl, 32, kWave);
+        runH += ph;          // meaningful in the lower half only
+        runL += pl;
+        // accB: the diagonal element of column l32 is row l32 = 8*(v/4) + 4*kh' + (v%4)
+        const int vd = 4 * (l32 >> 3) + (l32 & 3);
+        int diag = 0;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) diag = (v == vd) ? accB[v] : diag;
+        long long bd = (((l32 >> 2) & 1) == kh) ? (long long)diag : 0LL;
+        bd += __shfl_xor(bd, 32, kWave);
+        runB += bd;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) accA[v] = accB[v] = 0;
+    };
+
+    // one wave iteration: 256 consecutive elements, four per lane
     auto group = [&](const float x[4], uint32_t index0) {
         float uf[4] = {0.f, 0.f, 0.f, 0.f};
         uint32_t H[4], L[4];
@@ -112,15 +169,16 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
             const float xs = ldexpf(fabsf(x[e]), shift);     // exact, 0 .. 2^22
             const float h = floorf(xs);
             H[e] = (uint32_t)h;
-            L[e] = (uint32_t)rintf((xs - h) * 8388608.0f);   // remainder * 2^23: exact before rint
-            if (want_g) {
-                const double xd = (double)x[e];
-                G = fma(xd, xd, G);
-            }
+            L[e] = (uint32_t)rintf((xs - h) * 4194304.0f);   // remainder * 2^22: exact before rint
         }
         uint32_t pH[3], pL[3];
         digit_planes(H, pH);
         digit_planes(L, pL);
+#pragma unroll
+        for (int b = 0; b < 3; ++b) {
+            wr[(JC + b) * (DSGC_PITCH / 4)] = pH[b];
+            wr[(JC + 3 + b) * (DSGC_PITCH / 4)] = pL[b];
+        }
 #pragma unroll
         for (int j = 0; j < JC; ++j) {
             uint32_t rp;
@@ -131,147 +189,140 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
                 rp = low_bytes(round_nearest_code(fabsf(x[0]), inv[j]), round_nearest_code(fabsf(x[1]), inv[j]),
                                round_nearest_code(fabsf(x[2]), inv[j]), round_nearest_code(fabsf(x[3]), inv[j]));
             }
-            accB[j] = __builtin_amdgcn_udot4(rp, rp, accB[j], false);
-#pragma unroll
-            for (int b = 0; b < 3; ++b) {
-                accA[j][b] = __builtin_amdgcn_udot4(pH[b], rp, accA[j][b], false);
-                accA[j][3 + b] = __builtin_amdgcn_udot4(pL[b], rp, accA[j][3 + b], false);
-            }
+            wr[j * (DSGC_PITCH / 4)] = rp;
         }
+        __builtin_amdgcn_wave_barrier();   // keep the tile's stores ahead of its loads
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            const uint4 tc = *reinterpret_cast<const uint4*>(rd_code + 32 * s);
+            const uint4 td = *reinterpret_cast<const uint4*>(rd_dig + 32 * s);
+            const v4i fc = v4i{(int)tc.x, (int)tc.y, (int)tc.z, (int)tc.w};
+            const v4i fd = v4i{(int)td.x, (int)td.y, (int)td.z, (int)td.w};
+            accA = __builtin_amdgcn_mfma_i32_32x32x32_i8(fd, fc, accA, 0, 0, 0);
+            accB = __builtin_amdgcn_mfma_i32_32x32x32_i8(fc, fc, accB, 0, 0, 0);
+        }
+        __builtin_amdgcn_wave_barrier();   // and the next iteration's stores behind these loads
     };
 
     const size_t n4 = n >> 2;
     const float4* __restrict__ g4 = reinterpret_cast<const float4*>(g);
     const size_t stride = (size_t)gridDim.x * 256;
     {
-        // the next iteration's 16 bytes are requested before this iteration's arithmetic starts
+        // Wave-uniform trip count (the MFMAs need the whole wave): lanes beyond the end carry zeros,
+        // which add nothing to A or B.  The next iteration's 16 bytes are requested before this
+        // iteration's arithmetic starts.  The int32 tiles are turned into 64-bit totals after every
+        // DSGC_FLUSH_ITERS iterations, outside the inner loop, so inside it only MFMAs touch them.
         size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+        size_t ibase = (size_t)blockIdx.x * 256 + 64 * w;      // the wave's first float4
         float4 f = (i < n4) ? g4[i] : make_float4(0.f, 0.f, 0.f, 0.f);
-        while (i < n4) {
-            const size_t inext = i + stride;
-            const float4 fn = (inext < n4) ? g4[inext] : make_float4(0.f, 0.f, 0.f, 0.f);
-            const float vv[4] = {f.x, f.y, f.z, f.w};
-            group(vv, (uint32_t)(4 * i));
-            f = fn;
-            i = inext;
+        while (ibase < n4) {
+            for (int it = 0; it < DSGC_FLUSH_ITERS && ibase < n4; ++it) {
+                const size_t inext = i + stride;
+                const float4 fn = (inext < n4) ? g4[inext] : make_float4(0.f, 0.f, 0.f, 0.f);
+                const float vv[4] = {f.x, f.y, f.z, f.w};
+                group(vv, (uint32_t)(4 * i));
+                f = fn;
+                i = inext;
+                ibase += stride;
+            }
+            flush();
         }
     }
-    if (blockIdx.x == 0 && threadIdx.x == 0 && (n & 3)) {
-        // ragged tail: missing elements are zeros (zero contributes nothing to A, B or G)
+    if (blockIdx.x == 0 && w == 0 && (n & 3)) {
+        // ragged tail (wave-uniform branch): lane 0 carries the last 1..3 elements, zeros elsewhere
         float vv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-        for (int e = 0; e < (int)(n & 3); ++e) vv[e] = g[(n4 << 2) + e];
-        group(vv, (uint32_t)(n4 << 2));
+        if (lane == 0)
+            for (int e = 0; e < (int)(n & 3); ++e) vv[e] = g[(n4 << 2) + e];
+        group(vv, (uint32_t)(n4 << 2) + 4u * (uint32_t)lane);
+        flush();
     }
 
-    // per-thread totals: A = (2^23 * sum_b 256^b aH_b + sum_b 256^b aL_b) * 2^(e-45); the digit
-    // sums are exact integers below 2^49 in double, the last additions round like any fp64 sum
-    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    G = wave_sum(G);
-#pragma unroll
-    for (int j = 0; j < JC; ++j) {
-        const double dH = (double)accA[j][0] + 256.0 * (double)accA[j][1] + 65536.0 * (double)accA[j][2];
-        const double dL = (double)accA[j][3] + 256.0 * (double)accA[j][4] + 65536.0 * (double)accA[j][5];
-        const double at = ldexp(dH * 8388608.0 + dL, e2 - 45);
-        const double asum = wave_sum(at);
-        const unsigned long long b = wave_sum((unsigned long long)accB[j]);
-        if (lane == 0) {
-            s_red[w][j] = asum;
-            s_redB[w][j] = b;
-        }
+    // block totals -> one of the accumulator sets
+    if (lane < JC) {
+        s_red[w][lane][0] = runH;
+        s_red[w][lane][1] = runL;
+        s_red[w][lane][2] = runB;
     }
-    if (lane == 0) s_red[w][JC] = G;
     __syncthreads();
-    if (threadIdx.x < JC) {
-        const int j = threadIdx.x;
+    if (threadIdx.x < 3 * JC) {
+        const int j = threadIdx.x / 3, q = threadIdx.x - 3 * j;
         if (j < jn) {
-            partA[(size_t)blockIdx.x * DSGC_JPAD + j0 + j] =
-                (s_red[0][j] + s_red[1][j]) + (s_red[2][j] + s_red[3][j]);
-            partB[(size_t)blockIdx.x * DSGC_JPAD + j0 + j] =
-                s_redB[0][j] + s_redB[1][j] + s_redB[2][j] + s_redB[3][j];
+            const long long t = (s_red[0][j][q] + s_red[1][j][q]) + (s_red[2][j][q] + s_red[3][j][q]);
+            const int grp = (int)(blockIdx.x % DSGC_GROUPS);
+            __hip_atomic_fetch_add(&acc[((size_t)grp * DSGC_JPAD + j0 + j) * 3 + q], (unsigned long long)t,
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
-    if (threadIdx.x == 0 && want_g)
-        partG[blockIdx.x] = (s_red[0][JC] + s_red[1][JC]) + (s_red[2][JC] + s_red[3][JC]);
-}
+    // All data moves through device-scope atomics (performed at the memory side) and is read back
+    // with device-scope atomic loads, so no cache write-back is needed: it is enough that this
+    // block's additions have been acknowledged before its ticket is drawn: every thread waits for
+    // its outstanding memory operations, then the barrier.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0)
+        s_last = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == gridDim.x * gridDim.y - 1
+                     ? 1u : 0u;
+    __syncthreads();
+    if (!s_last) return;
+    float Mn = M;
+    if (STOCH) fp32_round_nearest_mode(Mn);   // the clip value below is a default-mode product
 
-// Sums the per-block partials in a fixed order, evaluates Eq.6 for every candidate and picks the
-// smallest deviation (ties: smallest j, i.e. the largest clip value for decreasing ratios).
-// 1024 threads = 64 candidates x 16 block segments; the order of the additions depends on
-// (nblocks, n_cand) only, so results are reproducible run to run.
-constexpr int DSGC_SEGS = 16;
-
-__global__ __launch_bounds__(1024) void dsgc_finish_kernel(
-    const double* __restrict__ partA, const unsigned long long* __restrict__ partB,
-    const double* __restrict__ partG, int nblocks, const float* __restrict__ ratios, int n_cand,
-    const float* __restrict__ absmax, float* __restrict__ clip_out, double* __restrict__ dev_out,
-    double* __restrict__ dev_all_out) {
-    __shared__ double sA[DSGC_SEGS][DSGC_JPAD];
-    __shared__ unsigned long long sB[DSGC_SEGS][DSGC_JPAD];
-    __shared__ double sG[DSGC_SEGS];
-    __shared__ double sD[DSGC_JPAD];
-    const int j = threadIdx.x & 63, seg = threadIdx.x >> 6;
-    const int b0 = (int)(((long long)nblocks * seg) / DSGC_SEGS);
-    const int b1 = (int)(((long long)nblocks * (seg + 1)) / DSGC_SEGS);
-    // every partial of this thread's segment is requested before the first one is used
-    // (at most DSGC_MAX_BLOCKS / DSGC_SEGS = 32 per segment, in two batches of 16)
-    const float M = *absmax;
-    double a[4] = {0.0, 0.0, 0.0, 0.0};
-    unsigned long long b[4] = {0, 0, 0, 0};
-    if (j < n_cand) {
-        for (int i = b0; i < b1; i += 16) {
-            double av[16];
-            unsigned long long bv[16];
-#pragma unroll
-            for (int k = 0; k < 16; ++k) {
-                const size_t idx = (size_t)((i + k < b1) ? i + k : b0) * DSGC_JPAD + j;
-                av[k] = partA[idx];
-                bv[k] = partB[idx];
-            }
-#pragma unroll
-            for (int k = 0; k < 16; ++k) {
-                const bool in = i + k < b1;
-                a[k & 3] += in ? av[k] : 0.0;
-                b[k & 3] += in ? bv[k] : 0ull;
-            }
-        }
-    }
-    sA[seg][j] = (a[0] + a[1]) + (a[2] + a[3]);
-    sB[seg][j] = b[0] + b[1] + b[2] + b[3];
+    // ---- last block: sum the sets, Eq.6 per candidate, smallest deviation (ties: smallest j, i.e.
+    // the largest clip value for decreasing ratios).  Every addition is in a fixed order. ----------
+    __shared__ long long f_part[4][DSGC_JPAD][3];
+    __shared__ double f_g[4];
+    __shared__ double f_dev[DSGC_JPAD];
     {
-        // G: each segment's wave sums its blocks, lane-strided, then a shuffle tree
-        double g = 0.0;
-        for (int i = b0 + j; i < b1; i += 64) g += partG[i];
-        g = wave_sum(g);
-        if (j == 0) sG[seg] = g;
+        const int j = threadIdx.x & 63, part = threadIdx.x >> 6;
+        long long t[3] = {0, 0, 0};
+        if (j < n_cand) {
+            long long v[DSGC_GROUPS / 4][3];
+#pragma unroll
+            for (int k = 0; k < DSGC_GROUPS / 4; ++k)
+#pragma unroll
+                for (int q = 0; q < 3; ++q)
+                    v[k][q] = (long long)__hip_atomic_load(&acc[((size_t)(4 * k + part) * DSGC_JPAD + j) * 3 + q],
+                                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+            for (int k = 0; k < DSGC_GROUPS / 4; ++k)
+#pragma unroll
+                for (int q = 0; q < 3; ++q) t[q] += v[k][q];
+        }
+#pragma unroll
+        for (int q = 0; q < 3; ++q) f_part[part][j][q] = t[q];
+        // G: the absmax pass's per-block sums of squares
+        double gs = 0.0;
+        for (int i = threadIdx.x; i < nparts; i += 256) gs += partG[i];
+        gs = wave_sum(gs);
+        if (j == 0) f_g[part] = gs;
     }
     __syncthreads();
     if (threadIdx.x < 64) {
+        const int j = threadIdx.x;
         double d = 0.0;
         if (j < n_cand) {
-            double At = 0.0, Gt = 0.0;
-            unsigned long long Bi = 0;
+            long long t[3];
 #pragma unroll
-            for (int k = 0; k < DSGC_SEGS; ++k) {
-                At += sA[k][j];
-                Bi += sB[k][j];
-                Gt += sG[k];
-            }
-            const double Bt = (double)Bi;
+            for (int q = 0; q < 3; ++q) t[q] = (f_part[0][j][q] + f_part[1][j][q]) + (f_part[2][j][q] + f_part[3][j][q]);
+            // A = (sumH * 2^22 + sumL) * 2^(e-44); the integer totals are exact, the conversions round once
+            const double At = ldexp((double)t[0] * 4194304.0 + (double)t[1], e2 - 44);
+            const double Bt = (double)t[2];
+            const double Gt = (f_g[0] + f_g[1]) + (f_g[2] + f_g[3]);
             if (Gt == 0.0) d = 0.0;
             else if (Bt == 0.0) d = 1.0;
             else d = 1.0 - At / (sqrt(Gt) * sqrt(Bt));
             if (dev_all_out) dev_all_out[j] = d;
         }
-        sD[j] = d;
+        f_dev[j] = d;
     }
     __syncthreads();
     if (threadIdx.x == 0) {
         int best = 0;
         for (int k = 1; k < n_cand; ++k)
-            if (sD[k] < sD[best]) best = k;
-        if (M == 0.0f) best = 0;
-        *clip_out = __fmul_rn(M, ratios[best]);
-        *dev_out = sD[best];
+            if (f_dev[k] < f_dev[best]) best = k;
+        if (Mn == 0.0f) best = 0;
+        *clip_out = __fmul_rn(Mn, ratios[best]);
+        *dev_out = f_dev[best];
     }
 }
 
@@ -284,28 +335,24 @@ hipError_t launch_dsgc(const float* g, size_t n, const float* ratios, int n_cand
                        uint64_t seed, const DsgcWs& ws, int nparts_absmax, float* clip_out,
                        double* dev_out, double* dev_all_out, hipStream_t st) {
     const int nchunks = (n_cand + DSGC_JC - 1) / DSGC_JC;
-    // about two blocks per compute unit in total; every candidate chunk uses the same x-grid so
-    // that the partial arrays have one row per x-block
+    // about three blocks per compute unit in total; every candidate chunk walks the same x-grid
     int blocks = dsgc_blocks(n);
     const int cap = (DSGC_MAX_BLOCKS + nchunks - 1) / nchunks;
     if (blocks > cap) blocks = cap;
     const uint32_t slo = (uint32_t)seed, shi = seed_hi_term(seed);
     dim3 grid(blocks, nchunks);
-    {
     KernelTimer kt(KID_DSGC_SWEEP, st);
     if (stochastic)
         hipLaunchKernelGGL((dsgc_sweep_kernel<true>), grid, dim3(256), 0, st, g, n, ratios, n_cand,
-                           ws.absmax_part, nparts_absmax, slo, shi, ws.absmax, ws.partA, ws.partB, ws.partG);
+                           ws.absmax_part, nparts_absmax, slo, shi, ws.acc, ws.ticket, ws.partG, clip_out,
+                           dev_out, dev_all_out);
     else
         hipLaunchKernelGGL((dsgc_sweep_kernel<false>), grid, dim3(256), 0, st, g, n, ratios, n_cand,
-                           ws.absmax_part, nparts_absmax, slo, shi, ws.absmax, ws.partA, ws.partB, ws.partG);
-    }
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    KernelTimer kt(KID_DSGC_FINISH, st);
-    hipLaunchKernelGGL(dsgc_finish_kernel, dim3(1), dim3(1024), 0, st, ws.partA, ws.partB, ws.partG,
-                       blocks, ratios, n_cand, ws.absmax, clip_out, dev_out, dev_all_out);
+                           ws.absmax_part, nparts_absmax, slo, shi, ws.acc, ws.ticket, ws.partG, clip_out,
+                           dev_out, dev_all_out);
     return hipGetLastError();
 }
+
+size_t dsgc_acc_words() { return (size_t)DSGC_GROUPS * DSGC_JPAD * 3; }
 
 }  // namespace int8t

@@ -19,7 +19,10 @@ struct DevPartial {
 
 // ---- quantize.hip ---------------------------------------------------------------------------
 // max|x| per block -> part[0..nparts); returns the number of partials through *nparts.
-hipError_t launch_absmax(const float* x, size_t n, float* part, int* nparts, hipStream_t st);
+// sumsq: nullptr, or kMaxPartials doubles that receive per-block sums of squares; then the pass
+// also clears the nzero 64-bit words at zero (the clip search's accumulators and ticket)
+hipError_t launch_absmax(const float* x, size_t n, float* part, int* nparts, hipStream_t st, double* sumsq = nullptr,
+                         unsigned long long* zero = nullptr, int nzero = 0);
 
 struct QuantArgs {
     const float* x;
@@ -44,12 +47,12 @@ hipError_t launch_deviation_finish(const DevPartial* part, int nparts, double* d
 // ---- dsgc.hip -------------------------------------------------------------------------------
 struct DsgcWs {
     float* absmax_part;          // kMaxPartials floats
-    float* absmax;               // 1 float (written by the sweep)
-    double* partA;               // [nblocks][jpad]
-    unsigned long long* partB;   // [nblocks][jpad]
-    double* partG;               // [nblocks]
+    unsigned long long* acc;     // dsgc_acc_words() 64-bit accumulators, then the ticket word; cleared by the absmax pass
+    unsigned int* ticket;
+    double* partG;               // [kMaxPartials]: per-block sums of g^2 from the absmax pass
 };
 int dsgc_blocks(size_t n);
+size_t dsgc_acc_words();
 hipError_t launch_dsgc(const float* g, size_t n, const float* ratios, int n_cand, int stochastic,
                        uint64_t seed, const DsgcWs& ws, int nparts_absmax, float* clip_out,
                        double* dev_out, double* dev_all_out, hipStream_t st);

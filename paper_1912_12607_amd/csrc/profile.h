@@ -14,7 +14,6 @@ enum KernelId : int {
     KID_QUANTIZE_WGT,
     KID_DEVIATION_FINISH,
     KID_DSGC_SWEEP,
-    KID_DSGC_FINISH,
     KID_IGEMM,
     KID_BAND,
     KID_WGRAD,

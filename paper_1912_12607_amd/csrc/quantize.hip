@@ -11,39 +11,67 @@
 namespace int8t {
 
 // ---------------------------------------------------------------------------------------------
-// absmax: grid-stride float4 sweep, one partial per block.
+// absmax: grid-stride float4 sweep, one partial per block.  SUMSQ also sums the squares in fp64
+// (the |g|^2 of Eq.6; the pass is bound by HBM, the extra arithmetic is free), one partial per
+// block, summed in a fixed order, and clears the clip search's accumulators (the sweep that
+// follows adds into them).
 // ---------------------------------------------------------------------------------------------
+template <bool SUMSQ>
 __global__ __launch_bounds__(256) void absmax_kernel(const float* __restrict__ x, size_t n,
-                                                     float* __restrict__ part) {
+                                                     float* __restrict__ part, double* __restrict__ sumsq,
+                                                     unsigned long long* __restrict__ zero, int nzero) {
     __shared__ float lds4[4];
+    __shared__ double ldsd[4];
+    if (SUMSQ) {
+        for (int z = blockIdx.x * 256 + threadIdx.x; z < nzero; z += gridDim.x * 256) zero[z] = 0ull;
+    }
     const size_t n4 = n >> 2;
     const float4* __restrict__ x4 = reinterpret_cast<const float4*>(x);
     float m = 0.0f;
+    double q[4] = {0.0, 0.0, 0.0, 0.0};
+    auto take = [&](const float4& a) {
+        m = fmaxf(m, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
+        if (SUMSQ) {
+            q[0] = fma((double)a.x, (double)a.x, q[0]);
+            q[1] = fma((double)a.y, (double)a.y, q[1]);
+            q[2] = fma((double)a.z, (double)a.z, q[2]);
+            q[3] = fma((double)a.w, (double)a.w, q[3]);
+        }
+    };
     const size_t stride = (size_t)gridDim.x * 256;
     size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     // four independent 16-byte loads in flight per thread
     for (; i + 3 * stride < n4; i += 4 * stride) {
         float4 a = x4[i], b = x4[i + stride], c = x4[i + 2 * stride], d = x4[i + 3 * stride];
-        m = fmaxf(m, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
-        m = fmaxf(m, fmaxf(fmaxf(fabsf(b.x), fabsf(b.y)), fmaxf(fabsf(b.z), fabsf(b.w))));
-        m = fmaxf(m, fmaxf(fmaxf(fabsf(c.x), fabsf(c.y)), fmaxf(fabsf(c.z), fabsf(c.w))));
-        m = fmaxf(m, fmaxf(fmaxf(fabsf(d.x), fabsf(d.y)), fmaxf(fabsf(d.z), fabsf(d.w))));
+        take(a);
+        take(b);
+        take(c);
+        take(d);
     }
-    for (; i < n4; i += stride) {
-        float4 a = x4[i];
-        m = fmaxf(m, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
+    for (; i < n4; i += stride) take(x4[i]);
+    if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
+        const float v = x[(n4 << 2) + threadIdx.x];
+        m = fmaxf(m, fabsf(v));
+        if (SUMSQ) q[0] = fma((double)v, (double)v, q[0]);
     }
-    if (blockIdx.x == 0 && threadIdx.x < (n & 3)) m = fmaxf(m, fabsf(x[(n4 << 2) + threadIdx.x]));
     m = block_max_256(m, lds4);
     if (threadIdx.x == 0) part[blockIdx.x] = m;
+    if (SUMSQ) {
+        const double t = wave_sum((q[0] + q[1]) + (q[2] + q[3]));
+        if ((threadIdx.x & 63) == 0) ldsd[threadIdx.x >> 6] = t;
+        __syncthreads();
+        if (threadIdx.x == 0) sumsq[blockIdx.x] = (ldsd[0] + ldsd[1]) + (ldsd[2] + ldsd[3]);
+    }
 }
 
-hipError_t launch_absmax(const float* x, size_t n, float* part, int* nparts, hipStream_t st) {
+hipError_t launch_absmax(const float* x, size_t n, float* part, int* nparts, hipStream_t st, double* sumsq,
+                         unsigned long long* zero, int nzero) {
     size_t want = (n / 4 + 256 * 8 - 1) / (256 * 8);   // >= 8 float4 per thread before adding blocks
     int blocks = (int)(want < 1 ? 1 : (want > (size_t)kMaxPartials ? (size_t)kMaxPartials : want));
     *nparts = blocks;
     KernelTimer kt(KID_ABSMAX, st);
-    hipLaunchKernelGGL(absmax_kernel, dim3(blocks), dim3(256), 0, st, x, n, part);
+    if (sumsq) hipLaunchKernelGGL(absmax_kernel<true>, dim3(blocks), dim3(256), 0, st, x, n, part, sumsq, zero, nzero);
+    else hipLaunchKernelGGL(absmax_kernel<false>, dim3(blocks), dim3(256), 0, st, x, n, part, sumsq, zero, 0);
     return hipGetLastError();
 }
 

@@ -24,8 +24,13 @@ def align256(v: int) -> int:
 
 
 class LayerStep:
-    def __init__(self, L: Layer, n_cand: int = 32, keep_acc: bool = False, device: str = "cuda:0"):
+    def __init__(self, L: Layer, n_cand: int = 32, keep_acc: bool = False, device: str = "cuda:0",
+                 requantize_deviation: bool = True):
+        """requantize_deviation: also let the quantizer of g_z report Eq.6 for the codes it wrote (into
+        dev_final).  The clip search has already returned the same d_c (dev_search), which is what Eq.7
+        consumes, so a training step can leave this off."""
         self.L, self.n_cand, self.dev = L, n_cand, torch.device(device)
+        self.requantize_deviation = requantize_deviation
         self.depthwise = L.groups != 1
         self.desc = B.make_desc(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad, L.groups)
         self.act_kind = B.ACT_PLANAR if self.depthwise else B.ACT
@@ -81,7 +86,7 @@ class LayerStep:
 
     def quantize_dy(self, seed: int, stream=None):
         B.int8t_quantize(self.dy, self.L.y_shape, self.act_kind, self.clip, B.ROUND_STOCHASTIC, seed,
-                         self.dyq, self.sdy, self.dev_final, self.ws, stream)
+                         self.dyq, self.sdy, self.dev_final if self.requantize_deviation else None, self.ws, stream)
 
     def fwd(self, stream=None):
         B.int8t_conv_fwd(self.desc, self.xq, self.sx, self.wq, self.sw, self.y, self.y_acc, None, stream)
