@@ -24,6 +24,7 @@ constexpr size_t BAND_LDS_MAX = 80 * 1024;   // two blocks per compute unit
 constexpr int BAND_STAGE = 12;               // staged 16-byte granules per thread and band, at most
 constexpr int BAND_MAXG = 64;                // reduction granules (16 bytes each) per output row, at most
 constexpr int BAND_WJ = BAND_MAXG / 4;       // weight granules per thread
+constexpr int BAND_REG_ROWS = 4;             // window rows of the register-weight variant, at most
 
 // odd pitch (in 16-byte granules): rows of a tile read at one granule index land in distinct banks
 __host__ __device__ inline int odd_pitch(int granules) { return (granules & 1) ? granules : granules + 1; }
@@ -231,6 +232,178 @@ __global__ __launch_bounds__(256) void band_kernel(const IgemmArgs a, int BP, in
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Variant with the weights in REGISTERS.  In the kernel above every k-step of a wave reads two
+// weight fragments and one pixel fragment from LDS for two MFMAs, and with eight waves per compute
+// unit the LDS port, not the matrix pipeline, sets the pace.  The weight fragments of a lane never
+// change, though: lane (row, half) always multiplies rows {row, 32 + row} of the filter matrix.
+// When the whole reduction is short (NKS k-steps, known at compile time) a lane keeps its 2*NKS
+// fragments in registers for the block's lifetime and LDS serves the pixel fragment only -- one
+// 16-byte read per two MFMAs.  The k-loop is fully unrolled; the tap offsets are scalars.
+// The epilogue of a band is deferred: the scaled results wait in registers and are stored a few
+// at a time between the MFMAs of the NEXT band, so the write stream and the matrix pipeline run
+// side by side instead of taking turns.
+// Needs an even number of channel granules (then the two halves of a k-step share a filter tap),
+// at most 64 output rows, stride 1, a band of at most 128 pixels (one 32-pixel tile per wave) and a
+// window of at most 4 rows of at most 256 granules (one granule per thread and row).
+// ---------------------------------------------------------------------------------------------
+struct BandRegTab {
+    int koff[18];   // LDS offset (granules) of every k-step: tap shift + first channel granule of the pair
+};
+
+template <bool DGRAD, int NKS>
+__global__ __launch_bounds__(256, 2) void band_reg_kernel(const IgemmArgs a, int BP, int nbands_h, int nbands,
+                                                          const BandRegTab tab) {
+    extern __shared__ __attribute__((aligned(16))) uint4 lds[];
+    const int Cg16 = a.Ca >> 4;
+    const int G = 2 * NKS;                    // = R * S * Cg16 (host)
+    const int PG = odd_pitch(Cg16);
+    const int WH = BP + a.R - 1, WW = a.OW + a.S - 1;
+    uint4* __restrict__ xW = lds;             // [WH*WW pixels][PG]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6, half = lane >> 5, l32 = lane & 31;
+    const int drmin = DGRAD ? (a.pad_h - (a.R - 1)) : -a.pad_h;
+    const int dsmin = DGRAD ? (a.pad_w - (a.S - 1)) : -a.pad_w;
+
+    // (weights are fetched after the first window has been requested, see below)
+
+    // ---- staging plan: thread = one 16-byte column granule of the window (a window row has at most
+    // 256 granules), slot k = window row k ------------------------------------------------------------
+    const int rowgran = WW * Cg16;
+    int s_goff = -1, s_ldst = 0;               // s_goff -1: padding column or no column for this thread
+    if (tid < rowgran) {
+        const int wx = tid / Cg16, cg = tid - wx * Cg16;
+        const int iw = dsmin + wx;
+        s_ldst = wx * PG + cg;
+        if ((unsigned)iw < (unsigned)a.IW) s_goff = iw * a.Ca + cg * 16;
+    }
+    const bool s_col = tid < rowgran;
+    const int rowpitch = WW * PG;
+
+    // ---- per-lane output bookkeeping: pixel p of the band, rows 4*half + ... ----------------------
+    const int npix = BP * a.OW;
+    const int OHW = a.OH * a.OW;
+    const int p = wave * 32 + l32;
+    const bool pvalid = p < npix;
+    const int pp = pvalid ? p : 0;
+    const int pl = pp / a.OW, ql = pp - pl * a.OW;
+    const int pb = (pl * WW + ql) * PG + half;                     // + koff[ks]
+    const uint32_t obase = (uint32_t)((4 * half) * OHW + pl * a.OW + ql);
+    const float scale = __fmul_rn(a.sa[0], a.sb[0]);
+
+    uint4 pre[BAND_REG_ROWS];
+    auto issue = [&](int band) {
+        const int n = band / nbands_h;
+        const int oh0 = (band - n * nbands_h) * BP;
+        const int8_t* __restrict__ img = a.act + (size_t)n * a.IH * a.IW * a.Ca;
+#pragma unroll
+        for (int k = 0; k < BAND_REG_ROWS; ++k) {
+            pre[k] = make_uint4(0, 0, 0, 0);
+            const int ih = oh0 + drmin + k;
+            if (k < WH && s_goff >= 0 && (unsigned)ih < (unsigned)a.IH)
+                pre[k] = *reinterpret_cast<const uint4*>(img + (size_t)ih * a.IW * a.Ca + s_goff);
+        }
+    };
+    if ((int)blockIdx.x < nbands) issue(blockIdx.x);
+
+    // ---- weight fragments, once per block, straight from global memory.  Buffer loads: a row
+    // beyond a.rows lies outside the descriptor and reads as zero, so no select waits on the data.
+    v4i fa[NKS][2];
+    {
+        const __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<int8_t*>(a.wgt), 0, (uint32_t)a.rows * G * 16u, 0x00020000);
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            const uint32_t off = ((uint32_t)(m * 32 + l32) * G + half) * 16u;
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) {
+                const auto t4 = __builtin_amdgcn_raw_buffer_load_b128(wr, off + ks * 32u, 0, 0);
+                fa[ks][m] = v4i{(int)t4[0], (int)t4[1], (int)t4[2], (int)t4[3]};
+            }
+        }
+    }
+    int koff[NKS];
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) koff[ks] = tab.koff[ks];
+
+    // Results of the previous band, waiting to be stored.  Stores go through a buffer descriptor
+    // that spans one image of the output: a lane without a valid pixel carries an offset beyond the
+    // descriptor's range and rows beyond a.rows fall outside it too, and the hardware drops such
+    // writes -- no branches between the MFMAs.
+    float outv[2][16];
+    __amdgpu_buffer_rsrc_t prev_rsrc = __builtin_amdgcn_make_buffer_rsrc(a.out, 0, 0, 0x00020000);
+    uint32_t prev_voff = 0x80000000u;
+    const uint32_t img_bytes = (uint32_t)a.rows * OHW * 4u;       // <= 2^31 (host)
+    auto store_one = [&](int m, int v) {
+        const int rowu = m * 32 + 8 * (v >> 2) + (v & 3);            // + 4*half, already in the lane's offset
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(outv[m][v]), prev_rsrc,
+                                              prev_voff + (uint32_t)(rowu * OHW) * 4u, 0, 0);
+    };
+
+    for (int band = blockIdx.x; band < nbands; band += gridDim.x) {
+        const int n = band / nbands_h;
+        const int oh0 = (band - n * nbands_h) * BP;
+        __syncthreads();   // previous band's LDS reads are done
+#pragma unroll
+        for (int k = 0; k < BAND_REG_ROWS; ++k)
+            if (k < WH && s_col) xW[k * rowpitch + s_ldst] = pre[k];
+        __syncthreads();
+        if (band + (int)gridDim.x < nbands) issue(band + gridDim.x);
+
+        v16i acc[2];
+#pragma unroll
+        for (int m = 0; m < 2; ++m)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[m][v] = 0;
+
+        // pixel fragments are requested two k-steps ahead of their MFMAs
+        // (the LDS address of a k-step is one add of a scalar; the empty asm keeps the compiler from
+        // hoisting all NKS sums out of the band loop into registers the weights need)
+        auto frag = [&](int ks) {
+            int pbk = pb;
+            asm volatile("" : "+v"(pbk));
+            return xW[pbk + koff[ks]];
+        };
+        uint4 tb0 = frag(0);
+        uint4 tb1 = frag(NKS > 1 ? 1 : 0);
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) {
+            const v4i fb = v4i{(int)tb0.x, (int)tb0.y, (int)tb0.z, (int)tb0.w};
+            tb0 = tb1;
+            if (ks + 2 < NKS) tb1 = frag(ks + 2 < NKS ? ks + 2 : 0);
+            acc[0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[ks][0], fb, acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[ks][1], fb, acc[1], 0, 0, 0);
+            // the previous band's 32 values, spread evenly over the k-steps
+#pragma unroll
+            for (int q = (32 * ks) / NKS; q < (32 * (ks + 1)) / NKS; ++q) store_one(q >> 4, q & 15);
+        }
+
+        // ---- Eq.2; the stores follow during the next band (or after the loop) -----------------------
+        const size_t bandoff = (size_t)n * a.rows * OHW + (size_t)oh0 * a.OW;
+        const bool ok = pvalid && oh0 + pl < a.OH;
+        if (a.acc) {
+            int32_t* __restrict__ accb = a.acc + bandoff;
+#pragma unroll
+            for (int m = 0; m < 2; ++m)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int rowu = m * 32 + 8 * (v >> 2) + (v & 3);
+                    int32_t* __restrict__ rowp = accb + (size_t)rowu * OHW;
+                    if (ok && rowu + 4 * half < a.rows) rowp[obase] = acc[m][v];
+                }
+        }
+#pragma unroll
+        for (int m = 0; m < 2; ++m)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) outv[m][v] = __fmul_rn((float)acc[m][v], scale);
+        prev_rsrc = __builtin_amdgcn_make_buffer_rsrc(a.out + (size_t)n * a.rows * OHW, 0, img_bytes, 0x00020000);
+        prev_voff = ok ? (obase + (uint32_t)(oh0 * a.OW)) * 4u : 0x80000000u;
+    }
+#pragma unroll
+    for (int q = 0; q < 32; ++q) store_one(q >> 4, q & 15);
+}
+
 // Returns true (and launches) when the layer fits this kernel; false: use the implicit GEMM.
 bool launch_band(const IgemmArgs& a, hipStream_t st, hipError_t* err) {
     if (a.stride_h != 1 || a.stride_w != 1 || a.rows > 64 || a.OW > BAND_MAXPIX) return false;
@@ -256,6 +429,49 @@ bool launch_band(const IgemmArgs& a, hipStream_t st, hipError_t* err) {
     const int nbands_h = (a.OH + BP - 1) / BP;
     const int nbands = a.N * nbands_h;
     const int grid = nbands < 512 ? nbands : 512;
+    // register-resident weights when the reduction length is one of the instantiated ones
+    if (ntw == 1 && (Cg16 & 1) == 0 && WH <= BAND_REG_ROWS && WW * Cg16 <= 256 &&
+        (size_t)a.rows * a.OH * a.OW <= ((size_t)1 << 29)) {
+        typedef void (*kern_t)(const IgemmArgs, int, int, int, const BandRegTab);
+        kern_t kr = nullptr;
+        int slot = -1;
+#define BR(NK, SL)                                                                          \
+    if (G == 2 * NK) {                                                                       \
+        kr = a.dgrad ? (kern_t)band_reg_kernel<true, NK> : (kern_t)band_reg_kernel<false, NK>; \
+        slot = 2 * SL + (a.dgrad ? 1 : 0);                                                   \
+    }
+        BR(2, 0) BR(4, 1) BR(9, 2) BR(18, 3)
+#undef BR
+        if (kr) {
+            const size_t ldsr = (size_t)WH * WW * odd_pitch(Cg16) * 16;
+            static bool attr_done_r[8] = {};
+            if (!attr_done_r[slot]) {
+                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kr),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)BAND_LDS_MAX);
+                if (e != hipSuccess) { *err = e; return true; }
+                attr_done_r[slot] = true;
+            }
+            BandRegTab tab = {};
+            {
+                const int PG = odd_pitch(Cg16);
+                const int drmin = a.dgrad ? (a.pad_h - (a.R - 1)) : -a.pad_h;
+                const int dsmin = a.dgrad ? (a.pad_w - (a.S - 1)) : -a.pad_w;
+                for (int ks = 0; 2 * ks < G; ++ks) {
+                    const int g = 2 * ks, tap = g / Cg16, cg = g - tap * Cg16;
+                    const int r = tap / a.S, sx = tap - r * a.S;
+                    const int dr = a.dgrad ? (a.pad_h - r) : (r - a.pad_h);
+                    const int ds = a.dgrad ? (a.pad_w - sx) : (sx - a.pad_w);
+                    tab.koff[ks] = ((dr - drmin) * WW + (ds - dsmin)) * PG + cg;
+                }
+            }
+            {
+                KernelTimer kt(KID_BAND, st);
+                hipLaunchKernelGGL(kr, dim3(grid), dim3(256), ldsr, st, a, BP, nbands_h, nbands, tab);
+            }
+            *err = hipGetLastError();
+            return true;
+        }
+    }
     const int mt = a.rows > 32 ? 2 : 1;
     const int uni = (a.rows % 8 == 0) ? 1 : 0;
     const int variant = (a.dgrad ? 8 : 0) + (mt - 1) * 4 + (ntw - 1) * 2 + uni;

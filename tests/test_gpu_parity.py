@@ -193,6 +193,11 @@ CONV_SHAPES = [
     (2, 12, 9, 9, 12, 3, 3, (1, 1), (1, 1), 12),      # depthwise
     (1, 5, 11, 8, 5, 3, 3, (2, 2), (1, 1), 5),        # depthwise stride 2
     (2, 7, 6, 9, 7, 5, 3, (1, 2), (2, 0), 7),         # depthwise odd filter
+    # small filter banks with an even number of channel granules (weights held in registers)
+    (2, 64, 7, 20, 64, 3, 3, (1, 1), (1, 1), 1),
+    (3, 32, 9, 13, 40, 3, 3, (1, 1), (1, 1), 1),
+    (2, 64, 6, 10, 24, 1, 1, (1, 1), (0, 0), 1),
+    (2, 128, 5, 9, 64, 1, 1, (1, 1), (0, 0), 1),
 ]
 
 
