@@ -305,7 +305,17 @@ __global__ __launch_bounds__(256, 2) void band_reg_kernel(const IgemmArgs a, int
                 pre[k] = *reinterpret_cast<const uint4*>(img + (size_t)ih * a.IW * a.Ca + s_goff);
         }
     };
-    if ((int)blockIdx.x < nbands) issue(blockIdx.x);
+    // Bands of a block: workgroups are dealt to the 8 XCDs round-robin, so workgroup b runs on XCD
+    // b % 8.  Each XCD gets a contiguous range of bands and its workgroups walk it side by side:
+    // neighbouring bands, which share input rows, then meet in the same L2.
+    int band_first = blockIdx.x, band_step = gridDim.x, band_end = nbands;
+    if ((gridDim.x & 7) == 0) {
+        const int xcd = blockIdx.x & 7;
+        band_first = (int)(((long long)nbands * xcd) >> 3) + (int)(blockIdx.x >> 3);
+        band_end = (int)(((long long)nbands * (xcd + 1)) >> 3);
+        band_step = gridDim.x >> 3;
+    }
+    if (band_first < band_end) issue(band_first);
 
     // ---- weight fragments, once per block, straight from global memory.  Buffer loads: a row
     // beyond a.rows lies outside the descriptor and reads as zero, so no select waits on the data.
@@ -341,7 +351,7 @@ __global__ __launch_bounds__(256, 2) void band_reg_kernel(const IgemmArgs a, int
                                               prev_voff + (uint32_t)(rowu * OHW) * 4u, 0, 0);
     };
 
-    for (int band = blockIdx.x; band < nbands; band += gridDim.x) {
+    for (int band = band_first; band < band_end; band += band_step) {
         const int n = band / nbands_h;
         const int oh0 = (band - n * nbands_h) * BP;
         __syncthreads();   // previous band's LDS reads are done
@@ -349,7 +359,7 @@ __global__ __launch_bounds__(256, 2) void band_reg_kernel(const IgemmArgs a, int
         for (int k = 0; k < BAND_REG_ROWS; ++k)
             if (k < WH && s_col) xW[k * rowpitch + s_ldst] = pre[k];
         __syncthreads();
-        if (band + (int)gridDim.x < nbands) issue(band + gridDim.x);
+        if (band + band_step < band_end) issue(band + band_step);
 
         v16i acc[2];
 #pragma unroll
