@@ -58,12 +58,13 @@ class LayerStep:
         self.dx_acc = torch.empty(L.x_shape, dtype=i32, device=d) if keep_acc else None
         self.dw_acc = torch.empty(L.w_shape, dtype=i32, device=d) if keep_acc else None
         n_y = int(np.prod(L.y_shape))
-        ws = max(B.int8t_quantize_workspace_bytes(L.x_shape, self.act_kind),
-                 B.int8t_quantize_workspace_bytes(L.w_shape, self.wgt_kind),
-                 B.int8t_quantize_workspace_bytes(L.y_shape, self.act_kind),
-                 B.int8t_workspace_bytes(B.OP_DSGC, None, n_y, n_cand),
-                 B.int8t_workspace_bytes(B.OP_CONV_BWD_WEIGHT, self.desc), 256)
-        self.ws = torch.empty(ws, dtype=torch.uint8, device=d)
+        # one scratch buffer per tensor's chain of calls, so that a caller may put the chains on different streams
+        u8 = torch.uint8
+        self.ws_x = torch.empty(max(256, B.int8t_quantize_workspace_bytes(L.x_shape, self.act_kind)), dtype=u8, device=d)
+        self.ws_w = torch.empty(max(256, B.int8t_quantize_workspace_bytes(L.w_shape, self.wgt_kind)), dtype=u8, device=d)
+        self.ws_dy = torch.empty(max(256, B.int8t_quantize_workspace_bytes(L.y_shape, self.act_kind),
+                                     B.int8t_workspace_bytes(B.OP_DSGC, None, n_y, n_cand)), dtype=u8, device=d)
+        self.ws = torch.empty(max(256, B.int8t_workspace_bytes(B.OP_CONV_BWD_WEIGHT, self.desc)), dtype=u8, device=d)
 
     def upload(self, x: np.ndarray, w: np.ndarray, dy: np.ndarray, ratios: np.ndarray):
         self.x.copy_(torch.from_numpy(np.ascontiguousarray(x)))
@@ -74,19 +75,19 @@ class LayerStep:
     # -- the individual calls -------------------------------------------------------------------
     def quantize_x(self, stream=None):
         B.int8t_quantize(self.x, self.L.x_shape, self.act_kind, None, B.ROUND_NEAREST_EVEN, 0,
-                         self.xq, self.sx, None, self.ws, stream)
+                         self.xq, self.sx, None, self.ws_x, stream)
 
     def quantize_w(self, stream=None):
         B.int8t_quantize(self.w, self.L.w_shape, self.wgt_kind, None, B.ROUND_NEAREST_EVEN, 0,
-                         self.wq, self.sw, None, self.ws, stream)
+                         self.wq, self.sw, None, self.ws_w, stream)
 
     def dsgc(self, seed: int, stream=None):
         B.int8t_dsgc_clip(self.dy, self.dy.numel(), self.ratios, self.n_cand, B.ROUND_STOCHASTIC, seed,
-                          self.clip, self.dev_search, self.dev_all, self.ws, stream)
+                          self.clip, self.dev_search, self.dev_all, self.ws_dy, stream)
 
     def quantize_dy(self, seed: int, stream=None):
         B.int8t_quantize(self.dy, self.L.y_shape, self.act_kind, self.clip, B.ROUND_STOCHASTIC, seed,
-                         self.dyq, self.sdy, self.dev_final if self.requantize_deviation else None, self.ws, stream)
+                         self.dyq, self.sdy, self.dev_final if self.requantize_deviation else None, self.ws_dy, stream)
 
     def fwd(self, stream=None):
         B.int8t_conv_fwd(self.desc, self.xq, self.sx, self.wq, self.sw, self.y, self.y_acc, None, stream)
