@@ -183,8 +183,7 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
         for (int j = 0; j < JC; ++j) {
             uint32_t rp;
             if (STOCH) {
-                rp = top_bytes(stoch_fixed_s(x[0], inv[j], uf[0]), stoch_fixed_s(x[1], inv[j], uf[1]),
-                               stoch_fixed_s(x[2], inv[j], uf[2]), stoch_fixed_s(x[3], inv[j], uf[3]));
+                rp = stoch_codes4(x, inv[j], uf);
             } else {
                 rp = low_bytes(round_nearest_code(fabsf(x[0]), inv[j]), round_nearest_code(fabsf(x[1]), inv[j]),
                                round_nearest_code(fabsf(x[2]), inv[j]), round_nearest_code(fabsf(x[3]), inv[j]));
