@@ -25,7 +25,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int W2_BM = 64;              // filters per block
-constexpr int W2_LDS_BUDGET = 64 * 1024;
+constexpr int W2_LDS_BUDGET = 72 * 1024;   // two blocks per compute unit
 // 4x4 byte transpose: in d[i] = 4 channels of image i; out o[c] = channel c of images 0..3.
 __device__ __forceinline__ void transpose4x4(const uint32_t d[4], uint32_t o[4]) {
     // v_perm_b32 picks 4 bytes out of the 8 bytes {hi, lo}; selector byte 0-3 = lo, 4-7 = hi
@@ -44,10 +44,12 @@ __device__ __forceinline__ void transpose4x4(const uint32_t d[4], uint32_t o[4])
 // consecutive loader lanes (4 or 16 channel granules per pixel, consecutive pixels), so the
 // loader's stores (same channel-in-granule from every lane) and the MFMA operand reads (32
 // consecutive channels of one pixel) both spread over all banks.
+// The position is (pixel part) xor (channel part), so either side can be precomputed.
 template <int LOGW>
-__device__ __forceinline__ int swz(int pix, int c) {
-    return (pix << LOGW) + (c & ~15) + ((c & 15) ^ (((c >> 4) + 4 * pix) & 15));
-}
+__device__ __forceinline__ int swz_pix(int pix) { return (pix << LOGW) | ((pix & 3) << 2); }
+__device__ __forceinline__ int swz_ch(int c) { return (c & ~15) | ((c & 15) ^ ((c >> 4) & 15)); }
+template <int LOGW>
+__device__ __forceinline__ int swz(int pix, int c) { return swz_pix<LOGW>(pix) ^ swz_ch(c); }
 
 // Component q of a 16-byte register granule.
 __device__ __forceinline__ uint32_t comp(const uint4& v, int q) { return q == 0 ? v.x : q == 1 ? v.y : q == 2 ? v.z : v.w; }
@@ -65,16 +67,16 @@ __host__ __device__ inline void tap_extent(int t0, int nt, int S, int* rmin, int
     }
 }
 
-constexpr int W2_MAXSTEPS = 8;         // MFMA steps per chunk: at most 16 tile pixels
+constexpr int W2_MAXSTEPS = 16;        // MFMA steps per chunk: at most 32 tile pixels
 
 template <int TB, int CS>
-__global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
+__global__ __launch_bounds__(256, TB == 7 ? 1 : 2) void wgrad_kernel(const WgradArgs a) {
     constexpr int CT = 64 * CS;                   // channels per block
     constexpr int LOGCT = (CS == 1) ? 6 : 8;
     static_assert(CS == 1 || CS == 4, "channel tile is 64 or 256");
     extern __shared__ __attribute__((aligned(16))) uint4 lds[];
     uint4* __restrict__ xT = lds;                   // [window pixel][CT channels] granules
-    uint4* __restrict__ dyT = lds + a.xt_slots;     // [tile pixel][64 filters] granules, then one zero granule
+    uint4* __restrict__ dyT = lds + a.xt_slots;     // [tile pixel][64 filters] granules, then one all-zero pixel
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -100,21 +102,21 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
     }
     const int units = a.BP * a.BQ;
     const int nsteps = (units + 1) >> 1;
-    const int zero_slot = units * W2_BM;            // in dyT
-    if (tid == 0) dyT[zero_slot] = make_uint4(0, 0, 0, 0);
-
+    // one all-zero tile pixel behind the real ones: the partner of the last pixel of an odd tile
+    if (tid < W2_BM) dyT[units * W2_BM + tid] = make_uint4(0, 0, 0, 0);
     // LDS operand positions of every MFMA step; they depend on the tile geometry only.  A step
-    // feeds two tile pixels, one per half-wave, each with 16 images.
-    int a_off[W2_MAXSTEPS], x_pix[W2_MAXSTEPS];
-#pragma unroll
-    for (int s = 0; s < W2_MAXSTEPS; ++s) {
-        const int u = 2 * s + half;
+    // feeds two tile pixels, one per half-wave, each with 16 images.  Entry u = 2*step + half:
+    // {pixel part of the gradient tile position, window pixel of the tile pixel}.
+    int2* __restrict__ stab = reinterpret_cast<int2*>(dyT + (units + 1) * W2_BM);
+    if (tid < 2 * W2_MAXSTEPS) {
+        const int u = tid;
         const bool uv = u < units;
         const int uu = uv ? u : 0;
         const int pl = uu / a.BQ, ql = uu - pl * a.BQ;
-        a_off[s] = uv ? swz<6>(uu, mt * 32 + l32) : zero_slot;
-        x_pix[s] = pl * a.stride_h * WW + ql * a.stride_w;
+        stab[u] = make_int2(swz_pix<6>(uv ? u : units), pl * a.stride_h * WW + ql * a.stride_w);
     }
+    const int2* __restrict__ const stab_h = stab + half;
+    const int a_ch = swz_ch(mt * 32 + l32);
     const int xc0 = ch * CS * 32 + l32;             // this lane's channel inside the block's tile (slab 0)
 
     v16i acc[TB][CS];
@@ -158,7 +160,7 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
     }
     // first granule of the task's 16 in LDS and the xor of swz() for them
     uint4* __restrict__ const t_row = (t_kind == 1) ? (dyT + (t_pix << 6) + 16 * t_g) : (xT + (t_pix << LOGCT) + 16 * t_g);
-    const int t_xor = (t_g + 4 * t_pix) & 15;
+    const int t_xor = (t_g ^ (4 * t_pix)) & 15;
 
     // Prefetch registers.  Loads are unconditional: a task with nothing to fetch (padding, ragged
     // tile edge, channel beyond the tensor) reads offset 0 of its tensor and is zeroed when it is
@@ -223,11 +225,12 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a) {
 #pragma unroll
         for (int s = 0; s < W2_MAXSTEPS; ++s) {
             if (s < nsteps) {
-                const uint4 ta = dyT[a_off[s]];
+                const int2 st = stab_h[2 * s];
+                const uint4 ta = dyT[st.x ^ a_ch];
                 const v4i fa = v4i{(int)ta.x, (int)ta.y, (int)ta.z, (int)ta.w};
 #pragma unroll
                 for (int j = 0; j < TB; ++j) {   // TB divides R*S: every tap of the group exists
-                    const int pix = x_pix[s] + tpix[j];
+                    const int pix = st.y + tpix[j];
 #pragma unroll
                     for (int i = 0; i < CS; ++i) {
                         const uint4 tb = xT[swz<LOGCT>(pix, xc0 + 32 * i)];
@@ -306,7 +309,45 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const WgradArgs a) {
 // Host-side plan: tile shapes, tap grouping, split count.  Shared by the workspace query and the
 // launch so that both see the same numbers.
 // ---------------------------------------------------------------------------------------------
+namespace {
+// The plan of the most recent geometry, per host thread: a layer is planned once, not per call.
+struct PlanCache {
+    int key[15];
+    WgradArgs plan;
+    bool valid;
+};
+thread_local PlanCache g_plan_cache = {};
+
+void plan_key(const WgradArgs* a, int key[15]) {
+    const int k[15] = {a->N, a->C, a->Cp, a->H, a->W, a->K, a->Kp, a->P, a->Q, a->R, a->S,
+                       a->stride_h, a->stride_w, a->pad_h, a->pad_w};
+    for (int i = 0; i < 15; ++i) key[i] = k[i];
+}
+void wgrad_plan_uncached(WgradArgs* a);
+}  // namespace
+
 void wgrad_plan(WgradArgs* a) {
+    int key[15];
+    plan_key(a, key);
+    PlanCache& c = g_plan_cache;
+    bool hit = c.valid;
+    for (int i = 0; hit && i < 15; ++i) hit = c.key[i] == key[i];
+    if (!hit) {
+        wgrad_plan_uncached(a);
+        for (int i = 0; i < 15; ++i) c.key[i] = key[i];
+        c.plan = *a;
+        c.valid = true;
+        return;
+    }
+    const WgradArgs& p = c.plan;
+    a->TB = p.TB; a->CS = p.CS; a->BP = p.BP; a->BQ = p.BQ; a->ntp = p.ntp; a->ntq = p.ntq;
+    a->ngrp = p.ngrp; a->chunks = p.chunks; a->splits = p.splits;
+    a->ktiles = p.ktiles; a->ctiles = p.ctiles; a->tapgroups = p.tapgroups;
+    a->xt_slots = p.xt_slots; a->lds_bytes = p.lds_bytes;
+}
+
+namespace {
+void wgrad_plan_uncached(WgradArgs* a) {
     const int RS = a->R * a->S;
     // taps per block / channel slabs per wave: one filter row of a 3-wide filter, a whole 1x7 or
     // 7x1 filter, a wide channel tile for 1x1, one tap at a time otherwise
@@ -319,33 +360,42 @@ void wgrad_plan(WgradArgs* a) {
     a->tapgroups = (RS + a->TB - 1) / a->TB;
     a->ktiles = (a->K + W2_BM - 1) / W2_BM;
     a->ctiles = (a->Cp + CT - 1) / CT;
-    // output-pixel tile: about 16 pixels, split evenly, shrunk until the staged window fits
-    int nq = (a->Q + 7) / 8;
-    int BQ = (a->Q + nq - 1) / nq;
-    int BP = 16 / BQ;
-    if (BP < 1) BP = 1;
-    if (BP > a->P) BP = a->P;
-    for (;;) {
-        int maxwin = 0;
-        for (int g = 0; g < a->tapgroups; ++g) {
-            const int t0 = g * a->TB, nt = (RS - t0 < a->TB) ? (RS - t0) : a->TB;
-            int rmin, rmax, smin, smax;
-            tap_extent(t0, nt, a->S, &rmin, &rmax, &smin, &smax);
-            const int WH = (BP - 1) * a->stride_h + (rmax - rmin) + 1;
-            const int WW = (BQ - 1) * a->stride_w + (smax - smin) + 1;
-            if (WH * WW > maxwin) maxwin = WH * WW;
+    // Output-pixel tile BP x BQ: the one that covers the most useful pixels per chunk among those
+    // whose staged window fits LDS, whose loader tasks fit one per thread and whose pixel count fits
+    // the unrolled MFMA steps.  (More pixels per chunk = more MFMAs per barrier pair and per
+    // transposed byte; tiles that divide P and Q waste nothing at the edges.)
+    int BP = 1, BQ = 1;
+    double best_score = -1.0;
+    for (int bp = 1; bp <= a->P && bp <= 2 * W2_MAXSTEPS; ++bp) {
+        for (int bq = 1; bq <= a->Q && bp * bq <= 2 * W2_MAXSTEPS; ++bq) {
+            int maxwin = 0;
+            for (int g = 0; g < a->tapgroups; ++g) {
+                const int t0 = g * a->TB, nt = (RS - t0 < a->TB) ? (RS - t0) : a->TB;
+                int rmin, rmax, smin, smax;
+                tap_extent(t0, nt, a->S, &rmin, &rmax, &smin, &smax);
+                const int WH = (bp - 1) * a->stride_h + (rmax - rmin) + 1;
+                const int WW = (bq - 1) * a->stride_w + (smax - smin) + 1;
+                if (WH * WW > maxwin) maxwin = WH * WW;
+            }
+            const size_t lds = (size_t)(maxwin * CT + (bp * bq + 1) * W2_BM) * 16 + 2 * W2_MAXSTEPS * sizeof(int2);
+            const int ntask = maxwin * (CT / 16) + bp * bq * 4;   // one loader task per thread
+            const bool fits = lds <= (size_t)W2_LDS_BUDGET && ntask <= 256;
+            if (!fits && !(bp == 1 && bq == 1)) continue;
+            const int ntp = (a->P + bp - 1) / bp, ntq = (a->Q + bq - 1) / bq;
+            const double cover = (double)a->P * a->Q / ((double)ntp * bp * ntq * bq);
+            // useful pixels per chunk, discounted by the fixed cost of a chunk (about 6 pixels' worth)
+            const double score = cover * (bp * bq) / (bp * bq + 6.0);
+            if (score > best_score) {
+                best_score = score;
+                BP = bp;
+                BQ = bq;
+                a->xt_slots = maxwin * CT;
+                a->lds_bytes = lds;
+            }
         }
-        a->xt_slots = maxwin * CT;
-        a->lds_bytes = (size_t)(a->xt_slots + BP * BQ * W2_BM + 1) * 16;
-        const int ntask = maxwin * (CT / 16) + BP * BQ * 4;   // one loader task per thread
-        if ((a->lds_bytes <= (size_t)W2_LDS_BUDGET && ntask <= 256 && BP * BQ <= 2 * W2_MAXSTEPS) ||
-            (BP == 1 && BQ == 1))
-            break;
-        if (BP > 1) BP = (BP + 1) / 2;
-        else BQ = (BQ + 1) / 2;
     }
     const int np = (a->P + BP - 1) / BP;
-    nq = (a->Q + BQ - 1) / BQ;
+    const int nq = (a->Q + BQ - 1) / BQ;
     a->BP = BP;
     a->BQ = BQ;
     a->ntp = np;
@@ -357,7 +407,7 @@ void wgrad_plan(WgradArgs* a) {
     // (blocks resident on the chip: registers allow two per compute unit for the narrow tiles, one
     // for the wide ones); a block pays a prologue plus its chunks; every split adds one write and
     // one read of the int32 partial tile set.  The constants are rough measurements in microseconds.
-    const int per_cu_regs = (a->TB == 7 || a->CS == 4) ? 1 : 2;
+    const int per_cu_regs = (a->TB == 7) ? 1 : 2;
     int per_cu_lds = (int)((160 * 1024) / a->lds_bytes);
     if (per_cu_lds < 1) per_cu_lds = 1;
     const int slots = 256 * (per_cu_regs < per_cu_lds ? per_cu_regs : per_cu_lds);
@@ -374,17 +424,28 @@ void wgrad_plan(WgradArgs* a) {
     }
     a->splits = splits;
 }
+}  // namespace
 
 hipError_t launch_wgrad(const WgradArgs& a, hipStream_t st) {
     dim3 grid(a.ktiles * a.ctiles * a.tapgroups, a.splits);
-#define LAUNCH(TBv, CSv) \
-    hipLaunchKernelGGL((wgrad_kernel<TBv, CSv>), grid, dim3(256), a.lds_bytes, st, a)
+    // the staged tiles may exceed the default 64 KB of dynamic LDS: raise the limit once per variant
+#define LAUNCH(TBv, CSv, SLOT)                                                                            \
+    do {                                                                                                  \
+        static bool attr_done = false;                                                                    \
+        if (!attr_done) {                                                                                 \
+            hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_kernel<TBv, CSv>),    \
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, W2_LDS_BUDGET); \
+            if (ea != hipSuccess) return ea;                                                              \
+            attr_done = true;                                                                             \
+        }                                                                                                 \
+        hipLaunchKernelGGL((wgrad_kernel<TBv, CSv>), grid, dim3(256), a.lds_bytes, st, a);                \
+    } while (0)
     {
         KernelTimer kt(KID_WGRAD, st);
-        if (a.TB == 1 && a.CS == 1) LAUNCH(1, 1);
-        else if (a.TB == 1 && a.CS == 4) LAUNCH(1, 4);
-        else if (a.TB == 3) LAUNCH(3, 1);
-        else if (a.TB == 7) LAUNCH(7, 1);
+        if (a.TB == 1 && a.CS == 1) LAUNCH(1, 1, 0);
+        else if (a.TB == 1 && a.CS == 4) LAUNCH(1, 4, 1);
+        else if (a.TB == 3) LAUNCH(3, 1, 2);
+        else if (a.TB == 7) LAUNCH(7, 1, 3);
         else return hipErrorInvalidValue;
     }
 #undef LAUNCH
