@@ -39,17 +39,15 @@ __device__ __forceinline__ void transpose4x4(const uint32_t d[4], uint32_t o[4])
     o[3] = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
 }
 
-// Granule index of channel c at pixel `pix` in a [pixel][2^LOGW channels] LDS tile.  Inside each
-// aligned group of 16 channels the position is xor-ed with a number that differs between the 16
-// consecutive loader lanes (4 or 16 channel granules per pixel, consecutive pixels), so the
-// loader's stores (same channel-in-granule from every lane) and the MFMA operand reads (32
-// consecutive channels of one pixel) both spread over all banks.
-// The position is (pixel part) xor (channel part), so either side can be precomputed.
-template <int LOGW>
-__device__ __forceinline__ int swz_pix(int pix) { return (pix << LOGW) | ((pix & 3) << 2); }
+// LDS tiles are [pixel][channels] in 16-byte granules with a pixel pitch of (channels + 4)
+// granules, and inside each aligned group of 16 channels the position is xor-ed with the group's
+// number.  The 16 consecutive loader lanes (4 or 16 channel granules per pixel, consecutive pixels)
+// store the same channel-in-granule and land in 16 different bank groups (the xor separates the
+// granules of a pixel, the pitch separates the pixels); the MFMA operand reads (32 consecutive
+// channels of one pixel) are a permutation inside each group.  The pixel part stays linear, so a
+// filter tap is a constant address offset.
+constexpr int W2_PAD = 4;
 __device__ __forceinline__ int swz_ch(int c) { return (c & ~15) | ((c & 15) ^ ((c >> 4) & 15)); }
-template <int LOGW>
-__device__ __forceinline__ int swz(int pix, int c) { return swz_pix<LOGW>(pix) ^ swz_ch(c); }
 
 // Component q of a 16-byte register granule.
 __device__ __forceinline__ uint32_t comp(const uint4& v, int q) { return q == 0 ? v.x : q == 1 ? v.y : q == 2 ? v.z : v.w; }
@@ -69,10 +67,13 @@ __host__ __device__ inline void tap_extent(int t0, int nt, int S, int* rmin, int
 
 constexpr int W2_MAXSTEPS = 16;        // MFMA steps per chunk: at most 32 tile pixels
 
+__host__ __device__ inline bool wgrad_xcd_mapping(int splits) { return splits >= 64 || (splits >= 8 && (splits & 7) == 0); }
+
 template <int TB, int CS>
-__global__ __launch_bounds__(256, TB == 7 ? 1 : 2) void wgrad_kernel(const WgradArgs a) {
+__global__ __launch_bounds__(256, 2) void wgrad_kernel(const WgradArgs a) {
     constexpr int CT = 64 * CS;                   // channels per block
-    constexpr int LOGCT = (CS == 1) ? 6 : 8;
+    constexpr int XP = CT + W2_PAD;               // pixel pitch of the input window tile
+    constexpr int YP = W2_BM + W2_PAD;            // pixel pitch of the gradient tile
     static_assert(CS == 1 || CS == 4, "channel tile is 64 or 256");
     extern __shared__ __attribute__((aligned(16))) uint4 lds[];
     uint4* __restrict__ xT = lds;                   // [window pixel][CT channels] granules
@@ -82,7 +83,24 @@ __global__ __launch_bounds__(256, TB == 7 ? 1 : 2) void wgrad_kernel(const Wgrad
     const int lane = tid & 63, wave = tid >> 6;
     const int mt = wave & 1, ch = wave >> 1, half = lane >> 5, l32 = lane & 31;
 
-    int ot = blockIdx.x;
+    // Workgroups are dealt to the 8 XCDs round-robin (workgroup b runs on XCD b % 8).  The output
+    // tiles of one reduction share -- the tap groups, channel and filter tiles that read the same
+    // input and gradient pixels -- are given to consecutive workgroups of ONE XCD, so those pixels
+    // are fetched into that XCD's L2 once.  Share z = 8 * (i / tiles) + xcd, tile = i % tiles, with
+    // i = b / 8; the grid is padded to whole groups of 8 shares and the surplus workgroups leave.
+    // With few shares (and not a multiple of 8) that would idle XCDs: then tiles simply follow each
+    // other.
+    const int out_tiles = a.ktiles * a.ctiles * a.tapgroups;
+    int zshare, ot;
+    if (wgrad_xcd_mapping(a.splits)) {
+        const int wg_i = blockIdx.x >> 3;
+        zshare = ((wg_i / out_tiles) << 3) + (int)(blockIdx.x & 7);
+        if (zshare >= a.splits) return;
+        ot = wg_i % out_tiles;
+    } else {
+        zshare = blockIdx.x / out_tiles;
+        ot = blockIdx.x - zshare * out_tiles;
+    }
     const int tg = ot % a.tapgroups;
     ot /= a.tapgroups;
     const int ct = ot % a.ctiles;
@@ -94,30 +112,32 @@ __global__ __launch_bounds__(256, TB == 7 ? 1 : 2) void wgrad_kernel(const Wgrad
     tap_extent(t0, nt, a.S, &rmin, &rmax, &smin, &smax);
     const int WH = (a.BP - 1) * a.stride_h + (rmax - rmin) + 1;
     const int WW = (a.BQ - 1) * a.stride_w + (smax - smin) + 1;
-    int tpix[TB];   // uniform: window pixel offset of each tap
+    int tpix[TB];   // uniform: LDS offset (granules) of each tap's pixel shift
 #pragma unroll
     for (int j = 0; j < TB; ++j) {
         const int t = t0 + ((j < nt) ? j : 0);
-        tpix[j] = __builtin_amdgcn_readfirstlane((t / a.S - rmin) * WW + (t % a.S - smin));
+        tpix[j] = __builtin_amdgcn_readfirstlane(((t / a.S - rmin) * WW + (t % a.S - smin)) * XP);
     }
     const int units = a.BP * a.BQ;
     const int nsteps = (units + 1) >> 1;
     // one all-zero tile pixel behind the real ones: the partner of the last pixel of an odd tile
-    if (tid < W2_BM) dyT[units * W2_BM + tid] = make_uint4(0, 0, 0, 0);
+    if (tid < W2_BM) dyT[units * YP + tid] = make_uint4(0, 0, 0, 0);
     // LDS operand positions of every MFMA step; they depend on the tile geometry only.  A step
     // feeds two tile pixels, one per half-wave, each with 16 images.  Entry u = 2*step + half:
-    // {pixel part of the gradient tile position, window pixel of the tile pixel}.
-    int2* __restrict__ stab = reinterpret_cast<int2*>(dyT + (units + 1) * W2_BM);
+    // {granule offset of the gradient tile pixel, granule offset of its window pixel}.
+    int2* __restrict__ stab = reinterpret_cast<int2*>(dyT + (units + 1) * YP);
     if (tid < 2 * W2_MAXSTEPS) {
         const int u = tid;
         const bool uv = u < units;
         const int uu = uv ? u : 0;
         const int pl = uu / a.BQ, ql = uu - pl * a.BQ;
-        stab[u] = make_int2(swz_pix<6>(uv ? u : units), pl * a.stride_h * WW + ql * a.stride_w);
+        stab[u] = make_int2((uv ? u : units) * YP, (pl * a.stride_h * WW + ql * a.stride_w) * XP);
     }
     const int2* __restrict__ const stab_h = stab + half;
     const int a_ch = swz_ch(mt * 32 + l32);
-    const int xc0 = ch * CS * 32 + l32;             // this lane's channel inside the block's tile (slab 0)
+    int x_ch[CS];                                   // this lane's channel positions inside the block's tile
+#pragma unroll
+    for (int i = 0; i < CS; ++i) x_ch[i] = swz_ch((ch * CS + i) * 32 + l32);
 
     v16i acc[TB][CS];
 #pragma unroll
@@ -127,8 +147,8 @@ __global__ __launch_bounds__(256, TB == 7 ? 1 : 2) void wgrad_kernel(const Wgrad
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[j][i][v] = 0;
 
-    const int c_begin = (int)(((uint32_t)a.chunks * blockIdx.y) / gridDim.y);   // chunks * splits < 2^31 (host)
-    const int c_end = (int)(((uint32_t)a.chunks * (blockIdx.y + 1)) / gridDim.y);
+    const int c_begin = (int)(((uint32_t)a.chunks * (uint32_t)zshare) / (uint32_t)a.splits);   // chunks * splits < 2^31 (host)
+    const int c_end = (int)(((uint32_t)a.chunks * (uint32_t)(zshare + 1)) / (uint32_t)a.splits);
     const int tiles_per_group = a.ntp * a.ntq;
     const int ntask_x = WH * WW * (CT / 16);    // input window: (window pixel, 16-channel granule)
     const int ntask = ntask_x + units * 4;      // + gradient tile: (tile pixel, 16-filter granule)
@@ -158,9 +178,9 @@ __global__ __launch_bounds__(256, TB == 7 ? 1 : 2) void wgrad_kernel(const Wgrad
             t_c = kt * W2_BM + 16 * t_g;
         }
     }
-    // first granule of the task's 16 in LDS and the xor of swz() for them
-    uint4* __restrict__ const t_row = (t_kind == 1) ? (dyT + (t_pix << 6) + 16 * t_g) : (xT + (t_pix << LOGCT) + 16 * t_g);
-    const int t_xor = (t_g ^ (4 * t_pix)) & 15;
+    // first granule of the task's 16 in LDS and the xor of swz_ch() for them
+    uint4* __restrict__ const t_row = (t_kind == 1) ? (dyT + t_pix * YP + 16 * t_g) : (xT + t_pix * XP + 16 * t_g);
+    const int t_xor = t_g & 15;
 
     // Prefetch registers.  Loads are unconditional: a task with nothing to fetch (padding, ragged
     // tile edge, channel beyond the tensor) reads offset 0 of its tensor and is zeroed when it is
@@ -193,30 +213,42 @@ __global__ __launch_bounds__(256, TB == 7 ? 1 : 2) void wgrad_kernel(const Wgrad
         }
     };
 
+    // 16 images x 16 channels -> sixteen [channel][16 images] granules, four channels at a time
+    auto commit = [&](uint32_t m0, uint32_t m1, uint32_t m2, uint32_t m3) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            uint32_t o[4][4];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const uint32_t d[4] = {comp(pre[4 * g], q), comp(pre[4 * g + 1], q), comp(pre[4 * g + 2], q),
+                                       comp(pre[4 * g + 3], q)};
+                transpose4x4(d, o[g]);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                t_row[(4 * q + j) ^ t_xor] = make_uint4(o[0][j] & m0, o[1][j] & m1, o[2][j] & m2, o[3][j] & m3);
+        }
+    };
+
     if (c_begin < c_end) issue(c_begin);
     for (int chunk = c_begin; chunk < c_end; ++chunk) {
         __syncthreads();   // the previous chunk's MFMA reads are done
         if (t_kind != 2) {
             if (!pre_ok) {
+                // padding, ragged tile edge or channel beyond the tensor: zeros
 #pragma unroll
-                for (int im = 0; im < 16; ++im) pre[im] = make_uint4(0, 0, 0, 0);
-            } else if (pre_nimg < 16) {
+                for (int k = 0; k < 16; ++k) t_row[k] = make_uint4(0, 0, 0, 0);
+            } else if (pre_nimg == 16) {
+                commit(0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu);
+            } else {
+                // last, partial image group: byte i of a granule is image i; images beyond N are zeroed
+                uint32_t m[4];
 #pragma unroll
-                for (int im = 0; im < 16; ++im)
-                    if (im >= pre_nimg) pre[im] = make_uint4(0, 0, 0, 0);
-            }
-            // 16 images x 16 channels -> sixteen [channel][16 images] granules, four channels at a time
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                uint32_t o[4][4];
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const uint32_t d[4] = {comp(pre[4 * g], q), comp(pre[4 * g + 1], q), comp(pre[4 * g + 2], q),
-                                           comp(pre[4 * g + 3], q)};
-                    transpose4x4(d, o[g]);
+                for (int k = 0; k < 4; ++k) {
+                    const int left = pre_nimg - 4 * k;
+                    m[k] = left >= 4 ? 0xffffffffu : left <= 0 ? 0u : ((1u << (8 * left)) - 1u);
                 }
-#pragma unroll
-                for (int j = 0; j < 4; ++j) t_row[(4 * q + j) ^ t_xor] = make_uint4(o[0][j], o[1][j], o[2][j], o[3][j]);
+                commit(m[0], m[1], m[2], m[3]);
             }
         }
         __syncthreads();
@@ -226,14 +258,14 @@ __global__ __launch_bounds__(256, TB == 7 ? 1 : 2) void wgrad_kernel(const Wgrad
         for (int s = 0; s < W2_MAXSTEPS; ++s) {
             if (s < nsteps) {
                 const int2 st = stab_h[2 * s];
-                const uint4 ta = dyT[st.x ^ a_ch];
+                const uint4 ta = dyT[st.x + a_ch];
                 const v4i fa = v4i{(int)ta.x, (int)ta.y, (int)ta.z, (int)ta.w};
 #pragma unroll
                 for (int j = 0; j < TB; ++j) {   // TB divides R*S: every tap of the group exists
-                    const int pix = st.y + tpix[j];
+                    const int pix = st.y + tpix[j];   // granule offset of the tap's window pixel
 #pragma unroll
                     for (int i = 0; i < CS; ++i) {
-                        const uint4 tb = xT[swz<LOGCT>(pix, xc0 + 32 * i)];
+                        const uint4 tb = xT[pix + x_ch[i]];
                         const v4i fb = v4i{(int)tb.x, (int)tb.y, (int)tb.z, (int)tb.w};
                         acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa, fb, acc[j][i], 0, 0, 0);
                     }
@@ -244,7 +276,7 @@ __global__ __launch_bounds__(256, TB == 7 ? 1 : 2) void wgrad_kernel(const Wgrad
 
     // partial[z][k][(tap,c)], channel fastest: 32 consecutive columns per store instruction
     const int ncolsp = RS * a.Cp;
-    int32_t* __restrict__ part = a.partial + (size_t)blockIdx.y * a.K * ncolsp;
+    int32_t* __restrict__ part = a.partial + (size_t)zshare * a.K * ncolsp;
 #pragma unroll
     for (int j = 0; j < TB; ++j) {
         if (j >= nt) continue;
@@ -377,7 +409,8 @@ void wgrad_plan_uncached(WgradArgs* a) {
                 const int WW = (bq - 1) * a->stride_w + (smax - smin) + 1;
                 if (WH * WW > maxwin) maxwin = WH * WW;
             }
-            const size_t lds = (size_t)(maxwin * CT + (bp * bq + 1) * W2_BM) * 16 + 2 * W2_MAXSTEPS * sizeof(int2);
+            const size_t lds = (size_t)(maxwin * (CT + W2_PAD) + (bp * bq + 1) * (W2_BM + W2_PAD)) * 16 +
+                               2 * W2_MAXSTEPS * sizeof(int2);
             const int ntask = maxwin * (CT / 16) + bp * bq * 4;   // one loader task per thread
             const bool fits = lds <= (size_t)W2_LDS_BUDGET && ntask <= 256;
             if (!fits && !(bp == 1 && bq == 1)) continue;
@@ -389,7 +422,7 @@ void wgrad_plan_uncached(WgradArgs* a) {
                 best_score = score;
                 BP = bp;
                 BQ = bq;
-                a->xt_slots = maxwin * CT;
+                a->xt_slots = maxwin * (CT + W2_PAD);
                 a->lds_bytes = lds;
             }
         }
@@ -407,7 +440,7 @@ void wgrad_plan_uncached(WgradArgs* a) {
     // (blocks resident on the chip: registers allow two per compute unit for the narrow tiles, one
     // for the wide ones); a block pays a prologue plus its chunks; every split adds one write and
     // one read of the int32 partial tile set.  The constants are rough measurements in microseconds.
-    const int per_cu_regs = (a->TB == 7) ? 1 : 2;
+    const int per_cu_regs = (a->TB == 7 || a->CS == 4) ? 2 : 3;   // by register count of the variants
     int per_cu_lds = (int)((160 * 1024) / a->lds_bytes);
     if (per_cu_lds < 1) per_cu_lds = 1;
     const int slots = 256 * (per_cu_regs < per_cu_lds ? per_cu_regs : per_cu_lds);
@@ -427,7 +460,8 @@ void wgrad_plan_uncached(WgradArgs* a) {
 }  // namespace
 
 hipError_t launch_wgrad(const WgradArgs& a, hipStream_t st) {
-    dim3 grid(a.ktiles * a.ctiles * a.tapgroups, a.splits);
+    const unsigned out_tiles = (unsigned)(a.ktiles * a.ctiles * a.tapgroups);
+    dim3 grid(wgrad_xcd_mapping(a.splits) ? out_tiles * 8u * (unsigned)((a.splits + 7) / 8) : out_tiles * (unsigned)a.splits);
     // the staged tiles may exceed the default 64 KB of dynamic LDS: raise the limit once per variant
 #define LAUNCH(TBv, CSv, SLOT)                                                                            \
     do {                                                                                                  \
