@@ -291,9 +291,14 @@ hipError_t launch_quantize_planar(const QuantArgs& a, hipStream_t st) {
 
 // ---------------------------------------------------------------------------------------------
 // Weights: fp32 K,Cg,R,S -> two int8 copies, [K][R][S][Cp] (forward / backward-weight view) and
-// [Cg][R][S][Kp] (backward-data view).  One thread per output dword; the tensors are small
-// (a few MB at most) and the strided reads hit L2.
+// [Cg][R][S][Kp] (backward-data view).  A block owns 16 filters x 16 channels x (up to 64) taps:
+// it reads, per filter, one contiguous run of 16 * taps floats, keeps the codes in LDS, and writes
+// both views as 16-byte granules (16 channels of one filter and tap; 16 filters of one channel and
+// tap).  Rows and channels beyond the tensor are zero codes, which fills the padded pitch.
 // ---------------------------------------------------------------------------------------------
+constexpr int QW_T = 16;
+constexpr int QW_TAPS = 64;
+
 template <bool STOCH, bool DEV>
 __global__ __launch_bounds__(256) void quantize_wgt_kernel(
     const float* __restrict__ w, int K, int Cg, int R, int S, int Cp, int Kp, size_t off2,
@@ -301,6 +306,7 @@ __global__ __launch_bounds__(256) void quantize_wgt_kernel(
     uint32_t seed_lo, uint32_t seed_hi_mul, int8_t* __restrict__ q, float* __restrict__ scale_out,
     DevPartial* __restrict__ devpart) {
     __shared__ float lds4[4];
+    __shared__ __attribute__((aligned(16))) int8_t tile[QW_T * QW_T * QW_TAPS];   // [filter][channel][tap]
     const float cval = resolve_clip(clip, absmax_part, nparts, lds4);
     float inv = inv_scale_of(cval);
     float sc = scale_of(cval);
@@ -308,73 +314,112 @@ __global__ __launch_bounds__(256) void quantize_wgt_kernel(
         inv = __fmul_rn(inv, kTwo24);        // the scaled value carries 24 fraction bits
         fp32_round_down_mode(inv, sc);
     }
-    if (blockIdx.x == 0 && threadIdx.x == 0) *scale_out = sc;
+    if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) *scale_out = sc;
 
     const int RS = R * S;
-    const size_t nd1 = (size_t)K * RS * (Cp / 4);
-    const size_t nd2 = (size_t)Cg * RS * (Kp / 4);
+    const int k0 = blockIdx.y * QW_T, c0 = blockIdx.x * QW_T;
     double A = 0.0, G = 0.0;
     unsigned long long B = 0;
-    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (t < nd1) {
-        const int c4 = (int)(t % (Cp / 4));
-        size_t rest = t / (Cp / 4);
-        const int rs = (int)(rest % RS);
-        const int k = (int)(rest / RS);
-        int code[4];
+    // small tensors spread their taps over blockIdx.z to have enough blocks
+    const int tpb = (RS + (int)gridDim.z - 1) / (int)gridDim.z;
+    const int rs_begin = blockIdx.z * tpb, rs_end = (rs_begin + tpb < RS) ? rs_begin + tpb : RS;
+    for (int rs0 = rs_begin; rs0 < rs_end; rs0 += QW_TAPS) {
+        const int nrs = (rs_end - rs0 < QW_TAPS) ? (rs_end - rs0) : QW_TAPS;
+        const int per_k = QW_T * nrs;
+        if (rs0 != rs_begin) __syncthreads();
+        const int cvalid = (Cg - c0 < QW_T) ? (Cg - c0) : QW_T;
+        if (nrs == RS) {
+            // all taps at once: a filter's 16 channels x taps are one contiguous run; a wave walks the
+            // runs of four filters, 64 consecutive floats per load
+            const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int c = 4 * c4 + j;
-            code[j] = 0;
-            if (c < Cg) {
-                const size_t idx = ((size_t)k * Cg + c) * RS + rs;
-                const float g32 = w[idx];
-                code[j] = quantize_one<STOCH>(g32, inv, seed_lo, seed_hi_mul, (uint32_t)idx);
-                if (DEV) {
-                    const double g = (double)g32;
-                    A = fma(g, (double)code[j], A);
-                    G = fma(g, g, G);
-                    B += (unsigned)(code[j] * code[j]);
+            for (int kk = 0; kk < 4; ++kk) {
+                const int k_l = wave * 4 + kk, k = k0 + k_l;
+                const size_t base = ((size_t)k * Cg + c0) * RS;
+                for (int rem = lane; rem < per_k; rem += 64) {
+                    int code = 0;
+                    if (k < K && rem < cvalid * RS) {
+                        const float g32 = w[base + rem];
+                        code = quantize_one<STOCH>(g32, inv, seed_lo, seed_hi_mul, (uint32_t)(base + rem));
+                        if (DEV) {
+                            const double g = (double)g32;
+                            A = fma(g, (double)code, A);
+                            G = fma(g, g, G);
+                            B += (unsigned)(code * code);
+                        }
+                    }
+                    tile[k_l * per_k + rem] = (int8_t)code;
                 }
             }
-        }
-        reinterpret_cast<uint32_t*>(q)[t] = pack4(code[0], code[1], code[2], code[3]);
-    } else if (t < nd1 + nd2) {
-        const size_t u = t - nd1;
-        const int k4 = (int)(u % (Kp / 4));
-        size_t rest = u / (Kp / 4);
-        const int rs = (int)(rest % RS);
-        const int c = (int)(rest / RS);
-        int code[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int k = 4 * k4 + j;
-            code[j] = 0;
-            if (k < K) {
-                const size_t idx = ((size_t)k * Cg + c) * RS + rs;
-                code[j] = quantize_one<STOCH>(w[idx], inv, seed_lo, seed_hi_mul, (uint32_t)idx);
+        } else {
+            for (int e = threadIdx.x; e < QW_T * per_k; e += 256) {
+                const int k_l = e / per_k, rem = e - k_l * per_k;
+                const int c_l = rem / nrs, rs_l = rem - c_l * nrs;
+                const int k = k0 + k_l;
+                int code = 0;
+                if (k < K && c_l < cvalid) {
+                    const size_t idx = ((size_t)k * Cg + c0 + c_l) * RS + rs0 + rs_l;
+                    const float g32 = w[idx];
+                    code = quantize_one<STOCH>(g32, inv, seed_lo, seed_hi_mul, (uint32_t)idx);
+                    if (DEV) {
+                        const double g = (double)g32;
+                        A = fma(g, (double)code, A);
+                        G = fma(g, g, G);
+                        B += (unsigned)(code * code);
+                    }
+                }
+                tile[e] = (int8_t)code;
             }
         }
-        reinterpret_cast<uint32_t*>(q + off2)[u] = pack4(code[0], code[1], code[2], code[3]);
+        __syncthreads();
+        // view 1: granule (filter, tap) = 16 channels
+        for (int u = threadIdx.x; u < QW_T * nrs; u += 256) {
+            const int k_l = u / nrs, rs_l = u - k_l * nrs;
+            if (k0 + k_l < K) {
+                uint32_t d[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    d[j] = pack4(tile[(k_l * QW_T + 4 * j) * nrs + rs_l], tile[(k_l * QW_T + 4 * j + 1) * nrs + rs_l],
+                                 tile[(k_l * QW_T + 4 * j + 2) * nrs + rs_l], tile[(k_l * QW_T + 4 * j + 3) * nrs + rs_l]);
+                *reinterpret_cast<uint4*>(q + ((size_t)(k0 + k_l) * RS + rs0 + rs_l) * Cp + c0) = make_uint4(d[0], d[1], d[2], d[3]);
+            }
+        }
+        // view 2: granule (channel, tap) = 16 filters
+        for (int u = threadIdx.x; u < QW_T * nrs; u += 256) {
+            const int c_l = u / nrs, rs_l = u - c_l * nrs;
+            if (c0 + c_l < Cg) {
+                uint32_t d[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    d[j] = pack4(tile[((4 * j) * QW_T + c_l) * nrs + rs_l], tile[((4 * j + 1) * QW_T + c_l) * nrs + rs_l],
+                                 tile[((4 * j + 2) * QW_T + c_l) * nrs + rs_l], tile[((4 * j + 3) * QW_T + c_l) * nrs + rs_l]);
+                *reinterpret_cast<uint4*>(q + off2 + ((size_t)(c0 + c_l) * RS + rs0 + rs_l) * Kp + k0) = make_uint4(d[0], d[1], d[2], d[3]);
+            }
+        }
     }
-    if (DEV) block_store_devpartial(A, G, B, devpart + blockIdx.x);
+    if (DEV) block_store_devpartial(A, G, B, devpart + (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x);
 }
 
+// blocks along the taps: 1 for tensors with many 16 x 16 tiles, up to R*S for small ones
+static int quant_wgt_zsplit(int K, int Cg, int R, int S) {
+    const int tiles = ((K + QW_T - 1) / QW_T) * ((Cg + QW_T - 1) / QW_T);
+    int z = (256 + tiles - 1) / tiles;
+    if (z > R * S) z = R * S;
+    return z < 1 ? 1 : z;
+}
 int quant_blocks_wgt(int K, int Cg, int R, int S) {
-    const int Cp = (Cg + 15) & ~15, Kp = (K + 15) & ~15;
-    const size_t nd = (size_t)K * R * S * (Cp / 4) + (size_t)Cg * R * S * (Kp / 4);
-    return (int)((nd + 255) / 256);
+    return ((K + QW_T - 1) / QW_T) * ((Cg + QW_T - 1) / QW_T) * quant_wgt_zsplit(K, Cg, R, S);
 }
 
 hipError_t launch_quantize_wgt(const QuantArgs& a, hipStream_t st) {
     const int K = a.d0, Cg = a.d1, R = a.d2, S = a.d3;
     const int Cp = (Cg + 15) & ~15, Kp = (K + 15) & ~15;
     const size_t off2 = (((size_t)K * R * S * Cp) + 255) & ~(size_t)255;
-    const int blocks = quant_blocks_wgt(K, Cg, R, S);
+    const dim3 grid((Cg + QW_T - 1) / QW_T, (K + QW_T - 1) / QW_T, quant_wgt_zsplit(K, Cg, R, S));
     const uint32_t slo = (uint32_t)a.seed, shi = seed_hi_term(a.seed);
     KernelTimer kt(KID_QUANTIZE_WGT, st);
 #define LAUNCH(ST, DV)                                                                              \
-    hipLaunchKernelGGL((quantize_wgt_kernel<ST, DV>), dim3(blocks), dim3(256), 0, st, a.x, K, Cg, R, \
+    hipLaunchKernelGGL((quantize_wgt_kernel<ST, DV>), grid, dim3(256), 0, st, a.x, K, Cg, R, \
                        S, Cp, Kp, off2, a.clip, a.absmax_part, a.nparts, slo, shi, a.q, a.scale,    \
                        a.devpart)
     if (a.stochastic) {
