@@ -63,6 +63,122 @@ __global__ __launch_bounds__(256) void dw_conv_kernel(const DwArgs a) {
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Stride-1 fast path (filters up to 8 wide).  The plane is staged into LDS with its zero border
+// (top = -drmin rows, left = -dsmin columns), so that the taps of output column ow start at LDS
+// column ow: a thread owns four consecutive outputs of a row, fetches the S + 3 bytes they read
+// from each filter row as aligned dwords, and forms each output's row sum with one byte-align and
+// one 4-way int8 dot product against the row's packed weights.  No bounds tests, no divisions per
+// tap; four results leave as one 16-byte store.
+//   forward        LDS row oh + r', column ow + s'  holds a[oh - ph + r', ow - pw + s'],   weight w[r'][s']
+//   backward-data  LDS row oh + r', column ow + s'  holds g[oh + ph - (R-1) + r', ...],    weight w[R-1-r'][S-1-s']
+// ---------------------------------------------------------------------------------------------
+constexpr int DW_FAST_MAXR = 8;
+
+// Copy plane `src` (IH x IW, contiguous) into LDS `dst` (rows of `pitch` bytes) at (top, left).
+__device__ __forceinline__ void dw_fill_plane(const int8_t* __restrict__ src, int IH, int IW, int8_t* dst,
+                                              int pitch, int top, int left) {
+    const int IHW = IH * IW;
+    if ((IHW & 15) == 0) {
+        // 16 source bytes per thread and pass; row / column advance without divisions
+        for (int i = threadIdx.x; i < (IHW >> 4); i += 256) {
+            const uint4 v = reinterpret_cast<const uint4*>(src)[i];
+            const uint32_t d[4] = {v.x, v.y, v.z, v.w};
+            int row = (16 * i) / IW, col = 16 * i - row * IW;
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                dst[(row + top) * pitch + col + left] = (int8_t)(d[k >> 2] >> (8 * (k & 3)));
+                if (++col == IW) {
+                    col = 0;
+                    ++row;
+                }
+            }
+        }
+    } else {
+        for (int i = threadIdx.x; i < IHW; i += 256) {
+            const int row = i / IW, col = i - row * IW;
+            dst[(row + top) * pitch + col + left] = src[i];
+        }
+    }
+}
+
+// Stage a plane with its zero border: `rows` x `pitch` bytes of LDS, the plane at (top, left).
+__device__ __forceinline__ void dw_stage_plane(const int8_t* __restrict__ src, int IH, int IW, int8_t* dst,
+                                               int rows, int pitch, int top, int left) {
+    const int ndw = rows * pitch >> 2;          // pitch is a multiple of 4
+    for (int i = threadIdx.x; i < ndw; i += 256) reinterpret_cast<uint32_t*>(dst)[i] = 0u;
+    __syncthreads();
+    dw_fill_plane(src, IH, IW, dst, pitch, top, left);
+    __syncthreads();
+}
+
+template <bool DGRAD, int SD>    // SD = dwords of packed weights per filter row (S <= 4*SD)
+__global__ __launch_bounds__(256) void dw_conv_fast_kernel(const DwArgs a, int pitch) {
+    extern __shared__ __attribute__((aligned(16))) int8_t plane[];
+    __shared__ uint32_t wrow[DW_FAST_MAXR][SD];
+    const int nc = blockIdx.x;
+    const int c = nc % a.C;
+    const int OHW = a.OH * a.OW, RS = a.R * a.S;
+    const int top = DGRAD ? (a.R - 1 - a.pad_h) : a.pad_h;     // = -drmin
+    const int left = DGRAD ? (a.S - 1 - a.pad_w) : a.pad_w;    // = -dsmin
+    if (threadIdx.x < a.R * SD) {
+        const int rp = threadIdx.x / SD, d = threadIdx.x - rp * SD;
+        uint32_t wv = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int sp = 4 * d + k;
+            if (sp < a.S) {
+                const int r = DGRAD ? (a.R - 1 - rp) : rp, sx = DGRAD ? (a.S - 1 - sp) : sp;
+                wv |= (uint32_t)(uint8_t)a.b[(size_t)c * RS + r * a.S + sx] << (8 * k);
+            }
+        }
+        wrow[rp][d] = wv;
+    }
+    dw_stage_plane(a.a + (size_t)nc * a.IH * a.IW, a.IH, a.IW, plane, a.OH + a.R - 1, pitch, top, left);
+
+    const float scale = __fmul_rn(a.sa[0], a.sb[0]);
+    const int QW = (a.OW + 3) >> 2;
+    const bool vec = (a.OW & 3) == 0;
+    float* __restrict__ outp = a.out + (size_t)nc * OHW;
+    int32_t* __restrict__ accp = a.acc ? a.acc + (size_t)nc * OHW : nullptr;
+    for (int t = threadIdx.x; t < a.OH * QW; t += 256) {
+        const int oh = t / QW, ow = (t - oh * QW) << 2;
+        int sum[4] = {0, 0, 0, 0};
+        for (int rp = 0; rp < a.R; ++rp) {
+            const uint32_t* __restrict__ rowp = reinterpret_cast<const uint32_t*>(plane + (oh + rp) * pitch + ow);
+            uint32_t d[SD + 1];
+#pragma unroll
+            for (int k = 0; k <= SD; ++k) d[k] = rowp[k];
+#pragma unroll
+            for (int k = 0; k < SD; ++k) {
+                const uint32_t wv = wrow[rp][k];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t win = j == 0 ? d[k] : __builtin_amdgcn_alignbyte(d[k + 1], d[k], j);
+                    sum[j] = __builtin_amdgcn_sdot4((int)win, (int)wv, sum[j], false);
+                }
+            }
+        }
+        const int o = oh * a.OW + ow;
+        if (vec) {
+            *reinterpret_cast<float4*>(outp + o) = make_float4(__fmul_rn((float)sum[0], scale), __fmul_rn((float)sum[1], scale),
+                                                               __fmul_rn((float)sum[2], scale), __fmul_rn((float)sum[3], scale));
+            if (accp) {   // the accumulator output is only required to be 4-byte aligned
+#pragma unroll
+                for (int j = 0; j < 4; ++j) accp[o + j] = sum[j];
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (ow + j < a.OW) {
+                    outp[o + j] = __fmul_rn((float)sum[j], scale);
+                    if (accp) accp[o + j] = sum[j];
+                }
+            }
+        }
+    }
+}
+
 // Backward-weight: g_W[c,r,s] = sum_{n,p,q} g_z[n,c,p,q] * a[n,c,p*sh+r-ph,q*sw+s-pw].
 // grid (C, chunks); a block sums its share of the images for one channel and writes
 // partial[chunk][c][rs]; the reduce kernel adds the chunks and applies Eq.2.
@@ -135,6 +251,63 @@ __global__ __launch_bounds__(256) void dw_wgrad_kernel(const DwArgs a) {
     }
 }
 
+// Stride-1 fast path of the backward-weight pass for R x S known at compile time: both planes in
+// LDS (the input with its zero border, so that tap (r,s) of output column q starts at LDS column
+// q + s), a thread owns four consecutive outputs of a row and adds, per tap, one 4-way int8 dot
+// product of the four gradient codes with the four input codes they meet.
+template <int R, int S>
+__global__ __launch_bounds__(256) void dw_wgrad_fast_kernel(const DwArgs a, int pitch, int gpitch) {
+    extern __shared__ __attribute__((aligned(16))) int8_t lds[];
+    __shared__ int red[4];
+    constexpr int SD = (S + 3) / 4;
+    const int c = blockIdx.x, chunk = blockIdx.y;
+    const int IHW = a.IH * a.IW, OHW = a.OH * a.OW;
+    const int n0 = (int)(((long long)a.N * chunk) / a.chunks);
+    const int n1 = (int)(((long long)a.N * (chunk + 1)) / a.chunks);
+    int32_t* __restrict__ part = a.partial + ((size_t)chunk * a.C + c) * (R * S);
+    const int xrows = a.OH + R - 1;
+    int8_t* xs = lds;                                   // (OH + R - 1) x pitch, zero border
+    int8_t* gs = lds + ((xrows * pitch + 15) & ~15);    // OH x gpitch, zero tail columns
+    {
+        const int ndw = (((xrows * pitch + 15) & ~15) + a.OH * gpitch) >> 2;
+        for (int i = threadIdx.x; i < ndw; i += 256) reinterpret_cast<uint32_t*>(lds)[i] = 0u;
+    }
+    int acc[R][S];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int sx = 0; sx < S; ++sx) acc[r][sx] = 0;
+    const int QW = (a.OW + 3) >> 2;
+    for (int n = n0; n < n1; ++n) {
+        const int8_t* __restrict__ xsrc = a.a + ((size_t)n * a.C + c) * IHW;
+        const int8_t* __restrict__ gsrc = a.b + ((size_t)n * a.C + c) * OHW;
+        __syncthreads();   // the previous image's reads (and the zero fill) are done
+        dw_fill_plane(xsrc, a.IH, a.IW, xs, pitch, a.pad_h, a.pad_w);
+        dw_fill_plane(gsrc, a.OH, a.OW, gs, gpitch, 0, 0);
+        __syncthreads();
+        for (int t = threadIdx.x; t < a.OH * QW; t += 256) {
+            const int p = t / QW, q = (t - p * QW) << 2;
+            const int g4 = *reinterpret_cast<const int*>(gs + p * gpitch + q);
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const uint32_t* __restrict__ rowp = reinterpret_cast<const uint32_t*>(xs + (p + r) * pitch + q);
+                uint32_t d[SD + 1];
+#pragma unroll
+                for (int k = 0; k <= SD; ++k) d[k] = rowp[k];
+#pragma unroll
+                for (int sx = 0; sx < S; ++sx) {
+                    const uint32_t win = (sx & 3) == 0 ? d[sx >> 2] : __builtin_amdgcn_alignbyte(d[(sx >> 2) + 1], d[sx >> 2], sx & 3);
+                    acc[r][sx] = __builtin_amdgcn_sdot4((int)win, g4, acc[r][sx], false);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int sx = 0; sx < S; ++sx) dw_block_sum_store(acc[r][sx], red, part + r * S + sx);
+}
+
 __global__ __launch_bounds__(256) void dw_wgrad_reduce_kernel(const DwArgs a) {
     const int RS = a.R * a.S;
     const int total = a.C * RS;
@@ -153,18 +326,56 @@ int dw_wgrad_chunks(int N, int C) {
     return chunks;
 }
 
+// LDS row pitch of the fast path: the widest row read starts at column OW - 1 rounded down to 4 and
+// takes 4 * (SD + 1) bytes
+static int dw_fast_pitch(int OW, int S) {
+    const int sd = (S + 3) / 4;
+    return (((OW + 3) & ~3) + 4 * sd + 3) & ~3;
+}
+
 hipError_t launch_dw_conv(const DwArgs& a, hipStream_t st) {
+    KernelTimer kt(KID_DW_CONV, st);
+    if (a.stride_h == 1 && a.stride_w == 1 && a.S <= 8 && a.R <= DW_FAST_MAXR &&
+        (a.dgrad ? (a.pad_h <= a.R - 1 && a.pad_w <= a.S - 1) : true)) {
+        const int pitch = dw_fast_pitch(a.OW, a.S);
+        const size_t lds = (size_t)(a.OH + a.R - 1) * pitch;
+        if (lds <= 60 * 1024) {
+            const bool two = a.S > 4;
+            if (a.dgrad) {
+                if (two) hipLaunchKernelGGL((dw_conv_fast_kernel<true, 2>), dim3(a.N * a.C), dim3(256), lds, st, a, pitch);
+                else hipLaunchKernelGGL((dw_conv_fast_kernel<true, 1>), dim3(a.N * a.C), dim3(256), lds, st, a, pitch);
+            } else {
+                if (two) hipLaunchKernelGGL((dw_conv_fast_kernel<false, 2>), dim3(a.N * a.C), dim3(256), lds, st, a, pitch);
+                else hipLaunchKernelGGL((dw_conv_fast_kernel<false, 1>), dim3(a.N * a.C), dim3(256), lds, st, a, pitch);
+            }
+            return hipGetLastError();
+        }
+    }
     const size_t lds = ((size_t)a.IH * a.IW + 15) & ~(size_t)15;
-    if (a.dgrad)
-        { KernelTimer kt(KID_DW_CONV, st); hipLaunchKernelGGL((dw_conv_kernel<true>), dim3(a.N * a.C), dim3(256), lds, st, a); }
-    else
-        { KernelTimer kt(KID_DW_CONV, st); hipLaunchKernelGGL((dw_conv_kernel<false>), dim3(a.N * a.C), dim3(256), lds, st, a); }
+    if (a.dgrad) hipLaunchKernelGGL((dw_conv_kernel<true>), dim3(a.N * a.C), dim3(256), lds, st, a);
+    else hipLaunchKernelGGL((dw_conv_kernel<false>), dim3(a.N * a.C), dim3(256), lds, st, a);
     return hipGetLastError();
 }
 
 hipError_t launch_dw_wgrad(const DwArgs& a, hipStream_t st) {
-    const size_t lds = (((size_t)a.IH * a.IW + 15) & ~(size_t)15) + (((size_t)a.OH * a.OW + 15) & ~(size_t)15);
-    { KernelTimer kt(KID_DW_WGRAD, st); hipLaunchKernelGGL(dw_wgrad_kernel, dim3(a.C, a.chunks), dim3(256), lds, st, a); }
+    {
+        KernelTimer kt(KID_DW_WGRAD, st);
+        bool fast = false;
+        if (a.stride_h == 1 && a.stride_w == 1 && a.R == a.S && (a.R == 3 || a.R == 5)) {
+            // here IH x IW is the input plane and OH x OW the gradient plane
+            const int pitch = dw_fast_pitch(a.OW, a.S), gpitch = (a.OW + 3) & ~3;
+            const size_t ldsf = (((size_t)(a.OH + a.R - 1) * pitch + 15) & ~(size_t)15) + (size_t)a.OH * gpitch;
+            if (ldsf <= 60 * 1024) {
+                fast = true;
+                if (a.R == 3) hipLaunchKernelGGL((dw_wgrad_fast_kernel<3, 3>), dim3(a.C, a.chunks), dim3(256), ldsf, st, a, pitch, gpitch);
+                else hipLaunchKernelGGL((dw_wgrad_fast_kernel<5, 5>), dim3(a.C, a.chunks), dim3(256), ldsf, st, a, pitch, gpitch);
+            }
+        }
+        if (!fast) {
+            const size_t lds = (((size_t)a.IH * a.IW + 15) & ~(size_t)15) + (((size_t)a.OH * a.OW + 15) & ~(size_t)15);
+            hipLaunchKernelGGL(dw_wgrad_kernel, dim3(a.C, a.chunks), dim3(256), lds, st, a);
+        }
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int total = a.C * a.R * a.S;

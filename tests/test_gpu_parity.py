@@ -193,6 +193,9 @@ CONV_SHAPES = [
     (2, 12, 9, 9, 12, 3, 3, (1, 1), (1, 1), 12),      # depthwise
     (1, 5, 11, 8, 5, 3, 3, (2, 2), (1, 1), 5),        # depthwise stride 2
     (2, 7, 6, 9, 7, 5, 3, (1, 2), (2, 0), 7),         # depthwise odd filter
+    (2, 6, 8, 12, 6, 3, 5, (1, 1), (1, 2), 6),         # depthwise stride 1, 5-wide filter, row length a multiple of 4
+    (1, 4, 10, 11, 4, 3, 3, (1, 1), (0, 0), 4),        # depthwise stride 1, no padding
+    (3, 5, 16, 16, 5, 3, 3, (1, 1), (1, 1), 5),        # depthwise, plane size a multiple of 16
     # small filter banks with an even number of channel granules (weights held in registers)
     (2, 64, 7, 20, 64, 3, 3, (1, 1), (1, 1), 1),
     (3, 32, 9, 13, 40, 3, 3, (1, 1), (1, 1), 1),
