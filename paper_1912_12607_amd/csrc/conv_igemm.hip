@@ -12,9 +12,11 @@
 // channels of ONE pixel, and a store instruction writes 32 consecutive pixels of one channel
 // (128 contiguous bytes) straight into the N,C,H,W result.
 //
-// Tile: BM (64 or 128) rows x 128 cols per 256-thread block, 64 reduction bytes per step, staged
-// through LDS (im2col gather done by the loader, zero fill for padding / ragged edges), next
-// step's global loads in flight while the current step's MFMAs run.
+// Tile: BM (64 or 128) rows x BN (128 or 256) cols per 256-thread block (2 x 2 waves, each
+// BM/2 x BN/2), 64 reduction bytes per stage.  Two LDS buffers: while the MFMAs of a stage run, the
+// next stage's global loads are in flight in registers and are written to the other buffer, so a
+// stage costs one barrier.  The wide tile (128 x 256: 16 MFMAs per wave and barrier, 0.75 LDS
+// operand reads per MFMA) serves the layers whose convolutions are bound by the matrix cores.
 #include "device_common.h"
 #include "kernels.h"
 
@@ -23,18 +25,18 @@ namespace int8t {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr int IG_BN = 128;
-
 // 16-byte slot of (row, granule) inside a [rows][4 granules] LDS tile.  The xor keeps both the
 // loader's writes (4 lanes per row) and the MFMA operand reads (32 consecutive rows, one
 // granule) spread over all banks.
 __device__ __forceinline__ int lds_slot(int row, int g) { return row * 4 + (g ^ ((row >> 1) & 3)); }
 
-template <int BM, bool DGRAD>
-__global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
+template <int BM, int BN, bool DGRAD>
+__global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmArgs a) {
     constexpr int MI = BM / 64;   // 32-row MFMA tiles per wave
-    __shared__ uint4 sA[BM * 4];
-    __shared__ uint4 sB[IG_BN * 4];
+    constexpr int NJ = BN / 64;   // 32-column MFMA tiles per wave
+    constexpr int NB = BN / 64;   // B-tile columns staged per thread
+    __shared__ uint4 sA[2][BM * 4];
+    __shared__ uint4 sB[2][BN * 4];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -47,15 +49,15 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
     const int gtot = a.R * a.S * Cg16;
     const int nsteps = (gtot + 3) >> 2;
     const int rowbase = blockIdx.y * BM;
-    const int colbase = blockIdx.x * IG_BN;
+    const int colbase = blockIdx.x * BN;
 
     // ---- loader state -----------------------------------------------------------------------
-    // B (pixels): two columns per thread, fixed for the whole reduction
-    int bh[2], bw[2];
-    const int8_t* bimg[2];
-    bool bvalid[2];
+    // B (pixels): NB columns per thread, fixed for the whole reduction
+    int bh[NB], bw[NB];
+    const int8_t* bimg[NB];
+    bool bvalid[NB];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < NB; ++i) {
         const int col = colbase + i * 64 + lrow;
         bvalid[i] = col < ncols;
         const int cc = bvalid[i] ? col : 0;
@@ -83,7 +85,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
         arow[i] = a.wgt + (size_t)(avalid[i] ? row : 0) * gtot * 16;
     }
 
-    uint4 ra[MI], rb[2];
+    uint4 ra[MI], rb[NB];
     auto load_step = [&](int step) {
         const int q = step * 4 + lg;
         const bool qv = q < gtot;
@@ -93,7 +95,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
             if (qv && avalid[i]) ra[i] = *reinterpret_cast<const uint4*>(arow[i] + (size_t)q * 16);
         }
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < NB; ++i) {
             rb[i] = make_uint4(0, 0, 0, 0);
             int ih, iw;
             bool ok = qv && bvalid[i];
@@ -125,42 +127,239 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
             }
         }
     };
+    auto stage = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < MI; ++i) sA[buf][lds_slot(i * 64 + lrow, lg)] = ra[i];
+#pragma unroll
+        for (int i = 0; i < NB; ++i) sB[buf][lds_slot(i * 64 + lrow, lg)] = rb[i];
+    };
 
-    v16i acc[MI][2];
+    v16i acc[MI][NJ];
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < NJ; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
     load_step(0);
+    stage(0);
+    __syncthreads();
     for (int step = 0; step < nsteps; ++step) {
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < MI; ++i) sA[lds_slot(i * 64 + lrow, lg)] = ra[i];
-#pragma unroll
-        for (int i = 0; i < 2; ++i) sB[lds_slot(i * 64 + lrow, lg)] = rb[i];
-        __syncthreads();
-        if (step + 1 < nsteps) load_step(step + 1);
+        const int buf = step & 1;
+        if (step + 1 < nsteps) load_step(step + 1);     // in flight while this stage computes
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
             const int g = kk * 2 + (lane >> 5);
-            v4i fa[MI], fb[2];
+            v4i fa[MI], fb[NJ];
+#pragma unroll
+            for (int i = 0; i < MI; ++i) {
+                const uint4 t = sA[buf][lds_slot(wm * (BM / 2) + i * 32 + (lane & 31), g)];
+                fa[i] = v4i{(int)t.x, (int)t.y, (int)t.z, (int)t.w};
+            }
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                const uint4 t = sB[buf][lds_slot(wn * (BN / 2) + j * 32 + (lane & 31), g)];
+                fb[j] = v4i{(int)t.x, (int)t.y, (int)t.z, (int)t.w};
+            }
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+        // the other buffer was last read one stage ago, before the barrier that ended that stage
+        if (step + 1 < nsteps) stage(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: Eq.2, straight into N,C,H,W ----------------------------------------------
+    const float scale = __fmul_rn(a.sa[0], a.sb[0]);
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        const int col = colbase + wn * (BN / 2) + j * 32 + (lane & 31);
+        if (col >= ncols) continue;
+        const int n = col / OHW, opix = col - n * OHW;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = rowbase + wm * (BM / 2) + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                if (row < a.rows) {
+                    const size_t idx = ((size_t)n * a.rows + row) * OHW + opix;
+                    const int val = acc[i][j][v];
+                    a.out[idx] = __fmul_rn((float)val, scale);
+                    if (a.acc) a.acc[idx] = val;
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Wide-tile variant for the layers bound by the matrix cores: 128 rows x 256 columns per block,
+// operands fetched by buffer loads that write straight into LDS (no staging registers), NSTAGE
+// LDS buffers in a ring with the loads running two stages ahead of the MFMAs, one barrier per
+// stage.  A wave-wide load fills 64 consecutive 16-byte slots, lane l the slot base + l; which
+// (row, granule) that slot holds follows from the slot index, so each lane simply fetches the
+// granule that belongs there.  Out-of-range rows, ragged columns, padding taps and the reduction
+// tail carry an offset beyond the buffer descriptor: the hardware then writes zeros.
+// ---------------------------------------------------------------------------------------------
+constexpr int IGD_BM = 128, IGD_BN = 256, IGD_NSTAGE = 3;
+constexpr uint32_t IGD_OOB = 0x80000000u;
+
+// Buffer descriptor (base, no stride, byte count, raw 32-bit format) as four scalar words.
+__device__ __forceinline__ v4i igd_rsrc(const void* p, uint32_t bytes) {
+    const uint64_t addr = (uint64_t)p;
+    return v4i{(int)(uint32_t)addr, (int)((uint32_t)(addr >> 32) & 0xffffu), (int)bytes, 0x00020000};
+}
+// One wave-wide 16-byte-per-lane buffer load into LDS: lane l's bytes land at lds_base + 16*l, an
+// offset beyond the descriptor writes zeros.  Written as an instruction block so that the wait for
+// it can be placed by hand (see the vmcnt waits in the kernel): the compiler would otherwise wait
+// for ALL outstanding loads in front of every LDS read.  (m0 carries the LDS base; the compiler keeps
+// no value of its own in it across statements.)
+__device__ __forceinline__ void igd_load_lds(const v4i& rsrc, uint32_t lds_base_uniform, uint32_t voff) {
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(lds_base_uniform), "v"(voff), "s"(rsrc) : "memory");
+}
+
+template <bool DGRAD>
+__global__ __launch_bounds__(256, 2) void igemm_dma_kernel(const IgemmArgs a) {
+    constexpr int BM = IGD_BM, BN = IGD_BN, MI = 2, NJ = 4;
+    constexpr int STAGE_SLOTS = (BM + BN) * 4;          // 16-byte slots per stage: A tile, then B tile
+    extern __shared__ __attribute__((aligned(16))) uint4 ring[];   // [NSTAGE][STAGE_SLOTS]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave & 1, wn = wave >> 1;
+
+    const int OHW = a.OH * a.OW;
+    const int ncols = a.N * OHW;
+    const int Cg16 = a.Ca >> 4;
+    const int gtot = a.R * a.S * Cg16;
+    const int nsteps = (gtot + 3) >> 2;
+    const int rowbase = blockIdx.y * BM;
+    const int colbase = blockIdx.x * BN;
+
+    const v4i wr = igd_rsrc(a.wgt, (uint32_t)((size_t)a.rows * gtot * 16));
+    const v4i xr = igd_rsrc(a.act, (uint32_t)((size_t)a.N * a.IH * a.IW * a.Ca));
+    // LDS byte address of this wave's first A / B load slot in buffer 0 (wave-uniform)
+    const uint32_t lds_a0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(size_t)(ring + 64 * wave));
+    const uint32_t lds_b0 = lds_a0 + BM * 4 * 16;
+
+    // ---- loader state: this wave issues A loads {wave, wave+4} and B loads {wave + 4*i}, i < 4.
+    // Load number wl covers tile rows 16*wl .. 16*wl+15; lane -> (row, granule) through the swizzle.
+    const int lrow = lane >> 2;                              // row inside the 16-row group
+    const int gsw = (lane & 3) ^ ((lrow >> 1) & 3);          // granule (0..3) held by this lane's slot
+    uint32_t aoff[2];                                        // byte offset of (row, granule 0) or OOB
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int row = rowbase + 16 * (wave + 4 * i) + lrow;
+        aoff[i] = row < a.rows ? (uint32_t)row * (uint32_t)gtot * 16u : IGD_OOB;
+    }
+    int bh[4], bw[4];
+    uint32_t bimg[4];                                        // byte offset of the column's image or OOB
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int col = colbase + 16 * (wave + 4 * i) + lrow;
+        const bool cv = col < ncols;
+        const int cc = cv ? col : 0;
+        const int n = cc / OHW, rem = cc - n * OHW;
+        const int oh = rem / a.OW, ow = rem - oh * a.OW;
+        bh[i] = DGRAD ? (oh + a.pad_h) : (oh * a.stride_h - a.pad_h);
+        bw[i] = DGRAD ? (ow + a.pad_w) : (ow * a.stride_w - a.pad_w);
+        bimg[i] = cv ? (uint32_t)n * (uint32_t)(a.IH * a.IW * a.Ca) : IGD_OOB;
+    }
+    // reduction position of this lane's granule: filter tap (r,s) and channel granule cg
+    int r, s, cg;
+    {
+        const int tap = gsw / Cg16;
+        cg = gsw - tap * Cg16;
+        r = tap / a.S;
+        s = tap - r * a.S;
+    }
+    int qnext = gsw;                                         // granule index of the next stage to issue
+
+    auto issue = [&](int buf) {
+        const uint32_t boff = (uint32_t)buf * (STAGE_SLOTS * 16u);
+        const bool qv = qnext < gtot;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const uint32_t off = (qv && aoff[i] != IGD_OOB) ? aoff[i] + (uint32_t)qnext * 16u : IGD_OOB;
+            igd_load_lds(wr, lds_a0 + boff + (uint32_t)i * (4 * 64 * 16), off);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int ih, iw;
+            bool ok = qv && bimg[i] != IGD_OOB;
+            if (DGRAD) {
+                const int th = bh[i] - r, tw = bw[i] - s;
+                if (a.stride_h == 1 && a.stride_w == 1) {
+                    ih = th;
+                    iw = tw;
+                } else {
+                    ih = th / a.stride_h;
+                    iw = tw / a.stride_w;
+                    ok = ok && th >= 0 && tw >= 0 && (ih * a.stride_h == th) && (iw * a.stride_w == tw);
+                }
+            } else {
+                ih = bh[i] + r;
+                iw = bw[i] + s;
+            }
+            ok = ok && (unsigned)ih < (unsigned)a.IH && (unsigned)iw < (unsigned)a.IW;
+            const uint32_t off = ok ? bimg[i] + (uint32_t)((ih * a.IW + iw) * a.Ca + cg * 16) : IGD_OOB;
+            igd_load_lds(xr, lds_b0 + boff + (uint32_t)i * (4 * 64 * 16), off);
+        }
+        // advance this lane's reduction position by one stage (4 granules)
+        qnext += 4;
+        cg += 4;
+        while (cg >= Cg16) {
+            cg -= Cg16;
+            if (++s == a.S) {
+                s = 0;
+                ++r;
+            }
+        }
+    };
+
+    v16i acc[MI][NJ];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+
+    // prologue: stages 0 and 1 on their way
+    issue(0);
+    if (nsteps > 1) issue(1);
+    for (int step = 0; step < nsteps; ++step) {
+        const int buf = step % IGD_NSTAGE;
+        // this stage's six loads are the oldest outstanding ones; the next stage's six may still fly
+        if (step + 1 < nsteps) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();   // every wave's part of this stage is in LDS; stage step-1 has been read by all
+        if (step + 2 < nsteps) issue((step + 2) % IGD_NSTAGE);   // into the buffer read in stage step-1
+        const uint4* __restrict__ sA = ring + buf * STAGE_SLOTS;
+        const uint4* __restrict__ sB = sA + BM * 4;
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            const int g = kk * 2 + (lane >> 5);
+            v4i fa[MI], fb[NJ];
 #pragma unroll
             for (int i = 0; i < MI; ++i) {
                 const uint4 t = sA[lds_slot(wm * (BM / 2) + i * 32 + (lane & 31), g)];
                 fa[i] = v4i{(int)t.x, (int)t.y, (int)t.z, (int)t.w};
             }
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const uint4 t = sB[lds_slot(wn * 64 + j * 32 + (lane & 31), g)];
+            for (int j = 0; j < NJ; ++j) {
+                const uint4 t = sB[lds_slot(wn * (BN / 2) + j * 32 + (lane & 31), g)];
                 fb[j] = v4i{(int)t.x, (int)t.y, (int)t.z, (int)t.w};
             }
 #pragma unroll
             for (int i = 0; i < MI; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
+                for (int j = 0; j < NJ; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
         }
     }
@@ -168,8 +367,8 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a) {
     // ---- epilogue: Eq.2, straight into N,C,H,W ----------------------------------------------
     const float scale = __fmul_rn(a.sa[0], a.sb[0]);
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int col = colbase + wn * 64 + j * 32 + (lane & 31);
+    for (int j = 0; j < NJ; ++j) {
+        const int col = colbase + wn * (BN / 2) + j * 32 + (lane & 31);
         if (col >= ncols) continue;
         const int n = col / OHW, opix = col - n * OHW;
 #pragma unroll
@@ -192,16 +391,30 @@ hipError_t launch_igemm(const IgemmArgs& a, hipStream_t st) {
     hipError_t berr = hipSuccess;
     if (launch_band(a, st, &berr)) return berr;   // small filter bank: LDS-resident kernel
     const int ncols = a.N * a.OH * a.OW;
-    const int ctiles = (ncols + IG_BN - 1) / IG_BN;
     KernelTimer kt(KID_IGEMM, st);
+    const long long gran = (long long)a.R * a.S * (a.Ca >> 4);
     if (a.rows <= 64) {
-        dim3 grid(ctiles, 1);
-        if (a.dgrad) hipLaunchKernelGGL((igemm_kernel<64, true>), grid, dim3(256), 0, st, a);
-        else hipLaunchKernelGGL((igemm_kernel<64, false>), grid, dim3(256), 0, st, a);
+        dim3 grid((ncols + 127) / 128, 1);
+        if (a.dgrad) hipLaunchKernelGGL((igemm_kernel<64, 128, true>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((igemm_kernel<64, 128, false>), grid, dim3(256), 0, st, a);
+    } else if (gran >= 32 && (long long)((ncols + 255) / 256) * ((a.rows + 127) / 128) >= 256) {
+        // long reduction and enough 128 x 256 tiles to cover the chip: the wide tile
+        dim3 grid((ncols + 255) / 256, (a.rows + 127) / 128);
+        const size_t lds = (size_t)IGD_NSTAGE * (IGD_BM + IGD_BN) * 4 * 16;
+        static bool attr_done[2] = {false, false};
+        if (!attr_done[a.dgrad ? 1 : 0]) {
+            hipError_t e = hipFuncSetAttribute(
+                a.dgrad ? reinterpret_cast<const void*>(igemm_dma_kernel<true>) : reinterpret_cast<const void*>(igemm_dma_kernel<false>),
+                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            attr_done[a.dgrad ? 1 : 0] = true;
+        }
+        if (a.dgrad) hipLaunchKernelGGL((igemm_dma_kernel<true>), grid, dim3(256), lds, st, a);
+        else hipLaunchKernelGGL((igemm_dma_kernel<false>), grid, dim3(256), lds, st, a);
     } else {
-        dim3 grid(ctiles, (a.rows + 127) / 128);
-        if (a.dgrad) hipLaunchKernelGGL((igemm_kernel<128, true>), grid, dim3(256), 0, st, a);
-        else hipLaunchKernelGGL((igemm_kernel<128, false>), grid, dim3(256), 0, st, a);
+        dim3 grid((ncols + 127) / 128, (a.rows + 127) / 128);
+        if (a.dgrad) hipLaunchKernelGGL((igemm_kernel<128, 128, true>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((igemm_kernel<128, 128, false>), grid, dim3(256), 0, st, a);
     }
     return hipGetLastError();
 }
