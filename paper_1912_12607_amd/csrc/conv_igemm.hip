@@ -197,16 +197,20 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Wide-tile variant for the layers bound by the matrix cores: 128 rows x 256 columns per block,
-// operands fetched by buffer loads that write straight into LDS (no staging registers), NSTAGE
-// LDS buffers in a ring with the loads running two stages ahead of the MFMAs, one barrier per
-// stage.  A wave-wide load fills 64 consecutive 16-byte slots, lane l the slot base + l; which
-// (row, granule) that slot holds follows from the slot index, so each lane simply fetches the
-// granule that belongs there.  Out-of-range rows, ragged columns, padding taps and the reduction
-// tail carry an offset beyond the buffer descriptor: the hardware then writes zeros.
+// Wide-tile variants for the layers bound by the matrix cores: (64*WM) rows x 256 columns per
+// block of 2*WM waves (each 64 x 128), operands fetched by buffer loads that write straight into
+// LDS (no staging registers), NSTAGE LDS buffers in a ring with the loads running NSTAGE-1 stages
+// ahead of the MFMAs, one barrier per stage.  A stage is KG 16-byte granules of the reduction per
+// row: KG = 8 makes every row's share of a stage one full 128-byte cache line.  A wave-wide load
+// fills 64 consecutive 16-byte slots, lane l the slot base + l; which (row, granule) that slot
+// holds follows from the slot index, so each lane simply fetches the granule that belongs there.
+// Out-of-range rows, ragged columns, padding taps and the reduction tail carry an offset beyond the
+// buffer descriptor: the hardware then writes zeros.
+//   <WM=2, KG=4, NSTAGE=3>: 128 x 256, 72 KB of LDS, two blocks per compute unit
+//   <WM=4, KG=8, NSTAGE=2>: 256 x 256, 128 KB of LDS, one block of eight waves per compute unit
 // ---------------------------------------------------------------------------------------------
-constexpr int IGD_BM = 128, IGD_BN = 256, IGD_NSTAGE = 3;
 constexpr uint32_t IGD_OOB = 0x80000000u;
+constexpr int IGD_BN = 256;
 
 // Buffer descriptor (base, no stride, byte count, raw 32-bit format) as four scalar words.
 __device__ __forceinline__ v4i igd_rsrc(const void* p, uint32_t bytes) {
@@ -222,46 +226,72 @@ __device__ __forceinline__ void igd_load_lds(const v4i& rsrc, uint32_t lds_base_
     asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                  :: "s"(lds_base_uniform), "v"(voff), "s"(rsrc) : "memory");
 }
+// slot of (row, granule) in a [rows][KG] tile; the xor spreads the MFMA operand reads (consecutive
+// rows, one granule) over the banks
+template <int KG>
+__device__ __forceinline__ int igd_slot(int row, int g) {
+    return KG == 4 ? row * 4 + (g ^ ((row >> 1) & 3)) : row * 8 + (g ^ (row & 7));
+}
+template <int N>
+__device__ __forceinline__ void igd_wait_vmcnt() {
+    static_assert(N == 0 || N == 6 || N == 12, "outstanding loads allowed while waiting");
+    if (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else if (N == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+}
 
-template <bool DGRAD>
-__global__ __launch_bounds__(256, 2) void igemm_dma_kernel(const IgemmArgs a) {
-    constexpr int BM = IGD_BM, BN = IGD_BN, MI = 2, NJ = 4;
-    constexpr int STAGE_SLOTS = (BM + BN) * 4;          // 16-byte slots per stage: A tile, then B tile
+template <bool DGRAD, int WM, int KG, int NSTAGE>
+__global__ __launch_bounds__(128 * WM, WM == 2 ? 2 : 1) void igemm_dma_kernel(const IgemmArgs a) {
+    constexpr int BM = 64 * WM, BN = IGD_BN, MI = 2, NJ = 4, NW = 2 * WM;
+    constexpr int STAGE_SLOTS = (BM + BN) * KG;         // 16-byte slots per stage: A tile, then B tile
+    constexpr int RPL = 64 / KG;                        // tile rows covered by one wave-wide load
+    constexpr int NLA = BM * KG / 64 / NW;              // A loads per wave and stage
+    constexpr int NLB = BN * KG / 64 / NW;              // B loads per wave and stage
+    constexpr int NL = NLA + NLB;
+    static_assert(NSTAGE == 2 || NL == 6, "vmcnt waits below are written for 6 loads per stage");
     extern __shared__ __attribute__((aligned(16))) uint4 ring[];   // [NSTAGE][STAGE_SLOTS]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave & 1, wn = wave >> 1;
+    const int wm = wave % WM, wn = wave / WM;
 
     const int OHW = a.OH * a.OW;
     const int ncols = a.N * OHW;
     const int Cg16 = a.Ca >> 4;
     const int gtot = a.R * a.S * Cg16;
-    const int nsteps = (gtot + 3) >> 2;
-    const int rowbase = blockIdx.y * BM;
-    const int colbase = blockIdx.x * BN;
+    const int nsteps = (gtot + KG - 1) / KG;
+    // Workgroups are dealt to the 8 XCDs round-robin (workgroup b runs on XCD b % 8).  Column tile
+    // ct = 8 * (i / rtiles) + xcd, row tile i % rtiles, i = b / 8: all row tiles of a column tile --
+    // they read the same pixels -- run on one XCD and share its L2, as do the column tiles of an XCD
+    // that read the same filter rows.  The grid is padded to whole groups of 8 column tiles.
+    const int rtiles = (a.rows + BM - 1) / BM;
+    const int wg_i = blockIdx.x >> 3;
+    const int ctile = ((wg_i / rtiles) << 3) + (int)(blockIdx.x & 7);
+    if (ctile * BN >= ncols) return;
+    const int rowbase = (wg_i % rtiles) * BM;
+    const int colbase = ctile * BN;
 
     const v4i wr = igd_rsrc(a.wgt, (uint32_t)((size_t)a.rows * gtot * 16));
     const v4i xr = igd_rsrc(a.act, (uint32_t)((size_t)a.N * a.IH * a.IW * a.Ca));
     // LDS byte address of this wave's first A / B load slot in buffer 0 (wave-uniform)
     const uint32_t lds_a0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(size_t)(ring + 64 * wave));
-    const uint32_t lds_b0 = lds_a0 + BM * 4 * 16;
+    const uint32_t lds_b0 = lds_a0 + BM * KG * 16;
 
-    // ---- loader state: this wave issues A loads {wave, wave+4} and B loads {wave + 4*i}, i < 4.
-    // Load number wl covers tile rows 16*wl .. 16*wl+15; lane -> (row, granule) through the swizzle.
-    const int lrow = lane >> 2;                              // row inside the 16-row group
-    const int gsw = (lane & 3) ^ ((lrow >> 1) & 3);          // granule (0..3) held by this lane's slot
-    uint32_t aoff[2];                                        // byte offset of (row, granule 0) or OOB
+    // ---- loader state: this wave issues A loads {wave + NW*i} and B loads {wave + NW*i}.  Load
+    // number wl covers tile rows RPL*wl .. RPL*wl + RPL-1; lane -> (row, granule) through the swizzle.
+    const int lrow = lane / KG;                              // row inside the load's row group
+    const int gsw = KG == 4 ? ((lane & 3) ^ ((lrow >> 1) & 3)) : ((lane & 7) ^ (lrow & 7));   // granule held by this lane's slot
+    uint32_t aoff[NLA];                                      // byte offset of (row, granule 0) or OOB
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int row = rowbase + 16 * (wave + 4 * i) + lrow;
+    for (int i = 0; i < NLA; ++i) {
+        const int row = rowbase + RPL * (wave + NW * i) + lrow;
         aoff[i] = row < a.rows ? (uint32_t)row * (uint32_t)gtot * 16u : IGD_OOB;
     }
-    int bh[4], bw[4];
-    uint32_t bimg[4];                                        // byte offset of the column's image or OOB
+    int bh[NLB], bw[NLB];
+    uint32_t bimg[NLB];                                      // byte offset of the column's image or OOB
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int col = colbase + 16 * (wave + 4 * i) + lrow;
+    for (int i = 0; i < NLB; ++i) {
+        const int col = colbase + RPL * (wave + NW * i) + lrow;
         const bool cv = col < ncols;
         const int cc = cv ? col : 0;
         const int n = cc / OHW, rem = cc - n * OHW;
@@ -280,16 +310,20 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(const IgemmArgs a) {
     }
     int qnext = gsw;                                         // granule index of the next stage to issue
 
-    auto issue = [&](int buf) {
+    auto issue_a = [&](int buf) {
         const uint32_t boff = (uint32_t)buf * (STAGE_SLOTS * 16u);
         const bool qv = qnext < gtot;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < NLA; ++i) {
             const uint32_t off = (qv && aoff[i] != IGD_OOB) ? aoff[i] + (uint32_t)qnext * 16u : IGD_OOB;
-            igd_load_lds(wr, lds_a0 + boff + (uint32_t)i * (4 * 64 * 16), off);
+            igd_load_lds(wr, lds_a0 + boff + (uint32_t)i * (NW * 64 * 16), off);
         }
+    };
+    auto issue_b = [&](int buf) {
+        const uint32_t boff = (uint32_t)buf * (STAGE_SLOTS * 16u);
+        const bool qv = qnext < gtot;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < NLB; ++i) {
             int ih, iw;
             bool ok = qv && bimg[i] != IGD_OOB;
             if (DGRAD) {
@@ -308,11 +342,11 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(const IgemmArgs a) {
             }
             ok = ok && (unsigned)ih < (unsigned)a.IH && (unsigned)iw < (unsigned)a.IW;
             const uint32_t off = ok ? bimg[i] + (uint32_t)((ih * a.IW + iw) * a.Ca + cg * 16) : IGD_OOB;
-            igd_load_lds(xr, lds_b0 + boff + (uint32_t)i * (4 * 64 * 16), off);
+            igd_load_lds(xr, lds_b0 + boff + (uint32_t)i * (NW * 64 * 16), off);
         }
-        // advance this lane's reduction position by one stage (4 granules)
-        qnext += 4;
-        cg += 4;
+        // advance this lane's reduction position by one stage (KG granules)
+        qnext += KG;
+        cg += KG;
         while (cg >= Cg16) {
             cg -= Cg16;
             if (++s == a.S) {
@@ -330,30 +364,40 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(const IgemmArgs a) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
-    // prologue: stages 0 and 1 on their way
-    issue(0);
-    if (nsteps > 1) issue(1);
+    // prologue: the first NSTAGE-1 stages on their way
+    issue_a(0);
+    issue_b(0);
+    if (NSTAGE == 3 && nsteps > 1) {
+        issue_a(1);
+        issue_b(1);
+    }
     for (int step = 0; step < nsteps; ++step) {
-        const int buf = step % IGD_NSTAGE;
-        // this stage's six loads are the oldest outstanding ones; the next stage's six may still fly
-        if (step + 1 < nsteps) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        const int buf = step % NSTAGE;
+        // this stage's loads are the oldest outstanding ones; with three buffers the next stage's
+        // may still be in flight
+        if (NSTAGE == 3 && step + 1 < nsteps) igd_wait_vmcnt<NSTAGE == 3 ? NL : 0>();
+        else igd_wait_vmcnt<0>();
         __syncthreads();   // every wave's part of this stage is in LDS; stage step-1 has been read by all
-        if (step + 2 < nsteps) issue((step + 2) % IGD_NSTAGE);   // into the buffer read in stage step-1
+        // the next loads go into the buffer read in stage step-1; the weight half is requested now,
+        // the pixel half in the middle of this stage's MFMAs, so the memory pipeline sees a steady
+        // stream instead of one burst per stage
+        const bool more = step + NSTAGE - 1 < nsteps;
+        const int nbuf = (step + NSTAGE - 1) % NSTAGE;
+        if (more) issue_a(nbuf);
         const uint4* __restrict__ sA = ring + buf * STAGE_SLOTS;
-        const uint4* __restrict__ sB = sA + BM * 4;
+        const uint4* __restrict__ sB = sA + BM * KG;
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
+        for (int kk = 0; kk < KG / 2; ++kk) {
             const int g = kk * 2 + (lane >> 5);
             v4i fa[MI], fb[NJ];
 #pragma unroll
             for (int i = 0; i < MI; ++i) {
-                const uint4 t = sA[lds_slot(wm * (BM / 2) + i * 32 + (lane & 31), g)];
+                const uint4 t = sA[igd_slot<KG>(wm * 64 + i * 32 + (lane & 31), g)];
                 fa[i] = v4i{(int)t.x, (int)t.y, (int)t.z, (int)t.w};
             }
 #pragma unroll
             for (int j = 0; j < NJ; ++j) {
-                const uint4 t = sB[lds_slot(wn * (BN / 2) + j * 32 + (lane & 31), g)];
+                const uint4 t = sB[igd_slot<KG>(wn * 128 + j * 32 + (lane & 31), g)];
                 fb[j] = v4i{(int)t.x, (int)t.y, (int)t.z, (int)t.w};
             }
 #pragma unroll
@@ -361,6 +405,7 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(const IgemmArgs a) {
 #pragma unroll
                 for (int j = 0; j < NJ; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+            if (kk == KG / 4 - 1 && more) issue_b(nbuf);
         }
     }
 
@@ -368,14 +413,14 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(const IgemmArgs a) {
     const float scale = __fmul_rn(a.sa[0], a.sb[0]);
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
-        const int col = colbase + wn * (BN / 2) + j * 32 + (lane & 31);
+        const int col = colbase + wn * 128 + j * 32 + (lane & 31);
         if (col >= ncols) continue;
         const int n = col / OHW, opix = col - n * OHW;
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int row = rowbase + wm * (BM / 2) + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                const int row = rowbase + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
                 if (row < a.rows) {
                     const size_t idx = ((size_t)n * a.rows + row) * OHW + opix;
                     const int val = acc[i][j][v];
@@ -385,6 +430,22 @@ __global__ __launch_bounds__(256, 2) void igemm_dma_kernel(const IgemmArgs a) {
             }
         }
     }
+}
+
+template <bool DGRAD, int WM, int KG, int NSTAGE>
+static hipError_t launch_igemm_dma(const IgemmArgs& a, int ncols, hipStream_t st) {
+    const size_t lds = (size_t)NSTAGE * (64 * WM + IGD_BN) * KG * 16;
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(igemm_dma_kernel<DGRAD, WM, KG, NSTAGE>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    const unsigned ctiles = (unsigned)((ncols + IGD_BN - 1) / IGD_BN), rtiles = (unsigned)((a.rows + 64 * WM - 1) / (64 * WM));
+    dim3 grid(((ctiles + 7) / 8) * 8 * rtiles);
+    hipLaunchKernelGGL((igemm_dma_kernel<DGRAD, WM, KG, NSTAGE>), grid, dim3(128 * WM), lds, st, a);
+    return hipGetLastError();
 }
 
 hipError_t launch_igemm(const IgemmArgs& a, hipStream_t st) {
@@ -398,19 +459,11 @@ hipError_t launch_igemm(const IgemmArgs& a, hipStream_t st) {
         if (a.dgrad) hipLaunchKernelGGL((igemm_kernel<64, 128, true>), grid, dim3(256), 0, st, a);
         else hipLaunchKernelGGL((igemm_kernel<64, 128, false>), grid, dim3(256), 0, st, a);
     } else if (gran >= 32 && (long long)((ncols + 255) / 256) * ((a.rows + 127) / 128) >= 256) {
-        // long reduction and enough 128 x 256 tiles to cover the chip: the wide tile
-        dim3 grid((ncols + 255) / 256, (a.rows + 127) / 128);
-        const size_t lds = (size_t)IGD_NSTAGE * (IGD_BM + IGD_BN) * 4 * 16;
-        static bool attr_done[2] = {false, false};
-        if (!attr_done[a.dgrad ? 1 : 0]) {
-            hipError_t e = hipFuncSetAttribute(
-                a.dgrad ? reinterpret_cast<const void*>(igemm_dma_kernel<true>) : reinterpret_cast<const void*>(igemm_dma_kernel<false>),
-                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            attr_done[a.dgrad ? 1 : 0] = true;
-        }
-        if (a.dgrad) hipLaunchKernelGGL((igemm_dma_kernel<true>), grid, dim3(256), lds, st, a);
-        else hipLaunchKernelGGL((igemm_dma_kernel<false>), grid, dim3(256), lds, st, a);
+        // long reduction and enough wide tiles to cover the chip
+        const long long t256 = (long long)((ncols + 255) / 256) * ((a.rows + 255) / 256);
+        if (t256 >= 192)
+            return a.dgrad ? launch_igemm_dma<true, 4, 8, 2>(a, ncols, st) : launch_igemm_dma<false, 4, 8, 2>(a, ncols, st);
+        return a.dgrad ? launch_igemm_dma<true, 2, 4, 3>(a, ncols, st) : launch_igemm_dma<false, 2, 4, 3>(a, ncols, st);
     } else {
         dim3 grid((ncols + 127) / 128, (a.rows + 127) / 128);
         if (a.dgrad) hipLaunchKernelGGL((igemm_kernel<128, 128, true>), grid, dim3(256), 0, st, a);
