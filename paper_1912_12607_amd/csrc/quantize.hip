@@ -116,7 +116,22 @@ __device__ __forceinline__ float resolve_clip(const float* __restrict__ clip,
 constexpr int QA_PIX = 64;
 constexpr int QA_CH = 64;
 
-template <bool STOCH, bool DEV>
+// 4x4 byte transpose: in d[i] = codes of 4 pixels for channel i; out o[p] = codes of 4 channels for pixel p
+__device__ __forceinline__ void qa_transpose4x4(const uint32_t d[4], uint32_t o[4]) {
+    const uint32_t t0 = __builtin_amdgcn_perm(d[1], d[0], 0x05010400u);  // d0.b0 d1.b0 d0.b1 d1.b1
+    const uint32_t t1 = __builtin_amdgcn_perm(d[1], d[0], 0x07030602u);  // d0.b2 d1.b2 d0.b3 d1.b3
+    const uint32_t t2 = __builtin_amdgcn_perm(d[3], d[2], 0x05010400u);
+    const uint32_t t3 = __builtin_amdgcn_perm(d[3], d[2], 0x07030602u);
+    o[0] = __builtin_amdgcn_perm(t2, t0, 0x05040100u);
+    o[1] = __builtin_amdgcn_perm(t2, t0, 0x07060302u);
+    o[2] = __builtin_amdgcn_perm(t3, t1, 0x05040100u);
+    o[3] = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
+}
+
+// VEC: H*W is a multiple of 4, so a thread can fetch four consecutive pixels of a channel with one
+// 16-byte load; it then owns a 4-channel x 4-pixel block, transposes its codes in registers and
+// writes one dword (4 channels) per pixel to the LDS tile.  Otherwise one pixel per lane, 4-byte loads.
+template <bool STOCH, bool DEV, bool VEC>
 __global__ __launch_bounds__(256) void quantize_act_kernel(
     const float* __restrict__ x, int C, int Cp, int HW, const float* __restrict__ clip,
     const float* __restrict__ absmax_part, int nparts, uint32_t seed_lo, uint32_t seed_hi_mul,
@@ -134,12 +149,23 @@ __global__ __launch_bounds__(256) void quantize_act_kernel(
 
     // issue every global load of this thread before anything depends on them
     float v[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    const int pq = threadIdx.x & 15, cgp = threadIdx.x >> 4;      // VEC: pixel quad, 4-channel group
+    if (VEC) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const int c = c0 + 4 * (wv + 4 * i) + j;
-            v[i][j] = (pv && c < C) ? x[((size_t)n * C + c) * HW + p] : 0.0f;
+            const int c = c0 + 4 * cgp + j;
+            float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (p0 + 4 * pq < HW && c < C) f = *reinterpret_cast<const float4*>(x + ((size_t)n * C + c) * HW + p0 + 4 * pq);
+            v[j][0] = f.x; v[j][1] = f.y; v[j][2] = f.z; v[j][3] = f.w;     // v[channel][pixel]
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int c = c0 + 4 * (wv + 4 * i) + j;
+                v[i][j] = (pv && c < C) ? x[((size_t)n * C + c) * HW + p] : 0.0f;
+            }
         }
     }
 
@@ -154,22 +180,46 @@ __global__ __launch_bounds__(256) void quantize_act_kernel(
 
     double A = 0.0, G = 0.0;
     unsigned long long B = 0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        int code[4];
+    if (VEC) {
+        uint32_t d[4], o[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const int c = c0 + 4 * (wv + 4 * i) + j;
-            const uint32_t idx = (uint32_t)(((size_t)n * C + c) * HW + p);
-            code[j] = quantize_one<STOCH>(v[i][j], inv, seed_lo, seed_hi_mul, idx);
-            if (DEV) {
-                const double g = (double)v[i][j];
-                A = fma(g, (double)code[j], A);
-                G = fma(g, g, G);
-                B += (unsigned)(code[j] * code[j]);
+            const int c = c0 + 4 * cgp + j;
+            int code[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t idx = (uint32_t)(((size_t)n * C + c) * HW + p0 + 4 * pq + k);
+                code[k] = quantize_one<STOCH>(v[j][k], inv, seed_lo, seed_hi_mul, idx);
+                if (DEV) {
+                    const double g = (double)v[j][k];
+                    A = fma(g, (double)code[k], A);
+                    G = fma(g, g, G);
+                    B += (unsigned)(code[k] * code[k]);
+                }
             }
+            d[j] = pack4(code[0], code[1], code[2], code[3]);
         }
-        tile[lane][wv + 4 * i] = pack4(code[0], code[1], code[2], code[3]);
+        qa_transpose4x4(d, o);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) tile[4 * pq + k][cgp] = o[k];
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int code[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int c = c0 + 4 * (wv + 4 * i) + j;
+                const uint32_t idx = (uint32_t)(((size_t)n * C + c) * HW + p);
+                code[j] = quantize_one<STOCH>(v[i][j], inv, seed_lo, seed_hi_mul, idx);
+                if (DEV) {
+                    const double g = (double)v[i][j];
+                    A = fma(g, (double)code[j], A);
+                    G = fma(g, g, G);
+                    B += (unsigned)(code[j] * code[j]);
+                }
+            }
+            tile[lane][wv + 4 * i] = pack4(code[0], code[1], code[2], code[3]);
+        }
     }
     __syncthreads();
 
@@ -198,9 +248,15 @@ hipError_t launch_quantize_act(const QuantArgs& a, hipStream_t st) {
     dim3 grid((HW + QA_PIX - 1) / QA_PIX, (Cp + QA_CH - 1) / QA_CH, N);
     const uint32_t slo = (uint32_t)a.seed, shi = seed_hi_term(a.seed);
     KernelTimer kt(KID_QUANTIZE_ACT, st);
-#define LAUNCH(ST, DV)                                                                               \
-    hipLaunchKernelGGL((quantize_act_kernel<ST, DV>), grid, dim3(256), 0, st, a.x, C, Cp, HW, a.clip, \
-                       a.absmax_part, a.nparts, slo, shi, a.q, a.scale, a.devpart)
+#define LAUNCH(ST, DV)                                                                                      \
+    do {                                                                                                    \
+        if ((HW & 3) == 0)                                                                                  \
+            hipLaunchKernelGGL((quantize_act_kernel<ST, DV, true>), grid, dim3(256), 0, st, a.x, C, Cp, HW, \
+                               a.clip, a.absmax_part, a.nparts, slo, shi, a.q, a.scale, a.devpart);         \
+        else                                                                                                \
+            hipLaunchKernelGGL((quantize_act_kernel<ST, DV, false>), grid, dim3(256), 0, st, a.x, C, Cp, HW, \
+                               a.clip, a.absmax_part, a.nparts, slo, shi, a.q, a.scale, a.devpart);         \
+    } while (0)
     if (a.stochastic) {
         if (a.devpart) LAUNCH(true, true); else LAUNCH(true, false);
     } else {
