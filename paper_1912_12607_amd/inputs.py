@@ -79,6 +79,9 @@ CONFIGS: Dict[int, List[Layer]] = {
     4: [Layer("inc_1x7", 64, 768, 17, 17, 768, 1, 7, pad=(0, 3)),
         Layer("inc_7x1", 64, 768, 17, 17, 768, 7, 1, pad=(3, 0)),
         Layer("inc_3x3_s2", 64, 768, 17, 17, 192, 3, 3, stride=(2, 2), pad=(0, 0))],
+    # beyond the benchmark's list: a fully connected layer (the paper replaces conv AND fc layers,
+    # Sec.4 setup) is the 1x1 convolution of a 1x1 image; ResNet-50's classifier at batch 256
+    5: [Layer("r50_fc", 256, 2048, 1, 1, 1000, 1, 1)],
 }
 
 # Default clip candidates of the search: ratio_j = 2^(-j/4), j = 0..31 (j = 0 is "no clipping").

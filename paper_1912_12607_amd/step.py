@@ -100,11 +100,14 @@ class LayerStep:
         B.int8t_conv_bwd_weight(self.desc, self.xq, self.sx, self.dyq, self.sdy, self.dw, self.dw_acc,
                                 self.ws, stream)
 
-    def run(self, seed: int = 0, stream=None):
-        """The whole hot path once."""
+    def run(self, seed: int = 0, stream=None, search: bool = True):
+        """The whole hot path once.  search=False keeps the clip value of the last search (the
+        paper's Periodic Update, Sec.3.4 / Table 2: the clip is refreshed every P iterations only);
+        the caller decides the period."""
         self.quantize_x(stream)
         self.quantize_w(stream)
-        self.dsgc(seed, stream)
+        if search:
+            self.dsgc(seed, stream)
         self.quantize_dy(seed, stream)
         self.fwd(stream)
         self.bwd_data(stream)

@@ -193,6 +193,7 @@ CONV_SHAPES = [
     (2, 12, 9, 9, 12, 3, 3, (1, 1), (1, 1), 12),      # depthwise
     (1, 5, 11, 8, 5, 3, 3, (2, 2), (1, 1), 5),        # depthwise stride 2
     (2, 7, 6, 9, 7, 5, 3, (1, 2), (2, 0), 7),         # depthwise odd filter
+    (33, 200, 1, 1, 70, 1, 1, (1, 1), (0, 0), 1),     # fully connected layer: 1x1 filter on a 1x1 image
     (2, 6, 8, 12, 6, 3, 5, (1, 1), (1, 2), 6),         # depthwise stride 1, 5-wide filter, row length a multiple of 4
     (1, 4, 10, 11, 4, 3, 3, (1, 1), (0, 0), 4),        # depthwise stride 1, no padding
     (3, 5, 16, 16, 5, 3, 3, (1, 1), (1, 1), 5),        # depthwise, plane size a multiple of 16
@@ -298,7 +299,7 @@ def test_config0_full_step_elementwise():
     assert phi == oracle.dclr(st.dev_final.item())
 
 
-FULL_LAYERS = [(1, 0), (2, 0), (2, 1), (2, 2), (3, 0), (3, 1), (3, 2), (4, 0), (4, 1), (4, 2)]
+FULL_LAYERS = [(1, 0), (2, 0), (2, 1), (2, 2), (3, 0), (3, 1), (3, 2), (4, 0), (4, 1), (4, 2), (5, 0)]
 
 
 @pytest.mark.parametrize("cfg,li", FULL_LAYERS)
