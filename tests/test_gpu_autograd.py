@@ -1,0 +1,105 @@
+"""The autograd plug-in (paper_1912_12607_amd/autograd.py) against the CPU oracle: one forward and
+backward pass of Int8Conv2d must give exactly the tensors the oracle's step gives for the same
+inputs, seed and candidate ratios; plus a plausibility check against an fp32 convolution and the
+Periodic Update bookkeeping."""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+if not torch.cuda.is_available():
+    pytest.skip("no GPU", allow_module_level=True)
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import oracle  # noqa: E402
+from paper_1912_12607_amd import inputs  # noqa: E402
+
+REL_TOL = 1e-6
+DEV_TOL = 1e-9
+STO = oracle.ROUND_STOCHASTIC
+
+
+def _layer(C, K, ks, stride, pad, groups, seed=0, **kw):
+    from paper_1912_12607_amd.autograd import Int8Conv2d
+    torch.manual_seed(seed)
+    return Int8Conv2d(C, K, ks, stride=stride, padding=pad, groups=groups, seed=100, **kw)
+
+
+@pytest.mark.parametrize("shape", [
+    (2, 16, 8, 8, 32, (3, 3), (1, 1), (1, 1), 1),
+    (3, 24, 7, 9, 40, (1, 1), (1, 1), (0, 0), 1),
+    (2, 12, 9, 9, 12, (3, 3), (1, 1), (1, 1), 12),
+    (2, 20, 11, 13, 10, (3, 3), (2, 2), (0, 0), 1),
+])
+def test_forward_backward_match_oracle(shape):
+    N, C, H, W, K, ks, stride, pad, groups = shape
+    m = _layer(C, K, ks, stride, pad, groups)
+    r = np.random.default_rng(7)
+    x = r.standard_normal((N, C, H, W)).astype(np.float32)
+    xt = torch.from_numpy(x).cuda().requires_grad_(True)
+    y = m(xt)
+    dy = (r.standard_t(3, size=tuple(y.shape)) * 1e-3).astype(np.float32)
+    y.backward(torch.from_numpy(dy).cuda())
+    torch.cuda.synchronize()
+
+    w = m.weight.detach().cpu().numpy()
+    od = oracle.make_desc(N, C, H, W, K, ks[0], ks[1], stride, pad, groups)
+    xq, sx = oracle.quantize(x)
+    wq, sw = oracle.quantize(w)
+    seed = 101                                   # the layer's first backward pass draws seed + 1
+    o = oracle.dsgc(dy.reshape(-1), inputs.default_ratios(32), mode=STO, seed=seed)
+    dyq, sdy = oracle.quantize(dy, c=o["clip"], mode=STO, seed=seed)
+    assert m.clip.item() == o["clip"]
+    assert abs(m.deviation.item() - o["deviation"]) < DEV_TOL
+    assert m.dclr_scale() == oracle.dclr(m.deviation.item())
+    for got, want64, s1, s2 in ((y, oracle.conv_fwd(od, xq, wq), sx, sw),
+                                (xt.grad, oracle.conv_bwd_data(od, dyq, wq), sdy, sw),
+                                (m.weight.grad, oracle.conv_bwd_weight(od, xq, dyq), sx, sdy)):
+        want32, ov = oracle.wrap32(want64)
+        assert ov == 0
+        ref = oracle.dequant(want32, s1, s2)
+        g = got.detach().cpu().numpy()
+        assert g.shape == ref.shape
+        assert np.all(np.abs(g - ref) <= REL_TOL * np.abs(ref))
+
+
+def test_close_to_fp32_convolution():
+    """Plausibility only: the INT8 layer's outputs and gradients point the same way as an fp32
+    convolution's (cosine similarity), to within what 8-bit codes allow."""
+    m = _layer(32, 48, (3, 3), (1, 1), (1, 1), 1)
+    r = np.random.default_rng(3)
+    x = torch.from_numpy(r.standard_normal((4, 32, 12, 12)).astype(np.float32)).cuda()
+    xa = x.clone().requires_grad_(True)
+    xb = x.clone().requires_grad_(True)
+    wb = m.weight.detach().clone().requires_grad_(True)
+    ya = m(xa)
+    yb = torch.nn.functional.conv2d(xb, wb, padding=1)
+    dy = torch.from_numpy(r.standard_normal(tuple(ya.shape)).astype(np.float32)).cuda()
+    ya.backward(dy)
+    yb.backward(dy)
+    cos = lambda a, b: float(torch.nn.functional.cosine_similarity(a.detach().flatten(), b.detach().flatten(), dim=0))
+    assert cos(ya, yb) > 0.999
+    assert cos(xa.grad, xb.grad) > 0.99
+    assert cos(m.weight.grad, wb.grad) > 0.99
+
+
+def test_periodic_update_keeps_clip_between_searches():
+    m = _layer(16, 16, (3, 3), (1, 1), (1, 1), 1, dsgc_period=3)
+    r = np.random.default_rng(5)
+    clips = []
+    for it in range(4):
+        x = torch.from_numpy(r.standard_normal((2, 16, 8, 8)).astype(np.float32)).cuda().requires_grad_(True)
+        y = m(x)
+        dy = (r.standard_t(3, size=tuple(y.shape)) * (1e-3 * (it + 1))).astype(np.float32)
+        y.backward(torch.from_numpy(dy).cuda())
+        clips.append(m.clip.item())
+        assert 0.0 <= m.deviation.item() <= 2.0
+    assert clips[0] == clips[1] == clips[2]        # searched at pass 0, kept for passes 1 and 2
+    assert clips[3] != clips[0]                    # searched again at pass 3 (the gradients have grown)
