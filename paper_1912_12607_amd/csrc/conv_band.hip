@@ -256,7 +256,7 @@ __global__ __launch_bounds__(256, 2) void band_reg_kernel(const IgemmArgs a, int
                                                           const BandRegTab tab) {
     extern __shared__ __attribute__((aligned(16))) uint4 lds[];
     const int Cg16 = a.Ca >> 4;
-    const int G = 2 * NKS;                    // = R * S * Cg16 (host)
+    constexpr int G = 2 * NKS;                // = R * S * Cg16 (host)
     const int PG = odd_pitch(Cg16);
     const int WH = BP + a.R - 1, WW = a.OW + a.S - 1;
     uint4* __restrict__ xW = lds;             // [WH*WW pixels][PG]
@@ -317,21 +317,38 @@ __global__ __launch_bounds__(256, 2) void band_reg_kernel(const IgemmArgs a, int
     }
     if (band_first < band_end) issue(band_first);
 
-    // ---- weight fragments, once per block, straight from global memory.  Buffer loads: a row
-    // beyond a.rows lies outside the descriptor and reads as zero, so no select waits on the data.
+    // ---- weight fragments, once per block.  Every wave needs the whole 64-row matrix; fetched by
+    // each lane for itself that is four copies of it through the L1 per block, and the L1 fill rate
+    // then sets the length of the prologue.  So the block fetches the matrix once, fully coalesced,
+    // into LDS (the window buffer is not in use yet) and the lanes pick their fragments from there.
+    // Buffer loads: a row beyond a.rows lies outside the descriptor and reads as zero.
     v4i fa[NKS][2];
     {
+        constexpr int GPW = (G & 1) ? G : G + 1;       // odd pitch: a wave's 32 rows hit 32 different bank groups
         const __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<int8_t*>(a.wgt), 0, (uint32_t)a.rows * G * 16u, 0x00020000);
+        constexpr int PER = (64 * G + 255) / 256;
+        uint4 tmp[PER];
 #pragma unroll
-        for (int m = 0; m < 2; ++m) {
-            const uint32_t off = ((uint32_t)(m * 32 + l32) * G + half) * 16u;
+        for (int i = 0; i < PER; ++i) {
+            const uint32_t gi = (uint32_t)(tid + 256 * i);          // granule index in [row][G] order
+            const auto t4 = __builtin_amdgcn_raw_buffer_load_b128(wr, gi < 64u * G ? gi * 16u : 0x80000000u, 0, 0);
+            tmp[i] = make_uint4(t4[0], t4[1], t4[2], t4[3]);
+        }
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int gi = tid + 256 * i;
+            if (gi < 64 * G) lds[(gi / G) * GPW + (gi % G)] = tmp[i];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int m = 0; m < 2; ++m)
 #pragma unroll
             for (int ks = 0; ks < NKS; ++ks) {
-                const auto t4 = __builtin_amdgcn_raw_buffer_load_b128(wr, off + ks * 32u, 0, 0);
-                fa[ks][m] = v4i{(int)t4[0], (int)t4[1], (int)t4[2], (int)t4[3]};
+                const uint4 t = lds[(m * 32 + l32) * GPW + 2 * ks + half];
+                fa[ks][m] = v4i{(int)t.x, (int)t.y, (int)t.z, (int)t.w};
             }
-        }
+        // (the band loop starts with a barrier, so the window may overwrite this area afterwards)
     }
     int koff[NKS];
 #pragma unroll
@@ -453,7 +470,9 @@ bool launch_band(const IgemmArgs& a, hipStream_t st, hipError_t* err) {
         BR(2, 0) BR(4, 1) BR(9, 2) BR(18, 3)
 #undef BR
         if (kr) {
-            const size_t ldsr = (size_t)WH * WW * odd_pitch(Cg16) * 16;
+            size_t ldsr = (size_t)WH * WW * odd_pitch(Cg16) * 16;
+            const size_t ldsw = (size_t)64 * odd_pitch(G) * 16;     // the weight matrix passes through LDS first
+            if (ldsw > ldsr) ldsr = ldsw;
             static bool attr_done_r[8] = {};
             if (!attr_done_r[slot]) {
                 hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kr),
