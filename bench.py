@@ -54,6 +54,7 @@ def algorithmic(L, n_cand):
         # point, digit planes, LDS traffic); the products and sums themselves run on the matrix cores
         "dsgc_sweep_kernel": dict(bytes=4 * n_y, ops=(2.75 * n_cand + 30 * ((n_cand + 31) // 32)) * n_y),
         "igemm_kernel": conv2, "band_kernel": conv2, "dw_conv_kernel": conv2,
+        "igemm_reduce_kernel": dict(bytes=4 * (n_x + n_y), ops=0),               # final sum of a split reduction
         "wgrad_kernel": wg, "dw_wgrad_kernel": wg,
         "wgrad_reduce_kernel": dict(bytes=4 * n_w, ops=0), "dw_wgrad_reduce_kernel": dict(bytes=4 * n_w, ops=0),
     }

@@ -107,7 +107,11 @@ size_t int8t_code_bytes(const int dims[4], int8t_kind kind);
 /* Scratch a call needs.  DSGC: n = element count, n_cand = number of candidates, desc ignored.
  * CONV_*: desc required, n / n_cand ignored.  QUANTIZE: use int8t_quantize_workspace_bytes()
  * (this function returns 0 for it).  0 also means "bad arguments" for the CONV ops whose
- * descriptor is invalid; the call itself then reports the error. */
+ * descriptor is invalid; the call itself then reports the error.
+ * CONV_BWD_WEIGHT and DSGC require their scratch.  CONV_FWD / CONV_BWD_DATA only use it as a
+ * performance aid (layers with few output tiles and a long reduction split the reduction over
+ * several workgroups and keep int32 partial sums there; integer sums, so the result is the same
+ * bit for bit): ws_dev may be NULL or smaller, the call then runs without the split. */
 size_t int8t_workspace_bytes(int8t_op op, const int8t_conv_desc *desc, size_t n, int n_cand);
 
 /* Scratch of int8t_quantize for a tensor of logical dims and code layout `kind`; covers both the
@@ -159,6 +163,8 @@ int8t_status int8t_dsgc_clip(const float *g_dev, size_t n, const float *ratios_d
  *   sx_dev, sw_dev   1 float each (the scales int8t_quantize wrote)
  *   y_dev    out: fp32 N,K,P,Q
  *   acc_dev  NULL, or out: int32 N,K,P,Q, the raw accumulators
+ *   ws_dev   NULL, or int8t_workspace_bytes(INT8T_OP_CONV_FWD, ...) bytes of scratch, 16-byte aligned
+ *            (optional, see there; the same holds for int8t_conv_bwd_data)
  */
 int8t_status int8t_conv_fwd(const int8t_conv_desc *desc,
                             const int8_t *xq_dev, const float *sx_dev,
@@ -195,7 +201,7 @@ int8t_status int8t_conv_bwd_weight(const int8t_conv_desc *desc,
  * every launch of the selected kernel.
  *   kernel   host string: the kernel's name ("dsgc_sweep_kernel", "absmax_kernel",
  *            "quantize_act_kernel", "quantize_planar_kernel", "quantize_wgt_kernel",
- *            "deviation_finish_kernel", "igemm_kernel", "band_kernel",
+ *            "deviation_finish_kernel", "igemm_kernel", "igemm_reduce_kernel", "band_kernel",
  *            "wgrad_kernel", "wgrad_reduce_kernel", "dw_conv_kernel", "dw_wgrad_kernel",
  *            "dw_wgrad_reduce_kernel"); NULL or "" selects every kernel.
  *            An unknown name returns INT8T_ERR_ARG and leaves timing off.

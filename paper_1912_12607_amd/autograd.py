@@ -43,7 +43,8 @@ class _Int8ConvFn(torch.autograd.Function):
         B.int8t_quantize(w, w.shape, wgt_kind, None, B.ROUND_NEAREST_EVEN, 0, wq, sw, None,
                          _scratch(B.int8t_quantize_workspace_bytes(w.shape, wgt_kind), dev))
         y = torch.empty((N, K, P, Q), dtype=f32, device=dev)
-        B.int8t_conv_fwd(desc, xq, sx, wq, sw, y)
+        nf = B.int8t_workspace_bytes(B.OP_CONV_FWD, desc)
+        B.int8t_conv_fwd(desc, xq, sx, wq, sw, y, None, _scratch(nf, dev) if nf else None)
         ctx.layer, ctx.desc, ctx.act_kind = layer, desc, act_kind
         ctx.x_shape, ctx.w_shape = tuple(x.shape), tuple(w.shape)
         ctx.save_for_backward(xq, sx, wq, sw)
@@ -60,7 +61,8 @@ class _Int8ConvFn(torch.autograd.Function):
         seed = layer.next_seed()
         ws = _scratch(max(B.int8t_workspace_bytes(B.OP_DSGC, None, n_y, layer.ratios.numel()),
                           B.int8t_quantize_workspace_bytes(dy.shape, ctx.act_kind),
-                          B.int8t_workspace_bytes(B.OP_CONV_BWD_WEIGHT, desc)), dev)
+                          B.int8t_workspace_bytes(B.OP_CONV_BWD_WEIGHT, desc),
+                          B.int8t_workspace_bytes(B.OP_CONV_BWD_DATA, desc)), dev)
         if layer.clip is None:
             layer.clip = torch.empty(1, dtype=f32, device=dev)
             layer.deviation = torch.zeros(1, dtype=f64, device=dev)
@@ -78,7 +80,7 @@ class _Int8ConvFn(torch.autograd.Function):
         dx = dw = None
         if ctx.needs_input_grad[0]:
             dx = torch.empty(ctx.x_shape, dtype=f32, device=dev)
-            B.int8t_conv_bwd_data(desc, dyq, sdy, wq, sw, dx)
+            B.int8t_conv_bwd_data(desc, dyq, sdy, wq, sw, dx, None, ws)
         if ctx.needs_input_grad[1]:
             dw = torch.empty(ctx.w_shape, dtype=f32, device=dev)
             B.int8t_conv_bwd_weight(desc, xq, sx, dyq, sdy, dw, None, ws)

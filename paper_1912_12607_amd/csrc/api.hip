@@ -80,6 +80,20 @@ void fill_wgrad_geometry(WgradArgs* a, const int8t_conv_desc* d, const Geo& g) {
     a->stride_h = d->stride_h; a->stride_w = d->stride_w; a->pad_h = d->pad_h; a->pad_w = d->pad_w;
 }
 
+// geometry of the implicit GEMMs (pointers are set by the entry points)
+void fill_igemm_fwd(IgemmArgs* a, const int8t_conv_desc* d, const Geo& g) {
+    a->N = d->N; a->rows = d->K; a->Ca = pad16(d->C);
+    a->IH = d->H; a->IW = d->W; a->OH = g.P; a->OW = g.Q; a->R = d->R; a->S = d->S;
+    a->stride_h = d->stride_h; a->stride_w = d->stride_w; a->pad_h = d->pad_h; a->pad_w = d->pad_w;
+    a->dgrad = 0;
+}
+void fill_igemm_bwd_data(IgemmArgs* a, const int8t_conv_desc* d, const Geo& g) {
+    a->N = d->N; a->rows = d->C; a->Ca = pad16(d->K);
+    a->IH = g.P; a->IW = g.Q; a->OH = d->H; a->OW = d->W; a->R = d->R; a->S = d->S;
+    a->stride_h = d->stride_h; a->stride_w = d->stride_w; a->pad_h = d->pad_h; a->pad_w = d->pad_w;
+    a->dgrad = 1;
+}
+
 }  // namespace
 
 extern "C" {
@@ -116,7 +130,16 @@ size_t int8t_workspace_bytes(int8t_op op, const int8t_conv_desc* desc, size_t n,
         case INT8T_OP_QUANTIZE: return 0;
         case INT8T_OP_DSGC: return dsgc_ws_bytes(n);
         case INT8T_OP_CONV_FWD:
-        case INT8T_OP_CONV_BWD_DATA: return 0;
+        case INT8T_OP_CONV_BWD_DATA: {
+            // optional: partial sums of a split reduction (layers with few output tiles)
+            Geo g;
+            if (desc_ok(desc, &g) != INT8T_OK || g.depthwise) return 0;
+            IgemmArgs a{};
+            if (op == INT8T_OP_CONV_FWD) fill_igemm_fwd(&a, desc, g);
+            else fill_igemm_bwd_data(&a, desc, g);
+            const int ks = igemm_ksplit(a);
+            return ks > 1 ? align256((size_t)ks * a.N * a.rows * a.OH * a.OW * 4) : 0;
+        }
         case INT8T_OP_CONV_BWD_WEIGHT: {
             Geo g;
             if (desc_ok(desc, &g) != INT8T_OK) return 0;
@@ -217,12 +240,12 @@ int8t_status int8t_dsgc_clip(const float* g_dev, size_t n, const float* ratios_d
 int8t_status int8t_conv_fwd(const int8t_conv_desc* desc, const int8_t* xq_dev, const float* sx_dev,
                             const int8_t* wq_dev, const float* sw_dev, float* y_dev, int32_t* acc_dev,
                             void* ws_dev, size_t ws_bytes, void* stream) {
-    (void)ws_dev; (void)ws_bytes;
     Geo g;
     int8t_status s = desc_ok(desc, &g);
     if (s != INT8T_OK) return s;
     if (!xq_dev || !sx_dev || !wq_dev || !sw_dev || !y_dev) return INT8T_ERR_NULL;
-    if (!aligned16(xq_dev) || !aligned16(wq_dev) || !aligned16(y_dev) || !aligned4(acc_dev)) return INT8T_ERR_ARG;
+    if (!aligned16(xq_dev) || !aligned16(wq_dev) || !aligned16(y_dev) || !aligned4(acc_dev) || !aligned16(ws_dev))
+        return INT8T_ERR_ARG;
     hipStream_t st = (hipStream_t)stream;
     if (g.depthwise) {
         DwArgs a{};
@@ -233,23 +256,21 @@ int8t_status int8t_conv_fwd(const int8t_conv_desc* desc, const int8_t* xq_dev, c
         return launch_dw_conv(a, st) == hipSuccess ? INT8T_OK : INT8T_ERR_RUNTIME;
     }
     IgemmArgs a{};
+    fill_igemm_fwd(&a, desc, g);
     a.act = xq_dev; a.wgt = wq_dev; a.sa = sx_dev; a.sb = sw_dev; a.out = y_dev; a.acc = acc_dev;
-    a.N = desc->N; a.rows = desc->K; a.Ca = pad16(desc->C);
-    a.IH = desc->H; a.IW = desc->W; a.OH = g.P; a.OW = g.Q; a.R = desc->R; a.S = desc->S;
-    a.stride_h = desc->stride_h; a.stride_w = desc->stride_w; a.pad_h = desc->pad_h; a.pad_w = desc->pad_w;
-    a.dgrad = 0;
+    a.partial = (int32_t*)ws_dev; a.partial_bytes = ws_dev ? ws_bytes : 0;
     return launch_igemm(a, st) == hipSuccess ? INT8T_OK : INT8T_ERR_RUNTIME;
 }
 
 int8t_status int8t_conv_bwd_data(const int8t_conv_desc* desc, const int8_t* dyq_dev, const float* sdy_dev,
                                  const int8_t* wq_dev, const float* sw_dev, float* dx_dev, int32_t* acc_dev,
                                  void* ws_dev, size_t ws_bytes, void* stream) {
-    (void)ws_dev; (void)ws_bytes;
     Geo g;
     int8t_status s = desc_ok(desc, &g);
     if (s != INT8T_OK) return s;
     if (!dyq_dev || !sdy_dev || !wq_dev || !sw_dev || !dx_dev) return INT8T_ERR_NULL;
-    if (!aligned16(dyq_dev) || !aligned16(wq_dev) || !aligned16(dx_dev) || !aligned4(acc_dev)) return INT8T_ERR_ARG;
+    if (!aligned16(dyq_dev) || !aligned16(wq_dev) || !aligned16(dx_dev) || !aligned4(acc_dev) || !aligned16(ws_dev))
+        return INT8T_ERR_ARG;
     hipStream_t st = (hipStream_t)stream;
     if (g.depthwise) {
         DwArgs a{};
@@ -260,14 +281,12 @@ int8t_status int8t_conv_bwd_data(const int8t_conv_desc* desc, const int8_t* dyq_
         return launch_dw_conv(a, st) == hipSuccess ? INT8T_OK : INT8T_ERR_RUNTIME;
     }
     IgemmArgs a{};
+    fill_igemm_bwd_data(&a, desc, g);
     a.act = dyq_dev;
     // second copy of the weight codes: [C][R][S][Kp]
     a.wgt = wq_dev + align256((size_t)desc->K * desc->R * desc->S * pad16(desc->C));
     a.sa = sdy_dev; a.sb = sw_dev; a.out = dx_dev; a.acc = acc_dev;
-    a.N = desc->N; a.rows = desc->C; a.Ca = pad16(desc->K);
-    a.IH = g.P; a.IW = g.Q; a.OH = desc->H; a.OW = desc->W; a.R = desc->R; a.S = desc->S;
-    a.stride_h = desc->stride_h; a.stride_w = desc->stride_w; a.pad_h = desc->pad_h; a.pad_w = desc->pad_w;
-    a.dgrad = 1;
+    a.partial = (int32_t*)ws_dev; a.partial_bytes = ws_dev ? ws_bytes : 0;
     return launch_igemm(a, st) == hipSuccess ? INT8T_OK : INT8T_ERR_RUNTIME;
 }
 

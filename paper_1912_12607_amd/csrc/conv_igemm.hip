@@ -50,6 +50,9 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmArgs a) {
     const int nsteps = (gtot + 3) >> 2;
     const int rowbase = blockIdx.y * BM;
     const int colbase = blockIdx.x * BN;
+    // split reduction: block z works on the stages [step0, step1) and stores raw partial sums
+    const int step0 = (int)(((long long)nsteps * blockIdx.z) / a.ksplit);
+    const int step1 = (int)(((long long)nsteps * (blockIdx.z + 1)) / a.ksplit);
 
     // ---- loader state -----------------------------------------------------------------------
     // B (pixels): NB columns per thread, fixed for the whole reduction
@@ -70,8 +73,9 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmArgs a) {
     // reduction position of this thread's granule: filter tap (r,s) and channel granule cg
     int r, s, cg;
     {
-        const int tap = lg / Cg16;
-        cg = lg - tap * Cg16;
+        const int q0 = step0 * 4 + lg;
+        const int tap = q0 / Cg16;
+        cg = q0 - tap * Cg16;
         r = tap / a.S;
         s = tap - r * a.S;
     }
@@ -142,12 +146,12 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmArgs a) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
-    load_step(0);
-    stage(0);
+    load_step(step0);
+    stage(step0 & 1);
     __syncthreads();
-    for (int step = 0; step < nsteps; ++step) {
+    for (int step = step0; step < step1; ++step) {
         const int buf = step & 1;
-        if (step + 1 < nsteps) load_step(step + 1);     // in flight while this stage computes
+        if (step + 1 < step1) load_step(step + 1);      // in flight while this stage computes
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
             const int g = kk * 2 + (lane >> 5);
@@ -169,11 +173,14 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmArgs a) {
                     acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
         }
         // the other buffer was last read one stage ago, before the barrier that ended that stage
-        if (step + 1 < nsteps) stage(buf ^ 1);
+        if (step + 1 < step1) stage(buf ^ 1);
         __syncthreads();
     }
 
-    // ---- epilogue: Eq.2, straight into N,C,H,W ----------------------------------------------
+    // ---- epilogue: Eq.2, straight into N,C,H,W; a split reduction leaves its share of the sums
+    // in partial[z][N][rows][OH*OW] for igemm_reduce_kernel instead ---------------------------
+    const bool split = a.ksplit > 1;
+    int32_t* __restrict__ const part = split ? a.partial + (size_t)blockIdx.z * a.N * a.rows * OHW : nullptr;
     const float scale = __fmul_rn(a.sa[0], a.sb[0]);
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
@@ -188,10 +195,48 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmArgs a) {
                 if (row < a.rows) {
                     const size_t idx = ((size_t)n * a.rows + row) * OHW + opix;
                     const int val = acc[i][j][v];
-                    a.out[idx] = __fmul_rn((float)val, scale);
-                    if (a.acc) a.acc[idx] = val;
+                    if (split) {
+                        part[idx] = val;
+                    } else {
+                        a.out[idx] = __fmul_rn((float)val, scale);
+                        if (a.acc) a.acc[idx] = val;
+                    }
                 }
             }
+        }
+    }
+}
+
+// Sum of the ksplit partial results (integer addition: exact in any order) and Eq.2.  A thread owns
+// four consecutive results; VEC: the result count is a multiple of 4, so every slice is 16-byte aligned.
+template <bool VEC>
+__global__ __launch_bounds__(256) void igemm_reduce_kernel(const IgemmArgs a, size_t total) {
+    const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i >= total) return;
+    const float scale = __fmul_rn(a.sa[0], a.sb[0]);
+    if (VEC) {
+        int4 sum = make_int4(0, 0, 0, 0);
+        int z = 0;
+        for (; z + 4 <= a.ksplit; z += 4) {
+            int4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const int4*>(a.partial + (size_t)(z + u) * total + i);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { sum.x += v[u].x; sum.y += v[u].y; sum.z += v[u].z; sum.w += v[u].w; }
+        }
+        for (; z < a.ksplit; ++z) {
+            const int4 v = *reinterpret_cast<const int4*>(a.partial + (size_t)z * total + i);
+            sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+        }
+        *reinterpret_cast<float4*>(a.out + i) = make_float4(__fmul_rn((float)sum.x, scale), __fmul_rn((float)sum.y, scale),
+                                                            __fmul_rn((float)sum.z, scale), __fmul_rn((float)sum.w, scale));
+        if (a.acc) { a.acc[i] = sum.x; a.acc[i + 1] = sum.y; a.acc[i + 2] = sum.z; a.acc[i + 3] = sum.w; }
+    } else {
+        for (size_t e = i; e < total && e < i + 4; ++e) {
+            int sum = 0;
+            for (int z = 0; z < a.ksplit; ++z) sum += a.partial[(size_t)z * total + e];
+            a.out[e] = __fmul_rn((float)sum, scale);
+            if (a.acc) a.acc[e] = sum;
         }
     }
 }
@@ -448,18 +493,59 @@ static hipError_t launch_igemm_dma(const IgemmArgs& a, int ncols, hipStream_t st
     return hipGetLastError();
 }
 
-hipError_t launch_igemm(const IgemmArgs& a, hipStream_t st) {
-    hipError_t berr = hipSuccess;
-    if (launch_band(a, st, &berr)) return berr;   // small filter bank: LDS-resident kernel
-    const int ncols = a.N * a.OH * a.OW;
-    KernelTimer kt(KID_IGEMM, st);
+namespace {
+// long reduction and enough wide tiles to cover the chip
+bool igemm_wide(const IgemmArgs& a) {
+    const long long ncols = (long long)a.N * a.OH * a.OW;
     const long long gran = (long long)a.R * a.S * (a.Ca >> 4);
+    return a.rows > 64 && gran >= 32 && ((ncols + 255) / 256) * ((a.rows + 127) / 128) >= 256;
+}
+}  // namespace
+
+// Layers with few output tiles and a long reduction (a strided 3x3 on a small image, a fully
+// connected layer) leave most compute units idle: their reduction is split over up to
+// ceil(512 / tiles) blocks per tile, at least 4 stages each.  1 = no split.
+int igemm_ksplit(const IgemmArgs& a) {
+    if (a.rows <= 64 || igemm_wide(a)) return 1;
+    const long long ncols = (long long)a.N * a.OH * a.OW;
+    const long long tiles = ((ncols + 127) / 128) * ((a.rows + 127) / 128);
+    const long long nsteps = ((long long)a.R * a.S * (a.Ca >> 4) + 3) / 4;
+    if (tiles >= 192 || nsteps < 8) return 1;
+    long long ks = (512 + tiles - 1) / tiles;
+    if (ks > nsteps / 4) ks = nsteps / 4;
+    return ks < 2 ? 1 : (int)ks;
+}
+
+hipError_t launch_igemm(const IgemmArgs& a_in, hipStream_t st) {
+    hipError_t berr = hipSuccess;
+    if (launch_band(a_in, st, &berr)) return berr;   // small filter bank: LDS-resident kernel
+    IgemmArgs a = a_in;
+    const int ncols = a.N * a.OH * a.OW;
+    // the split needs its scratch; without it the reduction simply stays whole
+    a.ksplit = igemm_ksplit(a);
+    if (a.ksplit > 1 && (a.partial == nullptr || a.partial_bytes < (size_t)a.ksplit * a.rows * ncols * 4)) a.ksplit = 1;
+    if (a.ksplit > 1) {
+        {
+            KernelTimer kt(KID_IGEMM, st);
+            dim3 grid((ncols + 127) / 128, (a.rows + 127) / 128, a.ksplit);
+            if (a.dgrad) hipLaunchKernelGGL((igemm_kernel<128, 128, true>), grid, dim3(256), 0, st, a);
+            else hipLaunchKernelGGL((igemm_kernel<128, 128, false>), grid, dim3(256), 0, st, a);
+        }
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        const size_t total = (size_t)a.rows * ncols;
+        KernelTimer kt(KID_IGEMM_REDUCE, st);
+        const dim3 rgrid((unsigned)((total + 1023) / 1024));
+        if ((total & 3) == 0) hipLaunchKernelGGL(igemm_reduce_kernel<true>, rgrid, dim3(256), 0, st, a, total);
+        else hipLaunchKernelGGL(igemm_reduce_kernel<false>, rgrid, dim3(256), 0, st, a, total);
+        return hipGetLastError();
+    }
+    KernelTimer kt(KID_IGEMM, st);
     if (a.rows <= 64) {
         dim3 grid((ncols + 127) / 128, 1);
         if (a.dgrad) hipLaunchKernelGGL((igemm_kernel<64, 128, true>), grid, dim3(256), 0, st, a);
         else hipLaunchKernelGGL((igemm_kernel<64, 128, false>), grid, dim3(256), 0, st, a);
-    } else if (gran >= 32 && (long long)((ncols + 255) / 256) * ((a.rows + 127) / 128) >= 256) {
-        // long reduction and enough wide tiles to cover the chip
+    } else if (igemm_wide(a)) {
         const long long t256 = (long long)((ncols + 255) / 256) * ((a.rows + 255) / 256);
         if (t256 >= 192)
             return a.dgrad ? launch_igemm_dma<true, 4, 8, 2>(a, ncols, st) : launch_igemm_dma<false, 4, 8, 2>(a, ncols, st);

@@ -69,7 +69,11 @@ struct IgemmArgs {
     int IH, IW, OH, OW, R, S;
     int stride_h, stride_w, pad_h, pad_w;
     int dgrad;                   // 0: ih = oh*stride + r - pad;  1: ih = (oh + pad - r)/stride
+    int32_t* partial;            // nullable scratch [ksplit][N][rows][OH*OW] of a split reduction
+    size_t partial_bytes;
+    int ksplit;                  // filled by launch_igemm(): blocks per output tile along the reduction
 };
+int igemm_ksplit(const IgemmArgs& a);   // split the launch will use when given enough scratch (1 = none)
 hipError_t launch_igemm(const IgemmArgs& a, hipStream_t st);
 // conv_band.hip: LDS-resident variant for small filter banks; false = shape not covered
 bool launch_band(const IgemmArgs& a, hipStream_t st, hipError_t* err);

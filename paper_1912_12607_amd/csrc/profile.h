@@ -15,6 +15,7 @@ enum KernelId : int {
     KID_DEVIATION_FINISH,
     KID_DSGC_SWEEP,
     KID_IGEMM,
+    KID_IGEMM_REDUCE,
     KID_BAND,
     KID_WGRAD,
     KID_WGRAD_REDUCE,

@@ -65,6 +65,11 @@ class LayerStep:
         self.ws_dy = torch.empty(max(256, B.int8t_quantize_workspace_bytes(L.y_shape, self.act_kind),
                                      B.int8t_workspace_bytes(B.OP_DSGC, None, n_y, n_cand)), dtype=u8, device=d)
         self.ws = torch.empty(max(256, B.int8t_workspace_bytes(B.OP_CONV_BWD_WEIGHT, self.desc)), dtype=u8, device=d)
+        # optional scratch of the forward / backward-data passes (split reduction of few-tile layers)
+        nf = B.int8t_workspace_bytes(B.OP_CONV_FWD, self.desc)
+        nb = B.int8t_workspace_bytes(B.OP_CONV_BWD_DATA, self.desc)
+        self.ws_fwd = torch.empty(nf, dtype=u8, device=d) if nf else None
+        self.ws_bwd_data = torch.empty(nb, dtype=u8, device=d) if nb else None
 
     def upload(self, x: np.ndarray, w: np.ndarray, dy: np.ndarray, ratios: np.ndarray):
         self.x.copy_(torch.from_numpy(np.ascontiguousarray(x)))
@@ -90,11 +95,11 @@ class LayerStep:
                          self.dyq, self.sdy, self.dev_final if self.requantize_deviation else None, self.ws_dy, stream)
 
     def fwd(self, stream=None):
-        B.int8t_conv_fwd(self.desc, self.xq, self.sx, self.wq, self.sw, self.y, self.y_acc, None, stream)
+        B.int8t_conv_fwd(self.desc, self.xq, self.sx, self.wq, self.sw, self.y, self.y_acc, self.ws_fwd, stream)
 
     def bwd_data(self, stream=None):
-        B.int8t_conv_bwd_data(self.desc, self.dyq, self.sdy, self.wq, self.sw, self.dx, self.dx_acc, None,
-                              stream)
+        B.int8t_conv_bwd_data(self.desc, self.dyq, self.sdy, self.wq, self.sw, self.dx, self.dx_acc,
+                              self.ws_bwd_data, stream)
 
     def bwd_weight(self, stream=None):
         B.int8t_conv_bwd_weight(self.desc, self.xq, self.sx, self.dyq, self.sdy, self.dw, self.dw_acc,

@@ -73,6 +73,11 @@ def test_workspace_sizes(lib):
     d = Desc(64, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1, 1)
     assert lib.int8t_workspace_bytes(4, C.byref(d), C.c_size_t(0), 0) >= 64 * 9 * 64 * 4
     assert lib.int8t_workspace_bytes(2, C.byref(d), C.c_size_t(0), 0) == 0
+    # forward / backward-data of a layer with few output tiles: optional scratch for a split reduction,
+    # a whole number of int32 result copies
+    few = Desc(64, 768, 17, 17, 192, 3, 3, 2, 2, 0, 0, 1)
+    nf = lib.int8t_workspace_bytes(2, C.byref(few), C.c_size_t(0), 0)
+    assert nf >= 2 * 64 * 192 * 8 * 8 * 4 and nf % (64 * 192 * 8 * 8 * 4) == 0
     bad = Desc(64, 64, 56, 56, 64, 3, 3, 1, 1, 1, 1, 2)     # grouped but not depthwise
     assert lib.int8t_workspace_bytes(4, C.byref(bad), C.c_size_t(0), 0) == 0
 

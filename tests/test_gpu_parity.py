@@ -202,6 +202,9 @@ CONV_SHAPES = [
     (3, 32, 9, 13, 40, 3, 3, (1, 1), (1, 1), 1),
     (2, 64, 6, 10, 24, 1, 1, (1, 1), (0, 0), 1),
     (2, 128, 5, 9, 64, 1, 1, (1, 1), (0, 0), 1),
+    # few output tiles and a long reduction: the reduction is split over several blocks
+    (2, 256, 9, 9, 96, 3, 3, (2, 2), (0, 0), 1),
+    (40, 520, 1, 1, 200, 1, 1, (1, 1), (0, 0), 1),
 ]
 
 
@@ -220,7 +223,9 @@ def test_conv_three_passes_bit_exact(shape):
     dyq = dev(dy.reshape(-1) if dwise else pack_act(dy))
     wq = dev(w.reshape(-1) if dwise else pack_wgt(w))
     sx, sw, sdy = (dev(np.array([v], np.float32)) for v in (0.0123, 3.3e-3, 7.7e-6))
-    ws = torch.empty(max(256, B.int8t_workspace_bytes(B.OP_CONV_BWD_WEIGHT, gd)), dtype=torch.uint8, device=DEV)
+    ws = torch.empty(max(256, *(B.int8t_workspace_bytes(op, gd) for op in
+                                (B.OP_CONV_FWD, B.OP_CONV_BWD_DATA, B.OP_CONV_BWD_WEIGHT))),
+                     dtype=torch.uint8, device=DEV)
 
     def run(fn, a, sa, b, sb, shape_out):
         out = torch.full(shape_out, float("nan"), dtype=torch.float32, device=DEV)
@@ -242,6 +247,33 @@ def test_conv_three_passes_bit_exact(shape):
         assert np.array_equal(acc, want32), name
         ref = oracle.dequant(want32, np.float32(s1), np.float32(s2))
         assert np.all(np.abs(out - ref) <= REL_TOL * np.abs(ref)), name
+
+
+def test_conv_without_optional_workspace():
+    # forward / backward-data take their scratch as a hint: without it the result is the same
+    shape = (2, 256, 9, 9, 96, 3, 3, (2, 2), (0, 0), 1)
+    N, C, H, W, K, R, S, st, pd, g = shape
+    gd = B.make_desc(N, C, H, W, K, R, S, st, pd, g)
+    assert B.int8t_workspace_bytes(B.OP_CONV_FWD, gd) > 0 and B.int8t_workspace_bytes(B.OP_CONV_BWD_DATA, gd) > 0
+    P, Q = (H - R) // 2 + 1, (W - S) // 2 + 1
+    r = np.random.RandomState(7)
+    x = r.randint(-127, 128, size=(N, C, H, W)).astype(np.int8)
+    w = r.randint(-127, 128, size=(K, C, R, S)).astype(np.int8)
+    dy = r.randint(-127, 128, size=(N, K, P, Q)).astype(np.int8)
+    xq, dyq, wq = dev(pack_act(x)), dev(pack_act(dy)), dev(pack_wgt(w))
+    one = dev(np.array([1.0], np.float32))
+    for fn, op, a, shape_out in ((B.int8t_conv_fwd, B.OP_CONV_FWD, xq, (N, K, P, Q)),
+                                 (B.int8t_conv_bwd_data, B.OP_CONV_BWD_DATA, dyq, (N, C, H, W))):
+        res = []
+        for nbytes in (B.int8t_workspace_bytes(op, gd), 0, 256):
+            ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV) if nbytes else None
+            out = torch.full(shape_out, float("nan"), dtype=torch.float32, device=DEV)
+            acc = torch.full(shape_out, -12345, dtype=torch.int32, device=DEV)
+            fn(gd, a, one, wq, one, out, acc, ws)
+            torch.cuda.synchronize()
+            res.append((out.cpu().numpy(), acc.cpu().numpy()))
+        for o, a_ in res[1:]:
+            assert np.array_equal(a_, res[0][1]) and np.array_equal(o, res[0][0])
 
 
 def test_bwd_weight_int32_wrap():
