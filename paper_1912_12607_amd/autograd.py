@@ -120,3 +120,33 @@ class Int8Conv2d(torch.nn.Module):
         if self.deviation is None:
             return 1.0
         return B.int8t_dclr_scale(float(self.deviation.item()), alpha, beta)
+
+
+class DclrSGD(torch.optim.SGD):
+    """SGD whose learning rate is scaled per INT8 layer by phi(d_c) of that layer's last backward
+    pass: Deviation Counteractive LR Scaling, Sec.3.5 Eq.7.  Parameters that belong to no
+    `Int8Conv2d` keep the base rate.  `step()` reads each layer's d_c back from the device."""
+
+    def __init__(self, model: torch.nn.Module, lr: float, alpha: float = 20.0, beta: float = 0.1, **sgd_kwargs):
+        self.alpha, self.beta = alpha, beta
+        self._layers = [m for m in model.modules() if isinstance(m, Int8Conv2d)]
+        int8_ids = {id(m.weight) for m in self._layers}
+        rest = [p for p in model.parameters() if id(p) not in int8_ids]
+        groups = [{"params": [m.weight], "base_lr": lr} for m in self._layers]
+        if rest:
+            groups.append({"params": rest, "base_lr": lr})
+        super().__init__(groups, lr=lr, **sgd_kwargs)
+
+    def set_lr(self, lr: float):
+        """New base rate (schedulers act on this, the DCLR factor is applied on top)."""
+        for g in self.param_groups:
+            g["base_lr"] = lr
+
+    @torch.no_grad()
+    def step(self, closure=None):
+        for g, m in zip(self.param_groups, self._layers):
+            g["lr"] = g["base_lr"] * m.dclr_scale(self.alpha, self.beta)
+        for g in self.param_groups[len(self._layers):]:
+            g["lr"] = g["base_lr"]
+        return super().step(closure)
+

@@ -103,3 +103,30 @@ def test_periodic_update_keeps_clip_between_searches():
         assert 0.0 <= m.deviation.item() <= 2.0
     assert clips[0] == clips[1] == clips[2]        # searched at pass 0, kept for passes 1 and 2
     assert clips[3] != clips[0]                    # searched again at pass 3 (the gradients have grown)
+
+
+def test_dclr_sgd_scales_each_layer_by_phi():
+    """Eq.7: the update of an INT8 layer's weight is lr * phi(d_c) * gradient with that layer's own d_c;
+    other parameters use the plain rate."""
+    from paper_1912_12607_amd.autograd import DclrSGD, Int8Conv2d
+    torch.manual_seed(1)
+    model = torch.nn.Sequential(Int8Conv2d(8, 16, 3, padding=1, seed=5), torch.nn.ReLU(),
+                                Int8Conv2d(16, 16, 3, padding=1, groups=16, seed=9),
+                                torch.nn.Flatten(), torch.nn.Linear(16 * 6 * 6, 4).cuda())
+    opt = DclrSGD(model, lr=0.5)
+    x = torch.randn(3, 8, 6, 6, device="cuda")
+    loss = model(x).square().sum()
+    loss.backward()
+    before = [p.detach().clone() for p in model.parameters()]
+    grads = [p.grad.detach().clone() for p in model.parameters()]
+    opt.step()
+    torch.cuda.synchronize()
+    layers = [m for m in model.modules() if isinstance(m, Int8Conv2d)]
+    phis = [oracle.dclr(m.deviation.item()) for m in layers]
+    assert all(0.1 <= p <= 1.0 for p in phis)
+    factors = {id(m.weight): p for m, p in zip(layers, phis)}
+    for p, b, g in zip(model.parameters(), before, grads):
+        lr = 0.5 * factors.get(id(p), 1.0)
+        err = (p.detach() - (b - lr * g)).abs().max().item()
+        assert err <= 4 * 2.0 ** -24 * (b.abs() + lr * g.abs()).max().item()      # one fp32 rounding each side
+
