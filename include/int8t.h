@@ -197,8 +197,11 @@ int8t_status int8t_conv_bwd_weight(const int8t_conv_desc *desc,
 
 /*
  * Kernel timing (measurement aid, not part of the method).  Between int8t_profile_start and
- * int8t_profile_stop the library records a pair of HIP events on the launch stream around
- * every launch of the selected kernel.
+ * int8t_profile_stop every launch of the selected kernel carries a pair of HIP events that take
+ * the dispatch's own start and end time stamps on the launch stream.  A timed dispatch costs a few
+ * microseconds of idle time before and after it; int8t_profile_start_sampled(kernel, every) times
+ * only every `every`-th launch (every >= 1) of each selected kernel, so that a measured loop is
+ * disturbed correspondingly less.
  *   kernel   host string: the kernel's name ("dsgc_sweep_kernel", "absmax_kernel",
  *            "quantize_act_kernel", "quantize_planar_kernel", "quantize_wgt_kernel",
  *            "deviation_finish_kernel", "igemm_kernel", "igemm_reduce_kernel", "band_kernel",
@@ -217,6 +220,7 @@ typedef struct int8t_kernel_time {
     double total_ms;
 } int8t_kernel_time;
 int8t_status int8t_profile_start(const char *kernel);
+int8t_status int8t_profile_start_sampled(const char *kernel, int every);
 int8t_status int8t_profile_stop(int8t_kernel_time *out, int capacity, int *count);
 
 /* Eq.7 on the host: max(exp(-alpha * d_c), beta).  The paper uses alpha = 20, beta = 0.1. */

@@ -22,7 +22,7 @@ MAX_CANDIDATES = 64
 EXPORTS = ["int8t_status_string", "int8t_code_bytes", "int8t_workspace_bytes",
            "int8t_quantize_workspace_bytes", "int8t_quantize", "int8t_dsgc_clip", "int8t_conv_fwd",
            "int8t_conv_bwd_data", "int8t_conv_bwd_weight", "int8t_dclr_scale",
-           "int8t_profile_start", "int8t_profile_stop"]
+           "int8t_profile_start", "int8t_profile_start_sampled", "int8t_profile_stop"]
 
 
 class KernelTime(C.Structure):
@@ -66,6 +66,8 @@ def _load():
     L.int8t_dclr_scale.argtypes = [C.c_double, C.c_double, C.c_double]
     L.int8t_profile_start.restype = i32
     L.int8t_profile_start.argtypes = [C.c_char_p]
+    L.int8t_profile_start_sampled.restype = i32
+    L.int8t_profile_start_sampled.argtypes = [C.c_char_p, C.c_int]
     L.int8t_profile_stop.restype = i32
     L.int8t_profile_stop.argtypes = [C.POINTER(KernelTime), i32, C.POINTER(i32)]
     return L
@@ -158,6 +160,10 @@ def int8t_dclr_scale(d_c: float, alpha: float = 20.0, beta: float = 0.1) -> floa
 
 def int8t_profile_start(kernel: str | None = None):
     _check(lib.int8t_profile_start(None if kernel is None else kernel.encode()))
+
+
+def int8t_profile_start_sampled(kernel: str | None, every: int):
+    _check(lib.int8t_profile_start_sampled(None if kernel is None else kernel.encode(), int(every)))
 
 
 def int8t_profile_stop() -> dict:

@@ -473,12 +473,10 @@ bool launch_band(const IgemmArgs& a, hipStream_t st, hipError_t* err) {
             size_t ldsr = (size_t)WH * WW * odd_pitch(Cg16) * 16;
             const size_t ldsw = (size_t)64 * odd_pitch(G) * 16;     // the weight matrix passes through LDS first
             if (ldsw > ldsr) ldsr = ldsw;
-            static bool attr_done_r[8] = {};
-            if (!attr_done_r[slot]) {
-                hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kr),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)BAND_LDS_MAX);
+            static std::atomic<unsigned long long> attr_done_r[8];
+            {
+                hipError_t e = raise_dynamic_lds(reinterpret_cast<const void*>(kr), (int)BAND_LDS_MAX, attr_done_r[slot]);
                 if (e != hipSuccess) { *err = e; return true; }
-                attr_done_r[slot] = true;
             }
             BandRegTab tab = {};
             {
@@ -495,7 +493,7 @@ bool launch_band(const IgemmArgs& a, hipStream_t st, hipError_t* err) {
             }
             {
                 KernelTimer kt(KID_BAND, st);
-                hipLaunchKernelGGL(kr, dim3(grid), dim3(256), ldsr, st, a, BP, nbands_h, nbands, tab);
+                launch_timed(kt, kr, dim3(grid), dim3(256), ldsr, st, a, BP, nbands_h, nbands, tab);
             }
             *err = hipGetLastError();
             return true;
@@ -509,16 +507,14 @@ bool launch_band(const IgemmArgs& a, hipStream_t st, hipError_t* err) {
     static const kern_t kerns[16] = {BK(false, 1, 1), BK(false, 1, 2), BK(false, 2, 1), BK(false, 2, 2),
                                      BK(true, 1, 1),  BK(true, 1, 2),  BK(true, 2, 1),  BK(true, 2, 2)};
 #undef BK
-    static bool attr_done[16] = {};
-    if (!attr_done[variant]) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kerns[variant]),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)BAND_LDS_MAX);
+    static std::atomic<unsigned long long> attr_done[16];
+    {
+        hipError_t e = raise_dynamic_lds(reinterpret_cast<const void*>(kerns[variant]), (int)BAND_LDS_MAX, attr_done[variant]);
         if (e != hipSuccess) { *err = e; return true; }
-        attr_done[variant] = true;
     }
     {
         KernelTimer kt(KID_BAND, st);
-        hipLaunchKernelGGL(kerns[variant], dim3(grid), dim3(256), lds, st, a, BP, nbands_h, nbands);
+        launch_timed(kt, kerns[variant], dim3(grid), dim3(256), lds, st, a, BP, nbands_h, nbands);
     }
     *err = hipGetLastError();
     return true;

@@ -342,18 +342,18 @@ hipError_t launch_dw_conv(const DwArgs& a, hipStream_t st) {
         if (lds <= 60 * 1024) {
             const bool two = a.S > 4;
             if (a.dgrad) {
-                if (two) hipLaunchKernelGGL((dw_conv_fast_kernel<true, 2>), dim3(a.N * a.C), dim3(256), lds, st, a, pitch);
-                else hipLaunchKernelGGL((dw_conv_fast_kernel<true, 1>), dim3(a.N * a.C), dim3(256), lds, st, a, pitch);
+                if (two) launch_timed(kt, (dw_conv_fast_kernel<true, 2>), dim3(a.N * a.C), dim3(256), lds, st, a, pitch);
+                else launch_timed(kt, (dw_conv_fast_kernel<true, 1>), dim3(a.N * a.C), dim3(256), lds, st, a, pitch);
             } else {
-                if (two) hipLaunchKernelGGL((dw_conv_fast_kernel<false, 2>), dim3(a.N * a.C), dim3(256), lds, st, a, pitch);
-                else hipLaunchKernelGGL((dw_conv_fast_kernel<false, 1>), dim3(a.N * a.C), dim3(256), lds, st, a, pitch);
+                if (two) launch_timed(kt, (dw_conv_fast_kernel<false, 2>), dim3(a.N * a.C), dim3(256), lds, st, a, pitch);
+                else launch_timed(kt, (dw_conv_fast_kernel<false, 1>), dim3(a.N * a.C), dim3(256), lds, st, a, pitch);
             }
             return hipGetLastError();
         }
     }
     const size_t lds = ((size_t)a.IH * a.IW + 15) & ~(size_t)15;
-    if (a.dgrad) hipLaunchKernelGGL((dw_conv_kernel<true>), dim3(a.N * a.C), dim3(256), lds, st, a);
-    else hipLaunchKernelGGL((dw_conv_kernel<false>), dim3(a.N * a.C), dim3(256), lds, st, a);
+    if (a.dgrad) launch_timed(kt, (dw_conv_kernel<true>), dim3(a.N * a.C), dim3(256), lds, st, a);
+    else launch_timed(kt, (dw_conv_kernel<false>), dim3(a.N * a.C), dim3(256), lds, st, a);
     return hipGetLastError();
 }
 
@@ -367,19 +367,19 @@ hipError_t launch_dw_wgrad(const DwArgs& a, hipStream_t st) {
             const size_t ldsf = (((size_t)(a.OH + a.R - 1) * pitch + 15) & ~(size_t)15) + (size_t)a.OH * gpitch;
             if (ldsf <= 60 * 1024) {
                 fast = true;
-                if (a.R == 3) hipLaunchKernelGGL((dw_wgrad_fast_kernel<3, 3>), dim3(a.C, a.chunks), dim3(256), ldsf, st, a, pitch, gpitch);
-                else hipLaunchKernelGGL((dw_wgrad_fast_kernel<5, 5>), dim3(a.C, a.chunks), dim3(256), ldsf, st, a, pitch, gpitch);
+                if (a.R == 3) launch_timed(kt, (dw_wgrad_fast_kernel<3, 3>), dim3(a.C, a.chunks), dim3(256), ldsf, st, a, pitch, gpitch);
+                else launch_timed(kt, (dw_wgrad_fast_kernel<5, 5>), dim3(a.C, a.chunks), dim3(256), ldsf, st, a, pitch, gpitch);
             }
         }
         if (!fast) {
             const size_t lds = (((size_t)a.IH * a.IW + 15) & ~(size_t)15) + (((size_t)a.OH * a.OW + 15) & ~(size_t)15);
-            hipLaunchKernelGGL(dw_wgrad_kernel, dim3(a.C, a.chunks), dim3(256), lds, st, a);
+            launch_timed(kt, dw_wgrad_kernel, dim3(a.C, a.chunks), dim3(256), lds, st, a);
         }
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int total = a.C * a.R * a.S;
-    { KernelTimer kt(KID_DW_WGRAD_REDUCE, st); hipLaunchKernelGGL(dw_wgrad_reduce_kernel, dim3((total + 255) / 256), dim3(256), 0, st, a); }
+    { KernelTimer kt(KID_DW_WGRAD_REDUCE, st); launch_timed(kt, dw_wgrad_reduce_kernel, dim3((total + 255) / 256), dim3(256), 0, st, a); }
     return hipGetLastError();
 }
 

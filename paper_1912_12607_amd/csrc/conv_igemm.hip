@@ -478,18 +478,16 @@ __global__ __launch_bounds__(128 * WM, WM == 2 ? 2 : 1) void igemm_dma_kernel(co
 }
 
 template <bool DGRAD, int WM, int KG, int NSTAGE>
-static hipError_t launch_igemm_dma(const IgemmArgs& a, int ncols, hipStream_t st) {
+static hipError_t launch_igemm_dma(const IgemmArgs& a, int ncols, hipStream_t st, const KernelTimer& kt) {
     const size_t lds = (size_t)NSTAGE * (64 * WM + IGD_BN) * KG * 16;
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(igemm_dma_kernel<DGRAD, WM, KG, NSTAGE>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    static std::atomic<unsigned long long> attr_done;
+    {
+        hipError_t e = raise_dynamic_lds(reinterpret_cast<const void*>(igemm_dma_kernel<DGRAD, WM, KG, NSTAGE>), (int)lds, attr_done);
         if (e != hipSuccess) return e;
-        attr_done = true;
     }
     const unsigned ctiles = (unsigned)((ncols + IGD_BN - 1) / IGD_BN), rtiles = (unsigned)((a.rows + 64 * WM - 1) / (64 * WM));
     dim3 grid(((ctiles + 7) / 8) * 8 * rtiles);
-    hipLaunchKernelGGL((igemm_dma_kernel<DGRAD, WM, KG, NSTAGE>), grid, dim3(128 * WM), lds, st, a);
+    launch_timed(kt, (igemm_dma_kernel<DGRAD, WM, KG, NSTAGE>), grid, dim3(128 * WM), lds, st, a);
     return hipGetLastError();
 }
 
@@ -528,32 +526,32 @@ hipError_t launch_igemm(const IgemmArgs& a_in, hipStream_t st) {
         {
             KernelTimer kt(KID_IGEMM, st);
             dim3 grid((ncols + 127) / 128, (a.rows + 127) / 128, a.ksplit);
-            if (a.dgrad) hipLaunchKernelGGL((igemm_kernel<128, 128, true>), grid, dim3(256), 0, st, a);
-            else hipLaunchKernelGGL((igemm_kernel<128, 128, false>), grid, dim3(256), 0, st, a);
+            if (a.dgrad) launch_timed(kt, (igemm_kernel<128, 128, true>), grid, dim3(256), 0, st, a);
+            else launch_timed(kt, (igemm_kernel<128, 128, false>), grid, dim3(256), 0, st, a);
         }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         const size_t total = (size_t)a.rows * ncols;
         KernelTimer kt(KID_IGEMM_REDUCE, st);
         const dim3 rgrid((unsigned)((total + 1023) / 1024));
-        if ((total & 3) == 0) hipLaunchKernelGGL(igemm_reduce_kernel<true>, rgrid, dim3(256), 0, st, a, total);
-        else hipLaunchKernelGGL(igemm_reduce_kernel<false>, rgrid, dim3(256), 0, st, a, total);
+        if ((total & 3) == 0) launch_timed(kt, igemm_reduce_kernel<true>, rgrid, dim3(256), 0, st, a, total);
+        else launch_timed(kt, igemm_reduce_kernel<false>, rgrid, dim3(256), 0, st, a, total);
         return hipGetLastError();
     }
     KernelTimer kt(KID_IGEMM, st);
     if (a.rows <= 64) {
         dim3 grid((ncols + 127) / 128, 1);
-        if (a.dgrad) hipLaunchKernelGGL((igemm_kernel<64, 128, true>), grid, dim3(256), 0, st, a);
-        else hipLaunchKernelGGL((igemm_kernel<64, 128, false>), grid, dim3(256), 0, st, a);
+        if (a.dgrad) launch_timed(kt, (igemm_kernel<64, 128, true>), grid, dim3(256), 0, st, a);
+        else launch_timed(kt, (igemm_kernel<64, 128, false>), grid, dim3(256), 0, st, a);
     } else if (igemm_wide(a)) {
         const long long t256 = (long long)((ncols + 255) / 256) * ((a.rows + 255) / 256);
         if (t256 >= 192)
-            return a.dgrad ? launch_igemm_dma<true, 4, 8, 2>(a, ncols, st) : launch_igemm_dma<false, 4, 8, 2>(a, ncols, st);
-        return a.dgrad ? launch_igemm_dma<true, 2, 4, 3>(a, ncols, st) : launch_igemm_dma<false, 2, 4, 3>(a, ncols, st);
+            return a.dgrad ? launch_igemm_dma<true, 4, 8, 2>(a, ncols, st, kt) : launch_igemm_dma<false, 4, 8, 2>(a, ncols, st, kt);
+        return a.dgrad ? launch_igemm_dma<true, 2, 4, 3>(a, ncols, st, kt) : launch_igemm_dma<false, 2, 4, 3>(a, ncols, st, kt);
     } else {
         dim3 grid((ncols + 127) / 128, (a.rows + 127) / 128);
-        if (a.dgrad) hipLaunchKernelGGL((igemm_kernel<128, 128, true>), grid, dim3(256), 0, st, a);
-        else hipLaunchKernelGGL((igemm_kernel<128, 128, false>), grid, dim3(256), 0, st, a);
+        if (a.dgrad) launch_timed(kt, (igemm_kernel<128, 128, true>), grid, dim3(256), 0, st, a);
+        else launch_timed(kt, (igemm_kernel<128, 128, false>), grid, dim3(256), 0, st, a);
     }
     return hipGetLastError();
 }

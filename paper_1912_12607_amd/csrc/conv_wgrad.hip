@@ -463,23 +463,20 @@ hipError_t launch_wgrad(const WgradArgs& a, hipStream_t st) {
     const unsigned out_tiles = (unsigned)(a.ktiles * a.ctiles * a.tapgroups);
     dim3 grid(wgrad_xcd_mapping(a.splits) ? out_tiles * 8u * (unsigned)((a.splits + 7) / 8) : out_tiles * (unsigned)a.splits);
     // the staged tiles may exceed the default 64 KB of dynamic LDS: raise the limit once per variant
-#define LAUNCH(TBv, CSv, SLOT)                                                                            \
+#define LAUNCH(TBv, CSv)                                                                                  \
     do {                                                                                                  \
-        static bool attr_done = false;                                                                    \
-        if (!attr_done) {                                                                                 \
-            hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_kernel<TBv, CSv>),    \
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, W2_LDS_BUDGET); \
-            if (ea != hipSuccess) return ea;                                                              \
-            attr_done = true;                                                                             \
-        }                                                                                                 \
-        hipLaunchKernelGGL((wgrad_kernel<TBv, CSv>), grid, dim3(256), a.lds_bytes, st, a);                \
+        static std::atomic<unsigned long long> attr_done;                                                 \
+        hipError_t ea = raise_dynamic_lds(reinterpret_cast<const void*>(wgrad_kernel<TBv, CSv>), W2_LDS_BUDGET, \
+                                          attr_done);                                                     \
+        if (ea != hipSuccess) return ea;                                                                  \
+        launch_timed(kt, (wgrad_kernel<TBv, CSv>), grid, dim3(256), a.lds_bytes, st, a);                \
     } while (0)
     {
         KernelTimer kt(KID_WGRAD, st);
-        if (a.TB == 1 && a.CS == 1) LAUNCH(1, 1, 0);
-        else if (a.TB == 1 && a.CS == 4) LAUNCH(1, 4, 1);
-        else if (a.TB == 3) LAUNCH(3, 1, 2);
-        else if (a.TB == 7) LAUNCH(7, 1, 3);
+        if (a.TB == 1 && a.CS == 1) LAUNCH(1, 1);
+        else if (a.TB == 1 && a.CS == 4) LAUNCH(1, 4);
+        else if (a.TB == 3) LAUNCH(3, 1);
+        else if (a.TB == 7) LAUNCH(7, 1);
         else return hipErrorInvalidValue;
     }
 #undef LAUNCH
@@ -488,7 +485,7 @@ hipError_t launch_wgrad(const WgradArgs& a, hipStream_t st) {
     const size_t total = (size_t)a.K * a.R * a.S * a.Cp;
     {
         KernelTimer kt(KID_WGRAD_REDUCE, st);
-        hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((total + 63) / 64)), dim3(256), 0, st, a);
+        launch_timed(kt, wgrad_reduce_kernel, dim3((unsigned)((total + 63) / 64)), dim3(256), 0, st, a);
     }
     return hipGetLastError();
 }

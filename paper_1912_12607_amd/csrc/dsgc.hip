@@ -342,11 +342,11 @@ hipError_t launch_dsgc(const float* g, size_t n, const float* ratios, int n_cand
     dim3 grid(blocks, nchunks);
     KernelTimer kt(KID_DSGC_SWEEP, st);
     if (stochastic)
-        hipLaunchKernelGGL((dsgc_sweep_kernel<true>), grid, dim3(256), 0, st, g, n, ratios, n_cand,
+        launch_timed(kt, (dsgc_sweep_kernel<true>), grid, dim3(256), 0, st, g, n, ratios, n_cand,
                            ws.absmax_part, nparts_absmax, slo, shi, ws.acc, ws.ticket, ws.partG, clip_out,
                            dev_out, dev_all_out);
     else
-        hipLaunchKernelGGL((dsgc_sweep_kernel<false>), grid, dim3(256), 0, st, g, n, ratios, n_cand,
+        launch_timed(kt, (dsgc_sweep_kernel<false>), grid, dim3(256), 0, st, g, n, ratios, n_cand,
                            ws.absmax_part, nparts_absmax, slo, shi, ws.acc, ws.ticket, ws.partG, clip_out,
                            dev_out, dev_all_out);
     return hipGetLastError();

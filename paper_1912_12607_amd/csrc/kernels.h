@@ -6,7 +6,23 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace int8t {
+
+// Raises a kernel's dynamic-LDS limit (the default is 64 KB) the first time it is launched on a
+// device; `done` is the call site's own bit mask of the devices already served.
+inline hipError_t raise_dynamic_lds(const void* fn, int bytes, std::atomic<unsigned long long>& done) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+    e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+    return e;
+}
+
 
 constexpr int kMaxPartials = 1024;   // per-block partial results of an absmax pass
 

@@ -1,9 +1,14 @@
-// Optional per-kernel timing inside the library: HIP events recorded on the launch stream right
-// before and after a kernel launch.  Off by default (then a KernelTimer costs one integer
-// compare); switched on and read out through int8t_profile_start / int8t_profile_stop.  Not
-// thread-safe: one thread drives the library while profiling is on.
+// Optional per-kernel timing inside the library.  A timed launch hands a pair of HIP events to the
+// dispatch itself (hipExtLaunchKernelGGL): they take the kernel's own start and end time stamps,
+// so nothing is put into the stream between kernels and the timing does not disturb the step it
+// measures.  Off by default (then a KernelTimer costs one integer compare and launches are plain);
+// switched on and read out through int8t_profile_start / int8t_profile_stop.  Not thread-safe: one
+// thread drives the library while profiling is on.
 #pragma once
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
+
+#include <cstdint>
 
 namespace int8t {
 
@@ -37,6 +42,10 @@ class KernelTimer {
     }
     KernelTimer(const KernelTimer&) = delete;
     KernelTimer& operator=(const KernelTimer&) = delete;
+    bool active() const { return slot_ >= 0; }
+    hipEvent_t start_event() const;   // valid while active()
+    hipEvent_t stop_event() const;
+    void mark_launched() const;
 
    private:
     void begin(int kid);
@@ -44,5 +53,20 @@ class KernelTimer {
     int slot_;
     hipStream_t st_;
 };
+
+// Launch `kernel` inside the scope of `kt`: timed when the timer is active, a plain launch otherwise.
+// The arguments are converted to the kernel's parameter types first.
+template <typename... KArgs, typename... Args>
+inline void launch_timed(const KernelTimer& kt, void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds,
+                         hipStream_t st, Args&&... args) {
+    static_assert(sizeof...(KArgs) == sizeof...(Args), "argument count must match the kernel's");
+    if (kt.active()) {
+        hipExtLaunchKernelGGL(kernel, grid, block, (std::uint32_t)lds, st, kt.start_event(), kt.stop_event(), 0,
+                              static_cast<KArgs>(args)...);
+        kt.mark_launched();
+    } else {
+        hipLaunchKernelGGL(kernel, grid, block, lds, st, static_cast<KArgs>(args)...);
+    }
+}
 
 }  // namespace int8t

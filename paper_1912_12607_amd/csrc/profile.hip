@@ -9,12 +9,14 @@
 namespace int8t {
 
 int g_profile_select = -2;
+int g_profile_every = 1;          // time every g_profile_every-th launch of a selected kernel
+int g_profile_seen[KID_COUNT] = {0};
 
 namespace {
 struct Rec {
     int kid;
     hipEvent_t a, b;
-    bool closed;
+    bool closed;     // a launch carried the events
 };
 std::vector<Rec> g_recs;
 
@@ -34,6 +36,7 @@ void drop_all() {
 }  // namespace
 
 void KernelTimer::begin(int kid) {
+    if (g_profile_seen[kid]++ % g_profile_every != 0) return;
     Rec r;
     r.kid = kid;
     r.closed = false;
@@ -42,26 +45,26 @@ void KernelTimer::begin(int kid) {
         (void)hipEventDestroy(r.a);
         return;
     }
-    if (hipEventRecord(r.a, st_) != hipSuccess) {
-        (void)hipEventDestroy(r.a);
-        (void)hipEventDestroy(r.b);
-        return;
-    }
     g_recs.push_back(r);
     slot_ = (int)g_recs.size() - 1;
 }
 
-void KernelTimer::end() {
-    Rec& r = g_recs[(size_t)slot_];
-    r.closed = hipEventRecord(r.b, st_) == hipSuccess;
-}
+void KernelTimer::end() {}
+
+hipEvent_t KernelTimer::start_event() const { return g_recs[(size_t)slot_].a; }
+hipEvent_t KernelTimer::stop_event() const { return g_recs[(size_t)slot_].b; }
+void KernelTimer::mark_launched() const { g_recs[(size_t)slot_].closed = true; }
 
 }  // namespace int8t
 
 using namespace int8t;
 
-extern "C" int8t_status int8t_profile_start(const char* kernel) {
+extern "C" int8t_status int8t_profile_start_sampled(const char* kernel, int every) {
     drop_all();
+    g_profile_select = -2;
+    if (every < 1) return INT8T_ERR_ARG;
+    g_profile_every = every;
+    for (int k = 0; k < KID_COUNT; ++k) g_profile_seen[k] = 0;
     if (kernel == nullptr || kernel[0] == '\0') {
         g_profile_select = -1;
         return INT8T_OK;
@@ -72,9 +75,10 @@ extern "C" int8t_status int8t_profile_start(const char* kernel) {
             return INT8T_OK;
         }
     }
-    g_profile_select = -2;
     return INT8T_ERR_ARG;
 }
+
+extern "C" int8t_status int8t_profile_start(const char* kernel) { return int8t_profile_start_sampled(kernel, 1); }
 
 extern "C" int8t_status int8t_profile_stop(int8t_kernel_time* out, int capacity, int* count) {
     g_profile_select = -2;

@@ -70,8 +70,8 @@ hipError_t launch_absmax(const float* x, size_t n, float* part, int* nparts, hip
     int blocks = (int)(want < 1 ? 1 : (want > (size_t)kMaxPartials ? (size_t)kMaxPartials : want));
     *nparts = blocks;
     KernelTimer kt(KID_ABSMAX, st);
-    if (sumsq) hipLaunchKernelGGL(absmax_kernel<true>, dim3(blocks), dim3(256), 0, st, x, n, part, sumsq, zero, nzero);
-    else hipLaunchKernelGGL(absmax_kernel<false>, dim3(blocks), dim3(256), 0, st, x, n, part, sumsq, zero, 0);
+    if (sumsq) launch_timed(kt, absmax_kernel<true>, dim3(blocks), dim3(256), 0, st, x, n, part, sumsq, zero, nzero);
+    else launch_timed(kt, absmax_kernel<false>, dim3(blocks), dim3(256), 0, st, x, n, part, sumsq, zero, 0);
     return hipGetLastError();
 }
 
@@ -251,10 +251,10 @@ hipError_t launch_quantize_act(const QuantArgs& a, hipStream_t st) {
 #define LAUNCH(ST, DV)                                                                                      \
     do {                                                                                                    \
         if ((HW & 3) == 0)                                                                                  \
-            hipLaunchKernelGGL((quantize_act_kernel<ST, DV, true>), grid, dim3(256), 0, st, a.x, C, Cp, HW, \
+            launch_timed(kt, (quantize_act_kernel<ST, DV, true>), grid, dim3(256), 0, st, a.x, C, Cp, HW, \
                                a.clip, a.absmax_part, a.nparts, slo, shi, a.q, a.scale, a.devpart);         \
         else                                                                                                \
-            hipLaunchKernelGGL((quantize_act_kernel<ST, DV, false>), grid, dim3(256), 0, st, a.x, C, Cp, HW, \
+            launch_timed(kt, (quantize_act_kernel<ST, DV, false>), grid, dim3(256), 0, st, a.x, C, Cp, HW, \
                                a.clip, a.absmax_part, a.nparts, slo, shi, a.q, a.scale, a.devpart);         \
     } while (0)
     if (a.stochastic) {
@@ -334,7 +334,7 @@ hipError_t launch_quantize_planar(const QuantArgs& a, hipStream_t st) {
     const uint32_t slo = (uint32_t)a.seed, shi = seed_hi_term(a.seed);
     KernelTimer kt(KID_QUANTIZE_PLANAR, st);
 #define LAUNCH(ST, DV)                                                                              \
-    hipLaunchKernelGGL((quantize_planar_kernel<ST, DV>), dim3(blocks), dim3(256), 0, st, a.x, n,    \
+    launch_timed(kt, (quantize_planar_kernel<ST, DV>), dim3(blocks), dim3(256), 0, st, a.x, n,    \
                        a.clip, a.absmax_part, a.nparts, slo, shi, a.q, a.scale, a.devpart)
     if (a.stochastic) {
         if (a.devpart) LAUNCH(true, true); else LAUNCH(true, false);
@@ -475,7 +475,7 @@ hipError_t launch_quantize_wgt(const QuantArgs& a, hipStream_t st) {
     const uint32_t slo = (uint32_t)a.seed, shi = seed_hi_term(a.seed);
     KernelTimer kt(KID_QUANTIZE_WGT, st);
 #define LAUNCH(ST, DV)                                                                              \
-    hipLaunchKernelGGL((quantize_wgt_kernel<ST, DV>), grid, dim3(256), 0, st, a.x, K, Cg, R, \
+    launch_timed(kt, (quantize_wgt_kernel<ST, DV>), grid, dim3(256), 0, st, a.x, K, Cg, R, \
                        S, Cp, Kp, off2, a.clip, a.absmax_part, a.nparts, slo, shi, a.q, a.scale,    \
                        a.devpart)
     if (a.stochastic) {
@@ -526,7 +526,7 @@ __global__ __launch_bounds__(256) void deviation_finish_kernel(const DevPartial*
 
 hipError_t launch_deviation_finish(const DevPartial* part, int nparts, double* dev_out, hipStream_t st) {
     KernelTimer kt(KID_DEVIATION_FINISH, st);
-    hipLaunchKernelGGL(deviation_finish_kernel, dim3(1), dim3(256), 0, st, part, nparts, dev_out);
+    launch_timed(kt, deviation_finish_kernel, dim3(1), dim3(256), 0, st, part, nparts, dev_out);
     return hipGetLastError();
 }
 

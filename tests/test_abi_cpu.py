@@ -137,3 +137,6 @@ def test_profile_entry_points_without_launches(lib):
     assert lib.int8t_profile_start(None) == 0
     assert lib.int8t_profile_stop(None, 0, C.byref(n)) == 0 and n.value == 0
     assert lib.int8t_profile_stop(None, 4, C.byref(n)) == 3          # capacity without a buffer
+    assert lib.int8t_profile_start_sampled(b"band_kernel", 0) == 3   # every >= 1
+    assert lib.int8t_profile_start_sampled(b"igemm_reduce_kernel", 5) == 0
+    assert lib.int8t_profile_stop(buf, 4, C.byref(n)) == 0 and n.value == 0
