@@ -44,10 +44,13 @@ def algorithmic(L, n_cand):
     conv2 = dict(bytes=(n_x + n_w + 4 * n_y) + (n_y + n_w + 4 * n_x), ops=4 * macs)   # forward + backward-data
     wg = dict(bytes=n_x + n_y + 4 * n_w, ops=2 * macs)
     return {
-        "absmax_kernel": dict(bytes=4 * (n_x + n_w + n_y), ops=0),               # a, W, g_z: one read each
-        "quantize_act_kernel": dict(bytes=5 * (n_x + n_y), ops=0),                # fp32 read + code write, a and g_z
-        "quantize_planar_kernel": dict(bytes=5 * (n_x + n_y), ops=0),
-        "quantize_wgt_kernel": dict(bytes=6 * n_w, ops=0),                        # fp32 read + two code copies
+        # the step quantizes a and W in one batched call (one absmax launch, one quantize launch) and g_z on its own
+        "absmax_batch_kernel": dict(bytes=4 * (n_x + n_w), ops=0),                # a, W: one read each
+        "quantize_batch_kernel": dict(bytes=5 * n_x + 6 * n_w, ops=0),            # fp32 read + code write (two copies of W)
+        "absmax_kernel": dict(bytes=4 * n_y, ops=0),                              # g_z: one read
+        "quantize_act_kernel": dict(bytes=5 * n_y, ops=0),                        # fp32 read + code write of g_z
+        "quantize_planar_kernel": dict(bytes=5 * n_y, ops=0),
+        "quantize_wgt_kernel": dict(bytes=6 * n_w, ops=0),
         "deviation_finish_kernel": dict(bytes=0, ops=0),
         # one read of g_z.  Vector-ALU work of the sweep: 2.75 operations per element and candidate (round-down
         # fused multiply-add, convert, 0.75 byte gather) + 30 per element and 32-candidate chunk (draw, fixed

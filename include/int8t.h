@@ -140,6 +140,30 @@ int8t_status int8t_quantize(const float *x_dev, const int dims[4], int8t_kind ki
                             void *ws_dev, size_t ws_bytes, void *stream);
 
 /*
+ * Eq.1 for several tensors at once (round to nearest only, no deviation output): the result of
+ * each item is exactly what int8t_quantize(..., INT8T_ROUND_NEAREST_EVEN, ...) writes for it, but
+ * all absmax passes share one launch and all quantize passes another.  Meant for the activations and
+ * the weights of a layer, or the weights of many layers: a small tensor no longer costs two kernel
+ * launches of its own.
+ *   items    host array of `count` (1 .. INT8T_MAX_BATCH) items, read before the call returns;
+ *            fields as the arguments of the same names of int8t_quantize
+ *   ws_dev   int8t_quantize_batch_workspace_bytes() bytes, 16-byte aligned; may be NULL when every
+ *            item brings its clip value
+ */
+#define INT8T_MAX_BATCH 8
+typedef struct int8t_quantize_item {
+    const float *x_dev;
+    int dims[4];
+    int8t_kind kind;
+    const float *clip_dev;
+    int8_t *q_dev;
+    float *scale_dev;
+} int8t_quantize_item;
+size_t int8t_quantize_batch_workspace_bytes(int count, const int8t_quantize_item *items);
+int8t_status int8t_quantize_batch(int count, const int8t_quantize_item *items,
+                                  void *ws_dev, size_t ws_bytes, void *stream);
+
+/*
  * Clip search of Sec.3.4.  Candidates c_j = fl32(max|g| * ratios[j]), j < n_cand
  * (1 <= n_cand <= INT8T_MAX_CANDIDATES).  For each, the tensor is quantized exactly
  * as int8t_quantize(mode, seed) would, and d_j = 1 - cos(g, q*s) (Eq.6) is evaluated;
@@ -203,7 +227,7 @@ int8t_status int8t_conv_bwd_weight(const int8t_conv_desc *desc,
  * only every `every`-th launch (every >= 1) of each selected kernel, so that a measured loop is
  * disturbed correspondingly less.
  *   kernel   host string: the kernel's name ("dsgc_sweep_kernel", "absmax_kernel",
- *            "quantize_act_kernel", "quantize_planar_kernel", "quantize_wgt_kernel",
+ *            "absmax_batch_kernel", "quantize_batch_kernel", "quantize_act_kernel", "quantize_planar_kernel", "quantize_wgt_kernel",
  *            "deviation_finish_kernel", "igemm_kernel", "igemm_reduce_kernel", "band_kernel",
  *            "wgrad_kernel", "wgrad_reduce_kernel", "dw_conv_kernel", "dw_wgrad_kernel",
  *            "dw_wgrad_reduce_kernel"); NULL or "" selects every kernel.

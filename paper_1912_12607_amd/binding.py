@@ -18,15 +18,22 @@ ROUND_NEAREST_EVEN, ROUND_STOCHASTIC = 0, 1
 ACT, WGT, ACT_PLANAR, WGT_PLANAR = 0, 1, 2, 3
 OP_QUANTIZE, OP_DSGC, OP_CONV_FWD, OP_CONV_BWD_DATA, OP_CONV_BWD_WEIGHT = range(5)
 MAX_CANDIDATES = 64
+MAX_BATCH = 8
 
 EXPORTS = ["int8t_status_string", "int8t_code_bytes", "int8t_workspace_bytes",
-           "int8t_quantize_workspace_bytes", "int8t_quantize", "int8t_dsgc_clip", "int8t_conv_fwd",
+           "int8t_quantize_workspace_bytes", "int8t_quantize", "int8t_quantize_batch_workspace_bytes",
+           "int8t_quantize_batch", "int8t_dsgc_clip", "int8t_conv_fwd",
            "int8t_conv_bwd_data", "int8t_conv_bwd_weight", "int8t_dclr_scale",
            "int8t_profile_start", "int8t_profile_start_sampled", "int8t_profile_stop"]
 
 
 class KernelTime(C.Structure):
     _fields_ = [("name", C.c_char_p), ("launches", C.c_int), ("total_ms", C.c_double)]
+
+
+class QuantizeItem(C.Structure):
+    _fields_ = [("x_dev", C.c_void_p), ("dims", C.c_int * 4), ("kind", C.c_int), ("clip_dev", C.c_void_p),
+                ("q_dev", C.c_void_p), ("scale_dev", C.c_void_p)]
 
 
 class ConvDesc(C.Structure):
@@ -56,6 +63,10 @@ def _load():
     L.int8t_quantize_workspace_bytes.argtypes = [dims, i32]
     L.int8t_quantize.restype = i32
     L.int8t_quantize.argtypes = [vp, dims, i32, vp, i32, u64, vp, vp, vp, vp, sz, vp]
+    L.int8t_quantize_batch_workspace_bytes.restype = sz
+    L.int8t_quantize_batch_workspace_bytes.argtypes = [i32, C.POINTER(QuantizeItem)]
+    L.int8t_quantize_batch.restype = i32
+    L.int8t_quantize_batch.argtypes = [i32, C.POINTER(QuantizeItem), vp, sz, vp]
     L.int8t_dsgc_clip.restype = i32
     L.int8t_dsgc_clip.argtypes = [vp, sz, vp, i32, i32, u64, vp, vp, vp, vp, sz, vp]
     for name in ("int8t_conv_fwd", "int8t_conv_bwd_data", "int8t_conv_bwd_weight"):
@@ -131,6 +142,24 @@ def int8t_quantize_workspace_bytes(dims, kind: int) -> int:
 def int8t_quantize(x, dims, kind, clip, mode, seed, q, scale, deviation=None, ws=None, stream=None):
     _check(lib.int8t_quantize(_ptr(x), _dims(dims), kind, _ptr(clip), mode, seed, _ptr(q), _ptr(scale),
                               _ptr(deviation), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def _items(items):
+    """[(x, dims, kind, clip or None, q, scale), ...] -> ctypes array; the tensors must stay alive until the call returns."""
+    arr = (QuantizeItem * len(items))()
+    for a, (x, dims, kind, clip, q, scale) in zip(arr, items):
+        a.x_dev, a.kind, a.clip_dev, a.q_dev, a.scale_dev = _ptr(x), kind, _ptr(clip), _ptr(q), _ptr(scale)
+        for j in range(4):
+            a.dims[j] = int(dims[j])
+    return arr
+
+
+def int8t_quantize_batch_workspace_bytes(items) -> int:
+    return int(lib.int8t_quantize_batch_workspace_bytes(len(items), _items(items)))
+
+
+def int8t_quantize_batch(items, ws=None, stream=None):
+    _check(lib.int8t_quantize_batch(len(items), _items(items), _ptr(ws), _nbytes(ws), _stream(stream)))
 
 
 def int8t_dsgc_clip(g, n, ratios, n_cand, mode, seed, clip, deviation, deviation_all=None, ws=None,

@@ -209,6 +209,74 @@ int8t_status int8t_quantize(const float* x_dev, const int dims[4], int8t_kind ki
     return INT8T_OK;
 }
 
+size_t int8t_quantize_batch_workspace_bytes(int count, const int8t_quantize_item* items) {
+    if (count < 1 || count > INT8T_MAX_BATCH || !items) return 0;
+    return (size_t)count * align256(kMaxPartials * sizeof(float));
+}
+
+int8t_status int8t_quantize_batch(int count, const int8t_quantize_item* items, void* ws_dev, size_t ws_bytes,
+                                  void* stream) {
+    if (!items) return INT8T_ERR_NULL;
+    if (count < 1 || count > INT8T_MAX_BATCH) return INT8T_ERR_ARG;
+    AbsmaxBatch ab{};
+    QuantBatch qb{};
+    qb.count = count;
+    long long ablocks = 0, qblocks = 0;
+    bool any_absmax = false;
+    for (int i = 0; i < count; ++i) {
+        const int8t_quantize_item& it = items[i];
+        if (!it.x_dev || !it.q_dev || !it.scale_dev) return INT8T_ERR_NULL;
+        size_t n;
+        if (!dims_ok(it.dims, &n)) return INT8T_ERR_SHAPE;
+        if (it.kind != INT8T_ACT && it.kind != INT8T_WGT && it.kind != INT8T_ACT_PLANAR && it.kind != INT8T_WGT_PLANAR)
+            return INT8T_ERR_ARG;
+        if (!aligned16(it.x_dev) || !aligned16(it.q_dev) || !aligned4(it.scale_dev) || !aligned4(it.clip_dev))
+            return INT8T_ERR_ARG;
+        if (it.kind == INT8T_ACT && (size_t)it.dims[0] * pad16(it.dims[1]) * it.dims[2] * it.dims[3] > kMaxElems)
+            return INT8T_ERR_SHAPE;
+        if (!it.clip_dev) any_absmax = true;
+    }
+    if (any_absmax) {
+        if (!ws_dev) return INT8T_ERR_NULL;
+        if (ws_bytes < int8t_quantize_batch_workspace_bytes(count, items)) return INT8T_ERR_WORKSPACE;
+        if (!aligned16(ws_dev)) return INT8T_ERR_ARG;
+    }
+    // Block ranges are dealt smallest tensor first: the dispatcher hands out blocks in order, so the
+    // few blocks of a small tensor run beside the first blocks of a large one instead of after its last.
+    int order[INT8T_MAX_BATCH];
+    size_t sizes[INT8T_MAX_BATCH];
+    for (int i = 0; i < count; ++i) {
+        order[i] = i;
+        (void)dims_ok(items[i].dims, &sizes[i]);
+    }
+    for (int i = 1; i < count; ++i)
+        for (int j = i; j > 0 && sizes[order[j]] < sizes[order[j - 1]]; --j) { const int t = order[j]; order[j] = order[j - 1]; order[j - 1] = t; }
+    for (int oi = 0; oi < count; ++oi) {
+        const int i = order[oi];
+        const int8t_quantize_item& it = items[i];
+        const size_t n = sizes[i];
+        float* part = any_absmax ? (float*)((char*)ws_dev + (size_t)i * align256(kMaxPartials * sizeof(float))) : nullptr;
+        const int nb = it.clip_dev ? 0 : absmax_blocks(n);
+        if (nb) {
+            AbsmaxBatchItem& a = ab.it[ab.count++];
+            a.x = it.x_dev; a.n = n; a.part = part; a.block0 = (int)ablocks; a.nblocks = nb;
+            ablocks += nb;
+        }
+        QuantBatchItem& q = qb.it[oi];
+        q.x = it.x_dev; q.d0 = it.dims[0]; q.d1 = it.dims[1]; q.d2 = it.dims[2]; q.d3 = it.dims[3];
+        q.clip = it.clip_dev; q.absmax_part = part; q.nparts = nb; q.q = it.q_dev; q.scale = it.scale_dev;
+        q.kind = it.kind == INT8T_ACT ? 0 : it.kind == INT8T_WGT ? 1 : 2;
+        quant_grid(q.kind, it.dims, &q.gx, &q.gy, &q.gz);
+        q.block0 = (int)qblocks;
+        qblocks += (long long)q.gx * q.gy * q.gz;
+        if (qblocks > 0x7FFFFFFFll) return INT8T_ERR_SHAPE;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    if (ab.count && launch_absmax_batch(ab, (int)ablocks, st) != hipSuccess) return INT8T_ERR_RUNTIME;
+    if (launch_quantize_batch(qb, (int)qblocks, st) != hipSuccess) return INT8T_ERR_RUNTIME;
+    return INT8T_OK;
+}
+
 int8t_status int8t_dsgc_clip(const float* g_dev, size_t n, const float* ratios_dev, int n_cand,
                              int8t_round mode, uint64_t seed, float* clip_dev, double* deviation_dev,
                              double* deviation_all_dev, void* ws_dev, size_t ws_bytes, void* stream) {

@@ -52,6 +52,37 @@ struct QuantArgs {
     float* scale;
     DevPartial* devpart;         // nullptr: no deviation
 };
+// several tensors per launch (round-to-nearest, no deviation output)
+constexpr int kMaxBatch = 8;
+struct AbsmaxBatchItem {
+    const float* x;
+    size_t n;
+    float* part;                 // this tensor's partials
+    int block0, nblocks;         // its block range inside the launch (nblocks = 0: clip supplied)
+};
+struct AbsmaxBatch {
+    int count;
+    AbsmaxBatchItem it[kMaxBatch];
+};
+struct QuantBatchItem {
+    const float* x;
+    int d0, d1, d2, d3;
+    const float* clip;
+    const float* absmax_part;
+    int nparts;
+    int8_t* q;
+    float* scale;
+    int kind;                    // 0 activations, 1 weights, 2 planar
+    int block0, gx, gy, gz;      // its block range and virtual grid inside the launch
+};
+struct QuantBatch {
+    int count;
+    QuantBatchItem it[kMaxBatch];
+};
+int absmax_blocks(size_t n);
+void quant_grid(int kind, const int d[4], int* gx, int* gy, int* gz);
+hipError_t launch_absmax_batch(const AbsmaxBatch& b, int total_blocks, hipStream_t st);
+hipError_t launch_quantize_batch(const QuantBatch& b, int total_blocks, hipStream_t st);
 int quant_blocks_act(int N, int Cp, int HW);
 int quant_blocks_planar(size_t n);
 int quant_blocks_wgt(int K, int Cg, int R, int S);

@@ -14,9 +14,11 @@ namespace int8t {
 
 enum KernelId : int {
     KID_ABSMAX = 0,
+    KID_ABSMAX_BATCH,
     KID_QUANTIZE_ACT,
     KID_QUANTIZE_PLANAR,
     KID_QUANTIZE_WGT,
+    KID_QUANTIZE_BATCH,
     KID_DEVIATION_FINISH,
     KID_DSGC_SWEEP,
     KID_IGEMM,

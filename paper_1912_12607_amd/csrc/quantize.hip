@@ -16,14 +16,21 @@ namespace int8t {
 // block, summed in a fixed order, and clears the clip search's accumulators (the sweep that
 // follows adds into them).
 // ---------------------------------------------------------------------------------------------
+// Position of a block inside the (virtual) grid of one tensor's pass: the kernels below are
+// written against it so that the batched launches can run several tensors' grids side by side.
+struct VBlock {
+    int x, y, z;       // block coordinates
+    int gx, gy, gz;    // grid extents
+};
+
 template <bool SUMSQ>
-__global__ __launch_bounds__(256) void absmax_kernel(const float* __restrict__ x, size_t n,
-                                                     float* __restrict__ part, double* __restrict__ sumsq,
-                                                     unsigned long long* __restrict__ zero, int nzero) {
+__device__ __forceinline__ void absmax_body(const float* __restrict__ x, size_t n, float* __restrict__ part,
+                                            double* __restrict__ sumsq, unsigned long long* __restrict__ zero,
+                                            int nzero, const int bx, const int gx) {
     __shared__ float lds4[4];
     __shared__ double ldsd[4];
     if (SUMSQ) {
-        for (int z = blockIdx.x * 256 + threadIdx.x; z < nzero; z += gridDim.x * 256) zero[z] = 0ull;
+        for (int z = bx * 256 + threadIdx.x; z < nzero; z += gx * 256) zero[z] = 0ull;
     }
     const size_t n4 = n >> 2;
     const float4* __restrict__ x4 = reinterpret_cast<const float4*>(x);
@@ -38,8 +45,8 @@ __global__ __launch_bounds__(256) void absmax_kernel(const float* __restrict__ x
             q[3] = fma((double)a.w, (double)a.w, q[3]);
         }
     };
-    const size_t stride = (size_t)gridDim.x * 256;
-    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t stride = (size_t)gx * 256;
+    size_t i = (size_t)bx * 256 + threadIdx.x;
     // four independent 16-byte loads in flight per thread
     for (; i + 3 * stride < n4; i += 4 * stride) {
         float4 a = x4[i], b = x4[i + stride], c = x4[i + 2 * stride], d = x4[i + 3 * stride];
@@ -49,25 +56,50 @@ __global__ __launch_bounds__(256) void absmax_kernel(const float* __restrict__ x
         take(d);
     }
     for (; i < n4; i += stride) take(x4[i]);
-    if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
+    if (bx == 0 && threadIdx.x < (n & 3)) {
         const float v = x[(n4 << 2) + threadIdx.x];
         m = fmaxf(m, fabsf(v));
         if (SUMSQ) q[0] = fma((double)v, (double)v, q[0]);
     }
     m = block_max_256(m, lds4);
-    if (threadIdx.x == 0) part[blockIdx.x] = m;
+    if (threadIdx.x == 0) part[bx] = m;
     if (SUMSQ) {
         const double t = wave_sum((q[0] + q[1]) + (q[2] + q[3]));
         if ((threadIdx.x & 63) == 0) ldsd[threadIdx.x >> 6] = t;
         __syncthreads();
-        if (threadIdx.x == 0) sumsq[blockIdx.x] = (ldsd[0] + ldsd[1]) + (ldsd[2] + ldsd[3]);
+        if (threadIdx.x == 0) sumsq[bx] = (ldsd[0] + ldsd[1]) + (ldsd[2] + ldsd[3]);
     }
+}
+
+template <bool SUMSQ>
+__global__ __launch_bounds__(256) void absmax_kernel(const float* __restrict__ x, size_t n,
+                                                     float* __restrict__ part, double* __restrict__ sumsq,
+                                                     unsigned long long* __restrict__ zero, int nzero) {
+    absmax_body<SUMSQ>(x, n, part, sumsq, zero, nzero, (int)blockIdx.x, (int)gridDim.x);
+}
+
+// several tensors in one launch: block b serves the tensor whose block range holds it
+__global__ __launch_bounds__(256) void absmax_batch_kernel(const AbsmaxBatch b) {
+    int i = 0;
+    while (i + 1 < b.count && (int)blockIdx.x >= b.it[i].block0 + b.it[i].nblocks) ++i;
+    const AbsmaxBatchItem& t = b.it[i];
+    absmax_body<false>(t.x, t.n, t.part, nullptr, nullptr, 0, (int)blockIdx.x - t.block0, t.nblocks);
+}
+
+int absmax_blocks(size_t n) {
+    size_t want = (n / 4 + 256 * 8 - 1) / (256 * 8);   // >= 8 float4 per thread before adding blocks
+    return (int)(want < 1 ? 1 : (want > (size_t)kMaxPartials ? (size_t)kMaxPartials : want));
+}
+
+hipError_t launch_absmax_batch(const AbsmaxBatch& b, int total_blocks, hipStream_t st) {
+    KernelTimer kt(KID_ABSMAX_BATCH, st);
+    launch_timed(kt, absmax_batch_kernel, dim3(total_blocks), dim3(256), 0, st, b);
+    return hipGetLastError();
 }
 
 hipError_t launch_absmax(const float* x, size_t n, float* part, int* nparts, hipStream_t st, double* sumsq,
                          unsigned long long* zero, int nzero) {
-    size_t want = (n / 4 + 256 * 8 - 1) / (256 * 8);   // >= 8 float4 per thread before adding blocks
-    int blocks = (int)(want < 1 ? 1 : (want > (size_t)kMaxPartials ? (size_t)kMaxPartials : want));
+    const int blocks = absmax_blocks(n);
     *nparts = blocks;
     KernelTimer kt(KID_ABSMAX, st);
     if (sumsq) launch_timed(kt, absmax_kernel<true>, dim3(blocks), dim3(256), 0, st, x, n, part, sumsq, zero, nzero);
@@ -132,16 +164,15 @@ __device__ __forceinline__ void qa_transpose4x4(const uint32_t d[4], uint32_t o[
 // 16-byte load; it then owns a 4-channel x 4-pixel block, transposes its codes in registers and
 // writes one dword (4 channels) per pixel to the LDS tile.  Otherwise one pixel per lane, 4-byte loads.
 template <bool STOCH, bool DEV, bool VEC>
-__global__ __launch_bounds__(256) void quantize_act_kernel(
+__device__ __forceinline__ void quantize_act_body(
     const float* __restrict__ x, int C, int Cp, int HW, const float* __restrict__ clip,
     const float* __restrict__ absmax_part, int nparts, uint32_t seed_lo, uint32_t seed_hi_mul,
-    int8_t* __restrict__ q, float* __restrict__ scale_out, DevPartial* __restrict__ devpart) {
-    __shared__ float lds4[4];
-    __shared__ uint32_t tile[QA_PIX][QA_CH / 4 + 1];
-
-    const int n = blockIdx.z;
-    const int c0 = blockIdx.y * QA_CH;
-    const int p0 = blockIdx.x * QA_PIX;
+    int8_t* __restrict__ q, float* __restrict__ scale_out, DevPartial* __restrict__ devpart, const VBlock vb,
+    float* lds4, uint32_t (*tile)[QA_CH / 4 + 1]) {
+    // lds4: 4 floats, tile: [QA_PIX][QA_CH / 4 + 1] dwords of LDS supplied by the kernel
+    const int n = vb.z;
+    const int c0 = vb.y * QA_CH;
+    const int p0 = vb.x * QA_PIX;
     const int lane = threadIdx.x & 63;
     const int wv = threadIdx.x >> 6;
     const int p = p0 + lane;
@@ -176,7 +207,7 @@ __global__ __launch_bounds__(256) void quantize_act_kernel(
         inv = __fmul_rn(inv, kTwo24);        // the scaled value carries 24 fraction bits
         fp32_round_down_mode(inv, sc);
     }
-    if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) *scale_out = sc;
+    if (vb.x == 0 && vb.y == 0 && vb.z == 0 && threadIdx.x == 0) *scale_out = sc;
 
     double A = 0.0, G = 0.0;
     unsigned long long B = 0;
@@ -234,9 +265,21 @@ __global__ __launch_bounds__(256) void quantize_act_kernel(
         *reinterpret_cast<uint4*>(q + ((size_t)n * HW + p0 + pl) * Cp + c0 + chunk * 16) = o;
     }
     if (DEV) {
-        const int b = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
+        const int b = (vb.z * vb.gy + vb.y) * vb.gx + vb.x;
         block_store_devpartial(A, G, B, devpart + b);
     }
+}
+
+template <bool STOCH, bool DEV, bool VEC>
+__global__ __launch_bounds__(256) void quantize_act_kernel(
+    const float* __restrict__ x, int C, int Cp, int HW, const float* __restrict__ clip,
+    const float* __restrict__ absmax_part, int nparts, uint32_t seed_lo, uint32_t seed_hi_mul,
+    int8_t* __restrict__ q, float* __restrict__ scale_out, DevPartial* __restrict__ devpart) {
+    __shared__ float lds4[4];
+    __shared__ uint32_t tile[QA_PIX][QA_CH / 4 + 1];
+    const VBlock vb = {(int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z, (int)gridDim.x, (int)gridDim.y, (int)gridDim.z};
+    quantize_act_body<STOCH, DEV, VEC>(x, C, Cp, HW, clip, absmax_part, nparts, seed_lo, seed_hi_mul, q, scale_out,
+                                       devpart, vb, lds4, tile);
 }
 
 int quant_blocks_act(int N, int Cp, int HW) {
@@ -272,11 +315,11 @@ hipError_t launch_quantize_act(const QuantArgs& a, hipStream_t st) {
 constexpr int QP_BLOCKS_MAX = 4096;
 
 template <bool STOCH, bool DEV>
-__global__ __launch_bounds__(256) void quantize_planar_kernel(
+__device__ __forceinline__ void quantize_planar_body(
     const float* __restrict__ x, size_t n, const float* __restrict__ clip,
     const float* __restrict__ absmax_part, int nparts, uint32_t seed_lo, uint32_t seed_hi_mul,
-    int8_t* __restrict__ q, float* __restrict__ scale_out, DevPartial* __restrict__ devpart) {
-    __shared__ float lds4[4];
+    int8_t* __restrict__ q, float* __restrict__ scale_out, DevPartial* __restrict__ devpart, const int bx, const int gx,
+    float* lds4) {
     const float cval = resolve_clip(clip, absmax_part, nparts, lds4);
     float inv = inv_scale_of(cval);
     float sc = scale_of(cval);
@@ -284,15 +327,15 @@ __global__ __launch_bounds__(256) void quantize_planar_kernel(
         inv = __fmul_rn(inv, kTwo24);        // the scaled value carries 24 fraction bits
         fp32_round_down_mode(inv, sc);
     }
-    if (blockIdx.x == 0 && threadIdx.x == 0) *scale_out = sc;
+    if (bx == 0 && threadIdx.x == 0) *scale_out = sc;
 
     double A = 0.0, G = 0.0;
     unsigned long long B = 0;
     const size_t n4 = n >> 2;
     const float4* __restrict__ x4 = reinterpret_cast<const float4*>(x);
     uint32_t* __restrict__ q4 = reinterpret_cast<uint32_t*>(q);
-    const size_t stride = (size_t)gridDim.x * 256;
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
+    const size_t stride = (size_t)gx * 256;
+    for (size_t i = (size_t)bx * 256 + threadIdx.x; i < n4; i += stride) {
         const float4 f = x4[i];
         const float vv[4] = {f.x, f.y, f.z, f.w};
         int code[4];
@@ -308,7 +351,7 @@ __global__ __launch_bounds__(256) void quantize_planar_kernel(
         }
         q4[i] = pack4(code[0], code[1], code[2], code[3]);
     }
-    if (blockIdx.x == 0 && threadIdx.x < (n & 3)) {
+    if (bx == 0 && threadIdx.x < (n & 3)) {
         const size_t i = (n4 << 2) + threadIdx.x;
         const float g32 = x[i];
         const int code = quantize_one<STOCH>(g32, inv, seed_lo, seed_hi_mul, (uint32_t)i);
@@ -320,7 +363,17 @@ __global__ __launch_bounds__(256) void quantize_planar_kernel(
             B += (unsigned)(code * code);
         }
     }
-    if (DEV) block_store_devpartial(A, G, B, devpart + blockIdx.x);
+    if (DEV) block_store_devpartial(A, G, B, devpart + bx);
+}
+
+template <bool STOCH, bool DEV>
+__global__ __launch_bounds__(256) void quantize_planar_kernel(
+    const float* __restrict__ x, size_t n, const float* __restrict__ clip,
+    const float* __restrict__ absmax_part, int nparts, uint32_t seed_lo, uint32_t seed_hi_mul,
+    int8_t* __restrict__ q, float* __restrict__ scale_out, DevPartial* __restrict__ devpart) {
+    __shared__ float lds4[4];
+    quantize_planar_body<STOCH, DEV>(x, n, clip, absmax_part, nparts, seed_lo, seed_hi_mul, q, scale_out, devpart,
+                                     (int)blockIdx.x, (int)gridDim.x, lds4);
 }
 
 int quant_blocks_planar(size_t n) {
@@ -354,15 +407,15 @@ hipError_t launch_quantize_planar(const QuantArgs& a, hipStream_t st) {
 // ---------------------------------------------------------------------------------------------
 constexpr int QW_T = 16;
 constexpr int QW_TAPS = 64;
+static int quant_wgt_zsplit(int K, int Cg, int R, int S);
 
 template <bool STOCH, bool DEV>
-__global__ __launch_bounds__(256) void quantize_wgt_kernel(
+__device__ __forceinline__ void quantize_wgt_body(
     const float* __restrict__ w, int K, int Cg, int R, int S, int Cp, int Kp, size_t off2,
     const float* __restrict__ clip, const float* __restrict__ absmax_part, int nparts,
     uint32_t seed_lo, uint32_t seed_hi_mul, int8_t* __restrict__ q, float* __restrict__ scale_out,
-    DevPartial* __restrict__ devpart) {
-    __shared__ float lds4[4];
-    __shared__ __attribute__((aligned(16))) int8_t tile[QW_T * QW_T * QW_TAPS];   // [filter][channel][tap]
+    DevPartial* __restrict__ devpart, const VBlock vb, float* lds4, int8_t* tile) {
+    // lds4: 4 floats, tile: QW_T * QW_T * QW_TAPS bytes of LDS, [filter][channel][tap], supplied by the kernel
     const float cval = resolve_clip(clip, absmax_part, nparts, lds4);
     float inv = inv_scale_of(cval);
     float sc = scale_of(cval);
@@ -370,15 +423,15 @@ __global__ __launch_bounds__(256) void quantize_wgt_kernel(
         inv = __fmul_rn(inv, kTwo24);        // the scaled value carries 24 fraction bits
         fp32_round_down_mode(inv, sc);
     }
-    if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) *scale_out = sc;
+    if (vb.x == 0 && vb.y == 0 && vb.z == 0 && threadIdx.x == 0) *scale_out = sc;
 
     const int RS = R * S;
-    const int k0 = blockIdx.y * QW_T, c0 = blockIdx.x * QW_T;
+    const int k0 = vb.y * QW_T, c0 = vb.x * QW_T;
     double A = 0.0, G = 0.0;
     unsigned long long B = 0;
     // small tensors spread their taps over blockIdx.z to have enough blocks
-    const int tpb = (RS + (int)gridDim.z - 1) / (int)gridDim.z;
-    const int rs_begin = blockIdx.z * tpb, rs_end = (rs_begin + tpb < RS) ? rs_begin + tpb : RS;
+    const int tpb = (RS + vb.gz - 1) / vb.gz;
+    const int rs_begin = vb.z * tpb, rs_end = (rs_begin + tpb < RS) ? rs_begin + tpb : RS;
     for (int rs0 = rs_begin; rs0 < rs_end; rs0 += QW_TAPS) {
         const int nrs = (rs_end - rs0 < QW_TAPS) ? (rs_end - rs0) : QW_TAPS;
         const int per_k = QW_T * nrs;
@@ -453,7 +506,75 @@ __global__ __launch_bounds__(256) void quantize_wgt_kernel(
             }
         }
     }
-    if (DEV) block_store_devpartial(A, G, B, devpart + (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x);
+    if (DEV) block_store_devpartial(A, G, B, devpart + (vb.z * vb.gy + vb.y) * vb.gx + vb.x);
+}
+
+template <bool STOCH, bool DEV>
+__global__ __launch_bounds__(256) void quantize_wgt_kernel(
+    const float* __restrict__ w, int K, int Cg, int R, int S, int Cp, int Kp, size_t off2,
+    const float* __restrict__ clip, const float* __restrict__ absmax_part, int nparts,
+    uint32_t seed_lo, uint32_t seed_hi_mul, int8_t* __restrict__ q, float* __restrict__ scale_out,
+    DevPartial* __restrict__ devpart) {
+    __shared__ float lds4[4];
+    __shared__ __attribute__((aligned(16))) int8_t tile[QW_T * QW_T * QW_TAPS];
+    const VBlock vb = {(int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z, (int)gridDim.x, (int)gridDim.y, (int)gridDim.z};
+    quantize_wgt_body<STOCH, DEV>(w, K, Cg, R, S, Cp, Kp, off2, clip, absmax_part, nparts, seed_lo, seed_hi_mul, q,
+                                  scale_out, devpart, vb, lds4, tile);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Batched round-to-nearest quantization (Eq.1) of several tensors in one launch: the activations
+// and the weights of a layer, or the weights of many layers.  Small tensors otherwise pay a whole
+// kernel launch each (a few microseconds of an idle GPU for a few thousand elements).  Block b
+// serves the tensor whose block range holds it and runs that tensor's ordinary pass.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void quantize_batch_kernel(const QuantBatch b) {
+    // one LDS area for whichever pass this block runs
+    __shared__ float lds4[4];
+    __shared__ __attribute__((aligned(16))) int8_t smem[QW_T * QW_T * QW_TAPS];
+    static_assert(sizeof(smem) >= sizeof(uint32_t) * QA_PIX * (QA_CH / 4 + 1), "the weight tile is the larger one");
+    uint32_t (*const atile)[QA_CH / 4 + 1] = reinterpret_cast<uint32_t (*)[QA_CH / 4 + 1]>(smem);
+    int i = 0;
+    while (i + 1 < b.count && (int)blockIdx.x >= b.it[i].block0 + b.it[i].gx * b.it[i].gy * b.it[i].gz) ++i;
+    const QuantBatchItem& t = b.it[i];
+    const int local = (int)blockIdx.x - t.block0;
+    const int gxy = t.gx * t.gy;
+    const int z = local / gxy, rem = local - z * gxy;
+    const int y = rem / t.gx;
+    const VBlock vb = {rem - y * t.gx, y, z, t.gx, t.gy, t.gz};
+    if (t.kind == 0) {          // activations, N,C,H,W -> N,H,W,Cp
+        const int HW = t.d2 * t.d3, Cp = (t.d1 + 15) & ~15;
+        if ((HW & 3) == 0)
+            quantize_act_body<false, false, true>(t.x, t.d1, Cp, HW, t.clip, t.absmax_part, t.nparts, 0u, 0u, t.q, t.scale, nullptr, vb, lds4, atile);
+        else
+            quantize_act_body<false, false, false>(t.x, t.d1, Cp, HW, t.clip, t.absmax_part, t.nparts, 0u, 0u, t.q, t.scale, nullptr, vb, lds4, atile);
+    } else if (t.kind == 1) {   // weights, two views
+        const int Cp = (t.d1 + 15) & ~15, Kp = (t.d0 + 15) & ~15;
+        const size_t off2 = (((size_t)t.d0 * t.d2 * t.d3 * Cp) + 255) & ~(size_t)255;
+        quantize_wgt_body<false, false>(t.x, t.d0, t.d1, t.d2, t.d3, Cp, Kp, off2, t.clip, t.absmax_part, t.nparts, 0u, 0u,
+                                        t.q, t.scale, nullptr, vb, lds4, smem);
+    } else {                    // planar
+        quantize_planar_body<false, false>(t.x, (size_t)t.d0 * t.d1 * t.d2 * t.d3, t.clip, t.absmax_part, t.nparts, 0u, 0u,
+                                           t.q, t.scale, nullptr, vb.x, vb.gx, lds4);
+    }
+}
+
+// grid of one tensor's quantize pass, by layout (0 activations, 1 weights, else planar)
+void quant_grid(int kind, const int d[4], int* gx, int* gy, int* gz) {
+    if (kind == 0) {
+        const int HW = d[2] * d[3], Cp = (d[1] + 15) & ~15;
+        *gx = (HW + QA_PIX - 1) / QA_PIX; *gy = (Cp + QA_CH - 1) / QA_CH; *gz = d[0];
+    } else if (kind == 1) {
+        *gx = (d[1] + QW_T - 1) / QW_T; *gy = (d[0] + QW_T - 1) / QW_T; *gz = quant_wgt_zsplit(d[0], d[1], d[2], d[3]);
+    } else {
+        *gx = quant_blocks_planar((size_t)d[0] * d[1] * d[2] * d[3]); *gy = 1; *gz = 1;
+    }
+}
+
+hipError_t launch_quantize_batch(const QuantBatch& b, int total_blocks, hipStream_t st) {
+    KernelTimer kt(KID_QUANTIZE_BATCH, st);
+    launch_timed(kt, quantize_batch_kernel, dim3(total_blocks), dim3(256), 0, st, b);
+    return hipGetLastError();
 }
 
 // blocks along the taps: 1 for tensors with many 16 x 16 tiles, up to R*S for small ones

@@ -1,7 +1,7 @@
 """One conv-layer training step of the INT8 path as a sequence of C-ABI calls.
 
 Pure plumbing: allocates device buffers with torch, uploads the fp32 tensors once, and chains
-    quantize(a) -> quantize(W) -> dsgc_clip(g_z) -> quantize(g_z; clip, stochastic, d_c)
+    quantize_batch(a, W) -> dsgc_clip(g_z) -> quantize(g_z; clip, stochastic, d_c)
     -> conv_fwd -> conv_bwd_data -> conv_bwd_weight
 on one stream with no host synchronisation in between (scales, clip and deviation stay in device
 memory).  Used by the tests, the smoke check and the benchmark.
@@ -68,6 +68,9 @@ class LayerStep:
         # optional scratch of the forward / backward-data passes (split reduction of few-tile layers)
         nf = B.int8t_workspace_bytes(B.OP_CONV_FWD, self.desc)
         nb = B.int8t_workspace_bytes(B.OP_CONV_BWD_DATA, self.desc)
+        self.xw_items = [(self.x, L.x_shape, self.act_kind, None, self.xq, self.sx),
+                         (self.w, L.w_shape, self.wgt_kind, None, self.wq, self.sw)]
+        self.ws_xw = torch.empty(B.int8t_quantize_batch_workspace_bytes(self.xw_items), dtype=u8, device=d)
         self.ws_fwd = torch.empty(nf, dtype=u8, device=d) if nf else None
         self.ws_bwd_data = torch.empty(nb, dtype=u8, device=d) if nb else None
 
@@ -85,6 +88,10 @@ class LayerStep:
     def quantize_w(self, stream=None):
         B.int8t_quantize(self.w, self.L.w_shape, self.wgt_kind, None, B.ROUND_NEAREST_EVEN, 0,
                          self.wq, self.sw, None, self.ws_w, stream)
+
+    def quantize_xw(self, stream=None):
+        """a and W in one batched call: same codes and scales as quantize_x() + quantize_w()."""
+        B.int8t_quantize_batch(self.xw_items, self.ws_xw, stream)
 
     def dsgc(self, seed: int, stream=None):
         B.int8t_dsgc_clip(self.dy, self.dy.numel(), self.ratios, self.n_cand, B.ROUND_STOCHASTIC, seed,
@@ -109,8 +116,7 @@ class LayerStep:
         """The whole hot path once.  search=False keeps the clip value of the last search (the
         paper's Periodic Update, Sec.3.4 / Table 2: the clip is refreshed every P iterations only);
         the caller decides the period."""
-        self.quantize_x(stream)
-        self.quantize_w(stream)
+        self.quantize_xw(stream)
         if search:
             self.dsgc(seed, stream)
         self.quantize_dy(seed, stream)

@@ -140,3 +140,35 @@ def test_profile_entry_points_without_launches(lib):
     assert lib.int8t_profile_start_sampled(b"band_kernel", 0) == 3   # every >= 1
     assert lib.int8t_profile_start_sampled(b"igemm_reduce_kernel", 5) == 0
     assert lib.int8t_profile_stop(buf, 4, C.byref(n)) == 0 and n.value == 0
+
+
+def test_quantize_batch_argument_errors(lib):
+    class Item(C.Structure):
+        _fields_ = [("x_dev", C.c_void_p), ("dims", C.c_int * 4), ("kind", C.c_int), ("clip_dev", C.c_void_p),
+                    ("q_dev", C.c_void_p), ("scale_dev", C.c_void_p)]
+    lib.int8t_quantize_batch_workspace_bytes.restype = C.c_size_t
+    lib.int8t_quantize_batch_workspace_bytes.argtypes = [C.c_int, C.POINTER(Item)]
+    f = lib.int8t_quantize_batch
+    f.restype = C.c_int
+    f.argtypes = [C.c_int, C.POINTER(Item), C.c_void_p, C.c_size_t, C.c_void_p]
+    items = (Item * 2)()
+    for it in items:
+        it.x_dev, it.q_dev, it.scale_dev, it.kind = 0x1000, 0x2000, 0x3000, 0
+        it.dims[:] = [1, 16, 4, 4]
+    assert lib.int8t_quantize_batch_workspace_bytes(2, items) == 2 * 4096
+    assert lib.int8t_quantize_batch_workspace_bytes(0, items) == 0
+    assert lib.int8t_quantize_batch_workspace_bytes(9, items) == 0
+    assert f(2, None, 0x4000, 1 << 20, None) == 1                  # INT8T_ERR_NULL
+    assert f(0, items, 0x4000, 1 << 20, None) == 3                 # INT8T_ERR_ARG: count
+    assert f(9, items, 0x4000, 1 << 20, None) == 3
+    assert f(2, items, None, 0, None) == 1                         # absmax needs the scratch
+    assert f(2, items, 0x4000, 4096, None) == 4                    # INT8T_ERR_WORKSPACE
+    items[1].kind = 9
+    assert f(2, items, 0x4000, 1 << 20, None) == 3
+    items[1].kind = 0
+    items[1].dims[2] = 0
+    assert f(2, items, 0x4000, 1 << 20, None) == 2                 # INT8T_ERR_SHAPE
+    items[1].dims[2] = 4
+    items[0].q_dev = 0x2004
+    assert f(2, items, 0x4000, 1 << 20, None) == 3                 # alignment
+

@@ -177,6 +177,46 @@ def test_dsgc_candidate_counts_and_degenerate():
     assert clip == np.float32(127 * 2.0 ** -12) and abs(d) < 1e-15
 
 
+def test_quantize_batch_equals_single_calls_and_oracle():
+    """One batched call = the per-tensor calls, bit for bit (codes, scales), for every layout, with and
+    without a supplied clip value."""
+    r = np.random.RandomState(11)
+    specs = [((3, 20, 6, 6), B.ACT, None),            # H*W a multiple of 4
+             ((2, 7, 5, 3), B.ACT, None),             # H*W = 15: one pixel per lane
+             ((40, 24, 3, 3), B.WGT, None),
+             ((5, 1, 3, 3), B.WGT_PLANAR, None),
+             ((2, 9, 7, 7), B.ACT_PLANAR, 0.75),
+             ((130, 70, 1, 1), B.WGT, 1.5)]
+    items, singles, host = [], [], []
+    for shape, kind, clip in specs:
+        x = (r.standard_normal(shape) * (1.0 + len(host))).astype(np.float32)
+        xd = dev(x)
+        cd = None if clip is None else dev(np.array([clip], np.float32))
+        nq = B.int8t_code_bytes(shape, kind)
+        qa, qb = (torch.full((nq,), 77, dtype=torch.int8, device=DEV) for _ in range(2))
+        sa, sb = (torch.full((1,), -1.0, dtype=torch.float32, device=DEV) for _ in range(2))
+        items.append((xd, shape, kind, cd, qa, sa))
+        singles.append((xd, shape, kind, cd, qb, sb))
+        host.append((x, clip))
+    ws = torch.empty(B.int8t_quantize_batch_workspace_bytes(items), dtype=torch.uint8, device=DEV)
+    B.int8t_quantize_batch(items, ws)
+    for xd, shape, kind, cd, qb, sb in singles:
+        w1 = torch.empty(max(256, B.int8t_quantize_workspace_bytes(shape, kind)), dtype=torch.uint8, device=DEV)
+        B.int8t_quantize(xd, shape, kind, cd, B.ROUND_NEAREST_EVEN, 0, qb, sb, None, w1)
+    torch.cuda.synchronize()
+    for (xd, shape, kind, cd, qa, sa), (_, _, _, _, qb, sb), (x, clip) in zip(items, singles, host):
+        assert torch.equal(qa, qb) and torch.equal(sa, sb), (shape, kind)
+        want_q, want_s = oracle.quantize(x, c=clip)
+        assert sa.item() == want_s
+        if kind == B.ACT:
+            assert np.array_equal(unpack_act(qa.cpu().numpy(), shape, False), want_q)
+        elif kind == B.WGT:
+            got, got2 = unpack_wgt(qa.cpu().numpy(), shape, False)
+            assert np.array_equal(got, want_q) and np.array_equal(got2, want_q)
+        else:
+            assert np.array_equal(qa.cpu().numpy().reshape(shape), want_q)
+
+
 # (N, C, H, W, K, R, S, stride, pad, groups)
 CONV_SHAPES = [
     (2, 16, 16, 16, 32, 3, 3, (1, 1), (1, 1), 1),
