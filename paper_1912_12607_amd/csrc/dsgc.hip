@@ -44,10 +44,17 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int DSGC_JC = 32;        // candidates per block: the 32 columns of one MFMA tile
 constexpr int DSGC_JPAD = 64;      // row pitch of the partial arrays (= INT8T_MAX_CANDIDATES)
-constexpr int DSGC_MAX_BLOCKS = 768;
+constexpr int DSGC_MAX_BLOCKS = 1024;   // four blocks per compute unit (LDS: 4 x 40 KB, registers: 4 waves per SIMD)
 constexpr int DSGC_GROUPS = 32;     // accumulator sets the blocks spread their atomics over
-constexpr int DSGC_PITCH = 272;    // bytes per LDS row: a wave's 256 elements + 16 (spreads the operand reads over the banks)
 constexpr int DSGC_ROWS = DSGC_JC + 6;   // 32 code rows, then the 6 digit rows
+// A wave's LDS tile holds 256 elements x DSGC_ROWS byte rows, stored by 16-element granule:
+// [granule 0..15][row][16 bytes], with the granule pitch padded to 39 rows.  An MFMA operand read
+// (32 lanes = 32 consecutive rows of one granule) is then 512 contiguous bytes, and the 16 granules
+// a store instruction touches (4 lanes each) start 156 banks apart, i.e. in 16 different groups of
+// 4 banks -- both free of bank conflicts, and 2.5 KB smaller per wave than padded rows, which is what
+// lets a fourth block fit a compute unit.
+constexpr int DSGC_GPITCH = (DSGC_ROWS + 1) * 16;   // 624 bytes
+constexpr int DSGC_TILE = 16 * DSGC_GPITCH;         // 9984 bytes per wave
 // int32 accumulators: |digit * code| <= 128 * 127 per element and lane sum; flushed well before 2^31
 constexpr int DSGC_FLUSH_ITERS = 256;    // 256 iterations x 256 elements x 16256 < 2^31
 
@@ -89,9 +96,11 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
     constexpr int JC = DSGC_JC;
     __shared__ float lds4[4];
     __shared__ float s_inv[JC];
-    __shared__ long long s_red[4][JC][3];
     __shared__ unsigned int s_last;
-    __shared__ __attribute__((aligned(16))) unsigned char s_tile[4][DSGC_ROWS * DSGC_PITCH];
+    __shared__ __attribute__((aligned(16))) unsigned char s_tile[4][DSGC_TILE];
+    // the block reductions after the sweep re-use the tiles' memory
+    long long (*const s_red)[JC][3] = reinterpret_cast<long long (*)[JC][3]>(&s_tile[0][0]);
+    static_assert(sizeof(long long) * 4 * JC * 3 <= sizeof(s_tile), "reduction scratch fits the tiles");
 
     const int j0 = blockIdx.y * JC;
     const int jn = (n_cand - j0 < JC) ? (n_cand - j0) : JC;
@@ -120,10 +129,11 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int l32 = lane & 31, kh = lane >> 5;
     unsigned char* __restrict__ const tile = s_tile[w];
-    uint32_t* __restrict__ const wr = reinterpret_cast<uint32_t*>(tile + 4 * lane);         // + row * PITCH
-    // MFMA operands of this lane: candidate l32's codes / digit row min(l32, 5), 16 elements from 16*kh
-    const unsigned char* __restrict__ const rd_code = tile + l32 * DSGC_PITCH + 16 * kh;
-    const unsigned char* __restrict__ const rd_dig = tile + (JC + (l32 < 5 ? l32 : 5)) * DSGC_PITCH + 16 * kh;
+    // this lane's four elements live in granule lane / 4, bytes 4 * (lane % 4) ..; + 16 * row
+    uint32_t* __restrict__ const wr = reinterpret_cast<uint32_t*>(tile + (lane >> 2) * DSGC_GPITCH + 4 * (lane & 3));
+    // MFMA operands of this lane: candidate l32's codes / digit row min(l32, 5), granule 2 * step + kh
+    const unsigned char* __restrict__ const rd_code = tile + kh * DSGC_GPITCH + l32 * 16;
+    const unsigned char* __restrict__ const rd_dig = tile + kh * DSGC_GPITCH + (JC + (l32 < 5 ? l32 : 5)) * 16;
 
     v16i accA, accB;      // [digit row][candidate] (rows 0..5 used) and [candidate][candidate] (diagonal used)
 #pragma unroll
@@ -176,8 +186,8 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
         digit_planes(L, pL);
 #pragma unroll
         for (int b = 0; b < 3; ++b) {
-            wr[(JC + b) * (DSGC_PITCH / 4)] = pH[b];
-            wr[(JC + 3 + b) * (DSGC_PITCH / 4)] = pL[b];
+            wr[(JC + b) * 4] = pH[b];
+            wr[(JC + 3 + b) * 4] = pL[b];
         }
 #pragma unroll
         for (int j = 0; j < JC; ++j) {
@@ -188,13 +198,13 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
                 rp = low_bytes(round_nearest_code(fabsf(x[0]), inv[j]), round_nearest_code(fabsf(x[1]), inv[j]),
                                round_nearest_code(fabsf(x[2]), inv[j]), round_nearest_code(fabsf(x[3]), inv[j]));
             }
-            wr[j * (DSGC_PITCH / 4)] = rp;
+            wr[j * 4] = rp;
         }
         __builtin_amdgcn_wave_barrier();   // keep the tile's stores ahead of its loads
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
-            const uint4 tc = *reinterpret_cast<const uint4*>(rd_code + 32 * s);
-            const uint4 td = *reinterpret_cast<const uint4*>(rd_dig + 32 * s);
+            const uint4 tc = *reinterpret_cast<const uint4*>(rd_code + 2 * DSGC_GPITCH * s);
+            const uint4 td = *reinterpret_cast<const uint4*>(rd_dig + 2 * DSGC_GPITCH * s);
             const v4i fc = v4i{(int)tc.x, (int)tc.y, (int)tc.z, (int)tc.w};
             const v4i fd = v4i{(int)td.x, (int)td.y, (int)td.z, (int)td.w};
             accA = __builtin_amdgcn_mfma_i32_32x32x32_i8(fd, fc, accA, 0, 0, 0);
@@ -237,6 +247,7 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
     }
 
     // block totals -> one of the accumulator sets
+    __syncthreads();   // every wave is done with its tile: the memory now serves the reductions
     if (lane < JC) {
         s_red[w][lane][0] = runH;
         s_red[w][lane][1] = runL;
@@ -268,9 +279,10 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
 
     // ---- last block: sum the sets, Eq.6 per candidate, smallest deviation (ties: smallest j, i.e.
     // the largest clip value for decreasing ratios).  Every addition is in a fixed order. ----------
-    __shared__ long long f_part[4][DSGC_JPAD][3];
-    __shared__ double f_g[4];
-    __shared__ double f_dev[DSGC_JPAD];
+    long long (*const f_part)[DSGC_JPAD][3] = reinterpret_cast<long long (*)[DSGC_JPAD][3]>(&s_tile[0][0]);
+    double* const f_g = reinterpret_cast<double*>(&s_tile[0][0] + sizeof(long long) * 4 * DSGC_JPAD * 3);
+    double* const f_dev = f_g + 4;
+    static_assert(sizeof(long long) * 4 * DSGC_JPAD * 3 + sizeof(double) * (4 + DSGC_JPAD) <= sizeof(s_tile), "fits the tiles");
     {
         const int j = threadIdx.x & 63, part = threadIdx.x >> 6;
         long long t[3] = {0, 0, 0};
@@ -334,7 +346,7 @@ hipError_t launch_dsgc(const float* g, size_t n, const float* ratios, int n_cand
                        uint64_t seed, const DsgcWs& ws, int nparts_absmax, float* clip_out,
                        double* dev_out, double* dev_all_out, hipStream_t st) {
     const int nchunks = (n_cand + DSGC_JC - 1) / DSGC_JC;
-    // about three blocks per compute unit in total; every candidate chunk walks the same x-grid
+    // about four blocks per compute unit in total; every candidate chunk walks the same x-grid
     int blocks = dsgc_blocks(n);
     const int cap = (DSGC_MAX_BLOCKS + nchunks - 1) / nchunks;
     if (blocks > cap) blocks = cap;
