@@ -19,6 +19,10 @@ HEADERS = ["device_common.h", "kernels.h", "profile.h", os.path.join("..", "..",
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-fno-fast-math", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]
+# Per-file additions.  dsgc.hip: keep the MFMA accumulators in ordinary vector registers (the kernel
+# has registers to spare); otherwise the compiler parks them in accumulation registers and copies
+# all of them back and forth on every trip of the inner loop.
+EXTRA_FLAGS = {"dsgc.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 
 
 def _stale(obj: str, deps) -> bool:
@@ -38,7 +42,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
         o = os.path.join(CSRC, src.replace(".hip", ".o"))
         objs.append(o)
         if force or _stale(o, [s] + hdrs):
-            cmd = [hipcc] + FLAGS + ["-c", s, "-o", o]
+            cmd = [hipcc] + FLAGS + EXTRA_FLAGS.get(src, []) + ["-c", s, "-o", o]
             if verbose:
                 print(" ".join(cmd), flush=True)
             procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)))

@@ -127,46 +127,53 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
         inv[j] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(s_inv[j])));
 
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int l32 = lane & 31, kh = lane >> 5;
+    const int l16 = lane & 15, kg = lane >> 4;
     unsigned char* __restrict__ const tile = s_tile[w];
     // this lane's four elements live in granule lane / 4, bytes 4 * (lane % 4) ..; + 16 * row
     uint32_t* __restrict__ const wr = reinterpret_cast<uint32_t*>(tile + (lane >> 2) * DSGC_GPITCH + 4 * (lane & 3));
-    // MFMA operands of this lane: candidate l32's codes / digit row min(l32, 5), granule 2 * step + kh
-    const unsigned char* __restrict__ const rd_code = tile + kh * DSGC_GPITCH + l32 * 16;
-    const unsigned char* __restrict__ const rd_dig = tile + kh * DSGC_GPITCH + (JC + (l32 < 5 ? l32 : 5)) * 16;
+    // MFMA operands of this lane (16 x 16 x 64 tiles: a lane supplies 16 reduction bytes of one row):
+    // codes of candidate l16 (+ 16 for the second candidate group) / digit row min(l16, 5), granule
+    // 4 * step + kg
+    const unsigned char* __restrict__ const rd_code = tile + kg * DSGC_GPITCH + l16 * 16;
+    const unsigned char* __restrict__ const rd_dig = tile + kg * DSGC_GPITCH + (JC + (l16 < 5 ? l16 : 5)) * 16;
 
-    v16i accA, accB;      // [digit row][candidate] (rows 0..5 used) and [candidate][candidate] (diagonal used)
+    // per candidate group h: [digit row][candidate] (rows 0..5 used) and [candidate][candidate] (diagonal
+    // used).  The 16-row tiles waste far fewer rows on the six digit rows than 32-row ones would.
+    v4i accA[2], accB[2];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) accA[v] = accB[v] = 0;
-    // lanes 0..31: candidate l32's totals so far (flushed part): sum H*m, sum L*m, sum m^2
-    long long runH = 0, runL = 0, runB = 0;
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) accA[h][v] = accB[h][v] = 0;
+    // lanes 0..15: totals so far (flushed part) of candidates l16 and 16 + l16: sum H*m, sum L*m, sum m^2
+    long long runH[2] = {0, 0}, runL[2] = {0, 0}, runB[2] = {0, 0};
 
-    // int32 tiles -> 64-bit per-candidate totals in lanes 0..31, accumulators cleared
+    // int32 tiles -> 64-bit per-candidate totals in lanes 0..15, accumulators cleared
     auto flush = [&]() {
-        // accA: lane (col, kh), register v holds row 8*(v/4) + 4*kh + (v%4): rows 0..3 (the H digits
-        // and L digit 0) sit in the lower half's registers 0..3, rows 4..5 (L digits 1, 2) in the
-        // upper half's registers 0..1
-        long long ph, pl;
-        if (kh == 0) {
-            ph = (long long)accA[0] + 256LL * accA[1] + 65536LL * accA[2];
-            pl = (long long)accA[3];
-        } else {
-            ph = 0;
-            pl = 256LL * accA[0] + 65536LL * accA[1];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            // accA[h]: lane (column l16, kg), register v holds digit row 4*kg + v: rows 0..3 (the H digits
+            // and L digit 0) sit in the lanes kg = 0, rows 4..5 (L digits 1, 2) in registers 0..1 of kg = 1
+            long long ph = 0, pl = 0;
+            if (kg == 0) {
+                ph = (long long)accA[h][0] + 256LL * accA[h][1] + 65536LL * accA[h][2];
+                pl = (long long)accA[h][3];
+            } else if (kg == 1) {
+                pl = 256LL * accA[h][0] + 65536LL * accA[h][1];
+            }
+            pl += __shfl_xor(pl, 16, kWave);
+            runH[h] += ph;       // meaningful in lanes 0..15 only
+            runL[h] += pl;
+            // accB[h]: the diagonal element of column l16 is row l16 = 4*kg + v
+            int diag = 0;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) diag = (v == (l16 & 3)) ? accB[h][v] : diag;
+            long long bd = ((l16 >> 2) == kg) ? (long long)diag : 0LL;
+            bd += __shfl_xor(bd, 16, kWave);
+            bd += __shfl_xor(bd, 32, kWave);
+            runB[h] += bd;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) accA[h][v] = accB[h][v] = 0;
         }
-        pl += __shfl_xor(pl, 32, kWave);
-        runH += ph;          // meaningful in the lower half only
-        runL += pl;
-        // accB: the diagonal element of column l32 is row l32 = 8*(v/4) + 4*kh' + (v%4)
-        const int vd = 4 * (l32 >> 3) + (l32 & 3);
-        int diag = 0;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) diag = (v == vd) ? accB[v] : diag;
-        long long bd = (((l32 >> 2) & 1) == kh) ? (long long)diag : 0LL;
-        bd += __shfl_xor(bd, 32, kWave);
-        runB += bd;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) accA[v] = accB[v] = 0;
     };
 
     // one wave iteration: 256 consecutive elements, four per lane
@@ -202,13 +209,16 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
         }
         __builtin_amdgcn_wave_barrier();   // keep the tile's stores ahead of its loads
 #pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            const uint4 tc = *reinterpret_cast<const uint4*>(rd_code + 2 * DSGC_GPITCH * s);
-            const uint4 td = *reinterpret_cast<const uint4*>(rd_dig + 2 * DSGC_GPITCH * s);
-            const v4i fc = v4i{(int)tc.x, (int)tc.y, (int)tc.z, (int)tc.w};
+        for (int s = 0; s < 4; ++s) {
+            const uint4 td = *reinterpret_cast<const uint4*>(rd_dig + 4 * DSGC_GPITCH * s);
             const v4i fd = v4i{(int)td.x, (int)td.y, (int)td.z, (int)td.w};
-            accA = __builtin_amdgcn_mfma_i32_32x32x32_i8(fd, fc, accA, 0, 0, 0);
-            accB = __builtin_amdgcn_mfma_i32_32x32x32_i8(fc, fc, accB, 0, 0, 0);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint4 tc = *reinterpret_cast<const uint4*>(rd_code + 4 * DSGC_GPITCH * s + 256 * h);
+                const v4i fc = v4i{(int)tc.x, (int)tc.y, (int)tc.z, (int)tc.w};
+                accA[h] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fd, fc, accA[h], 0, 0, 0);
+                accB[h] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fc, fc, accB[h], 0, 0, 0);
+            }
         }
         __builtin_amdgcn_wave_barrier();   // and the next iteration's stores behind these loads
     };
@@ -248,10 +258,13 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
 
     // block totals -> one of the accumulator sets
     __syncthreads();   // every wave is done with its tile: the memory now serves the reductions
-    if (lane < JC) {
-        s_red[w][lane][0] = runH;
-        s_red[w][lane][1] = runL;
-        s_red[w][lane][2] = runB;
+    if (lane < 16) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            s_red[w][16 * h + lane][0] = runH[h];
+            s_red[w][16 * h + lane][1] = runL[h];
+            s_red[w][16 * h + lane][2] = runB[h];
+        }
     }
     __syncthreads();
     if (threadIdx.x < 3 * JC) {
