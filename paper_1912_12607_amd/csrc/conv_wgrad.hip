@@ -133,8 +133,8 @@ __global__ __launch_bounds__(256, 2) void wgrad_kernel(const WgradArgs a) {
         const int pl = uu / a.BQ, ql = uu - pl * a.BQ;
         stab[u] = make_int2((uv ? u : units) * YP, (pl * a.stride_h * WW + ql * a.stride_w) * XP);
     }
-    const int2* __restrict__ const stab_h = stab + half;
-    const int a_ch = swz_ch(mt * 32 + l32);
+    // gradient operand of step s: tile pixel 2*s + half (the pixel `units` is the all-zero one)
+    const int a_ch = swz_ch(mt * 32 + l32) + half * YP;
     int x_ch[CS];                                   // this lane's channel positions inside the block's tile
 #pragma unroll
     for (int i = 0; i < CS; ++i) x_ch[i] = swz_ch((ch * CS + i) * 32 + l32);
@@ -146,6 +146,19 @@ __global__ __launch_bounds__(256, 2) void wgrad_kernel(const WgradArgs a) {
         for (int i = 0; i < CS; ++i)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[j][i][v] = 0;
+
+    // window pixel of this half-wave in every step: the same for all chunks, kept in registers so
+    // that the operand reads of a step depend on nothing that is read in that step
+    // (only the variants with few accumulators have the registers for this and for the operand
+    // prefetch below; the others look the position up in LDS step by step)
+    constexpr bool PF = TB * CS <= 3;
+    __syncthreads();
+    int wpix[PF ? W2_MAXSTEPS : 1];
+    if (PF) {
+#pragma unroll
+        for (int s = 0; s < W2_MAXSTEPS; ++s) wpix[s] = stab[2 * s + half].y;
+    }
+    const int2* __restrict__ const stab_h = stab + half;
 
     const int c_begin = (int)(((uint32_t)a.chunks * (uint32_t)zshare) / (uint32_t)a.splits);   // chunks * splits < 2^31 (host)
     const int c_end = (int)(((uint32_t)a.chunks * (uint32_t)(zshare + 1)) / (uint32_t)a.splits);
@@ -254,18 +267,34 @@ __global__ __launch_bounds__(256, 2) void wgrad_kernel(const WgradArgs a) {
         __syncthreads();
         if (chunk + 1 < c_end) issue(chunk + 1);   // in flight while this chunk's MFMAs run
 
+        // The operands of step s+1 are requested before the MFMAs of step s are issued (two register
+        // sets), so the LDS latency of a step hides behind the previous step's matrix work.
+        constexpr int NSET = PF ? 2 : 1;
+        uint4 ra[NSET], rb[NSET][TB][CS];
+        auto fetch = [&](int s, int set) {
+            ra[set] = dyT[a_ch + 2 * s * YP];
+            const int wp = PF ? wpix[PF ? s : 0] : stab_h[2 * s].y;
+#pragma unroll
+            for (int j = 0; j < TB; ++j)   // TB divides R*S: every tap of the group exists
+#pragma unroll
+                for (int i = 0; i < CS; ++i) rb[set][j][i] = xT[wp + tpix[j] + x_ch[i]];
+        };
+        if (PF) fetch(0, 0);
 #pragma unroll
         for (int s = 0; s < W2_MAXSTEPS; ++s) {
             if (s < nsteps) {
-                const int2 st = stab_h[2 * s];
-                const uint4 ta = dyT[st.x + a_ch];
+                if (PF) {
+                    if (s + 1 < W2_MAXSTEPS && s + 1 < nsteps) fetch(s + 1, (s + 1) & 1);
+                } else {
+                    fetch(s, 0);
+                }
+                const uint4 ta = ra[s & (NSET - 1)];
                 const v4i fa = v4i{(int)ta.x, (int)ta.y, (int)ta.z, (int)ta.w};
 #pragma unroll
-                for (int j = 0; j < TB; ++j) {   // TB divides R*S: every tap of the group exists
-                    const int pix = st.y + tpix[j];   // granule offset of the tap's window pixel
+                for (int j = 0; j < TB; ++j) {
 #pragma unroll
                     for (int i = 0; i < CS; ++i) {
-                        const uint4 tb = xT[pix + x_ch[i]];
+                        const uint4 tb = rb[s & (NSET - 1)][j][i];
                         const v4i fb = v4i{(int)tb.x, (int)tb.y, (int)tb.z, (int)tb.w};
                         acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa, fb, acc[j][i], 0, 0, 0);
                     }
@@ -440,7 +469,7 @@ void wgrad_plan_uncached(WgradArgs* a) {
     // (blocks resident on the chip: registers allow two per compute unit for the narrow tiles, one
     // for the wide ones); a block pays a prologue plus its chunks; every split adds one write and
     // one read of the int32 partial tile set.  The constants are rough measurements in microseconds.
-    const int per_cu_regs = (a->TB == 7 || a->CS == 4) ? 2 : 3;   // by register count of the variants
+    const int per_cu_regs = (a->TB == 1 && a->CS == 1) ? 3 : 2;   // by register count of the variants
     int per_cu_lds = (int)((160 * 1024) / a->lds_bytes);
     if (per_cu_lds < 1) per_cu_lds = 1;
     const int slots = 256 * (per_cu_regs < per_cu_lds ? per_cu_regs : per_cu_lds);
