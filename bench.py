@@ -108,7 +108,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(the path shards over the batch, see DESIGN.md, but no multi-GPU run is part of it).",
+              "(the path would shard over the batch, but no multi-GPU run is part of it).",
               file=sys.stderr)
         sys.exit(2)
 
