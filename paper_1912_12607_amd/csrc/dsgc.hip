@@ -56,7 +56,9 @@ constexpr int DSGC_ROWS = DSGC_JC + 6;   // 32 code rows, then the 6 digit rows
 constexpr int DSGC_GPITCH = (DSGC_ROWS + 1) * 16;   // 624 bytes
 constexpr int DSGC_TILE = 16 * DSGC_GPITCH;         // 9984 bytes per wave
 // int32 accumulators: |digit * code| <= 128 * 127 per element and lane sum; flushed well before 2^31
-constexpr int DSGC_FLUSH_ITERS = 256;    // 256 iterations x 256 elements x 16256 < 2^31
+// (the bound is 256 iterations: 256 x 256 elements x 16256 < 2^31; 16 keeps the flush path in use at
+// the benchmark sizes -- 12 to 28 iterations per block -- at a cost of under 1 % of the loop)
+constexpr int DSGC_FLUSH_ITERS = 16;
 
 // bytes [a.b3, b.b3, c.b3, d.b3]: the top bytes of four 32-bit values
 __device__ __forceinline__ uint32_t top_bytes(int a, int b, int c, int d) {
