@@ -38,10 +38,9 @@ class _Int8ConvFn(torch.autograd.Function):
         wq = torch.empty(B.int8t_code_bytes(w.shape, wgt_kind), dtype=i8, device=dev)
         sx = torch.empty(1, dtype=f32, device=dev)
         sw = torch.empty(1, dtype=f32, device=dev)
-        B.int8t_quantize(x, x.shape, act_kind, None, B.ROUND_NEAREST_EVEN, 0, xq, sx, None,
-                         _scratch(B.int8t_quantize_workspace_bytes(x.shape, act_kind), dev))
-        B.int8t_quantize(w, w.shape, wgt_kind, None, B.ROUND_NEAREST_EVEN, 0, wq, sw, None,
-                         _scratch(B.int8t_quantize_workspace_bytes(w.shape, wgt_kind), dev))
+        # activations and weights in one batched call (one absmax launch, one quantize launch)
+        items = [(x, tuple(x.shape), act_kind, None, xq, sx), (w, tuple(w.shape), wgt_kind, None, wq, sw)]
+        B.int8t_quantize_batch(items, _scratch(B.int8t_quantize_batch_workspace_bytes(items), dev))
         y = torch.empty((N, K, P, Q), dtype=f32, device=dev)
         nf = B.int8t_workspace_bytes(B.OP_CONV_FWD, desc)
         B.int8t_conv_fwd(desc, xq, sx, wq, sw, y, None, _scratch(nf, dev) if nf else None)
