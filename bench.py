@@ -100,6 +100,9 @@ def main():
                     help="run the clip search every P-th step only (Periodic Update, Table 2); default 1 = "
                          "every step, the benchmark's setting")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="issue every call on one stream (default: a, W quantization and the forward convolution "
+                         "run on a second stream beside the clip search in the steps that search)")
     ap.add_argument("--cpu-images", type=int, default=64)
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="after the steps, run a plain elementwise copy of this many MiB three times "
@@ -117,12 +120,14 @@ def main():
 
     from paper_1912_12607_amd import binding as B
     from paper_1912_12607_amd import inputs
-    from paper_1912_12607_amd.step import LayerStep
+    from paper_1912_12607_amd.step import LayerStep, two_stream_default
 
     assert torch.cuda.is_available(), "bench.py needs the GPU: the HIP library has no CPU fallback"
     n_cand = 32
     period = max(1, args.dsgc_period)
     ratios = inputs.default_ratios(n_cand)
+
+    overlap = False if args.no_overlap else None        # None: LayerStep decides per layer
 
     def bench_layer(cfg, li, steps, warmup):
         """Returns layer, host tensors, seconds per step, {kernel: (launches per step, us per launch)} of
@@ -133,7 +138,7 @@ def main():
         st.upload(x, w, dy, ratios)
         torch.cuda.synchronize()
         for i in range(warmup):
-            st.run(seed=i)
+            st.run(seed=i, overlap=overlap)
         torch.cuda.synchronize()
         # pass 1 (untimed): HIP events around every kernel launch, on the launch stream, inside the library
         nprof = max(3, min(10, steps))
@@ -144,6 +149,7 @@ def main():
         prof = B.int8t_profile_stop()
         per_kernel = {k: (n / nprof, ms * 1e3 / n) for k, (n, ms) in prof.items()}
         dom = max(prof, key=lambda k: prof[k][1])
+        torch.cuda.synchronize()
         # pass 2 (the timed region): only the dominant kernel carries events, and only every 5th of its
         # launches -- a timed dispatch idles the GPU for about 5 us before and after it (measured with a
         # kernel trace), which would otherwise be charged to every step
@@ -152,7 +158,7 @@ def main():
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(steps):
-            st.run(seed=i, search=(i % period == 0))
+            st.run(seed=i, search=(i % period == 0), overlap=overlap)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         n, ms = B.int8t_profile_stop()[dom]
@@ -175,6 +181,12 @@ def main():
     roof["kernel"] = dom
     roof["launches_per_step"] = dom_launches
     roof["us_per_launch"] = dom_us
+    two_streams = overlap is None and period == 1 and two_stream_default(L)
+    if two_streams:
+        # In the timed region the kernel shares the compute units with the second stream's kernels; what it
+        # does with the machine to itself comes from the untimed one-stream pass.
+        roof["us_per_launch_one_stream"] = per_kernel[dom][1]
+        roof["frac_one_stream"] = roof["frac"] * dom_us / per_kernel[dom][1]
 
     out = {
         "metric": "INT8 conv TOPS (fwd+bwd-data+bwd-weight incl. quantize); % int8 MFMA peak",
@@ -184,6 +196,8 @@ def main():
         "config": {"workload": f"config {args.config} layer {args.layer}: {L.name} N={L.N} C={L.C} "
                                f"H=W={L.H}x{L.W} K={L.K} {L.R}x{L.S} stride {L.stride[0]} pad {L.pad} "
                                f"groups {L.groups}; DSGC 32 candidates " + ("every step" if period == 1 else f"every {period} steps"),
+                   "streams": ("2: quantization of a, W and the forward convolution beside the clip search"
+                               if two_streams else "1"),
                    "pct_int8_mfma_peak": 100.0 * tops / INT8_MFMA_PEAK_TOPS,
                    "us_per_kernel": {k: {"launches_per_step": v[0], "us_per_launch": round(v[1], 2)}
                                      for k, v in sorted(per_kernel.items(), key=lambda kv: -kv[1][0] * kv[1][1])},

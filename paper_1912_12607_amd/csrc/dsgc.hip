@@ -44,7 +44,7 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int DSGC_JC = 32;        // candidates per block: the 32 columns of one MFMA tile
 constexpr int DSGC_JPAD = 64;      // row pitch of the partial arrays (= INT8T_MAX_CANDIDATES)
-constexpr int DSGC_MAX_BLOCKS = 1024;   // four blocks per compute unit (LDS: 4 x 40 KB, registers: 4 waves per SIMD)
+constexpr int DSGC_MAX_BLOCKS = 768;   // four blocks per compute unit (LDS: 4 x 40 KB, registers: 4 waves per SIMD)
 constexpr int DSGC_GROUPS = 32;     // accumulator sets the blocks spread their atomics over
 constexpr int DSGC_ROWS = DSGC_JC + 6;   // 32 code rows, then the 6 digit rows
 // A wave's LDS tile holds 256 elements x DSGC_ROWS byte rows, stored by 16-element granule:

@@ -529,10 +529,11 @@ __global__ __launch_bounds__(256) void quantize_wgt_kernel(
 // serves the tensor whose block range holds it and runs that tensor's ordinary pass.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void quantize_batch_kernel(const QuantBatch b) {
-    // one LDS area for whichever pass this block runs
+    // one LDS area for whichever pass this block runs, sized by the host for the tensors of this launch
+    // (a 3x3 weight tensor needs 2.3 KB of tile, not the 16 KB of the largest case: the kernel then fits
+    // beside other kernels' blocks on a compute unit)
     __shared__ float lds4[4];
-    __shared__ __attribute__((aligned(16))) int8_t smem[QW_T * QW_T * QW_TAPS];
-    static_assert(sizeof(smem) >= sizeof(uint32_t) * QA_PIX * (QA_CH / 4 + 1), "the weight tile is the larger one");
+    extern __shared__ __attribute__((aligned(16))) int8_t smem[];
     uint32_t (*const atile)[QA_CH / 4 + 1] = reinterpret_cast<uint32_t (*)[QA_CH / 4 + 1]>(smem);
     int i = 0;
     while (i + 1 < b.count && (int)blockIdx.x >= b.it[i].block0 + b.it[i].gx * b.it[i].gy * b.it[i].gz) ++i;
@@ -572,8 +573,21 @@ void quant_grid(int kind, const int d[4], int* gx, int* gy, int* gz) {
 }
 
 hipError_t launch_quantize_batch(const QuantBatch& b, int total_blocks, hipStream_t st) {
+    size_t lds = 16;
+    for (int i = 0; i < b.count; ++i) {
+        const QuantBatchItem& t = b.it[i];
+        size_t need = 0;
+        if (t.kind == 0) {
+            need = sizeof(uint32_t) * QA_PIX * (QA_CH / 4 + 1);
+        } else if (t.kind == 1) {
+            const int tpb = (t.d2 * t.d3 + t.gz - 1) / t.gz;          // taps per block along z
+            need = (size_t)QW_T * QW_T * (tpb < QW_TAPS ? tpb : QW_TAPS);
+        }
+        if (need > lds) lds = need;
+    }
+    lds = (lds + 15) & ~(size_t)15;
     KernelTimer kt(KID_QUANTIZE_BATCH, st);
-    launch_timed(kt, quantize_batch_kernel, dim3(total_blocks), dim3(256), 0, st, b);
+    launch_timed(kt, quantize_batch_kernel, dim3(total_blocks), dim3(256), lds, st, b);
     return hipGetLastError();
 }
 

@@ -23,6 +23,14 @@ def align256(v: int) -> int:
     return (v + 255) & ~255
 
 
+def two_stream_default(L: Layer) -> bool:
+    """Whether LayerStep.run(overlap=None) uses the second stream in a step that searches the clip: the
+    search must be long enough to hide the other chain behind (the hand-over between the streams costs
+    about 10 us per step), and a depthwise layer's kernels fill the LDS and cannot share a compute
+    unit with the search."""
+    return L.groups == 1 and L.N * L.K * L.P * L.Q >= (1 << 21)
+
+
 class LayerStep:
     def __init__(self, L: Layer, n_cand: int = 32, keep_acc: bool = False, device: str = "cuda:0",
                  requantize_deviation: bool = True):
@@ -71,6 +79,7 @@ class LayerStep:
         self.xw_items = [(self.x, L.x_shape, self.act_kind, None, self.xq, self.sx),
                          (self.w, L.w_shape, self.wgt_kind, None, self.wq, self.sw)]
         self.ws_xw = torch.empty(B.int8t_quantize_batch_workspace_bytes(self.xw_items), dtype=u8, device=d)
+        self._side = None
         self.ws_fwd = torch.empty(nf, dtype=u8, device=d) if nf else None
         self.ws_bwd_data = torch.empty(nb, dtype=u8, device=d) if nb else None
 
@@ -112,17 +121,48 @@ class LayerStep:
         B.int8t_conv_bwd_weight(self.desc, self.xq, self.sx, self.dyq, self.sdy, self.dw, self.dw_acc,
                                 self.ws, stream)
 
-    def run(self, seed: int = 0, stream=None, search: bool = True):
+    def run(self, seed: int = 0, stream=None, search: bool = True, overlap: bool | None = False):
         """The whole hot path once.  search=False keeps the clip value of the last search (the
         paper's Periodic Update, Sec.3.4 / Table 2: the clip is refreshed every P iterations only);
-        the caller decides the period."""
-        self.quantize_xw(stream)
+        the caller decides the period.
+
+        overlap=True puts the quantization of a and W and the forward convolution on a second stream
+        beside the clip search: the two chains are independent until the backward convolutions, the
+        search is bound by the vector ALUs and the other kernels by HBM.  Both streams have the
+        default priority.  Outputs are complete once the main stream is.  overlap=None decides by the
+        layer (two_stream_default) and only in steps that search."""
+        if overlap is None:
+            overlap = search and two_stream_default(self.L)
+        if not overlap:
+            self.quantize_xw(stream)
+            if search:
+                self.dsgc(seed, stream)
+            self.quantize_dy(seed, stream)
+            self.fwd(stream)
+            self.bwd_data(stream)
+            self.bwd_weight(stream)
+            return
+        main = stream if stream is not None else torch.cuda.current_stream()
+        if self._side is None:
+            self._side = torch.cuda.Stream(device=self.dev)
+            self._ev_side = torch.cuda.Event()
+            self._ev_main = torch.cuda.Event()
+        side = self._side
+        # side stream: quantize a and W, forward convolution (needs nothing from the gradient chain).
+        # It starts behind whatever is already queued on the main stream: the previous step's backward
+        # passes still read the codes that are about to be overwritten.
+        self._ev_main.record(main)
+        side.wait_event(self._ev_main)
+        self.quantize_xw(side)
+        self.fwd(side)
+        self._ev_side.record(side)
+        # main stream: clip search, quantize g_z, then the two backward convolutions
         if search:
-            self.dsgc(seed, stream)
-        self.quantize_dy(seed, stream)
-        self.fwd(stream)
-        self.bwd_data(stream)
-        self.bwd_weight(stream)
+            self.dsgc(seed, main)
+        self.quantize_dy(seed, main)
+        main.wait_event(self._ev_side)
+        self.bwd_data(main)
+        self.bwd_weight(main)
 
     # -- host views of the library's code layouts (tests only need numpy reshapes) -----------------
     def codes_x(self) -> np.ndarray:

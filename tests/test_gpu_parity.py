@@ -422,6 +422,24 @@ def test_full_size_layers(cfg, li):
         assert lhs == int((dx_acc.astype(np.int64) * xq).sum()) == int((dw_acc.astype(np.int64) * wq).sum())
 
 
+@pytest.mark.parametrize("cfg,li", [(0, 0), (1, 0), (3, 1)])
+def test_two_stream_step_equals_one_stream_step(cfg, li):
+    """The step with the a / W chain and the forward pass on a second stream writes exactly what the
+    one-stream step writes (several steps in a row, so that the streams' hand-overs are exercised)."""
+    L, x, w, dy = inputs.make_layer_inputs(cfg, li)
+    outs = []
+    for overlap in (False, True):
+        st = LayerStep(L, n_cand=32, keep_acc=True)
+        st.upload(x, w, dy, inputs.default_ratios(32))
+        for seed in (5, 6, 7):
+            st.run(seed=seed, overlap=overlap)
+        torch.cuda.synchronize()
+        outs.append([t.clone() for t in (st.xq, st.wq, st.dyq, st.sx, st.sw, st.sdy, st.clip, st.dev_search,
+                                          st.y, st.dx, st.dw, st.y_acc, st.dx_acc, st.dw_acc)])
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
 def test_same_seed_same_codes_different_seed_differs():
     L, x, w, dy = inputs.make_layer_inputs(0, 0)
     a, _, _ = gpu_quantize(dy, B.ACT, 0.01, STO, seed=42)
