@@ -44,7 +44,11 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int DSGC_JC = 32;        // candidates per block: the 32 columns of one MFMA tile
 constexpr int DSGC_JPAD = 64;      // row pitch of the partial arrays (= INT8T_MAX_CANDIDATES)
-constexpr int DSGC_MAX_BLOCKS = 768;   // four blocks per compute unit (LDS: 4 x 40 KB, registers: 4 waves per SIMD)
+// Three blocks per compute unit.  A fourth would fit (LDS 4 x 40 KB, 4 waves per SIMD) and is about
+// 2 us faster when the sweep has the GPU to itself, but three leave 40 KB of LDS and half the wave
+// slots to kernels of another stream: the sweep is bound by the vector ALUs, so HBM-bound kernels
+// (quantizers, a forward convolution) can run beside it.
+constexpr int DSGC_MAX_BLOCKS = 768;
 constexpr int DSGC_GROUPS = 32;     // accumulator sets the blocks spread their atomics over
 constexpr int DSGC_ROWS = DSGC_JC + 6;   // 32 code rows, then the 6 digit rows
 // A wave's LDS tile holds 256 elements x DSGC_ROWS byte rows, stored by 16-element granule:
@@ -361,7 +365,7 @@ hipError_t launch_dsgc(const float* g, size_t n, const float* ratios, int n_cand
                        uint64_t seed, const DsgcWs& ws, int nparts_absmax, float* clip_out,
                        double* dev_out, double* dev_all_out, hipStream_t st) {
     const int nchunks = (n_cand + DSGC_JC - 1) / DSGC_JC;
-    // about four blocks per compute unit in total; every candidate chunk walks the same x-grid
+    // about three blocks per compute unit in total; every candidate chunk walks the same x-grid
     int blocks = dsgc_blocks(n);
     const int cap = (DSGC_MAX_BLOCKS + nchunks - 1) / nchunks;
     if (blocks > cap) blocks = cap;
