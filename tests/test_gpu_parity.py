@@ -245,6 +245,11 @@ CONV_SHAPES = [
     # few output tiles and a long reduction: the reduction is split over several blocks
     (2, 256, 9, 9, 96, 3, 3, (2, 2), (0, 0), 1),
     (40, 520, 1, 1, 200, 1, 1, (1, 1), (0, 0), 1),
+    # more strides
+    (2, 64, 8, 8, 128, 1, 1, (2, 2), (0, 0), 1),       # 1x1 stride 2: most input pixels receive no gradient
+    (2, 40, 9, 10, 72, 3, 3, (2, 2), (1, 1), 1),
+    (1, 16, 13, 11, 24, 5, 3, (3, 2), (2, 1), 1),
+    (1, 16, 7, 7, 16, 2, 2, (3, 3), (0, 0), 1),        # stride larger than the filter: pixels no tap reaches
 ]
 
 
@@ -291,11 +296,11 @@ def test_conv_three_passes_bit_exact(shape):
 
 def test_conv_without_optional_workspace():
     # forward / backward-data take their scratch as a hint: without it the result is the same
-    shape = (2, 256, 9, 9, 96, 3, 3, (2, 2), (0, 0), 1)
+    shape = (2, 256, 9, 9, 96, 3, 3, (1, 1), (1, 1), 1)
     N, C, H, W, K, R, S, st, pd, g = shape
     gd = B.make_desc(N, C, H, W, K, R, S, st, pd, g)
     assert B.int8t_workspace_bytes(B.OP_CONV_FWD, gd) > 0 and B.int8t_workspace_bytes(B.OP_CONV_BWD_DATA, gd) > 0
-    P, Q = (H - R) // 2 + 1, (W - S) // 2 + 1
+    P, Q = H, W
     r = np.random.RandomState(7)
     x = r.randint(-127, 128, size=(N, C, H, W)).astype(np.int8)
     w = r.randint(-127, 128, size=(K, C, R, S)).astype(np.int8)
