@@ -180,6 +180,19 @@ int8t_status int8t_dsgc_clip(const float *g_dev, size_t n, const float *ratios_d
                              void *ws_dev, size_t ws_bytes, void *stream);
 
 /*
+ * The same search in its two phases, for callers that want to put something between them (an event
+ * for a second stream, say): int8t_dsgc_prepare is the pass over g that finds max|g| and the sum of
+ * squares of Eq.6 and clears the accumulators in the scratch; int8t_dsgc_search is the sweep over
+ * the candidates, which needs the scratch exactly as the preceding int8t_dsgc_prepare on the same g,
+ * n and ws_dev left it.  int8t_dsgc_clip is the two calls in a row; arguments as there.
+ */
+int8t_status int8t_dsgc_prepare(const float *g_dev, size_t n, void *ws_dev, size_t ws_bytes, void *stream);
+int8t_status int8t_dsgc_search(const float *g_dev, size_t n, const float *ratios_dev, int n_cand,
+                               int8t_round mode, uint64_t seed,
+                               float *clip_dev, double *deviation_dev, double *deviation_all_dev,
+                               void *ws_dev, size_t ws_bytes, void *stream);
+
+/*
  * Forward convolution on codes: acc[n,k,p,q] = sum_{c,r,s} xq[n,c,p*sh+r-ph,q*sw+s-pw] * wq[k,c,r,s]
  * in int32 (two's-complement wrap), then Eq.2: y = (float)acc * (sx * sw).
  *   xq_dev   INT8T_ACT codes of dims {N,C,H,W}   (INT8T_ACT_PLANAR when depthwise)

@@ -277,9 +277,35 @@ int8t_status int8t_quantize_batch(int count, const int8t_quantize_item* items, v
     return INT8T_OK;
 }
 
-int8t_status int8t_dsgc_clip(const float* g_dev, size_t n, const float* ratios_dev, int n_cand,
-                             int8t_round mode, uint64_t seed, float* clip_dev, double* deviation_dev,
-                             double* deviation_all_dev, void* ws_dev, size_t ws_bytes, void* stream) {
+namespace {
+DsgcWs dsgc_ws_layout(void* ws_dev) {
+    char* p = (char*)ws_dev;
+    DsgcWs ws;
+    const size_t nacc = dsgc_acc_words();
+    ws.absmax_part = (float*)p;                 p += align256(kMaxPartials * sizeof(float));
+    ws.acc = (unsigned long long*)p;
+    ws.ticket = (unsigned int*)(ws.acc + nacc);  p += align256((nacc + 1) * sizeof(unsigned long long));
+    ws.partG = (double*)p;
+    return ws;
+}
+}  // namespace
+
+int8t_status int8t_dsgc_prepare(const float* g_dev, size_t n, void* ws_dev, size_t ws_bytes, void* stream) {
+    if (!g_dev || !ws_dev) return INT8T_ERR_NULL;
+    if (n == 0 || n > kMaxElems) return INT8T_ERR_SHAPE;
+    if (!aligned16(g_dev) || !aligned16(ws_dev)) return INT8T_ERR_ARG;
+    if (ws_bytes < dsgc_ws_bytes(n)) return INT8T_ERR_WORKSPACE;
+    const DsgcWs ws = dsgc_ws_layout(ws_dev);
+    int nparts = 0;
+    if (launch_absmax(g_dev, n, ws.absmax_part, &nparts, (hipStream_t)stream, ws.partG, ws.acc,
+                      (int)dsgc_acc_words() + 1) != hipSuccess)
+        return INT8T_ERR_RUNTIME;
+    return INT8T_OK;
+}
+
+int8t_status int8t_dsgc_search(const float* g_dev, size_t n, const float* ratios_dev, int n_cand,
+                               int8t_round mode, uint64_t seed, float* clip_dev, double* deviation_dev,
+                               double* deviation_all_dev, void* ws_dev, size_t ws_bytes, void* stream) {
     if (!g_dev || !ratios_dev || !clip_dev || !deviation_dev || !ws_dev) return INT8T_ERR_NULL;
     if (n == 0 || n > kMaxElems) return INT8T_ERR_SHAPE;
     if (n_cand < 1 || n_cand > INT8T_MAX_CANDIDATES) return INT8T_ERR_ARG;
@@ -288,21 +314,29 @@ int8t_status int8t_dsgc_clip(const float* g_dev, size_t n, const float* ratios_d
         (reinterpret_cast<uintptr_t>(deviation_dev) & 7) || (reinterpret_cast<uintptr_t>(deviation_all_dev) & 7))
         return INT8T_ERR_ARG;
     if (ws_bytes < dsgc_ws_bytes(n)) return INT8T_ERR_WORKSPACE;
-    hipStream_t st = (hipStream_t)stream;
-    char* p = (char*)ws_dev;
-    DsgcWs ws;
-    const size_t nacc = dsgc_acc_words();
-    ws.absmax_part = (float*)p;                 p += align256(kMaxPartials * sizeof(float));
-    ws.acc = (unsigned long long*)p;
-    ws.ticket = (unsigned int*)(ws.acc + nacc);  p += align256((nacc + 1) * sizeof(unsigned long long));
-    ws.partG = (double*)p;
-    int nparts = 0;
-    if (launch_absmax(g_dev, n, ws.absmax_part, &nparts, st, ws.partG, ws.acc, (int)nacc + 1) != hipSuccess)
-        return INT8T_ERR_RUNTIME;
-    if (launch_dsgc(g_dev, n, ratios_dev, n_cand, mode == INT8T_ROUND_STOCHASTIC, seed, ws, nparts, clip_dev,
-                    deviation_dev, deviation_all_dev, st) != hipSuccess)
+    const DsgcWs ws = dsgc_ws_layout(ws_dev);
+    if (launch_dsgc(g_dev, n, ratios_dev, n_cand, mode == INT8T_ROUND_STOCHASTIC, seed, ws, absmax_blocks(n), clip_dev,
+                    deviation_dev, deviation_all_dev, (hipStream_t)stream) != hipSuccess)
         return INT8T_ERR_RUNTIME;
     return INT8T_OK;
+}
+
+int8t_status int8t_dsgc_clip(const float* g_dev, size_t n, const float* ratios_dev, int n_cand,
+                             int8t_round mode, uint64_t seed, float* clip_dev, double* deviation_dev,
+                             double* deviation_all_dev, void* ws_dev, size_t ws_bytes, void* stream) {
+    // argument checks of both phases first, so that nothing is launched on bad input
+    if (!g_dev || !ratios_dev || !clip_dev || !deviation_dev || !ws_dev) return INT8T_ERR_NULL;
+    if (n == 0 || n > kMaxElems) return INT8T_ERR_SHAPE;
+    if (n_cand < 1 || n_cand > INT8T_MAX_CANDIDATES) return INT8T_ERR_ARG;
+    if (mode != INT8T_ROUND_NEAREST_EVEN && mode != INT8T_ROUND_STOCHASTIC) return INT8T_ERR_ARG;
+    if (!aligned16(g_dev) || !aligned16(ws_dev) || !aligned4(ratios_dev) || !aligned4(clip_dev) ||
+        (reinterpret_cast<uintptr_t>(deviation_dev) & 7) || (reinterpret_cast<uintptr_t>(deviation_all_dev) & 7))
+        return INT8T_ERR_ARG;
+    if (ws_bytes < dsgc_ws_bytes(n)) return INT8T_ERR_WORKSPACE;
+    int8t_status s = int8t_dsgc_prepare(g_dev, n, ws_dev, ws_bytes, stream);
+    if (s != INT8T_OK) return s;
+    return int8t_dsgc_search(g_dev, n, ratios_dev, n_cand, mode, seed, clip_dev, deviation_dev, deviation_all_dev,
+                             ws_dev, ws_bytes, stream);
 }
 
 int8t_status int8t_conv_fwd(const int8t_conv_desc* desc, const int8_t* xq_dev, const float* sx_dev,

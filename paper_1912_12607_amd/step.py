@@ -148,17 +148,23 @@ class LayerStep:
             self._ev_side = torch.cuda.Event()
             self._ev_main = torch.cuda.Event()
         side = self._side
+        # main stream: clip search, quantize g_z, then the two backward convolutions.
         # side stream: quantize a and W, forward convolution (needs nothing from the gradient chain).
-        # It starts behind whatever is already queued on the main stream: the previous step's backward
-        # passes still read the codes that are about to be overwritten.
+        # It starts behind whatever is queued on the main stream up to the search's first pass (the
+        # previous step's backward passes still read the codes that are about to be overwritten, and
+        # that pass is bound by HBM like the side stream's kernels: beside each other they would only
+        # slow each other down), i.e. together with the sweep.
+        n_y = self.dy.numel()
+        if search:
+            B.int8t_dsgc_prepare(self.dy, n_y, self.ws_dy, main)
         self._ev_main.record(main)
         side.wait_event(self._ev_main)
         self.quantize_xw(side)
         self.fwd(side)
         self._ev_side.record(side)
-        # main stream: clip search, quantize g_z, then the two backward convolutions
         if search:
-            self.dsgc(seed, main)
+            B.int8t_dsgc_search(self.dy, n_y, self.ratios, self.n_cand, B.ROUND_STOCHASTIC, seed,
+                                self.clip, self.dev_search, self.dev_all, self.ws_dy, main)
         self.quantize_dy(seed, main)
         main.wait_event(self._ev_side)
         self.bwd_data(main)

@@ -172,3 +172,19 @@ def test_quantize_batch_argument_errors(lib):
     items[0].q_dev = 0x2004
     assert f(2, items, 0x4000, 1 << 20, None) == 3                 # alignment
 
+
+def test_dsgc_two_phase_argument_errors(lib):
+    vp = C.c_void_p
+    prep, search = lib.int8t_dsgc_prepare, lib.int8t_dsgc_search
+    prep.restype = search.restype = C.c_int
+    prep.argtypes = [vp, C.c_size_t, vp, C.c_size_t, vp]
+    search.argtypes = [vp, C.c_size_t, vp, C.c_int, C.c_int, C.c_uint64, vp, vp, vp, vp, C.c_size_t, vp]
+    need = lib.int8t_workspace_bytes(1, None, C.c_size_t(1000), 32)
+    assert prep(None, 1000, 0x4000, need, None) == 1
+    assert prep(0x1000, 0, 0x4000, need, None) == 2
+    assert prep(0x1004, 1000, 0x4000, need, None) == 3
+    assert prep(0x1000, 1000, 0x4000, need - 1, None) == 4
+    assert search(0x1000, 1000, None, 32, 1, 0, 0x2000, 0x3000, None, 0x4000, need, None) == 1
+    assert search(0x1000, 1000, 0x5000, 65, 1, 0, 0x2000, 0x3000, None, 0x4000, need, None) == 3
+    assert search(0x1000, 1000, 0x5000, 32, 1, 0, 0x2000, 0x3000, None, 0x4000, need - 1, None) == 4
+
