@@ -92,8 +92,10 @@ def cpu_baseline(L, x, w, dy, ratios, n_img):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    # a step takes about 0.15 ms: with a few dozen steps the GPU is still ramping its clocks up while it is
+    # measured (50 steps after 5: 0.149 ms per step; 500 after 200: 0.140 ms), hence the long defaults
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--config", type=int, default=1, help="benchmark config index (default 1: ResNet-18 3x3)")
     ap.add_argument("--layer", type=int, default=0)
     ap.add_argument("--dsgc-period", type=int, default=1,
