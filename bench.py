@@ -110,6 +110,9 @@ def main():
                     help="after the steps, run a plain elementwise copy of this many MiB three times "
                          "(reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--all-layers", action="store_true", help="also print a per-layer table for every config (stderr)")
+    ap.add_argument("--resnet50", type=int, default=0, metavar="BATCH",
+                    help="also time the step of every ResNet-50 convolution and its classifier at this batch "
+                         "(Fig.10's workload) and print the per-layer table and the network total (stderr)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -231,6 +234,30 @@ def main():
                     row[k] = {"us_per_step": round(n * us, 2), "GB/s": round(al[k]["bytes"] / t / 1e9, 1),
                               "TOP/s": round(al[k]["ops"] / t / 1e12, 2)}
                 print(json.dumps(row), file=sys.stderr, flush=True)
+
+    if args.resnet50 > 0:
+        total_ms, total_macs = 0.0, 0
+        for i, (count, Lx) in enumerate(inputs.resnet50_layers(args.resnet50)):
+            st = LayerStep(Lx, n_cand=n_cand, keep_acc=False, requantize_deviation=False)
+            st.upload(inputs.make_x(Lx, 50, i), inputs.make_w(Lx, 50, i), inputs.make_dy(Lx, 50, i), ratios)
+            nst = max(20, args.steps // 10)
+            for k in range(10):
+                st.run(seed=k, overlap=overlap)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for k in range(nst):
+                st.run(seed=k, search=(k % period == 0), overlap=overlap)
+            torch.cuda.synchronize()
+            ts = (time.perf_counter() - t0) / nst
+            total_ms += count * ts * 1e3
+            total_macs += count * Lx.macs
+            print(json.dumps({"layer": Lx.name, "count": count, "C": Lx.C, "HW": Lx.H, "K": Lx.K, "RS": Lx.R,
+                              "stride": Lx.stride[0], "ms_per_step": round(ts * 1e3, 4),
+                              "TOPS": round(6 * Lx.macs / ts / 1e12, 1)}), file=sys.stderr, flush=True)
+            del st
+        print(json.dumps({"network": "ResNet-50 convolutions + classifier", "batch": args.resnet50,
+                          "ms_per_iteration": round(total_ms, 3), "TOPS": round(6 * total_macs / total_ms / 1e9, 1),
+                          "images_per_s": round(args.resnet50 / total_ms * 1e3, 1)}), file=sys.stderr, flush=True)
 
     print(json.dumps(out), flush=True)
 

@@ -30,8 +30,39 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 // granule) spread over all banks.
 __device__ __forceinline__ int lds_slot(int row, int g) { return row * 4 + (g ^ ((row >> 1) & 3)); }
 
-template <int BM, int BN, bool DGRAD>
+// Strided backward-data by residue classes.  The input pixels (h, w) with h % stride_h == ch and
+// w % stride_w == cw all receive the same filter taps: r = r0 + stride_h * tr, s = s0 + stride_w * ts,
+// and for pixel h = ch + stride_h * i the tap tr reads gradient row i + bh - tr.  In the class's own
+// coordinates (i, j, tr, ts) that is a stride-1 backward-data pass over nr x ns taps, so a tile whose
+// columns are pixels of ONE class spends no matrix-core work on the taps that never reach it (a
+// tile of neighbouring pixels multiplies stride_h * stride_w - 1 zeros for every useful product).
+// A class without taps (1x1 filter, stride 2: three pixels in four) gets zeros.
+struct DgradClass {
+    int ch, cw;        // residues of the class
+    int OHc, OWc;      // pixels of the class per image: rows, columns
+    int r0, s0, nr, ns;
+    int bh, bw;
+};
+__device__ __forceinline__ DgradClass dgrad_class(const IgemmArgs& a, int cls) {
+    DgradClass c;
+    const int csh = a.cls_h, csw = a.cls_w;     // the stride, or 1 where that direction is not split
+    c.ch = cls / csw;
+    c.cw = cls - c.ch * csw;
+    c.OHc = (a.OH - c.ch + csh - 1) / csh;
+    c.OWc = (a.OW - c.cw + csw - 1) / csw;
+    c.r0 = (c.ch + a.pad_h) % csh;
+    c.s0 = (c.cw + a.pad_w) % csw;
+    c.nr = c.r0 < a.R ? (a.R - c.r0 + csh - 1) / csh : 0;
+    c.ns = c.s0 < a.S ? (a.S - c.s0 + csw - 1) / csw : 0;
+    c.bh = (c.ch + a.pad_h - c.r0) / csh;
+    c.bw = (c.cw + a.pad_w - c.s0) / csw;
+    return c;
+}
+
+// CLS (backward-data with a stride only): blockIdx.x = column tile * classes + class.
+template <int BM, int BN, bool DGRAD, bool CLS = false>
 __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmArgs a) {
+    static_assert(DGRAD || !CLS, "residue classes exist in the backward-data pass only");
     constexpr int MI = BM / 64;   // 32-row MFMA tiles per wave
     constexpr int NJ = BN / 64;   // 32-column MFMA tiles per wave
     constexpr int NB = BN / 64;   // B-tile columns staged per thread
@@ -43,13 +74,23 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmArgs a) {
     const int wm = wave & 1, wn = wave >> 1;
     const int lrow = tid >> 2, lg = tid & 3;
 
-    const int OHW = a.OH * a.OW;
-    const int ncols = a.N * OHW;
+    const int OHWfull = a.OH * a.OW;
     const int Cg16 = a.Ca >> 4;
-    const int gtot = a.R * a.S * Cg16;
+    DgradClass dc;
+    int colblock = blockIdx.x;
+    if (CLS) {
+        const int ncls = a.cls_h * a.cls_w;
+        colblock = blockIdx.x / ncls;
+        dc = dgrad_class(a, (int)blockIdx.x - colblock * ncls);
+    }
+    const int OWc = CLS ? dc.OWc : a.OW;
+    const int OHW = CLS ? dc.OHc * dc.OWc : OHWfull;     // columns per image
+    const int ncols = a.N * OHW;
+    const int nr = CLS ? dc.nr : a.R, ns = CLS ? dc.ns : a.S;
+    const int gtot = nr * ns * Cg16;
     const int nsteps = (gtot + 3) >> 2;
     const int rowbase = blockIdx.y * BM;
-    const int colbase = blockIdx.x * BN;
+    const int colbase = colblock * BN;
     // split reduction: block z works on the stages [step0, step1) and stores raw partial sums
     const int step0 = (int)(((long long)nsteps * blockIdx.z) / a.ksplit);
     const int step1 = (int)(((long long)nsteps * (blockIdx.z + 1)) / a.ksplit);
@@ -65,9 +106,9 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmArgs a) {
         bvalid[i] = col < ncols;
         const int cc = bvalid[i] ? col : 0;
         const int n = cc / OHW, rem = cc - n * OHW;
-        const int oh = rem / a.OW, ow = rem - oh * a.OW;
-        bh[i] = DGRAD ? (oh + a.pad_h) : (oh * a.stride_h - a.pad_h);
-        bw[i] = DGRAD ? (ow + a.pad_w) : (ow * a.stride_w - a.pad_w);
+        const int oh = rem / OWc, ow = rem - oh * OWc;
+        bh[i] = CLS ? (oh + dc.bh) : DGRAD ? (oh + a.pad_h) : (oh * a.stride_h - a.pad_h);
+        bw[i] = CLS ? (ow + dc.bw) : DGRAD ? (ow + a.pad_w) : (ow * a.stride_w - a.pad_w);
         bimg[i] = a.act + (size_t)n * a.IH * a.IW * a.Ca;
     }
     // reduction position of this thread's granule: filter tap (r,s) and channel granule cg
@@ -76,8 +117,8 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmArgs a) {
         const int q0 = step0 * 4 + lg;
         const int tap = q0 / Cg16;
         cg = q0 - tap * Cg16;
-        r = tap / a.S;
-        s = tap - r * a.S;
+        r = tap / (ns > 0 ? ns : 1);
+        s = tap - r * ns;
     }
     // A (weights): MI rows per thread
     const int8_t* arow[MI];
@@ -86,17 +127,19 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmArgs a) {
     for (int i = 0; i < MI; ++i) {
         const int row = rowbase + i * 64 + lrow;
         avalid[i] = row < a.rows;
-        arow[i] = a.wgt + (size_t)(avalid[i] ? row : 0) * gtot * 16;
+        arow[i] = a.wgt + (size_t)(avalid[i] ? row : 0) * (a.R * a.S * Cg16) * 16;
     }
 
     uint4 ra[MI], rb[NB];
     auto load_step = [&](int step) {
         const int q = step * 4 + lg;
         const bool qv = q < gtot;
+        // granule of the filter row: the taps of a class are a sub-grid of the R x S filter
+        const int wq = CLS ? ((dc.r0 + a.cls_h * r) * a.S + dc.s0 + a.cls_w * s) * Cg16 + cg : q;
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
             ra[i] = make_uint4(0, 0, 0, 0);
-            if (qv && avalid[i]) ra[i] = *reinterpret_cast<const uint4*>(arow[i] + (size_t)q * 16);
+            if (qv && avalid[i]) ra[i] = *reinterpret_cast<const uint4*>(arow[i] + (size_t)wq * 16);
         }
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
@@ -105,13 +148,15 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmArgs a) {
             bool ok = qv && bvalid[i];
             if (DGRAD) {
                 const int th = bh[i] - r, tw = bw[i] - s;
-                if (a.stride_h == 1 && a.stride_w == 1) {
+                // a direction split into classes is a stride-1 pass; otherwise only the taps that divide reach a pixel
+                const int dsh = CLS ? a.stride_h / a.cls_h : a.stride_h, dsw = CLS ? a.stride_w / a.cls_w : a.stride_w;
+                if (dsh == 1 && dsw == 1) {
                     ih = th;
                     iw = tw;
                 } else {
-                    ih = th / a.stride_h;
-                    iw = tw / a.stride_w;
-                    ok = ok && th >= 0 && tw >= 0 && (ih * a.stride_h == th) && (iw * a.stride_w == tw);
+                    ih = th / dsh;
+                    iw = tw / dsw;
+                    ok = ok && th >= 0 && tw >= 0 && (ih * dsh == th) && (iw * dsw == tw);
                 }
             } else {
                 ih = bh[i] + r;
@@ -125,7 +170,7 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmArgs a) {
         cg += 4;
         while (cg >= Cg16) {
             cg -= Cg16;
-            if (++s == a.S) {
+            if (++s == ns) {
                 s = 0;
                 ++r;
             }
@@ -180,20 +225,25 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmArgs a) {
     // ---- epilogue: Eq.2, straight into N,C,H,W; a split reduction leaves its share of the sums
     // in partial[z][N][rows][OH*OW] for igemm_reduce_kernel instead ---------------------------
     const bool split = a.ksplit > 1;
-    int32_t* __restrict__ const part = split ? a.partial + (size_t)blockIdx.z * a.N * a.rows * OHW : nullptr;
+    int32_t* __restrict__ const part = split ? a.partial + (size_t)blockIdx.z * a.N * a.rows * OHWfull : nullptr;
     const float scale = __fmul_rn(a.sa[0], a.sb[0]);
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
         const int col = colbase + wn * (BN / 2) + j * 32 + (lane & 31);
         if (col >= ncols) continue;
-        const int n = col / OHW, opix = col - n * OHW;
+        const int n = col / OHW;
+        int opix = col - n * OHW;
+        if (CLS) {
+            const int ci = opix / OWc;
+            opix = (dc.ch + a.cls_h * ci) * a.OW + dc.cw + a.cls_w * (opix - ci * OWc);
+        }
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = rowbase + wm * (BM / 2) + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
                 if (row < a.rows) {
-                    const size_t idx = ((size_t)n * a.rows + row) * OHW + opix;
+                    const size_t idx = ((size_t)n * a.rows + row) * OHWfull + opix;
                     const int val = acc[i][j][v];
                     if (split) {
                         part[idx] = val;
@@ -285,8 +335,9 @@ __device__ __forceinline__ void igd_wait_vmcnt() {
     else asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
 }
 
-template <bool DGRAD, int WM, int KG, int NSTAGE>
+template <bool DGRAD, int WM, int KG, int NSTAGE, bool CLS = false>
 __global__ __launch_bounds__(128 * WM, WM == 2 ? 2 : 1) void igemm_dma_kernel(const IgemmArgs a) {
+    static_assert(DGRAD || !CLS, "residue classes exist in the backward-data pass only");
     constexpr int BM = 64 * WM, BN = IGD_BN, MI = 2, NJ = 4, NW = 2 * WM;
     constexpr int STAGE_SLOTS = (BM + BN) * KG;         // 16-byte slots per stage: A tile, then B tile
     constexpr int RPL = 64 / KG;                        // tile rows covered by one wave-wide load
@@ -300,23 +351,37 @@ __global__ __launch_bounds__(128 * WM, WM == 2 ? 2 : 1) void igemm_dma_kernel(co
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WM, wn = wave / WM;
 
-    const int OHW = a.OH * a.OW;
-    const int ncols = a.N * OHW;
+    const int OHWfull = a.OH * a.OW;
     const int Cg16 = a.Ca >> 4;
-    const int gtot = a.R * a.S * Cg16;
-    const int nsteps = (gtot + KG - 1) / KG;
+    const int gfull = a.R * a.S * Cg16;
     // Workgroups are dealt to the 8 XCDs round-robin (workgroup b runs on XCD b % 8).  Column tile
     // ct = 8 * (i / rtiles) + xcd, row tile i % rtiles, i = b / 8: all row tiles of a column tile --
     // they read the same pixels -- run on one XCD and share its L2, as do the column tiles of an XCD
     // that read the same filter rows.  The grid is padded to whole groups of 8 column tiles.
+    // CLS: the residue classes of a column tile follow each other on the same XCD as well (they read
+    // the same gradient pixels and write interleaved floats of the same cache lines).
     const int rtiles = (a.rows + BM - 1) / BM;
     const int wg_i = blockIdx.x >> 3;
-    const int ctile = ((wg_i / rtiles) << 3) + (int)(blockIdx.x & 7);
+    int cgroup = wg_i / rtiles;
+    DgradClass dc;
+    if (CLS) {
+        const int ncls = a.cls_h * a.cls_w;
+        const int g = cgroup / ncls;
+        dc = dgrad_class(a, cgroup - g * ncls);
+        cgroup = g;
+    }
+    const int OWc = CLS ? dc.OWc : a.OW;
+    const int OHW = CLS ? dc.OHc * dc.OWc : OHWfull;     // columns per image
+    const int ncols = a.N * OHW;
+    const int nr = CLS ? dc.nr : a.R, ns = CLS ? dc.ns : a.S;
+    const int gtot = nr * ns * Cg16;
+    const int nsteps = (gtot + KG - 1) / KG;
+    const int ctile = (cgroup << 3) + (int)(blockIdx.x & 7);
     if (ctile * BN >= ncols) return;
     const int rowbase = (wg_i % rtiles) * BM;
     const int colbase = ctile * BN;
 
-    const v4i wr = igd_rsrc(a.wgt, (uint32_t)((size_t)a.rows * gtot * 16));
+    const v4i wr = igd_rsrc(a.wgt, (uint32_t)((size_t)a.rows * gfull * 16));
     const v4i xr = igd_rsrc(a.act, (uint32_t)((size_t)a.N * a.IH * a.IW * a.Ca));
     // LDS byte address of this wave's first A / B load slot in buffer 0 (wave-uniform)
     const uint32_t lds_a0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(size_t)(ring + 64 * wave));
@@ -330,7 +395,7 @@ __global__ __launch_bounds__(128 * WM, WM == 2 ? 2 : 1) void igemm_dma_kernel(co
 #pragma unroll
     for (int i = 0; i < NLA; ++i) {
         const int row = rowbase + RPL * (wave + NW * i) + lrow;
-        aoff[i] = row < a.rows ? (uint32_t)row * (uint32_t)gtot * 16u : IGD_OOB;
+        aoff[i] = row < a.rows ? (uint32_t)row * (uint32_t)gfull * 16u : IGD_OOB;
     }
     int bh[NLB], bw[NLB];
     uint32_t bimg[NLB];                                      // byte offset of the column's image or OOB
@@ -340,9 +405,9 @@ __global__ __launch_bounds__(128 * WM, WM == 2 ? 2 : 1) void igemm_dma_kernel(co
         const bool cv = col < ncols;
         const int cc = cv ? col : 0;
         const int n = cc / OHW, rem = cc - n * OHW;
-        const int oh = rem / a.OW, ow = rem - oh * a.OW;
-        bh[i] = DGRAD ? (oh + a.pad_h) : (oh * a.stride_h - a.pad_h);
-        bw[i] = DGRAD ? (ow + a.pad_w) : (ow * a.stride_w - a.pad_w);
+        const int oh = rem / OWc, ow = rem - oh * OWc;
+        bh[i] = CLS ? (oh + dc.bh) : DGRAD ? (oh + a.pad_h) : (oh * a.stride_h - a.pad_h);
+        bw[i] = CLS ? (ow + dc.bw) : DGRAD ? (ow + a.pad_w) : (ow * a.stride_w - a.pad_w);
         bimg[i] = cv ? (uint32_t)n * (uint32_t)(a.IH * a.IW * a.Ca) : IGD_OOB;
     }
     // reduction position of this lane's granule: filter tap (r,s) and channel granule cg
@@ -350,17 +415,19 @@ __global__ __launch_bounds__(128 * WM, WM == 2 ? 2 : 1) void igemm_dma_kernel(co
     {
         const int tap = gsw / Cg16;
         cg = gsw - tap * Cg16;
-        r = tap / a.S;
-        s = tap - r * a.S;
+        r = tap / (ns > 0 ? ns : 1);
+        s = tap - r * ns;
     }
     int qnext = gsw;                                         // granule index of the next stage to issue
 
     auto issue_a = [&](int buf) {
         const uint32_t boff = (uint32_t)buf * (STAGE_SLOTS * 16u);
         const bool qv = qnext < gtot;
+        // granule of the filter row: the taps of a class are a sub-grid of the R x S filter
+        const int wq = CLS ? ((dc.r0 + a.cls_h * r) * a.S + dc.s0 + a.cls_w * s) * Cg16 + cg : qnext;
 #pragma unroll
         for (int i = 0; i < NLA; ++i) {
-            const uint32_t off = (qv && aoff[i] != IGD_OOB) ? aoff[i] + (uint32_t)qnext * 16u : IGD_OOB;
+            const uint32_t off = (qv && aoff[i] != IGD_OOB) ? aoff[i] + (uint32_t)wq * 16u : IGD_OOB;
             igd_load_lds(wr, lds_a0 + boff + (uint32_t)i * (NW * 64 * 16), off);
         }
     };
@@ -373,13 +440,15 @@ __global__ __launch_bounds__(128 * WM, WM == 2 ? 2 : 1) void igemm_dma_kernel(co
             bool ok = qv && bimg[i] != IGD_OOB;
             if (DGRAD) {
                 const int th = bh[i] - r, tw = bw[i] - s;
-                if (a.stride_h == 1 && a.stride_w == 1) {
+                // a direction split into classes is a stride-1 pass; otherwise only the taps that divide reach a pixel
+                const int dsh = CLS ? a.stride_h / a.cls_h : a.stride_h, dsw = CLS ? a.stride_w / a.cls_w : a.stride_w;
+                if (dsh == 1 && dsw == 1) {
                     ih = th;
                     iw = tw;
                 } else {
-                    ih = th / a.stride_h;
-                    iw = tw / a.stride_w;
-                    ok = ok && th >= 0 && tw >= 0 && (ih * a.stride_h == th) && (iw * a.stride_w == tw);
+                    ih = th / dsh;
+                    iw = tw / dsw;
+                    ok = ok && th >= 0 && tw >= 0 && (ih * dsh == th) && (iw * dsw == tw);
                 }
             } else {
                 ih = bh[i] + r;
@@ -394,7 +463,7 @@ __global__ __launch_bounds__(128 * WM, WM == 2 ? 2 : 1) void igemm_dma_kernel(co
         cg += KG;
         while (cg >= Cg16) {
             cg -= Cg16;
-            if (++s == a.S) {
+            if (++s == ns) {
                 s = 0;
                 ++r;
             }
@@ -410,8 +479,10 @@ __global__ __launch_bounds__(128 * WM, WM == 2 ? 2 : 1) void igemm_dma_kernel(co
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
     // prologue: the first NSTAGE-1 stages on their way
-    issue_a(0);
-    issue_b(0);
+    if (nsteps > 0) {     // (a class without taps has nothing to load: its pixels get zeros)
+        issue_a(0);
+        issue_b(0);
+    }
     if (NSTAGE == 3 && nsteps > 1) {
         issue_a(1);
         issue_b(1);
@@ -460,14 +531,19 @@ __global__ __launch_bounds__(128 * WM, WM == 2 ? 2 : 1) void igemm_dma_kernel(co
     for (int j = 0; j < NJ; ++j) {
         const int col = colbase + wn * 128 + j * 32 + (lane & 31);
         if (col >= ncols) continue;
-        const int n = col / OHW, opix = col - n * OHW;
+        const int n = col / OHW;
+        int opix = col - n * OHW;
+        if (CLS) {
+            const int ci = opix / OWc;
+            opix = (dc.ch + a.cls_h * ci) * a.OW + dc.cw + a.cls_w * (opix - ci * OWc);
+        }
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = rowbase + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
                 if (row < a.rows) {
-                    const size_t idx = ((size_t)n * a.rows + row) * OHW + opix;
+                    const size_t idx = ((size_t)n * a.rows + row) * OHWfull + opix;
                     const int val = acc[i][j][v];
                     a.out[idx] = __fmul_rn((float)val, scale);
                     if (a.acc) a.acc[idx] = val;
@@ -477,37 +553,77 @@ __global__ __launch_bounds__(128 * WM, WM == 2 ? 2 : 1) void igemm_dma_kernel(co
     }
 }
 
-template <bool DGRAD, int WM, int KG, int NSTAGE>
-static hipError_t launch_igemm_dma(const IgemmArgs& a, int ncols, hipStream_t st, const KernelTimer& kt) {
+namespace {
+// Shape of the GEMM(s) a launch runs.  A strided backward-data pass is stride_h * stride_w stride-1
+// problems, one per residue class of the pixels (dgrad_class): fewer columns and fewer taps each.
+struct IgemmShape {
+    bool cls;
+    int cls_h, cls_w;  // class strides (1, 1 when the pixels are not split)
+    int ncls;
+    long long ncols;   // columns of one GEMM (the largest class)
+    long long gran;    // 16-byte reduction granules per column (the largest class)
+};
+IgemmShape igemm_shape(const IgemmArgs& a) {
+    IgemmShape g;
+    // Split when more than one class has taps.  With a single one (a 1x1 filter) the pass is bound by
+    // writing the result, mostly zeros, and a tile of neighbouring pixels writes whole cache lines.
+    const int tap_classes = (a.R < a.stride_h ? a.R : a.stride_h) * (a.S < a.stride_w ? a.S : a.stride_w);
+    g.cls = a.dgrad && (a.stride_h > 1 || a.stride_w > 1) && tap_classes > 1;
+    g.cls_h = g.cls ? a.stride_h : 1;
+    g.cls_w = g.cls ? a.stride_w : 1;
+    if (g.cls) {
+        g.ncls = g.cls_h * g.cls_w;
+        g.ncols = (long long)a.N * ((a.OH + g.cls_h - 1) / g.cls_h) * ((a.OW + g.cls_w - 1) / g.cls_w);
+        g.gran = (long long)((a.R + g.cls_h - 1) / g.cls_h) * ((a.S + g.cls_w - 1) / g.cls_w) * (a.Ca >> 4);
+    } else {
+        g.ncls = 1;
+        g.ncols = (long long)a.N * a.OH * a.OW;
+        g.gran = (long long)a.R * a.S * (a.Ca >> 4);
+    }
+    return g;
+}
+// long reduction and enough wide tiles to cover the chip
+bool igemm_wide(const IgemmArgs& a) {
+    const IgemmShape g = igemm_shape(a);
+    return a.rows > 64 && g.gran >= 32 && g.ncls * ((g.ncols + 255) / 256) * ((a.rows + 127) / 128) >= 256;
+}
+}  // namespace
+
+template <bool DGRAD, int WM, int KG, int NSTAGE, bool CLS>
+static hipError_t launch_igemm_dma(const IgemmArgs& a, const IgemmShape& g, hipStream_t st, const KernelTimer& kt) {
     const size_t lds = (size_t)NSTAGE * (64 * WM + IGD_BN) * KG * 16;
     static std::atomic<unsigned long long> attr_done;
     {
-        hipError_t e = raise_dynamic_lds(reinterpret_cast<const void*>(igemm_dma_kernel<DGRAD, WM, KG, NSTAGE>), (int)lds, attr_done);
+        hipError_t e = raise_dynamic_lds(reinterpret_cast<const void*>(igemm_dma_kernel<DGRAD, WM, KG, NSTAGE, CLS>), (int)lds, attr_done);
         if (e != hipSuccess) return e;
     }
-    const unsigned ctiles = (unsigned)((ncols + IGD_BN - 1) / IGD_BN), rtiles = (unsigned)((a.rows + 64 * WM - 1) / (64 * WM));
-    dim3 grid(((ctiles + 7) / 8) * 8 * rtiles);
-    launch_timed(kt, (igemm_dma_kernel<DGRAD, WM, KG, NSTAGE>), grid, dim3(128 * WM), lds, st, a);
+    const unsigned ctiles = (unsigned)((g.ncols + IGD_BN - 1) / IGD_BN), rtiles = (unsigned)((a.rows + 64 * WM - 1) / (64 * WM));
+    dim3 grid(((ctiles + 7) / 8) * 8 * rtiles * (unsigned)g.ncls);
+    launch_timed(kt, (igemm_dma_kernel<DGRAD, WM, KG, NSTAGE, CLS>), grid, dim3(128 * WM), lds, st, a);
     return hipGetLastError();
 }
-
-namespace {
-// long reduction and enough wide tiles to cover the chip
-bool igemm_wide(const IgemmArgs& a) {
-    const long long ncols = (long long)a.N * a.OH * a.OW;
-    const long long gran = (long long)a.R * a.S * (a.Ca >> 4);
-    return a.rows > 64 && gran >= 32 && ((ncols + 255) / 256) * ((a.rows + 127) / 128) >= 256;
+template <int WM, int KG, int NSTAGE>
+static hipError_t launch_igemm_dma_any(const IgemmArgs& a, const IgemmShape& g, hipStream_t st, const KernelTimer& kt) {
+    if (!a.dgrad) return launch_igemm_dma<false, WM, KG, NSTAGE, false>(a, g, st, kt);
+    if (g.cls) return launch_igemm_dma<true, WM, KG, NSTAGE, true>(a, g, st, kt);
+    return launch_igemm_dma<true, WM, KG, NSTAGE, false>(a, g, st, kt);
 }
-}  // namespace
+template <int BM, int BN>
+static void launch_igemm_generic(const IgemmArgs& a, const IgemmShape& g, int ksplit, hipStream_t st, const KernelTimer& kt) {
+    dim3 grid((unsigned)((g.ncols + BN - 1) / BN) * (unsigned)g.ncls, (unsigned)((a.rows + BM - 1) / BM), (unsigned)ksplit);
+    if (!a.dgrad) launch_timed(kt, (igemm_kernel<BM, BN, false, false>), grid, dim3(256), 0, st, a);
+    else if (g.cls) launch_timed(kt, (igemm_kernel<BM, BN, true, true>), grid, dim3(256), 0, st, a);
+    else launch_timed(kt, (igemm_kernel<BM, BN, true, false>), grid, dim3(256), 0, st, a);
+}
 
 // Layers with few output tiles and a long reduction (a strided 3x3 on a small image, a fully
 // connected layer) leave most compute units idle: their reduction is split over up to
 // ceil(512 / tiles) blocks per tile, at least 4 stages each.  1 = no split.
 int igemm_ksplit(const IgemmArgs& a) {
     if (a.rows <= 64 || igemm_wide(a)) return 1;
-    const long long ncols = (long long)a.N * a.OH * a.OW;
-    const long long tiles = ((ncols + 127) / 128) * ((a.rows + 127) / 128);
-    const long long nsteps = ((long long)a.R * a.S * (a.Ca >> 4) + 3) / 4;
+    const IgemmShape g = igemm_shape(a);
+    const long long tiles = g.ncls * ((g.ncols + 127) / 128) * ((a.rows + 127) / 128);
+    const long long nsteps = (g.gran + 3) / 4;
     if (tiles >= 192 || nsteps < 8) return 1;
     long long ks = (512 + tiles - 1) / tiles;
     if (ks > nsteps / 4) ks = nsteps / 4;
@@ -518,6 +634,9 @@ hipError_t launch_igemm(const IgemmArgs& a_in, hipStream_t st) {
     hipError_t berr = hipSuccess;
     if (launch_band(a_in, st, &berr)) return berr;   // small filter bank: LDS-resident kernel
     IgemmArgs a = a_in;
+    const IgemmShape g = igemm_shape(a);
+    a.cls_h = g.cls_h;
+    a.cls_w = g.cls_w;
     const int ncols = a.N * a.OH * a.OW;
     // the split needs its scratch; without it the reduction simply stays whole
     a.ksplit = igemm_ksplit(a);
@@ -525,9 +644,7 @@ hipError_t launch_igemm(const IgemmArgs& a_in, hipStream_t st) {
     if (a.ksplit > 1) {
         {
             KernelTimer kt(KID_IGEMM, st);
-            dim3 grid((ncols + 127) / 128, (a.rows + 127) / 128, a.ksplit);
-            if (a.dgrad) launch_timed(kt, (igemm_kernel<128, 128, true>), grid, dim3(256), 0, st, a);
-            else launch_timed(kt, (igemm_kernel<128, 128, false>), grid, dim3(256), 0, st, a);
+            launch_igemm_generic<128, 128>(a, g, a.ksplit, st, kt);
         }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -540,18 +657,15 @@ hipError_t launch_igemm(const IgemmArgs& a_in, hipStream_t st) {
     }
     KernelTimer kt(KID_IGEMM, st);
     if (a.rows <= 64) {
-        dim3 grid((ncols + 127) / 128, 1);
-        if (a.dgrad) launch_timed(kt, (igemm_kernel<64, 128, true>), grid, dim3(256), 0, st, a);
-        else launch_timed(kt, (igemm_kernel<64, 128, false>), grid, dim3(256), 0, st, a);
+        launch_igemm_generic<64, 128>(a, g, 1, st, kt);
     } else if (igemm_wide(a)) {
-        const long long t256 = (long long)((ncols + 255) / 256) * ((a.rows + 255) / 256);
-        if (t256 >= 192)
-            return a.dgrad ? launch_igemm_dma<true, 4, 8, 2>(a, ncols, st, kt) : launch_igemm_dma<false, 4, 8, 2>(a, ncols, st, kt);
-        return a.dgrad ? launch_igemm_dma<true, 2, 4, 3>(a, ncols, st, kt) : launch_igemm_dma<false, 2, 4, 3>(a, ncols, st, kt);
+        // 256-row tiles only where they are full (half-empty ones cost the short reductions of a
+        // residue class a quarter of their time)
+        const long long t256 = g.ncls * ((g.ncols + 255) / 256) * ((a.rows + 255) / 256);
+        if (t256 >= 192 && a.rows > 128) return launch_igemm_dma_any<4, 8, 2>(a, g, st, kt);
+        return launch_igemm_dma_any<2, 4, 3>(a, g, st, kt);
     } else {
-        dim3 grid((ncols + 127) / 128, (a.rows + 127) / 128);
-        if (a.dgrad) launch_timed(kt, (igemm_kernel<128, 128, true>), grid, dim3(256), 0, st, a);
-        else launch_timed(kt, (igemm_kernel<128, 128, false>), grid, dim3(256), 0, st, a);
+        launch_igemm_generic<128, 128>(a, g, 1, st, kt);
     }
     return hipGetLastError();
 }

@@ -116,6 +116,7 @@ struct IgemmArgs {
     int IH, IW, OH, OW, R, S;
     int stride_h, stride_w, pad_h, pad_w;
     int dgrad;                   // 0: ih = oh*stride + r - pad;  1: ih = (oh + pad - r)/stride
+    int cls_h, cls_w;            // filled by launch_igemm(): strides of the residue classes a strided backward-data pass splits its pixels into (1 = not split)
     int32_t* partial;            // nullable scratch [ksplit][N][rows][OH*OW] of a split reduction
     size_t partial_bytes;
     int ksplit;                  // filled by launch_igemm(): blocks per output tile along the reduction

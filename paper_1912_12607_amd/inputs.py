@@ -82,7 +82,34 @@ CONFIGS: Dict[int, List[Layer]] = {
     # beyond the benchmark's list: a fully connected layer (the paper replaces conv AND fc layers,
     # Sec.4 setup) is the 1x1 convolution of a 1x1 image; ResNet-50's classifier at batch 256
     5: [Layer("r50_fc", 256, 2048, 1, 1, 1000, 1, 1)],
+    # ... and ResNet-50's strided layers (Fig.10 times every convolution of that network): the 7x7
+    # stem on 3 channels, the 3x3 and the 1x1 shortcut that halve the image
+    6: [Layer("r50_stem", 16, 3, 224, 224, 64, 7, 7, stride=(2, 2), pad=(3, 3), x_dist="normal", dy_scale=1e-4),
+        Layer("r50_3x3_s2", 64, 128, 56, 56, 128, 3, 3, stride=(2, 2), pad=(1, 1), x_dist="relu", dy_scale=1e-4),
+        Layer("r50_shortcut_s2", 32, 256, 56, 56, 512, 1, 1, stride=(2, 2), x_dist="relu", dy_scale=1e-4)],
 }
+
+
+def resnet50_layers(N: int = 64):
+    """[(how often the shape occurs, Layer)] for every convolution of ResNet-50 on 224 x 224 images
+    (stride on the 3x3 of a bottleneck) and its classifier: the per-layer workload of Fig.10."""
+    def L(name, C, H, K, R, s=1):
+        return Layer(name, N, C, H, H, K, R, R, stride=(s, s), pad=(R // 2, R // 2), x_dist="relu", dy_scale=1e-4)
+    out = [(1, L("stem_7x7_s2", 3, 224, 64, 7, 2))]
+    H, Cin = 56, 64
+    for stage, (width, blocks) in enumerate(((64, 3), (128, 4), (256, 6), (512, 3))):
+        s = 1 if stage == 0 else 2
+        tag = f"s{stage + 1}"
+        # first block: reduces from the previous stage's width, strided 3x3, projection shortcut
+        out += [(1, L(f"{tag}_1x1_in", Cin, H, width, 1)), (1, L(f"{tag}_3x3_first", width, H, width, 3, s)),
+                (1, L(f"{tag}_shortcut", Cin, H, 4 * width, 1, s))]
+        H //= s
+        out += [(blocks, L(f"{tag}_1x1_expand", width, H, 4 * width, 1)),
+                (blocks - 1, L(f"{tag}_1x1_reduce", 4 * width, H, width, 1)),
+                (blocks - 1, L(f"{tag}_3x3", width, H, width, 3))]
+        Cin = 4 * width
+    out.append((1, Layer("fc", N, 2048, 1, 1, 1000, 1, 1, x_dist="relu", dy_scale=1e-4)))
+    return out
 
 # Default clip candidates of the search: ratio_j = 2^(-j/4), j = 0..31 (j = 0 is "no clipping").
 def default_ratios(n_cand: int = 32) -> np.ndarray:

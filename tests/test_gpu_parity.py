@@ -376,7 +376,8 @@ def test_config0_full_step_elementwise():
     assert phi == oracle.dclr(st.dev_final.item())
 
 
-FULL_LAYERS = [(1, 0), (2, 0), (2, 1), (2, 2), (3, 0), (3, 1), (3, 2), (4, 0), (4, 1), (4, 2), (5, 0)]
+FULL_LAYERS = [(1, 0), (2, 0), (2, 1), (2, 2), (3, 0), (3, 1), (3, 2), (4, 0), (4, 1), (4, 2), (5, 0),
+               (6, 0), (6, 1), (6, 2)]
 
 
 @pytest.mark.parametrize("cfg,li", FULL_LAYERS)
