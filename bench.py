@@ -60,6 +60,7 @@ def algorithmic(L, n_cand):
         "igemm_reduce_kernel": dict(bytes=4 * (n_x + n_y), ops=0),               # final sum of a split reduction
         "wgrad_kernel": wg, "dw_wgrad_kernel": wg,
         "wgrad_reduce_kernel": dict(bytes=4 * n_w, ops=0), "dw_wgrad_reduce_kernel": dict(bytes=4 * n_w, ops=0),
+        "s2d_repack_kernel": dict(bytes=2 * n_x, ops=0),                          # codes of a in, rearranged codes out
     }
 
 

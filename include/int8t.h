@@ -242,7 +242,7 @@ int8t_status int8t_conv_bwd_weight(const int8t_conv_desc *desc,
  *   kernel   host string: the kernel's name ("dsgc_sweep_kernel", "absmax_kernel",
  *            "absmax_batch_kernel", "quantize_batch_kernel", "quantize_act_kernel", "quantize_planar_kernel", "quantize_wgt_kernel",
  *            "deviation_finish_kernel", "igemm_kernel", "igemm_reduce_kernel", "band_kernel",
- *            "wgrad_kernel", "wgrad_reduce_kernel", "dw_conv_kernel", "dw_wgrad_kernel",
+ *            "wgrad_kernel", "wgrad_reduce_kernel", "s2d_repack_kernel", "dw_conv_kernel", "dw_wgrad_kernel",
  *            "dw_wgrad_reduce_kernel"); NULL or "" selects every kernel.
  *            An unknown name returns INT8T_ERR_ARG and leaves timing off.
  * int8t_profile_stop waits for the recorded events, writes one entry per kernel that was

@@ -147,8 +147,9 @@ size_t int8t_workspace_bytes(int8t_op op, const int8t_conv_desc* desc, size_t n,
                 return align256((size_t)dw_wgrad_chunks(desc->N, desc->C) * desc->C * desc->R * desc->S * 4);
             WgradArgs a{};
             fill_wgrad_geometry(&a, desc, g);
+            const size_t s2d_bytes = wgrad_s2d(&a);
             wgrad_plan(&a);
-            return align256((size_t)a.splits * desc->K * desc->R * desc->S * pad16(desc->C) * 4);
+            return align256((size_t)a.splits * a.K * a.R * a.S * a.Cp * 4) + align256(s2d_bytes);
         }
     }
     return 0;
@@ -414,9 +415,11 @@ int8t_status int8t_conv_bwd_weight(const int8t_conv_desc* desc, const int8_t* xq
     }
     WgradArgs a{};
     fill_wgrad_geometry(&a, desc, g);
+    wgrad_s2d(&a);
     wgrad_plan(&a);
     a.x = xq_dev; a.dy = dyq_dev; a.sa = sx_dev; a.sb = sdy_dev; a.dw = dw_dev; a.acc = acc_dev;
     a.partial = (int32_t*)ws_dev;
+    a.xs = (int8_t*)ws_dev + align256((size_t)a.splits * a.K * a.R * a.S * a.Cp * 4);
     return launch_wgrad(a, st) == hipSuccess ? INT8T_OK : INT8T_ERR_RUNTIME;
 }
 

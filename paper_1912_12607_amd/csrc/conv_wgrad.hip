@@ -361,9 +361,67 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const WgradArgs a) {
     const int col = (int)(t - (size_t)k * ncolsp);
     const int rs = col / a.Cp, c = col - rs * a.Cp;
     if (c >= a.C) return;
-    const size_t o = ((size_t)k * a.C + c) * (a.R * a.S) + rs;
+    size_t o = ((size_t)k * a.C + c) * (a.R * a.S) + rs;
+    if (a.s2d) {
+        // back from the space-to-depth form: channel (2 dy + dx) * oC + c0 of tap (r', s') is channel c0
+        // of tap (2 r' + dy - eh, 2 s' + dx - ew); taps outside the layer's own filter are dropped
+        const int blk = c / a.oC, c0 = c - blk * a.oC;
+        const int rr = rs / a.S;
+        const int r = 2 * rr + (blk >> 1) - a.eh, s = 2 * (rs - rr * a.S) + (blk & 1) - a.ew;
+        if (r < 0 || r >= a.oR || s < 0 || s >= a.oS) return;
+        o = (((size_t)k * a.oC + c0) * a.oR + r) * a.oS + s;
+    }
     a.dw[o] = __fmul_rn((float)sum, __fmul_rn(a.sa[0], a.sb[0]));
     if (a.acc) a.acc[o] = sum;
+}
+
+// Input codes [N][2 H2][2 W2][16] (C <= 4 channels in use) -> space-to-depth codes [N][H2][W2][16]:
+// byte (2 dy + dx) * C + c of pixel (h', w') is channel c of pixel (2 h' + dy, 2 w' + dx), the rest 0.
+// One thread per output pixel; it reads the first four bytes of four input pixels.
+__global__ __launch_bounds__(256) void s2d_repack_kernel(const int8_t* __restrict__ x, int8_t* __restrict__ xs,
+                                                         int N, int H2, int W2, int C) {
+    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= (size_t)N * H2 * W2) return;
+    const int w2 = (int)(t % W2);
+    const size_t nh = t / W2;                 // n * H2 + h'
+    const uint32_t* __restrict__ row0 = reinterpret_cast<const uint32_t*>(x) + ((2 * nh) * (size_t)(2 * W2) + 2 * w2) * 4;
+    const uint32_t* __restrict__ row1 = row0 + (size_t)(2 * W2) * 4;
+    const uint32_t px[4] = {row0[0], row0[4], row1[0], row1[4]};
+    const uint32_t keep = C >= 4 ? 0xffffffffu : ((1u << (8 * C)) - 1u);
+    // 4 C bytes, packed: a 128-bit shift register built from 32-bit pieces
+    unsigned long long lo = 0, hi = 0;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        const unsigned long long v = px[b] & keep;
+        const int sh = 8 * C * b;             // 0 .. 96
+        if (sh < 64) {
+            lo |= v << sh;
+            if (sh > 32) hi |= v >> (64 - sh);
+        } else {
+            hi |= v << (sh - 64);
+        }
+    }
+    reinterpret_cast<uint4*>(xs)[t] = make_uint4((uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32));
+}
+
+size_t wgrad_s2d(WgradArgs* a) {
+    a->s2d = 0;
+    if (a->stride_h != 2 || a->stride_w != 2 || a->C > 4 || (a->H & 1) || (a->W & 1)) return 0;
+    a->s2d = 1;
+    a->oC = a->C; a->oR = a->R; a->oS = a->S;
+    const int ph = (a->pad_h + 1) / 2, pw = (a->pad_w + 1) / 2;
+    a->eh = 2 * ph - a->pad_h;
+    a->ew = 2 * pw - a->pad_w;
+    a->C = 4 * a->oC;
+    a->Cp = 16;
+    a->H /= 2;
+    a->W /= 2;
+    a->R = (a->oR + a->eh + 1) / 2;
+    a->S = (a->oS + a->ew + 1) / 2;
+    a->pad_h = ph;
+    a->pad_w = pw;
+    a->stride_h = a->stride_w = 1;        // P and Q stay: the rewritten layer has the same output pixels
+    return (size_t)a->N * a->H * a->W * 16;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -488,7 +546,19 @@ void wgrad_plan_uncached(WgradArgs* a) {
 }
 }  // namespace
 
-hipError_t launch_wgrad(const WgradArgs& a, hipStream_t st) {
+hipError_t launch_wgrad(const WgradArgs& a_in, hipStream_t st) {
+    WgradArgs a = a_in;
+    if (a.s2d) {
+        const size_t npix = (size_t)a.N * a.H * a.W;
+        {
+            KernelTimer kt(KID_S2D_REPACK, st);
+            launch_timed(kt, s2d_repack_kernel, dim3((unsigned)((npix + 255) / 256)), dim3(256), 0, st,
+                         a.x, a.xs, a.N, a.H, a.W, a.oC);
+        }
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        a.x = a.xs;
+    }
     const unsigned out_tiles = (unsigned)(a.ktiles * a.ctiles * a.tapgroups);
     dim3 grid(wgrad_xcd_mapping(a.splits) ? out_tiles * 8u * (unsigned)((a.splits + 7) / 8) : out_tiles * (unsigned)a.splits);
     // the staged tiles may exceed the default 64 KB of dynamic LDS: raise the limit once per variant

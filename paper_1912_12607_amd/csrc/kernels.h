@@ -144,8 +144,19 @@ struct WgradArgs {
     int ktiles, ctiles, tapgroups;
     int xt_slots;                // 16-byte granules of the staged input window
     size_t lds_bytes;
+    // filled by wgrad_s2d() when it rewrites the geometry above into the space-to-depth form:
+    int s2d;                     // 1: C, Cp, H, W, R, S, strides and pads describe the rewritten problem
+    int oC, oR, oS, eh, ew;      // the layer's own channels and filter; tap r = 2 r' + dy - eh, s = 2 s' + dx - ew
+    int8_t* xs;                  // scratch: the input codes in space-to-depth form, [N][H][W][16]
 };
-void wgrad_plan(WgradArgs* a);   // needs the geometry fields above the comment
+// A stride-2 layer with at most 4 input channels (the stem of an image network) as the stride-1
+// layer on the space-to-depth image: pixel (h', w') holds the 2 x 2 block of pixels (2h' + dy,
+// 2w' + dx) as channel (2 dy + dx) * C + c, and the R x S filter becomes a ceil((R+eh)/2) x
+// ceil((S+ew)/2) one.  The 16-byte pixel granule then carries 4 C channels instead of C, and the
+// taps shrink fourfold.  Returns the bytes of the rewritten input codes (0: does not apply, the
+// geometry is left alone).  Call before wgrad_plan().
+size_t wgrad_s2d(WgradArgs* a);
+void wgrad_plan(WgradArgs* a);   // needs the geometry fields above the first comment
 hipError_t launch_wgrad(const WgradArgs& a, hipStream_t st);
 
 // ---- conv_dw.hip (depthwise, planar codes) ----------------------------------------------------

@@ -26,6 +26,7 @@ enum KernelId : int {
     KID_BAND,
     KID_WGRAD,
     KID_WGRAD_REDUCE,
+    KID_S2D_REPACK,
     KID_DW_CONV,
     KID_DW_WGRAD,
     KID_DW_WGRAD_REDUCE,

@@ -250,6 +250,14 @@ CONV_SHAPES = [
     (2, 40, 9, 10, 72, 3, 3, (2, 2), (1, 1), 1),
     (1, 16, 13, 11, 24, 5, 3, (3, 2), (2, 1), 1),
     (1, 16, 7, 7, 16, 2, 2, (3, 3), (0, 0), 1),        # stride larger than the filter: pixels no tap reaches
+    # stride 2 with at most 4 input channels: backward-weight runs on the space-to-depth image
+    (2, 3, 12, 10, 8, 7, 7, (2, 2), (3, 3), 1),
+    (17, 3, 16, 16, 70, 7, 7, (2, 2), (3, 3), 1),      # more than one image group and filter tile
+    (1, 4, 8, 8, 5, 3, 3, (2, 2), (1, 1), 1),
+    (2, 2, 6, 8, 4, 2, 2, (2, 2), (0, 0), 1),
+    (1, 1, 10, 12, 3, 5, 3, (2, 2), (2, 0), 1),
+    (3, 3, 8, 8, 6, 4, 6, (2, 2), (1, 2), 1),          # even filter, even and odd padding
+    (2, 3, 9, 8, 6, 3, 3, (2, 2), (1, 1), 1),          # odd image height: not rewritten
 ]
 
 
