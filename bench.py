@@ -61,6 +61,7 @@ def algorithmic(L, n_cand):
         "wgrad_kernel": wg, "dw_wgrad_kernel": wg,
         "wgrad_reduce_kernel": dict(bytes=4 * n_w, ops=0), "dw_wgrad_reduce_kernel": dict(bytes=4 * n_w, ops=0),
         "s2d_repack_kernel": dict(bytes=2 * n_x, ops=0),                          # codes of a in, rearranged codes out
+        "s2d_weights_kernel": dict(bytes=2 * n_w, ops=0),
     }
 
 
@@ -239,7 +240,9 @@ def main():
     if args.resnet50 > 0:
         total_ms, total_macs = 0.0, 0
         for i, (count, Lx) in enumerate(inputs.resnet50_layers(args.resnet50)):
-            st = LayerStep(Lx, n_cand=n_cand, keep_acc=False, requantize_deviation=False)
+            # the first layer's input is the image: no backward-data pass there (4 of the 6 MAC passes counted)
+            st = LayerStep(Lx, n_cand=n_cand, keep_acc=False, requantize_deviation=False, input_grad=i > 0)
+            passes = 6 if i > 0 else 4
             st.upload(inputs.make_x(Lx, 50, i), inputs.make_w(Lx, 50, i), inputs.make_dy(Lx, 50, i), ratios)
             nst = max(20, args.steps // 10)
             for k in range(10):
@@ -251,10 +254,10 @@ def main():
             torch.cuda.synchronize()
             ts = (time.perf_counter() - t0) / nst
             total_ms += count * ts * 1e3
-            total_macs += count * Lx.macs
+            total_macs += count * Lx.macs * passes // 6
             print(json.dumps({"layer": Lx.name, "count": count, "C": Lx.C, "HW": Lx.H, "K": Lx.K, "RS": Lx.R,
                               "stride": Lx.stride[0], "ms_per_step": round(ts * 1e3, 4),
-                              "TOPS": round(6 * Lx.macs / ts / 1e12, 1)}), file=sys.stderr, flush=True)
+                              "TOPS": round(passes * Lx.macs / ts / 1e12, 1)}), file=sys.stderr, flush=True)
             del st
         print(json.dumps({"network": "ResNet-50 convolutions + classifier", "batch": args.resnet50,
                           "ms_per_iteration": round(total_ms, 3), "TOPS": round(6 * total_macs / total_ms / 1e9, 1),

@@ -110,8 +110,12 @@ size_t int8t_code_bytes(const int dims[4], int8t_kind kind);
  * descriptor is invalid; the call itself then reports the error.
  * CONV_BWD_WEIGHT and DSGC require their scratch.  CONV_FWD / CONV_BWD_DATA only use it as a
  * performance aid (layers with few output tiles and a long reduction split the reduction over
- * several workgroups and keep int32 partial sums there; integer sums, so the result is the same
- * bit for bit): ws_dev may be NULL or smaller, the call then runs without the split. */
+ * several workgroups and keep int32 partial sums there; the forward pass of a stride-2 layer with
+ * at most 4 input channels -- the stem of an image network -- runs on a space-to-depth copy of its
+ * codes kept there, four times the channels per 16-byte pixel and a quarter of the taps; integer
+ * sums of the same products either way, so the result is the same bit for bit): ws_dev may be NULL
+ * or smaller, the call then runs without them.  CONV_BWD_WEIGHT of such a layer holds the same
+ * copy of the input codes in its (required) scratch. */
 size_t int8t_workspace_bytes(int8t_op op, const int8t_conv_desc *desc, size_t n, int n_cand);
 
 /* Scratch of int8t_quantize for a tensor of logical dims and code layout `kind`; covers both the
@@ -242,7 +246,7 @@ int8t_status int8t_conv_bwd_weight(const int8t_conv_desc *desc,
  *   kernel   host string: the kernel's name ("dsgc_sweep_kernel", "absmax_kernel",
  *            "absmax_batch_kernel", "quantize_batch_kernel", "quantize_act_kernel", "quantize_planar_kernel", "quantize_wgt_kernel",
  *            "deviation_finish_kernel", "igemm_kernel", "igemm_reduce_kernel", "band_kernel",
- *            "wgrad_kernel", "wgrad_reduce_kernel", "s2d_repack_kernel", "dw_conv_kernel", "dw_wgrad_kernel",
+ *            "wgrad_kernel", "wgrad_reduce_kernel", "s2d_repack_kernel", "s2d_weights_kernel", "dw_conv_kernel", "dw_wgrad_kernel",
  *            "dw_wgrad_reduce_kernel"); NULL or "" selects every kernel.
  *            An unknown name returns INT8T_ERR_ARG and leaves timing off.
  * int8t_profile_stop waits for the recorded events, writes one entry per kernel that was

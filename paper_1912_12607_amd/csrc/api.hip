@@ -86,6 +86,7 @@ void fill_igemm_fwd(IgemmArgs* a, const int8t_conv_desc* d, const Geo& g) {
     a->IH = d->H; a->IW = d->W; a->OH = g.P; a->OW = g.Q; a->R = d->R; a->S = d->S;
     a->stride_h = d->stride_h; a->stride_w = d->stride_w; a->pad_h = d->pad_h; a->pad_w = d->pad_w;
     a->dgrad = 0;
+    a->C = d->C;
 }
 void fill_igemm_bwd_data(IgemmArgs* a, const int8t_conv_desc* d, const Geo& g) {
     a->N = d->N; a->rows = d->C; a->Ca = pad16(d->K);
@@ -134,11 +135,13 @@ size_t int8t_workspace_bytes(int8t_op op, const int8t_conv_desc* desc, size_t n,
             // optional: partial sums of a split reduction (layers with few output tiles)
             Geo g;
             if (desc_ok(desc, &g) != INT8T_OK || g.depthwise) return 0;
+            // ... and, in the forward pass of a stride-2 layer with at most 4 channels, its rewritten codes
             IgemmArgs a{};
             if (op == INT8T_OP_CONV_FWD) fill_igemm_fwd(&a, desc, g);
             else fill_igemm_bwd_data(&a, desc, g);
+            const size_t s2d_bytes = igemm_s2d(&a);
             const int ks = igemm_ksplit(a);
-            return ks > 1 ? align256((size_t)ks * a.N * a.rows * a.OH * a.OW * 4) : 0;
+            return s2d_bytes + (ks > 1 ? align256((size_t)ks * a.N * a.rows * a.OH * a.OW * 4) : 0);
         }
         case INT8T_OP_CONV_BWD_WEIGHT: {
             Geo g;
@@ -362,6 +365,16 @@ int8t_status int8t_conv_fwd(const int8t_conv_desc* desc, const int8_t* xq_dev, c
     fill_igemm_fwd(&a, desc, g);
     a.act = xq_dev; a.wgt = wq_dev; a.sa = sx_dev; a.sb = sw_dev; a.out = y_dev; a.acc = acc_dev;
     a.partial = (int32_t*)ws_dev; a.partial_bytes = ws_dev ? ws_bytes : 0;
+    {
+        // the rewritten codes of a layer s2d.hip covers come first in the scratch; without it the layer runs as it is
+        IgemmArgs t = a;
+        const size_t s2d_bytes = igemm_s2d(&t);
+        if (s2d_bytes && a.partial_bytes >= s2d_bytes) {
+            a.s2d = (int8_t*)ws_dev;
+            a.partial = (int32_t*)((int8_t*)ws_dev + s2d_bytes);
+            a.partial_bytes -= s2d_bytes;
+        }
+    }
     return launch_igemm(a, st) == hipSuccess ? INT8T_OK : INT8T_ERR_RUNTIME;
 }
 

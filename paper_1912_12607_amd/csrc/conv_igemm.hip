@@ -630,10 +630,41 @@ int igemm_ksplit(const IgemmArgs& a) {
     return ks < 2 ? 1 : (int)ks;
 }
 
+size_t igemm_s2d(IgemmArgs* a) {
+    if (a->dgrad || a->C < 1 || a->Ca != 16 || !s2d_applies(a->C, a->IH, a->IW, a->stride_h, a->stride_w)) return 0;
+    const S2dGeo g = s2d_geometry(a->R, a->S, a->pad_h, a->pad_w);
+    a->C *= 4;
+    a->IH /= 2;
+    a->IW /= 2;
+    a->R = g.R2;
+    a->S = g.S2;
+    a->pad_h = g.ph;
+    a->pad_w = g.pw;
+    a->stride_h = a->stride_w = 1;        // OH and OW stay: the rewritten layer has the same output pixels
+    const size_t a256 = 255;
+    return (((size_t)a->N * a->IH * a->IW * 16 + a256) & ~a256) + (((size_t)a->rows * g.R2 * g.S2 * 16 + a256) & ~a256);
+}
+
 hipError_t launch_igemm(const IgemmArgs& a_in, hipStream_t st) {
-    hipError_t berr = hipSuccess;
-    if (launch_band(a_in, st, &berr)) return berr;   // small filter bank: LDS-resident kernel
     IgemmArgs a = a_in;
+    if (a.s2d) {
+        // forward pass of a stride-2 layer with at most 4 channels: rewrite codes and geometry (s2d.hip)
+        IgemmArgs t = a;
+        if (igemm_s2d(&t)) {
+            const S2dGeo g = s2d_geometry(a.R, a.S, a.pad_h, a.pad_w);
+            int8_t* const xs = a.s2d;
+            int8_t* const ws = a.s2d + (((size_t)t.N * t.IH * t.IW * 16 + 255) & ~(size_t)255);
+            hipError_t e = launch_s2d_repack(a.act, xs, a.N, t.IH, t.IW, a.C, st);
+            if (e != hipSuccess) return e;
+            e = launch_s2d_weights(a.wgt, ws, a.rows, a.R, a.S, a.C, g, st);
+            if (e != hipSuccess) return e;
+            t.act = xs;
+            t.wgt = ws;
+            a = t;
+        }
+    }
+    hipError_t berr = hipSuccess;
+    if (launch_band(a, st, &berr)) return berr;   // small filter bank: LDS-resident kernel
     const IgemmShape g = igemm_shape(a);
     a.cls_h = g.cls_h;
     a.cls_w = g.cls_w;

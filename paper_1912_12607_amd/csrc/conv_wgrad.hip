@@ -375,51 +375,22 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const WgradArgs a) {
     if (a.acc) a.acc[o] = sum;
 }
 
-// Input codes [N][2 H2][2 W2][16] (C <= 4 channels in use) -> space-to-depth codes [N][H2][W2][16]:
-// byte (2 dy + dx) * C + c of pixel (h', w') is channel c of pixel (2 h' + dy, 2 w' + dx), the rest 0.
-// One thread per output pixel; it reads the first four bytes of four input pixels.
-__global__ __launch_bounds__(256) void s2d_repack_kernel(const int8_t* __restrict__ x, int8_t* __restrict__ xs,
-                                                         int N, int H2, int W2, int C) {
-    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (t >= (size_t)N * H2 * W2) return;
-    const int w2 = (int)(t % W2);
-    const size_t nh = t / W2;                 // n * H2 + h'
-    const uint32_t* __restrict__ row0 = reinterpret_cast<const uint32_t*>(x) + ((2 * nh) * (size_t)(2 * W2) + 2 * w2) * 4;
-    const uint32_t* __restrict__ row1 = row0 + (size_t)(2 * W2) * 4;
-    const uint32_t px[4] = {row0[0], row0[4], row1[0], row1[4]};
-    const uint32_t keep = C >= 4 ? 0xffffffffu : ((1u << (8 * C)) - 1u);
-    // 4 C bytes, packed: a 128-bit shift register built from 32-bit pieces
-    unsigned long long lo = 0, hi = 0;
-#pragma unroll
-    for (int b = 0; b < 4; ++b) {
-        const unsigned long long v = px[b] & keep;
-        const int sh = 8 * C * b;             // 0 .. 96
-        if (sh < 64) {
-            lo |= v << sh;
-            if (sh > 32) hi |= v >> (64 - sh);
-        } else {
-            hi |= v << (sh - 64);
-        }
-    }
-    reinterpret_cast<uint4*>(xs)[t] = make_uint4((uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32));
-}
-
 size_t wgrad_s2d(WgradArgs* a) {
     a->s2d = 0;
-    if (a->stride_h != 2 || a->stride_w != 2 || a->C > 4 || (a->H & 1) || (a->W & 1)) return 0;
+    if (!s2d_applies(a->C, a->H, a->W, a->stride_h, a->stride_w)) return 0;
+    const S2dGeo g = s2d_geometry(a->R, a->S, a->pad_h, a->pad_w);
     a->s2d = 1;
     a->oC = a->C; a->oR = a->R; a->oS = a->S;
-    const int ph = (a->pad_h + 1) / 2, pw = (a->pad_w + 1) / 2;
-    a->eh = 2 * ph - a->pad_h;
-    a->ew = 2 * pw - a->pad_w;
+    a->eh = g.eh;
+    a->ew = g.ew;
     a->C = 4 * a->oC;
     a->Cp = 16;
     a->H /= 2;
     a->W /= 2;
-    a->R = (a->oR + a->eh + 1) / 2;
-    a->S = (a->oS + a->ew + 1) / 2;
-    a->pad_h = ph;
-    a->pad_w = pw;
+    a->R = g.R2;
+    a->S = g.S2;
+    a->pad_h = g.ph;
+    a->pad_w = g.pw;
     a->stride_h = a->stride_w = 1;        // P and Q stay: the rewritten layer has the same output pixels
     return (size_t)a->N * a->H * a->W * 16;
 }
@@ -549,13 +520,7 @@ void wgrad_plan_uncached(WgradArgs* a) {
 hipError_t launch_wgrad(const WgradArgs& a_in, hipStream_t st) {
     WgradArgs a = a_in;
     if (a.s2d) {
-        const size_t npix = (size_t)a.N * a.H * a.W;
-        {
-            KernelTimer kt(KID_S2D_REPACK, st);
-            launch_timed(kt, s2d_repack_kernel, dim3((unsigned)((npix + 255) / 256)), dim3(256), 0, st,
-                         a.x, a.xs, a.N, a.H, a.W, a.oC);
-        }
-        hipError_t e = hipGetLastError();
+        hipError_t e = launch_s2d_repack(a.x, a.xs, a.N, a.H, a.W, a.oC, st);
         if (e != hipSuccess) return e;
         a.x = a.xs;
     }

@@ -116,15 +116,49 @@ struct IgemmArgs {
     int IH, IW, OH, OW, R, S;
     int stride_h, stride_w, pad_h, pad_w;
     int dgrad;                   // 0: ih = oh*stride + r - pad;  1: ih = (oh + pad - r)/stride
+    int C;                       // forward: channels in use (<= Ca); lets the launch recognise a layer for s2d.hip
+    int8_t* s2d;                 // nullable scratch of igemm_s2d_bytes() bytes for the rewritten codes
     int cls_h, cls_w;            // filled by launch_igemm(): strides of the residue classes a strided backward-data pass splits its pixels into (1 = not split)
     int32_t* partial;            // nullable scratch [ksplit][N][rows][OH*OW] of a split reduction
     size_t partial_bytes;
     int ksplit;                  // filled by launch_igemm(): blocks per output tile along the reduction
 };
 int igemm_ksplit(const IgemmArgs& a);   // split the launch will use when given enough scratch (1 = none)
+// Forward pass of a layer s2d.hip covers: rewrites the geometry and returns the scratch bytes of the
+// rewritten input and filter codes (0: does not apply, the geometry is left alone).
+size_t igemm_s2d(IgemmArgs* a);
 hipError_t launch_igemm(const IgemmArgs& a, hipStream_t st);
 // conv_band.hip: LDS-resident variant for small filter banks; false = shape not covered
 bool launch_band(const IgemmArgs& a, hipStream_t st, hipError_t* err);
+
+// ---- s2d.hip ----------------------------------------------------------------------------------
+// A stride-2 layer with at most 4 input channels (the stem of an image network) as the stride-1
+// layer on the space-to-depth image: pixel (h', w') holds the 2 x 2 block of pixels (2h' + dy,
+// 2w' + dx) as channel (2 dy + dx) * C + c.  Input row 2p + r - pad = 2 (p + r' - ph) + dy with
+// ph = ceil(pad / 2) and r = 2 r' + dy - eh, eh = 2 ph - pad: the R x S filter becomes a
+// ceil((R+eh)/2) x ceil((S+ew)/2) one whose taps outside the original filter are zero.  The 16-byte
+// pixel granule then carries 4 C channels instead of C, and the taps shrink fourfold.  The output
+// pixels stay the same.
+struct S2dGeo {
+    int ph, pw, eh, ew, R2, S2;
+};
+inline bool s2d_applies(int C, int H, int W, int stride_h, int stride_w) {
+    return stride_h == 2 && stride_w == 2 && C <= 4 && !(H & 1) && !(W & 1);
+}
+inline S2dGeo s2d_geometry(int R, int S, int pad_h, int pad_w) {
+    S2dGeo g;
+    g.ph = (pad_h + 1) / 2;
+    g.pw = (pad_w + 1) / 2;
+    g.eh = 2 * g.ph - pad_h;
+    g.ew = 2 * g.pw - pad_w;
+    g.R2 = (R + g.eh + 1) / 2;
+    g.S2 = (S + g.ew + 1) / 2;
+    return g;
+}
+// input codes [N][2 H2][2 W2][16] -> [N][H2][W2][16]
+hipError_t launch_s2d_repack(const int8_t* x, int8_t* xs, int N, int H2, int W2, int C, hipStream_t st);
+// filter codes [K][R][S][16] -> [K][R2][S2][16]
+hipError_t launch_s2d_weights(const int8_t* w, int8_t* ws, int K, int R, int S, int C, const S2dGeo& g, hipStream_t st);
 
 // ---- conv_wgrad.hip (dense backward-weight) ---------------------------------------------------
 struct WgradArgs {
@@ -149,12 +183,8 @@ struct WgradArgs {
     int oC, oR, oS, eh, ew;      // the layer's own channels and filter; tap r = 2 r' + dy - eh, s = 2 s' + dx - ew
     int8_t* xs;                  // scratch: the input codes in space-to-depth form, [N][H][W][16]
 };
-// A stride-2 layer with at most 4 input channels (the stem of an image network) as the stride-1
-// layer on the space-to-depth image: pixel (h', w') holds the 2 x 2 block of pixels (2h' + dy,
-// 2w' + dx) as channel (2 dy + dx) * C + c, and the R x S filter becomes a ceil((R+eh)/2) x
-// ceil((S+ew)/2) one.  The 16-byte pixel granule then carries 4 C channels instead of C, and the
-// taps shrink fourfold.  Returns the bytes of the rewritten input codes (0: does not apply, the
-// geometry is left alone).  Call before wgrad_plan().
+// Rewrites the geometry into the space-to-depth form (s2d.hip) when it applies.  Returns the bytes of
+// the rewritten input codes (0: does not apply, the geometry is left alone).  Call before wgrad_plan().
 size_t wgrad_s2d(WgradArgs* a);
 void wgrad_plan(WgradArgs* a);   // needs the geometry fields above the first comment
 hipError_t launch_wgrad(const WgradArgs& a, hipStream_t st);

@@ -27,6 +27,7 @@ enum KernelId : int {
     KID_WGRAD,
     KID_WGRAD_REDUCE,
     KID_S2D_REPACK,
+    KID_S2D_WEIGHTS,
     KID_DW_CONV,
     KID_DW_WGRAD,
     KID_DW_WGRAD_REDUCE,

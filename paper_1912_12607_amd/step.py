@@ -33,12 +33,15 @@ def two_stream_default(L: Layer) -> bool:
 
 class LayerStep:
     def __init__(self, L: Layer, n_cand: int = 32, keep_acc: bool = False, device: str = "cuda:0",
-                 requantize_deviation: bool = True):
-        """requantize_deviation: also let the quantizer of g_z report Eq.6 for the codes it wrote (into
+                 requantize_deviation: bool = True, input_grad: bool = True):
+        """input_grad=False leaves the backward-data pass out (the first layer of a network: nothing
+        consumes the gradient of the images).
+        requantize_deviation: also let the quantizer of g_z report Eq.6 for the codes it wrote (into
         dev_final).  The clip search has already returned the same d_c (dev_search), which is what Eq.7
         consumes, so a training step can leave this off."""
         self.L, self.n_cand, self.dev = L, n_cand, torch.device(device)
         self.requantize_deviation = requantize_deviation
+        self.input_grad = input_grad
         self.depthwise = L.groups != 1
         self.desc = B.make_desc(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad, L.groups)
         self.act_kind = B.ACT_PLANAR if self.depthwise else B.ACT
@@ -114,6 +117,8 @@ class LayerStep:
         B.int8t_conv_fwd(self.desc, self.xq, self.sx, self.wq, self.sw, self.y, self.y_acc, self.ws_fwd, stream)
 
     def bwd_data(self, stream=None):
+        if not self.input_grad:
+            return
         B.int8t_conv_bwd_data(self.desc, self.dyq, self.sdy, self.wq, self.sw, self.dx, self.dx_acc,
                               self.ws_bwd_data, stream)
 
