@@ -567,8 +567,13 @@ IgemmShape igemm_shape(const IgemmArgs& a) {
     IgemmShape g;
     // Split when more than one class has taps.  With a single one (a 1x1 filter) the pass is bound by
     // writing the result, mostly zeros, and a tile of neighbouring pixels writes whole cache lines.
+    // Nor on small images with a short reduction: a store instruction covers 32 pixels of a class, which
+    // are runs of OW / stride_w strided floats; with runs under 12 pixels the scattered stores cost
+    // more than the zeros do unless a pixel's reduction is long (17 x 17 image, 192 channels: 56 us
+    // split against 51 whole; 14 x 14, 512 channels: 40 against 85).
     const int tap_classes = (a.R < a.stride_h ? a.R : a.stride_h) * (a.S < a.stride_w ? a.S : a.stride_w);
-    g.cls = a.dgrad && (a.stride_h > 1 || a.stride_w > 1) && tap_classes > 1;
+    const bool short_runs = a.OW / a.stride_w < 12 && a.R * a.S * a.Ca < 2048;
+    g.cls = a.dgrad && (a.stride_h > 1 || a.stride_w > 1) && tap_classes > 1 && !short_runs;
     g.cls_h = g.cls ? a.stride_h : 1;
     g.cls_w = g.cls ? a.stride_w : 1;
     if (g.cls) {

@@ -250,6 +250,15 @@ CONV_SHAPES = [
     (2, 40, 9, 10, 72, 3, 3, (2, 2), (1, 1), 1),
     (1, 16, 13, 11, 24, 5, 3, (3, 2), (2, 1), 1),
     (1, 16, 7, 7, 16, 2, 2, (3, 3), (0, 0), 1),        # stride larger than the filter: pixels no tap reaches
+    # strided backward-data split into residue classes of the pixels: rows of at least 24 pixels, or a
+    # reduction of at least 2048 bytes per pixel
+    (1, 16, 9, 26, 24, 3, 3, (2, 2), (1, 1), 1),
+    (2, 70, 7, 37, 8, 5, 3, (3, 2), (2, 1), 1),        # 3 x 2 classes of unequal size, two row tiles
+    (1, 8, 30, 30, 16, 2, 2, (2, 2), (0, 0), 1),       # every class has exactly one tap
+    (1, 12, 5, 50, 20, 3, 5, (1, 2), (1, 2), 1),       # strided along the row only
+    (1, 8, 9, 9, 240, 3, 3, (2, 2), (1, 1), 1),
+    (2, 130, 9, 9, 240, 3, 3, (2, 2), (1, 1), 1),      # ... with the reduction of each class split over blocks
+    (1, 40, 33, 6, 130, 4, 3, (3, 1), (0, 1), 1),      # strided along the column only, stride 3 on a 4-tap filter
     # stride 2 with at most 4 input channels: backward-weight runs on the space-to-depth image
     (2, 3, 12, 10, 8, 7, 7, (2, 2), (3, 3), 1),
     (17, 3, 16, 16, 70, 7, 7, (2, 2), (3, 3), 1),      # more than one image group and filter tile
