@@ -60,8 +60,16 @@ int8t_status desc_ok(const int8t_conv_desc* d, Geo* g) {
 // scratch of int8t_quantize: [absmax partials][deviation partials]
 size_t quant_ws_bytes(int blocks) { return align256(kMaxPartials * sizeof(float)) + align256((size_t)blocks * sizeof(DevPartial)); }
 
+// The pass that writes a tensor's codes.  Channels-last codes of a 1 x 1 image whose channel count
+// needs no padding (the input of a fully connected layer) are the tensor's own element order: the
+// element-wise pass writes them, instead of the transposing one at one pixel per block.
+int8t_kind pass_kind(const int d[4], int8t_kind kind) {
+    if (kind == INT8T_ACT && d[2] * d[3] == 1 && (d[1] & 15) == 0) return INT8T_ACT_PLANAR;
+    return kind;
+}
+
 int quant_blocks(const int d[4], int8t_kind kind) {
-    switch (kind) {
+    switch (pass_kind(d, kind)) {
         case INT8T_ACT: return quant_blocks_act(d[0], pad16(d[1]), d[2] * d[3]);
         case INT8T_WGT: return quant_blocks_wgt(d[0], d[1], d[2], d[3]);
         default: return quant_blocks_planar((size_t)d[0] * d[1] * d[2] * d[3]);
@@ -205,8 +213,9 @@ int8t_status int8t_quantize(const float* x_dev, const int dims[4], int8t_kind ki
     a.scale = scale_dev;
     a.devpart = devpart;
     hipError_t e;
-    if (kind == INT8T_ACT) e = launch_quantize_act(a, st);
-    else if (kind == INT8T_WGT) e = launch_quantize_wgt(a, st);
+    const int8t_kind pk = pass_kind(dims, kind);
+    if (pk == INT8T_ACT) e = launch_quantize_act(a, st);
+    else if (pk == INT8T_WGT) e = launch_quantize_wgt(a, st);
     else e = launch_quantize_planar(a, st);
     if (e != hipSuccess) return INT8T_ERR_RUNTIME;
     if (need_dev && launch_deviation_finish(devpart, blocks, deviation_dev, st) != hipSuccess) return INT8T_ERR_RUNTIME;
@@ -269,7 +278,8 @@ int8t_status int8t_quantize_batch(int count, const int8t_quantize_item* items, v
         QuantBatchItem& q = qb.it[oi];
         q.x = it.x_dev; q.d0 = it.dims[0]; q.d1 = it.dims[1]; q.d2 = it.dims[2]; q.d3 = it.dims[3];
         q.clip = it.clip_dev; q.absmax_part = part; q.nparts = nb; q.q = it.q_dev; q.scale = it.scale_dev;
-        q.kind = it.kind == INT8T_ACT ? 0 : it.kind == INT8T_WGT ? 1 : 2;
+        const int8t_kind pk = pass_kind(it.dims, it.kind);
+        q.kind = pk == INT8T_ACT ? 0 : pk == INT8T_WGT ? 1 : 2;
         quant_grid(q.kind, it.dims, &q.gx, &q.gy, &q.gz);
         q.block0 = (int)qblocks;
         qblocks += (long long)q.gx * q.gy * q.gz;

@@ -408,6 +408,20 @@ hipError_t launch_quantize_planar(const QuantArgs& a, hipStream_t st) {
 constexpr int QW_T = 16;
 constexpr int QW_TAPS = 64;
 static int quant_wgt_zsplit(int K, int Cg, int R, int S);
+// Channel tiles per block.  A filter's share of a block is one contiguous run of 16 * taps floats;
+// with one to three taps that is 64 to 192 bytes, a fraction of what a wave-wide load can fetch, and
+// a fully connected layer's 2 M weights would be 8000 blocks of 256 elements (44 us).  Few-tap
+// filters therefore take 64 or 32 channels per block.
+__host__ __device__ inline int quant_wgt_cm(int Cg, int R, int S) {
+    const int RS = R * S;
+    int cm = RS == 1 ? 4 : RS <= 3 ? 2 : 1;
+    while (cm > 1 && Cg <= QW_T * (cm / 2)) cm /= 2;      // no wider than the tensor
+    return cm;
+}
+static int quant_wgt_gx(int Cg, int R, int S) {
+    const int ct = QW_T * quant_wgt_cm(Cg, R, S);
+    return (Cg + ct - 1) / ct;
+}
 
 template <bool STOCH, bool DEV>
 __device__ __forceinline__ void quantize_wgt_body(
@@ -415,7 +429,7 @@ __device__ __forceinline__ void quantize_wgt_body(
     const float* __restrict__ clip, const float* __restrict__ absmax_part, int nparts,
     uint32_t seed_lo, uint32_t seed_hi_mul, int8_t* __restrict__ q, float* __restrict__ scale_out,
     DevPartial* __restrict__ devpart, const VBlock vb, float* lds4, int8_t* tile) {
-    // lds4: 4 floats, tile: QW_T * QW_T * QW_TAPS bytes of LDS, [filter][channel][tap], supplied by the kernel
+    // lds4: 4 floats, tile: QW_T * CT * min(taps, QW_TAPS) bytes of LDS, [filter][channel][tap], supplied by the kernel
     const float cval = resolve_clip(clip, absmax_part, nparts, lds4);
     float inv = inv_scale_of(cval);
     float sc = scale_of(cval);
@@ -426,7 +440,8 @@ __device__ __forceinline__ void quantize_wgt_body(
     if (vb.x == 0 && vb.y == 0 && vb.z == 0 && threadIdx.x == 0) *scale_out = sc;
 
     const int RS = R * S;
-    const int k0 = vb.y * QW_T, c0 = vb.x * QW_T;
+    const int CM = quant_wgt_cm(Cg, R, S), CT = QW_T * CM;      // channels per block
+    const int k0 = vb.y * QW_T, c0 = vb.x * CT;
     double A = 0.0, G = 0.0;
     unsigned long long B = 0;
     // small tensors spread their taps over blockIdx.z to have enough blocks
@@ -434,9 +449,9 @@ __device__ __forceinline__ void quantize_wgt_body(
     const int rs_begin = vb.z * tpb, rs_end = (rs_begin + tpb < RS) ? rs_begin + tpb : RS;
     for (int rs0 = rs_begin; rs0 < rs_end; rs0 += QW_TAPS) {
         const int nrs = (rs_end - rs0 < QW_TAPS) ? (rs_end - rs0) : QW_TAPS;
-        const int per_k = QW_T * nrs;
+        const int per_k = CT * nrs;
         if (rs0 != rs_begin) __syncthreads();
-        const int cvalid = (Cg - c0 < QW_T) ? (Cg - c0) : QW_T;
+        const int cvalid = (Cg - c0 < CT) ? (Cg - c0) : CT;
         if (nrs == RS) {
             // all taps at once: a filter's 16 channels x taps are one contiguous run; a wave walks the
             // runs of four filters, 64 consecutive floats per load
@@ -481,27 +496,28 @@ __device__ __forceinline__ void quantize_wgt_body(
             }
         }
         __syncthreads();
-        // view 1: granule (filter, tap) = 16 channels
-        for (int u = threadIdx.x; u < QW_T * nrs; u += 256) {
-            const int k_l = u / nrs, rs_l = u - k_l * nrs;
-            if (k0 + k_l < K) {
+        // view 1: granule (filter, tap, channel tile) = 16 channels; the channel tile runs fastest
+        for (int u = threadIdx.x; u < QW_T * nrs * CM; u += 256) {
+            const int k_l = u / (nrs * CM), r2 = u - k_l * (nrs * CM);
+            const int rs_l = r2 / CM, cb = (r2 - rs_l * CM) * QW_T;
+            if (k0 + k_l < K && c0 + cb < Cp) {
                 uint32_t d[4];
+                const int8_t* __restrict__ tp = tile + (k_l * CT + cb) * nrs + rs_l;
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    d[j] = pack4(tile[(k_l * QW_T + 4 * j) * nrs + rs_l], tile[(k_l * QW_T + 4 * j + 1) * nrs + rs_l],
-                                 tile[(k_l * QW_T + 4 * j + 2) * nrs + rs_l], tile[(k_l * QW_T + 4 * j + 3) * nrs + rs_l]);
-                *reinterpret_cast<uint4*>(q + ((size_t)(k0 + k_l) * RS + rs0 + rs_l) * Cp + c0) = make_uint4(d[0], d[1], d[2], d[3]);
+                    d[j] = pack4(tp[(4 * j) * nrs], tp[(4 * j + 1) * nrs], tp[(4 * j + 2) * nrs], tp[(4 * j + 3) * nrs]);
+                *reinterpret_cast<uint4*>(q + ((size_t)(k0 + k_l) * RS + rs0 + rs_l) * Cp + c0 + cb) = make_uint4(d[0], d[1], d[2], d[3]);
             }
         }
         // view 2: granule (channel, tap) = 16 filters
-        for (int u = threadIdx.x; u < QW_T * nrs; u += 256) {
+        for (int u = threadIdx.x; u < CT * nrs; u += 256) {
             const int c_l = u / nrs, rs_l = u - c_l * nrs;
             if (c0 + c_l < Cg) {
                 uint32_t d[4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    d[j] = pack4(tile[((4 * j) * QW_T + c_l) * nrs + rs_l], tile[((4 * j + 1) * QW_T + c_l) * nrs + rs_l],
-                                 tile[((4 * j + 2) * QW_T + c_l) * nrs + rs_l], tile[((4 * j + 3) * QW_T + c_l) * nrs + rs_l]);
+                    d[j] = pack4(tile[((4 * j) * CT + c_l) * nrs + rs_l], tile[((4 * j + 1) * CT + c_l) * nrs + rs_l],
+                                 tile[((4 * j + 2) * CT + c_l) * nrs + rs_l], tile[((4 * j + 3) * CT + c_l) * nrs + rs_l]);
                 *reinterpret_cast<uint4*>(q + off2 + ((size_t)(c0 + c_l) * RS + rs0 + rs_l) * Kp + k0) = make_uint4(d[0], d[1], d[2], d[3]);
             }
         }
@@ -566,7 +582,7 @@ void quant_grid(int kind, const int d[4], int* gx, int* gy, int* gz) {
         const int HW = d[2] * d[3], Cp = (d[1] + 15) & ~15;
         *gx = (HW + QA_PIX - 1) / QA_PIX; *gy = (Cp + QA_CH - 1) / QA_CH; *gz = d[0];
     } else if (kind == 1) {
-        *gx = (d[1] + QW_T - 1) / QW_T; *gy = (d[0] + QW_T - 1) / QW_T; *gz = quant_wgt_zsplit(d[0], d[1], d[2], d[3]);
+        *gx = quant_wgt_gx(d[1], d[2], d[3]); *gy = (d[0] + QW_T - 1) / QW_T; *gz = quant_wgt_zsplit(d[0], d[1], d[2], d[3]);
     } else {
         *gx = quant_blocks_planar((size_t)d[0] * d[1] * d[2] * d[3]); *gy = 1; *gz = 1;
     }
@@ -581,7 +597,7 @@ hipError_t launch_quantize_batch(const QuantBatch& b, int total_blocks, hipStrea
             need = sizeof(uint32_t) * QA_PIX * (QA_CH / 4 + 1);
         } else if (t.kind == 1) {
             const int tpb = (t.d2 * t.d3 + t.gz - 1) / t.gz;          // taps per block along z
-            need = (size_t)QW_T * QW_T * (tpb < QW_TAPS ? tpb : QW_TAPS);
+            need = (size_t)QW_T * QW_T * quant_wgt_cm(t.d1, t.d2, t.d3) * (tpb < QW_TAPS ? tpb : QW_TAPS);
         }
         if (need > lds) lds = need;
     }
@@ -593,20 +609,20 @@ hipError_t launch_quantize_batch(const QuantBatch& b, int total_blocks, hipStrea
 
 // blocks along the taps: 1 for tensors with many 16 x 16 tiles, up to R*S for small ones
 static int quant_wgt_zsplit(int K, int Cg, int R, int S) {
-    const int tiles = ((K + QW_T - 1) / QW_T) * ((Cg + QW_T - 1) / QW_T);
+    const int tiles = ((K + QW_T - 1) / QW_T) * quant_wgt_gx(Cg, R, S);
     int z = (256 + tiles - 1) / tiles;
     if (z > R * S) z = R * S;
     return z < 1 ? 1 : z;
 }
 int quant_blocks_wgt(int K, int Cg, int R, int S) {
-    return ((K + QW_T - 1) / QW_T) * ((Cg + QW_T - 1) / QW_T) * quant_wgt_zsplit(K, Cg, R, S);
+    return ((K + QW_T - 1) / QW_T) * quant_wgt_gx(Cg, R, S) * quant_wgt_zsplit(K, Cg, R, S);
 }
 
 hipError_t launch_quantize_wgt(const QuantArgs& a, hipStream_t st) {
     const int K = a.d0, Cg = a.d1, R = a.d2, S = a.d3;
     const int Cp = (Cg + 15) & ~15, Kp = (K + 15) & ~15;
     const size_t off2 = (((size_t)K * R * S * Cp) + 255) & ~(size_t)255;
-    const dim3 grid((Cg + QW_T - 1) / QW_T, (K + QW_T - 1) / QW_T, quant_wgt_zsplit(K, Cg, R, S));
+    const dim3 grid(quant_wgt_gx(Cg, R, S), (K + QW_T - 1) / QW_T, quant_wgt_zsplit(K, Cg, R, S));
     const uint32_t slo = (uint32_t)a.seed, shi = seed_hi_term(a.seed);
     KernelTimer kt(KID_QUANTIZE_WGT, st);
 #define LAUNCH(ST, DV)                                                                              \

@@ -66,7 +66,8 @@ def gpu_quantize(x, kind, clip=None, mode=RTN, seed=0, want_dev=False):
 
 
 ACT_SHAPES = [(2, 16, 16, 16), (1, 3, 5, 7), (3, 24, 14, 14), (2, 70, 17, 17), (1, 144, 9, 3),
-              (2, 64, 8, 8), (1, 1, 1, 1), (5, 130, 1, 66)]
+              (2, 64, 8, 8), (1, 1, 1, 1), (5, 130, 1, 66),
+              (33, 208, 1, 1), (7, 200, 1, 1)]      # 1 x 1 images: without / with channel padding
 
 
 @pytest.mark.parametrize("shape", ACT_SHAPES)
