@@ -34,27 +34,32 @@ __global__ __launch_bounds__(256) void dw_conv_kernel(const DwArgs a) {
     for (int o = threadIdx.x; o < OHW; o += 256) {
         const int oh = o / a.OW, ow = o - oh * a.OW;
         int sum = 0;
-        for (int r = 0; r < a.R; ++r) {
-            int ih;
-            if (DGRAD) {
-                const int th = oh + a.pad_h - r;
-                ih = th / a.stride_h;
-                if (th < 0 || ih * a.stride_h != th) continue;
-            } else {
-                ih = oh * a.stride_h - a.pad_h + r;
-            }
-            if ((unsigned)ih >= (unsigned)a.IH) continue;
-            for (int s = 0; s < a.S; ++s) {
-                int iw;
-                if (DGRAD) {
-                    const int tw = ow + a.pad_w - s;
-                    iw = tw / a.stride_w;
-                    if (tw < 0 || iw * a.stride_w != tw) continue;
-                } else {
-                    iw = ow * a.stride_w - a.pad_w + s;
+        if (DGRAD) {
+            // Only the taps r = r0 + k * stride_h with r0 = (oh + pad_h) mod stride_h reach this pixel,
+            // tap r0 from gradient row (oh + pad_h - r0) / stride_h and every further one from the row
+            // above; the same along w.  Two divisions per pixel instead of one per tap, and the taps
+            // that never divide are not visited at all.
+            const int ph = oh + a.pad_h, pw = ow + a.pad_w;
+            const int qh = ph / a.stride_h, qw = pw / a.stride_w;
+            const int r0 = ph - qh * a.stride_h, s0 = pw - qw * a.stride_w;
+            int ih = qh;
+            for (int r = r0; r < a.R && ih >= 0; r += a.stride_h, --ih) {
+                if (ih >= a.IH) continue;
+                int iw = qw;
+                for (int s = s0; s < a.S && iw >= 0; s += a.stride_w, --iw) {
+                    if (iw >= a.IW) continue;
+                    sum += (int)plane[ih * a.IW + iw] * wtap[r * a.S + s];
                 }
-                if ((unsigned)iw >= (unsigned)a.IW) continue;
-                sum += (int)plane[ih * a.IW + iw] * wtap[r * a.S + s];
+            }
+        } else {
+            for (int r = 0; r < a.R; ++r) {
+                const int ih = oh * a.stride_h - a.pad_h + r;
+                if ((unsigned)ih >= (unsigned)a.IH) continue;
+                for (int s = 0; s < a.S; ++s) {
+                    const int iw = ow * a.stride_w - a.pad_w + s;
+                    if ((unsigned)iw >= (unsigned)a.IW) continue;
+                    sum += (int)plane[ih * a.IW + iw] * wtap[r * a.S + s];
+                }
             }
         }
         const size_t idx = (size_t)nc * OHW + o;
