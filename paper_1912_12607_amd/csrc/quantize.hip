@@ -147,6 +147,15 @@ __device__ __forceinline__ float resolve_clip(const float* __restrict__ clip,
 // ---------------------------------------------------------------------------------------------
 constexpr int QA_PIX = 64;
 constexpr int QA_CH = 64;
+// Tensors of at most 16 channels (an image, the gradient of a narrow layer) have one 16-byte granule
+// per pixel: a thread then makes one pixel's granule on its own -- up to 16 loads that walk the
+// pixels of each channel plane, one 16-byte store -- and a block takes 256 pixels; the 64 x 64 tile
+// would be a quarter full and the 3-channel image of a stem 50 000 blocks of 192 elements (112 us
+// for 9.6 M elements).
+constexpr int QA_NARROW_PIX = 256;
+__host__ __device__ inline int quant_act_gx(int Cp, int HW) {
+    return Cp == 16 ? (HW + QA_NARROW_PIX - 1) / QA_NARROW_PIX : (HW + QA_PIX - 1) / QA_PIX;
+}
 
 // 4x4 byte transpose: in d[i] = codes of 4 pixels for channel i; out o[p] = codes of 4 channels for pixel p
 __device__ __forceinline__ void qa_transpose4x4(const uint32_t d[4], uint32_t o[4]) {
@@ -171,6 +180,46 @@ __device__ __forceinline__ void quantize_act_body(
     float* lds4, uint32_t (*tile)[QA_CH / 4 + 1]) {
     // lds4: 4 floats, tile: [QA_PIX][QA_CH / 4 + 1] dwords of LDS supplied by the kernel
     const int n = vb.z;
+    if (Cp == 16) {
+        const int p = vb.x * QA_NARROW_PIX + (int)threadIdx.x;
+        const bool pv = p < HW;
+        float v[16];
+#pragma unroll
+        for (int c = 0; c < 16; ++c) v[c] = (pv && c < C) ? x[((size_t)n * C + c) * HW + p] : 0.0f;
+        const float cval = resolve_clip(clip, absmax_part, nparts, lds4);
+        float inv = inv_scale_of(cval);
+        float sc = scale_of(cval);
+        if (STOCH) {
+            inv = __fmul_rn(inv, kTwo24);        // the scaled value carries 24 fraction bits
+            fp32_round_down_mode(inv, sc);
+        }
+        if (vb.x == 0 && vb.z == 0 && threadIdx.x == 0) *scale_out = sc;
+        double A = 0.0, G = 0.0;
+        unsigned long long B = 0;
+        uint32_t d[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int code[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int c = 4 * j + k;
+                code[k] = 0;
+                if (pv && c < C) {
+                    code[k] = quantize_one<STOCH>(v[c], inv, seed_lo, seed_hi_mul, (uint32_t)(((size_t)n * C + c) * HW + p));
+                    if (DEV) {
+                        const double g = (double)v[c];
+                        A = fma(g, (double)code[k], A);
+                        G = fma(g, g, G);
+                        B += (unsigned)(code[k] * code[k]);
+                    }
+                }
+            }
+            d[j] = pack4(code[0], code[1], code[2], code[3]);
+        }
+        if (pv) *reinterpret_cast<uint4*>(q + ((size_t)n * HW + p) * 16) = make_uint4(d[0], d[1], d[2], d[3]);
+        if (DEV) block_store_devpartial(A, G, B, devpart + (vb.z * vb.gx + vb.x));
+        return;
+    }
     const int c0 = vb.y * QA_CH;
     const int p0 = vb.x * QA_PIX;
     const int lane = threadIdx.x & 63;
@@ -283,12 +332,12 @@ __global__ __launch_bounds__(256) void quantize_act_kernel(
 }
 
 int quant_blocks_act(int N, int Cp, int HW) {
-    return ((HW + QA_PIX - 1) / QA_PIX) * ((Cp + QA_CH - 1) / QA_CH) * N;
+    return quant_act_gx(Cp, HW) * ((Cp + QA_CH - 1) / QA_CH) * N;
 }
 
 hipError_t launch_quantize_act(const QuantArgs& a, hipStream_t st) {
     const int N = a.d0, C = a.d1, HW = a.d2 * a.d3, Cp = (C + 15) & ~15;
-    dim3 grid((HW + QA_PIX - 1) / QA_PIX, (Cp + QA_CH - 1) / QA_CH, N);
+    dim3 grid(quant_act_gx(Cp, HW), (Cp + QA_CH - 1) / QA_CH, N);
     const uint32_t slo = (uint32_t)a.seed, shi = seed_hi_term(a.seed);
     KernelTimer kt(KID_QUANTIZE_ACT, st);
 #define LAUNCH(ST, DV)                                                                                      \
@@ -580,7 +629,7 @@ __global__ __launch_bounds__(256) void quantize_batch_kernel(const QuantBatch b)
 void quant_grid(int kind, const int d[4], int* gx, int* gy, int* gz) {
     if (kind == 0) {
         const int HW = d[2] * d[3], Cp = (d[1] + 15) & ~15;
-        *gx = (HW + QA_PIX - 1) / QA_PIX; *gy = (Cp + QA_CH - 1) / QA_CH; *gz = d[0];
+        *gx = quant_act_gx(Cp, HW); *gy = (Cp + QA_CH - 1) / QA_CH; *gz = d[0];
     } else if (kind == 1) {
         *gx = quant_wgt_gx(d[1], d[2], d[3]); *gy = (d[0] + QW_T - 1) / QW_T; *gz = quant_wgt_zsplit(d[0], d[1], d[2], d[3]);
     } else {
