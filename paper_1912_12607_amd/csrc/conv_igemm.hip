@@ -636,11 +636,11 @@ int igemm_ksplit(const IgemmArgs& a) {
 }
 
 size_t igemm_s2d(IgemmArgs* a) {
-    if (a->dgrad || a->C < 1 || a->Ca != 16 || !s2d_applies(a->C, a->IH, a->IW, a->stride_h, a->stride_w)) return 0;
+    if (a->dgrad || a->C < 1 || a->Ca != 16 || !s2d_applies(a->C, a->stride_h, a->stride_w)) return 0;
     const S2dGeo g = s2d_geometry(a->R, a->S, a->pad_h, a->pad_w);
     a->C *= 4;
-    a->IH /= 2;
-    a->IW /= 2;
+    a->IH = (a->IH + 1) / 2;
+    a->IW = (a->IW + 1) / 2;
     a->R = g.R2;
     a->S = g.S2;
     a->pad_h = g.ph;
@@ -659,7 +659,7 @@ hipError_t launch_igemm(const IgemmArgs& a_in, hipStream_t st) {
             const S2dGeo g = s2d_geometry(a.R, a.S, a.pad_h, a.pad_w);
             int8_t* const xs = a.s2d;
             int8_t* const ws = a.s2d + (((size_t)t.N * t.IH * t.IW * 16 + 255) & ~(size_t)255);
-            hipError_t e = launch_s2d_repack(a.act, xs, a.N, t.IH, t.IW, a.C, st);
+            hipError_t e = launch_s2d_repack(a.act, xs, a.N, a.IH, a.IW, a.C, st);
             if (e != hipSuccess) return e;
             e = launch_s2d_weights(a.wgt, ws, a.rows, a.R, a.S, a.C, g, st);
             if (e != hipSuccess) return e;

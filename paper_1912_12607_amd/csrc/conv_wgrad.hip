@@ -377,16 +377,16 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const WgradArgs a) {
 
 size_t wgrad_s2d(WgradArgs* a) {
     a->s2d = 0;
-    if (!s2d_applies(a->C, a->H, a->W, a->stride_h, a->stride_w)) return 0;
+    if (!s2d_applies(a->C, a->stride_h, a->stride_w)) return 0;
     const S2dGeo g = s2d_geometry(a->R, a->S, a->pad_h, a->pad_w);
     a->s2d = 1;
-    a->oC = a->C; a->oR = a->R; a->oS = a->S;
+    a->oC = a->C; a->oR = a->R; a->oS = a->S; a->oH = a->H; a->oW = a->W;
     a->eh = g.eh;
     a->ew = g.ew;
     a->C = 4 * a->oC;
     a->Cp = 16;
-    a->H /= 2;
-    a->W /= 2;
+    a->H = (a->H + 1) / 2;
+    a->W = (a->W + 1) / 2;
     a->R = g.R2;
     a->S = g.S2;
     a->pad_h = g.ph;
@@ -520,7 +520,7 @@ void wgrad_plan_uncached(WgradArgs* a) {
 hipError_t launch_wgrad(const WgradArgs& a_in, hipStream_t st) {
     WgradArgs a = a_in;
     if (a.s2d) {
-        hipError_t e = launch_s2d_repack(a.x, a.xs, a.N, a.H, a.W, a.oC, st);
+        hipError_t e = launch_s2d_repack(a.x, a.xs, a.N, a.oH, a.oW, a.oC, st);
         if (e != hipSuccess) return e;
         a.x = a.xs;
     }

@@ -138,13 +138,12 @@ bool launch_band(const IgemmArgs& a, hipStream_t st, hipError_t* err);
 // ph = ceil(pad / 2) and r = 2 r' + dy - eh, eh = 2 ph - pad: the R x S filter becomes a
 // ceil((R+eh)/2) x ceil((S+ew)/2) one whose taps outside the original filter are zero.  The 16-byte
 // pixel granule then carries 4 C channels instead of C, and the taps shrink fourfold.  The output
-// pixels stay the same.
+// pixels stay the same.  An odd image gets a last block row / column whose missing pixels are zero, as
+// the padding around the image is.
 struct S2dGeo {
     int ph, pw, eh, ew, R2, S2;
 };
-inline bool s2d_applies(int C, int H, int W, int stride_h, int stride_w) {
-    return stride_h == 2 && stride_w == 2 && C <= 4 && !(H & 1) && !(W & 1);
-}
+inline bool s2d_applies(int C, int stride_h, int stride_w) { return stride_h == 2 && stride_w == 2 && C <= 4; }
 inline S2dGeo s2d_geometry(int R, int S, int pad_h, int pad_w) {
     S2dGeo g;
     g.ph = (pad_h + 1) / 2;
@@ -155,8 +154,8 @@ inline S2dGeo s2d_geometry(int R, int S, int pad_h, int pad_w) {
     g.S2 = (S + g.ew + 1) / 2;
     return g;
 }
-// input codes [N][2 H2][2 W2][16] -> [N][H2][W2][16]
-hipError_t launch_s2d_repack(const int8_t* x, int8_t* xs, int N, int H2, int W2, int C, hipStream_t st);
+// input codes [N][H][W][16] -> [N][ceil(H/2)][ceil(W/2)][16]
+hipError_t launch_s2d_repack(const int8_t* x, int8_t* xs, int N, int H, int W, int C, hipStream_t st);
 // filter codes [K][R][S][16] -> [K][R2][S2][16]
 hipError_t launch_s2d_weights(const int8_t* w, int8_t* ws, int K, int R, int S, int C, const S2dGeo& g, hipStream_t st);
 
@@ -180,7 +179,7 @@ struct WgradArgs {
     size_t lds_bytes;
     // filled by wgrad_s2d() when it rewrites the geometry above into the space-to-depth form:
     int s2d;                     // 1: C, Cp, H, W, R, S, strides and pads describe the rewritten problem
-    int oC, oR, oS, eh, ew;      // the layer's own channels and filter; tap r = 2 r' + dy - eh, s = 2 s' + dx - ew
+    int oC, oR, oS, oH, oW, eh, ew;   // the layer's own channels, filter and image; tap r = 2 r' + dy - eh, s = 2 s' + dx - ew
     int8_t* xs;                  // scratch: the input codes in space-to-depth form, [N][H][W][16]
 };
 // Rewrites the geometry into the space-to-depth form (s2d.hip) when it applies.  Returns the bytes of

@@ -26,17 +26,22 @@ __device__ __forceinline__ uint4 s2d_pack(const uint32_t px[4], int C) {
     return make_uint4((uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32));
 }
 
-// Input codes: byte (2 dy + dx) * C + c of pixel (h', w') is channel c of pixel (2 h' + dy, 2 w' + dx).
+// Input codes: byte (2 dy + dx) * C + c of pixel (h', w') is channel c of pixel (2 h' + dy, 2 w' + dx),
+// zero where that pixel lies beyond an odd image.
 // One thread per output pixel; it reads the first four bytes of four input pixels.
 __global__ __launch_bounds__(256) void s2d_repack_kernel(const int8_t* __restrict__ x, int8_t* __restrict__ xs,
-                                                         int N, int H2, int W2, int C) {
+                                                         int N, int H, int W, int C) {
+    const int H2 = (H + 1) >> 1, W2 = (W + 1) >> 1;
     const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (t >= (size_t)N * H2 * W2) return;
     const int w2 = (int)(t % W2);
-    const size_t nh = t / W2;                 // n * H2 + h'
-    const uint32_t* __restrict__ row0 = reinterpret_cast<const uint32_t*>(x) + ((2 * nh) * (size_t)(2 * W2) + 2 * w2) * 4;
-    const uint32_t* __restrict__ row1 = row0 + (size_t)(2 * W2) * 4;
-    const uint32_t px[4] = {row0[0], row0[4], row1[0], row1[4]};
+    const size_t nh = t / W2;
+    const int h2 = (int)(nh % H2);
+    const size_t n = nh / H2;
+    const uint32_t* __restrict__ row0 = reinterpret_cast<const uint32_t*>(x) + ((n * H + 2 * h2) * (size_t)W + 2 * w2) * 4;
+    const uint32_t* __restrict__ row1 = row0 + (size_t)W * 4;
+    const bool w1 = 2 * w2 + 1 < W, h1 = 2 * h2 + 1 < H;     // the block's second column / row exists
+    const uint32_t px[4] = {row0[0], w1 ? row0[4] : 0u, h1 ? row1[0] : 0u, (h1 && w1) ? row1[4] : 0u};
     reinterpret_cast<uint4*>(xs)[t] = s2d_pack(px, C);
 }
 
@@ -57,10 +62,10 @@ __global__ __launch_bounds__(256) void s2d_weights_kernel(const int8_t* __restri
     reinterpret_cast<uint4*>(ws)[t] = s2d_pack(px, C);
 }
 
-hipError_t launch_s2d_repack(const int8_t* x, int8_t* xs, int N, int H2, int W2, int C, hipStream_t st) {
-    const size_t npix = (size_t)N * H2 * W2;
+hipError_t launch_s2d_repack(const int8_t* x, int8_t* xs, int N, int H, int W, int C, hipStream_t st) {
+    const size_t npix = (size_t)N * ((H + 1) / 2) * ((W + 1) / 2);
     KernelTimer kt(KID_S2D_REPACK, st);
-    launch_timed(kt, s2d_repack_kernel, dim3((unsigned)((npix + 255) / 256)), dim3(256), 0, st, x, xs, N, H2, W2, C);
+    launch_timed(kt, s2d_repack_kernel, dim3((unsigned)((npix + 255) / 256)), dim3(256), 0, st, x, xs, N, H, W, C);
     return hipGetLastError();
 }
 

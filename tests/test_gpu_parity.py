@@ -270,7 +270,9 @@ CONV_SHAPES = [
     (2, 2, 6, 8, 4, 2, 2, (2, 2), (0, 0), 1),
     (1, 1, 10, 12, 3, 5, 3, (2, 2), (2, 0), 1),
     (3, 3, 8, 8, 6, 4, 6, (2, 2), (1, 2), 1),          # even filter, even and odd padding
-    (2, 3, 9, 8, 6, 3, 3, (2, 2), (1, 1), 1),          # odd image height: not rewritten
+    (2, 3, 9, 8, 6, 3, 3, (2, 2), (1, 1), 1),          # odd image height: the last block row is half empty
+    (1, 3, 11, 13, 5, 3, 3, (2, 2), (0, 0), 1),        # odd both ways, no padding
+    (2, 2, 7, 9, 4, 5, 5, (2, 2), (2, 2), 1),
 ]
 
 
