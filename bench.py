@@ -115,6 +115,9 @@ def main():
     ap.add_argument("--resnet50", type=int, default=0, metavar="BATCH",
                     help="also time the step of every ResNet-50 convolution and its classifier at this batch "
                          "(Fig.10's workload) and print the per-layer table and the network total (stderr)")
+    ap.add_argument("--mobilenetv2", type=int, default=0, metavar="BATCH", help="the same for every convolution of MobileNetV2")
+    ap.add_argument("--inceptionv3", type=int, default=0, metavar="BATCH",
+                    help="the same for one layer of each kind in InceptionV3 (no network total: not every layer is listed)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -237,13 +240,14 @@ def main():
                               "TOP/s": round(al[k]["ops"] / t / 1e12, 2)}
                 print(json.dumps(row), file=sys.stderr, flush=True)
 
-    if args.resnet50 > 0:
-        total_ms, total_macs = 0.0, 0
-        for i, (count, Lx) in enumerate(inputs.resnet50_layers(args.resnet50)):
+    def sweep(title, batch, layers, seed_cfg):
+        """One step per distinct layer shape; the network's time is the sum over shapes x multiplicity."""
+        total_ms, total_ops = 0.0, 0
+        for i, (count, Lx) in enumerate(layers):
             # the first layer's input is the image: no backward-data pass there (4 of the 6 MAC passes counted)
             st = LayerStep(Lx, n_cand=n_cand, keep_acc=False, requantize_deviation=False, input_grad=i > 0)
             passes = 6 if i > 0 else 4
-            st.upload(inputs.make_x(Lx, 50, i), inputs.make_w(Lx, 50, i), inputs.make_dy(Lx, 50, i), ratios)
+            st.upload(inputs.make_x(Lx, seed_cfg, i), inputs.make_w(Lx, seed_cfg, i), inputs.make_dy(Lx, seed_cfg, i), ratios)
             nst = max(20, args.steps // 10)
             for k in range(80):          # the first few dozen steps on fresh buffers run at up to twice the steady time
                 st.run(seed=k, overlap=overlap)
@@ -254,14 +258,21 @@ def main():
             torch.cuda.synchronize()
             ts = (time.perf_counter() - t0) / nst
             total_ms += count * ts * 1e3
-            total_macs += count * Lx.macs * passes // 6
-            print(json.dumps({"layer": Lx.name, "count": count, "C": Lx.C, "HW": Lx.H, "K": Lx.K, "RS": Lx.R,
-                              "stride": Lx.stride[0], "ms_per_step": round(ts * 1e3, 4),
+            total_ops += count * Lx.macs * passes
+            print(json.dumps({"layer": Lx.name, "count": count, "C": Lx.C, "HW": Lx.H, "K": Lx.K, "RS": [Lx.R, Lx.S],
+                              "stride": Lx.stride[0], "groups": Lx.groups, "ms_per_step": round(ts * 1e3, 4),
                               "TOPS": round(passes * Lx.macs / ts / 1e12, 1)}), file=sys.stderr, flush=True)
             del st
-        print(json.dumps({"network": "ResNet-50 convolutions + classifier", "batch": args.resnet50,
-                          "ms_per_iteration": round(total_ms, 3), "TOPS": round(6 * total_macs / total_ms / 1e9, 1),
-                          "images_per_s": round(args.resnet50 / total_ms * 1e3, 1)}), file=sys.stderr, flush=True)
+        print(json.dumps({"network": title, "batch": batch, "ms_per_iteration": round(total_ms, 3),
+                          "TOPS": round(total_ops / total_ms / 1e9, 1),
+                          "images_per_s": round(batch / total_ms * 1e3, 1)}), file=sys.stderr, flush=True)
+
+    if args.resnet50 > 0:
+        sweep("ResNet-50 convolutions + classifier", args.resnet50, inputs.resnet50_layers(args.resnet50), 50)
+    if args.mobilenetv2 > 0:
+        sweep("MobileNetV2 convolutions", args.mobilenetv2, inputs.mobilenetv2_layers(args.mobilenetv2), 51)
+    if args.inceptionv3 > 0:
+        sweep("InceptionV3, one layer of each kind", args.inceptionv3, inputs.inceptionv3_layers(args.inceptionv3), 52)
 
     print(json.dumps(out), flush=True)
 

@@ -155,7 +155,8 @@ size_t int8t_workspace_bytes(int8t_op op, const int8t_conv_desc* desc, size_t n,
             Geo g;
             if (desc_ok(desc, &g) != INT8T_OK) return 0;
             if (g.depthwise)
-                return align256((size_t)dw_wgrad_chunks(desc->N, desc->C) * desc->C * desc->R * desc->S * 4);
+                return align256((size_t)dw_wgrad_chunks(desc->N, desc->C, dw_wgrad_threads(g.P, g.Q, desc->R, desc->S, desc->stride_h, desc->stride_w)) *
+                                desc->C * desc->R * desc->S * 4);
             WgradArgs a{};
             fill_wgrad_geometry(&a, desc, g);
             const size_t s2d_bytes = wgrad_s2d(&a);
@@ -430,7 +431,9 @@ int8t_status int8t_conv_bwd_weight(const int8t_conv_desc* desc, const int8_t* xq
     if (g.depthwise) {
         DwArgs a{};
         a.a = xq_dev; a.b = dyq_dev; a.sa = sx_dev; a.sb = sdy_dev; a.out = dw_dev; a.acc = acc_dev;
-        a.partial = (int32_t*)ws_dev; a.chunks = dw_wgrad_chunks(desc->N, desc->C);
+        a.partial = (int32_t*)ws_dev;
+        a.threads = dw_wgrad_threads(g.P, g.Q, desc->R, desc->S, desc->stride_h, desc->stride_w);
+        a.chunks = dw_wgrad_chunks(desc->N, desc->C, a.threads);
         a.N = desc->N; a.C = desc->C; a.IH = desc->H; a.IW = desc->W; a.OH = g.P; a.OW = g.Q;
         a.R = desc->R; a.S = desc->S; a.stride_h = desc->stride_h; a.stride_w = desc->stride_w;
         a.pad_h = desc->pad_h; a.pad_w = desc->pad_w; a.dgrad = 0;

@@ -22,16 +22,16 @@ __global__ __launch_bounds__(256) void dw_conv_kernel(const DwArgs a) {
     const int IHW = a.IH * a.IW, OHW = a.OH * a.OW, RS = a.R * a.S;
     const int8_t* __restrict__ src = a.a + (size_t)nc * IHW;
     if ((IHW & 15) == 0) {
-        for (int i = threadIdx.x; i < (IHW >> 4); i += 256)
+        for (int i = threadIdx.x; i < (IHW >> 4); i += blockDim.x)
             reinterpret_cast<uint4*>(plane)[i] = reinterpret_cast<const uint4*>(src)[i];
     } else {
-        for (int i = threadIdx.x; i < IHW; i += 256) plane[i] = src[i];
+        for (int i = threadIdx.x; i < IHW; i += blockDim.x) plane[i] = src[i];
     }
     if (threadIdx.x < RS) wtap[threadIdx.x] = (int)a.b[(size_t)c * RS + threadIdx.x];
     __syncthreads();
 
     const float scale = __fmul_rn(a.sa[0], a.sb[0]);
-    for (int o = threadIdx.x; o < OHW; o += 256) {
+    for (int o = threadIdx.x; o < OHW; o += blockDim.x) {
         const int oh = o / a.OW, ow = o - oh * a.OW;
         int sum = 0;
         if (DGRAD) {
@@ -86,7 +86,7 @@ __device__ __forceinline__ void dw_fill_plane(const int8_t* __restrict__ src, in
     const int IHW = IH * IW;
     if ((IHW & 15) == 0) {
         // 16 source bytes per thread and pass; row / column advance without divisions
-        for (int i = threadIdx.x; i < (IHW >> 4); i += 256) {
+        for (int i = threadIdx.x; i < (IHW >> 4); i += blockDim.x) {
             const uint4 v = reinterpret_cast<const uint4*>(src)[i];
             const uint32_t d[4] = {v.x, v.y, v.z, v.w};
             int row = (16 * i) / IW, col = 16 * i - row * IW;
@@ -100,7 +100,7 @@ __device__ __forceinline__ void dw_fill_plane(const int8_t* __restrict__ src, in
             }
         }
     } else {
-        for (int i = threadIdx.x; i < IHW; i += 256) {
+        for (int i = threadIdx.x; i < IHW; i += blockDim.x) {
             const int row = i / IW, col = i - row * IW;
             dst[(row + top) * pitch + col + left] = src[i];
         }
@@ -111,7 +111,7 @@ __device__ __forceinline__ void dw_fill_plane(const int8_t* __restrict__ src, in
 __device__ __forceinline__ void dw_stage_plane(const int8_t* __restrict__ src, int IH, int IW, int8_t* dst,
                                                int rows, int pitch, int top, int left) {
     const int ndw = rows * pitch >> 2;          // pitch is a multiple of 4
-    for (int i = threadIdx.x; i < ndw; i += 256) reinterpret_cast<uint32_t*>(dst)[i] = 0u;
+    for (int i = threadIdx.x; i < ndw; i += blockDim.x) reinterpret_cast<uint32_t*>(dst)[i] = 0u;
     __syncthreads();
     dw_fill_plane(src, IH, IW, dst, pitch, top, left);
     __syncthreads();
@@ -146,7 +146,7 @@ __global__ __launch_bounds__(256) void dw_conv_fast_kernel(const DwArgs a, int p
     const bool vec = (a.OW & 3) == 0;
     float* __restrict__ outp = a.out + (size_t)nc * OHW;
     int32_t* __restrict__ accp = a.acc ? a.acc + (size_t)nc * OHW : nullptr;
-    for (int t = threadIdx.x; t < a.OH * QW; t += 256) {
+    for (int t = threadIdx.x; t < a.OH * QW; t += blockDim.x) {
         const int oh = t / QW, ow = (t - oh * QW) << 2;
         int sum[4] = {0, 0, 0, 0};
         for (int rp = 0; rp < a.R; ++rp) {
@@ -193,7 +193,11 @@ __device__ __forceinline__ void dw_block_sum_store(int v, int* red, int32_t* dst
     __syncthreads();
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
     __syncthreads();
-    if (threadIdx.x == 0) *dst = red[0] + red[1] + red[2] + red[3];
+    if (threadIdx.x == 0) {
+        int t = red[0];
+        for (int w = 1; w < (int)(blockDim.x >> 6); ++w) t += red[w];
+        *dst = t;
+    }
 }
 
 __global__ __launch_bounds__(256) void dw_wgrad_kernel(const DwArgs a) {
@@ -216,10 +220,10 @@ __global__ __launch_bounds__(256) void dw_wgrad_kernel(const DwArgs a) {
             const int8_t* __restrict__ xsrc = a.a + ((size_t)n * a.C + c) * IHW;
             const int8_t* __restrict__ gsrc = a.b + ((size_t)n * a.C + c) * OHW;
             __syncthreads();
-            for (int i = threadIdx.x; i < IHW; i += 256) xs[i] = xsrc[i];
-            for (int i = threadIdx.x; i < OHW; i += 256) gs[i] = gsrc[i];
+            for (int i = threadIdx.x; i < IHW; i += blockDim.x) xs[i] = xsrc[i];
+            for (int i = threadIdx.x; i < OHW; i += blockDim.x) gs[i] = gsrc[i];
             __syncthreads();
-            for (int o = threadIdx.x; o < OHW; o += 256) {
+            for (int o = threadIdx.x; o < OHW; o += blockDim.x) {
                 const int p = o / a.OW, q = o - p * a.OW;
                 const int g = (int)gs[o];
 #pragma unroll
@@ -244,7 +248,7 @@ __global__ __launch_bounds__(256) void dw_wgrad_kernel(const DwArgs a) {
             for (int n = n0; n < n1; ++n) {
                 const int8_t* __restrict__ xsrc = a.a + ((size_t)n * a.C + c) * IHW;
                 const int8_t* __restrict__ gsrc = a.b + ((size_t)n * a.C + c) * OHW;
-                for (int o = threadIdx.x; o < OHW; o += 256) {
+                for (int o = threadIdx.x; o < OHW; o += blockDim.x) {
                     const int p = o / a.OW, q = o - p * a.OW;
                     const int ih = p * a.stride_h - a.pad_h + r, iw = q * a.stride_w - a.pad_w + s;
                     if ((unsigned)ih < (unsigned)a.IH && (unsigned)iw < (unsigned)a.IW)
@@ -275,7 +279,7 @@ __global__ __launch_bounds__(256) void dw_wgrad_fast_kernel(const DwArgs a, int 
     int8_t* gs = lds + ((xrows * pitch + 15) & ~15);    // OH x gpitch, zero tail columns
     {
         const int ndw = (((xrows * pitch + 15) & ~15) + a.OH * gpitch) >> 2;
-        for (int i = threadIdx.x; i < ndw; i += 256) reinterpret_cast<uint32_t*>(lds)[i] = 0u;
+        for (int i = threadIdx.x; i < ndw; i += blockDim.x) reinterpret_cast<uint32_t*>(lds)[i] = 0u;
     }
     int acc[R][S];
 #pragma unroll
@@ -290,7 +294,7 @@ __global__ __launch_bounds__(256) void dw_wgrad_fast_kernel(const DwArgs a, int 
         dw_fill_plane(xsrc, a.IH, a.IW, xs, pitch, a.pad_h, a.pad_w);
         dw_fill_plane(gsrc, a.OH, a.OW, gs, gpitch, 0, 0);
         __syncthreads();
-        for (int t = threadIdx.x; t < a.OH * QW; t += 256) {
+        for (int t = threadIdx.x; t < a.OH * QW; t += blockDim.x) {
             const int p = t / QW, q = (t - p * QW) << 2;
             const int g4 = *reinterpret_cast<const int*>(gs + p * gpitch + q);
 #pragma unroll
@@ -324,10 +328,18 @@ __global__ __launch_bounds__(256) void dw_wgrad_reduce_kernel(const DwArgs a) {
     if (a.acc) a.acc[t] = sum;
 }
 
-// Blocks = C x chunks, eight of them fit a compute unit: at most 2048 run at once, and a grid just
-// above that (144 channels x 15 chunks = 2160) would take two rounds for 5 % more blocks.
-int dw_wgrad_chunks(int N, int C) {
-    int chunks = 2048 / C;
+// Threads per block of the depthwise kernels: a plane of OH x OW results is OH * ceil(OW / 4) tasks in
+// the stride-1 kernels (one per result in the others).  A 7 x 7 or 14 x 14 plane keeps one wave
+// busy, not four: small planes get small blocks, and a compute unit holds as many more of them.
+int dw_threads(int OH, int OW, bool quads) {
+    const long long tasks = (long long)OH * (quads ? (OW + 3) / 4 : OW);
+    return tasks <= 64 ? 64 : tasks <= 128 ? 128 : 256;
+}
+
+// Blocks = C x chunks; 32 waves fit a compute unit: at most 2048 blocks of four waves run at once,
+// and a grid just above that (144 channels x 15 chunks = 2160) would take two rounds for 5 % more blocks.
+int dw_wgrad_chunks(int N, int C, int threads) {
+    int chunks = 2048 * (256 / threads) / C;
     if (chunks > N) chunks = N;
     if (chunks < 1) chunks = 1;
     return chunks;
@@ -348,20 +360,28 @@ hipError_t launch_dw_conv(const DwArgs& a, hipStream_t st) {
         const size_t lds = (size_t)(a.OH + a.R - 1) * pitch;
         if (lds <= 60 * 1024) {
             const bool two = a.S > 4;
+            const dim3 thr(dw_threads(a.OH, a.OW, true));
             if (a.dgrad) {
-                if (two) launch_timed(kt, (dw_conv_fast_kernel<true, 2>), dim3(a.N * a.C), dim3(256), lds, st, a, pitch);
-                else launch_timed(kt, (dw_conv_fast_kernel<true, 1>), dim3(a.N * a.C), dim3(256), lds, st, a, pitch);
+                if (two) launch_timed(kt, (dw_conv_fast_kernel<true, 2>), dim3(a.N * a.C), thr, lds, st, a, pitch);
+                else launch_timed(kt, (dw_conv_fast_kernel<true, 1>), dim3(a.N * a.C), thr, lds, st, a, pitch);
             } else {
-                if (two) launch_timed(kt, (dw_conv_fast_kernel<false, 2>), dim3(a.N * a.C), dim3(256), lds, st, a, pitch);
-                else launch_timed(kt, (dw_conv_fast_kernel<false, 1>), dim3(a.N * a.C), dim3(256), lds, st, a, pitch);
+                if (two) launch_timed(kt, (dw_conv_fast_kernel<false, 2>), dim3(a.N * a.C), thr, lds, st, a, pitch);
+                else launch_timed(kt, (dw_conv_fast_kernel<false, 1>), dim3(a.N * a.C), thr, lds, st, a, pitch);
             }
             return hipGetLastError();
         }
     }
     const size_t lds = ((size_t)a.IH * a.IW + 15) & ~(size_t)15;
-    if (a.dgrad) launch_timed(kt, (dw_conv_kernel<true>), dim3(a.N * a.C), dim3(256), lds, st, a);
-    else launch_timed(kt, (dw_conv_kernel<false>), dim3(a.N * a.C), dim3(256), lds, st, a);
+    const dim3 thr(dw_threads(a.OH, a.OW, false));
+    if (a.dgrad) launch_timed(kt, (dw_conv_kernel<true>), dim3(a.N * a.C), thr, lds, st, a);
+    else launch_timed(kt, (dw_conv_kernel<false>), dim3(a.N * a.C), thr, lds, st, a);
     return hipGetLastError();
+}
+
+// block size of the backward-weight pass: its tasks are the gradient plane's results, in quads on the stride-1 path
+int dw_wgrad_threads(int P, int Q, int R, int S, int stride_h, int stride_w) {
+    const bool fast = stride_h == 1 && stride_w == 1 && R == S && (R == 3 || R == 5);
+    return dw_threads(P, Q, fast);
 }
 
 hipError_t launch_dw_wgrad(const DwArgs& a, hipStream_t st) {
@@ -374,13 +394,14 @@ hipError_t launch_dw_wgrad(const DwArgs& a, hipStream_t st) {
             const size_t ldsf = (((size_t)(a.OH + a.R - 1) * pitch + 15) & ~(size_t)15) + (size_t)a.OH * gpitch;
             if (ldsf <= 60 * 1024) {
                 fast = true;
-                if (a.R == 3) launch_timed(kt, (dw_wgrad_fast_kernel<3, 3>), dim3(a.C, a.chunks), dim3(256), ldsf, st, a, pitch, gpitch);
-                else launch_timed(kt, (dw_wgrad_fast_kernel<5, 5>), dim3(a.C, a.chunks), dim3(256), ldsf, st, a, pitch, gpitch);
+                const dim3 thr(a.threads);
+                if (a.R == 3) launch_timed(kt, (dw_wgrad_fast_kernel<3, 3>), dim3(a.C, a.chunks), thr, ldsf, st, a, pitch, gpitch);
+                else launch_timed(kt, (dw_wgrad_fast_kernel<5, 5>), dim3(a.C, a.chunks), thr, ldsf, st, a, pitch, gpitch);
             }
         }
         if (!fast) {
             const size_t lds = (((size_t)a.IH * a.IW + 15) & ~(size_t)15) + (((size_t)a.OH * a.OW + 15) & ~(size_t)15);
-            launch_timed(kt, dw_wgrad_kernel, dim3(a.C, a.chunks), dim3(256), lds, st, a);
+            launch_timed(kt, dw_wgrad_kernel, dim3(a.C, a.chunks), dim3(a.threads), lds, st, a);
         }
     }
     hipError_t e = hipGetLastError();

@@ -197,12 +197,15 @@ struct DwArgs {
     float* out;
     int32_t* acc;                // nullable
     int32_t* partial;            // bwd-weight scratch [chunks][C*R*S]
-    int chunks;
+    int chunks;                  // bwd-weight: dw_wgrad_chunks(N, C, threads)
+    int threads;                 // bwd-weight: dw_wgrad_threads() of the layer
     int N, C, IH, IW, OH, OW, R, S;
     int stride_h, stride_w, pad_h, pad_w;
     int dgrad;
 };
-int dw_wgrad_chunks(int N, int C);
+int dw_threads(int OH, int OW, bool quads);       // block size by plane size (quads: four results per task)
+int dw_wgrad_threads(int P, int Q, int R, int S, int stride_h, int stride_w);
+int dw_wgrad_chunks(int N, int C, int threads);
 hipError_t launch_dw_conv(const DwArgs& a, hipStream_t st);
 hipError_t launch_dw_wgrad(const DwArgs& a, hipStream_t st);
 

@@ -154,3 +154,56 @@ def make_dy(L: Layer, cfg: int, li: int, seed: int = 0) -> np.ndarray:
 def make_layer_inputs(cfg: int, li: int, seed: int = 0):
     L = CONFIGS[cfg][li]
     return L, make_x(L, cfg, li, seed), make_w(L, cfg, li, seed), make_dy(L, cfg, li, seed)
+
+
+def mobilenetv2_layers(N: int = 32):
+    """[(how often, Layer)] for every convolution of MobileNetV2 (width 1.0, 224 x 224 images): the
+    3x3 stride-2 stem, per inverted-residual block the 1x1 expansion, the 3x3 depthwise layer
+    (stride 2 in the first block of four stages) and the 1x1 projection, and the last 1x1 layer."""
+    out = []
+
+    def add(name, C, H, K, R, s, g=1):
+        L = Layer(name, N, C, H, H, K, R, R, stride=(s, s), pad=(R // 2, R // 2), groups=g, x_dist="relu6",
+                  dy_df=2.0, dy_scale=1e-4, dy_outliers=False)
+        for i, (cnt, Lo) in enumerate(out):
+            if Lo == L:
+                out[i] = (cnt + 1, Lo)
+                return
+        out.append((1, L))
+
+    add("stem_3x3_s2", 3, 224, 32, 3, 2)
+    H, Cin = 112, 32
+    for t, c, n, s in ((1, 16, 1, 1), (6, 24, 2, 2), (6, 32, 3, 2), (6, 64, 4, 2), (6, 96, 3, 1), (6, 160, 3, 2), (6, 320, 1, 1)):
+        for i in range(n):
+            st = s if i == 0 else 1
+            hid = Cin * t
+            if t != 1:
+                add(f"expand_{Cin}_{hid}_at{H}", Cin, H, hid, 1, 1)
+            add(f"depthwise_{hid}_at{H}_s{st}", hid, H, hid, 3, st, hid)
+            H //= st
+            add(f"project_{hid}_{c}_at{H}", hid, H, c, 1, 1)
+            Cin = c
+    add("last_1x1", 320, 7, 1280, 1, 1)
+    return out
+
+
+def inceptionv3_layers(N: int = 32):
+    """[(1, Layer)] for the distinct kinds of convolution in InceptionV3 (299 x 299 images): the
+    unpadded 3x3 stem layers, 1x1 / 5x5 / 3x3 branches at 35 x 35, the unpadded stride-2 reductions,
+    the 1x7 / 7x1 pairs at 17 x 17, the 1x3 / 3x1 pairs at 8 x 8 and the classifier."""
+    sh = [("stem_3x3_s2", 3, 299, 32, 3, 3, 2, 0, 0), ("stem_3x3", 32, 149, 32, 3, 3, 1, 0, 0),
+          ("stem_3x3_pad", 32, 147, 64, 3, 3, 1, 1, 1), ("stem_1x1", 64, 73, 80, 1, 1, 1, 0, 0),
+          ("stem_3x3_192", 80, 73, 192, 3, 3, 1, 0, 0),
+          ("a_1x1_64", 192, 35, 64, 1, 1, 1, 0, 0), ("a_1x1_48", 192, 35, 48, 1, 1, 1, 0, 0),
+          ("a_5x5", 48, 35, 64, 5, 5, 1, 2, 2), ("a_3x3_64_96", 64, 35, 96, 3, 3, 1, 1, 1),
+          ("a_3x3_96_96", 96, 35, 96, 3, 3, 1, 1, 1), ("a_1x1_288", 288, 35, 64, 1, 1, 1, 0, 0),
+          ("reduce_a_3x3_s2", 288, 35, 384, 3, 3, 2, 0, 0), ("reduce_a_3x3_s2_96", 96, 35, 96, 3, 3, 2, 0, 0),
+          ("b_1x1_128", 768, 17, 128, 1, 1, 1, 0, 0), ("b_1x7_128", 128, 17, 128, 1, 7, 1, 0, 3),
+          ("b_7x1_192", 128, 17, 192, 7, 1, 1, 3, 0), ("b_1x7_160", 160, 17, 160, 1, 7, 1, 0, 3),
+          ("b_1x1_192", 768, 17, 192, 1, 1, 1, 0, 0),
+          ("reduce_b_3x3_s2_320", 192, 17, 320, 3, 3, 2, 0, 0), ("reduce_b_3x3_s2_192", 192, 17, 192, 3, 3, 2, 0, 0),
+          ("c_1x1_320", 1280, 8, 320, 1, 1, 1, 0, 0), ("c_1x3", 384, 8, 384, 1, 3, 1, 0, 1),
+          ("c_3x1", 384, 8, 384, 3, 1, 1, 1, 0), ("c_3x3_448", 448, 8, 384, 3, 3, 1, 1, 1),
+          ("c_1x1_2048", 2048, 8, 448, 1, 1, 1, 0, 0), ("fc", 2048, 1, 1000, 1, 1, 1, 0, 0)]
+    return [(1, Layer(name, N, C, H, H, K, R, S, stride=(s, s), pad=(ph, pw), x_dist="relu", dy_scale=1e-4))
+            for name, C, H, K, R, S, s, ph, pw in sh]
