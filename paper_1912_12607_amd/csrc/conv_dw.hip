@@ -13,8 +13,11 @@ constexpr int DW_MAX_TAPS = 64;   // R*S limit of the depthwise kernels
 
 // One block per (n,c) plane.  Forward: in = codes of a, gather ih = oh*stride - pad + r.
 // Backward-data: in = codes of g_z, gather ih = (oh + pad - r)/stride when divisible.
-template <bool DGRAD>
-__global__ __launch_bounds__(256) void dw_conv_kernel(const DwArgs a) {
+// ST: both strides when known at compile time (2: the divisions below become shifts), 0 = any.
+// NT: threads per block (64, 128 or 256 by plane size, dw_threads()).
+template <bool DGRAD, int ST, int NT>
+__global__ __launch_bounds__(NT) void dw_conv_kernel(const DwArgs a) {
+    const int stride_h = ST ? ST : a.stride_h, stride_w = ST ? ST : a.stride_w;
     extern __shared__ __attribute__((aligned(16))) int8_t plane[];
     __shared__ int wtap[DW_MAX_TAPS];
     const int nc = blockIdx.x;
@@ -22,16 +25,16 @@ __global__ __launch_bounds__(256) void dw_conv_kernel(const DwArgs a) {
     const int IHW = a.IH * a.IW, OHW = a.OH * a.OW, RS = a.R * a.S;
     const int8_t* __restrict__ src = a.a + (size_t)nc * IHW;
     if ((IHW & 15) == 0) {
-        for (int i = threadIdx.x; i < (IHW >> 4); i += blockDim.x)
+        for (int i = threadIdx.x; i < (IHW >> 4); i += NT)
             reinterpret_cast<uint4*>(plane)[i] = reinterpret_cast<const uint4*>(src)[i];
     } else {
-        for (int i = threadIdx.x; i < IHW; i += blockDim.x) plane[i] = src[i];
+        for (int i = threadIdx.x; i < IHW; i += NT) plane[i] = src[i];
     }
     if (threadIdx.x < RS) wtap[threadIdx.x] = (int)a.b[(size_t)c * RS + threadIdx.x];
     __syncthreads();
 
     const float scale = __fmul_rn(a.sa[0], a.sb[0]);
-    for (int o = threadIdx.x; o < OHW; o += blockDim.x) {
+    for (int o = threadIdx.x; o < OHW; o += NT) {
         const int oh = o / a.OW, ow = o - oh * a.OW;
         int sum = 0;
         if (DGRAD) {
@@ -40,23 +43,23 @@ __global__ __launch_bounds__(256) void dw_conv_kernel(const DwArgs a) {
             // above; the same along w.  Two divisions per pixel instead of one per tap, and the taps
             // that never divide are not visited at all.
             const int ph = oh + a.pad_h, pw = ow + a.pad_w;
-            const int qh = ph / a.stride_h, qw = pw / a.stride_w;
-            const int r0 = ph - qh * a.stride_h, s0 = pw - qw * a.stride_w;
+            const int qh = ph / stride_h, qw = pw / stride_w;
+            const int r0 = ph - qh * stride_h, s0 = pw - qw * stride_w;
             int ih = qh;
-            for (int r = r0; r < a.R && ih >= 0; r += a.stride_h, --ih) {
+            for (int r = r0; r < a.R && ih >= 0; r += stride_h, --ih) {
                 if (ih >= a.IH) continue;
                 int iw = qw;
-                for (int s = s0; s < a.S && iw >= 0; s += a.stride_w, --iw) {
+                for (int s = s0; s < a.S && iw >= 0; s += stride_w, --iw) {
                     if (iw >= a.IW) continue;
                     sum += (int)plane[ih * a.IW + iw] * wtap[r * a.S + s];
                 }
             }
         } else {
             for (int r = 0; r < a.R; ++r) {
-                const int ih = oh * a.stride_h - a.pad_h + r;
+                const int ih = oh * stride_h - a.pad_h + r;
                 if ((unsigned)ih >= (unsigned)a.IH) continue;
                 for (int s = 0; s < a.S; ++s) {
-                    const int iw = ow * a.stride_w - a.pad_w + s;
+                    const int iw = ow * stride_w - a.pad_w + s;
                     if ((unsigned)iw >= (unsigned)a.IW) continue;
                     sum += (int)plane[ih * a.IW + iw] * wtap[r * a.S + s];
                 }
@@ -81,12 +84,13 @@ __global__ __launch_bounds__(256) void dw_conv_kernel(const DwArgs a) {
 constexpr int DW_FAST_MAXR = 8;
 
 // Copy plane `src` (IH x IW, contiguous) into LDS `dst` (rows of `pitch` bytes) at (top, left).
+template <int NT>
 __device__ __forceinline__ void dw_fill_plane(const int8_t* __restrict__ src, int IH, int IW, int8_t* dst,
                                               int pitch, int top, int left) {
     const int IHW = IH * IW;
     if ((IHW & 15) == 0) {
         // 16 source bytes per thread and pass; row / column advance without divisions
-        for (int i = threadIdx.x; i < (IHW >> 4); i += blockDim.x) {
+        for (int i = threadIdx.x; i < (IHW >> 4); i += NT) {
             const uint4 v = reinterpret_cast<const uint4*>(src)[i];
             const uint32_t d[4] = {v.x, v.y, v.z, v.w};
             int row = (16 * i) / IW, col = 16 * i - row * IW;
@@ -100,7 +104,7 @@ __device__ __forceinline__ void dw_fill_plane(const int8_t* __restrict__ src, in
             }
         }
     } else {
-        for (int i = threadIdx.x; i < IHW; i += blockDim.x) {
+        for (int i = threadIdx.x; i < IHW; i += NT) {
             const int row = i / IW, col = i - row * IW;
             dst[(row + top) * pitch + col + left] = src[i];
         }
@@ -108,17 +112,18 @@ __device__ __forceinline__ void dw_fill_plane(const int8_t* __restrict__ src, in
 }
 
 // Stage a plane with its zero border: `rows` x `pitch` bytes of LDS, the plane at (top, left).
+template <int NT>
 __device__ __forceinline__ void dw_stage_plane(const int8_t* __restrict__ src, int IH, int IW, int8_t* dst,
                                                int rows, int pitch, int top, int left) {
     const int ndw = rows * pitch >> 2;          // pitch is a multiple of 4
-    for (int i = threadIdx.x; i < ndw; i += blockDim.x) reinterpret_cast<uint32_t*>(dst)[i] = 0u;
+    for (int i = threadIdx.x; i < ndw; i += NT) reinterpret_cast<uint32_t*>(dst)[i] = 0u;
     __syncthreads();
-    dw_fill_plane(src, IH, IW, dst, pitch, top, left);
+    dw_fill_plane<NT>(src, IH, IW, dst, pitch, top, left);
     __syncthreads();
 }
 
-template <bool DGRAD, int SD>    // SD = dwords of packed weights per filter row (S <= 4*SD)
-__global__ __launch_bounds__(256) void dw_conv_fast_kernel(const DwArgs a, int pitch) {
+template <bool DGRAD, int SD, int NT>    // SD = dwords of packed weights per filter row (S <= 4*SD)
+__global__ __launch_bounds__(NT) void dw_conv_fast_kernel(const DwArgs a, int pitch) {
     extern __shared__ __attribute__((aligned(16))) int8_t plane[];
     __shared__ uint32_t wrow[DW_FAST_MAXR][SD];
     const int nc = blockIdx.x;
@@ -139,14 +144,14 @@ __global__ __launch_bounds__(256) void dw_conv_fast_kernel(const DwArgs a, int p
         }
         wrow[rp][d] = wv;
     }
-    dw_stage_plane(a.a + (size_t)nc * a.IH * a.IW, a.IH, a.IW, plane, a.OH + a.R - 1, pitch, top, left);
+    dw_stage_plane<NT>(a.a + (size_t)nc * a.IH * a.IW, a.IH, a.IW, plane, a.OH + a.R - 1, pitch, top, left);
 
     const float scale = __fmul_rn(a.sa[0], a.sb[0]);
     const int QW = (a.OW + 3) >> 2;
     const bool vec = (a.OW & 3) == 0;
     float* __restrict__ outp = a.out + (size_t)nc * OHW;
     int32_t* __restrict__ accp = a.acc ? a.acc + (size_t)nc * OHW : nullptr;
-    for (int t = threadIdx.x; t < a.OH * QW; t += blockDim.x) {
+    for (int t = threadIdx.x; t < a.OH * QW; t += NT) {
         const int oh = t / QW, ow = (t - oh * QW) << 2;
         int sum[4] = {0, 0, 0, 0};
         for (int rp = 0; rp < a.R; ++rp) {
@@ -187,6 +192,7 @@ __global__ __launch_bounds__(256) void dw_conv_fast_kernel(const DwArgs a, int p
 // Backward-weight: g_W[c,r,s] = sum_{n,p,q} g_z[n,c,p,q] * a[n,c,p*sh+r-ph,q*sw+s-pw].
 // grid (C, chunks); a block sums its share of the images for one channel and writes
 // partial[chunk][c][rs]; the reduce kernel adds the chunks and applies Eq.2.
+template <int NT>
 __device__ __forceinline__ void dw_block_sum_store(int v, int* red, int32_t* dst) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
@@ -195,12 +201,13 @@ __device__ __forceinline__ void dw_block_sum_store(int v, int* red, int32_t* dst
     __syncthreads();
     if (threadIdx.x == 0) {
         int t = red[0];
-        for (int w = 1; w < (int)(blockDim.x >> 6); ++w) t += red[w];
+        for (int w = 1; w < (int)(NT >> 6); ++w) t += red[w];
         *dst = t;
     }
 }
 
-__global__ __launch_bounds__(256) void dw_wgrad_kernel(const DwArgs a) {
+template <int NT>
+__global__ __launch_bounds__(NT) void dw_wgrad_kernel(const DwArgs a) {
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
     __shared__ int red[4];
     const int c = blockIdx.x, chunk = blockIdx.y;
@@ -220,10 +227,10 @@ __global__ __launch_bounds__(256) void dw_wgrad_kernel(const DwArgs a) {
             const int8_t* __restrict__ xsrc = a.a + ((size_t)n * a.C + c) * IHW;
             const int8_t* __restrict__ gsrc = a.b + ((size_t)n * a.C + c) * OHW;
             __syncthreads();
-            for (int i = threadIdx.x; i < IHW; i += blockDim.x) xs[i] = xsrc[i];
-            for (int i = threadIdx.x; i < OHW; i += blockDim.x) gs[i] = gsrc[i];
+            for (int i = threadIdx.x; i < IHW; i += NT) xs[i] = xsrc[i];
+            for (int i = threadIdx.x; i < OHW; i += NT) gs[i] = gsrc[i];
             __syncthreads();
-            for (int o = threadIdx.x; o < OHW; o += blockDim.x) {
+            for (int o = threadIdx.x; o < OHW; o += NT) {
                 const int p = o / a.OW, q = o - p * a.OW;
                 const int g = (int)gs[o];
 #pragma unroll
@@ -239,7 +246,7 @@ __global__ __launch_bounds__(256) void dw_wgrad_kernel(const DwArgs a) {
             }
         }
 #pragma unroll
-        for (int i = 0; i < 9; ++i) dw_block_sum_store(acc9[i], red, part + i);
+        for (int i = 0; i < 9; ++i) dw_block_sum_store<NT>(acc9[i], red, part + i);
     } else {
         // other filter sizes: one tap at a time, straight from global memory
         for (int rs = 0; rs < RS; ++rs) {
@@ -248,14 +255,14 @@ __global__ __launch_bounds__(256) void dw_wgrad_kernel(const DwArgs a) {
             for (int n = n0; n < n1; ++n) {
                 const int8_t* __restrict__ xsrc = a.a + ((size_t)n * a.C + c) * IHW;
                 const int8_t* __restrict__ gsrc = a.b + ((size_t)n * a.C + c) * OHW;
-                for (int o = threadIdx.x; o < OHW; o += blockDim.x) {
+                for (int o = threadIdx.x; o < OHW; o += NT) {
                     const int p = o / a.OW, q = o - p * a.OW;
                     const int ih = p * a.stride_h - a.pad_h + r, iw = q * a.stride_w - a.pad_w + s;
                     if ((unsigned)ih < (unsigned)a.IH && (unsigned)iw < (unsigned)a.IW)
                         v += (int)gsrc[o] * (int)xsrc[ih * a.IW + iw];
                 }
             }
-            dw_block_sum_store(v, red, part + rs);
+            dw_block_sum_store<NT>(v, red, part + rs);
         }
     }
 }
@@ -264,8 +271,8 @@ __global__ __launch_bounds__(256) void dw_wgrad_kernel(const DwArgs a) {
 // LDS (the input with its zero border, so that tap (r,s) of output column q starts at LDS column
 // q + s), a thread owns four consecutive outputs of a row and adds, per tap, one 4-way int8 dot
 // product of the four gradient codes with the four input codes they meet.
-template <int R, int S>
-__global__ __launch_bounds__(256) void dw_wgrad_fast_kernel(const DwArgs a, int pitch, int gpitch) {
+template <int R, int S, int NT>
+__global__ __launch_bounds__(NT) void dw_wgrad_fast_kernel(const DwArgs a, int pitch, int gpitch) {
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
     __shared__ int red[4];
     constexpr int SD = (S + 3) / 4;
@@ -279,7 +286,7 @@ __global__ __launch_bounds__(256) void dw_wgrad_fast_kernel(const DwArgs a, int 
     int8_t* gs = lds + ((xrows * pitch + 15) & ~15);    // OH x gpitch, zero tail columns
     {
         const int ndw = (((xrows * pitch + 15) & ~15) + a.OH * gpitch) >> 2;
-        for (int i = threadIdx.x; i < ndw; i += blockDim.x) reinterpret_cast<uint32_t*>(lds)[i] = 0u;
+        for (int i = threadIdx.x; i < ndw; i += NT) reinterpret_cast<uint32_t*>(lds)[i] = 0u;
     }
     int acc[R][S];
 #pragma unroll
@@ -291,10 +298,10 @@ __global__ __launch_bounds__(256) void dw_wgrad_fast_kernel(const DwArgs a, int 
         const int8_t* __restrict__ xsrc = a.a + ((size_t)n * a.C + c) * IHW;
         const int8_t* __restrict__ gsrc = a.b + ((size_t)n * a.C + c) * OHW;
         __syncthreads();   // the previous image's reads (and the zero fill) are done
-        dw_fill_plane(xsrc, a.IH, a.IW, xs, pitch, a.pad_h, a.pad_w);
-        dw_fill_plane(gsrc, a.OH, a.OW, gs, gpitch, 0, 0);
+        dw_fill_plane<NT>(xsrc, a.IH, a.IW, xs, pitch, a.pad_h, a.pad_w);
+        dw_fill_plane<NT>(gsrc, a.OH, a.OW, gs, gpitch, 0, 0);
         __syncthreads();
-        for (int t = threadIdx.x; t < a.OH * QW; t += blockDim.x) {
+        for (int t = threadIdx.x; t < a.OH * QW; t += NT) {
             const int p = t / QW, q = (t - p * QW) << 2;
             const int g4 = *reinterpret_cast<const int*>(gs + p * gpitch + q);
 #pragma unroll
@@ -314,7 +321,7 @@ __global__ __launch_bounds__(256) void dw_wgrad_fast_kernel(const DwArgs a, int 
 #pragma unroll
     for (int r = 0; r < R; ++r)
 #pragma unroll
-        for (int sx = 0; sx < S; ++sx) dw_block_sum_store(acc[r][sx], red, part + r * S + sx);
+        for (int sx = 0; sx < S; ++sx) dw_block_sum_store<NT>(acc[r][sx], red, part + r * S + sx);
 }
 
 __global__ __launch_bounds__(256) void dw_wgrad_reduce_kernel(const DwArgs a) {
@@ -360,21 +367,37 @@ hipError_t launch_dw_conv(const DwArgs& a, hipStream_t st) {
         const size_t lds = (size_t)(a.OH + a.R - 1) * pitch;
         if (lds <= 60 * 1024) {
             const bool two = a.S > 4;
-            const dim3 thr(dw_threads(a.OH, a.OW, true));
+            const int nt = dw_threads(a.OH, a.OW, true);
+#define FAST(DG, SDv)                                                                                              \
+    do {                                                                                                           \
+        if (nt == 64) launch_timed(kt, (dw_conv_fast_kernel<DG, SDv, 64>), dim3(a.N * a.C), dim3(64), lds, st, a, pitch);        \
+        else if (nt == 128) launch_timed(kt, (dw_conv_fast_kernel<DG, SDv, 128>), dim3(a.N * a.C), dim3(128), lds, st, a, pitch); \
+        else launch_timed(kt, (dw_conv_fast_kernel<DG, SDv, 256>), dim3(a.N * a.C), dim3(256), lds, st, a, pitch);               \
+    } while (0)
             if (a.dgrad) {
-                if (two) launch_timed(kt, (dw_conv_fast_kernel<true, 2>), dim3(a.N * a.C), thr, lds, st, a, pitch);
-                else launch_timed(kt, (dw_conv_fast_kernel<true, 1>), dim3(a.N * a.C), thr, lds, st, a, pitch);
+                if (two) FAST(true, 2); else FAST(true, 1);
             } else {
-                if (two) launch_timed(kt, (dw_conv_fast_kernel<false, 2>), dim3(a.N * a.C), thr, lds, st, a, pitch);
-                else launch_timed(kt, (dw_conv_fast_kernel<false, 1>), dim3(a.N * a.C), thr, lds, st, a, pitch);
+                if (two) FAST(false, 2); else FAST(false, 1);
             }
+#undef FAST
             return hipGetLastError();
         }
     }
     const size_t lds = ((size_t)a.IH * a.IW + 15) & ~(size_t)15;
-    const dim3 thr(dw_threads(a.OH, a.OW, false));
-    if (a.dgrad) launch_timed(kt, (dw_conv_kernel<true>), dim3(a.N * a.C), thr, lds, st, a);
-    else launch_timed(kt, (dw_conv_kernel<false>), dim3(a.N * a.C), thr, lds, st, a);
+    const int nt = dw_threads(a.OH, a.OW, false);
+    const bool s2 = a.stride_h == 2 && a.stride_w == 2;
+#define GEN(DG, STv)                                                                                      \
+    do {                                                                                                  \
+        if (nt == 64) launch_timed(kt, (dw_conv_kernel<DG, STv, 64>), dim3(a.N * a.C), dim3(64), lds, st, a);        \
+        else if (nt == 128) launch_timed(kt, (dw_conv_kernel<DG, STv, 128>), dim3(a.N * a.C), dim3(128), lds, st, a); \
+        else launch_timed(kt, (dw_conv_kernel<DG, STv, 256>), dim3(a.N * a.C), dim3(256), lds, st, a);               \
+    } while (0)
+    if (a.dgrad) {
+        if (s2) GEN(true, 2); else GEN(true, 0);
+    } else {
+        if (s2) GEN(false, 2); else GEN(false, 0);
+    }
+#undef GEN
     return hipGetLastError();
 }
 
@@ -394,14 +417,21 @@ hipError_t launch_dw_wgrad(const DwArgs& a, hipStream_t st) {
             const size_t ldsf = (((size_t)(a.OH + a.R - 1) * pitch + 15) & ~(size_t)15) + (size_t)a.OH * gpitch;
             if (ldsf <= 60 * 1024) {
                 fast = true;
-                const dim3 thr(a.threads);
-                if (a.R == 3) launch_timed(kt, (dw_wgrad_fast_kernel<3, 3>), dim3(a.C, a.chunks), thr, ldsf, st, a, pitch, gpitch);
-                else launch_timed(kt, (dw_wgrad_fast_kernel<5, 5>), dim3(a.C, a.chunks), thr, ldsf, st, a, pitch, gpitch);
+#define WFAST(Rv)                                                                                                   \
+    do {                                                                                                            \
+        if (a.threads == 64) launch_timed(kt, (dw_wgrad_fast_kernel<Rv, Rv, 64>), dim3(a.C, a.chunks), dim3(64), ldsf, st, a, pitch, gpitch);        \
+        else if (a.threads == 128) launch_timed(kt, (dw_wgrad_fast_kernel<Rv, Rv, 128>), dim3(a.C, a.chunks), dim3(128), ldsf, st, a, pitch, gpitch); \
+        else launch_timed(kt, (dw_wgrad_fast_kernel<Rv, Rv, 256>), dim3(a.C, a.chunks), dim3(256), ldsf, st, a, pitch, gpitch);                      \
+    } while (0)
+                if (a.R == 3) WFAST(3); else WFAST(5);
+#undef WFAST
             }
         }
         if (!fast) {
             const size_t lds = (((size_t)a.IH * a.IW + 15) & ~(size_t)15) + (((size_t)a.OH * a.OW + 15) & ~(size_t)15);
-            launch_timed(kt, dw_wgrad_kernel, dim3(a.C, a.chunks), dim3(a.threads), lds, st, a);
+            if (a.threads == 64) launch_timed(kt, dw_wgrad_kernel<64>, dim3(a.C, a.chunks), dim3(64), lds, st, a);
+            else if (a.threads == 128) launch_timed(kt, dw_wgrad_kernel<128>, dim3(a.C, a.chunks), dim3(128), lds, st, a);
+            else launch_timed(kt, dw_wgrad_kernel<256>, dim3(a.C, a.chunks), dim3(256), lds, st, a);
         }
     }
     hipError_t e = hipGetLastError();
