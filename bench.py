@@ -32,7 +32,8 @@ VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 
 # HBM bytes per launch from rocprofv3 counter runs (FETCH_SIZE + WRITE_SIZE, each scaled by what the same
 # counter reads for a copy kernel of known size); keyed by (config, layer, kernel).  See profiles/.
-TRAFFIC = {(1, 0, "dsgc_sweep_kernel"): 50979 * 1024}
+TRAFFIC = {(1, 0, "dsgc_sweep_kernel"): 50979 * 1024,
+           (1, 0, "band_kernel"): 63166 * 1024}        # mean of the forward and the backward-data launch
 
 def algorithmic(L, n_cand):
     """Algorithmic HBM bytes and arithmetic of one step, per kernel name (what the method must move
