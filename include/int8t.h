@@ -144,10 +144,11 @@ int8t_status int8t_quantize(const float *x_dev, const int dims[4], int8t_kind ki
                             void *ws_dev, size_t ws_bytes, void *stream);
 
 /*
- * Eq.1 for several tensors at once (round to nearest only, no deviation output): the result of
- * each item is exactly what int8t_quantize(..., INT8T_ROUND_NEAREST_EVEN, ...) writes for it, but
- * all absmax passes share one launch and all quantize passes another.  Meant for the activations and
- * the weights of a layer, or the weights of many layers: a small tensor no longer costs two kernel
+ * Eq.1 / Eq.3 for several tensors at once (no deviation output): the result of each item is exactly
+ * what int8t_quantize(..., mode, seed, ...) writes for it, but all absmax passes share one launch
+ * and all quantize passes another.  Meant for the activations and the weights of a layer -- and, in
+ * an iteration that keeps the clip value of an earlier search (Periodic Update, Sec.3.4), its
+ * output gradient too -- or the weights of many layers: a small tensor no longer costs two kernel
  * launches of its own.
  *   items    host array of `count` (1 .. INT8T_MAX_BATCH) items, read before the call returns;
  *            fields as the arguments of the same names of int8t_quantize
@@ -162,6 +163,8 @@ typedef struct int8t_quantize_item {
     const float *clip_dev;
     int8_t *q_dev;
     float *scale_dev;
+    int8t_round mode;
+    uint64_t seed;             /* used by INT8T_ROUND_STOCHASTIC only */
 } int8t_quantize_item;
 size_t int8t_quantize_batch_workspace_bytes(int count, const int8t_quantize_item *items);
 int8t_status int8t_quantize_batch(int count, const int8t_quantize_item *items,

@@ -33,7 +33,7 @@ class KernelTime(C.Structure):
 
 class QuantizeItem(C.Structure):
     _fields_ = [("x_dev", C.c_void_p), ("dims", C.c_int * 4), ("kind", C.c_int), ("clip_dev", C.c_void_p),
-                ("q_dev", C.c_void_p), ("scale_dev", C.c_void_p)]
+                ("q_dev", C.c_void_p), ("scale_dev", C.c_void_p), ("mode", C.c_int), ("seed", C.c_uint64)]
 
 
 class ConvDesc(C.Structure):
@@ -149,9 +149,12 @@ def int8t_quantize(x, dims, kind, clip, mode, seed, q, scale, deviation=None, ws
 
 
 def _items(items):
-    """[(x, dims, kind, clip or None, q, scale), ...] -> ctypes array; the tensors must stay alive until the call returns."""
+    """[(x, dims, kind, clip or None, q, scale[, mode, seed]), ...] -> ctypes array (round to nearest
+    unless mode and seed are given); the tensors must stay alive until the call returns."""
     arr = (QuantizeItem * len(items))()
-    for a, (x, dims, kind, clip, q, scale) in zip(arr, items):
+    for a, it in zip(arr, items):
+        x, dims, kind, clip, q, scale = it[:6]
+        a.mode, a.seed = (int(it[6]), int(it[7])) if len(it) > 6 else (ROUND_NEAREST_EVEN, 0)
         a.x_dev, a.kind, a.clip_dev, a.q_dev, a.scale_dev = _ptr(x), kind, _ptr(clip), _ptr(q), _ptr(scale)
         for j in range(4):
             a.dims[j] = int(dims[j])

@@ -4,6 +4,7 @@
 
 #include "../../include/int8t.h"
 #include "kernels.h"
+#include "device_common.h"
 
 using namespace int8t;
 
@@ -244,6 +245,7 @@ int8t_status int8t_quantize_batch(int count, const int8t_quantize_item* items, v
         if (!dims_ok(it.dims, &n)) return INT8T_ERR_SHAPE;
         if (it.kind != INT8T_ACT && it.kind != INT8T_WGT && it.kind != INT8T_ACT_PLANAR && it.kind != INT8T_WGT_PLANAR)
             return INT8T_ERR_ARG;
+        if (it.mode != INT8T_ROUND_NEAREST_EVEN && it.mode != INT8T_ROUND_STOCHASTIC) return INT8T_ERR_ARG;
         if (!aligned16(it.x_dev) || !aligned16(it.q_dev) || !aligned4(it.scale_dev) || !aligned4(it.clip_dev))
             return INT8T_ERR_ARG;
         if (it.kind == INT8T_ACT && (size_t)it.dims[0] * pad16(it.dims[1]) * it.dims[2] * it.dims[3] > kMaxElems)
@@ -281,6 +283,9 @@ int8t_status int8t_quantize_batch(int count, const int8t_quantize_item* items, v
         q.clip = it.clip_dev; q.absmax_part = part; q.nparts = nb; q.q = it.q_dev; q.scale = it.scale_dev;
         const int8t_kind pk = pass_kind(it.dims, it.kind);
         q.kind = pk == INT8T_ACT ? 0 : pk == INT8T_WGT ? 1 : 2;
+        q.stoch = it.mode == INT8T_ROUND_STOCHASTIC;
+        q.seed_lo = (uint32_t)it.seed;
+        q.seed_hi = seed_hi_term(it.seed);
         quant_grid(q.kind, it.dims, &q.gx, &q.gy, &q.gz);
         q.block0 = (int)qblocks;
         qblocks += (long long)q.gx * q.gy * q.gz;

@@ -74,6 +74,8 @@ struct QuantBatchItem {
     float* scale;
     int kind;                    // 0 activations, 1 weights, 2 planar
     int block0, gx, gy, gz;      // its block range and virtual grid inside the launch
+    int stoch;                   // Eq.3 instead of Eq.1
+    uint32_t seed_lo, seed_hi;   // (uint32_t)seed, seed_hi_term(seed)
 };
 struct QuantBatch {
     int count;

@@ -588,11 +588,15 @@ __global__ __launch_bounds__(256) void quantize_wgt_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// Batched round-to-nearest quantization (Eq.1) of several tensors in one launch: the activations
-// and the weights of a layer, or the weights of many layers.  Small tensors otherwise pay a whole
+// Batched quantization (Eq.1, or Eq.3 per item) of several tensors in one launch: the activations
+// and the weights of a layer (and its output gradient when the clip value is kept), or the weights
+// of many layers.  Small tensors otherwise pay a whole
 // kernel launch each (a few microseconds of an idle GPU for a few thousand elements).  Block b
 // serves the tensor whose block range holds it and runs that tensor's ordinary pass.
 // ---------------------------------------------------------------------------------------------
+// ANYSTOCH: some item rounds stochastically (Eq.3).  The round-to-nearest launch of a layer's a and
+// W is a kernel of its own, so that it keeps its register count beside the clip search.
+template <bool ANYSTOCH>
 __global__ __launch_bounds__(256) void quantize_batch_kernel(const QuantBatch b) {
     // one LDS area for whichever pass this block runs, sized by the host for the tensors of this launch
     // (a 3x3 weight tensor needs 2.3 KB of tile, not the 16 KB of the largest case: the kernel then fits
@@ -608,20 +612,31 @@ __global__ __launch_bounds__(256) void quantize_batch_kernel(const QuantBatch b)
     const int z = local / gxy, rem = local - z * gxy;
     const int y = rem / t.gx;
     const VBlock vb = {rem - y * t.gx, y, z, t.gx, t.gy, t.gz};
+    const bool st = ANYSTOCH && t.stoch;          // block-uniform
     if (t.kind == 0) {          // activations, N,C,H,W -> N,H,W,Cp
         const int HW = t.d2 * t.d3, Cp = (t.d1 + 15) & ~15;
-        if ((HW & 3) == 0)
-            quantize_act_body<false, false, true>(t.x, t.d1, Cp, HW, t.clip, t.absmax_part, t.nparts, 0u, 0u, t.q, t.scale, nullptr, vb, lds4, atile);
-        else
-            quantize_act_body<false, false, false>(t.x, t.d1, Cp, HW, t.clip, t.absmax_part, t.nparts, 0u, 0u, t.q, t.scale, nullptr, vb, lds4, atile);
+#define ACT(STv, VECv) quantize_act_body<STv, false, VECv>(t.x, t.d1, Cp, HW, t.clip, t.absmax_part, t.nparts, t.seed_lo, t.seed_hi, t.q, t.scale, nullptr, vb, lds4, atile)
+        if (ANYSTOCH && st) {
+            if ((HW & 3) == 0) ACT(ANYSTOCH, true); else ACT(ANYSTOCH, false);
+        } else {
+            if ((HW & 3) == 0) ACT(false, true); else ACT(false, false);
+        }
+#undef ACT
     } else if (t.kind == 1) {   // weights, two views
         const int Cp = (t.d1 + 15) & ~15, Kp = (t.d0 + 15) & ~15;
         const size_t off2 = (((size_t)t.d0 * t.d2 * t.d3 * Cp) + 255) & ~(size_t)255;
-        quantize_wgt_body<false, false>(t.x, t.d0, t.d1, t.d2, t.d3, Cp, Kp, off2, t.clip, t.absmax_part, t.nparts, 0u, 0u,
-                                        t.q, t.scale, nullptr, vb, lds4, smem);
+        if (ANYSTOCH && st)
+            quantize_wgt_body<ANYSTOCH, false>(t.x, t.d0, t.d1, t.d2, t.d3, Cp, Kp, off2, t.clip, t.absmax_part, t.nparts, t.seed_lo, t.seed_hi,
+                                               t.q, t.scale, nullptr, vb, lds4, smem);
+        else
+            quantize_wgt_body<false, false>(t.x, t.d0, t.d1, t.d2, t.d3, Cp, Kp, off2, t.clip, t.absmax_part, t.nparts, 0u, 0u,
+                                            t.q, t.scale, nullptr, vb, lds4, smem);
     } else {                    // planar
-        quantize_planar_body<false, false>(t.x, (size_t)t.d0 * t.d1 * t.d2 * t.d3, t.clip, t.absmax_part, t.nparts, 0u, 0u,
-                                           t.q, t.scale, nullptr, vb.x, vb.gx, lds4);
+        const size_t n = (size_t)t.d0 * t.d1 * t.d2 * t.d3;
+        if (ANYSTOCH && st)
+            quantize_planar_body<ANYSTOCH, false>(t.x, n, t.clip, t.absmax_part, t.nparts, t.seed_lo, t.seed_hi, t.q, t.scale, nullptr, vb.x, vb.gx, lds4);
+        else
+            quantize_planar_body<false, false>(t.x, n, t.clip, t.absmax_part, t.nparts, 0u, 0u, t.q, t.scale, nullptr, vb.x, vb.gx, lds4);
     }
 }
 
@@ -652,7 +667,10 @@ hipError_t launch_quantize_batch(const QuantBatch& b, int total_blocks, hipStrea
     }
     lds = (lds + 15) & ~(size_t)15;
     KernelTimer kt(KID_QUANTIZE_BATCH, st);
-    launch_timed(kt, quantize_batch_kernel, dim3(total_blocks), dim3(256), lds, st, b);
+    bool any_stoch = false;
+    for (int i = 0; i < b.count; ++i) any_stoch = any_stoch || b.it[i].stoch;
+    if (any_stoch) launch_timed(kt, quantize_batch_kernel<true>, dim3(total_blocks), dim3(256), lds, st, b);
+    else launch_timed(kt, quantize_batch_kernel<false>, dim3(total_blocks), dim3(256), lds, st, b);
     return hipGetLastError();
 }
 

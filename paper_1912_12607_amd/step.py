@@ -97,7 +97,9 @@ class LayerStep:
         nb = B.int8t_workspace_bytes(B.OP_CONV_BWD_DATA, self.desc)
         self.xw_items = [(self.x, L.x_shape, self.act_kind, None, self.xq, self.sx),
                          (self.w, L.w_shape, self.wgt_kind, None, self.wq, self.sw)]
-        self.ws_xw = torch.empty(B.int8t_quantize_batch_workspace_bytes(self.xw_items), dtype=u8, device=d)
+        # (sized for the call that also carries g_z, in the steps that keep the clip value)
+        self.ws_xw = torch.empty(B.int8t_quantize_batch_workspace_bytes(
+            self.xw_items + [(self.dy, L.y_shape, self.act_kind, self.clip, self.dyq, self.sdy)]), dtype=u8, device=d)
         self._side = None
         self.ws_fwd = torch.empty(nf, dtype=u8, device=d) if nf else None
         self.ws_bwd_data = torch.empty(nb, dtype=u8, device=d) if nb else None
@@ -155,10 +157,15 @@ class LayerStep:
         if overlap is None:
             overlap = search and two_stream_default(self.L)
         if not overlap:
-            self.quantize_xw(stream)
-            if search:
-                self.dsgc(seed, stream)
-            self.quantize_dy(seed, stream)
+            if not search and not self.requantize_deviation:
+                # the clip value is known: a, W and g_z in one batched call (one launch fewer)
+                B.int8t_quantize_batch(self.xw_items + [(self.dy, self.L.y_shape, self.act_kind, self.clip, self.dyq,
+                                                         self.sdy, B.ROUND_STOCHASTIC, seed)], self.ws_xw, stream)
+            else:
+                self.quantize_xw(stream)
+                if search:
+                    self.dsgc(seed, stream)
+                self.quantize_dy(seed, stream)
             self.fwd(stream)
             self.bwd_data(stream)
             self.bwd_weight(stream)

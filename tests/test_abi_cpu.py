@@ -145,7 +145,7 @@ def test_profile_entry_points_without_launches(lib):
 def test_quantize_batch_argument_errors(lib):
     class Item(C.Structure):
         _fields_ = [("x_dev", C.c_void_p), ("dims", C.c_int * 4), ("kind", C.c_int), ("clip_dev", C.c_void_p),
-                    ("q_dev", C.c_void_p), ("scale_dev", C.c_void_p)]
+                    ("q_dev", C.c_void_p), ("scale_dev", C.c_void_p), ("mode", C.c_int), ("seed", C.c_uint64)]
     lib.int8t_quantize_batch_workspace_bytes.restype = C.c_size_t
     lib.int8t_quantize_batch_workspace_bytes.argtypes = [C.c_int, C.POINTER(Item)]
     f = lib.int8t_quantize_batch
@@ -166,6 +166,9 @@ def test_quantize_batch_argument_errors(lib):
     items[1].kind = 9
     assert f(2, items, 0x4000, 1 << 20, None) == 3
     items[1].kind = 0
+    items[1].mode = 2                                              # neither nearest-even nor stochastic
+    assert f(2, items, 0x4000, 1 << 20, None) == 3
+    items[1].mode = 1
     items[1].dims[2] = 0
     assert f(2, items, 0x4000, 1 << 20, None) == 2                 # INT8T_ERR_SHAPE
     items[1].dims[2] = 4

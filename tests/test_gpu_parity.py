@@ -185,29 +185,32 @@ def test_quantize_batch_equals_single_calls_and_oracle():
     specs = [((3, 20, 6, 6), B.ACT, None),            # H*W a multiple of 4
              ((2, 7, 5, 3), B.ACT, None),             # H*W = 15: one pixel per lane
              ((40, 24, 3, 3), B.WGT, None),
-             ((5, 1, 3, 3), B.WGT_PLANAR, None),
              ((2, 9, 7, 7), B.ACT_PLANAR, 0.75),
-             ((130, 70, 1, 1), B.WGT, 1.5)]
+             ((130, 70, 1, 1), B.WGT, 1.5),
+             # stochastic items (Eq.3): every layout, with and without a clip value
+             ((2, 24, 6, 6), B.ACT, 1.25, 99), ((3, 3, 5, 7), B.ACT, None, 7), ((2, 5, 4, 4), B.ACT_PLANAR, None, 5)]
+    assert len(specs) == B.MAX_BATCH
     items, singles, host = [], [], []
-    for shape, kind, clip in specs:
+    for shape, kind, clip, *sd in specs:
+        mode, seed = (STO, sd[0]) if sd else (RTN, 0)
         x = (r.standard_normal(shape) * (1.0 + len(host))).astype(np.float32)
         xd = dev(x)
         cd = None if clip is None else dev(np.array([clip], np.float32))
         nq = B.int8t_code_bytes(shape, kind)
         qa, qb = (torch.full((nq,), 77, dtype=torch.int8, device=DEV) for _ in range(2))
         sa, sb = (torch.full((1,), -1.0, dtype=torch.float32, device=DEV) for _ in range(2))
-        items.append((xd, shape, kind, cd, qa, sa))
-        singles.append((xd, shape, kind, cd, qb, sb))
-        host.append((x, clip))
+        items.append((xd, shape, kind, cd, qa, sa, mode, seed))
+        singles.append((xd, shape, kind, cd, qb, sb, mode, seed))
+        host.append((x, clip, mode, seed))
     ws = torch.empty(B.int8t_quantize_batch_workspace_bytes(items), dtype=torch.uint8, device=DEV)
     B.int8t_quantize_batch(items, ws)
-    for xd, shape, kind, cd, qb, sb in singles:
+    for xd, shape, kind, cd, qb, sb, mode, seed in singles:
         w1 = torch.empty(max(256, B.int8t_quantize_workspace_bytes(shape, kind)), dtype=torch.uint8, device=DEV)
-        B.int8t_quantize(xd, shape, kind, cd, B.ROUND_NEAREST_EVEN, 0, qb, sb, None, w1)
+        B.int8t_quantize(xd, shape, kind, cd, mode, seed, qb, sb, None, w1)
     torch.cuda.synchronize()
-    for (xd, shape, kind, cd, qa, sa), (_, _, _, _, qb, sb), (x, clip) in zip(items, singles, host):
+    for (xd, shape, kind, cd, qa, sa, _, _), (_, _, _, _, qb, sb, _, _), (x, clip, mode, seed) in zip(items, singles, host):
         assert torch.equal(qa, qb) and torch.equal(sa, sb), (shape, kind)
-        want_q, want_s = oracle.quantize(x, c=clip)
+        want_q, want_s = oracle.quantize(x, c=clip, mode=mode, seed=seed)
         assert sa.item() == want_s
         if kind == B.ACT:
             assert np.array_equal(unpack_act(qa.cpu().numpy(), shape, False), want_q)
@@ -469,6 +472,24 @@ def test_two_stream_step_equals_one_stream_step(cfg, li):
         outs.append([t.clone() for t in (st.xq, st.wq, st.dyq, st.sx, st.sw, st.sdy, st.clip, st.dev_search,
                                           st.y, st.dx, st.dw, st.y_acc, st.dx_acc, st.dw_acc)])
     for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("cfg,li", [(0, 0), (3, 1), (5, 0)])
+def test_step_that_keeps_the_clip_equals_step_that_searches(cfg, li):
+    """Periodic Update: a step with search=False reuses the clip value in device memory (and quantizes
+    a, W and g_z in one batched call); with the same seed it must write what the searching step wrote."""
+    L, x, w, dy = inputs.make_layer_inputs(cfg, li)
+    st = LayerStep(L, n_cand=32, requantize_deviation=False)
+    st.upload(x, w, dy, inputs.default_ratios(32))
+    st.run(seed=3, search=True)
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (st.xq, st.wq, st.dyq, st.sx, st.sw, st.sdy, st.y, st.dx, st.dw)]
+    for t in (st.xq, st.wq, st.dyq, st.y, st.dx, st.dw):
+        t.zero_()
+    st.run(seed=3, search=False)
+    torch.cuda.synchronize()
+    for a, b in zip(want, (st.xq, st.wq, st.dyq, st.sx, st.sw, st.sdy, st.y, st.dx, st.dw)):
         assert torch.equal(a, b)
 
 
