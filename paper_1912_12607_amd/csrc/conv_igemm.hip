@@ -59,10 +59,29 @@ __device__ __forceinline__ DgradClass dgrad_class(const IgemmArgs& a, int cls) {
     return c;
 }
 
+// When only ONE class has taps (a 1x1 filter under a stride) the other pixels are zero, and the pass
+// is bound by writing them.  "Cell" form (CELL, stride 2 x 2 and an even row length): the columns are
+// the 2 x 2 cells of pixels, the tile runs the one class's taps, and the epilogue writes each cell
+// whole -- the value at the class's pixel, zeros around it -- as two 8-byte stores, so that a lane
+// stores neighbouring floats and a wave whole cache lines.  T = float (result) or int (partial sums,
+// accumulators); `o` is the cell's top left element (even: 8-byte aligned).
+template <typename T, typename T2>
+__device__ __forceinline__ void store_cell(T* __restrict__ dst, size_t o, int OW, bool second_row, int ch, int cw, T v) {
+    const T z = (T)0;
+    T2 top, bot;
+    top.x = (ch == 0 && cw == 0) ? v : z;
+    top.y = (ch == 0 && cw == 1) ? v : z;
+    bot.x = (ch == 1 && cw == 0) ? v : z;
+    bot.y = (ch == 1 && cw == 1) ? v : z;
+    *reinterpret_cast<T2*>(dst + o) = top;
+    if (second_row) *reinterpret_cast<T2*>(dst + o + OW) = bot;
+}
+
 // CLS (backward-data with a stride only): blockIdx.x = column tile * classes + class.
-template <int BM, int BN, bool DGRAD, bool CLS = false>
+template <int BM, int BN, bool DGRAD, bool CLS = false, bool CELL = false>
 __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmArgs a) {
     static_assert(DGRAD || !CLS, "residue classes exist in the backward-data pass only");
+    static_assert(CLS || !CELL, "the cell form is a residue-class form");
     constexpr int MI = BM / 64;   // 32-row MFMA tiles per wave
     constexpr int NJ = BN / 64;   // 32-column MFMA tiles per wave
     constexpr int NB = BN / 64;   // B-tile columns staged per thread
@@ -79,9 +98,15 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmArgs a) {
     DgradClass dc;
     int colblock = blockIdx.x;
     if (CLS) {
-        const int ncls = a.cls_h * a.cls_w;
-        colblock = blockIdx.x / ncls;
-        dc = dgrad_class(a, (int)blockIdx.x - colblock * ncls);
+        if (CELL) {
+            dc = dgrad_class(a, a.cell - 1);
+            dc.OHc = (a.OH + a.cls_h - 1) / a.cls_h;      // cells, not pixels of the class
+            dc.OWc = (a.OW + a.cls_w - 1) / a.cls_w;
+        } else {
+            const int ncls = a.cls_h * a.cls_w;
+            colblock = blockIdx.x / ncls;
+            dc = dgrad_class(a, (int)blockIdx.x - colblock * ncls);
+        }
     }
     const int OWc = CLS ? dc.OWc : a.OW;
     const int OHW = CLS ? dc.OHc * dc.OWc : OHWfull;     // columns per image
@@ -233,9 +258,11 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmArgs a) {
         if (col >= ncols) continue;
         const int n = col / OHW;
         int opix = col - n * OHW;
+        int ci = 0, cj = 0;
         if (CLS) {
-            const int ci = opix / OWc;
-            opix = (dc.ch + a.cls_h * ci) * a.OW + dc.cw + a.cls_w * (opix - ci * OWc);
+            ci = opix / OWc;
+            cj = opix - ci * OWc;
+            opix = (dc.ch + a.cls_h * ci) * a.OW + dc.cw + a.cls_w * cj;
         }
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
@@ -245,7 +272,16 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmArgs a) {
                 if (row < a.rows) {
                     const size_t idx = ((size_t)n * a.rows + row) * OHWfull + opix;
                     const int val = acc[i][j][v];
-                    if (split) {
+                    if (CELL) {
+                        const size_t o = ((size_t)n * a.rows + row) * OHWfull + (size_t)(2 * ci) * a.OW + 2 * cj;
+                        const bool two = 2 * ci + 1 < a.OH;
+                        if (split) {
+                            store_cell<int32_t, int2>(part, o, a.OW, two, dc.ch, dc.cw, val);
+                        } else {
+                            store_cell<float, float2>(a.out, o, a.OW, two, dc.ch, dc.cw, __fmul_rn((float)val, scale));
+                            if (a.acc) store_cell<int32_t, int2>(a.acc, o, a.OW, two, dc.ch, dc.cw, val);
+                        }
+                    } else if (split) {
                         part[idx] = val;
                     } else {
                         a.out[idx] = __fmul_rn((float)val, scale);
@@ -335,9 +371,10 @@ __device__ __forceinline__ void igd_wait_vmcnt() {
     else asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
 }
 
-template <bool DGRAD, int WM, int KG, int NSTAGE, bool CLS = false>
+template <bool DGRAD, int WM, int KG, int NSTAGE, bool CLS = false, bool CELL = false>
 __global__ __launch_bounds__(128 * WM, WM == 2 ? 2 : 1) void igemm_dma_kernel(const IgemmArgs a) {
     static_assert(DGRAD || !CLS, "residue classes exist in the backward-data pass only");
+    static_assert(CLS || !CELL, "the cell form is a residue-class form");
     constexpr int BM = 64 * WM, BN = IGD_BN, MI = 2, NJ = 4, NW = 2 * WM;
     constexpr int STAGE_SLOTS = (BM + BN) * KG;         // 16-byte slots per stage: A tile, then B tile
     constexpr int RPL = 64 / KG;                        // tile rows covered by one wave-wide load
@@ -365,10 +402,16 @@ __global__ __launch_bounds__(128 * WM, WM == 2 ? 2 : 1) void igemm_dma_kernel(co
     int cgroup = wg_i / rtiles;
     DgradClass dc;
     if (CLS) {
-        const int ncls = a.cls_h * a.cls_w;
-        const int g = cgroup / ncls;
-        dc = dgrad_class(a, cgroup - g * ncls);
-        cgroup = g;
+        if (CELL) {
+            dc = dgrad_class(a, a.cell - 1);
+            dc.OHc = (a.OH + a.cls_h - 1) / a.cls_h;      // cells, not pixels of the class
+            dc.OWc = (a.OW + a.cls_w - 1) / a.cls_w;
+        } else {
+            const int ncls = a.cls_h * a.cls_w;
+            const int g = cgroup / ncls;
+            dc = dgrad_class(a, cgroup - g * ncls);
+            cgroup = g;
+        }
     }
     const int OWc = CLS ? dc.OWc : a.OW;
     const int OHW = CLS ? dc.OHc * dc.OWc : OHWfull;     // columns per image
@@ -533,9 +576,11 @@ __global__ __launch_bounds__(128 * WM, WM == 2 ? 2 : 1) void igemm_dma_kernel(co
         if (col >= ncols) continue;
         const int n = col / OHW;
         int opix = col - n * OHW;
+        int ci = 0, cj = 0;
         if (CLS) {
-            const int ci = opix / OWc;
-            opix = (dc.ch + a.cls_h * ci) * a.OW + dc.cw + a.cls_w * (opix - ci * OWc);
+            ci = opix / OWc;
+            cj = opix - ci * OWc;
+            opix = (dc.ch + a.cls_h * ci) * a.OW + dc.cw + a.cls_w * cj;
         }
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
@@ -545,8 +590,15 @@ __global__ __launch_bounds__(128 * WM, WM == 2 ? 2 : 1) void igemm_dma_kernel(co
                 if (row < a.rows) {
                     const size_t idx = ((size_t)n * a.rows + row) * OHWfull + opix;
                     const int val = acc[i][j][v];
-                    a.out[idx] = __fmul_rn((float)val, scale);
-                    if (a.acc) a.acc[idx] = val;
+                    if (CELL) {
+                        const size_t o = ((size_t)n * a.rows + row) * OHWfull + (size_t)(2 * ci) * a.OW + 2 * cj;
+                        const bool two = 2 * ci + 1 < a.OH;
+                        store_cell<float, float2>(a.out, o, a.OW, two, dc.ch, dc.cw, __fmul_rn((float)val, scale));
+                        if (a.acc) store_cell<int32_t, int2>(a.acc, o, a.OW, two, dc.ch, dc.cw, val);
+                    } else {
+                        a.out[idx] = __fmul_rn((float)val, scale);
+                        if (a.acc) a.acc[idx] = val;
+                    }
                 }
             }
         }
@@ -557,6 +609,7 @@ namespace {
 // Shape of the GEMM(s) a launch runs.  A strided backward-data pass is stride_h * stride_w stride-1
 // problems, one per residue class of the pixels (dgrad_class): fewer columns and fewer taps each.
 struct IgemmShape {
+    int cell;          // 0, or 1 + the class of the cell form (store_cell)
     bool cls;
     int cls_h, cls_w;  // class strides (1, 1 when the pixels are not split)
     int ncls;
@@ -565,18 +618,29 @@ struct IgemmShape {
 };
 IgemmShape igemm_shape(const IgemmArgs& a) {
     IgemmShape g;
-    // Split when more than one class has taps.  With a single one (a 1x1 filter) the pass is bound by
-    // writing the result, mostly zeros, and a tile of neighbouring pixels writes whole cache lines.
-    // Nor on small images with a short reduction: a store instruction covers 32 pixels of a class, which
+    // Split when more than one class has taps; with a single one (a 1x1 filter) the cell form runs
+    // (store_cell).  No split on small images with a short reduction: a store instruction covers 32 pixels of a class, which
     // are runs of OW / stride_w strided floats; with runs under 12 pixels the scattered stores cost
     // more than the zeros do unless a pixel's reduction is long (17 x 17 image, 192 channels: 56 us
     // split against 51 whole; 14 x 14, 512 channels: 40 against 85).
     const int tap_classes = (a.R < a.stride_h ? a.R : a.stride_h) * (a.S < a.stride_w ? a.S : a.stride_w);
     const bool short_runs = a.OW / a.stride_w < 12 && a.R * a.S * a.Ca < 2048;
-    g.cls = a.dgrad && (a.stride_h > 1 || a.stride_w > 1) && tap_classes > 1 && !short_runs;
+    const bool strided = a.dgrad && (a.stride_h > 1 || a.stride_w > 1);
+    g.cell = 0;
+    if (strided && tap_classes == 1 && a.stride_h == 2 && a.stride_w == 2 && !(a.OW & 1)) {
+        // the class whose residue makes the filter's first tap divide: r0 = (ch + pad_h) mod stride_h = 0
+        const int ch = a.R < a.stride_h ? (a.stride_h - a.pad_h % a.stride_h) % a.stride_h : 0;
+        const int cw = a.S < a.stride_w ? (a.stride_w - a.pad_w % a.stride_w) % a.stride_w : 0;
+        g.cell = 1 + ch * a.stride_w + cw;
+    }
+    g.cls = strided && (g.cell || (tap_classes > 1 && !short_runs));
     g.cls_h = g.cls ? a.stride_h : 1;
     g.cls_w = g.cls ? a.stride_w : 1;
-    if (g.cls) {
+    if (g.cell) {
+        g.ncls = 1;
+        g.ncols = (long long)a.N * ((a.OH + g.cls_h - 1) / g.cls_h) * ((a.OW + g.cls_w - 1) / g.cls_w);
+        g.gran = (long long)((a.R + g.cls_h - 1) / g.cls_h) * ((a.S + g.cls_w - 1) / g.cls_w) * (a.Ca >> 4);
+    } else if (g.cls) {
         g.ncls = g.cls_h * g.cls_w;
         g.ncols = (long long)a.N * ((a.OH + g.cls_h - 1) / g.cls_h) * ((a.OW + g.cls_w - 1) / g.cls_w);
         g.gran = (long long)((a.R + g.cls_h - 1) / g.cls_h) * ((a.S + g.cls_w - 1) / g.cls_w) * (a.Ca >> 4);
@@ -594,31 +658,33 @@ bool igemm_wide(const IgemmArgs& a) {
 }
 }  // namespace
 
-template <bool DGRAD, int WM, int KG, int NSTAGE, bool CLS>
+template <bool DGRAD, int WM, int KG, int NSTAGE, bool CLS, bool CELL>
 static hipError_t launch_igemm_dma(const IgemmArgs& a, const IgemmShape& g, hipStream_t st, const KernelTimer& kt) {
     const size_t lds = (size_t)NSTAGE * (64 * WM + IGD_BN) * KG * 16;
     static std::atomic<unsigned long long> attr_done;
     {
-        hipError_t e = raise_dynamic_lds(reinterpret_cast<const void*>(igemm_dma_kernel<DGRAD, WM, KG, NSTAGE, CLS>), (int)lds, attr_done);
+        hipError_t e = raise_dynamic_lds(reinterpret_cast<const void*>(igemm_dma_kernel<DGRAD, WM, KG, NSTAGE, CLS, CELL>), (int)lds, attr_done);
         if (e != hipSuccess) return e;
     }
     const unsigned ctiles = (unsigned)((g.ncols + IGD_BN - 1) / IGD_BN), rtiles = (unsigned)((a.rows + 64 * WM - 1) / (64 * WM));
     dim3 grid(((ctiles + 7) / 8) * 8 * rtiles * (unsigned)g.ncls);
-    launch_timed(kt, (igemm_dma_kernel<DGRAD, WM, KG, NSTAGE, CLS>), grid, dim3(128 * WM), lds, st, a);
+    launch_timed(kt, (igemm_dma_kernel<DGRAD, WM, KG, NSTAGE, CLS, CELL>), grid, dim3(128 * WM), lds, st, a);
     return hipGetLastError();
 }
 template <int WM, int KG, int NSTAGE>
 static hipError_t launch_igemm_dma_any(const IgemmArgs& a, const IgemmShape& g, hipStream_t st, const KernelTimer& kt) {
-    if (!a.dgrad) return launch_igemm_dma<false, WM, KG, NSTAGE, false>(a, g, st, kt);
-    if (g.cls) return launch_igemm_dma<true, WM, KG, NSTAGE, true>(a, g, st, kt);
-    return launch_igemm_dma<true, WM, KG, NSTAGE, false>(a, g, st, kt);
+    if (!a.dgrad) return launch_igemm_dma<false, WM, KG, NSTAGE, false, false>(a, g, st, kt);
+    if (g.cell) return launch_igemm_dma<true, WM, KG, NSTAGE, true, true>(a, g, st, kt);
+    if (g.cls) return launch_igemm_dma<true, WM, KG, NSTAGE, true, false>(a, g, st, kt);
+    return launch_igemm_dma<true, WM, KG, NSTAGE, false, false>(a, g, st, kt);
 }
 template <int BM, int BN>
 static void launch_igemm_generic(const IgemmArgs& a, const IgemmShape& g, int ksplit, hipStream_t st, const KernelTimer& kt) {
     dim3 grid((unsigned)((g.ncols + BN - 1) / BN) * (unsigned)g.ncls, (unsigned)((a.rows + BM - 1) / BM), (unsigned)ksplit);
-    if (!a.dgrad) launch_timed(kt, (igemm_kernel<BM, BN, false, false>), grid, dim3(256), 0, st, a);
-    else if (g.cls) launch_timed(kt, (igemm_kernel<BM, BN, true, true>), grid, dim3(256), 0, st, a);
-    else launch_timed(kt, (igemm_kernel<BM, BN, true, false>), grid, dim3(256), 0, st, a);
+    if (!a.dgrad) launch_timed(kt, (igemm_kernel<BM, BN, false, false, false>), grid, dim3(256), 0, st, a);
+    else if (g.cell) launch_timed(kt, (igemm_kernel<BM, BN, true, true, true>), grid, dim3(256), 0, st, a);
+    else if (g.cls) launch_timed(kt, (igemm_kernel<BM, BN, true, true, false>), grid, dim3(256), 0, st, a);
+    else launch_timed(kt, (igemm_kernel<BM, BN, true, false, false>), grid, dim3(256), 0, st, a);
 }
 
 // Layers with few output tiles and a long reduction (a strided 3x3 on a small image, a fully
@@ -673,6 +739,7 @@ hipError_t launch_igemm(const IgemmArgs& a_in, hipStream_t st) {
     const IgemmShape g = igemm_shape(a);
     a.cls_h = g.cls_h;
     a.cls_w = g.cls_w;
+    a.cell = g.cell;
     const int ncols = a.N * a.OH * a.OW;
     // the split needs its scratch; without it the reduction simply stays whole
     a.ksplit = igemm_ksplit(a);

@@ -120,6 +120,7 @@ struct IgemmArgs {
     int dgrad;                   // 0: ih = oh*stride + r - pad;  1: ih = (oh + pad - r)/stride
     int C;                       // forward: channels in use (<= Ca); lets the launch recognise a layer for s2d.hip
     int8_t* s2d;                 // nullable scratch of igemm_s2d_bytes() bytes for the rewritten codes
+    int cell;                    // filled by launch_igemm(): 0, or 1 + the only residue class that has taps (cell form, conv_igemm.hip)
     int cls_h, cls_w;            // filled by launch_igemm(): strides of the residue classes a strided backward-data pass splits its pixels into (1 = not split)
     int32_t* partial;            // nullable scratch [ksplit][N][rows][OH*OW] of a split reduction
     size_t partial_bytes;

@@ -254,6 +254,11 @@ CONV_SHAPES = [
     (40, 520, 1, 1, 200, 1, 1, (1, 1), (0, 0), 1),
     # more strides
     (2, 64, 8, 8, 128, 1, 1, (2, 2), (0, 0), 1),       # 1x1 stride 2: most input pixels receive no gradient
+    (1, 16, 9, 8, 24, 1, 1, (2, 2), (1, 1), 1),        # ... odd height, padding: the pixels with taps are the odd ones
+    (1, 16, 9, 7, 24, 1, 1, (2, 2), (1, 1), 1),        # ... odd row length
+    (2, 8, 6, 10, 16, 1, 1, (3, 2), (0, 0), 1),
+    (1, 8, 5, 12, 8, 3, 1, (1, 2), (1, 0), 1),         # stride along the row only, three taps along the column
+    (2, 200, 8, 8, 520, 1, 1, (2, 2), (0, 0), 1),      # ... with a split reduction
     (2, 40, 9, 10, 72, 3, 3, (2, 2), (1, 1), 1),
     (1, 16, 13, 11, 24, 5, 3, (3, 2), (2, 1), 1),
     (1, 16, 7, 7, 16, 2, 2, (3, 3), (0, 0), 1),        # stride larger than the filter: pixels no tap reaches
