@@ -4,6 +4,8 @@
 // is not a dense contraction and the MFMA is of no use: every (n,c) plane is an independent 2-D
 // filter, staged in LDS and evaluated on the plain integer ALUs; the kernels are HBM bound
 // (1 byte in, 4 bytes out per element).
+#include <type_traits>
+
 #include "device_common.h"
 #include "kernels.h"
 
@@ -122,8 +124,11 @@ __device__ __forceinline__ void dw_stage_plane(const int8_t* __restrict__ src, i
     __syncthreads();
 }
 
-template <bool DGRAD, int SD, int NT>    // SD = dwords of packed weights per filter row (S <= 4*SD)
-__global__ __launch_bounds__(NT) void dw_conv_fast_kernel(const DwArgs a, int pitch) {
+// ST = 2 (forward only): the four outputs of a thread read windows that start two bytes apart, from
+// LDS row 2 * oh + r' and column 2 * ow; `rows` is the height of the staged area.
+template <bool DGRAD, int SD, int NT, int ST = 1>    // SD = dwords of packed weights per filter row (S <= 4*SD)
+__global__ __launch_bounds__(NT) void dw_conv_fast_kernel(const DwArgs a, int pitch, int rows) {
+    static_assert(ST == 1 || (ST == 2 && !DGRAD), "the strided form is the forward pass at stride 2");
     extern __shared__ __attribute__((aligned(16))) int8_t plane[];
     __shared__ uint32_t wrow[DW_FAST_MAXR][SD];
     const int nc = blockIdx.x;
@@ -144,7 +149,7 @@ __global__ __launch_bounds__(NT) void dw_conv_fast_kernel(const DwArgs a, int pi
         }
         wrow[rp][d] = wv;
     }
-    dw_stage_plane<NT>(a.a + (size_t)nc * a.IH * a.IW, a.IH, a.IW, plane, a.OH + a.R - 1, pitch, top, left);
+    dw_stage_plane<NT>(a.a + (size_t)nc * a.IH * a.IW, a.IH, a.IW, plane, rows, pitch, top, left);
 
     const float scale = __fmul_rn(a.sa[0], a.sb[0]);
     const int QW = (a.OW + 3) >> 2;
@@ -155,16 +160,18 @@ __global__ __launch_bounds__(NT) void dw_conv_fast_kernel(const DwArgs a, int pi
         const int oh = t / QW, ow = (t - oh * QW) << 2;
         int sum[4] = {0, 0, 0, 0};
         for (int rp = 0; rp < a.R; ++rp) {
-            const uint32_t* __restrict__ rowp = reinterpret_cast<const uint32_t*>(plane + (oh + rp) * pitch + ow);
-            uint32_t d[SD + 1];
+            const uint32_t* __restrict__ rowp = reinterpret_cast<const uint32_t*>(plane + (ST * oh + rp) * pitch + ST * ow);
+            uint32_t d[SD + ST];
 #pragma unroll
-            for (int k = 0; k <= SD; ++k) d[k] = rowp[k];
+            for (int k = 0; k < SD + ST; ++k) d[k] = rowp[k];
 #pragma unroll
             for (int k = 0; k < SD; ++k) {
                 const uint32_t wv = wrow[rp][k];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const uint32_t win = j == 0 ? d[k] : __builtin_amdgcn_alignbyte(d[k + 1], d[k], j);
+                    // output j's window starts ST * j bytes into the row segment
+                    const int dwi = k + (ST * j) / 4, sh = (ST * j) % 4;
+                    const uint32_t win = sh == 0 ? d[dwi] : __builtin_amdgcn_alignbyte(d[dwi + 1], d[dwi], sh);
                     sum[j] = __builtin_amdgcn_sdot4((int)win, (int)wv, sum[j], false);
                 }
             }
@@ -181,6 +188,86 @@ __global__ __launch_bounds__(NT) void dw_conv_fast_kernel(const DwArgs a, int pi
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 if (ow + j < a.OW) {
+                    outp[o + j] = __fmul_rn((float)sum[j], scale);
+                    if (accp) accp[o + j] = sum[j];
+                }
+            }
+        }
+    }
+}
+
+
+// ---------------------------------------------------------------------------------------------
+// Backward-data at stride 2 for an R x S filter known at compile time.  Pixel (h, w) is reached by
+// the taps r = r0 + 2a, r0 = (h + ph) & 1, from gradient row ((h + ph) >> 1) - a, and likewise
+// along w: the gradient plane sits in LDS at (TB, LB) inside a zeroed area, so no tap needs a bounds
+// test, a thread owns four consecutive pixels of a row (their column parities are known: w0 is a
+// multiple of 4), reads the few gradient bytes they share once per tap row, and picks each tap
+// row's weights by the row parity with selects -- no divisions, no loop over taps that never reach.
+// ---------------------------------------------------------------------------------------------
+template <int R, int S, int NT>
+__global__ __launch_bounds__(NT) void dw_dgrad_s2_kernel(const DwArgs a, int pitch, int rows) {
+    extern __shared__ __attribute__((aligned(16))) int8_t plane[];
+    constexpr int TB = (R - 1) / 2, LB = (S - 1) / 2, NA = (R + 1) / 2;
+    const int nc = blockIdx.x;
+    const int c = nc % a.C;
+    int wt[R][S];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int sx = 0; sx < S; ++sx) wt[r][sx] = (int)a.b[(size_t)c * (R * S) + r * S + sx];
+    dw_stage_plane<NT>(a.a + (size_t)nc * a.IH * a.IW, a.IH, a.IW, plane, rows, pitch, TB, LB);
+
+    const float scale = __fmul_rn(a.sa[0], a.sb[0]);
+    const int OHW = a.OH * a.OW;
+    const int QW = (a.OW + 3) >> 2;
+    const bool vec = (a.OW & 3) == 0;
+    const int p0 = a.pad_w & 1;                        // column parity of a thread's first pixel
+    float* __restrict__ outp = a.out + (size_t)nc * OHW;
+    int32_t* __restrict__ accp = a.acc ? a.acc + (size_t)nc * OHW : nullptr;
+    for (int t = threadIdx.x; t < a.OH * QW; t += NT) {
+        const int h = t / QW, w0 = (t - h * QW) << 2;
+        const int hh = h + a.pad_h;
+        const bool rodd = hh & 1;
+        const int8_t* __restrict__ base = plane + ((hh >> 1) + TB) * pitch + ((w0 + a.pad_w) >> 1) + LB;
+        int sum[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int aa = 0; aa < NA; ++aa) {
+            const int8_t* __restrict__ rowp = base - aa * pitch;
+            int v[LB + 3];
+#pragma unroll
+            for (int i = 0; i < LB + 3; ++i) v[i] = (int)rowp[i - LB];
+            int wr[S];                                 // weights of tap row r0 + 2 aa (zero beyond the filter)
+#pragma unroll
+            for (int sx = 0; sx < S; ++sx) {
+                const int we = wt[2 * aa][sx];
+                const int wo = (2 * aa + 1 < R) ? wt[2 * aa + 1 < R ? 2 * aa + 1 : 0][sx] : 0;     // (index kept inside the array)
+                wr[sx] = rodd ? wo : we;
+            }
+            auto row_sum = [&](auto P0) {
+                constexpr int p = decltype(P0)::value;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int q = (p + j) & 1, cr = (p + j) >> 1;
+#pragma unroll
+                    for (int b = 0; q + 2 * b < S; ++b) sum[j] += wr[q + 2 * b] * v[LB + cr - b];
+                }
+            };
+            if (p0) row_sum(std::integral_constant<int, 1>{});
+            else row_sum(std::integral_constant<int, 0>{});
+        }
+        const int o = h * a.OW + w0;
+        if (vec) {
+            *reinterpret_cast<float4*>(outp + o) = make_float4(__fmul_rn((float)sum[0], scale), __fmul_rn((float)sum[1], scale),
+                                                               __fmul_rn((float)sum[2], scale), __fmul_rn((float)sum[3], scale));
+            if (accp) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) accp[o + j] = sum[j];
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (w0 + j < a.OW) {
                     outp[o + j] = __fmul_rn((float)sum[j], scale);
                     if (accp) accp[o + j] = sum[j];
                 }
@@ -361,6 +448,53 @@ static int dw_fast_pitch(int OW, int S) {
 
 hipError_t launch_dw_conv(const DwArgs& a, hipStream_t st) {
     KernelTimer kt(KID_DW_CONV, st);
+    if (a.dgrad && a.stride_h == 2 && a.stride_w == 2 && a.R == a.S && (a.R == 3 || a.R == 5)) {
+        // backward-data at stride 2: gradient plane (IH x IW) at (TB, LB) in an area that reaches as far
+        // as the taps of the last pixels do
+        const int TB = (a.R - 1) / 2, LB = (a.S - 1) / 2;
+        int rows = ((a.OH - 1 + a.pad_h) >> 1) + TB + 1;
+        if (rows < TB + a.IH) rows = TB + a.IH;
+        int pitch = ((4 * ((a.OW + 3) / 4 - 1) + a.pad_w) >> 1) + LB + 3;
+        if (pitch < LB + a.IW) pitch = LB + a.IW;
+        pitch = (pitch + 3) & ~3;
+        const size_t lds = (size_t)rows * pitch;
+        if (lds <= 60 * 1024) {
+            const int nt = dw_threads(a.OH, a.OW, true);
+#define DG2(Rv)                                                                                                        \
+    do {                                                                                                               \
+        if (nt == 64) launch_timed(kt, (dw_dgrad_s2_kernel<Rv, Rv, 64>), dim3(a.N * a.C), dim3(64), lds, st, a, pitch, rows);        \
+        else if (nt == 128) launch_timed(kt, (dw_dgrad_s2_kernel<Rv, Rv, 128>), dim3(a.N * a.C), dim3(128), lds, st, a, pitch, rows); \
+        else launch_timed(kt, (dw_dgrad_s2_kernel<Rv, Rv, 256>), dim3(a.N * a.C), dim3(256), lds, st, a, pitch, rows);               \
+    } while (0)
+            if (a.R == 3) DG2(3); else DG2(5);
+#undef DG2
+            return hipGetLastError();
+        }
+    }
+    if (!a.dgrad && a.stride_h == 2 && a.stride_w == 2 && a.S <= 8 && a.R <= DW_FAST_MAXR) {
+        // forward at stride 2: the staged area holds the plane with its top / left border and reaches as
+        // far as the last output's window does (four outputs per thread: 8 * ceil(OW / 4) columns + the
+        // dwords of one row segment)
+        const int sd = (a.S + 3) / 4;
+        int pitch = 8 * ((a.OW + 3) / 4) + 4 * (sd + 2);
+        if (pitch < a.pad_w + a.IW) pitch = a.pad_w + a.IW;
+        pitch = (pitch + 3) & ~3;
+        int rows = 2 * (a.OH - 1) + a.R;
+        if (rows < a.pad_h + a.IH) rows = a.pad_h + a.IH;
+        const size_t lds = (size_t)rows * pitch;
+        if (lds <= 60 * 1024) {
+            const int nt = dw_threads(a.OH, a.OW, true);
+#define FAST2(SDv)                                                                                                       \
+    do {                                                                                                                 \
+        if (nt == 64) launch_timed(kt, (dw_conv_fast_kernel<false, SDv, 64, 2>), dim3(a.N * a.C), dim3(64), lds, st, a, pitch, rows);        \
+        else if (nt == 128) launch_timed(kt, (dw_conv_fast_kernel<false, SDv, 128, 2>), dim3(a.N * a.C), dim3(128), lds, st, a, pitch, rows); \
+        else launch_timed(kt, (dw_conv_fast_kernel<false, SDv, 256, 2>), dim3(a.N * a.C), dim3(256), lds, st, a, pitch, rows);               \
+    } while (0)
+            if (a.S > 4) FAST2(2); else FAST2(1);
+#undef FAST2
+            return hipGetLastError();
+        }
+    }
     if (a.stride_h == 1 && a.stride_w == 1 && a.S <= 8 && a.R <= DW_FAST_MAXR &&
         (a.dgrad ? (a.pad_h <= a.R - 1 && a.pad_w <= a.S - 1) : true)) {
         const int pitch = dw_fast_pitch(a.OW, a.S);
@@ -370,9 +504,9 @@ hipError_t launch_dw_conv(const DwArgs& a, hipStream_t st) {
             const int nt = dw_threads(a.OH, a.OW, true);
 #define FAST(DG, SDv)                                                                                              \
     do {                                                                                                           \
-        if (nt == 64) launch_timed(kt, (dw_conv_fast_kernel<DG, SDv, 64>), dim3(a.N * a.C), dim3(64), lds, st, a, pitch);        \
-        else if (nt == 128) launch_timed(kt, (dw_conv_fast_kernel<DG, SDv, 128>), dim3(a.N * a.C), dim3(128), lds, st, a, pitch); \
-        else launch_timed(kt, (dw_conv_fast_kernel<DG, SDv, 256>), dim3(a.N * a.C), dim3(256), lds, st, a, pitch);               \
+        if (nt == 64) launch_timed(kt, (dw_conv_fast_kernel<DG, SDv, 64>), dim3(a.N * a.C), dim3(64), lds, st, a, pitch, a.OH + a.R - 1);        \
+        else if (nt == 128) launch_timed(kt, (dw_conv_fast_kernel<DG, SDv, 128>), dim3(a.N * a.C), dim3(128), lds, st, a, pitch, a.OH + a.R - 1); \
+        else launch_timed(kt, (dw_conv_fast_kernel<DG, SDv, 256>), dim3(a.N * a.C), dim3(256), lds, st, a, pitch, a.OH + a.R - 1);               \
     } while (0)
             if (a.dgrad) {
                 if (two) FAST(true, 2); else FAST(true, 1);

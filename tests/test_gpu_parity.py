@@ -240,6 +240,11 @@ CONV_SHAPES = [
     (2, 20, 14, 18, 20, 3, 3, (2, 2), (1, 1), 20),    # depthwise stride 2, larger planes
     (1, 6, 13, 10, 6, 5, 5, (3, 3), (2, 2), 6),       # depthwise stride 3 under a 5 x 5 filter
     (1, 3, 9, 9, 3, 2, 2, (3, 2), (0, 1), 3),         # depthwise, stride above the filter height
+    (2, 9, 16, 24, 9, 3, 3, (2, 2), (1, 1), 9),       # depthwise stride 2: row length a multiple of 4 (16-byte stores)
+    (1, 4, 15, 13, 4, 5, 5, (2, 2), (2, 2), 4),       # 5 x 5 at stride 2, odd sizes
+    (1, 4, 12, 12, 4, 5, 5, (2, 2), (1, 2), 4),       # odd and even padding
+    (2, 3, 10, 9, 3, 3, 3, (2, 2), (0, 0), 3),        # no padding
+    (1, 2, 9, 12, 2, 4, 6, (2, 2), (1, 2), 2),        # even filter at stride 2 (forward fast path, generic backward)
     (33, 200, 1, 1, 70, 1, 1, (1, 1), (0, 0), 1),     # fully connected layer: 1x1 filter on a 1x1 image
     (2, 6, 8, 12, 6, 3, 5, (1, 1), (1, 2), 6),         # depthwise stride 1, 5-wide filter, row length a multiple of 4
     (1, 4, 10, 11, 4, 3, 3, (1, 1), (0, 0), 4),        # depthwise stride 1, no padding
