@@ -127,6 +127,22 @@ def _check(status: int):
         raise Int8tError(status)
 
 
+def bind(func, *cargs):
+    """A call with its arguments marshalled once: bind(lib.int8t_conv_fwd, byref(desc), _ptr(xq), ...)
+    returns f(stream_pointer) that appends the stream and checks the status.  For callers that issue the
+    same call on the same buffers many times (a training step): converting a dozen tensors to pointers
+    costs more host time per call than the launch itself."""
+    def call(stream_ptr):
+        status = func(*cargs, stream_ptr)
+        if status != OK:
+            raise Int8tError(status)
+    return call
+
+
+def stream_pointer(stream=None):
+    return _stream(stream)
+
+
 def int8t_status_string(status: int) -> str:
     return lib.int8t_status_string(status).decode()
 

@@ -26,9 +26,11 @@ def align256(v: int) -> int:
 def two_stream_default(L: Layer) -> bool:
     """Whether LayerStep.run(overlap=None) uses the second stream in a step that searches the clip: the
     search must be long enough to hide the other chain behind (the hand-over between the streams costs
-    about 10 us per step), and a depthwise layer's kernels fill the LDS and cannot share a compute
-    unit with the search."""
-    return L.groups == 1 and L.N * L.K * L.P * L.Q >= (1 << 21)
+    about 10 us per step, and the extra calls make a step cost the host about 100 us: over the dense
+    layers of ResNet-50, MobileNetV2 and InceptionV3 at batch 32-64 the second stream gains from about
+    6 M gradient elements on and loses up to 20 us below 5 M), and a depthwise layer's kernels fill the
+    LDS and cannot share a compute unit with the search."""
+    return L.groups == 1 and L.N * L.K * L.P * L.Q >= (6 << 20)
 
 
 _SIDE_STREAMS: dict = {}
@@ -104,6 +106,44 @@ class LayerStep:
         self.ws_fwd = torch.empty(nf, dtype=u8, device=d) if nf else None
         self.ws_bwd_data = torch.empty(nb, dtype=u8, device=d) if nb else None
 
+        self._bind_calls()
+
+    def _bind_calls(self):
+        """The calls of run() with their arguments marshalled once (the buffers live as long as the object):
+        nine calls with about ten arguments each otherwise cost the host 65 us per step, which is the whole
+        step time of a small layer."""
+        import ctypes as C
+        p, nb, lib, L = B._ptr, B._nbytes, B.lib, self.L
+        n_y = self.dy.numel()
+        self._items_xw = B._items(self.xw_items)
+        self._items_xwg = B._items(self.xw_items + [(self.dy, L.y_shape, self.act_kind, self.clip, self.dyq, self.sdy,
+                                                     B.ROUND_STOCHASTIC, 0)])
+        self._k_xw = B.bind(lib.int8t_quantize_batch, 2, self._items_xw, p(self.ws_xw), nb(self.ws_xw))
+        self._k_xwg = B.bind(lib.int8t_quantize_batch, 3, self._items_xwg, p(self.ws_xw), nb(self.ws_xw))
+        self._k_prepare = B.bind(lib.int8t_dsgc_prepare, p(self.dy), n_y, p(self.ws_dy), nb(self.ws_dy))
+        d = C.byref(self.desc)
+        self._k_fwd = B.bind(lib.int8t_conv_fwd, d, p(self.xq), p(self.sx), p(self.wq), p(self.sw), p(self.y), p(self.y_acc),
+                             p(self.ws_fwd), nb(self.ws_fwd))
+        self._k_bwd_data = B.bind(lib.int8t_conv_bwd_data, d, p(self.dyq), p(self.sdy), p(self.wq), p(self.sw), p(self.dx),
+                                  p(self.dx_acc), p(self.ws_bwd_data), nb(self.ws_bwd_data))
+        self._k_bwd_weight = B.bind(lib.int8t_conv_bwd_weight, d, p(self.xq), p(self.sx), p(self.dyq), p(self.sdy), p(self.dw),
+                                    p(self.dw_acc), p(self.ws), nb(self.ws))
+        a_search = (p(self.dy), n_y, p(self.ratios), self.n_cand, B.ROUND_STOCHASTIC)
+        b_search = (p(self.clip), p(self.dev_search), p(self.dev_all), p(self.ws_dy), nb(self.ws_dy))
+        a_qdy = (p(self.dy), B._dims(L.y_shape), self.act_kind, p(self.clip), B.ROUND_STOCHASTIC)
+        b_qdy = (p(self.dyq), p(self.sdy), p(self.dev_final if self.requantize_deviation else None), p(self.ws_dy), nb(self.ws_dy))
+
+        def k_search(seed, sp):
+            B._check(lib.int8t_dsgc_search(*a_search, seed, *b_search, sp))
+
+        def k_clip(seed, sp):
+            B._check(lib.int8t_dsgc_clip(*a_search, seed, *b_search, sp))
+
+        def k_qdy(seed, sp):
+            B._check(lib.int8t_quantize(*a_qdy, seed, *b_qdy, sp))
+
+        self._k_search, self._k_clip, self._k_qdy = k_search, k_clip, k_qdy
+
     def upload(self, x: np.ndarray, w: np.ndarray, dy: np.ndarray, ratios: np.ndarray):
         self.x.copy_(torch.from_numpy(np.ascontiguousarray(x)))
         self.w.copy_(torch.from_numpy(np.ascontiguousarray(w)))
@@ -157,18 +197,20 @@ class LayerStep:
         if overlap is None:
             overlap = search and two_stream_default(self.L)
         if not overlap:
+            sp = B.stream_pointer(stream)
             if not search and not self.requantize_deviation:
                 # the clip value is known: a, W and g_z in one batched call (one launch fewer)
-                B.int8t_quantize_batch(self.xw_items + [(self.dy, self.L.y_shape, self.act_kind, self.clip, self.dyq,
-                                                         self.sdy, B.ROUND_STOCHASTIC, seed)], self.ws_xw, stream)
+                self._items_xwg[2].seed = seed
+                self._k_xwg(sp)
             else:
-                self.quantize_xw(stream)
+                self._k_xw(sp)
                 if search:
-                    self.dsgc(seed, stream)
-                self.quantize_dy(seed, stream)
-            self.fwd(stream)
-            self.bwd_data(stream)
-            self.bwd_weight(stream)
+                    self._k_clip(seed, sp)
+                self._k_qdy(seed, sp)
+            self._k_fwd(sp)
+            if self.input_grad:
+                self._k_bwd_data(sp)
+            self._k_bwd_weight(sp)
             return
         main = stream if stream is not None else torch.cuda.current_stream()
         if self._side is None:
@@ -176,27 +218,27 @@ class LayerStep:
             self._ev_side = torch.cuda.Event()
             self._ev_main = torch.cuda.Event()
         side = self._side
+        mp, sp = B.stream_pointer(main), B.stream_pointer(side)
         # main stream: clip search, quantize g_z, then the two backward convolutions.
         # side stream: quantize a and W, forward convolution (needs nothing from the gradient chain).
         # It starts behind whatever is queued on the main stream up to the search's first pass (the
         # previous step's backward passes still read the codes that are about to be overwritten, and
         # that pass is bound by HBM like the side stream's kernels: beside each other they would only
         # slow each other down), i.e. together with the sweep.
-        n_y = self.dy.numel()
         if search:
-            B.int8t_dsgc_prepare(self.dy, n_y, self.ws_dy, main)
+            self._k_prepare(mp)
         self._ev_main.record(main)
         side.wait_event(self._ev_main)
-        self.quantize_xw(side)
-        self.fwd(side)
+        self._k_xw(sp)
+        self._k_fwd(sp)
         self._ev_side.record(side)
         if search:
-            B.int8t_dsgc_search(self.dy, n_y, self.ratios, self.n_cand, B.ROUND_STOCHASTIC, seed,
-                                self.clip, self.dev_search, self.dev_all, self.ws_dy, main)
-        self.quantize_dy(seed, main)
+            self._k_search(seed, mp)
+        self._k_qdy(seed, mp)
         main.wait_event(self._ev_side)
-        self.bwd_data(main)
-        self.bwd_weight(main)
+        if self.input_grad:
+            self._k_bwd_data(mp)
+        self._k_bwd_weight(mp)
 
     # -- host views of the library's code layouts (tests only need numpy reshapes) -----------------
     def codes_x(self) -> np.ndarray:
