@@ -82,6 +82,18 @@ def test_workspace_sizes(lib):
     assert lib.int8t_workspace_bytes(4, C.byref(bad), C.c_size_t(0), 0) == 0
 
 
+def test_dclr_scale_golden_table(lib):
+    # the library's host function against the fixture written from Eq.7 (tests/golden/dclr_eq7.txt)
+    n = 0
+    for line in open(os.path.join(ROOT, "tests", "golden", "dclr_eq7.txt")):
+        if line.startswith("#"):
+            continue
+        alpha, beta, d, phi = (float(v) for v in line.split())
+        assert lib.int8t_dclr_scale(d, alpha, beta) == pytest.approx(phi, rel=1e-15)
+        n += 1
+    assert n == 36
+
+
 def test_dclr_scale_eq7(lib):
     assert lib.int8t_dclr_scale(0.0, 20.0, 0.1) == 1.0
     assert lib.int8t_dclr_scale(0.05, 20.0, 0.1) == pytest.approx(math.exp(-1.0), rel=1e-15)
