@@ -330,6 +330,59 @@ def test_conv_three_passes_bit_exact(shape):
         assert np.all(np.abs(out - ref) <= REL_TOL * np.abs(ref)), name
 
 
+def test_conv_three_passes_random_shapes():
+    """120 seeded random small layers (filters 1..7, strides 1..3, any padding below the filter, dense
+    and depthwise, ragged channel counts): accumulators and results of all three passes, bit for bit."""
+    r = np.random.RandomState(2)
+    one = dev(np.array([1.0], np.float32))
+    done = 0
+    while done < 120:
+        dwise = r.rand() < 0.3
+        R, S = int(r.choice([1, 2, 3, 5, 7])), int(r.choice([1, 2, 3, 5, 7]))
+        if r.rand() < 0.5:
+            S = R
+        sh, sw = int(r.choice([1, 1, 2, 2, 3])), int(r.choice([1, 1, 2, 2, 3]))
+        if r.rand() < 0.6:
+            sw = sh
+        ph, pw = int(r.randint(0, R)), int(r.randint(0, S))
+        H, W = int(r.randint(R, 40)), int(r.randint(S, 40))
+        if r.rand() < 0.3:
+            W = (W + 3) & ~3
+        N = int(r.randint(1, 5))
+        if dwise:
+            C = K = g = int(r.randint(2, 20))
+        else:
+            C, K, g = int(r.choice([1, 3, 4, 16, 24, 40, 70, 130])), int(r.choice([4, 16, 24, 64, 72, 130, 250])), 1
+        od = oracle.make_desc(N, C, H, W, K, R, S, (sh, sw), (ph, pw), g)
+        P, Q = oracle.out_hw(od)
+        if P < 1 or Q < 1:
+            continue
+        done += 1
+        shape = (N, C, H, W, K, R, S, (sh, sw), (ph, pw), g)
+        gd = B.make_desc(*shape)
+        x = r.randint(-127, 128, size=(N, C, H, W)).astype(np.int8)
+        w = r.randint(-127, 128, size=(K, C // g, R, S)).astype(np.int8)
+        dy = r.randint(-127, 128, size=(N, K, P, Q)).astype(np.int8)
+        xq = dev(x.reshape(-1) if dwise else pack_act(x))
+        dyq = dev(dy.reshape(-1) if dwise else pack_act(dy))
+        wq = dev(w.reshape(-1) if dwise else pack_wgt(w))
+        ws = torch.empty(max(256, *(B.int8t_workspace_bytes(op, gd) for op in
+                                    (B.OP_CONV_FWD, B.OP_CONV_BWD_DATA, B.OP_CONV_BWD_WEIGHT))),
+                         dtype=torch.uint8, device=DEV)
+        for name, fn, a, b, so, want in (
+            ("fwd", B.int8t_conv_fwd, xq, wq, (N, K, P, Q), oracle.conv_fwd(od, x, w)),
+            ("bwd_data", B.int8t_conv_bwd_data, dyq, wq, (N, C, H, W), oracle.conv_bwd_data(od, dy, w)),
+            ("bwd_weight", B.int8t_conv_bwd_weight, xq, dyq, (K, C // g, R, S), oracle.conv_bwd_weight(od, x, dy)),
+        ):
+            out = torch.full(so, float("nan"), dtype=torch.float32, device=DEV)
+            acc = torch.full(so, -12345, dtype=torch.int32, device=DEV)
+            fn(gd, a, one, b, one, out, acc, ws)
+            torch.cuda.synchronize()
+            want32, _ = oracle.wrap32(want)
+            assert np.array_equal(acc.cpu().numpy(), want32), (name, shape)
+            assert np.array_equal(out.cpu().numpy(), want32.astype(np.float32)), (name, shape)   # scales are 1
+
+
 @pytest.mark.parametrize("shape", [
     (2, 256, 9, 9, 96, 3, 3, (1, 1), (1, 1), 1),       # split reduction in both passes
     (2, 3, 12, 10, 8, 7, 7, (2, 2), (3, 3), 1),        # forward pass on the space-to-depth codes
