@@ -115,6 +115,37 @@ def test_quantize_planar(shape, mode):
         assert abs(d - oracle.deviation(x, qo, so)) < DEV_TOL
 
 
+def test_quantize_random_shapes():
+    """Seeded random tensors in every layout (narrow and wide channel counts, 1 x 1 images, filters of 1 to
+    49 taps with ragged filter / channel counts), both rounding modes, with and without a clip value:
+    codes, scale and deviation against the oracle."""
+    r = np.random.RandomState(5)
+    for it in range(90):
+        kind = [B.ACT, B.WGT, B.ACT_PLANAR][it % 3]
+        if kind == B.WGT:
+            R, S = int(r.choice([1, 1, 2, 3, 7])), int(r.choice([1, 1, 3, 5, 7]))
+            shape = (int(r.choice([1, 5, 16, 17, 70, 130])), int(r.choice([1, 3, 16, 33, 64, 100, 200])), R, S)
+        else:
+            H, W = (1, 1) if r.rand() < 0.25 else (int(r.randint(1, 20)), int(r.randint(1, 20)))
+            shape = (int(r.randint(1, 6)), int(r.choice([1, 3, 16, 17, 48, 64, 130, 208])), H, W)
+        mode = STO if r.rand() < 0.5 else RTN
+        clip = None if r.rand() < 0.5 else float(r.uniform(0.5, 3.0))
+        seed = int(r.randint(0, 2 ** 31))
+        x = (r.standard_normal(shape) * 2).astype(np.float32)
+        q, s, d = gpu_quantize(x, kind, clip, mode, seed=seed, want_dev=True)
+        qo, so = oracle.quantize(x, c=clip, mode=mode, seed=seed)
+        assert s == so, (shape, kind, mode, clip)
+        if kind == B.ACT:
+            got = unpack_act(q, shape, False)
+        elif kind == B.WGT:
+            got, got2 = unpack_wgt(q, shape, False)
+            assert np.array_equal(got2, qo), (shape, kind, mode, clip)
+        else:
+            got = q.reshape(shape)
+        assert np.array_equal(got, qo), (shape, kind, mode, clip)
+        assert abs(d - oracle.deviation(x, qo, so)) < DEV_TOL, (shape, kind, mode, clip)
+
+
 def test_quantize_zero_tensor_and_nan():
     z = np.zeros((2, 5, 4, 4), np.float32)
     for mode in (RTN, STO):
