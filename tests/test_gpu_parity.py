@@ -193,6 +193,26 @@ def test_dsgc_small(n, mode):
     check_dsgc(g, inputs.default_ratios(32), mode, seed=n)
 
 
+def test_dsgc_random_cases():
+    """Seeded random lengths (incl. n mod 4 != 0 and lengths around the block / wave sizes), value
+    distributions, candidate sets (random, unsorted ratios) and seeds."""
+    r = np.random.RandomState(17)
+    sizes = [2, 5, 63, 64, 65, 255, 257, 1023, 4097, 65537, 262145] + [int(v) for v in r.randint(6, 300000, size=9)]
+    for n in sizes:
+        kind = r.randint(3)
+        if kind == 0:
+            g = (r.standard_t(2, size=n) * 10.0 ** r.uniform(-6, 1)).astype(np.float32)
+        elif kind == 1:
+            g = r.standard_normal(n).astype(np.float32)
+        else:
+            g = (r.uniform(-1, 1, size=n) * (r.rand(n) < 0.05)).astype(np.float32)       # mostly zeros
+            g[r.randint(n)] = 0.75
+        J = int(r.choice([1, 2, 5, 32, 40]))
+        ratios = r.uniform(0.01, 1.0, size=J).astype(np.float32)
+        mode = STO if r.rand() < 0.6 else RTN
+        check_dsgc(g, ratios, mode, seed=int(r.randint(0, 2 ** 31)))
+
+
 def test_dsgc_candidate_counts_and_degenerate():
     r = np.random.RandomState(5)
     g = (r.standard_t(3, size=50000) * 1e-3).astype(np.float32)
