@@ -257,6 +257,8 @@ def main():
             nst = max(20, args.steps // 10)
             for k in range(80):          # the first few dozen steps on fresh buffers run at up to twice the steady time
                 st.run(seed=k, overlap=overlap)
+            if overlap is None and period == 1:
+                st.tune()                # one or two streams for this layer, by measurement (untimed)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             for k in range(nst):

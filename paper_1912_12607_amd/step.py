@@ -103,6 +103,7 @@ class LayerStep:
         self.ws_xw = torch.empty(B.int8t_quantize_batch_workspace_bytes(
             self.xw_items + [(self.dy, L.y_shape, self.act_kind, self.clip, self.dyq, self.sdy)]), dtype=u8, device=d)
         self._side = None
+        self._tuned_overlap = None
         self.ws_fwd = torch.empty(nf, dtype=u8, device=d) if nf else None
         self.ws_bwd_data = torch.empty(nb, dtype=u8, device=d) if nb else None
 
@@ -195,7 +196,7 @@ class LayerStep:
         default priority.  Outputs are complete once the main stream is.  overlap=None decides by the
         layer (two_stream_default) and only in steps that search."""
         if overlap is None:
-            overlap = search and two_stream_default(self.L)
+            overlap = search and (self._tuned_overlap if self._tuned_overlap is not None else two_stream_default(self.L))
         if not overlap:
             sp = B.stream_pointer(stream)
             if not search and not self.requantize_deviation:
@@ -239,6 +240,29 @@ class LayerStep:
         if self.input_grad:
             self._k_bwd_data(mp)
         self._k_bwd_weight(mp)
+
+    def tune(self, steps: int = 40) -> bool:
+        """Choose between the one-stream and the two-stream arrangement of a searching step by timing both
+        on this layer's own buffers (the per-layer choice "before training" of the paper's Suppl. "INT8
+        Convolution", here between two schedules of the same kernels).  run(overlap=None) then follows the
+        measurement instead of two_stream_default().  Returns the choice.  The buffers must hold data
+        (upload() first); their contents are what a step leaves."""
+        import time
+        if self.depthwise:
+            self._tuned_overlap = False
+            return False
+        best = []
+        for overlap in (False, True):
+            for k in range(steps):
+                self.run(seed=k, overlap=overlap)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for k in range(steps):
+                self.run(seed=k, overlap=overlap)
+            torch.cuda.synchronize()
+            best.append(time.perf_counter() - t0)
+        self._tuned_overlap = best[1] < best[0]
+        return self._tuned_overlap
 
     # -- host views of the library's code layouts (tests only need numpy reshapes) -----------------
     def codes_x(self) -> np.ndarray:

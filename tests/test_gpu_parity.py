@@ -607,6 +607,21 @@ def test_step_that_keeps_the_clip_equals_step_that_searches(cfg, li):
         assert torch.equal(a, b)
 
 
+def test_tuned_schedule_writes_the_same_tensors():
+    L, x, w, dy = inputs.make_layer_inputs(1, 0)
+    st = LayerStep(L, n_cand=32, requantize_deviation=False)
+    st.upload(x, w, dy, inputs.default_ratios(32))
+    st.run(seed=4, overlap=False)
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (st.dyq, st.y, st.dx, st.dw, st.clip)]
+    choice = st.tune(steps=5)
+    assert choice in (True, False)
+    st.run(seed=4)                      # overlap=None: the tuned schedule
+    torch.cuda.synchronize()
+    for a, b in zip(want, (st.dyq, st.y, st.dx, st.dw, st.clip)):
+        assert torch.equal(a, b)
+
+
 def test_same_seed_same_codes_different_seed_differs():
     L, x, w, dy = inputs.make_layer_inputs(0, 0)
     a, _, _ = gpu_quantize(dy, B.ACT, 0.01, STO, seed=42)
