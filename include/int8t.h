@@ -69,16 +69,21 @@ typedef enum {
     INT8T_ERR_SHAPE = 2,      /* non-positive or unsupported dimensions */
     INT8T_ERR_ARG = 3,        /* bad enum value, misaligned pointer, too many candidates */
     INT8T_ERR_WORKSPACE = 4,  /* ws_bytes smaller than int8t_workspace_bytes() */
-    INT8T_ERR_RUNTIME = 5     /* a HIP launch failed */
+    INT8T_ERR_RUNTIME = 5,    /* a HIP launch failed */
+    INT8T_STATUS_MAX_ENUM = 0x7fffffff
 } int8t_status;
 
-typedef enum { INT8T_ROUND_NEAREST_EVEN = 0, INT8T_ROUND_STOCHASTIC = 1 } int8t_round;
+/* (The *_MAX_ENUM enumerators only make every non-negative int a representable value of its enum, so
+ * that a caller's out-of-range argument reaches the argument checks as a value, not as undefined
+ * behaviour in the C++ implementation.  They are never returned and never valid as arguments.) */
+typedef enum { INT8T_ROUND_NEAREST_EVEN = 0, INT8T_ROUND_STOCHASTIC = 1, INT8T_ROUND_MAX_ENUM = 0x7fffffff } int8t_round;
 
 typedef enum {
     INT8T_ACT = 0,
     INT8T_WGT = 1,
     INT8T_ACT_PLANAR = 2,
-    INT8T_WGT_PLANAR = 3
+    INT8T_WGT_PLANAR = 3,
+    INT8T_KIND_MAX_ENUM = 0x7fffffff
 } int8t_kind;
 
 typedef enum {
@@ -86,7 +91,8 @@ typedef enum {
     INT8T_OP_DSGC = 1,
     INT8T_OP_CONV_FWD = 2,
     INT8T_OP_CONV_BWD_DATA = 3,
-    INT8T_OP_CONV_BWD_WEIGHT = 4
+    INT8T_OP_CONV_BWD_WEIGHT = 4,
+    INT8T_OP_MAX_ENUM = 0x7fffffff
 } int8t_op;
 
 /* Convolution geometry, PyTorch conventions: cross-correlation, zero padding,
@@ -103,6 +109,22 @@ const char *int8t_status_string(int8t_status s);
 
 /* Bytes of the int8 code tensor of `kind` for logical dims; 0 on bad input. */
 size_t int8t_code_bytes(const int dims[4], int8t_kind kind);
+
+/*
+ * Checking aid (HOST memory on both sides, plain loops, no GPU work): rewrites a code tensor from the
+ * library's layout (see "Layout of int8 code tensors" above; Suppl. "INT8 Convolution" for why the
+ * reduction dimension is packed innermost) into logical order, so that a caller can compare codes
+ * with Eq.1 / Eq.3 evaluated element by element without knowing the layout.
+ *   codes_host    int8t_code_bytes(dims, kind) bytes copied back from the device
+ *   copy          INT8T_WGT only: 0 = the forward copy [K][R][S][Cp], 1 = the backward-data copy
+ *                 [C][R][S][Kp]; must be 0 for the other kinds
+ *   out_host      out: dims[0]*dims[1]*dims[2]*dims[3] codes in logical order (N,C,H,W or K,Cg,R,S)
+ *   pad_nonzero   NULL, or out: number of padding bytes (channel positions >= C resp. >= K) of the
+ *                 unpacked copy that are not zero -- the convolutions rely on their being zero
+ * Returns INT8T_ERR_NULL / INT8T_ERR_SHAPE / INT8T_ERR_ARG on bad input and touches nothing then.
+ */
+int8t_status int8t_unpack_codes(const int8_t *codes_host, const int dims[4], int8t_kind kind, int copy,
+                                int8_t *out_host, size_t *pad_nonzero);
 
 /* Scratch a call needs.  DSGC: n = element count, n_cand = number of candidates, desc ignored.
  * CONV_*: desc required, n / n_cand ignored.  QUANTIZE: use int8t_quantize_workspace_bytes()
@@ -248,9 +270,11 @@ int8t_status int8t_conv_bwd_weight(const int8t_conv_desc *desc,
  * disturbed correspondingly less.
  *   kernel   host string: the kernel's name ("dsgc_sweep_kernel", "absmax_kernel",
  *            "absmax_batch_kernel", "quantize_batch_kernel", "quantize_act_kernel", "quantize_planar_kernel", "quantize_wgt_kernel",
- *            "deviation_finish_kernel", "igemm_kernel", "igemm_reduce_kernel", "band_kernel",
- *            "wgrad_kernel", "wgrad_reduce_kernel", "s2d_repack_kernel", "s2d_weights_kernel", "dw_conv_kernel", "dw_wgrad_kernel",
- *            "dw_wgrad_reduce_kernel"); NULL or "" selects every kernel.
+ *            "deviation_finish_kernel", "igemm_kernel", "igemm_dma_kernel", "igemm_reduce_kernel",
+ *            "band_kernel", "band_reg_kernel", "wgrad_kernel", "wgrad_reduce_kernel", "s2d_repack_kernel",
+ *            "s2d_weights_kernel", "dw_conv_kernel" (every depthwise forward / backward-data variant),
+ *            "dw_wgrad_kernel" (both depthwise backward-weight variants), "dw_wgrad_reduce_kernel");
+ *            NULL or "" selects every kernel.
  *            An unknown name returns INT8T_ERR_ARG and leaves timing off.
  * int8t_profile_stop waits for the recorded events, writes one entry per kernel that was
  * launched (name: static string owned by the library; launches; summed duration in ms) into

@@ -20,7 +20,7 @@ OP_QUANTIZE, OP_DSGC, OP_CONV_FWD, OP_CONV_BWD_DATA, OP_CONV_BWD_WEIGHT = range(
 MAX_CANDIDATES = 64
 MAX_BATCH = 8
 
-EXPORTS = ["int8t_status_string", "int8t_code_bytes", "int8t_workspace_bytes",
+EXPORTS = ["int8t_status_string", "int8t_code_bytes", "int8t_unpack_codes", "int8t_workspace_bytes",
            "int8t_quantize_workspace_bytes", "int8t_quantize", "int8t_quantize_batch_workspace_bytes",
            "int8t_quantize_batch", "int8t_dsgc_clip", "int8t_dsgc_prepare", "int8t_dsgc_search", "int8t_conv_fwd",
            "int8t_conv_bwd_data", "int8t_conv_bwd_weight", "int8t_dclr_scale",
@@ -57,6 +57,8 @@ def _load():
     L.int8t_status_string.argtypes = [i32]
     L.int8t_code_bytes.restype = sz
     L.int8t_code_bytes.argtypes = [dims, i32]
+    L.int8t_unpack_codes.restype = i32
+    L.int8t_unpack_codes.argtypes = [vp, dims, i32, i32, vp, C.POINTER(sz)]
     L.int8t_workspace_bytes.restype = sz
     L.int8t_workspace_bytes.argtypes = [i32, dp, sz, i32]
     L.int8t_quantize_workspace_bytes.restype = sz
@@ -149,6 +151,19 @@ def int8t_status_string(status: int) -> str:
 
 def int8t_code_bytes(dims, kind: int) -> int:
     return int(lib.int8t_code_bytes(_dims(dims), kind))
+
+
+def int8t_unpack_codes(codes_host, dims, kind: int, copy: int = 0):
+    """Host numpy int8 array in the library's layout -> (codes in logical order, shape dims; number of
+    non-zero padding bytes).  The loops run inside the library (host code)."""
+    import numpy as np
+    src = np.ascontiguousarray(codes_host, dtype=np.int8).reshape(-1)
+    assert src.size >= int8t_code_bytes(dims, kind), "code tensor shorter than int8t_code_bytes()"
+    out = np.empty(tuple(int(v) for v in dims), dtype=np.int8)
+    bad = C.c_size_t(0)
+    _check(lib.int8t_unpack_codes(src.ctypes.data_as(C.c_void_p), _dims(dims), kind, copy,
+                                  out.ctypes.data_as(C.c_void_p), C.byref(bad)))
+    return out, int(bad.value)
 
 
 def int8t_workspace_bytes(op: int, desc: ConvDesc | None = None, n: int = 0, n_cand: int = 0) -> int:

@@ -116,6 +116,7 @@ const char* int8t_status_string(int8t_status s) {
         case INT8T_ERR_ARG: return "bad argument (enum value, alignment, candidate count)";
         case INT8T_ERR_WORKSPACE: return "workspace too small";
         case INT8T_ERR_RUNTIME: return "HIP launch failed";
+        default: break;
     }
     return "unknown status";
 }
@@ -130,8 +131,43 @@ size_t int8t_code_bytes(const int dims[4], int8t_kind kind) {
                    (size_t)dims[1] * dims[2] * dims[3] * pad16(dims[0]);
         case INT8T_ACT_PLANAR:
         case INT8T_WGT_PLANAR: return n;
+        default: break;
     }
     return 0;
+}
+
+int8t_status int8t_unpack_codes(const int8_t* codes_host, const int dims[4], int8t_kind kind, int copy,
+                                int8_t* out_host, size_t* pad_nonzero) {
+    if (!codes_host || !dims || !out_host) return INT8T_ERR_NULL;
+    size_t n;
+    if (!dims_ok(dims, &n)) return INT8T_ERR_SHAPE;
+    if (kind != INT8T_ACT && kind != INT8T_WGT && kind != INT8T_ACT_PLANAR && kind != INT8T_WGT_PLANAR) return INT8T_ERR_ARG;
+    if (copy != 0 && !(kind == INT8T_WGT && copy == 1)) return INT8T_ERR_ARG;
+    size_t bad = 0;
+    if (kind == INT8T_ACT_PLANAR || kind == INT8T_WGT_PLANAR) {
+        for (size_t i = 0; i < n; ++i) out_host[i] = codes_host[i];
+    } else {
+        // both dense layouts are [outer][plane position][inner padded to 16]: activations outer = N,
+        // inner = C; weights, forward copy outer = K, inner = Cg; backward-data copy outer = Cg, inner = K
+        const int plane = dims[2] * dims[3];
+        const bool second = kind == INT8T_WGT && copy == 1;
+        const int outer = second ? dims[1] : dims[0], inner = second ? dims[0] : dims[1];
+        const int ip = pad16(inner);
+        const int8_t* src = codes_host;
+        if (second) src += align256((size_t)dims[0] * plane * pad16(dims[1]));
+        for (int o = 0; o < outer; ++o)
+            for (int p = 0; p < plane; ++p) {
+                const int8_t* g = src + ((size_t)o * plane + p) * ip;
+                for (int i = 0; i < inner; ++i) {
+                    // logical index: [dims0][dims1][plane]
+                    const size_t d0 = second ? (size_t)i : (size_t)o, d1 = second ? (size_t)o : (size_t)i;
+                    out_host[(d0 * dims[1] + d1) * plane + p] = g[i];
+                }
+                for (int i = inner; i < ip; ++i) bad += g[i] != 0;
+            }
+    }
+    if (pad_nonzero) *pad_nonzero = bad;
+    return INT8T_OK;
 }
 
 size_t int8t_workspace_bytes(int8t_op op, const int8t_conv_desc* desc, size_t n, int n_cand) {
@@ -164,6 +200,7 @@ size_t int8t_workspace_bytes(int8t_op op, const int8t_conv_desc* desc, size_t n,
             wgrad_plan(&a);
             return align256((size_t)a.splits * a.K * a.R * a.S * a.Cp * 4) + align256(s2d_bytes);
         }
+        default: break;
     }
     return 0;
 }

@@ -492,7 +492,7 @@ bool launch_band(const IgemmArgs& a, hipStream_t st, hipError_t* err) {
                 }
             }
             {
-                KernelTimer kt(KID_BAND, st);
+                KernelTimer kt(KID_BAND_REG, st);
                 launch_timed(kt, kr, dim3(grid), dim3(256), ldsr, st, a, BP, nbands_h, nbands, tab);
             }
             *err = hipGetLastError();

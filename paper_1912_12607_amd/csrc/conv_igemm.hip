@@ -758,18 +758,17 @@ hipError_t launch_igemm(const IgemmArgs& a_in, hipStream_t st) {
         else launch_timed(kt, igemm_reduce_kernel<false>, rgrid, dim3(256), 0, st, a, total);
         return hipGetLastError();
     }
-    KernelTimer kt(KID_IGEMM, st);
-    if (a.rows <= 64) {
-        launch_igemm_generic<64, 128>(a, g, 1, st, kt);
-    } else if (igemm_wide(a)) {
+    if (a.rows > 64 && igemm_wide(a)) {
+        KernelTimer kt(KID_IGEMM_DMA, st);
         // 256-row tiles only where they are full (half-empty ones cost the short reductions of a
         // residue class a quarter of their time)
         const long long t256 = g.ncls * ((g.ncols + 255) / 256) * ((a.rows + 255) / 256);
         if (t256 >= 192 && a.rows > 128) return launch_igemm_dma_any<4, 8, 2>(a, g, st, kt);
         return launch_igemm_dma_any<2, 4, 3>(a, g, st, kt);
-    } else {
-        launch_igemm_generic<128, 128>(a, g, 1, st, kt);
     }
+    KernelTimer kt(KID_IGEMM, st);
+    if (a.rows <= 64) launch_igemm_generic<64, 128>(a, g, 1, st, kt);
+    else launch_igemm_generic<128, 128>(a, g, 1, st, kt);
     return hipGetLastError();
 }
 

@@ -383,6 +383,7 @@ hipError_t launch_dsgc(const float* g, size_t n, const float* ratios, int n_cand
     return hipGetLastError();
 }
 
-size_t dsgc_acc_words() { return (size_t)DSGC_GROUPS * DSGC_JPAD * 3; }
+static_assert(kDsgcAccWords == (size_t)DSGC_GROUPS * DSGC_JPAD * 3, "accumulator layout known to the C-ABI layer");
+size_t dsgc_acc_words() { return kDsgcAccWords; }
 
 }  // namespace int8t

@@ -101,7 +101,9 @@ struct DsgcWs {
     double* partG;               // [kMaxPartials]: per-block sums of g^2 from the absmax pass
 };
 int dsgc_blocks(size_t n);
-size_t dsgc_acc_words();
+// 64-bit accumulator words of the sweep: 32 sets x 64 candidates x {sum H*m, sum L*m, sum m^2}
+constexpr size_t kDsgcAccWords = (size_t)32 * 64 * 3;
+size_t dsgc_acc_words();             // == kDsgcAccWords
 hipError_t launch_dsgc(const float* g, size_t n, const float* ratios, int n_cand, int stochastic,
                        uint64_t seed, const DsgcWs& ws, int nparts_absmax, float* clip_out,
                        double* dev_out, double* dev_all_out, hipStream_t st);

@@ -22,8 +22,10 @@ enum KernelId : int {
     KID_DEVIATION_FINISH,
     KID_DSGC_SWEEP,
     KID_IGEMM,
+    KID_IGEMM_DMA,
     KID_IGEMM_REDUCE,
     KID_BAND,
+    KID_BAND_REG,
     KID_WGRAD,
     KID_WGRAD_REDUCE,
     KID_S2D_REPACK,

@@ -264,7 +264,7 @@ class LayerStep:
         self._tuned_overlap = best[1] < best[0]
         return self._tuned_overlap
 
-    # -- host views of the library's code layouts (tests only need numpy reshapes) -----------------
+    # -- host copies of the code tensors in logical order (the library's own unpacking aid) ----------
     def codes_x(self) -> np.ndarray:
         return unpack_act(self.xq.cpu().numpy(), self.L.x_shape, self.depthwise)
 
@@ -276,26 +276,17 @@ class LayerStep:
 
 
 def unpack_act(q: np.ndarray, shape, planar: bool) -> np.ndarray:
-    """Library layout -> logical N,C,H,W codes.  Checks that channel padding is zero."""
-    N, Cc, H, W = shape
-    if planar:
-        return q.reshape(N, Cc, H, W)
-    Cp = pad16(Cc)
-    v = q.reshape(N, H, W, Cp)
-    assert not v[..., Cc:].any(), "channel padding of the code tensor must be zero"
-    return np.ascontiguousarray(v[..., :Cc].transpose(0, 3, 1, 2))
+    """Library layout -> logical N,C,H,W codes (int8t_unpack_codes).  Checks that channel padding is zero."""
+    out, bad = B.int8t_unpack_codes(q, shape, B.ACT_PLANAR if planar else B.ACT)
+    assert bad == 0, "channel padding of the code tensor must be zero"
+    return out
 
 
 def unpack_wgt(q: np.ndarray, shape, planar: bool):
     """Library layout -> (logical K,Cg,R,S codes, same from the backward-data copy or None)."""
-    K, Cg, R, S = shape
     if planar:
-        return q.reshape(K, Cg, R, S), None
-    Cp, Kp = pad16(Cg), pad16(K)
-    n1 = K * R * S * Cp
-    a = q[:n1].reshape(K, R, S, Cp)
-    off = align256(n1)
-    b = q[off:off + Cg * R * S * Kp].reshape(Cg, R, S, Kp)
-    assert not a[..., Cg:].any() and not b[..., K:].any(), "padding of the weight codes must be zero"
-    return (np.ascontiguousarray(a[..., :Cg].transpose(0, 3, 1, 2)),
-            np.ascontiguousarray(b[..., :K].transpose(3, 0, 1, 2)))
+        return B.int8t_unpack_codes(q, shape, B.WGT_PLANAR)[0], None
+    a, bad_a = B.int8t_unpack_codes(q, shape, B.WGT, 0)
+    b, bad_b = B.int8t_unpack_codes(q, shape, B.WGT, 1)
+    assert bad_a == 0 and bad_b == 0, "padding of the weight codes must be zero"
+    return a, b

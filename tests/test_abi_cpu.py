@@ -203,3 +203,37 @@ def test_dsgc_two_phase_argument_errors(lib):
     assert search(0x1000, 1000, 0x5000, 65, 1, 0, 0x2000, 0x3000, None, 0x4000, need, None) == 3
     assert search(0x1000, 1000, 0x5000, 32, 1, 0, 0x2000, 0x3000, None, 0x4000, need - 1, None) == 4
 
+
+
+def test_unpack_codes_matches_the_documented_layouts():
+    """int8t_unpack_codes against the layout formulas of include/int8t.h written out with numpy."""
+    import numpy as np
+
+    from paper_1912_12607_amd import binding as B
+    r = np.random.RandomState(3)
+    N, Cc, H, W = 3, 24, 5, 7
+    q = r.randint(-127, 128, size=(N, Cc, H, W)).astype(np.int8)
+    packed = np.zeros((N, H, W, 32), np.int8)
+    packed[..., :Cc] = q.transpose(0, 2, 3, 1)
+    out, bad = B.int8t_unpack_codes(packed.reshape(-1), (N, Cc, H, W), B.ACT)
+    assert bad == 0 and np.array_equal(out, q)
+    packed[1, 2, 3, 30] = 1
+    assert B.int8t_unpack_codes(packed.reshape(-1), (N, Cc, H, W), B.ACT)[1] == 1
+    K, Cg, R, S = 20, 40, 3, 2
+    w = r.randint(-127, 128, size=(K, Cg, R, S)).astype(np.int8)
+    n1 = K * R * S * 48
+    buf = np.zeros(((n1 + 255) // 256) * 256 + Cg * R * S * 32, np.int8)
+    a = np.zeros((K, R, S, 48), np.int8)
+    a[..., :Cg] = w.transpose(0, 2, 3, 1)
+    b = np.zeros((Cg, R, S, 32), np.int8)
+    b[..., :K] = w.transpose(1, 2, 3, 0)
+    buf[:n1] = a.reshape(-1)
+    buf[((n1 + 255) // 256) * 256:] = b.reshape(-1)
+    assert buf.size == B.int8t_code_bytes((K, Cg, R, S), B.WGT)
+    for copy in (0, 1):
+        out, bad = B.int8t_unpack_codes(buf, (K, Cg, R, S), B.WGT, copy)
+        assert bad == 0 and np.array_equal(out, w)
+    out, _ = B.int8t_unpack_codes(w.reshape(-1), (K, Cg, R, S), B.WGT_PLANAR)
+    assert np.array_equal(out, w)
+    with pytest.raises(B.Int8tError):
+        B.int8t_unpack_codes(buf, (K, Cg, R, S), B.ACT_PLANAR, 1)

@@ -2,8 +2,11 @@
 MobileNetV2, InceptionV3, at batch 32 with the benchmark's call sequence.
 
 Per layer: the three code tensors against the oracle's quantizer in full (the gradient with the clip
-value the search picked, whose choice the clip-search tests cover), the int32 accumulators of the
-three convolutions on sampled outputs that the oracle computes one by one, and the adjoint identity
+value the search picked); the clip search itself -- every candidate's deviation and the winner --
+against the oracle's brute-force search on the layers whose gradient has at most 2 M elements and on
+the first layer of each network (the brute force is 32 quantize + Eq.6 passes on one core; elsewhere
+the clip must be one of the candidates); the int32 accumulators and fp32 results of the three
+convolutions on sampled outputs that the oracle computes one by one, and the adjoint identity
   sum(q_gz * Y) = sum(DX * q_a) = sum(DW * q_W)
 on the whole accumulators, which is exact in integers and which a single wrong element breaks.
 """
@@ -45,11 +48,18 @@ def test_network_layer(net, i, L):
     clip = np.float32(st.clip.item())
     amax = np.float32(np.abs(dy).max())
     assert any(clip == np.float32(amax * r) for r in inputs.default_ratios(32))      # one of the candidates
+    if dy.size <= (2 << 20) or i == 0:
+        o = oracle.dsgc(dy.reshape(-1), inputs.default_ratios(32), mode=B.ROUND_STOCHASTIC, seed=0)
+        assert np.all(np.abs(st.dev_all.cpu().numpy() - o["dev"]) < 1e-9)
+        j = int(np.argmin(np.abs(o["clips"] - clip)))
+        assert clip == o["clips"][j] and o["dev"][j] - o["deviation"] <= 2e-9
+        assert abs(st.dev_search.item() - o["dev"][j]) < 1e-9
     dyq, sdy = oracle.quantize(dy, c=clip, mode=B.ROUND_STOCHASTIC, seed=0)
     assert np.array_equal(st.codes_dy(), dyq) and st.sdy.item() == sdy
 
     od = oracle.make_desc(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad, L.groups)
     y_acc, dx_acc, dw_acc = st.y_acc.cpu().numpy(), st.dx_acc.cpu().numpy(), st.dw_acc.cpu().numpy()
+    y, dx, dw = st.y.cpu().numpy(), st.dx.cpu().numpy(), st.dw.cpu().numpy()
     r = np.random.RandomState(1000 * cfg + i)
 
     def sample(shape, count):
@@ -59,12 +69,18 @@ def test_network_layer(net, i, L):
     def wrap(v):
         return oracle.wrap32(np.array([v], np.int64))[0][0]
 
+    def check(name, acc, out, idx, want64, s1, s2):
+        want = wrap(want64)
+        assert acc[idx] == want, (name, idx)
+        ref = oracle.dequant(np.array([want], np.int32), s1, s2)[0]      # Eq.2 in double, rounded once
+        assert abs(out[idx] - ref) <= 1e-6 * abs(ref), (name, idx)
+
     for idx in sample(y_acc.shape, 120):
-        assert y_acc[idx] == wrap(oracle.conv_fwd_at(od, xq, wq, *idx)), ("fwd", idx)
+        check("fwd", y_acc, y, idx, oracle.conv_fwd_at(od, xq, wq, *idx), sx, sw)
     for idx in sample(dx_acc.shape, 120):
-        assert dx_acc[idx] == wrap(oracle.conv_bwd_data_at(od, dyq, wq, *idx)), ("bwd_data", idx)
+        check("bwd_data", dx_acc, dx, idx, oracle.conv_bwd_data_at(od, dyq, wq, *idx), sdy, sw)
     for idx in sample(dw_acc.shape, 24):
-        assert dw_acc[idx] == wrap(oracle.conv_bwd_weight_at(od, xq, dyq, *idx)), ("bwd_weight", idx)
+        check("bwd_weight", dw_acc, dw, idx, oracle.conv_bwd_weight_at(od, xq, dyq, *idx), sx, sdy)
     if np.abs(dw_acc).max() < 2 ** 31 - 1 and np.abs(y_acc).max() < 2 ** 31 - 1:
         lhs = int((dyq.astype(np.int64) * y_acc).sum())
         assert lhs == int((dx_acc.astype(np.int64) * xq).sum()) == int((dw_acc.astype(np.int64) * wq).sum())

@@ -434,6 +434,61 @@ def test_conv_three_passes_random_shapes():
             assert np.array_equal(out.cpu().numpy(), want32.astype(np.float32)), (name, shape)   # scales are 1
 
 
+# Layers just over the threshold from which forward / backward-data run the wide-tile kernel
+# (igemm_dma_kernel: more than 64 rows, at least 32 reduction granules, at least 256 tiles of 128 x 256),
+# one per instantiation; every accumulator and every fp32 result is compared.
+# (N, C, H, W, K, R, S, stride, pad, groups), passes that must run the wide kernel
+WIDE_SHAPES = [
+    # forward and plain backward-data, 128 x 256 tiles (192 rows: one full and one half row tile; ragged columns)
+    ((4, 192, 95, 97, 192, 1, 3, (1, 1), (0, 1), 1), ("fwd", "bwd_data")),
+    # ... 256 x 256 tiles (at least 192 of them)
+    ((6, 192, 95, 97, 192, 1, 3, (1, 1), (0, 1), 1), ("fwd", "bwd_data")),
+    # backward-data by residue classes (3 x 3, stride 2: four classes with 4, 2, 2, 1 taps), 128 x 256 tiles
+    ((2, 192, 127, 129, 128, 3, 3, (2, 2), (1, 1), 1), ("bwd_data",)),
+    # ... 256 x 256 tiles
+    ((3, 192, 127, 129, 128, 3, 3, (2, 2), (1, 1), 1), ("bwd_data",)),
+    # backward-data in the cell form (1 x 1, stride 2, even row length, odd height), 128 x 256 tiles
+    ((32, 192, 63, 64, 512, 1, 1, (2, 2), (0, 0), 1), ("bwd_data",)),
+    # ... 256 x 256 tiles
+    ((48, 192, 63, 64, 512, 1, 1, (2, 2), (0, 0), 1), ("bwd_data",)),
+]
+
+
+@pytest.mark.parametrize("shape,wide_passes", WIDE_SHAPES)
+def test_wide_tile_kernels_elementwise(shape, wide_passes):
+    N, C, H, W, K, R, S, st, pd, g = shape
+    od = oracle.make_desc(N, C, H, W, K, R, S, st, pd, g)
+    gd = B.make_desc(N, C, H, W, K, R, S, st, pd, g)
+    P, Q = oracle.out_hw(od)
+    r = np.random.RandomState(abs(hash(shape)) % 2 ** 31)
+    x = r.randint(-127, 128, size=(N, C, H, W)).astype(np.int8)
+    w = r.randint(-127, 128, size=(K, C, R, S)).astype(np.int8)
+    dy = r.randint(-127, 128, size=(N, K, P, Q)).astype(np.int8)
+    xq, dyq, wq = dev(pack_act(x)), dev(pack_act(dy)), dev(pack_wgt(w))
+    s1, s2 = np.float32(0.0123), np.float32(3.3e-3)
+    sa, sb = dev(np.array([s1], np.float32)), dev(np.array([s2], np.float32))
+    for name, fn, op, a, shape_out, want_fn, args in (
+        ("fwd", B.int8t_conv_fwd, B.OP_CONV_FWD, xq, (N, K, P, Q), oracle.conv_fwd, (x, w)),
+        ("bwd_data", B.int8t_conv_bwd_data, B.OP_CONV_BWD_DATA, dyq, (N, C, H, W), oracle.conv_bwd_data, (dy, w)),
+    ):
+        if name not in wide_passes:
+            continue
+        nws = B.int8t_workspace_bytes(op, gd)
+        ws = torch.empty(nws, dtype=torch.uint8, device=DEV) if nws else None
+        out = torch.full(shape_out, float("nan"), dtype=torch.float32, device=DEV)
+        acc = torch.full(shape_out, -12345, dtype=torch.int32, device=DEV)
+        B.int8t_profile_start(None)
+        fn(gd, a, sa, wq, sb, out, acc, ws)
+        torch.cuda.synchronize()
+        ran = B.int8t_profile_stop()
+        assert list(ran) == ["igemm_dma_kernel"], (name, ran)       # the kernel under test, and nothing else
+        want32, ov = oracle.wrap32(want_fn(od, *args))
+        assert ov == 0
+        assert np.array_equal(acc.cpu().numpy(), want32), name
+        ref = oracle.dequant(want32, s1, s2)
+        assert np.all(np.abs(out.cpu().numpy() - ref) <= REL_TOL * np.abs(ref)), name
+
+
 @pytest.mark.parametrize("shape", [
     (2, 256, 9, 9, 96, 3, 3, (1, 1), (1, 1), 1),       # split reduction in both passes
     (2, 3, 12, 10, 8, 7, 7, (2, 2), (3, 3), 1),        # forward pass on the space-to-depth codes
@@ -525,8 +580,9 @@ FULL_LAYERS = [(1, 0), (2, 0), (2, 1), (2, 2), (3, 0), (3, 1), (3, 2), (4, 0), (
 
 @pytest.mark.parametrize("cfg,li", FULL_LAYERS)
 def test_full_size_layers(cfg, li):
-    """Benchmark-size layers in the benchmark's launch configuration: quantizers compared in
-    full, the clip search in full, convolutions on sampled outputs the oracle computes one by one."""
+    """Benchmark-size layers in the benchmark's launch configuration, everything compared in full:
+    the three code tensors, the clip search (every candidate's deviation), and every int32
+    accumulator and fp32 result of the three convolutions against the oracle's whole-tensor sums."""
     L, x, w, dy, st = run_layer(cfg, li)
     od = oracle.make_desc(L.N, L.C, L.H, L.W, L.K, L.R, L.S, L.stride, L.pad, L.groups)
     xq, sx = oracle.quantize(x)
@@ -543,32 +599,17 @@ def test_full_size_layers(cfg, li):
     assert np.array_equal(st.codes_dy(), dyq) and st.sdy.item() == sdy
     assert abs(st.dev_final.item() - o["dev"][j]) < DEV_TOL
 
-    r = np.random.RandomState(cfg * 10 + li)
-    y_acc, dx_acc, dw_acc = st.y_acc.cpu().numpy(), st.dx_acc.cpu().numpy(), st.dw_acc.cpu().numpy()
-    y, dx, dw = st.y.cpu().numpy(), st.dx.cpu().numpy(), st.dw.cpu().numpy()
-
-    def sample(shape, count):
-        pts = [tuple(int(r.randint(0, s)) for s in shape) for _ in range(count)]
-        corners = [tuple(0 for _ in shape), tuple(s - 1 for s in shape)]
-        return pts + corners
-
-    def cmp(acc, out, idx, want, s1, s2):
-        want32, _ = oracle.wrap32(np.array([want], np.int64))
-        assert acc[idx] == want32[0], (idx, acc[idx], want32[0])
-        ref = oracle.dequant(want32, s1, s2)[0]
-        assert abs(out[idx] - ref) <= REL_TOL * abs(ref)
-
-    for idx in sample(y_acc.shape, 600):
-        cmp(y_acc, y, idx, oracle.conv_fwd_at(od, xq, wq, *idx), sx, sw)
-    for idx in sample(dx_acc.shape, 600):
-        cmp(dx_acc, dx, idx, oracle.conv_bwd_data_at(od, dyq, wq, *idx), sdy, sw)
-    nw = 60 if L.N * L.P * L.Q > 100000 else 200
-    for idx in sample(dw_acc.shape, nw):
-        cmp(dw_acc, dw, idx, oracle.conv_bwd_weight_at(od, xq, dyq, *idx), sx, sdy)
-    # property that holds at any size: the exact adjoint identity on the int32 accumulators
-    if np.abs(y_acc).max() < 2 ** 31 - 1:
-        lhs = int((dyq.astype(np.int64) * y_acc).sum())
-        assert lhs == int((dx_acc.astype(np.int64) * xq).sum()) == int((dw_acc.astype(np.int64) * wq).sum())
+    for name, acc, out, want64, s1, s2 in (
+        ("fwd", st.y_acc, st.y, oracle.conv_fwd(od, xq, wq), sx, sw),
+        ("bwd_data", st.dx_acc, st.dx, oracle.conv_bwd_data(od, dyq, wq), sdy, sw),
+        ("bwd_weight", st.dw_acc, st.dw, oracle.conv_bwd_weight(od, xq, dyq), sx, sdy),
+    ):
+        want32, ov = oracle.wrap32(want64)
+        assert ov == 0, name                       # the benchmark's distributions stay inside int32
+        got = acc.cpu().numpy()
+        assert np.array_equal(got, want32), (name, int((got != want32).sum()))
+        ref = oracle.dequant(want32, s1, s2)
+        assert np.all(np.abs(out.cpu().numpy() - ref) <= REL_TOL * np.abs(ref)), name
 
 
 @pytest.mark.parametrize("cfg,li", [(0, 0), (1, 0), (3, 1)])
