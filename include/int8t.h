@@ -70,6 +70,7 @@ typedef enum {
     INT8T_ERR_ARG = 3,        /* bad enum value, misaligned pointer, too many candidates */
     INT8T_ERR_WORKSPACE = 4,  /* ws_bytes smaller than int8t_workspace_bytes() */
     INT8T_ERR_RUNTIME = 5,    /* a HIP launch failed */
+    INT8T_ERR_LIMIT = 6,      /* size beyond what an allocation-free variant (int8t_dsgc_clip_static) takes */
     INT8T_STATUS_MAX_ENUM = 0x7fffffff
 } int8t_status;
 
@@ -220,6 +221,30 @@ int8t_status int8t_dsgc_search(const float *g_dev, size_t n, const float *ratios
                                int8t_round mode, uint64_t seed,
                                float *clip_dev, double *deviation_dev, double *deviation_all_dev,
                                void *ws_dev, size_t ws_bytes, void *stream);
+
+/*
+ * int8t_dsgc_clip for callers that cannot provide scratch because they cannot allocate: code under
+ * HIP graph capture, tight serving / training loops, harnesses that forbid hipMalloc.  Same search,
+ * same results bit for bit, same arguments minus ws_dev / ws_bytes: the scratch (absmax partials,
+ * accumulator sets and ticket, sum-of-squares partials; INT8T_DSGC_STATIC_SCRATCH_BYTES = 61 696 bytes,
+ * whatever n is) is an array inside the library's device image, one copy per GPU, held until the
+ * process ends.  The call allocates and frees nothing -- no hipMalloc, no hipFree, no allocating
+ * library routine -- and clears what must start at zero with a kernel's own stores, not a memset node.
+ *   Limits: n <= INT8T_DSGC_STATIC_MAX_ELEMS and n_cand <= INT8T_MAX_CANDIDATES, else
+ *   INT8T_ERR_LIMIT and nothing is launched (n == 0 is INT8T_ERR_SHAPE, n_cand < 1 INT8T_ERR_ARG).
+ *   All calls on one GPU share that GPU's array, which keeps the previous call's contents: calls on
+ *   the same stream are ordered and safe; calls that OVERLAP on one GPU (different streams, or
+ *   several host threads on several streams) race on it and give wrong results.  Use
+ *   int8t_dsgc_clip with separate scratch for concurrent searches.
+ *   The first call on a GPU looks the array's device address up (hipGetSymbolAddress, with that GPU
+ *   current); make that call outside stream capture.
+ */
+#define INT8T_DSGC_STATIC_SCRATCH_BYTES 61696
+#define INT8T_DSGC_STATIC_MAX_ELEMS 0x7FFFFFFFull
+int8t_status int8t_dsgc_clip_static(const float *g_dev, size_t n, const float *ratios_dev, int n_cand,
+                                    int8t_round mode, uint64_t seed,
+                                    float *clip_dev, double *deviation_dev, double *deviation_all_dev,
+                                    void *stream);
 
 /*
  * Forward convolution on codes: acc[n,k,p,q] = sum_{c,r,s} xq[n,c,p*sh+r-ph,q*sw+s-pw] * wq[k,c,r,s]

@@ -22,7 +22,7 @@ MAX_BATCH = 8
 
 EXPORTS = ["int8t_status_string", "int8t_code_bytes", "int8t_unpack_codes", "int8t_workspace_bytes",
            "int8t_quantize_workspace_bytes", "int8t_quantize", "int8t_quantize_batch_workspace_bytes",
-           "int8t_quantize_batch", "int8t_dsgc_clip", "int8t_dsgc_prepare", "int8t_dsgc_search", "int8t_conv_fwd",
+           "int8t_quantize_batch", "int8t_dsgc_clip", "int8t_dsgc_clip_static", "int8t_dsgc_prepare", "int8t_dsgc_search", "int8t_conv_fwd",
            "int8t_conv_bwd_data", "int8t_conv_bwd_weight", "int8t_dclr_scale",
            "int8t_profile_start", "int8t_profile_start_sampled", "int8t_profile_stop"]
 
@@ -71,6 +71,8 @@ def _load():
     L.int8t_quantize_batch.argtypes = [i32, C.POINTER(QuantizeItem), vp, sz, vp]
     L.int8t_dsgc_clip.restype = i32
     L.int8t_dsgc_clip.argtypes = [vp, sz, vp, i32, i32, u64, vp, vp, vp, vp, sz, vp]
+    L.int8t_dsgc_clip_static.restype = i32
+    L.int8t_dsgc_clip_static.argtypes = [vp, sz, vp, i32, i32, u64, vp, vp, vp, vp]
     L.int8t_dsgc_search.restype = i32
     L.int8t_dsgc_search.argtypes = [vp, sz, vp, i32, i32, u64, vp, vp, vp, vp, sz, vp]
     L.int8t_dsgc_prepare.restype = i32
@@ -204,6 +206,11 @@ def int8t_dsgc_clip(g, n, ratios, n_cand, mode, seed, clip, deviation, deviation
                     stream=None):
     _check(lib.int8t_dsgc_clip(_ptr(g), n, _ptr(ratios), n_cand, mode, seed, _ptr(clip), _ptr(deviation),
                                _ptr(deviation_all), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def int8t_dsgc_clip_static(g, n, ratios, n_cand, mode, seed, clip, deviation, deviation_all=None, stream=None):
+    _check(lib.int8t_dsgc_clip_static(_ptr(g), n, _ptr(ratios), n_cand, mode, seed, _ptr(clip), _ptr(deviation),
+                                      _ptr(deviation_all), _stream(stream)))
 
 
 def int8t_dsgc_prepare(g, n, ws, stream=None):

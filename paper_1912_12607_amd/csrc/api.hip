@@ -8,6 +8,15 @@
 
 using namespace int8t;
 
+// Scratch of int8t_dsgc_clip_static: the clip search's absmax partials, its 64-bit accumulator sets
+// with the ticket word, and the sum-of-squares partials -- the same three areas int8t_dsgc_clip carves
+// out of the caller's scratch.  One copy per GPU, held until the process ends.
+#define INT8T_STATIC_A256(v) (((v) + 255) & ~(size_t)255)
+constexpr size_t kStaticDsgcBytes = INT8T_STATIC_A256(kMaxPartials * sizeof(float)) +
+                                    INT8T_STATIC_A256((kDsgcAccWords + 1) * sizeof(unsigned long long)) +
+                                    INT8T_STATIC_A256(kMaxPartials * sizeof(double));
+static __device__ __align__(256) unsigned char scratch[kStaticDsgcBytes];
+
 namespace {
 
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -116,6 +125,7 @@ const char* int8t_status_string(int8t_status s) {
         case INT8T_ERR_ARG: return "bad argument (enum value, alignment, candidate count)";
         case INT8T_ERR_WORKSPACE: return "workspace too small";
         case INT8T_ERR_RUNTIME: return "HIP launch failed";
+        case INT8T_ERR_LIMIT: return "size beyond the limit of the allocation-free variant";
         default: break;
     }
     return "unknown status";
@@ -394,6 +404,43 @@ int8t_status int8t_dsgc_clip(const float* g_dev, size_t n, const float* ratios_d
     if (s != INT8T_OK) return s;
     return int8t_dsgc_search(g_dev, n, ratios_dev, n_cand, mode, seed, clip_dev, deviation_dev, deviation_all_dev,
                              ws_dev, ws_bytes, stream);
+}
+
+namespace {
+// Device address of `scratch` on each GPU (every GPU holds its own copy of the array at its own
+// address); looked up once per device, with that device current, by the first call on it.
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_static_scratch[kMaxDevices];
+
+int8t_status static_scratch(void** out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return INT8T_ERR_RUNTIME;
+    void* p = g_static_scratch[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return INT8T_ERR_RUNTIME;
+        g_static_scratch[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return INT8T_OK;
+}
+}  // namespace
+
+int8t_status int8t_dsgc_clip_static(const float* g_dev, size_t n, const float* ratios_dev, int n_cand,
+                                    int8t_round mode, uint64_t seed, float* clip_dev, double* deviation_dev,
+                                    double* deviation_all_dev, void* stream) {
+    if (!g_dev || !ratios_dev || !clip_dev || !deviation_dev) return INT8T_ERR_NULL;
+    if (n == 0) return INT8T_ERR_SHAPE;
+    if (n > INT8T_DSGC_STATIC_MAX_ELEMS || n_cand > INT8T_MAX_CANDIDATES) return INT8T_ERR_LIMIT;
+    static_assert(INT8T_DSGC_STATIC_MAX_ELEMS <= kMaxElems, "the static variant's limit is the kernels' own");
+    static_assert(kStaticDsgcBytes == INT8T_DSGC_STATIC_SCRATCH_BYTES, "size stated in the header");
+    void* ws = nullptr;
+    const int8t_status s = static_scratch(&ws);
+    if (s != INT8T_OK) return s;
+    if (dsgc_ws_bytes(n) > kStaticDsgcBytes) return INT8T_ERR_LIMIT;
+    // the same two phases on the GPU's own array; the first pass clears the accumulators and the
+    // ticket with its own stores (no memset node, so a caller may capture the call into a graph)
+    return int8t_dsgc_clip(g_dev, n, ratios_dev, n_cand, mode, seed, clip_dev, deviation_dev, deviation_all_dev, ws,
+                           kStaticDsgcBytes, stream);
 }
 
 int8t_status int8t_conv_fwd(const int8t_conv_desc* desc, const int8_t* xq_dev, const float* sx_dev,
