@@ -3,15 +3,27 @@
 
 A "step" is one pass of the whole path over one layer's synthetic tensors, all resident in HBM
 before the timed region starts:
-    quantize(a) + quantize(W) + DSGC clip search(g_z) + quantize(g_z; stochastic, d_c)
+    quantize(a) + quantize(W) + DSGC clip search(g_z) + quantize(g_z; stochastic)
     + conv forward + conv backward-data + conv backward-weight.
 The clip search returns d_c (the input of Eq.7); the quantizer's optional second Eq.6 report is off.
-The workload is the ResNet-18-style 3x3 layer (N=64, C=K=64, 56x56, stride 1, pad 1).
+
+Workload of the headline line: the largest of the benchmark's layers, the InceptionV3-style 1x7
+convolution (config 4 layer 0: N=64, C=K=768, 17x17, pad (0,3); 152.7 G integer operations per
+convolution pass) -- the layer on which "per cent of the int8 MFMA peak" means something.  Any other
+layer: --config / --layer.
 Metric: INT8 conv TOPS = 3 * 2 * N*K*P*Q*C*R*S / step time  (the three convolutions' integer
 operations over the time of the whole step, quantizers and clip search included).
 
-Prints ONE JSON line.  `roofline` is for the kernel that dominates the step; `cpu_baseline` times
-the CPU oracle on a bounded slice of the same workload on this machine's host cores.
+Successive steps alternate between --rotate (default 2) complete sets of buffers holding the same
+values, so that no step finds its tensors in the 256 MB last-level cache because the previous step
+left them there (a layer of a network never does); `single_set_ms_per_step` is the same loop on one
+set, for comparison.
+
+Prints ONE JSON line.  `roofline` is for the kernel with the largest share of the step, its
+duration measured with HIP events inside the timed region; `config.passes` and `config.layers` give
+every pass of the headline layer and every benchmark layer against its own roofline (int8 MFMA peak
+for the convolutions, HBM peak for the quantizer passes); `cpu_baseline` times the CPU oracle on a
+bounded slice of the same workload on this machine's host cores.
 """
 from __future__ import annotations
 
@@ -30,40 +42,56 @@ INT8_MFMA_PEAK_TOPS = 5000.0
 # plain (unpacked) vector ALU: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, one operation per lane per issue
 VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 
-# HBM bytes per launch from rocprofv3 counter runs (FETCH_SIZE + WRITE_SIZE, each scaled by what the same
-# counter reads for a copy kernel of known size); keyed by (config, layer, kernel).  See profiles/.
-TRAFFIC = {(1, 0, "dsgc_sweep_kernel"): 50979 * 1024,
-           (1, 0, "band_kernel"): 63166 * 1024}        # mean of the forward and the backward-data launch
+# STORED figures, not measured by this run: HBM bytes per launch from rocprofv3 counter runs
+# (FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter reads for a copy kernel of known
+# size), keyed by (config, layer, kernel) -> (bytes, the profiles/ file that holds the run).
+TRAFFIC = {
+    (1, 0, "dsgc_sweep_kernel"): (50979 * 1024, "profiles/dsgc_sweep_config1_hbm_traffic.md"),
+    (1, 0, "band_reg_kernel"): (63166 * 1024, "profiles/dsgc_sweep_config1_hbm_traffic.md"),
+}
 
-def algorithmic(L, n_cand):
-    """Algorithmic HBM bytes and arithmetic of one step, per kernel name (what the method must move
-    and compute, summed over that kernel's launches in the step; scratch traffic is not counted)."""
+MIN_STEPS_BEFORE_TIMING = 300
+
+
+def sizes(L):
     n_x = L.N * L.C * L.H * L.W
     n_w = L.K * (L.C // L.groups) * L.R * L.S
     n_y = L.N * L.K * L.P * L.Q
+    return n_x, n_w, n_y
+
+
+def pass_algorithmic(L, n_cand):
+    """Algorithmic HBM bytes and arithmetic of each pass of the step: what the method must move and
+    compute (scratch traffic, second code copies' reads and the like are not counted).
+    {pass: (bytes, ops, kind of ops)}"""
+    n_x, n_w, n_y = sizes(L)
     macs = L.macs
-    conv2 = dict(bytes=(n_x + n_w + 4 * n_y) + (n_y + n_w + 4 * n_x), ops=4 * macs)   # forward + backward-data
-    wg = dict(bytes=n_x + n_y + 4 * n_w, ops=2 * macs)
     return {
-        # the step quantizes a and W in one batched call (one absmax launch, one quantize launch) and g_z on its own
-        "absmax_batch_kernel": dict(bytes=4 * (n_x + n_w), ops=0),                # a, W: one read each
-        "quantize_batch_kernel": dict(bytes=5 * n_x + 6 * n_w, ops=0),            # fp32 read + code write (two copies of W)
-        "absmax_kernel": dict(bytes=4 * n_y, ops=0),                              # g_z: one read
-        "quantize_act_kernel": dict(bytes=5 * n_y, ops=0),                        # fp32 read + code write of g_z
-        "quantize_planar_kernel": dict(bytes=5 * n_y, ops=0),
-        "quantize_wgt_kernel": dict(bytes=6 * n_w, ops=0),
-        "deviation_finish_kernel": dict(bytes=0, ops=0),
-        # one read of g_z.  Vector-ALU work of the sweep: 2.75 operations per element and candidate (round-down
+        "absmax_xw": (4 * (n_x + n_w), 0, None),                 # one read of a and W
+        "quantize_xw": (5 * n_x + 6 * n_w, 0, None),             # fp32 read + code write (W: two layouts)
+        "absmax_gz": (4 * n_y, 0, None),                         # max|g_z| and sum g_z^2, one read
+        # One read of g_z.  Vector-ALU work of the sweep: 2.75 operations per element and candidate (round-down
         # fused multiply-add, convert, 0.75 byte gather) + 30 per element and 32-candidate chunk (draw, fixed
-        # point, digit planes, LDS traffic); the products and sums themselves run on the matrix cores
-        "dsgc_sweep_kernel": dict(bytes=4 * n_y, ops=(2.75 * n_cand + 30 * ((n_cand + 31) // 32)) * n_y),
-        "igemm_kernel": conv2, "band_kernel": conv2, "dw_conv_kernel": conv2,
-        "igemm_reduce_kernel": dict(bytes=4 * (n_x + n_y), ops=0),               # final sum of a split reduction
-        "wgrad_kernel": wg, "dw_wgrad_kernel": wg,
-        "wgrad_reduce_kernel": dict(bytes=4 * n_w, ops=0), "dw_wgrad_reduce_kernel": dict(bytes=4 * n_w, ops=0),
-        "s2d_repack_kernel": dict(bytes=2 * n_x, ops=0),                          # codes of a in, rearranged codes out
-        "s2d_weights_kernel": dict(bytes=2 * n_w, ops=0),
+        # point, digit planes, LDS traffic); the products and sums themselves run on the matrix cores.
+        "dsgc_search": (4 * n_y, (2.75 * n_cand + 30 * ((n_cand + 31) // 32)) * n_y, "valu"),
+        "quantize_gz": (5 * n_y, 0, None),
+        "fwd": (n_x + n_w + 4 * n_y, 2 * macs, "mfma"),
+        "bwd_data": (n_y + n_w + 4 * n_x, 2 * macs, "mfma"),
+        "bwd_weight": (n_x + n_y + 4 * n_w, 2 * macs, "mfma"),
     }
+
+
+def roofline_of(nbytes, ops, kind, seconds, depthwise=False):
+    """The roofline that bounds (bytes, ops) and the fraction of it reached in `seconds`."""
+    t_hbm = nbytes / (HBM_PEAK_GBS * 1e9)
+    if kind == "mfma" and not depthwise and ops / (INT8_MFMA_PEAK_TOPS * 1e12) > t_hbm:
+        r = dict(bound="mfma", achieved=ops / seconds / 1e12, peak=INT8_MFMA_PEAK_TOPS, unit="TOP/s")
+    elif kind == "valu" and ops / (VALU_PEAK_TOPS * 1e12) > t_hbm:
+        r = dict(bound="alu", achieved=ops / seconds / 1e12, peak=VALU_PEAK_TOPS, unit="TOP/s")
+    else:
+        r = dict(bound="hbm", achieved=nbytes / seconds / 1e9, peak=HBM_PEAK_GBS, unit="GB/s")
+    r["frac"] = r["achieved"] / r["peak"]
+    return r
 
 
 def cpu_baseline(L, x, w, dy, ratios, n_img):
@@ -95,24 +123,28 @@ def cpu_baseline(L, x, w, dy, ratios, n_img):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    # a step takes about 0.15 ms: with a few dozen steps the GPU is still ramping its clocks up while it is
-    # measured (50 steps after 5: 0.149 ms per step; 500 after 200: 0.140 ms), hence the long defaults
+    # a step takes 0.1 - 0.4 ms: with a few dozen steps the GPU is still ramping its clocks up while it is
+    # measured, hence the long defaults (and MIN_STEPS_BEFORE_TIMING)
     ap.add_argument("--steps", type=int, default=1000)
-    ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--config", type=int, default=1, help="benchmark config index (default 1: ResNet-18 3x3)")
-    ap.add_argument("--layer", type=int, default=0)
+    ap.add_argument("--warmup", type=int, default=300)
+    ap.add_argument("--config", type=int, default=4, help="benchmark config index (default 4: InceptionV3-style layers)")
+    ap.add_argument("--layer", type=int, default=0, help="layer of the config (default 0: the 1x7 convolution)")
+    ap.add_argument("--rotate", type=int, default=2,
+                    help="sets of buffers the steps alternate between (default 2: together above the 256 MB "
+                         "last-level cache for every benchmark layer; 1 = one set, re-used by every step)")
     ap.add_argument("--dsgc-period", type=int, default=1,
                     help="run the clip search every P-th step only (Periodic Update, Table 2); default 1 = "
                          "every step, the benchmark's setting")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true",
                     help="issue every call on one stream (default: a, W quantization and the forward convolution "
-                         "run on a second stream beside the clip search in the steps that search)")
-    ap.add_argument("--cpu-images", type=int, default=64)
+                         "run on a second stream beside the clip search where that pays)")
+    ap.add_argument("--no-layers", action="store_true", help="leave the per-layer table of all benchmark layers out")
+    ap.add_argument("--cpu-images", type=int, default=0, help="images of the batch the oracle is timed on (0: by layer size)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="after the steps, run a plain elementwise copy of this many MiB three times "
                          "(reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
-    ap.add_argument("--all-layers", action="store_true", help="also print a per-layer table for every config (stderr)")
+    ap.add_argument("--all-layers", action="store_true", help="also print the per-kernel table of every layer (stderr)")
     ap.add_argument("--resnet50", type=int, default=0, metavar="BATCH",
                     help="also time the step of every ResNet-50 convolution and its classifier at this batch "
                          "(Fig.10's workload) and print the per-layer table and the network total (stderr)")
@@ -136,77 +168,145 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU: the HIP library has no CPU fallback"
     n_cand = 32
     period = max(1, args.dsgc_period)
+    rotate = max(1, args.rotate)
     ratios = inputs.default_ratios(n_cand)
-
     overlap = False if args.no_overlap else None        # None: LayerStep decides per layer
 
-    def bench_layer(cfg, li, steps, warmup):
-        """Returns layer, host tensors, seconds per step, {kernel: (launches per step, us per launch)} of
-        an untimed pass with every kernel launch carrying events, and the dominant kernel's
-        (name, launches per step, us per launch) measured by events inside the timed region itself."""
-        L, x, w, dy = inputs.make_layer_inputs(cfg, li)
-        st = LayerStep(L, n_cand=n_cand, keep_acc=False, requantize_deviation=False)
-        st.upload(x, w, dy, ratios)
+    def profile_calls(calls, reps):
+        """{kernel: (launches per call sequence, us per launch)} of `calls` run `reps` times on one
+        stream with every launch carrying HIP events."""
+        for c in calls:
+            c()
         torch.cuda.synchronize()
-        # The GPU ramps its clocks up over the first tens of milliseconds of work (50 steps after 5 read 6 %
-        # slower than 1000 after 200): whatever W is, the card has run at least 300 steps before the timed
-        # region, so that a short run measures the same steady state as a long one.
-        for i in range(max(0, 300 - warmup)):
-            st.run(seed=i, overlap=overlap)
-        for i in range(warmup):
-            st.run(seed=i, overlap=overlap)
-        torch.cuda.synchronize()
-        # pass 1 (untimed): HIP events around every kernel launch, on the launch stream, inside the library
-        nprof = max(3, min(10, steps))
         B.int8t_profile_start(None)
-        for i in range(nprof):
-            st.run(seed=i, search=(i % period == 0))
+        for _ in range(reps):
+            for c in calls:
+                c()
         torch.cuda.synchronize()
         prof = B.int8t_profile_stop()
-        per_kernel = {k: (n / nprof, ms * 1e3 / n) for k, (n, ms) in prof.items()}
-        dom = max(prof, key=lambda k: prof[k][1])
+        return {k: (n / reps, ms * 1e3 / n) for k, (n, ms) in prof.items()}
+
+    def pass_table(L, st):
+        """Every pass of the step on its own (one stream, launches back to back): its kernels, its time,
+        its algorithmic bytes / operations and the fraction of the roofline that bounds it.  Also returns
+        {kernel: [algorithmic bytes, ops, kind, launches]} summed over the passes each kernel served."""
+        alg = pass_algorithmic(L, n_cand)
+        dw = L.groups != 1
+        calls = [("quantize_xw", lambda: st.quantize_xw()), ("dsgc", lambda: st.dsgc(0)),
+                 ("quantize_gz", lambda: st.quantize_dy(0)), ("fwd", lambda: st.fwd()),
+                 ("bwd_data", lambda: st.bwd_data()), ("bwd_weight", lambda: st.bwd_weight())]
+        rows, per_kernel = [], {}
+
+        def add(name, kernels, key):
+            us = sum(n * t for n, t in kernels.values())
+            nbytes, ops, kind = alg[key]
+            row = {"pass": name, "us": round(us, 2), "kernels": {k: round(n * t, 2) for k, (n, t) in kernels.items()},
+                   "algorithmic_bytes": nbytes, "algorithmic_ops": ops}
+            row.update({k: (round(v, 4) if isinstance(v, float) else v)
+                        for k, v in roofline_of(nbytes, ops, kind, us * 1e-6, dw).items()})
+            rows.append(row)
+            main_k = max(kernels, key=lambda k: kernels[k][0] * kernels[k][1])
+            e = per_kernel.setdefault(main_k, [0, 0, kind, 0])
+            e[0] += nbytes
+            e[1] += ops
+            e[3] += kernels[main_k][0]
+
+        for name, fn in calls:
+            pk = profile_calls([fn], 5)
+            if name == "quantize_xw":
+                add("absmax_xw", {k: v for k, v in pk.items() if k.startswith("absmax")}, "absmax_xw")
+                add("quantize_xw", {k: v for k, v in pk.items() if not k.startswith("absmax")}, "quantize_xw")
+            elif name == "dsgc":
+                add("absmax_gz", {k: v for k, v in pk.items() if k.startswith("absmax")}, "absmax_gz")
+                add("dsgc_search", {k: v for k, v in pk.items() if not k.startswith("absmax")}, "dsgc_search")
+            else:
+                add(name, pk, name)
+        return rows, per_kernel
+
+    def make_sets(cfg, li, count):
+        L, x, w, dy = inputs.make_layer_inputs(cfg, li)
+        sets = []
+        for _ in range(count):
+            st = LayerStep(L, n_cand=n_cand, keep_acc=False, requantize_deviation=False)
+            st.upload(x, w, dy, ratios)
+            sets.append(st)
         torch.cuda.synchronize()
-        # pass 2 (the timed region): only the dominant kernel carries events, and only every 5th of its
-        # launches -- a timed dispatch idles the GPU for about 5 us before and after it (measured with a
-        # kernel trace), which would otherwise be charged to every step
-        every = 5 if steps * per_kernel[dom][0] >= 5 else 1
-        B.int8t_profile_start_sampled(dom, every)
+        return L, (x, w, dy), sets
+
+    def timed_steps(sets, steps, warm, sampled_kernel=None, every=5):
+        """Seconds per step over `steps` steps after `warm` untimed ones, the steps alternating between
+        the buffer sets; with sampled_kernel, every `every`-th launch of that kernel carries HIP events
+        inside the timed region: returns (seconds per step, us per sampled launch or None)."""
+        k = len(sets)
+        for i in range(warm):
+            sets[i % k].run(seed=i, search=(i % period == 0), overlap=overlap)
+        torch.cuda.synchronize()
+        if sampled_kernel:
+            B.int8t_profile_start_sampled(sampled_kernel, every)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(steps):
-            st.run(seed=i, search=(i % period == 0), overlap=overlap)
+            sets[i % k].run(seed=i, search=(i % period == 0), overlap=overlap)
         torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
-        n, ms = B.int8t_profile_stop()[dom]
-        return L, (x, w, dy), dt / steps, per_kernel, (dom, per_kernel[dom][0], ms * 1e3 / n)
+        dt = (time.perf_counter() - t0) / steps
+        us = None
+        if sampled_kernel:
+            n, ms = B.int8t_profile_stop()[sampled_kernel]
+            us = ms * 1e3 / n
+        return dt, us
 
-    L, host, t_step, per_kernel, (dom, dom_launches, dom_us) = bench_layer(args.config, args.layer, args.steps, args.warmup)
+    def step_kernels(st):
+        """{kernel: (launches per step, us per launch)} of whole one-stream steps with every launch timed."""
+        nprof = 5
+        for i in range(3):
+            st.run(seed=i, overlap=False)
+        torch.cuda.synchronize()
+        B.int8t_profile_start(None)
+        for i in range(nprof):
+            st.run(seed=i, search=(i % period == 0), overlap=False)
+        torch.cuda.synchronize()
+        prof = B.int8t_profile_stop()
+        return {k: (n / nprof, ms * 1e3 / n) for k, (n, ms) in prof.items()}
+
+    # ---- headline layer -------------------------------------------------------------------------
+    L, host, sets = make_sets(args.config, args.layer, rotate)
+    warm_total = max(args.warmup, MIN_STEPS_BEFORE_TIMING)
+    # The GPU ramps its clocks up over the first tens of milliseconds of work: whatever --warmup is, at
+    # least MIN_STEPS_BEFORE_TIMING steps run before anything is measured; `warmup` in the output is the
+    # number that ran.
+    timed_steps(sets, 1, warm_total)
+    per_kernel = step_kernels(sets[0])
+    dom = max(per_kernel, key=lambda k: per_kernel[k][0] * per_kernel[k][1])
+    passes, kernel_alg = pass_table(L, sets[0])
+    every = 5 if args.steps * per_kernel[dom][0] >= 5 else 1
+    t_step, dom_us = timed_steps(sets, args.steps, 20, dom, every)
     tops = 6 * L.macs / t_step / 1e12
-    a = algorithmic(L, n_cand)[dom]
-    t_dom = dom_us * 1e-6 * dom_launches           # the kernel's time per step
-    # which roofline bounds the dominant kernel
-    t_hbm = a["bytes"] / (HBM_PEAK_GBS * 1e9)
-    if dom == "dsgc_sweep_kernel" and a["ops"] / (VALU_PEAK_TOPS * 1e12) > t_hbm:
-        roof = dict(bound="alu", achieved=a["ops"] / t_dom / 1e12, peak=VALU_PEAK_TOPS, unit="TOP/s")
-    elif dom != "dsgc_sweep_kernel" and a["ops"] / (INT8_MFMA_PEAK_TOPS * 1e12) > t_hbm:
-        roof = dict(bound="mfma", achieved=a["ops"] / t_dom / 1e12, peak=INT8_MFMA_PEAK_TOPS, unit="TOP/s")
-    else:
-        roof = dict(bound="hbm", achieved=a["bytes"] / t_dom / 1e9, peak=HBM_PEAK_GBS, unit="GB/s")
-    roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = TRAFFIC.get((args.config, args.layer, dom))
+
+    nbytes, ops, kind, launches = kernel_alg.get(dom, [0, 0, None, per_kernel[dom][0]])
+    launches = launches or per_kernel[dom][0]
+    # per launch, as the duration is: the kernel's algorithmic work of the step / its launches per step
+    roof = roofline_of(nbytes / launches, ops / launches, kind, dom_us * 1e-6, L.groups != 1)
+    tr = TRAFFIC.get((args.config, args.layer, dom))
+    roof["traffic"] = tr[0] if tr else None
+    roof["traffic_source"] = ("stored figure, not measured by this run: " + tr[1]) if tr else None
     roof["kernel"] = dom
-    roof["launches_per_step"] = dom_launches
+    roof["launches_per_step"] = per_kernel[dom][0]
     roof["us_per_launch"] = dom_us
+    roof["algorithmic_bytes_per_launch"] = nbytes / launches
+    roof["algorithmic_ops_per_launch"] = ops / launches
     two_streams = overlap is None and period == 1 and two_stream_default(L)
     if two_streams:
-        # In the timed region the kernel shares the compute units with the second stream's kernels; what it
-        # does with the machine to itself comes from the untimed one-stream pass.
+        # In the timed region the kernel may share the compute units with the second stream's kernels;
+        # what it does with the machine to itself comes from the untimed one-stream pass.
         roof["us_per_launch_one_stream"] = per_kernel[dom][1]
-        roof["frac_one_stream"] = roof["frac"] * dom_us / per_kernel[dom][1]
+
+    single_ms = None
+    if rotate > 1:
+        single_ms = timed_steps(sets[:1], max(50, args.steps // 4), 50)[0] * 1e3
 
     out = {
         "metric": "INT8 conv TOPS (fwd+bwd-data+bwd-weight incl. quantize); % int8 MFMA peak",
-        "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": warm_total + 20,
         "ms_per_step": t_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": f"config {args.config} layer {args.layer}: {L.name} N={L.N} C={L.C} "
@@ -214,14 +314,40 @@ def main():
                                f"groups {L.groups}; DSGC 32 candidates " + ("every step" if period == 1 else f"every {period} steps"),
                    "streams": ("2: quantization of a, W and the forward convolution beside the clip search"
                                if two_streams else "1"),
+                   "buffer_sets": rotate, "single_set_ms_per_step": single_ms,
+                   "warmup_requested": args.warmup,
                    "pct_int8_mfma_peak": 100.0 * tops / INT8_MFMA_PEAK_TOPS,
                    "us_per_kernel": {k: {"launches_per_step": v[0], "us_per_launch": round(v[1], 2)}
                                      for k, v in sorted(per_kernel.items(), key=lambda kv: -kv[1][0] * kv[1][1])},
-                   "sum_kernels_us": sum(v[0] * v[1] for v in per_kernel.values())},
+                   "sum_kernels_us": sum(v[0] * v[1] for v in per_kernel.values()),
+                   "passes": passes},
         "roofline": roof,
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(L, *host, ratios, args.cpu_images)
+        n_img = args.cpu_images or max(1, min(L.N, int(L.N * 4.0e10 / (3 * L.macs + 1))))
+        out["cpu_baseline"] = cpu_baseline(L, *host, ratios, n_img)
+    del sets
+    torch.cuda.empty_cache()
+
+    # ---- every benchmark layer against its own rooflines ------------------------------------------
+    if not args.no_layers:
+        rows = []
+        for cfg in sorted(c for c in inputs.CONFIGS if 1 <= c <= 4):
+            for li in range(len(inputs.CONFIGS[cfg])):
+                Lx, _, sx = make_sets(cfg, li, rotate)
+                ts, _ = timed_steps(sx, max(100, args.steps // 5), 150)
+                prow, _ = pass_table(Lx, sx[0])
+                row = {"layer": f"{cfg}.{li} {Lx.name}", "ms_per_step": round(ts * 1e3, 4),
+                       "TOPS": round(6 * Lx.macs / ts / 1e12, 2),
+                       "pct_int8_mfma_peak": round(600 * Lx.macs / ts / 1e12 / INT8_MFMA_PEAK_TOPS, 3),
+                       "passes": {p["pass"]: {"us": p["us"], "bound": p["bound"], "achieved": round(p["achieved"], 1),
+                                              "unit": p["unit"], "frac": round(p["frac"], 4)} for p in prow}}
+                rows.append(row)
+                if args.all_layers:
+                    print(json.dumps({"layer": row["layer"], "passes": prow}), file=sys.stderr, flush=True)
+                del sx
+                torch.cuda.empty_cache()
+        out["config"]["layers"] = rows
 
     if args.copy_calibration > 0:
         src = torch.ones(args.copy_calibration * (1 << 20) // 4, dtype=torch.float32, device="cuda")
@@ -230,29 +356,13 @@ def main():
             torch.mul(src, 1.0, out=dst)       # one elementwise kernel: reads and writes the stated size once
         torch.cuda.synchronize()
 
-    if args.all_layers:
-        for cfg in sorted(inputs.CONFIGS):
-            for li in range(len(inputs.CONFIGS[cfg])):
-                if (cfg, li) == (args.config, args.layer):
-                    Lx, ts, pk = L, t_step, per_kernel
-                else:
-                    Lx, _, ts, pk, _ = bench_layer(cfg, li, max(5, args.steps // 2), 3)
-                al = algorithmic(Lx, n_cand)
-                row = {"layer": f"{cfg}.{li} {Lx.name}", "ms_per_step": round(ts * 1e3, 4),
-                       "TOPS": round(6 * Lx.macs / ts / 1e12, 2)}
-                for k, (n, us) in sorted(pk.items(), key=lambda kv: -kv[1][0] * kv[1][1]):
-                    t = n * us * 1e-6
-                    row[k] = {"us_per_step": round(n * us, 2), "GB/s": round(al[k]["bytes"] / t / 1e9, 1),
-                              "TOP/s": round(al[k]["ops"] / t / 1e12, 2)}
-                print(json.dumps(row), file=sys.stderr, flush=True)
-
     def sweep(title, batch, layers, seed_cfg):
         """One step per distinct layer shape; the network's time is the sum over shapes x multiplicity."""
         total_ms, total_ops = 0.0, 0
         for i, (count, Lx) in enumerate(layers):
             # the first layer's input is the image: no backward-data pass there (4 of the 6 MAC passes counted)
             st = LayerStep(Lx, n_cand=n_cand, keep_acc=False, requantize_deviation=False, input_grad=i > 0)
-            passes = 6 if i > 0 else 4
+            npass = 6 if i > 0 else 4
             st.upload(inputs.make_x(Lx, seed_cfg, i), inputs.make_w(Lx, seed_cfg, i), inputs.make_dy(Lx, seed_cfg, i), ratios)
             nst = max(20, args.steps // 10)
             for k in range(80):          # the first few dozen steps on fresh buffers run at up to twice the steady time
@@ -266,10 +376,10 @@ def main():
             torch.cuda.synchronize()
             ts = (time.perf_counter() - t0) / nst
             total_ms += count * ts * 1e3
-            total_ops += count * Lx.macs * passes
+            total_ops += count * Lx.macs * npass
             print(json.dumps({"layer": Lx.name, "count": count, "C": Lx.C, "HW": Lx.H, "K": Lx.K, "RS": [Lx.R, Lx.S],
                               "stride": Lx.stride[0], "groups": Lx.groups, "ms_per_step": round(ts * 1e3, 4),
-                              "TOPS": round(passes * Lx.macs / ts / 1e12, 1)}), file=sys.stderr, flush=True)
+                              "TOPS": round(npass * Lx.macs / ts / 1e12, 1)}), file=sys.stderr, flush=True)
             del st
         print(json.dumps({"network": title, "batch": batch, "ms_per_iteration": round(total_ms, 3),
                           "TOPS": round(total_ops / total_ms / 1e9, 1),

@@ -287,6 +287,39 @@ int8t_status int8t_conv_bwd_weight(const int8t_conv_desc *desc,
                                    void *ws_dev, size_t ws_bytes, void *stream);
 
 /*
+ * Choice of the kernel per layer by measurement "before training" (Suppl. "INT8 Convolution", last
+ * paragraph: the paper picks between its two convolution algorithms per layer; here the choice is
+ * among this library's kernels for a pass).  Every variant computes the same integer sums, so the
+ * results are identical bit for bit; a caller times the variants int8t_conv_variant_ok() admits on
+ * the layer's own buffers and selects the fastest.  The selection is kept in a process-wide table
+ * keyed by (pass, descriptor) until it is changed; INT8T_VARIANT_AUTO (the default for every layer)
+ * restores the library's own rules.  Thread-safe; not device-specific.
+ *   forward / backward-data:  BAND, TILE, TILE_SPLIT, WIDE128, WIDE256, WIDE256_DEEP
+ *   backward-weight:          WGRAD_FEWER, WGRAD_MORE (half / twice the reduction shares of the
+ *                             cost model's choice; query int8t_workspace_bytes() again afterwards)
+ * Depthwise layers have one kernel per pass.  A variant that needs scratch (TILE_SPLIT) and is not
+ * given enough falls back to TILE.
+ */
+typedef enum {
+    INT8T_VARIANT_AUTO = 0,
+    INT8T_VARIANT_BAND = 1,          /* filter bank resident on chip, output rows streamed (small banks, stride 1) */
+    INT8T_VARIANT_TILE = 2,          /* 64/128 x 128 implicit-GEMM tiles staged through registers */
+    INT8T_VARIANT_TILE_SPLIT = 3,    /* ... with the reduction split over several blocks per tile */
+    INT8T_VARIANT_WIDE128 = 4,       /* 128 x 256 tiles, operands loaded straight into a 3-stage LDS ring */
+    INT8T_VARIANT_WIDE256 = 5,       /* 256 x 256 tiles, 2 stages of 128 reduction bytes */
+    INT8T_VARIANT_WIDE256_DEEP = 6,  /* 256 x 256 tiles, 4 stages of 64 reduction bytes */
+    INT8T_VARIANT_WGRAD_FEWER = 7,
+    INT8T_VARIANT_WGRAD_MORE = 8,
+    INT8T_VARIANT_MAX_ENUM = 0x7fffffff
+} int8t_variant;
+#define INT8T_VARIANT_COUNT 9
+/* 1 when `variant` can run pass `op` (INT8T_OP_CONV_*) of the layer, else 0 (also on a bad descriptor). */
+int int8t_conv_variant_ok(int8t_op op, const int8t_conv_desc *desc, int8t_variant variant);
+/* INT8T_ERR_ARG when the variant cannot run that pass of that layer; then nothing changes. */
+int8t_status int8t_conv_select_variant(int8t_op op, const int8t_conv_desc *desc, int8t_variant variant);
+int8t_variant int8t_conv_selected_variant(int8t_op op, const int8t_conv_desc *desc);
+
+/*
  * Kernel timing (measurement aid, not part of the method).  Between int8t_profile_start and
  * int8t_profile_stop every launch of the selected kernel carries a pair of HIP events that take
  * the dispatch's own start and end time stamps on the launch stream.  A timed dispatch costs a few

@@ -17,6 +17,9 @@ OK = 0
 ROUND_NEAREST_EVEN, ROUND_STOCHASTIC = 0, 1
 ACT, WGT, ACT_PLANAR, WGT_PLANAR = 0, 1, 2, 3
 OP_QUANTIZE, OP_DSGC, OP_CONV_FWD, OP_CONV_BWD_DATA, OP_CONV_BWD_WEIGHT = range(5)
+(VARIANT_AUTO, VARIANT_BAND, VARIANT_TILE, VARIANT_TILE_SPLIT, VARIANT_WIDE128, VARIANT_WIDE256,
+ VARIANT_WIDE256_DEEP, VARIANT_WGRAD_FEWER, VARIANT_WGRAD_MORE) = range(9)
+VARIANT_NAMES = ["auto", "band", "tile", "tile_split", "wide128", "wide256", "wide256_deep", "wgrad_fewer", "wgrad_more"]
 MAX_CANDIDATES = 64
 MAX_BATCH = 8
 
@@ -24,6 +27,7 @@ EXPORTS = ["int8t_status_string", "int8t_code_bytes", "int8t_unpack_codes", "int
            "int8t_quantize_workspace_bytes", "int8t_quantize", "int8t_quantize_batch_workspace_bytes",
            "int8t_quantize_batch", "int8t_dsgc_clip", "int8t_dsgc_clip_static", "int8t_dsgc_prepare", "int8t_dsgc_search", "int8t_conv_fwd",
            "int8t_conv_bwd_data", "int8t_conv_bwd_weight", "int8t_dclr_scale",
+           "int8t_conv_variant_ok", "int8t_conv_select_variant", "int8t_conv_selected_variant",
            "int8t_profile_start", "int8t_profile_start_sampled", "int8t_profile_stop"]
 
 
@@ -81,6 +85,12 @@ def _load():
         f = getattr(L, name)
         f.restype = i32
         f.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.int8t_conv_variant_ok.restype = i32
+    L.int8t_conv_variant_ok.argtypes = [i32, dp, i32]
+    L.int8t_conv_select_variant.restype = i32
+    L.int8t_conv_select_variant.argtypes = [i32, dp, i32]
+    L.int8t_conv_selected_variant.restype = i32
+    L.int8t_conv_selected_variant.argtypes = [i32, dp]
     L.int8t_dclr_scale.restype = C.c_double
     L.int8t_dclr_scale.argtypes = [C.c_double, C.c_double, C.c_double]
     L.int8t_profile_start.restype = i32
@@ -236,6 +246,18 @@ def int8t_conv_bwd_data(desc, dyq, sdy, wq, sw, dx, acc=None, ws=None, stream=No
 def int8t_conv_bwd_weight(desc, xq, sx, dyq, sdy, dw, acc=None, ws=None, stream=None):
     _check(lib.int8t_conv_bwd_weight(C.byref(desc), _ptr(xq), _ptr(sx), _ptr(dyq), _ptr(sdy), _ptr(dw),
                                      _ptr(acc), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def int8t_conv_variant_ok(op: int, desc: ConvDesc, variant: int) -> bool:
+    return bool(lib.int8t_conv_variant_ok(op, C.byref(desc), variant))
+
+
+def int8t_conv_select_variant(op: int, desc: ConvDesc, variant: int):
+    _check(lib.int8t_conv_select_variant(op, C.byref(desc), variant))
+
+
+def int8t_conv_selected_variant(op: int, desc: ConvDesc) -> int:
+    return int(lib.int8t_conv_selected_variant(op, C.byref(desc)))
 
 
 def int8t_dclr_scale(d_c: float, alpha: float = 20.0, beta: float = 0.1) -> float:

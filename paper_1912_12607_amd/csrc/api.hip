@@ -2,6 +2,10 @@
 // No device memory is allocated here and nothing synchronises with the host.
 #include <math.h>
 
+#include <array>
+#include <map>
+#include <mutex>
+
 #include "../../include/int8t.h"
 #include "kernels.h"
 #include "device_common.h"
@@ -113,9 +117,62 @@ void fill_igemm_bwd_data(IgemmArgs* a, const int8t_conv_desc* d, const Geo& g) {
     a->dgrad = 1;
 }
 
+// Kernel variants selected per (pass, layer) by int8t_conv_select_variant; everything else runs the
+// library's own choice.  Process-wide, guarded by a mutex (a lookup per convolution call).
+std::mutex g_variant_mutex;
+std::map<std::array<int, 13>, int> g_variant_table;
+
+std::array<int, 13> variant_key(int8t_op op, const int8t_conv_desc* d) {
+    return {(int)op, d->N, d->C, d->H, d->W, d->K, d->R, d->S, d->stride_h, d->stride_w, d->pad_h, d->pad_w, d->groups};
+}
+int selected_variant(int8t_op op, const int8t_conv_desc* d) {
+    std::lock_guard<std::mutex> lock(g_variant_mutex);
+    if (g_variant_table.empty()) return VAR_AUTO;
+    const auto it = g_variant_table.find(variant_key(op, d));
+    return it == g_variant_table.end() ? VAR_AUTO : it->second;
+}
+
+// whether `variant` can run pass `op` of the layer
+bool variant_ok(int8t_op op, const int8t_conv_desc* d, const Geo& g, int variant) {
+    if (variant == VAR_AUTO) return true;
+    if (g.depthwise) return false;
+    if (op == INT8T_OP_CONV_BWD_WEIGHT) return variant == VAR_WGRAD_FEWER || variant == VAR_WGRAD_MORE;
+    if (op != INT8T_OP_CONV_FWD && op != INT8T_OP_CONV_BWD_DATA) return false;
+    IgemmArgs a{};
+    if (op == INT8T_OP_CONV_FWD) fill_igemm_fwd(&a, d, g);
+    else fill_igemm_bwd_data(&a, d, g);
+    (void)igemm_s2d(&a);      // a layer that runs on its space-to-depth form is judged in that form
+    return igemm_variant_ok(a, variant);
+}
+
 }  // namespace
 
 extern "C" {
+
+int int8t_conv_variant_ok(int8t_op op, const int8t_conv_desc* desc, int8t_variant variant) {
+    Geo g;
+    if (desc_ok(desc, &g) != INT8T_OK) return 0;
+    if ((int)variant < 0 || (int)variant >= VAR_COUNT) return 0;
+    return variant_ok(op, desc, g, (int)variant) ? 1 : 0;
+}
+
+int8t_status int8t_conv_select_variant(int8t_op op, const int8t_conv_desc* desc, int8t_variant variant) {
+    Geo g;
+    const int8t_status s = desc_ok(desc, &g);
+    if (s != INT8T_OK) return s;
+    if (op != INT8T_OP_CONV_FWD && op != INT8T_OP_CONV_BWD_DATA && op != INT8T_OP_CONV_BWD_WEIGHT) return INT8T_ERR_ARG;
+    if ((int)variant < 0 || (int)variant >= VAR_COUNT || !variant_ok(op, desc, g, (int)variant)) return INT8T_ERR_ARG;
+    std::lock_guard<std::mutex> lock(g_variant_mutex);
+    if (variant == INT8T_VARIANT_AUTO) g_variant_table.erase(variant_key(op, desc));
+    else g_variant_table[variant_key(op, desc)] = (int)variant;
+    return INT8T_OK;
+}
+
+int8t_variant int8t_conv_selected_variant(int8t_op op, const int8t_conv_desc* desc) {
+    Geo g;
+    if (desc_ok(desc, &g) != INT8T_OK) return INT8T_VARIANT_AUTO;
+    return (int8t_variant)selected_variant(op, desc);
+}
 
 const char* int8t_status_string(int8t_status s) {
     switch (s) {
@@ -194,7 +251,7 @@ size_t int8t_workspace_bytes(int8t_op op, const int8t_conv_desc* desc, size_t n,
             IgemmArgs a{};
             if (op == INT8T_OP_CONV_FWD) fill_igemm_fwd(&a, desc, g);
             else fill_igemm_bwd_data(&a, desc, g);
-            const size_t s2d_bytes = igemm_s2d(&a);
+            const size_t s2d_bytes = igemm_s2d(&a);   // (sized for the split variant whichever is selected)
             const int ks = igemm_ksplit(a);
             return s2d_bytes + (ks > 1 ? align256((size_t)ks * a.N * a.rows * a.OH * a.OW * 4) : 0);
         }
@@ -207,6 +264,7 @@ size_t int8t_workspace_bytes(int8t_op op, const int8t_conv_desc* desc, size_t n,
             WgradArgs a{};
             fill_wgrad_geometry(&a, desc, g);
             const size_t s2d_bytes = wgrad_s2d(&a);
+            a.variant = selected_variant(INT8T_OP_CONV_BWD_WEIGHT, desc);
             wgrad_plan(&a);
             return align256((size_t)a.splits * a.K * a.R * a.S * a.Cp * 4) + align256(s2d_bytes);
         }
@@ -463,6 +521,7 @@ int8t_status int8t_conv_fwd(const int8t_conv_desc* desc, const int8_t* xq_dev, c
     }
     IgemmArgs a{};
     fill_igemm_fwd(&a, desc, g);
+    a.variant = selected_variant(INT8T_OP_CONV_FWD, desc);
     a.act = xq_dev; a.wgt = wq_dev; a.sa = sx_dev; a.sb = sw_dev; a.out = y_dev; a.acc = acc_dev;
     a.partial = (int32_t*)ws_dev; a.partial_bytes = ws_dev ? ws_bytes : 0;
     {
@@ -498,6 +557,7 @@ int8t_status int8t_conv_bwd_data(const int8t_conv_desc* desc, const int8_t* dyq_
     }
     IgemmArgs a{};
     fill_igemm_bwd_data(&a, desc, g);
+    a.variant = selected_variant(INT8T_OP_CONV_BWD_DATA, desc);
     a.act = dyq_dev;
     // second copy of the weight codes: [C][R][S][Kp]
     a.wgt = wq_dev + align256((size_t)desc->K * desc->R * desc->S * pad16(desc->C));
@@ -531,6 +591,7 @@ int8t_status int8t_conv_bwd_weight(const int8t_conv_desc* desc, const int8_t* xq
     WgradArgs a{};
     fill_wgrad_geometry(&a, desc, g);
     wgrad_s2d(&a);
+    a.variant = selected_variant(INT8T_OP_CONV_BWD_WEIGHT, desc);
     wgrad_plan(&a);
     a.x = xq_dev; a.dy = dyq_dev; a.sa = sx_dev; a.sb = sdy_dev; a.dw = dw_dev; a.acc = acc_dev;
     a.partial = (int32_t*)ws_dev;

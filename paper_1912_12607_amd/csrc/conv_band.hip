@@ -432,7 +432,7 @@ __global__ __launch_bounds__(256, 2) void band_reg_kernel(const IgemmArgs a, int
 }
 
 // Returns true (and launches) when the layer fits this kernel; false: use the implicit GEMM.
-bool launch_band(const IgemmArgs& a, hipStream_t st, hipError_t* err) {
+bool launch_band(const IgemmArgs& a, hipStream_t st, hipError_t* err, bool dry_run) {
     if (a.stride_h != 1 || a.stride_w != 1 || a.rows > 64 || a.OW > BAND_MAXPIX) return false;
     const int Cg16 = a.Ca >> 4;
     const int G = a.R * a.S * Cg16;
@@ -453,6 +453,7 @@ bool launch_band(const IgemmArgs& a, hipStream_t st, hipError_t* err) {
     const size_t lds = ((size_t)64 * odd_pitch(G) + (size_t)WH * WW * odd_pitch(Cg16) + 1) * 16 +
                        (size_t)(G + 4) * sizeof(int2);
     if (lds > BAND_LDS_MAX) return false;
+    if (dry_run) return true;
     const int nbands_h = (a.OH + BP - 1) / BP;
     const int nbands = a.N * nbands_h;
     const int grid = nbands < 512 ? nbands : 512;

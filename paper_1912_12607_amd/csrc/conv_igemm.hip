@@ -25,10 +25,13 @@ namespace int8t {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-// 16-byte slot of (row, granule) inside a [rows][4 granules] LDS tile.  The xor keeps both the
-// loader's writes (4 lanes per row) and the MFMA operand reads (32 consecutive rows, one
-// granule) spread over all banks.
-__device__ __forceinline__ int lds_slot(int row, int g) { return row * 4 + (g ^ ((row >> 1) & 3)); }
+// 16-byte slot of (row, granule) inside a [rows][4 granules] LDS tile.  LDS serves a 16-byte-per-lane
+// access 16 lanes at a time, and those 16 lanes are conflict-free when their slots differ mod 16
+// (64 banks of 4 bytes).  MFMA operand reads are 16 consecutive rows of one granule: slot mod 16 =
+// 4 * (row & 3) + position, so the position must differ between rows r, r+4, r+8, r+12 -- the xor
+// with bits 2..3 of the row.  The loader's writes (4 consecutive rows x 4 granules) stay 16
+// consecutive slots.
+__device__ __forceinline__ int lds_slot(int row, int g) { return row * 4 + (g ^ ((row >> 2) & 3)); }
 
 // Strided backward-data by residue classes.  The input pixels (h, w) with h % stride_h == ch and
 // w % stride_w == cw all receive the same filter taps: r = r0 + stride_h * tr, s = s0 + stride_w * ts,
@@ -339,6 +342,7 @@ __global__ __launch_bounds__(256) void igemm_reduce_kernel(const IgemmArgs a, si
 // buffer descriptor: the hardware then writes zeros.
 //   <WM=2, KG=4, NSTAGE=3>: 128 x 256, 72 KB of LDS, two blocks per compute unit
 //   <WM=4, KG=8, NSTAGE=2>: 256 x 256, 128 KB of LDS, one block of eight waves per compute unit
+//   <WM=4, KG=4, NSTAGE=4>: 256 x 256, 128 KB of LDS, loads three (half as long) stages ahead
 // ---------------------------------------------------------------------------------------------
 constexpr uint32_t IGD_OOB = 0x80000000u;
 constexpr int IGD_BN = 256;
@@ -357,17 +361,20 @@ __device__ __forceinline__ void igd_load_lds(const v4i& rsrc, uint32_t lds_base_
     asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                  :: "s"(lds_base_uniform), "v"(voff), "s"(rsrc) : "memory");
 }
-// slot of (row, granule) in a [rows][KG] tile; the xor spreads the MFMA operand reads (consecutive
-// rows, one granule) over the banks
+// slot of (row, granule) in a [rows][KG] tile; the xor makes the MFMA operand reads (16 consecutive
+// rows of one granule per LDS pass) hit 16 different slots mod 16, see lds_slot(): with 8 granules per
+// row, slot mod 16 = 8 * (row & 1) + position, so rows of equal parity need different positions
 template <int KG>
 __device__ __forceinline__ int igd_slot(int row, int g) {
-    return KG == 4 ? row * 4 + (g ^ ((row >> 1) & 3)) : row * 8 + (g ^ (row & 7));
+    return KG == 4 ? row * 4 + (g ^ ((row >> 2) & 3)) : row * 8 + (g ^ ((row >> 1) & 7));
 }
 template <int N>
 __device__ __forceinline__ void igd_wait_vmcnt() {
-    static_assert(N == 0 || N == 6 || N == 12, "outstanding loads allowed while waiting");
+    static_assert(N == 0 || N == 4 || N == 6 || N == 8 || N == 12, "outstanding loads allowed while waiting");
     if (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else if (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
     else if (N == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+    else if (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
     else asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
 }
 
@@ -381,7 +388,7 @@ __global__ __launch_bounds__(128 * WM, WM == 2 ? 2 : 1) void igemm_dma_kernel(co
     constexpr int NLA = BM * KG / 64 / NW;              // A loads per wave and stage
     constexpr int NLB = BN * KG / 64 / NW;              // B loads per wave and stage
     constexpr int NL = NLA + NLB;
-    static_assert(NSTAGE == 2 || NL == 6, "vmcnt waits below are written for 6 loads per stage");
+    static_assert(NSTAGE == 2 || NL == 6 || (NSTAGE == 4 && NL == 4), "vmcnt waits below are written for these");
     extern __shared__ __attribute__((aligned(16))) uint4 ring[];   // [NSTAGE][STAGE_SLOTS]
 
     const int tid = threadIdx.x;
@@ -433,7 +440,11 @@ __global__ __launch_bounds__(128 * WM, WM == 2 ? 2 : 1) void igemm_dma_kernel(co
     // ---- loader state: this wave issues A loads {wave + NW*i} and B loads {wave + NW*i}.  Load
     // number wl covers tile rows RPL*wl .. RPL*wl + RPL-1; lane -> (row, granule) through the swizzle.
     const int lrow = lane / KG;                              // row inside the load's row group
-    const int gsw = KG == 4 ? ((lane & 3) ^ ((lrow >> 1) & 3)) : ((lane & 7) ^ (lrow & 7));   // granule held by this lane's slot
+    // granule held by this lane's slot: the inverse of igd_slot().  KG = 4: a load covers 16 rows from a
+    // multiple of 16, bits 2..3 of the row are those of lrow.  KG = 8: a load covers 8 rows from
+    // 8 * (wave + NW * i); with NW even, bit 3 of the row is the wave's parity for every i.
+    static_assert(KG == 4 || (NW & 1) == 0, "the swizzle of the 8-granule tile needs an even wave count");
+    const int gsw = KG == 4 ? ((lane & 3) ^ ((lrow >> 2) & 3)) : ((lane & 7) ^ (((lrow >> 1) & 3) | ((wave & 1) << 2)));
     uint32_t aoff[NLA];                                      // byte offset of (row, granule 0) or OOB
 #pragma unroll
     for (int i = 0; i < NLA; ++i) {
@@ -526,15 +537,19 @@ __global__ __launch_bounds__(128 * WM, WM == 2 ? 2 : 1) void igemm_dma_kernel(co
         issue_a(0);
         issue_b(0);
     }
-    if (NSTAGE == 3 && nsteps > 1) {
-        issue_a(1);
-        issue_b(1);
+#pragma unroll
+    for (int p = 1; p < NSTAGE - 1; ++p) {
+        if (nsteps > p) {
+            issue_a(p);
+            issue_b(p);
+        }
     }
     for (int step = 0; step < nsteps; ++step) {
         const int buf = step % NSTAGE;
-        // this stage's loads are the oldest outstanding ones; with three buffers the next stage's
-        // may still be in flight
-        if (NSTAGE == 3 && step + 1 < nsteps) igd_wait_vmcnt<NSTAGE == 3 ? NL : 0>();
+        // this stage's loads are the oldest outstanding ones; the loads of the up to NSTAGE - 2 stages
+        // behind it may still be in flight
+        if (NSTAGE == 4 && step + 2 < nsteps) igd_wait_vmcnt<NSTAGE == 4 ? 2 * NL : 0>();
+        else if (NSTAGE >= 3 && step + 1 < nsteps) igd_wait_vmcnt<NSTAGE >= 3 ? NL : 0>();
         else igd_wait_vmcnt<0>();
         __syncthreads();   // every wave's part of this stage is in LDS; stage step-1 has been read by all
         // the next loads go into the buffer read in stage step-1; the weight half is requested now,
@@ -564,7 +579,7 @@ __global__ __launch_bounds__(128 * WM, WM == 2 ? 2 : 1) void igemm_dma_kernel(co
 #pragma unroll
                 for (int j = 0; j < NJ; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
-            if (kk == KG / 4 - 1 && more) issue_b(nbuf);
+            if (kk == (KG >= 8 ? KG / 4 - 1 : 0) && more) issue_b(nbuf);
         }
     }
 
@@ -691,7 +706,7 @@ static void launch_igemm_generic(const IgemmArgs& a, const IgemmShape& g, int ks
 // connected layer) leave most compute units idle: their reduction is split over up to
 // ceil(512 / tiles) blocks per tile, at least 4 stages each.  1 = no split.
 int igemm_ksplit(const IgemmArgs& a) {
-    if (a.rows <= 64 || igemm_wide(a)) return 1;
+    if (a.rows <= 64) return 1;
     const IgemmShape g = igemm_shape(a);
     const long long tiles = g.ncls * ((g.ncols + 127) / 128) * ((a.rows + 127) / 128);
     const long long nsteps = (g.gran + 3) / 4;
@@ -699,6 +714,32 @@ int igemm_ksplit(const IgemmArgs& a) {
     long long ks = (512 + tiles - 1) / tiles;
     if (ks > nsteps / 4) ks = nsteps / 4;
     return ks < 2 ? 1 : (int)ks;
+}
+
+// The variant the library picks on its own (rules from measurements over the layers of ResNet-50,
+// MobileNetV2 and InceptionV3); a caller may overrule it per layer (include/int8t.h).
+int igemm_auto_variant(const IgemmArgs& a) {
+    hipError_t e = hipSuccess;
+    if (launch_band(a, nullptr, &e, true)) return VAR_BAND;
+    if (a.rows <= 64) return VAR_TILE;
+    if (igemm_wide(a)) {
+        // 256-row tiles only where they are full (half-empty ones cost the short reductions of a
+        // residue class a quarter of their time)
+        const IgemmShape g = igemm_shape(a);
+        const long long t256 = g.ncls * ((g.ncols + 255) / 256) * ((a.rows + 255) / 256);
+        return (t256 >= 192 && a.rows > 128) ? VAR_WIDE256 : VAR_WIDE128;
+    }
+    return igemm_ksplit(a) > 1 ? VAR_TILE_SPLIT : VAR_TILE;
+}
+
+bool igemm_variant_ok(const IgemmArgs& a, int variant) {
+    hipError_t e = hipSuccess;
+    switch (variant) {
+        case VAR_AUTO: case VAR_TILE: case VAR_WIDE128: case VAR_WIDE256: case VAR_WIDE256_DEEP: return true;
+        case VAR_BAND: return launch_band(a, nullptr, &e, true);
+        case VAR_TILE_SPLIT: return igemm_ksplit(a) > 1;
+        default: return false;
+    }
 }
 
 size_t igemm_s2d(IgemmArgs* a) {
@@ -734,15 +775,20 @@ hipError_t launch_igemm(const IgemmArgs& a_in, hipStream_t st) {
             a = t;
         }
     }
-    hipError_t berr = hipSuccess;
-    if (launch_band(a, st, &berr)) return berr;   // small filter bank: LDS-resident kernel
+    int variant = a.variant;
+    if (variant == VAR_AUTO || !igemm_variant_ok(a, variant)) variant = igemm_auto_variant(a);
+    if (variant == VAR_BAND) {
+        hipError_t berr = hipSuccess;
+        if (launch_band(a, st, &berr)) return berr;   // small filter bank: LDS-resident kernel
+        return hipErrorInvalidValue;                  // (igemm_variant_ok said it fits)
+    }
     const IgemmShape g = igemm_shape(a);
     a.cls_h = g.cls_h;
     a.cls_w = g.cls_w;
     a.cell = g.cell;
     const int ncols = a.N * a.OH * a.OW;
     // the split needs its scratch; without it the reduction simply stays whole
-    a.ksplit = igemm_ksplit(a);
+    a.ksplit = variant == VAR_TILE_SPLIT ? igemm_ksplit(a) : 1;
     if (a.ksplit > 1 && (a.partial == nullptr || a.partial_bytes < (size_t)a.ksplit * a.rows * ncols * 4)) a.ksplit = 1;
     if (a.ksplit > 1) {
         {
@@ -758,12 +804,10 @@ hipError_t launch_igemm(const IgemmArgs& a_in, hipStream_t st) {
         else launch_timed(kt, igemm_reduce_kernel<false>, rgrid, dim3(256), 0, st, a, total);
         return hipGetLastError();
     }
-    if (a.rows > 64 && igemm_wide(a)) {
+    if (variant == VAR_WIDE128 || variant == VAR_WIDE256 || variant == VAR_WIDE256_DEEP) {
         KernelTimer kt(KID_IGEMM_DMA, st);
-        // 256-row tiles only where they are full (half-empty ones cost the short reductions of a
-        // residue class a quarter of their time)
-        const long long t256 = g.ncls * ((g.ncols + 255) / 256) * ((a.rows + 255) / 256);
-        if (t256 >= 192 && a.rows > 128) return launch_igemm_dma_any<4, 8, 2>(a, g, st, kt);
+        if (variant == VAR_WIDE256) return launch_igemm_dma_any<4, 8, 2>(a, g, st, kt);
+        if (variant == VAR_WIDE256_DEEP) return launch_igemm_dma_any<4, 4, 4>(a, g, st, kt);
         return launch_igemm_dma_any<2, 4, 3>(a, g, st, kt);
     }
     KernelTimer kt(KID_IGEMM, st);

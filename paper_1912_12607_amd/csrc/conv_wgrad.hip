@@ -402,29 +402,29 @@ size_t wgrad_s2d(WgradArgs* a) {
 namespace {
 // The plan of the most recent geometry, per host thread: a layer is planned once, not per call.
 struct PlanCache {
-    int key[15];
+    int key[16];
     WgradArgs plan;
     bool valid;
 };
 thread_local PlanCache g_plan_cache = {};
 
-void plan_key(const WgradArgs* a, int key[15]) {
-    const int k[15] = {a->N, a->C, a->Cp, a->H, a->W, a->K, a->Kp, a->P, a->Q, a->R, a->S,
-                       a->stride_h, a->stride_w, a->pad_h, a->pad_w};
-    for (int i = 0; i < 15; ++i) key[i] = k[i];
+void plan_key(const WgradArgs* a, int key[16]) {
+    const int k[16] = {a->N, a->C, a->Cp, a->H, a->W, a->K, a->Kp, a->P, a->Q, a->R, a->S,
+                       a->stride_h, a->stride_w, a->pad_h, a->pad_w, a->variant};
+    for (int i = 0; i < 16; ++i) key[i] = k[i];
 }
 void wgrad_plan_uncached(WgradArgs* a);
 }  // namespace
 
 void wgrad_plan(WgradArgs* a) {
-    int key[15];
+    int key[16];
     plan_key(a, key);
     PlanCache& c = g_plan_cache;
     bool hit = c.valid;
-    for (int i = 0; hit && i < 15; ++i) hit = c.key[i] == key[i];
+    for (int i = 0; hit && i < 16; ++i) hit = c.key[i] == key[i];
     if (!hit) {
         wgrad_plan_uncached(a);
-        for (int i = 0; i < 15; ++i) c.key[i] = key[i];
+        for (int i = 0; i < 16; ++i) c.key[i] = key[i];
         c.plan = *a;
         c.valid = true;
         return;
@@ -513,6 +513,9 @@ void wgrad_plan_uncached(WgradArgs* a) {
         if (t < best) { best = t; splits = sp; }
         if (blocks > 8LL * slots || (long long)a->chunks * (sp + 2) >= (1LL << 31)) break;
     }
+    // a caller may ask for half or twice the shares of this choice (per-layer tuning by measurement)
+    if (a->variant == VAR_WGRAD_FEWER) splits = splits > 1 ? splits / 2 : 1;
+    if (a->variant == VAR_WGRAD_MORE) splits = (2 * splits <= a->chunks && 2 * splits <= 4096) ? 2 * splits : splits;
     a->splits = splits;
 }
 }  // namespace

@@ -127,14 +127,32 @@ struct IgemmArgs {
     int32_t* partial;            // nullable scratch [ksplit][N][rows][OH*OW] of a split reduction
     size_t partial_bytes;
     int ksplit;                  // filled by launch_igemm(): blocks per output tile along the reduction
+    int variant;                 // ConvVariant: VAR_AUTO, or the kernel the caller selected for this layer
 };
-int igemm_ksplit(const IgemmArgs& a);   // split the launch will use when given enough scratch (1 = none)
+// Kernel variants of the dense passes (values of INT8T_VARIANT_* in include/int8t.h).
+enum ConvVariant : int {
+    VAR_AUTO = 0,
+    VAR_BAND = 1,          // forward / backward-data: filter bank resident on chip (conv_band.hip)
+    VAR_TILE = 2,          // 64/128 x 128 tiles through registers, reduction whole
+    VAR_TILE_SPLIT = 3,    // ... reduction split over several blocks per tile
+    VAR_WIDE128 = 4,       // 128 x 256 tiles, operands straight into an LDS ring of 3 stages
+    VAR_WIDE256 = 5,       // 256 x 256 tiles, ring of 2 stages of 128 reduction bytes
+    VAR_WIDE256_DEEP = 6,  // 256 x 256 tiles, ring of 4 stages of 64 reduction bytes
+    VAR_WGRAD_FEWER = 7,   // backward-weight: half the reduction shares of the cost model's choice
+    VAR_WGRAD_MORE = 8,    // backward-weight: twice as many
+    VAR_COUNT
+};
+int igemm_ksplit(const IgemmArgs& a);   // largest split a launch of this layer may use (1 = none): sizes the scratch
+// whether `variant` can run this layer (VAR_AUTO always can); resolved = the variant VAR_AUTO stands for
+bool igemm_variant_ok(const IgemmArgs& a, int variant);
+int igemm_auto_variant(const IgemmArgs& a);
 // Forward pass of a layer s2d.hip covers: rewrites the geometry and returns the scratch bytes of the
 // rewritten input and filter codes (0: does not apply, the geometry is left alone).
 size_t igemm_s2d(IgemmArgs* a);
 hipError_t launch_igemm(const IgemmArgs& a, hipStream_t st);
 // conv_band.hip: LDS-resident variant for small filter banks; false = shape not covered
-bool launch_band(const IgemmArgs& a, hipStream_t st, hipError_t* err);
+// (dry_run: only say whether the shape is covered, launch nothing)
+bool launch_band(const IgemmArgs& a, hipStream_t st, hipError_t* err, bool dry_run = false);
 
 // ---- s2d.hip ----------------------------------------------------------------------------------
 // A stride-2 layer with at most 4 input channels (the stem of an image network) as the stride-1
@@ -186,6 +204,7 @@ struct WgradArgs {
     int s2d;                     // 1: C, Cp, H, W, R, S, strides and pads describe the rewritten problem
     int oC, oR, oS, oH, oW, eh, ew;   // the layer's own channels, filter and image; tap r = 2 r' + dy - eh, s = 2 s' + dx - ew
     int8_t* xs;                  // scratch: the input codes in space-to-depth form, [N][H][W][16]
+    int variant;                 // VAR_AUTO, VAR_WGRAD_FEWER or VAR_WGRAD_MORE: set before wgrad_plan()
 };
 // Rewrites the geometry into the space-to-depth form (s2d.hip) when it applies.  Returns the bytes of
 // the rewritten input codes (0: does not apply, the geometry is left alone).  Call before wgrad_plan().

@@ -264,6 +264,56 @@ class LayerStep:
         self._tuned_overlap = best[1] < best[0]
         return self._tuned_overlap
 
+    def tune_kernels(self, reps: int = 30, verbose: bool = False) -> dict:
+        """The per-layer choice of the convolution kernels "before training" (Suppl. "INT8 Convolution",
+        last paragraph): for each of the three passes, times every kernel variant the library admits for
+        this layer on the layer's own buffers and selects the fastest (int8t_conv_select_variant; the
+        library keeps the choice per (pass, shape), so every layer of that shape in the process uses it).
+        All variants write identical results.  The code buffers must hold codes (run() once before).
+        Returns {pass: (chosen variant name, {variant name: microseconds})}."""
+        import time
+        if self.depthwise:
+            return {}
+        out = {}
+        for name, op, call in (("fwd", B.OP_CONV_FWD, "_k_fwd"), ("bwd_data", B.OP_CONV_BWD_DATA, "_k_bwd_data"),
+                               ("bwd_weight", B.OP_CONV_BWD_WEIGHT, "_k_bwd_weight")):
+            if name == "bwd_data" and not self.input_grad:
+                continue
+            times = {}
+            sp = B.stream_pointer(None)
+            for v in range(len(B.VARIANT_NAMES)):
+                if not B.int8t_conv_variant_ok(op, self.desc, v):
+                    continue
+                B.int8t_conv_select_variant(op, self.desc, v)
+                if op == B.OP_CONV_BWD_WEIGHT:
+                    need = B.int8t_workspace_bytes(op, self.desc)      # depends on the variant's split count
+                    if need > self.ws.numel():
+                        self.ws = torch.empty(need, dtype=torch.uint8, device=self.dev)
+                        self._bind_calls()
+                fn = getattr(self, call)
+                for _ in range(5):
+                    fn(sp)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(reps):
+                    fn(sp)
+                torch.cuda.synchronize()
+                times[v] = (time.perf_counter() - t0) / reps * 1e6
+            # the library's own choice stays unless another variant is at least 2 % faster (timing noise)
+            best = min(times, key=times.get)
+            if times[best] > 0.98 * times[B.VARIANT_AUTO]:
+                best = B.VARIANT_AUTO
+            B.int8t_conv_select_variant(op, self.desc, best)
+            if op == B.OP_CONV_BWD_WEIGHT:
+                need = B.int8t_workspace_bytes(op, self.desc)
+                if need > self.ws.numel():
+                    self.ws = torch.empty(need, dtype=torch.uint8, device=self.dev)
+                    self._bind_calls()
+            out[name] = (B.VARIANT_NAMES[best], {B.VARIANT_NAMES[v]: round(t, 2) for v, t in times.items()})
+            if verbose:
+                print(self.L.name, name, out[name], flush=True)
+        return out
+
     # -- host copies of the code tensors in logical order (the library's own unpacking aid) ----------
     def codes_x(self) -> np.ndarray:
         return unpack_act(self.xq.cpu().numpy(), self.L.x_shape, self.depthwise)

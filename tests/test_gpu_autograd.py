@@ -130,3 +130,90 @@ def test_dclr_sgd_scales_each_layer_by_phi():
         err = (p.detach() - (b - lr * g)).abs().max().item()
         assert err <= 4 * 2.0 ** -24 * (b.abs() + lr * g.abs()).max().item()      # one fp32 rounding each side
 
+
+
+def test_int8_linear_matches_oracle_and_bias_stays_fp32():
+    """The fully connected counterpart (Sec.3.6 item 1) is the 1x1 convolution of a 1x1 image through the
+    same entry points; the bias is added in fp32 to the dequantized result."""
+    from paper_1912_12607_amd.autograd import Int8Linear
+    torch.manual_seed(2)
+    N, Cin, K = 33, 200, 70
+    m = Int8Linear(Cin, K, bias=True, seed=100)
+    with torch.no_grad():
+        m.bias.copy_(torch.randn(K, device="cuda"))
+    assert tuple(m.weight.shape) == (K, Cin)
+    r = np.random.default_rng(11)
+    x = r.standard_normal((N, Cin)).astype(np.float32)
+    xt = torch.from_numpy(x).cuda().requires_grad_(True)
+    y = m(xt)
+    assert tuple(y.shape) == (N, K)
+    dy = (r.standard_t(3, size=(N, K)) * 1e-3).astype(np.float32)
+    y.backward(torch.from_numpy(dy).cuda())
+    torch.cuda.synchronize()
+    w = m.weight.detach().cpu().numpy().reshape(K, Cin, 1, 1)
+    od = oracle.make_desc(N, Cin, 1, 1, K, 1, 1)
+    xq, sx = oracle.quantize(x.reshape(N, Cin, 1, 1))
+    wq, sw = oracle.quantize(w)
+    o = oracle.dsgc(dy.reshape(-1), inputs.default_ratios(32), mode=STO, seed=101)
+    dyq, sdy = oracle.quantize(dy.reshape(N, K, 1, 1), c=o["clip"], mode=STO, seed=101)
+    ref_y = oracle.dequant(oracle.wrap32(oracle.conv_fwd(od, xq, wq))[0], sx, sw).reshape(N, K)
+    want_y = ref_y + m.bias.detach().cpu().numpy()[None, :]
+    assert np.all(np.abs(y.detach().cpu().numpy() - want_y) <= REL_TOL * np.abs(ref_y) + 2.0 ** -23 * np.abs(want_y))
+    ref_dx = oracle.dequant(oracle.wrap32(oracle.conv_bwd_data(od, dyq, wq))[0], sdy, sw).reshape(N, Cin)
+    ref_dw = oracle.dequant(oracle.wrap32(oracle.conv_bwd_weight(od, xq, dyq))[0], sx, sdy).reshape(K, Cin)
+    assert np.all(np.abs(xt.grad.cpu().numpy() - ref_dx) <= REL_TOL * np.abs(ref_dx))
+    assert m.weight.grad.shape == (K, Cin)
+    assert np.all(np.abs(m.weight.grad.cpu().numpy() - ref_dw) <= REL_TOL * np.abs(ref_dw))
+    assert np.allclose(m.bias.grad.cpu().numpy(), dy.sum(0), rtol=1e-5, atol=1e-9)
+
+
+def test_replace_modules_swaps_conv_and_linear_and_trains_without_new_buffers():
+    """The automatic match and replacement (Sec.3.6 item 1): Conv2d (dense and depthwise) and Linear
+    become INT8 layers that keep the very Parameter objects; a convolution the library does not cover
+    (dilation 2) and a skipped module stay; the replaced model's output and gradients point the same
+    way as the fp32 model's; after the first iteration a training loop re-uses every code buffer."""
+    from paper_1912_12607_amd.autograd import DclrSGD, Int8Conv2d, Int8Linear, replace_modules
+    torch.manual_seed(4)
+    nn = torch.nn
+
+    def make():
+        return nn.Sequential(nn.Conv2d(3, 16, 3, padding=1, bias=True), nn.ReLU(),
+                             nn.Conv2d(16, 16, 3, padding=1, groups=16, bias=False), nn.ReLU(),
+                             nn.Conv2d(16, 24, 3, padding=2, dilation=2), nn.ReLU(),
+                             nn.Conv2d(24, 32, 1, stride=2), nn.Flatten(),
+                             nn.Linear(32 * 5 * 5, 10), nn.ReLU(), nn.Linear(10, 4)).cuda()
+    ref = make()
+    model = make()
+    model.load_state_dict(ref.state_dict())
+    params = [id(p) for p in model.parameters()]
+    assert replace_modules(model, skip=("10",)) == 4
+    assert [type(m).__name__ for m in model] == ["Int8Conv2d", "ReLU", "Int8Conv2d", "ReLU", "Conv2d", "ReLU",
+                                                 "Int8Conv2d", "Flatten", "Int8Linear", "ReLU", "Linear"]
+    assert [id(p) for p in model.parameters()] == params
+    assert set(model.state_dict()) == set(ref.state_dict())
+    assert len({m._seed for m in model if isinstance(m, Int8Conv2d)}) == 4       # every layer its own draw stream
+    x = torch.randn(6, 3, 10, 10, device="cuda")
+    cos = lambda a, b: float(torch.nn.functional.cosine_similarity(a.detach().flatten(), b.detach().flatten(), dim=0))
+    ya, yb = model(x), ref(x)
+    assert cos(ya, yb) > 0.995
+    ya.square().sum().backward()
+    yb.square().sum().backward()
+    for (n, pa), pb in zip(model.named_parameters(), ref.parameters()):
+        assert pa.grad is not None and pa.grad.shape == pb.grad.shape, n
+        assert cos(pa.grad, pb.grad) > 0.95, n
+    opt = DclrSGD(model, lr=1e-3)
+    assert len(opt.deviations()) == 4 and all(0.0 <= d <= 2.0 for d in opt.deviations())
+    int8 = [m for m in model if isinstance(m, Int8Conv2d)]
+    held = None
+    for it in range(4):
+        opt.zero_grad()
+        model(x).square().sum().backward()
+        opt.step()
+        bufs = [id(b.ws) for m in int8 for b in m._buffers.values()] + [id(t[0]) for m in int8 for b in m._buffers.values() for t in b.xq_pool]
+        assert all(len(m._buffers) == 1 and len(next(iter(m._buffers.values())).xq_pool) == 1 for m in int8)
+        if held is not None:
+            assert bufs == held                    # same scratch and code buffers as in the previous iteration
+        held = bufs
+    with torch.no_grad():                          # inference: the activation codes go straight back to the pool
+        model(x)
+    assert all(len(next(iter(m._buffers.values())).xq_pool) == 1 for m in int8)

@@ -663,6 +663,79 @@ def test_tuned_schedule_writes_the_same_tensors():
         assert torch.equal(a, b)
 
 
+def test_every_kernel_variant_is_exact():
+    """Per-layer kernel choice: every variant int8t_conv_variant_ok() admits for a pass of a layer --
+    i.e. everything a tuner may select -- writes the oracle's accumulators and results, on small layers
+    with ragged channels, several taps, strides and padding (each variant also runs layers it would never
+    be chosen for).  The selection is restored to the library's own choice afterwards."""
+    shapes = [(2, 16, 16, 16, 32, 3, 3, (1, 1), (1, 1), 1), (3, 64, 14, 14, 130, 3, 3, (1, 1), (1, 1), 1),
+              (2, 70, 9, 11, 40, 1, 7, (1, 1), (0, 3), 1), (2, 256, 9, 9, 96, 3, 3, (2, 2), (0, 0), 1),
+              (2, 24, 9, 9, 144, 1, 1, (1, 1), (0, 0), 1), (1, 40, 33, 6, 130, 4, 3, (3, 1), (0, 1), 1),
+              (2, 64, 8, 8, 128, 1, 1, (2, 2), (0, 0), 1), (40, 520, 1, 1, 200, 1, 1, (1, 1), (0, 0), 1),
+              (2, 3, 12, 10, 8, 7, 7, (2, 2), (3, 3), 1), (17, 130, 7, 37, 72, 5, 3, (1, 2), (2, 1), 1)]
+    one = dev(np.array([1.0], np.float32))
+    seen = set()
+    for shape in shapes:
+        N, C, H, W, K, R, S, st, pd, g = shape
+        od = oracle.make_desc(*shape)
+        gd = B.make_desc(*shape)
+        P, Q = oracle.out_hw(od)
+        r = np.random.RandomState(abs(hash(shape)) % 2 ** 31)
+        x = r.randint(-127, 128, size=(N, C, H, W)).astype(np.int8)
+        w = r.randint(-127, 128, size=(K, C, R, S)).astype(np.int8)
+        dy = r.randint(-127, 128, size=(N, K, P, Q)).astype(np.int8)
+        xq, dyq, wq = dev(pack_act(x)), dev(pack_act(dy)), dev(pack_wgt(w))
+        for name, fn, op, a, b, so, want in (
+            ("fwd", B.int8t_conv_fwd, B.OP_CONV_FWD, xq, wq, (N, K, P, Q), oracle.conv_fwd(od, x, w)),
+            ("bwd_data", B.int8t_conv_bwd_data, B.OP_CONV_BWD_DATA, dyq, wq, (N, C, H, W), oracle.conv_bwd_data(od, dy, w)),
+            ("bwd_weight", B.int8t_conv_bwd_weight, B.OP_CONV_BWD_WEIGHT, xq, dyq, (K, C, R, S), oracle.conv_bwd_weight(od, x, dy)),
+        ):
+            want32, _ = oracle.wrap32(want)
+            try:
+                for v in range(len(B.VARIANT_NAMES)):
+                    if not B.int8t_conv_variant_ok(op, gd, v):
+                        with pytest.raises(B.Int8tError):
+                            B.int8t_conv_select_variant(op, gd, v)
+                        continue
+                    B.int8t_conv_select_variant(op, gd, v)
+                    assert B.int8t_conv_selected_variant(op, gd) == v
+                    seen.add((name, v))
+                    ws = torch.empty(max(256, B.int8t_workspace_bytes(op, gd)), dtype=torch.uint8, device=DEV)
+                    out = torch.full(so, float("nan"), dtype=torch.float32, device=DEV)
+                    acc = torch.full(so, -12345, dtype=torch.int32, device=DEV)
+                    fn(gd, a, one, b, one, out, acc, ws)
+                    torch.cuda.synchronize()
+                    assert np.array_equal(acc.cpu().numpy(), want32), (name, B.VARIANT_NAMES[v], shape)
+                    assert np.array_equal(out.cpu().numpy(), want32.astype(np.float32)), (name, B.VARIANT_NAMES[v], shape)
+            finally:
+                B.int8t_conv_select_variant(op, gd, B.VARIANT_AUTO)
+    # every variant ran at least once in each pass it exists for
+    for v in (B.VARIANT_BAND, B.VARIANT_TILE, B.VARIANT_TILE_SPLIT, B.VARIANT_WIDE128, B.VARIANT_WIDE256, B.VARIANT_WIDE256_DEEP):
+        assert ("fwd", v) in seen and ("bwd_data", v) in seen, B.VARIANT_NAMES[v]
+    assert ("bwd_weight", B.VARIANT_WGRAD_FEWER) in seen and ("bwd_weight", B.VARIANT_WGRAD_MORE) in seen
+
+
+def test_tuned_kernels_write_the_same_tensors():
+    L, x, w, dy = inputs.make_layer_inputs(2, 1)
+    st = LayerStep(L, n_cand=32, requantize_deviation=False, keep_acc=True)
+    st.upload(x, w, dy, inputs.default_ratios(32))
+    st.run(seed=4, overlap=False)
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (st.y, st.dx, st.dw, st.y_acc, st.dx_acc, st.dw_acc)]
+    try:
+        choice = st.tune_kernels(reps=5)
+        assert set(choice) == {"fwd", "bwd_data", "bwd_weight"}
+        for t in (st.y, st.dx, st.dw):
+            t.zero_()
+        st.run(seed=4, overlap=False)
+        torch.cuda.synchronize()
+        for a, b in zip(want, (st.y, st.dx, st.dw, st.y_acc, st.dx_acc, st.dw_acc)):
+            assert torch.equal(a, b)
+    finally:
+        for op in (B.OP_CONV_FWD, B.OP_CONV_BWD_DATA, B.OP_CONV_BWD_WEIGHT):
+            B.int8t_conv_select_variant(op, st.desc, B.VARIANT_AUTO)
+
+
 def test_same_seed_same_codes_different_seed_differs():
     L, x, w, dy = inputs.make_layer_inputs(0, 0)
     a, _, _ = gpu_quantize(dy, B.ACT, 0.01, STO, seed=42)
