@@ -264,6 +264,27 @@ int8t_status int8t_conv_fwd(const int8t_conv_desc *desc,
                             void *ws_dev, size_t ws_bytes, void *stream);
 
 /*
+ * The quantization-convolution fused kernel of the paper's Suppl. "INT8 Convolution" ("avoids one
+ * extra global memory read and write"), for the layers where it saves traffic here: a 1 x 1 filter at
+ * stride 1 without padding (dense).  int8t_quantize(a) + int8t_conv_fwd in one call: the forward pass
+ * reads the fp32 activations, applies Eq.1 (round to nearest) in its load path with c = *clip_dev or
+ * max|a| (found by a first pass when clip_dev is NULL), and multiplies the codes without their making
+ * the round trip through memory.  Results are bit for bit those of the two separate calls.
+ *   x_dev    fp32 N,C,H,W;  wq_dev / sw_dev as in int8t_conv_fwd
+ *   xq_dev   NULL, or out: the INT8T_ACT codes of a, for the backward-weight pass (a forward-only
+ *            caller leaves it out and saves their write as well)
+ *   sx_dev   out: 1 float, the scale of a
+ *   ws_dev   1024 floats of scratch when clip_dev is NULL, else unused
+ * INT8T_ERR_SHAPE for any other filter, stride, padding or a depthwise layer.  A layer with more
+ * than 128 filters reads (and quantizes) its activations once per 128 filters: the separate calls are
+ * the better choice there.
+ */
+int8t_status int8t_conv_fwd_fused(const int8t_conv_desc *desc, const float *x_dev, const float *clip_dev,
+                                  const int8_t *wq_dev, const float *sw_dev,
+                                  float *y_dev, int32_t *acc_dev, int8_t *xq_dev, float *sx_dev,
+                                  void *ws_dev, size_t ws_bytes, void *stream);
+
+/*
  * Backward-data: acc[n,c,h,w] = sum over (k,r,s,p,q) with p*sh+r-ph = h, q*sw+s-pw = w of
  * dyq[n,k,p,q] * wq[k,c,r,s];  dx = (float)acc * (sdy * sw).
  *   dyq_dev  INT8T_ACT codes of dims {N,K,P,Q} (planar when depthwise);  wq_dev as in forward
@@ -328,7 +349,7 @@ int8t_variant int8t_conv_selected_variant(int8t_op op, const int8t_conv_desc *de
  * disturbed correspondingly less.
  *   kernel   host string: the kernel's name ("dsgc_sweep_kernel", "absmax_kernel",
  *            "absmax_batch_kernel", "quantize_batch_kernel", "quantize_act_kernel", "quantize_planar_kernel", "quantize_wgt_kernel",
- *            "deviation_finish_kernel", "igemm_kernel", "igemm_dma_kernel", "igemm_reduce_kernel",
+ *            "deviation_finish_kernel", "igemm_kernel", "igemm_dma_kernel", "igemm_fused_kernel", "igemm_reduce_kernel",
  *            "band_kernel", "band_reg_kernel", "wgrad_kernel", "wgrad_reduce_kernel", "s2d_repack_kernel",
  *            "s2d_weights_kernel", "dw_conv_kernel" (every depthwise forward / backward-data variant),
  *            "dw_wgrad_kernel" (both depthwise backward-weight variants), "dw_wgrad_reduce_kernel");

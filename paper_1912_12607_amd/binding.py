@@ -25,7 +25,7 @@ MAX_BATCH = 8
 
 EXPORTS = ["int8t_status_string", "int8t_code_bytes", "int8t_unpack_codes", "int8t_workspace_bytes",
            "int8t_quantize_workspace_bytes", "int8t_quantize", "int8t_quantize_batch_workspace_bytes",
-           "int8t_quantize_batch", "int8t_dsgc_clip", "int8t_dsgc_clip_static", "int8t_dsgc_prepare", "int8t_dsgc_search", "int8t_conv_fwd",
+           "int8t_quantize_batch", "int8t_dsgc_clip", "int8t_dsgc_clip_static", "int8t_dsgc_prepare", "int8t_dsgc_search", "int8t_conv_fwd", "int8t_conv_fwd_fused",
            "int8t_conv_bwd_data", "int8t_conv_bwd_weight", "int8t_dclr_scale",
            "int8t_conv_variant_ok", "int8t_conv_select_variant", "int8t_conv_selected_variant",
            "int8t_profile_start", "int8t_profile_start_sampled", "int8t_profile_stop"]
@@ -85,6 +85,8 @@ def _load():
         f = getattr(L, name)
         f.restype = i32
         f.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.int8t_conv_fwd_fused.restype = i32
+    L.int8t_conv_fwd_fused.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     L.int8t_conv_variant_ok.restype = i32
     L.int8t_conv_variant_ok.argtypes = [i32, dp, i32]
     L.int8t_conv_select_variant.restype = i32
@@ -236,6 +238,11 @@ def int8t_dsgc_search(g, n, ratios, n_cand, mode, seed, clip, deviation, deviati
 def int8t_conv_fwd(desc, xq, sx, wq, sw, y, acc=None, ws=None, stream=None):
     _check(lib.int8t_conv_fwd(C.byref(desc), _ptr(xq), _ptr(sx), _ptr(wq), _ptr(sw), _ptr(y), _ptr(acc),
                               _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def int8t_conv_fwd_fused(desc, x, clip, wq, sw, y, acc=None, xq=None, sx=None, ws=None, stream=None):
+    _check(lib.int8t_conv_fwd_fused(C.byref(desc), _ptr(x), _ptr(clip), _ptr(wq), _ptr(sw), _ptr(y), _ptr(acc),
+                                    _ptr(xq), _ptr(sx), _ptr(ws), _nbytes(ws), _stream(stream)))
 
 
 def int8t_conv_bwd_data(desc, dyq, sdy, wq, sw, dx, acc=None, ws=None, stream=None):

@@ -537,6 +537,35 @@ int8t_status int8t_conv_fwd(const int8t_conv_desc* desc, const int8_t* xq_dev, c
     return launch_igemm(a, st) == hipSuccess ? INT8T_OK : INT8T_ERR_RUNTIME;
 }
 
+int8t_status int8t_conv_fwd_fused(const int8t_conv_desc* desc, const float* x_dev, const float* clip_dev,
+                                  const int8_t* wq_dev, const float* sw_dev, float* y_dev, int32_t* acc_dev,
+                                  int8_t* xq_dev, float* sx_dev, void* ws_dev, size_t ws_bytes, void* stream) {
+    Geo g;
+    int8t_status s = desc_ok(desc, &g);
+    if (s != INT8T_OK) return s;
+    if (g.depthwise || desc->R != 1 || desc->S != 1 || desc->stride_h != 1 || desc->stride_w != 1 || desc->pad_h || desc->pad_w)
+        return INT8T_ERR_SHAPE;
+    if (!x_dev || !wq_dev || !sw_dev || !y_dev || !sx_dev) return INT8T_ERR_NULL;
+    if (!aligned16(x_dev) || !aligned16(wq_dev) || !aligned16(y_dev) || !aligned4(acc_dev) || !aligned16(xq_dev) ||
+        !aligned4(sx_dev) || !aligned4(clip_dev) || !aligned16(ws_dev))
+        return INT8T_ERR_ARG;
+    if (!clip_dev) {
+        if (!ws_dev) return INT8T_ERR_NULL;
+        if (ws_bytes < kMaxPartials * sizeof(float)) return INT8T_ERR_WORKSPACE;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    IgemmArgs a{};
+    fill_igemm_fwd(&a, desc, g);
+    a.xf = x_dev; a.xclip = clip_dev; a.xq_out = xq_dev; a.sx_out = sx_dev;
+    a.wgt = wq_dev; a.sb = sw_dev; a.out = y_dev; a.acc = acc_dev;
+    if (!clip_dev) {
+        a.xabs_part = (const float*)ws_dev;
+        if (launch_absmax(x_dev, (size_t)desc->N * desc->C * desc->H * desc->W, (float*)ws_dev, &a.xabs_nparts, st) != hipSuccess)
+            return INT8T_ERR_RUNTIME;
+    }
+    return launch_igemm_fused(a, st) == hipSuccess ? INT8T_OK : INT8T_ERR_RUNTIME;
+}
+
 int8t_status int8t_conv_bwd_data(const int8t_conv_desc* desc, const int8_t* dyq_dev, const float* sdy_dev,
                                  const int8_t* wq_dev, const float* sw_dev, float* dx_dev, int32_t* acc_dev,
                                  void* ws_dev, size_t ws_bytes, void* stream) {

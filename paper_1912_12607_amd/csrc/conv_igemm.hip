@@ -81,10 +81,18 @@ __device__ __forceinline__ void store_cell(T* __restrict__ dst, size_t o, int OW
 }
 
 // CLS (backward-data with a stride only): blockIdx.x = column tile * classes + class.
-template <int BM, int BN, bool DGRAD, bool CLS = false, bool CELL = false>
+// FUSEQ (forward, 1 x 1 filter, stride 1, no padding): the quantization of the activations (Eq.1) is fused
+// into the load path -- the quantization-convolution fused kernel of the paper's Suppl. "INT8
+// Convolution".  A thread then makes its 16-byte granule itself: 16 fp32 loads (16 consecutive
+// channels of its pixel; a wave reads 64 consecutive pixels of a channel plane per instruction),
+// Eq.1 on each, packed to codes.  The codes never make the round trip through HBM before the
+// convolution reads them; the first row tile still writes them out when the caller wants them for
+// the backward-weight pass.
+template <int BM, int BN, bool DGRAD, bool CLS = false, bool CELL = false, bool FUSEQ = false>
 __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmArgs a) {
     static_assert(DGRAD || !CLS, "residue classes exist in the backward-data pass only");
     static_assert(CLS || !CELL, "the cell form is a residue-class form");
+    static_assert(!FUSEQ || (!DGRAD && !CLS), "the fused quantizer serves the forward pass");
     constexpr int MI = BM / 64;   // 32-row MFMA tiles per wave
     constexpr int NJ = BN / 64;   // 32-column MFMA tiles per wave
     constexpr int NB = BN / 64;   // B-tile columns staged per thread
@@ -94,10 +102,20 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmArgs a) {
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave & 1, wn = wave >> 1;
-    const int lrow = tid >> 2, lg = tid & 3;
+    // loader: (tile row or column, granule of the stage).  FUSEQ: a wave takes one granule of 64
+    // consecutive pixels, so that its fp32 loads walk a channel plane
+    const int lrow = FUSEQ ? (tid & 63) : (tid >> 2), lg = FUSEQ ? (tid >> 6) : (tid & 3);
 
     const int OHWfull = a.OH * a.OW;
     const int Cg16 = a.Ca >> 4;
+    float qinv = 0.0f, qscale = 0.0f;
+    if (FUSEQ) {
+        __shared__ float lds4[4];
+        const float cval = a.xclip ? a.xclip[0] : reduce_absmax_partials(a.xabs_part, a.xabs_nparts, lds4);
+        qinv = inv_scale_of(cval);
+        qscale = scale_of(cval);
+        if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && tid == 0) a.sx_out[0] = qscale;
+    }
     DgradClass dc;
     int colblock = blockIdx.x;
     if (CLS) {
@@ -172,6 +190,26 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmArgs a) {
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
             rb[i] = make_uint4(0, 0, 0, 0);
+            if (FUSEQ) {
+                // column = pixel (n, oh*OW + ow) of the input itself; granule cg = channels 16 cg .. 16 cg + 15
+                if (qv && bvalid[i]) {
+                    const int col = colbase + i * 64 + lrow;
+                    const int n = col / OHW, pix = col - n * OHW;
+                    const float* __restrict__ px = a.xf + ((size_t)n * a.C + 16 * cg) * OHW + pix;
+                    float v[16];
+#pragma unroll
+                    for (int k = 0; k < 16; ++k) v[k] = (16 * cg + k < a.C) ? px[(size_t)k * OHW] : 0.0f;
+                    uint32_t d[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        d[j] = pack4(quantize_one<false>(v[4 * j], qinv, 0, 0, 0), quantize_one<false>(v[4 * j + 1], qinv, 0, 0, 0),
+                                     quantize_one<false>(v[4 * j + 2], qinv, 0, 0, 0), quantize_one<false>(v[4 * j + 3], qinv, 0, 0, 0));
+                    rb[i] = make_uint4(d[0], d[1], d[2], d[3]);
+                    if (a.xq_out && blockIdx.y == 0)
+                        *reinterpret_cast<uint4*>(a.xq_out + ((size_t)n * OHW + pix) * a.Ca + 16 * cg) = rb[i];
+                }
+                continue;
+            }
             int ih, iw;
             bool ok = qv && bvalid[i];
             if (DGRAD) {
@@ -254,7 +292,7 @@ __global__ __launch_bounds__(256, 2) void igemm_kernel(const IgemmArgs a) {
     // in partial[z][N][rows][OH*OW] for igemm_reduce_kernel instead ---------------------------
     const bool split = a.ksplit > 1;
     int32_t* __restrict__ const part = split ? a.partial + (size_t)blockIdx.z * a.N * a.rows * OHWfull : nullptr;
-    const float scale = __fmul_rn(a.sa[0], a.sb[0]);
+    const float scale = __fmul_rn(FUSEQ ? qscale : a.sa[0], a.sb[0]);
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
         const int col = colbase + wn * (BN / 2) + j * 32 + (lane & 31);
@@ -740,6 +778,25 @@ bool igemm_variant_ok(const IgemmArgs& a, int variant) {
         case VAR_TILE_SPLIT: return igemm_ksplit(a) > 1;
         default: return false;
     }
+}
+
+hipError_t launch_igemm_fused(const IgemmArgs& a_in, hipStream_t st) {
+    IgemmArgs a = a_in;
+    if (a.dgrad || a.R != 1 || a.S != 1 || a.stride_h != 1 || a.stride_w != 1 || a.pad_h || a.pad_w || !a.xf || !a.sx_out)
+        return hipErrorInvalidValue;
+    a.cls_h = a.cls_w = 1;
+    a.cell = 0;
+    a.ksplit = 1;
+    const unsigned ncols = (unsigned)(a.N * a.OH * a.OW);
+    KernelTimer kt(KID_IGEMM_FUSED, st);
+    if (a.rows <= 64) {
+        dim3 grid((ncols + 127) / 128, 1, 1);
+        launch_timed(kt, (igemm_kernel<64, 128, false, false, false, true>), grid, dim3(256), 0, st, a);
+    } else {
+        dim3 grid((ncols + 127) / 128, (unsigned)((a.rows + 127) / 128), 1);
+        launch_timed(kt, (igemm_kernel<128, 128, false, false, false, true>), grid, dim3(256), 0, st, a);
+    }
+    return hipGetLastError();
 }
 
 size_t igemm_s2d(IgemmArgs* a) {

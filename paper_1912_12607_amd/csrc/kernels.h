@@ -128,6 +128,13 @@ struct IgemmArgs {
     size_t partial_bytes;
     int ksplit;                  // filled by launch_igemm(): blocks per output tile along the reduction
     int variant;                 // ConvVariant: VAR_AUTO, or the kernel the caller selected for this layer
+    // Quantization fused into the forward pass of a 1 x 1, stride-1, unpadded layer (launch_igemm_fused):
+    const float* xf;             // fp32 activations N,C,H,W (act is not read)
+    const float* xclip;          // clip value of a, or nullptr: max|a| from xabs_part[0..xabs_nparts)
+    const float* xabs_part;
+    int xabs_nparts;
+    int8_t* xq_out;              // nullable: the codes of a (N,H,W,Ca), written by the first row tile
+    float* sx_out;               // the scale of a
 };
 // Kernel variants of the dense passes (values of INT8T_VARIANT_* in include/int8t.h).
 enum ConvVariant : int {
@@ -150,6 +157,8 @@ int igemm_auto_variant(const IgemmArgs& a);
 // rewritten input and filter codes (0: does not apply, the geometry is left alone).
 size_t igemm_s2d(IgemmArgs* a);
 hipError_t launch_igemm(const IgemmArgs& a, hipStream_t st);
+// forward pass that quantizes fp32 activations in its load path; 1 x 1 filter, stride 1, no padding
+hipError_t launch_igemm_fused(const IgemmArgs& a, hipStream_t st);
 // conv_band.hip: LDS-resident variant for small filter banks; false = shape not covered
 // (dry_run: only say whether the shape is covered, launch nothing)
 bool launch_band(const IgemmArgs& a, hipStream_t st, hipError_t* err, bool dry_run = false);

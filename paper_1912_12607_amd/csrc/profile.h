@@ -23,6 +23,7 @@ enum KernelId : int {
     KID_DSGC_SWEEP,
     KID_IGEMM,
     KID_IGEMM_DMA,
+    KID_IGEMM_FUSED,
     KID_IGEMM_REDUCE,
     KID_BAND,
     KID_BAND_REG,

@@ -51,13 +51,17 @@ def side_stream(device) -> "torch.cuda.Stream":
 
 class LayerStep:
     def __init__(self, L: Layer, n_cand: int = 32, keep_acc: bool = False, device: str = "cuda:0",
-                 requantize_deviation: bool = True, input_grad: bool = True):
+                 requantize_deviation: bool = True, input_grad: bool = True, fused_fwd: bool = False):
         """input_grad=False leaves the backward-data pass out (the first layer of a network: nothing
         consumes the gradient of the images).
         requantize_deviation: also let the quantizer of g_z report Eq.6 for the codes it wrote (into
         dev_final).  The clip search has already returned the same d_c (dev_search), which is what Eq.7
         consumes, so a training step can leave this off."""
         self.L, self.n_cand, self.dev = L, n_cand, torch.device(device)
+        # fused_fwd: quantize a inside the forward convolution (int8t_conv_fwd_fused; 1x1 stride-1 layers only)
+        self.fused_fwd = bool(fused_fwd)
+        if self.fused_fwd:
+            assert L.groups == 1 and (L.R, L.S) == (1, 1) and L.stride == (1, 1) and L.pad == (0, 0), "1x1 stride-1 layers"
         self.requantize_deviation = requantize_deviation
         self.input_grad = input_grad
         self.depthwise = L.groups != 1
@@ -121,6 +125,10 @@ class LayerStep:
                                                      B.ROUND_STOCHASTIC, 0)])
         self._k_xw = B.bind(lib.int8t_quantize_batch, 2, self._items_xw, p(self.ws_xw), nb(self.ws_xw))
         self._k_xwg = B.bind(lib.int8t_quantize_batch, 3, self._items_xwg, p(self.ws_xw), nb(self.ws_xw))
+        self._k_w = B.bind(lib.int8t_quantize, p(self.w), B._dims(L.w_shape), self.wgt_kind, None, B.ROUND_NEAREST_EVEN, 0,
+                           p(self.wq), p(self.sw), None, p(self.ws_w), nb(self.ws_w))
+        self._k_fwd_fused = B.bind(lib.int8t_conv_fwd_fused, C.byref(self.desc), p(self.x), None, p(self.wq), p(self.sw), p(self.y),
+                                   p(self.y_acc), p(self.xq), p(self.sx), p(self.ws_x), nb(self.ws_x))
         self._k_prepare = B.bind(lib.int8t_dsgc_prepare, p(self.dy), n_y, p(self.ws_dy), nb(self.ws_dy))
         d = C.byref(self.desc)
         self._k_fwd = B.bind(lib.int8t_conv_fwd, d, p(self.xq), p(self.sx), p(self.wq), p(self.sw), p(self.y), p(self.y_acc),
@@ -199,16 +207,24 @@ class LayerStep:
             overlap = search and (self._tuned_overlap if self._tuned_overlap is not None else two_stream_default(self.L))
         if not overlap:
             sp = B.stream_pointer(stream)
-            if not search and not self.requantize_deviation:
+            if not search and not self.requantize_deviation and not self.fused_fwd:
                 # the clip value is known: a, W and g_z in one batched call (one launch fewer)
                 self._items_xwg[2].seed = seed
                 self._k_xwg(sp)
+            elif self.fused_fwd:
+                self._k_w(sp)
+                if search:
+                    self._k_clip(seed, sp)
+                self._k_qdy(seed, sp)
             else:
                 self._k_xw(sp)
                 if search:
                     self._k_clip(seed, sp)
                 self._k_qdy(seed, sp)
-            self._k_fwd(sp)
+            if self.fused_fwd:
+                self._k_fwd_fused(sp)
+            else:
+                self._k_fwd(sp)
             if self.input_grad:
                 self._k_bwd_data(sp)
             self._k_bwd_weight(sp)
@@ -230,8 +246,12 @@ class LayerStep:
             self._k_prepare(mp)
         self._ev_main.record(main)
         side.wait_event(self._ev_main)
-        self._k_xw(sp)
-        self._k_fwd(sp)
+        if self.fused_fwd:
+            self._k_w(sp)
+            self._k_fwd_fused(sp)
+        else:
+            self._k_xw(sp)
+            self._k_fwd(sp)
         self._ev_side.record(side)
         if search:
             self._k_search(seed, mp)

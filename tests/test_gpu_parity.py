@@ -663,6 +663,62 @@ def test_tuned_schedule_writes_the_same_tensors():
         assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("shape", [(2, 24, 9, 9, 144), (3, 144, 7, 7, 24), (2, 70, 5, 6, 130), (33, 200, 1, 1, 70), (2, 16, 16, 16, 300)])
+def test_fused_quantize_conv_equals_separate_calls_and_oracle(shape):
+    """int8t_conv_fwd_fused (Eq.1 inside the forward pass of a 1x1 stride-1 layer) writes the codes, the
+    scale, the accumulators and the results of int8t_quantize + int8t_conv_fwd, which are the oracle's."""
+    N, C, H, W, K = shape
+    r = np.random.RandomState(N * 100 + C)
+    x = (r.standard_normal((N, C, H, W)) * 1.7).astype(np.float32)
+    x[0, 0, 0, 0] = np.nan if C > 20 else x[0, 0, 0, 0]
+    w = r.randint(-127, 128, size=(K, C, 1, 1)).astype(np.int8)
+    gd = B.make_desc(N, C, H, W, K, 1, 1)
+    od = oracle.make_desc(N, C, H, W, K, 1, 1)
+    wq, sw = dev(pack_wgt(w)), dev(np.array([3.3e-3], np.float32))
+    xd = dev(x)
+    ws = torch.empty(4096, dtype=torch.uint8, device=DEV)
+    for clip in (None, 2.5):
+        cd = None if clip is None else dev(np.array([clip], np.float32))
+        for want_codes in (True, False):
+            y = torch.full((N, K, H, W), float("nan"), dtype=torch.float32, device=DEV)
+            acc = torch.full((N, K, H, W), -12345, dtype=torch.int32, device=DEV)
+            xq = torch.full((B.int8t_code_bytes(x.shape, B.ACT),), 77, dtype=torch.int8, device=DEV) if want_codes else None
+            sx = torch.zeros(1, dtype=torch.float32, device=DEV)
+            B.int8t_conv_fwd_fused(gd, xd, cd, wq, sw, y, acc, xq, sx, ws)
+            torch.cuda.synchronize()
+            qo, so = oracle.quantize(x, c=clip)
+            assert sx.item() == so
+            if want_codes:
+                q2, s2, _ = gpu_quantize(x, B.ACT, clip)
+                assert np.array_equal(xq.cpu().numpy(), q2) and s2 == so            # incl. zero channel padding
+                assert np.array_equal(unpack_act(xq.cpu().numpy(), x.shape, False), qo)
+            want32, ov = oracle.wrap32(oracle.conv_fwd(od, qo, w))
+            assert ov == 0 and np.array_equal(acc.cpu().numpy(), want32)
+            ref = oracle.dequant(want32, so, np.float32(3.3e-3))
+            assert np.all(np.abs(y.cpu().numpy() - ref) <= REL_TOL * np.abs(ref))
+    with pytest.raises(B.Int8tError) as e:
+        B.int8t_conv_fwd_fused(B.make_desc(N, C, H + 2, W + 2, K, 3, 3), xd, None, wq, sw, y, None, None, sx, ws)
+    assert e.value.status == 2
+
+
+def test_step_with_fused_forward_equals_plain_step():
+    L, x, w, dy = inputs.make_layer_inputs(3, 2)
+    outs = []
+    for fused in (False, True):
+        for overlap in (False, True):
+            st = LayerStep(L, n_cand=32, keep_acc=True, fused_fwd=fused)
+            st.upload(x, w, dy, inputs.default_ratios(32))
+            st.wq.zero_()                  # (the alignment gap between the two weight layouts is never written)
+            for seed in (5, 6):
+                st.run(seed=seed, overlap=overlap)
+            torch.cuda.synchronize()
+            outs.append([t.clone() for t in (st.xq, st.wq, st.dyq, st.sx, st.sw, st.sdy, st.y, st.dx, st.dw, st.y_acc, st.dw_acc)])
+    names = ("xq", "wq", "dyq", "sx", "sw", "sdy", "y", "dx", "dw", "y_acc", "dw_acc")
+    for k, other in enumerate(outs[1:]):
+        for name, a, b in zip(names, outs[0], other):
+            assert torch.equal(a, b), (k + 1, name, int((a != b).sum()))
+
+
 def test_every_kernel_variant_is_exact():
     """Per-layer kernel choice: every variant int8t_conv_variant_ok() admits for a pass of a layer --
     i.e. everything a tuner may select -- writes the oracle's accumulators and results, on small layers
