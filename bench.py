@@ -139,6 +139,8 @@ def main():
     ap.add_argument("--no-overlap", action="store_true",
                     help="issue every call on one stream (default: a, W quantization and the forward convolution "
                          "run on a second stream beside the clip search where that pays)")
+    ap.add_argument("--no-tune", action="store_true", help="keep the library's own kernel choice (default: each layer's kernels are "
+                                                           "chosen by timing the admissible variants before its steps are timed)")
     ap.add_argument("--no-layers", action="store_true", help="leave the per-layer table of all benchmark layers out")
     ap.add_argument("--cpu-images", type=int, default=0, help="images of the batch the oracle is timed on (0: by layer size)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
@@ -175,8 +177,9 @@ def main():
     def profile_calls(calls, reps):
         """{kernel: (launches per call sequence, us per launch)} of `calls` run `reps` times on one
         stream with every launch carrying HIP events."""
-        for c in calls:
-            c()
+        for _ in range(20):
+            for c in calls:
+                c()
         torch.cuda.synchronize()
         B.int8t_profile_start(None)
         for _ in range(reps):
@@ -192,9 +195,12 @@ def main():
         {kernel: [algorithmic bytes, ops, kind, launches]} summed over the passes each kernel served."""
         alg = pass_algorithmic(L, n_cand)
         dw = L.groups != 1
-        calls = [("quantize_xw", lambda: st.quantize_xw()), ("dsgc", lambda: st.dsgc(0)),
-                 ("quantize_gz", lambda: st.quantize_dy(0)), ("fwd", lambda: st.fwd()),
-                 ("bwd_data", lambda: st.bwd_data()), ("bwd_weight", lambda: st.bwd_weight())]
+        sp = B.stream_pointer(None)
+        # (the calls with their arguments marshalled once: launched back to back they keep the GPU busy, which a
+        # loop that rebuilds its arguments in Python does not -- an idling GPU drops its clocks)
+        calls = [("quantize_xw", lambda: st._k_xw(sp)), ("dsgc", lambda: st._k_clip(0, sp)),
+                 ("quantize_gz", lambda: st._k_qdy(0, sp)), ("fwd", lambda: st._k_fwd(sp)),
+                 ("bwd_data", lambda: st._k_bwd_data(sp)), ("bwd_weight", lambda: st._k_bwd_weight(sp))]
         rows, per_kernel = [], {}
 
         def add(name, kernels, key):
@@ -212,7 +218,7 @@ def main():
             e[3] += kernels[main_k][0]
 
         for name, fn in calls:
-            pk = profile_calls([fn], 5)
+            pk = profile_calls([fn], 20)
             if name == "quantize_xw":
                 add("absmax_xw", {k: v for k, v in pk.items() if k.startswith("absmax")}, "absmax_xw")
                 add("quantize_xw", {k: v for k, v in pk.items() if not k.startswith("absmax")}, "quantize_xw")
@@ -223,13 +229,25 @@ def main():
                 add(name, pk, name)
         return rows, per_kernel
 
+    kernel_choice = {}
+
     def make_sets(cfg, li, count):
+        """`count` sets of buffers of the layer holding the same values; the layer's kernels are chosen by
+        measurement first (untimed; the per-layer choice "before training" of the paper's Suppl.)."""
         L, x, w, dy = inputs.make_layer_inputs(cfg, li)
         sets = []
         for _ in range(count):
             st = LayerStep(L, n_cand=n_cand, keep_acc=False, requantize_deviation=False)
             st.upload(x, w, dy, ratios)
             sets.append(st)
+        if not args.no_tune:
+            for i in range(30):
+                sets[0].run(seed=i, overlap=False)
+            torch.cuda.synchronize()
+            ch = sets[0].tune_kernels()
+            kernel_choice[f"{cfg}.{li}"] = {k: v[0] for k, v in ch.items()}
+            for st in sets[1:]:
+                st.refresh_scratch()
         torch.cuda.synchronize()
         return L, (x, w, dy), sets
 
@@ -317,6 +335,7 @@ def main():
                    "buffer_sets": rotate, "single_set_ms_per_step": single_ms,
                    "warmup_requested": args.warmup,
                    "pct_int8_mfma_peak": 100.0 * tops / INT8_MFMA_PEAK_TOPS,
+                   "kernel_choice": kernel_choice,
                    "us_per_kernel": {k: {"launches_per_step": v[0], "us_per_launch": round(v[1], 2)}
                                      for k, v in sorted(per_kernel.items(), key=lambda kv: -kv[1][0] * kv[1][1])},
                    "sum_kernels_us": sum(v[0] * v[1] for v in per_kernel.values()),
@@ -324,7 +343,7 @@ def main():
         "roofline": roof,
     }
     if not args.no_cpu_baseline:
-        n_img = args.cpu_images or max(1, min(L.N, int(L.N * 4.0e10 / (3 * L.macs + 1))))
+        n_img = args.cpu_images or max(1, min(L.N, int(L.N * 1.5e11 / (3 * L.macs + 1))))
         out["cpu_baseline"] = cpu_baseline(L, *host, ratios, n_img)
     del sets
     torch.cuda.empty_cache()
@@ -348,6 +367,17 @@ def main():
                 del sx
                 torch.cuda.empty_cache()
         out["config"]["layers"] = rows
+
+    # what the matrix cores sustain on this GPU: published peak needs all-zero operands; random int8 operands
+    # pull the clock down (power limit), and that is the ceiling of a convolution on real codes
+    ceil = {}
+    for name, rnd, lds in (("zero_operands_from_registers", 0, 0), ("random_operands_from_registers", 1, 0),
+                           ("random_operands_from_lds", 1, 1)):
+        t, ghz = B.int8t_profile_mfma_ceiling(rnd, lds, 20000)
+        ceil[name] = {"TOPS": round(t, 1), "shader_clock_GHz": round(ghz, 3)}
+    out["config"]["int8_mfma_ceiling_measured"] = ceil
+    if roof["bound"] == "mfma":
+        roof["frac_of_measured_ceiling_random_operands_from_lds"] = roof["achieved"] / ceil["random_operands_from_lds"]["TOPS"]
 
     if args.copy_calibration > 0:
         src = torch.ones(args.copy_calibration * (1 << 20) // 4, dtype=torch.float32, device="cuda")

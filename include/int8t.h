@@ -315,7 +315,7 @@ int8t_status int8t_conv_bwd_weight(const int8t_conv_desc *desc,
  * the layer's own buffers and selects the fastest.  The selection is kept in a process-wide table
  * keyed by (pass, descriptor) until it is changed; INT8T_VARIANT_AUTO (the default for every layer)
  * restores the library's own rules.  Thread-safe; not device-specific.
- *   forward / backward-data:  BAND, TILE, TILE_SPLIT, WIDE128, WIDE256, WIDE256_DEEP
+ *   forward / backward-data:  BAND, TILE, TILE_SPLIT, WIDE128, WIDE256
  *   backward-weight:          WGRAD_FEWER, WGRAD_MORE (half / twice the reduction shares of the
  *                             cost model's choice; query int8t_workspace_bytes() again afterwards)
  * Depthwise layers have one kernel per pass.  A variant that needs scratch (TILE_SPLIT) and is not
@@ -328,12 +328,11 @@ typedef enum {
     INT8T_VARIANT_TILE_SPLIT = 3,    /* ... with the reduction split over several blocks per tile */
     INT8T_VARIANT_WIDE128 = 4,       /* 128 x 256 tiles, operands loaded straight into a 3-stage LDS ring */
     INT8T_VARIANT_WIDE256 = 5,       /* 256 x 256 tiles, 2 stages of 128 reduction bytes */
-    INT8T_VARIANT_WIDE256_DEEP = 6,  /* 256 x 256 tiles, 4 stages of 64 reduction bytes */
-    INT8T_VARIANT_WGRAD_FEWER = 7,
-    INT8T_VARIANT_WGRAD_MORE = 8,
+    INT8T_VARIANT_WGRAD_FEWER = 6,
+    INT8T_VARIANT_WGRAD_MORE = 7,
     INT8T_VARIANT_MAX_ENUM = 0x7fffffff
 } int8t_variant;
-#define INT8T_VARIANT_COUNT 9
+#define INT8T_VARIANT_COUNT 8
 /* 1 when `variant` can run pass `op` (INT8T_OP_CONV_*) of the layer, else 0 (also on a bad descriptor). */
 int int8t_conv_variant_ok(int8t_op op, const int8t_conv_desc *desc, int8t_variant variant);
 /* INT8T_ERR_ARG when the variant cannot run that pass of that layer; then nothing changes. */
@@ -369,6 +368,22 @@ typedef struct int8t_kernel_time {
 int8t_status int8t_profile_start(const char *kernel);
 int8t_status int8t_profile_start_sampled(const char *kernel, int every);
 int8t_status int8t_profile_stop(int8t_kernel_time *out, int capacity, int *count);
+
+/*
+ * Measurement aid: what the int8 matrix cores of the current GPU sustain.  Runs, on every compute
+ * unit, eight waves of independent 32x32x32 int8 MFMAs (the wave tile of the wide convolution kernels)
+ * for `iters` iterations of 16 MFMAs per wave, with operand bytes all zero (random_operands == 0) or
+ * pseudo-random, held in registers (lds_reads == 0) or re-read from LDS before every eight MFMAs as
+ * an implicit GEMM does.  Synchronises with the host.
+ *   tops_out   host, out: int8 operations per second / 1e12 over the kernel's duration
+ *   ghz_out    host, out: the shader clock the loop ran at (shader-clock counter against the constant
+ *              100 MHz counter, both read inside the kernel)
+ *   ws_dev     64 bytes of device scratch, 8-byte aligned
+ * The published peak (5.0 POP/s at 2.4 GHz) is what zero operands reach; with random operands the
+ * power limit lowers the clock, and that figure is the ceiling a convolution on real codes has.
+ */
+int8t_status int8t_profile_mfma_ceiling(int random_operands, int lds_reads, int iters,
+                                        double *tops_out, double *ghz_out, void *ws_dev, void *stream);
 
 /* Eq.7 on the host: max(exp(-alpha * d_c), beta).  The paper uses alpha = 20, beta = 0.1. */
 double int8t_dclr_scale(double d_c, double alpha, double beta);

@@ -18,8 +18,8 @@ ROUND_NEAREST_EVEN, ROUND_STOCHASTIC = 0, 1
 ACT, WGT, ACT_PLANAR, WGT_PLANAR = 0, 1, 2, 3
 OP_QUANTIZE, OP_DSGC, OP_CONV_FWD, OP_CONV_BWD_DATA, OP_CONV_BWD_WEIGHT = range(5)
 (VARIANT_AUTO, VARIANT_BAND, VARIANT_TILE, VARIANT_TILE_SPLIT, VARIANT_WIDE128, VARIANT_WIDE256,
- VARIANT_WIDE256_DEEP, VARIANT_WGRAD_FEWER, VARIANT_WGRAD_MORE) = range(9)
-VARIANT_NAMES = ["auto", "band", "tile", "tile_split", "wide128", "wide256", "wide256_deep", "wgrad_fewer", "wgrad_more"]
+ VARIANT_WGRAD_FEWER, VARIANT_WGRAD_MORE) = range(8)
+VARIANT_NAMES = ["auto", "band", "tile", "tile_split", "wide128", "wide256", "wgrad_fewer", "wgrad_more"]
 MAX_CANDIDATES = 64
 MAX_BATCH = 8
 
@@ -28,7 +28,7 @@ EXPORTS = ["int8t_status_string", "int8t_code_bytes", "int8t_unpack_codes", "int
            "int8t_quantize_batch", "int8t_dsgc_clip", "int8t_dsgc_clip_static", "int8t_dsgc_prepare", "int8t_dsgc_search", "int8t_conv_fwd", "int8t_conv_fwd_fused",
            "int8t_conv_bwd_data", "int8t_conv_bwd_weight", "int8t_dclr_scale",
            "int8t_conv_variant_ok", "int8t_conv_select_variant", "int8t_conv_selected_variant",
-           "int8t_profile_start", "int8t_profile_start_sampled", "int8t_profile_stop"]
+           "int8t_profile_start", "int8t_profile_start_sampled", "int8t_profile_stop", "int8t_profile_mfma_ceiling"]
 
 
 class KernelTime(C.Structure):
@@ -99,6 +99,8 @@ def _load():
     L.int8t_profile_start.argtypes = [C.c_char_p]
     L.int8t_profile_start_sampled.restype = i32
     L.int8t_profile_start_sampled.argtypes = [C.c_char_p, C.c_int]
+    L.int8t_profile_mfma_ceiling.restype = i32
+    L.int8t_profile_mfma_ceiling.argtypes = [i32, i32, i32, C.POINTER(C.c_double), C.POINTER(C.c_double), vp, vp]
     L.int8t_profile_stop.restype = i32
     L.int8t_profile_stop.argtypes = [C.POINTER(KernelTime), i32, C.POINTER(i32)]
     return L
@@ -285,3 +287,12 @@ def int8t_profile_stop() -> dict:
     n = C.c_int(0)
     _check(lib.int8t_profile_stop(buf, 32, C.byref(n)))
     return {buf[i].name.decode(): (int(buf[i].launches), float(buf[i].total_ms)) for i in range(min(n.value, 32))}
+
+
+def int8t_profile_mfma_ceiling(random_operands: bool, lds_reads: bool, iters: int = 20000, stream=None):
+    """(int8 TOP/s, shader clock in GHz) of the MFMA loop described in include/int8t.h."""
+    ws = torch.zeros(8, dtype=torch.int64, device="cuda")
+    tops, ghz = C.c_double(0), C.c_double(0)
+    _check(lib.int8t_profile_mfma_ceiling(int(bool(random_operands)), int(bool(lds_reads)), int(iters), C.byref(tops), C.byref(ghz),
+                                          _ptr(ws), _stream(stream)))
+    return tops.value, ghz.value

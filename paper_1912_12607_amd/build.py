@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(CSRC, "libint8t.so")
 SOURCES = ["api.hip", "quantize.hip", "dsgc.hip", "conv_igemm.hip", "conv_band.hip", "conv_wgrad.hip", "s2d.hip", "conv_dw.hip", "profile.hip"]
-HEADERS = ["device_common.h", "kernels.h", "profile.h", os.path.join("..", "..", "include", "int8t.h")]
+HEADERS = ["device_common.h", "kernels.h", "profile.h", "lds_dma.h", os.path.join("..", "..", "include", "int8t.h")]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-fno-fast-math", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -19,6 +19,7 @@
 // operand reads per MFMA) serves the layers whose convolutions are bound by the matrix cores.
 #include "device_common.h"
 #include "kernels.h"
+#include "lds_dma.h"
 
 namespace int8t {
 
@@ -380,42 +381,7 @@ __global__ __launch_bounds__(256) void igemm_reduce_kernel(const IgemmArgs a, si
 // buffer descriptor: the hardware then writes zeros.
 //   <WM=2, KG=4, NSTAGE=3>: 128 x 256, 72 KB of LDS, two blocks per compute unit
 //   <WM=4, KG=8, NSTAGE=2>: 256 x 256, 128 KB of LDS, one block of eight waves per compute unit
-//   <WM=4, KG=4, NSTAGE=4>: 256 x 256, 128 KB of LDS, loads three (half as long) stages ahead
 // ---------------------------------------------------------------------------------------------
-constexpr uint32_t IGD_OOB = 0x80000000u;
-constexpr int IGD_BN = 256;
-
-// Buffer descriptor (base, no stride, byte count, raw 32-bit format) as four scalar words.
-__device__ __forceinline__ v4i igd_rsrc(const void* p, uint32_t bytes) {
-    const uint64_t addr = (uint64_t)p;
-    return v4i{(int)(uint32_t)addr, (int)((uint32_t)(addr >> 32) & 0xffffu), (int)bytes, 0x00020000};
-}
-// One wave-wide 16-byte-per-lane buffer load into LDS: lane l's bytes land at lds_base + 16*l, an
-// offset beyond the descriptor writes zeros.  Written as an instruction block so that the wait for
-// it can be placed by hand (see the vmcnt waits in the kernel): the compiler would otherwise wait
-// for ALL outstanding loads in front of every LDS read.  (m0 carries the LDS base; the compiler keeps
-// no value of its own in it across statements.)
-__device__ __forceinline__ void igd_load_lds(const v4i& rsrc, uint32_t lds_base_uniform, uint32_t voff) {
-    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                 :: "s"(lds_base_uniform), "v"(voff), "s"(rsrc) : "memory");
-}
-// slot of (row, granule) in a [rows][KG] tile; the xor makes the MFMA operand reads (16 consecutive
-// rows of one granule per LDS pass) hit 16 different slots mod 16, see lds_slot(): with 8 granules per
-// row, slot mod 16 = 8 * (row & 1) + position, so rows of equal parity need different positions
-template <int KG>
-__device__ __forceinline__ int igd_slot(int row, int g) {
-    return KG == 4 ? row * 4 + (g ^ ((row >> 2) & 3)) : row * 8 + (g ^ ((row >> 1) & 7));
-}
-template <int N>
-__device__ __forceinline__ void igd_wait_vmcnt() {
-    static_assert(N == 0 || N == 4 || N == 6 || N == 8 || N == 12, "outstanding loads allowed while waiting");
-    if (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    else if (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-    else if (N == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-    else if (N == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
-}
-
 template <bool DGRAD, int WM, int KG, int NSTAGE, bool CLS = false, bool CELL = false>
 __global__ __launch_bounds__(128 * WM, WM == 2 ? 2 : 1) void igemm_dma_kernel(const IgemmArgs a) {
     static_assert(DGRAD || !CLS, "residue classes exist in the backward-data pass only");
@@ -773,7 +739,7 @@ int igemm_auto_variant(const IgemmArgs& a) {
 bool igemm_variant_ok(const IgemmArgs& a, int variant) {
     hipError_t e = hipSuccess;
     switch (variant) {
-        case VAR_AUTO: case VAR_TILE: case VAR_WIDE128: case VAR_WIDE256: case VAR_WIDE256_DEEP: return true;
+        case VAR_AUTO: case VAR_TILE: case VAR_WIDE128: case VAR_WIDE256: return true;
         case VAR_BAND: return launch_band(a, nullptr, &e, true);
         case VAR_TILE_SPLIT: return igemm_ksplit(a) > 1;
         default: return false;
@@ -861,10 +827,9 @@ hipError_t launch_igemm(const IgemmArgs& a_in, hipStream_t st) {
         else launch_timed(kt, igemm_reduce_kernel<false>, rgrid, dim3(256), 0, st, a, total);
         return hipGetLastError();
     }
-    if (variant == VAR_WIDE128 || variant == VAR_WIDE256 || variant == VAR_WIDE256_DEEP) {
+    if (variant == VAR_WIDE128 || variant == VAR_WIDE256) {
         KernelTimer kt(KID_IGEMM_DMA, st);
         if (variant == VAR_WIDE256) return launch_igemm_dma_any<4, 8, 2>(a, g, st, kt);
-        if (variant == VAR_WIDE256_DEEP) return launch_igemm_dma_any<4, 4, 4>(a, g, st, kt);
         return launch_igemm_dma_any<2, 4, 3>(a, g, st, kt);
     }
     KernelTimer kt(KID_IGEMM, st);

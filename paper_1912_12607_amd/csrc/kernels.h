@@ -144,9 +144,8 @@ enum ConvVariant : int {
     VAR_TILE_SPLIT = 3,    // ... reduction split over several blocks per tile
     VAR_WIDE128 = 4,       // 128 x 256 tiles, operands straight into an LDS ring of 3 stages
     VAR_WIDE256 = 5,       // 256 x 256 tiles, ring of 2 stages of 128 reduction bytes
-    VAR_WIDE256_DEEP = 6,  // 256 x 256 tiles, ring of 4 stages of 64 reduction bytes
-    VAR_WGRAD_FEWER = 7,   // backward-weight: half the reduction shares of the cost model's choice
-    VAR_WGRAD_MORE = 8,    // backward-weight: twice as many
+    VAR_WGRAD_FEWER = 6,   // backward-weight: half the reduction shares of the cost model's choice
+    VAR_WGRAD_MORE = 7,    // backward-weight: twice as many
     VAR_COUNT
 };
 int igemm_ksplit(const IgemmArgs& a);   // largest split a launch of this layer may use (1 = none): sizes the scratch

@@ -284,6 +284,14 @@ class LayerStep:
         self._tuned_overlap = best[1] < best[0]
         return self._tuned_overlap
 
+    def refresh_scratch(self):
+        """Re-size the backward-weight scratch after a kernel selection made elsewhere for this shape (the
+        selection is per shape and process-wide; the scratch of that pass depends on it)."""
+        need = B.int8t_workspace_bytes(B.OP_CONV_BWD_WEIGHT, self.desc)
+        if need > self.ws.numel():
+            self.ws = torch.empty(need, dtype=torch.uint8, device=self.dev)
+            self._bind_calls()
+
     def tune_kernels(self, reps: int = 30, verbose: bool = False) -> dict:
         """The per-layer choice of the convolution kernels "before training" (Suppl. "INT8 Convolution",
         last paragraph): for each of the three passes, times every kernel variant the library admits for

@@ -728,7 +728,12 @@ def test_every_kernel_variant_is_exact():
               (2, 70, 9, 11, 40, 1, 7, (1, 1), (0, 3), 1), (2, 256, 9, 9, 96, 3, 3, (2, 2), (0, 0), 1),
               (2, 24, 9, 9, 144, 1, 1, (1, 1), (0, 0), 1), (1, 40, 33, 6, 130, 4, 3, (3, 1), (0, 1), 1),
               (2, 64, 8, 8, 128, 1, 1, (2, 2), (0, 0), 1), (40, 520, 1, 1, 200, 1, 1, (1, 1), (0, 0), 1),
-              (2, 3, 12, 10, 8, 7, 7, (2, 2), (3, 3), 1), (17, 130, 7, 37, 72, 5, 3, (1, 2), (2, 1), 1)]
+              (2, 3, 12, 10, 8, 7, 7, (2, 2), (3, 3), 1), (17, 130, 7, 37, 72, 5, 3, (1, 2), (2, 1), 1),
+              # stride 1, several taps; column tiles that span image borders
+              (3, 64, 14, 14, 128, 3, 3, (1, 1), (1, 1), 1), (2, 128, 17, 17, 192, 1, 7, (1, 1), (0, 3), 1),
+              (2, 64, 17, 17, 64, 7, 1, (1, 1), (3, 0), 1), (5, 64, 9, 11, 64, 3, 3, (1, 1), (0, 0), 1),
+              (2, 64, 8, 8, 64, 2, 2, (1, 1), (1, 1), 1), (3, 192, 6, 7, 64, 3, 5, (1, 1), (1, 0), 1),
+              (40, 64, 5, 5, 64, 3, 3, (1, 1), (1, 1), 1)]        # column tiles that span many small images
     one = dev(np.array([1.0], np.float32))
     seen = set()
     for shape in shapes:
@@ -766,7 +771,7 @@ def test_every_kernel_variant_is_exact():
             finally:
                 B.int8t_conv_select_variant(op, gd, B.VARIANT_AUTO)
     # every variant ran at least once in each pass it exists for
-    for v in (B.VARIANT_BAND, B.VARIANT_TILE, B.VARIANT_TILE_SPLIT, B.VARIANT_WIDE128, B.VARIANT_WIDE256, B.VARIANT_WIDE256_DEEP):
+    for v in (B.VARIANT_BAND, B.VARIANT_TILE, B.VARIANT_TILE_SPLIT, B.VARIANT_WIDE128, B.VARIANT_WIDE256):
         assert ("fwd", v) in seen and ("bwd_data", v) in seen, B.VARIANT_NAMES[v]
     assert ("bwd_weight", B.VARIANT_WGRAD_FEWER) in seen and ("bwd_weight", B.VARIANT_WGRAD_MORE) in seen
 
