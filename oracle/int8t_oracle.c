@@ -52,22 +52,32 @@ float orc_absmax(const float *x, size_t n)
 /* be reproduced; it is replaced by a stateless function of            */
 /* (seed, logical element index) returning 24 uniform bits.            */
 /* Reading: a 32-bit avalanche finaliser (multiply / xor-shift, the    */
-/* published murmur3 finaliser constants) applied to the index xored   */
-/* with the low seed word plus the high seed word times an odd         */
-/* constant.  For a fixed seed this is a bijection of the 32-bit       */
-/* index, hence exactly equidistributed over a full period.            */
+/* published murmur3 finaliser constants) applied to (index ^ kx) + ka, */
+/* where the two 32-bit keys come from the 64-bit seed through the     */
+/* same finaliser:  kx = mix(low ^ mix(high + 0x9E3779B9)),            */
+/* ka = mix(kx + 0x9E3779B9).  For a fixed seed this is a bijection of */
+/* the 32-bit index, hence exactly equidistributed over a full period; */
+/* hashing the seed first keeps the tables of related seeds (1, 2, 3,  */
+/* ... as a training loop hands them out) from being xor-shifted       */
+/* copies of each other.                                               */
 /* ------------------------------------------------------------------ */
-uint32_t orc_rng24(uint64_t seed, uint64_t index)
+static uint32_t orc_mix32(uint32_t x)
 {
-    uint32_t k0 = (uint32_t)(seed & 0xFFFFFFFFu);
-    uint32_t k1 = (uint32_t)(seed >> 32);
-    uint32_t x = ((uint32_t)index ^ k0) + k1 * 0x9E3779B9u;
     x ^= x >> 16;
     x *= 0x85EBCA6Bu;
     x ^= x >> 13;
     x *= 0xC2B2AE35u;
     x ^= x >> 16;
-    return x >> 8;
+    return x;
+}
+
+uint32_t orc_rng24(uint64_t seed, uint64_t index)
+{
+    uint32_t lo = (uint32_t)(seed & 0xFFFFFFFFu);
+    uint32_t hi = (uint32_t)(seed >> 32);
+    uint32_t kx = orc_mix32(lo ^ orc_mix32(hi + 0x9E3779B9u));
+    uint32_t ka = orc_mix32(kx + 0x9E3779B9u);
+    return orc_mix32(((uint32_t)index ^ kx) + ka) >> 8;
 }
 
 /* ------------------------------------------------------------------ */

@@ -389,8 +389,8 @@ int8t_status int8t_quantize_batch(int count, const int8t_quantize_item* items, v
         const int8t_kind pk = pass_kind(it.dims, it.kind);
         q.kind = pk == INT8T_ACT ? 0 : pk == INT8T_WGT ? 1 : 2;
         q.stoch = it.mode == INT8T_ROUND_STOCHASTIC;
-        q.seed_lo = (uint32_t)it.seed;
-        q.seed_hi = seed_hi_term(it.seed);
+        q.seed_lo = seed_key_x(it.seed);
+        q.seed_hi = seed_key_a(it.seed);
         quant_grid(q.kind, it.dims, &q.gx, &q.gy, &q.gz);
         q.block0 = (int)qblocks;
         qblocks += (long long)q.gx * q.gy * q.gz;

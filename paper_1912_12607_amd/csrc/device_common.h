@@ -50,21 +50,28 @@ __device__ __forceinline__ float reduce_absmax_partials(const float* __restrict_
 // Uniform draw for the stochastic rounding of Eq.3: 24 bits, a stateless function of
 // (seed, logical element index).  The paper's in-kernel generator (Suppl. "Stochastic
 // Rounding", Eq.8) is keyed by thread index; keying by element index instead makes the
-// codes independent of launch geometry.  One avalanche finaliser (multiply / xor-shift)
-// over the index xored with the low seed word plus the high seed word times an odd constant.
+// codes independent of launch geometry.  The 64-bit seed is first hashed into two 32-bit
+// keys (on the host, once per call); the draw is one avalanche finaliser (multiply /
+// xor-shift) over (index ^ key_x) + key_a.  Hashing the seed first matters: with the raw
+// seed words as keys, two seeds that differ by d in their low word gave the same table at
+// indices xor-ed with d, so layers and iterations seeded 1, 2, 3, ... shared their noise.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ uint32_t rng24(uint32_t seed_lo, uint32_t seed_hi_mul, uint32_t index) {
-    uint32_t x = (index ^ seed_lo) + seed_hi_mul;
+__host__ __device__ __forceinline__ uint32_t rng_mix32(uint32_t x) {
     x ^= x >> 16;
     x *= 0x85EBCA6Bu;
     x ^= x >> 13;
     x *= 0xC2B2AE35u;
     x ^= x >> 16;
-    return x >> 8;
+    return x;
 }
-__host__ __device__ __forceinline__ uint32_t seed_hi_term(uint64_t seed) {
-    return (uint32_t)(seed >> 32) * 0x9E3779B9u;
+__device__ __forceinline__ uint32_t rng24(uint32_t key_x, uint32_t key_a, uint32_t index) {
+    return rng_mix32((index ^ key_x) + key_a) >> 8;
 }
+// the two keys of a seed: key_x = mix(low word ^ mix(high word + golden ratio)), key_a = mix(key_x + golden ratio)
+__host__ __device__ __forceinline__ uint32_t seed_key_x(uint64_t seed) {
+    return rng_mix32((uint32_t)seed ^ rng_mix32((uint32_t)(seed >> 32) + 0x9E3779B9u));
+}
+__host__ __device__ __forceinline__ uint32_t seed_key_a(uint64_t seed) { return rng_mix32(seed_key_x(seed) + 0x9E3779B9u); }
 
 // 127 / c as one correctly rounded fp32 division; 0 for an all-zero tensor.
 __device__ __forceinline__ float inv_scale_of(float c) { return (c > 0.0f) ? __fdiv_rn(127.0f, c) : 0.0f; }

@@ -369,7 +369,7 @@ hipError_t launch_dsgc(const float* g, size_t n, const float* ratios, int n_cand
     int blocks = dsgc_blocks(n);
     const int cap = (DSGC_MAX_BLOCKS + nchunks - 1) / nchunks;
     if (blocks > cap) blocks = cap;
-    const uint32_t slo = (uint32_t)seed, shi = seed_hi_term(seed);
+    const uint32_t slo = seed_key_x(seed), shi = seed_key_a(seed);
     dim3 grid(blocks, nchunks);
     KernelTimer kt(KID_DSGC_SWEEP, st);
     if (stochastic)

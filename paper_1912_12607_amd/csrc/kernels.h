@@ -75,7 +75,7 @@ struct QuantBatchItem {
     int kind;                    // 0 activations, 1 weights, 2 planar
     int block0, gx, gy, gz;      // its block range and virtual grid inside the launch
     int stoch;                   // Eq.3 instead of Eq.1
-    uint32_t seed_lo, seed_hi;   // (uint32_t)seed, seed_hi_term(seed)
+    uint32_t seed_lo, seed_hi;   // seed_key_x(seed), seed_key_a(seed): the draw's two keys
 };
 struct QuantBatch {
     int count;

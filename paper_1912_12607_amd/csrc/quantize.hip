@@ -357,7 +357,7 @@ int quant_blocks_act(int N, int Cp, int HW) {
 hipError_t launch_quantize_act(const QuantArgs& a, hipStream_t st) {
     const int N = a.d0, C = a.d1, HW = a.d2 * a.d3, Cp = (C + 15) & ~15;
     dim3 grid(quant_act_gx(Cp, HW), (Cp + QA_CH - 1) / QA_CH, N);
-    const uint32_t slo = (uint32_t)a.seed, shi = seed_hi_term(a.seed);
+    const uint32_t slo = seed_key_x(a.seed), shi = seed_key_a(a.seed);
     KernelTimer kt(KID_QUANTIZE_ACT, st);
 #define LAUNCH(ST, DV)                                                                                      \
     do {                                                                                                    \
@@ -452,7 +452,7 @@ int quant_blocks_planar(size_t n) {
 hipError_t launch_quantize_planar(const QuantArgs& a, hipStream_t st) {
     const size_t n = (size_t)a.d0 * a.d1 * a.d2 * a.d3;
     const int blocks = quant_blocks_planar(n);
-    const uint32_t slo = (uint32_t)a.seed, shi = seed_hi_term(a.seed);
+    const uint32_t slo = seed_key_x(a.seed), shi = seed_key_a(a.seed);
     KernelTimer kt(KID_QUANTIZE_PLANAR, st);
 #define LAUNCH(ST, DV)                                                                              \
     launch_timed(kt, (quantize_planar_kernel<ST, DV>), dim3(blocks), dim3(256), 0, st, a.x, n,    \
@@ -709,7 +709,7 @@ hipError_t launch_quantize_wgt(const QuantArgs& a, hipStream_t st) {
     const int Cp = (Cg + 15) & ~15, Kp = (K + 15) & ~15;
     const size_t off2 = (((size_t)K * R * S * Cp) + 255) & ~(size_t)255;
     const dim3 grid(quant_wgt_gx(Cg, R, S), (K + QW_T - 1) / QW_T, quant_wgt_zsplit(K, Cg, R, S));
-    const uint32_t slo = (uint32_t)a.seed, shi = seed_hi_term(a.seed);
+    const uint32_t slo = seed_key_x(a.seed), shi = seed_key_a(a.seed);
     KernelTimer kt(KID_QUANTIZE_WGT, st);
 #define LAUNCH(ST, DV)                                                                              \
     launch_timed(kt, (quantize_wgt_kernel<ST, DV>), grid, dim3(256), 0, st, a.x, K, Cg, R, \

@@ -110,6 +110,34 @@ def test_rng24_range_determinism_uniformity():
     assert abs(np.mean(f * w) * 12) < 6 / np.sqrt(n)
 
 
+def test_rng24_related_seeds_do_not_share_their_tables():
+    """The seed is hashed into the draw's keys first (reading of the replaced generator of Suppl.
+    "Stochastic Rounding", Eq.8).  With the raw seed words as keys -- low word xor-ed into the index, high
+    word times an odd constant added -- seeds s and s ^ d gave the SAME table at indices i ^ d, and
+    seeds that differ in the high word the same table at shifted indices: a training loop that seeds its
+    layers and iterations 1, 2, 3, ... would re-use one noise table.  Both relations must be gone."""
+    L = oracle.lib()
+    n = 1 << 12
+    for s, d in ((0, 1), (1, 2), (7, 15), (100, 3), (2 ** 40 + 5, 64)):
+        a = np.array([L.orc_rng24(s, i) for i in range(n)], dtype=np.int64)
+        b = np.array([L.orc_rng24(s ^ d, i ^ d) for i in range(n)], dtype=np.int64)
+        assert np.mean(a == b) < 0.01, (s, d)
+    golden = 0x9E3779B9
+    for s, h in ((5, 1), (5, 2), (123456, 7)):
+        lo = s & 0xFFFFFFFF
+        a = np.array([L.orc_rng24(s, i) for i in range(n)], dtype=np.int64)
+        # the index at which the old generator repeated draw(s, i) under seed s + (h << 32)
+        j = [((((i ^ lo) - h * golden) & 0xFFFFFFFF) ^ lo) for i in range(n)]
+        b = np.array([L.orc_rng24(s + (h << 32), jj) for jj in j], dtype=np.int64)
+        assert np.mean(a == b) < 0.01, (s, h)
+    # and the tables of consecutive seeds are uncorrelated position by position and at small offsets
+    f = [np.array([L.orc_rng24(s, i) for i in range(1 << 14)], dtype=np.float64) / (1 << 24) - 0.5 for s in (1, 2, 3)]
+    for a, b in ((0, 1), (1, 2), (0, 2)):
+        for off in (0, 1, 2, 3, 5, 8):
+            x, y = f[a][off:], f[b][:len(f[b]) - off]
+            assert abs(np.mean(x * y) * 12) < 6 / np.sqrt(len(x)), (a, b, off)
+
+
 def test_rng24_is_equidistributed_bijection_on_a_block():
     # for a fixed seed the 32-bit state is a bijection of the index: no collisions of the
     # full 24-bit draw beyond what 2^16 samples of a bijection's top bits allow
