@@ -26,19 +26,6 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int W2_BM = 64;              // filters per block
 constexpr int W2_LDS_BUDGET = 72 * 1024;   // two blocks per compute unit
-// 4x4 byte transpose: in d[i] = 4 channels of image i; out o[c] = channel c of images 0..3.
-__device__ __forceinline__ void transpose4x4(const uint32_t d[4], uint32_t o[4]) {
-    // v_perm_b32 picks 4 bytes out of the 8 bytes {hi, lo}; selector byte 0-3 = lo, 4-7 = hi
-    const uint32_t t0 = __builtin_amdgcn_perm(d[1], d[0], 0x05010400u);  // d0.b0 d1.b0 d0.b1 d1.b1
-    const uint32_t t1 = __builtin_amdgcn_perm(d[1], d[0], 0x07030602u);  // d0.b2 d1.b2 d0.b3 d1.b3
-    const uint32_t t2 = __builtin_amdgcn_perm(d[3], d[2], 0x05010400u);
-    const uint32_t t3 = __builtin_amdgcn_perm(d[3], d[2], 0x07030602u);
-    o[0] = __builtin_amdgcn_perm(t2, t0, 0x05040100u);  // t0.b0 t0.b1 t2.b0 t2.b1
-    o[1] = __builtin_amdgcn_perm(t2, t0, 0x07060302u);  // t0.b2 t0.b3 t2.b2 t2.b3
-    o[2] = __builtin_amdgcn_perm(t3, t1, 0x05040100u);
-    o[3] = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
-}
-
 // LDS tiles are [pixel][channels] in 16-byte granules with a pixel pitch of (channels + 4)
 // granules, and inside each aligned group of 16 channels the position is xor-ed with the group's
 // number.  The 16 consecutive loader lanes (4 or 16 channel granules per pixel, consecutive pixels)
@@ -235,7 +222,7 @@ __global__ __launch_bounds__(256, 2) void wgrad_kernel(const WgradArgs a) {
             for (int g = 0; g < 4; ++g) {
                 const uint32_t d[4] = {comp(pre[4 * g], q), comp(pre[4 * g + 1], q), comp(pre[4 * g + 2], q),
                                        comp(pre[4 * g + 3], q)};
-                transpose4x4(d, o[g]);
+                transpose4x4_bytes(d, o[g]);
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j)

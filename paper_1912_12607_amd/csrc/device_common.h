@@ -159,6 +159,23 @@ __device__ __forceinline__ int quantize_one(float x, float inv, uint32_t seed_lo
     }
 }
 
+// 4x4 byte transpose with v_perm_b32 (the gfx950 byte permute; the paper's Suppl. "INT8 Convolution"
+// does the same "4x4 8-bit integer block transpose" with prmt): in d[i] = bytes (i,0..3), out
+// o[j] = bytes (0..3, j).  Two rounds of four permutes: pairs of rows interleaved, then the halves
+// joined.  Used by the activation quantizer (channel-major dwords -> pixel-major) and by
+// backward-weight's loader (image-major -> channel-major).
+__device__ __forceinline__ void transpose4x4_bytes(const uint32_t d[4], uint32_t o[4]) {
+    // v_perm_b32 picks 4 bytes out of the 8 bytes {hi, lo}; selector byte 0-3 = lo, 4-7 = hi
+    const uint32_t t0 = __builtin_amdgcn_perm(d[1], d[0], 0x05010400u);  // d0.b0 d1.b0 d0.b1 d1.b1
+    const uint32_t t1 = __builtin_amdgcn_perm(d[1], d[0], 0x07030602u);  // d0.b2 d1.b2 d0.b3 d1.b3
+    const uint32_t t2 = __builtin_amdgcn_perm(d[3], d[2], 0x05010400u);
+    const uint32_t t3 = __builtin_amdgcn_perm(d[3], d[2], 0x07030602u);
+    o[0] = __builtin_amdgcn_perm(t2, t0, 0x05040100u);  // t0.b0 t0.b1 t2.b0 t2.b1
+    o[1] = __builtin_amdgcn_perm(t2, t0, 0x07060302u);  // t0.b2 t0.b3 t2.b2 t2.b3
+    o[2] = __builtin_amdgcn_perm(t3, t1, 0x05040100u);
+    o[3] = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
+}
+
 __device__ __forceinline__ uint32_t pack4(int q0, int q1, int q2, int q3) {
     return (uint32_t)(q0 & 0xff) | ((uint32_t)(q1 & 0xff) << 8) | ((uint32_t)(q2 & 0xff) << 16) |
            ((uint32_t)q3 << 24);

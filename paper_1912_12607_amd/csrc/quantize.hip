@@ -167,18 +167,6 @@ __host__ __device__ inline int quant_act_gx(int Cp, int HW) {
     return Cp == 16 ? (HW + QA_NARROW_PIX - 1) / QA_NARROW_PIX : (HW + QA_PIX * quant_act_nsub(HW) - 1) / (QA_PIX * quant_act_nsub(HW));
 }
 
-// 4x4 byte transpose: in d[i] = codes of 4 pixels for channel i; out o[p] = codes of 4 channels for pixel p
-__device__ __forceinline__ void qa_transpose4x4(const uint32_t d[4], uint32_t o[4]) {
-    const uint32_t t0 = __builtin_amdgcn_perm(d[1], d[0], 0x05010400u);  // d0.b0 d1.b0 d0.b1 d1.b1
-    const uint32_t t1 = __builtin_amdgcn_perm(d[1], d[0], 0x07030602u);  // d0.b2 d1.b2 d0.b3 d1.b3
-    const uint32_t t2 = __builtin_amdgcn_perm(d[3], d[2], 0x05010400u);
-    const uint32_t t3 = __builtin_amdgcn_perm(d[3], d[2], 0x07030602u);
-    o[0] = __builtin_amdgcn_perm(t2, t0, 0x05040100u);
-    o[1] = __builtin_amdgcn_perm(t2, t0, 0x07060302u);
-    o[2] = __builtin_amdgcn_perm(t3, t1, 0x05040100u);
-    o[3] = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
-}
-
 // VEC: H*W is a multiple of 4, so a thread can fetch four consecutive pixels of a channel with one
 // 16-byte load; it then owns a 4-channel x 4-pixel block, transposes its codes in registers and
 // writes one dword (4 channels) per pixel to the LDS tile.  Otherwise one pixel per lane, 4-byte loads.
@@ -297,7 +285,7 @@ __device__ __forceinline__ void quantize_act_body(
                 }
                 d[j] = pack4(code[0], code[1], code[2], code[3]);
             }
-            qa_transpose4x4(d, o);
+            transpose4x4_bytes(d, o);     // d[channel] = 4 pixels -> o[pixel] = 4 channels
 #pragma unroll
             for (int k = 0; k < 4; ++k) tile[4 * pq + k][cgp] = o[k];
         } else {
