@@ -330,9 +330,12 @@ typedef enum {
     INT8T_VARIANT_WIDE256 = 5,       /* 256 x 256 tiles, 2 stages of 128 reduction bytes */
     INT8T_VARIANT_WGRAD_FEWER = 6,
     INT8T_VARIANT_WGRAD_MORE = 7,
+    INT8T_VARIANT_WGRAD_IMAGES = 8,  /* backward-weight: operands of 16 images per pixel, transposed in registers */
+    INT8T_VARIANT_WGRAD_LINES = 9,   /* backward-weight, stride 1, 3 or 7 taps along an axis: operands of 32 image lines per
+                                        position through transposing LDS reads, gradient operands in a sliding window */
     INT8T_VARIANT_MAX_ENUM = 0x7fffffff
 } int8t_variant;
-#define INT8T_VARIANT_COUNT 8
+#define INT8T_VARIANT_COUNT 10
 /* 1 when `variant` can run pass `op` (INT8T_OP_CONV_*) of the layer, else 0 (also on a bad descriptor). */
 int int8t_conv_variant_ok(int8t_op op, const int8t_conv_desc *desc, int8t_variant variant);
 /* INT8T_ERR_ARG when the variant cannot run that pass of that layer; then nothing changes. */
@@ -349,7 +352,7 @@ int8t_variant int8t_conv_selected_variant(int8t_op op, const int8t_conv_desc *de
  *   kernel   host string: the kernel's name ("dsgc_sweep_kernel", "absmax_kernel",
  *            "absmax_batch_kernel", "quantize_batch_kernel", "quantize_act_kernel", "quantize_planar_kernel", "quantize_wgt_kernel",
  *            "deviation_finish_kernel", "igemm_kernel", "igemm_dma_kernel", "igemm_fused_kernel", "igemm_reduce_kernel",
- *            "band_kernel", "band_reg_kernel", "wgrad_kernel", "wgrad_reduce_kernel", "s2d_repack_kernel",
+ *            "band_kernel", "band_reg_kernel", "wgrad_kernel", "wgrad_lines_kernel", "wgrad_reduce_kernel", "s2d_repack_kernel",
  *            "s2d_weights_kernel", "dw_conv_kernel" (every depthwise forward / backward-data variant),
  *            "dw_wgrad_kernel" (both depthwise backward-weight variants), "dw_wgrad_reduce_kernel");
  *            NULL or "" selects every kernel.

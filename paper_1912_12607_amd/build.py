@@ -13,7 +13,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(CSRC, "libint8t.so")
-SOURCES = ["api.hip", "quantize.hip", "dsgc.hip", "conv_igemm.hip", "conv_band.hip", "conv_wgrad.hip", "s2d.hip", "conv_dw.hip", "profile.hip"]
+SOURCES = ["api.hip", "quantize.hip", "dsgc.hip", "conv_igemm.hip", "conv_band.hip", "conv_wgrad.hip", "conv_wgrad_lines.hip", "s2d.hip", "conv_dw.hip", "profile.hip"]
 HEADERS = ["device_common.h", "kernels.h", "profile.h", "lds_dma.h", os.path.join("..", "..", "include", "int8t.h")]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",

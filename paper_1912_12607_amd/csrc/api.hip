@@ -136,7 +136,14 @@ int selected_variant(int8t_op op, const int8t_conv_desc* d) {
 bool variant_ok(int8t_op op, const int8t_conv_desc* d, const Geo& g, int variant) {
     if (variant == VAR_AUTO) return true;
     if (g.depthwise) return false;
-    if (op == INT8T_OP_CONV_BWD_WEIGHT) return variant == VAR_WGRAD_FEWER || variant == VAR_WGRAD_MORE;
+    if (op == INT8T_OP_CONV_BWD_WEIGHT) {
+        if (variant == VAR_WGRAD_FEWER || variant == VAR_WGRAD_MORE || variant == VAR_WGRAD_IMAGES) return true;
+        if (variant != VAR_WGRAD_LINES) return false;
+        WgradArgs a{};
+        fill_wgrad_geometry(&a, d, g);
+        (void)wgrad_s2d(&a);
+        return wgrad_lines_applies(a);
+    }
     if (op != INT8T_OP_CONV_FWD && op != INT8T_OP_CONV_BWD_DATA) return false;
     IgemmArgs a{};
     if (op == INT8T_OP_CONV_FWD) fill_igemm_fwd(&a, d, g);

@@ -54,7 +54,6 @@ __host__ __device__ inline void tap_extent(int t0, int nt, int S, int* rmin, int
 
 constexpr int W2_MAXSTEPS = 16;        // MFMA steps per chunk: at most 32 tile pixels
 
-__host__ __device__ inline bool wgrad_xcd_mapping(int splits) { return splits >= 64 || (splits >= 8 && (splits & 7) == 0); }
 
 template <int TB, int CS>
 __global__ __launch_bounds__(256, 2) void wgrad_kernel(const WgradArgs a) {
@@ -310,57 +309,87 @@ __global__ __launch_bounds__(256, 2) void wgrad_kernel(const WgradArgs a) {
     }
 }
 
-// Sum the split partials, apply Eq.2 and scatter [k][(r,s,c)] -> K,C,R,S.  A block owns 64
-// consecutive partial columns; its 256 threads are 16 split lanes x 16 column quads, every thread
-// adds up the splits z = lane, lane+16, ... with independent 16-byte loads, and the 16 lanes are
-// combined through LDS.  (K*R*S*Cp is a multiple of 16, so a quad never straddles the end.)
+// Sum the split partials, apply Eq.2 and scatter [k][(r,s,c)] -> K,C,R,S.  A block owns, for one filter k,
+// 4*QN channels x RSC taps; its 256 threads are 256/QN split lanes x QN channel quads.  Every thread adds up the
+// splits z = lane, lane + 256/QN, ... of its quad at each tap (independent 16-byte loads, RSC of them in flight
+// per split), the lanes are combined through LDS, and the sums leave in the order of the result tensor -- with
+// all taps of a filter in the block (RSC = R*S) that is one contiguous run of 4*QN*RSC floats.  LDS holds
+// [split lane][channel][tap] with a lane pitch that is 1 mod 4 words: the stores of a wave (channel quads 4*RSC
+// words apart, lanes one pitch apart) and the final reads (consecutive words) both spread over the banks.
+template <int QN, int RSC>
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const WgradArgs a) {
-    __shared__ int4 sred[16][17];
-    const int ncolsp = a.R * a.S * a.Cp;
+    constexpr int ZL = 256 / QN, CB = 4 * QN, PITCH = CB * RSC + 1;
+    __shared__ int sred[ZL * PITCH];
+    const int RS = a.R * a.S;
+    const int ncolsp = RS * a.Cp;
     const size_t total = (size_t)a.K * ncolsp;
-    const int zl = threadIdx.x >> 4, quad = threadIdx.x & 15;
-    const size_t t4 = (size_t)blockIdx.x * 64 + 4 * quad;
-    int4 s4 = make_int4(0, 0, 0, 0);
-    if (t4 < total) {
-        const int32_t* __restrict__ p = a.partial + t4;
-        int z = zl;
-        for (; z + 48 < a.splits; z += 64) {
-            int4 v[4];
+    const int nrg = RS / RSC, nct = a.Cp / CB;
+    int b = blockIdx.x;
+    const int rg = b % nrg;
+    b /= nrg;
+    const int ct = b % nct, k = b / nct;
+    const int quad = threadIdx.x % QN, zl = threadIdx.x / QN;
+    const int32_t* __restrict__ p = a.partial + (size_t)k * ncolsp + (size_t)(rg * RSC) * a.Cp + ct * CB + 4 * quad;
+    int4 s4[RSC];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const int4*>(p + (size_t)(z + 16 * u) * total);
+    for (int j = 0; j < RSC; ++j) s4[j] = make_int4(0, 0, 0, 0);
+    // ZU splits at a time, so that a thread has ZU * RSC (at least 4) loads in flight
+    constexpr int ZU = RSC >= 4 ? 1 : RSC == 3 ? 2 : 4;
+    int z = zl;
+    for (; z + (ZU - 1) * ZL < a.splits; z += ZU * ZL) {
+        int4 v[ZU][RSC];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) { s4.x += v[u].x; s4.y += v[u].y; s4.z += v[u].z; s4.w += v[u].w; }
-        }
-        for (; z < a.splits; z += 16) {
-            const int4 v = *reinterpret_cast<const int4*>(p + (size_t)z * total);
-            s4.x += v.x; s4.y += v.y; s4.z += v.z; s4.w += v.w;
+        for (int u = 0; u < ZU; ++u)
+#pragma unroll
+            for (int j = 0; j < RSC; ++j)
+                v[u][j] = *reinterpret_cast<const int4*>(p + (size_t)(z + u * ZL) * total + (size_t)j * a.Cp);
+#pragma unroll
+        for (int u = 0; u < ZU; ++u)
+#pragma unroll
+            for (int j = 0; j < RSC; ++j) { s4[j].x += v[u][j].x; s4[j].y += v[u][j].y; s4[j].z += v[u][j].z; s4[j].w += v[u][j].w; }
+    }
+    for (; z < a.splits; z += ZL) {
+#pragma unroll
+        for (int j = 0; j < RSC; ++j) {
+            const int4 v = *reinterpret_cast<const int4*>(p + (size_t)z * total + (size_t)j * a.Cp);
+            s4[j].x += v.x; s4[j].y += v.y; s4[j].z += v.z; s4[j].w += v.w;
         }
     }
-    sred[zl][quad] = s4;
+    int* __restrict__ mine = sred + zl * PITCH + 4 * quad * RSC;
+#pragma unroll
+    for (int j = 0; j < RSC; ++j) {
+        mine[j] = s4[j].x;
+        mine[RSC + j] = s4[j].y;
+        mine[2 * RSC + j] = s4[j].z;
+        mine[3 * RSC + j] = s4[j].w;
+    }
     __syncthreads();
-    if (threadIdx.x >= 64) return;
-    const size_t t = (size_t)blockIdx.x * 64 + threadIdx.x;
-    if (t >= total) return;
-    int sum = 0;
-#pragma unroll
-    for (int l = 0; l < 16; ++l) sum += reinterpret_cast<const int*>(&sred[l][threadIdx.x >> 2])[threadIdx.x & 3];
-    const int k = (int)(t / ncolsp);
-    const int col = (int)(t - (size_t)k * ncolsp);
-    const int rs = col / a.Cp, c = col - rs * a.Cp;
-    if (c >= a.C) return;
-    size_t o = ((size_t)k * a.C + c) * (a.R * a.S) + rs;
-    if (a.s2d) {
-        // back from the space-to-depth form: channel (2 dy + dx) * oC + c0 of tap (r', s') is channel c0
-        // of tap (2 r' + dy - eh, 2 s' + dx - ew); taps outside the layer's own filter are dropped
-        const int blk = c / a.oC, c0 = c - blk * a.oC;
-        const int rr = rs / a.S;
-        const int r = 2 * rr + (blk >> 1) - a.eh, s = 2 * (rs - rr * a.S) + (blk & 1) - a.ew;
-        if (r < 0 || r >= a.oR || s < 0 || s >= a.oS) return;
-        o = (((size_t)k * a.oC + c0) * a.oR + r) * a.oS + s;
+    const int nz = a.splits < ZL ? a.splits : ZL;
+    const float scale = __fmul_rn(a.sa[0], a.sb[0]);
+    for (int t = threadIdx.x; t < CB * RSC; t += 256) {
+        int sum = 0;
+        for (int z = 0; z < nz; ++z) sum += sred[z * PITCH + t];
+        const int cl = t / RSC;
+        const int c = ct * CB + cl, rs = rg * RSC + (t - cl * RSC);
+        if (c >= a.C) continue;
+        size_t o = ((size_t)k * a.C + c) * RS + rs;
+        if (a.s2d) {
+            // back from the space-to-depth form: channel (2 dy + dx) * oC + c0 of tap (r', s') is channel c0
+            // of tap (2 r' + dy - eh, 2 s' + dx - ew); taps outside the layer's own filter are dropped
+            const int blk = c / a.oC, c0 = c - blk * a.oC;
+            const int rr = rs / a.S;
+            const int r = 2 * rr + (blk >> 1) - a.eh, s = 2 * (rs - rr * a.S) + (blk & 1) - a.ew;
+            if (r < 0 || r >= a.oR || s < 0 || s >= a.oS) continue;
+            o = (((size_t)k * a.oC + c0) * a.oR + r) * a.oS + s;
+        }
+        a.dw[o] = __fmul_rn((float)sum, scale);
+        if (a.acc) a.acc[o] = sum;
     }
-    a.dw[o] = __fmul_rn((float)sum, __fmul_rn(a.sa[0], a.sb[0]));
-    if (a.acc) a.acc[o] = sum;
 }
+
+// The kernel VAR_AUTO runs: wgrad_lines_kernel wherever it applies (measured on the benchmark's 1x7, 7x1
+// and 3x3 layers it needs 0.6 - 0.85 of wgrad_kernel's time).
+bool wgrad_auto_lines(const WgradArgs& a) { return wgrad_lines_applies(a); }
 
 size_t wgrad_s2d(WgradArgs* a) {
     a->s2d = 0;
@@ -420,11 +449,16 @@ void wgrad_plan(WgradArgs* a) {
     a->TB = p.TB; a->CS = p.CS; a->BP = p.BP; a->BQ = p.BQ; a->ntp = p.ntp; a->ntq = p.ntq;
     a->ngrp = p.ngrp; a->chunks = p.chunks; a->splits = p.splits;
     a->ktiles = p.ktiles; a->ctiles = p.ctiles; a->tapgroups = p.tapgroups;
-    a->xt_slots = p.xt_slots; a->lds_bytes = p.lds_bytes;
+    a->xt_slots = p.xt_slots; a->lds_bytes = p.lds_bytes; a->lines = p.lines;
 }
 
 namespace {
 void wgrad_plan_uncached(WgradArgs* a) {
+    a->lines = 0;
+    if (a->variant == VAR_WGRAD_LINES || (a->variant != VAR_WGRAD_IMAGES && wgrad_auto_lines(*a))) {
+        wgrad_plan_lines(a);
+        return;
+    }
     const int RS = a->R * a->S;
     // taps per block / channel slabs per wave: one filter row of a 3-wide filter, a whole 1x7 or
     // 7x1 filter, a wide channel tile for 1x1, one tap at a time otherwise
@@ -525,7 +559,10 @@ hipError_t launch_wgrad(const WgradArgs& a_in, hipStream_t st) {
         if (ea != hipSuccess) return ea;                                                                  \
         launch_timed(kt, (wgrad_kernel<TBv, CSv>), grid, dim3(256), a.lds_bytes, st, a);                \
     } while (0)
-    {
+    if (a.lines) {
+        hipError_t el = launch_wgrad_lines(a, grid, st);
+        if (el != hipSuccess) return el;
+    } else {
         KernelTimer kt(KID_WGRAD, st);
         if (a.TB == 1 && a.CS == 1) LAUNCH(1, 1);
         else if (a.TB == 1 && a.CS == 4) LAUNCH(1, 4);
@@ -536,10 +573,37 @@ hipError_t launch_wgrad(const WgradArgs& a_in, hipStream_t st) {
 #undef LAUNCH
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const size_t total = (size_t)a.K * a.R * a.S * a.Cp;
+    // Shape of the reducing blocks: the most taps (9, 7 or 3 where they divide R*S) and channels (64 or 16) per
+    // block that still give the chip 1024 blocks -- few fat blocks leave compute units idle and the loads of a
+    // small layer are latency, not bandwidth; one tap x 16 channels if nothing does.
+    const int RS = a.R * a.S;
+    int rsc = 1;
+    bool wide = false;
+    {
+        const int cand[3] = {9, 7, 3};
+        bool found = false;
+        for (int w = 1; w >= 0 && !found; --w) {
+            if (w && a.Cp % 64 != 0) continue;
+            for (int i = 0; i < 4 && !found; ++i) {
+                const int r = i < 3 ? cand[i] : 1;
+                if (RS % r != 0) continue;
+                if ((long long)a.K * (a.Cp / (w ? 64 : 16)) * (RS / r) >= 1024) { rsc = r; wide = w != 0; found = true; }
+            }
+        }
+    }
+    const unsigned rblocks = (unsigned)(a.K * (a.Cp / (wide ? 64 : 16)) * (RS / rsc));
     {
         KernelTimer kt(KID_WGRAD_REDUCE, st);
-        launch_timed(kt, wgrad_reduce_kernel, dim3((unsigned)((total + 63) / 64)), dim3(256), 0, st, a);
+#define REDUCE(RSCv)                                                                                      \
+    do {                                                                                                  \
+        if (wide) launch_timed(kt, (wgrad_reduce_kernel<16, RSCv>), dim3(rblocks), dim3(256), 0, st, a); \
+        else launch_timed(kt, (wgrad_reduce_kernel<4, RSCv>), dim3(rblocks), dim3(256), 0, st, a);       \
+    } while (0)
+        if (rsc == 9) REDUCE(9);
+        else if (rsc == 7) REDUCE(7);
+        else if (rsc == 3) REDUCE(3);
+        else REDUCE(1);
+#undef REDUCE
     }
     return hipGetLastError();
 }

@@ -146,6 +146,8 @@ enum ConvVariant : int {
     VAR_WIDE256 = 5,       // 256 x 256 tiles, ring of 2 stages of 128 reduction bytes
     VAR_WGRAD_FEWER = 6,   // backward-weight: half the reduction shares of the cost model's choice
     VAR_WGRAD_MORE = 7,    // backward-weight: twice as many
+    VAR_WGRAD_IMAGES = 8,  // backward-weight: operands of 16 images per pixel, transposed in registers (conv_wgrad.hip)
+    VAR_WGRAD_LINES = 9,   // backward-weight: operands of 32 image lines per position, transposing LDS reads (conv_wgrad_lines.hip)
     VAR_COUNT
 };
 int igemm_ksplit(const IgemmArgs& a);   // largest split a launch of this layer may use (1 = none): sizes the scratch
@@ -212,13 +214,22 @@ struct WgradArgs {
     int s2d;                     // 1: C, Cp, H, W, R, S, strides and pads describe the rewritten problem
     int oC, oR, oS, oH, oW, eh, ew;   // the layer's own channels, filter and image; tap r = 2 r' + dy - eh, s = 2 s' + dx - ew
     int8_t* xs;                  // scratch: the input codes in space-to-depth form, [N][H][W][16]
-    int variant;                 // VAR_AUTO, VAR_WGRAD_FEWER or VAR_WGRAD_MORE: set before wgrad_plan()
+    int variant;                 // VAR_AUTO or a VAR_WGRAD_*: set before wgrad_plan()
+    int lines;                   // filled by wgrad_plan(): 1 = wgrad_lines_kernel runs (TB = taps along the line)
 };
 // Rewrites the geometry into the space-to-depth form (s2d.hip) when it applies.  Returns the bytes of
 // the rewritten input codes (0: does not apply, the geometry is left alone).  Call before wgrad_plan().
 size_t wgrad_s2d(WgradArgs* a);
 void wgrad_plan(WgradArgs* a);   // needs the geometry fields above the first comment
 hipError_t launch_wgrad(const WgradArgs& a, hipStream_t st);
+// conv_wgrad_lines.hip: the kernel for stride-1 filters with 3 or 7 taps along an image axis
+bool wgrad_lines_applies(const WgradArgs& a);    // geometry as wgrad_plan() takes it (after wgrad_s2d())
+void wgrad_plan_lines(WgradArgs* a);
+hipError_t launch_wgrad_lines(const WgradArgs& a, dim3 grid, hipStream_t st);
+// which kernel VAR_AUTO stands for: true = wgrad_lines_kernel
+bool wgrad_auto_lines(const WgradArgs& a);
+// reduction shares of one XCD are given neighbouring workgroups when there are enough of them
+__host__ __device__ inline bool wgrad_xcd_mapping(int splits) { return splits >= 64 || (splits >= 8 && (splits & 7) == 0); }
 
 // ---- conv_dw.hip (depthwise, planar codes) ----------------------------------------------------
 struct DwArgs {

@@ -28,6 +28,7 @@ enum KernelId : int {
     KID_BAND,
     KID_BAND_REG,
     KID_WGRAD,
+    KID_WGRAD_LINES,
     KID_WGRAD_REDUCE,
     KID_S2D_REPACK,
     KID_S2D_WEIGHTS,

@@ -26,7 +26,7 @@ const char* const kNames[KID_COUNT] = {
     "absmax_kernel",       "absmax_batch_kernel", "quantize_act_kernel", "quantize_planar_kernel", "quantize_wgt_kernel",
     "quantize_batch_kernel",
     "deviation_finish_kernel", "dsgc_sweep_kernel",   "igemm_kernel", "igemm_dma_kernel", "igemm_fused_kernel", "igemm_reduce_kernel",
-    "band_kernel",         "band_reg_kernel",     "wgrad_kernel",        "wgrad_reduce_kernel",    "s2d_repack_kernel", "s2d_weights_kernel", "dw_conv_kernel",
+    "band_kernel",         "band_reg_kernel",     "wgrad_kernel",        "wgrad_lines_kernel", "wgrad_reduce_kernel",    "s2d_repack_kernel", "s2d_weights_kernel", "dw_conv_kernel",
     "dw_wgrad_kernel",     "dw_wgrad_reduce_kernel"};
 
 void drop_all() {
