@@ -28,18 +28,24 @@ typedef int wl_v4i __attribute__((ext_vector_type(4)));
 typedef int wl_v16i __attribute__((ext_vector_type(16)));
 
 constexpr int WL_LINES = 32;                     // lines per chunk: the reduction depth of one MFMA
-constexpr int WL_GP = 8;                         // positions per ring stage
-constexpr int WL_SLAB = WL_LINES * 64;           // bytes of one position of one tensor: 32 lines x 64 channels
-constexpr int WL_STAGE = 2 * WL_GP * WL_SLAB;    // input slabs, then gradient slabs
+constexpr int WL_SUB = WL_LINES * 64;            // bytes of one position of 64 channels of one tensor
 constexpr int WL_NSTAGE = 2;
-constexpr int WL_BM = 64;                        // filters per block
+// ring stage of a variant: GP positions, each the input's WN and the gradient's WM 64-channel slabs
+__host__ __device__ constexpr int wl_stage_bytes(int WM, int WN, int GP) { return GP * (WM + WN) * WL_SUB; }
 
 typedef __attribute__((address_space(3))) wl_v2i* wl_lds_ptr;
 
-template <int ST>
+// ST taps along the line; a wave owns WM x WN MFMA tiles (32 filters x 32 channels each) per tap, the block's
+// four waves (2 x 2) a tile of 64 WM filters x 64 WN channels; GP positions per ring stage.
+template <int ST, int WM, int WN, int GP>
 __global__ __launch_bounds__(256, 2) void wgrad_lines_kernel(const WgradArgs a) {
     constexpr int NSLOT = ST + 1;                // gradient operands kept: the window of ST plus the one being fetched
-    static_assert(WL_GP % NSLOT == 0, "the window slot of a position must not depend on the stage");
+    static_assert(GP % NSLOT == 0, "the window slot of a position must not depend on the stage");
+    static_assert((WM == 1 && WN == 1) || (WM == 2 && WN == 2), "loader roles below");
+    constexpr bool BOTH = WM + WN == 4;          // every wave loads both tensors (else waves 0,1 the input, 2,3 the gradient)
+    constexpr int STAGE = wl_stage_bytes(WM, WN, GP);
+    constexpr int XPOS = WN * WL_SUB, YPOS = WM * WL_SUB;   // bytes per position
+    constexpr int YOFF = GP * XPOS;                        // gradient slabs follow the input slabs
     extern __shared__ __attribute__((aligned(1024))) unsigned char lsm[];
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -65,7 +71,7 @@ __global__ __launch_bounds__(256, 2) void wgrad_lines_kernel(const WgradArgs a) 
 
     // Lines and positions.  along_w: a line is an image row, positions run along W, the block owns tap
     // row tg; otherwise (R x 1 filters) a line is an image column and positions run along H.
-    const bool along_w = a.S > 1;
+    const bool along_w = wgrad_lines_along_w(a.R, a.S);
     const int NLI = along_w ? a.P : a.Q;          // gradient lines per image
     const int QL = along_w ? a.Q : a.P;           // gradient positions on a line
     const int WLn = along_w ? a.W : a.H;          // input positions on a line
@@ -78,106 +84,145 @@ __global__ __launch_bounds__(256, 2) void wgrad_lines_kernel(const WgradArgs a) 
     const uint32_t x_ls = along_w ? (uint32_t)a.W * a.Cp : (uint32_t)a.Cp;
     const uint32_t x_ps = along_w ? (uint32_t)a.Cp : (uint32_t)a.W * a.Cp;
     // Step u of a line: the gradient position u enters the window, the input position u - pl is
-    // multiplied with the gradient positions u, u-1, .., u-ST+1 (taps 0 .. ST-1).
+    // multiplied with the gradient positions u, u-1, .., u-ST+1 (taps 0 .. ST-1).  A ring stage holds GP
+    // steps of one chunk.  (Letting the stages run on across chunk ends saves the idle steps of a chunk's last
+    // stage, but the bookkeeping per step costs more than they do: measured 26 -> 28 us on 14 x 14 images.)
     const int U = WLn + pl;
-    const int GC = (U + WL_GP - 1) / WL_GP;       // ring stages per chunk
+    const int GC = (U + GP - 1) / GP;             // ring stages per chunk
     const int total_lines = a.N * NLI;
-
-    // ---- loader role: waves 0,1 fetch the input, waves 2,3 the gradient; a wave-wide load fills 16 lines
-    // x 64 channels of one position (1 KB of LDS in lane order).  The 32-byte halves of a line are swapped
-    // in lines 4..7 (mod 8): the transposing reads below then touch every LDS bank once.
-    const int tensor = wave >> 1;
-    const int myline = 16 * (wave & 1) + (lane >> 2);
-    const int gg = (lane & 3) ^ (((myline >> 2) & 1) << 1);           // granule of the line this lane fetches
-    const int chan = (tensor ? kt * WL_BM : ct * 64) + 16 * gg;
-    const bool chan_ok = chan < (tensor ? a.Kp : a.Cp);
-    const wl_v4i rsrc = igd_rsrc(tensor ? (const void*)a.dy : (const void*)a.x,
-                                 tensor ? (uint32_t)a.N * a.P * a.Q * a.Kp : (uint32_t)a.N * a.H * a.W * a.Cp);
-    const uint32_t my_ls = tensor ? dy_ls : x_ls, my_ps = tensor ? dy_ps : x_ps;
-    const uint32_t my_img = tensor ? (uint32_t)a.P * a.Q * a.Kp : (uint32_t)a.H * a.W * a.Cp;
-    const int my_npos = tensor ? QL : WLn, my_poff = tensor ? 0 : pl;
-    const int my_lshift = tensor ? 0 : xshift, my_nlines = tensor ? NLI : XC;
-    const uint32_t lds0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(size_t)lsm);
-    const uint32_t lds_mine = lds0 + (uint32_t)(tensor * WL_GP * WL_SLAB + (wave & 1) * 1024);
-
-    // byte offset of this lane's line in chunk `chunk` (IGD_OOB: no such line -- zeros are loaded)
-    auto line_base = [&](int chunk) -> uint32_t {
-        const int L = chunk * WL_LINES + myline;
-        if (L >= total_lines || !chan_ok) return IGD_OOB;
-        const int n = L / NLI;
-        const int l = L - n * NLI + my_lshift;
-        if ((unsigned)l >= (unsigned)my_nlines) return IGD_OOB;
-        return (uint32_t)n * my_img + (uint32_t)l * my_ls + (uint32_t)chan;
-    };
-    auto issue = [&](uint32_t lb, int g, int slot) {
-        const uint32_t dst = lds_mine + (uint32_t)slot * WL_STAGE;
-        int pos = g * WL_GP - my_poff;
-#pragma unroll
-        for (int j = 0; j < WL_GP; ++j, ++pos) {
-            const bool ok = lb != IGD_OOB && (unsigned)pos < (unsigned)my_npos;
-            igd_load_lds(rsrc, dst + (uint32_t)j * WL_SLAB, ok ? lb + (uint32_t)pos * my_ps : IGD_OOB);
-        }
-    };
-
-    // ---- operand role: wave (mt, ch) owns filters 32 mt .. +31 and channels 32 ch .. +31 of the block's tile.
-    // Chunk address of this lane for the first of an operand's two reads (the second: 8 lines on, +512 B).
-    const int rl = ((lane & 15) >> 1) + 16 * half;
-    const int b2 = (lane >> 3) & 1, hi = (lane >> 4) & 1;
-    const uint32_t rd_common = (uint32_t)(rl * 64 + 16 * hi + 8 * (lane & 1));
-    const uint32_t offA = (uint32_t)(WL_GP * WL_SLAB) + rd_common + 32u * (uint32_t)(mt ^ b2);
-    const uint32_t offB = rd_common + 32u * (uint32_t)(ch ^ b2);
-
-    wl_v16i acc[ST];
-#pragma unroll
-    for (int s = 0; s < ST; ++s)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[s][v] = 0;
-    wl_v4i A[NSLOT];
-#pragma unroll
-    for (int s = 0; s < NSLOT; ++s) A[s] = wl_v4i{0, 0, 0, 0};
-
     const int c_begin = (int)(((uint32_t)a.chunks * (uint32_t)zshare) / (uint32_t)a.splits);
     const int c_end = (int)(((uint32_t)a.chunks * (uint32_t)(zshare + 1)) / (uint32_t)a.splits);
     const int NS = (c_end - c_begin) * GC;
 
-    int ci = c_begin, gi = 0;           // stage that is fetched next
-    uint32_t lb = IGD_OOB;
-    if (NS > 0) {
-        lb = line_base(ci);
-        issue(lb, 0, 0);
-        if (++gi == GC) { gi = 0; ++ci; if (ci < c_end) lb = line_base(ci); }
+    // ---- loader role.  A wave-wide load fills 16 lines x 64 channels of one position (1 KB of LDS in lane
+    // order).  The 32-byte halves of a line are swapped in lines 4..7 (mod 8): the transposing reads below
+    // then touch every LDS bank once.  NLD loads per wave and position: with one MFMA tile per wave and tap,
+    // waves 0,1 fetch the input and waves 2,3 the gradient; with 2 x 2, wave w fetches lines 16 (w%2) .. +15 of
+    // the 64-channel slab w/2 of both tensors.
+    constexpr int NLD = BOTH ? 2 : 1;
+    const int myline = 16 * (wave & 1) + (lane >> 2);
+    const int gg = (lane & 3) ^ (((myline >> 2) & 1) << 1);           // granule of the line this lane fetches
+    const uint32_t lds0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(size_t)lsm);
+    wl_v4i rsrc[NLD];
+    uint32_t ld_ps[NLD], ld_img[NLD], ld_ls[NLD], ld_dst[NLD], ld_pitch[NLD], ld_base[NLD];
+    int ld_npos[NLD], ld_poff[NLD], ld_lshift[NLD], ld_nlines[NLD], ld_chan[NLD];
+    bool ld_chan_ok[NLD];
+#pragma unroll
+    for (int e = 0; e < NLD; ++e) {
+        const int tensor = BOTH ? e : (wave >> 1);              // 0: input codes, 1: gradient codes
+        const int sub = BOTH ? (wave >> 1) : 0;
+        rsrc[e] = igd_rsrc(tensor ? (const void*)a.dy : (const void*)a.x,
+                           tensor ? (uint32_t)a.N * a.P * a.Q * a.Kp : (uint32_t)a.N * a.H * a.W * a.Cp);
+        ld_ls[e] = tensor ? dy_ls : x_ls;
+        ld_ps[e] = tensor ? dy_ps : x_ps;
+        ld_img[e] = tensor ? (uint32_t)a.P * a.Q * a.Kp : (uint32_t)a.H * a.W * a.Cp;
+        ld_npos[e] = tensor ? QL : WLn;
+        ld_poff[e] = tensor ? 0 : pl;
+        ld_lshift[e] = tensor ? 0 : xshift;
+        ld_nlines[e] = tensor ? NLI : XC;
+        ld_chan[e] = (tensor ? kt * (64 * WM) : ct * (64 * WN)) + 64 * sub + 16 * gg;
+        ld_chan_ok[e] = ld_chan[e] < (tensor ? a.Kp : a.Cp);
+        ld_pitch[e] = tensor ? YPOS : XPOS;
+        ld_dst[e] = lds0 + (uint32_t)((tensor ? YOFF : 0) + sub * WL_SUB + (wave & 1) * 1024);
+        ld_base[e] = IGD_OOB;
     }
-    int g = 0;                          // stage that is multiplied next (its chunk does not matter any more)
+    // byte offset of this lane's line in chunk `chunk` (IGD_OOB: no such line -- zeros are loaded)
+    auto line_base = [&](int e, int chunk) -> uint32_t {
+        const int L = chunk * WL_LINES + myline;
+        if (chunk >= c_end || L >= total_lines || !ld_chan_ok[e]) return IGD_OOB;
+        const int n = L / NLI;
+        const int l = L - n * NLI + ld_lshift[e];
+        if ((unsigned)l >= (unsigned)ld_nlines[e]) return IGD_OOB;
+        return (uint32_t)n * ld_img[e] + (uint32_t)l * ld_ls[e] + (uint32_t)ld_chan[e];
+    };
+    int lc = c_begin, lg = 0;           // chunk and stage (of the chunk) that is fetched next
+#pragma unroll
+    for (int e = 0; e < NLD; ++e) ld_base[e] = line_base(e, lc);
+    auto issue = [&](int slot) {
+#pragma unroll
+        for (int j = 0; j < GP; ++j) {
+#pragma unroll
+            for (int e = 0; e < NLD; ++e) {
+                const int pos = lg * GP + j - ld_poff[e];
+                const bool ok = ld_base[e] != IGD_OOB && (unsigned)pos < (unsigned)ld_npos[e];
+                igd_load_lds(rsrc[e], ld_dst[e] + (uint32_t)slot * STAGE + (uint32_t)j * ld_pitch[e],
+                             ok ? ld_base[e] + (uint32_t)pos * ld_ps[e] : IGD_OOB);
+            }
+        }
+        if (++lg == GC) {
+            lg = 0;
+            ++lc;
+#pragma unroll
+            for (int e = 0; e < NLD; ++e) ld_base[e] = line_base(e, lc);
+        }
+    };
+
+    // ---- operand role: wave (mt, ch) owns WM x WN MFMA tiles.  Chunk address of this lane for the first of
+    // an operand's two reads (the second: 8 lines on, +512 B).
+    const int rl = ((lane & 15) >> 1) + 16 * half;
+    const int b2 = (lane >> 3) & 1, hi = (lane >> 4) & 1;
+    const uint32_t rd_common = (uint32_t)(rl * 64 + 16 * hi + 8 * (lane & 1));
+    uint32_t offA[WM], offB[WN];
+#pragma unroll
+    for (int i = 0; i < WM; ++i) offA[i] = YOFF + rd_common + (WM == 2 ? (uint32_t)(mt * WL_SUB) + 32u * (uint32_t)(i ^ b2) : 32u * (uint32_t)(mt ^ b2));
+#pragma unroll
+    for (int i = 0; i < WN; ++i) offB[i] = rd_common + (WN == 2 ? (uint32_t)(ch * WL_SUB) + 32u * (uint32_t)(i ^ b2) : 32u * (uint32_t)(ch ^ b2));
+
+    wl_v16i acc[ST][WM][WN];
+#pragma unroll
+    for (int s = 0; s < ST; ++s)
+#pragma unroll
+        for (int i = 0; i < WM; ++i)
+#pragma unroll
+            for (int k = 0; k < WN; ++k)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[s][i][k][v] = 0;
+    wl_v4i A[NSLOT][WM];
+#pragma unroll
+    for (int s = 0; s < NSLOT; ++s)
+#pragma unroll
+        for (int i = 0; i < WM; ++i) A[s][i] = wl_v4i{0, 0, 0, 0};
+
+    if (NS > 0) issue(0);
+    int g = 0;                          // stage (of its chunk) that is multiplied next
     for (int i = 0; i < NS; ++i) {
         igd_wait_vmcnt<0>();            // this wave's loads of stage i have landed ...
         __syncthreads();                // ... and everyone's; all waves are done with stage i-1's slot
-        if (i + 1 < NS) {
-            issue(lb, gi, (i + 1) & 1);
-            if (++gi == GC) { gi = 0; ++ci; if (ci < c_end) lb = line_base(ci); }
-        }
-        const wl_lds_ptr pa = (wl_lds_ptr)(uintptr_t)(lds0 + (uint32_t)(i & 1) * WL_STAGE + offA);
-        const wl_lds_ptr pb = (wl_lds_ptr)(uintptr_t)(lds0 + (uint32_t)(i & 1) * WL_STAGE + offB);
-        auto fetch = [&](wl_lds_ptr p, int j) -> wl_v4i {
-            const wl_v2i r0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32(p + (j * WL_SLAB) / 8);
-            const wl_v2i r1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32(p + (j * WL_SLAB + 512) / 8);
+        if (i + 1 < NS) issue((i + 1) & 1);
+        const uint32_t sbase = lds0 + (uint32_t)(i & 1) * STAGE;
+        auto fetch = [&](uint32_t off, int bytes) -> wl_v4i {
+            const wl_lds_ptr p = (wl_lds_ptr)(uintptr_t)(sbase + off);
+            const wl_v2i r0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32(p + bytes / 8);
+            const wl_v2i r1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32(p + (bytes + 512) / 8);
             return wl_v4i{r0.x, r0.y, r1.x, r1.y};
         };
-        const int u0 = g * WL_GP;
-        wl_v4i Bn = fetch(pb, 0), Bc;
-        A[0] = fetch(pa, 0);
+        wl_v4i Bn[WN], Bc[WN];
 #pragma unroll
-        for (int j = 0; j < WL_GP; ++j) {
-            Bc = Bn;
-            if (j + 1 < WL_GP) {
-                A[(j + 1) % NSLOT] = fetch(pa, j + 1);
-                Bn = fetch(pb, j + 1);
+        for (int k = 0; k < WN; ++k) Bn[k] = fetch(offB[k], 0);
+#pragma unroll
+        for (int k = 0; k < WM; ++k) A[0][k] = fetch(offA[k], 0);
+#pragma unroll
+        for (int j = 0; j < GP; ++j) {
+#pragma unroll
+            for (int k = 0; k < WN; ++k) Bc[k] = Bn[k];
+            if (j + 1 < GP) {
+#pragma unroll
+                for (int k = 0; k < WM; ++k) A[(j + 1) % NSLOT][k] = fetch(offA[k], (j + 1) * YPOS);
+#pragma unroll
+                for (int k = 0; k < WN; ++k) Bn[k] = fetch(offB[k], (j + 1) * XPOS);
             }
-            const int u = u0 + j;
-            if ((unsigned)(u - pl) < (unsigned)WLn) {
+            const int u = g * GP + j;
+            if (__builtin_expect((unsigned)(u - pl) < (unsigned)WLn, 1)) {
 #pragma unroll
                 for (int s = 0; s < ST; ++s) {
-                    if ((unsigned)(u - s) < (unsigned)QL)
-                        acc[s] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[(j - s + NSLOT) % NSLOT], Bc, acc[s], 0, 0, 0);
+                    if (__builtin_expect((unsigned)(u - s) < (unsigned)QL, 1)) {
+#pragma unroll
+                        for (int m = 0; m < WM; ++m)
+#pragma unroll
+                            for (int k = 0; k < WN; ++k)
+                                acc[s][m][k] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[(j - s + NSLOT) % NSLOT][m], Bc[k],
+                                                                                     acc[s][m][k], 0, 0, 0);
+                    }
                 }
             }
         }
@@ -187,54 +232,61 @@ __global__ __launch_bounds__(256, 2) void wgrad_lines_kernel(const WgradArgs a) 
     // partial[z][k][(tap,c)], channel fastest: 32 consecutive columns per store instruction
     const int ncolsp = a.R * a.S * a.Cp;
     int32_t* __restrict__ part = a.partial + (size_t)zshare * a.K * ncolsp;
-    const int c = ct * 64 + ch * 32 + l32;
-    if (c < a.Cp) {
+#pragma unroll
+    for (int k2 = 0; k2 < WN; ++k2) {
+        const int c = ct * (64 * WN) + (ch * WN + k2) * 32 + l32;
+        if (c >= a.Cp) continue;
 #pragma unroll
         for (int s = 0; s < ST; ++s) {
             const int col = (t0 + s) * a.Cp + c;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int k = kt * WL_BM + mt * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-                if (k < a.K) part[(size_t)k * ncolsp + col] = acc[s][v];
-            }
+            for (int m = 0; m < WM; ++m)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int k = kt * (64 * WM) + (mt * WM + m) * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+                    if (k < a.K) part[(size_t)k * ncolsp + col] = acc[s][m][k2][v];
+                }
         }
     }
 }
 
 bool wgrad_lines_applies(const WgradArgs& a) {
     if (a.s2d || a.stride_h != 1 || a.stride_w != 1) return false;
+    const bool one = a.R == 1 && a.S == 1;
     const bool along_w = a.S == 3 || a.S == 7;
     const bool along_h = a.S == 1 && (a.R == 3 || a.R == 7);
-    if (!along_w && !along_h) return false;
+    if (!one && !along_w && !along_h) return false;
     // byte offsets into either tensor stay below the value that stands for "nothing to load"
     if ((unsigned long long)a.N * a.H * a.W * a.Cp >= IGD_OOB || (unsigned long long)a.N * a.P * a.Q * a.Kp >= IGD_OOB) return false;
     return true;
 }
 
 void wgrad_plan_lines(WgradArgs* a) {
-    const bool along_w = a->S > 1;
+    const bool along_w = wgrad_lines_along_w(a->R, a->S);
     const int ST = along_w ? a->S : a->R;
+    const int WT = ST == 1 ? 2 : 1;              // MFMA tiles per wave and tap in each direction
+    const int GP = ST == 1 ? 4 : 8;
     a->lines = 1;
     a->TB = ST;
-    a->CS = 1;
+    a->CS = WT;
     a->BP = a->BQ = a->ntp = a->ntq = a->ngrp = 0;
     a->xt_slots = 0;
     a->tapgroups = along_w ? a->R : 1;
-    a->ktiles = (a->K + WL_BM - 1) / WL_BM;
-    a->ctiles = (a->Cp + 63) / 64;
+    a->ktiles = (a->K + 64 * WT - 1) / (64 * WT);
+    a->ctiles = (a->Cp + 64 * WT - 1) / (64 * WT);
     const int NLI = along_w ? a->P : a->Q;
     const int QL = along_w ? a->Q : a->P;
     const int WLn = along_w ? a->W : a->H;
     const int pl = along_w ? a->pad_w : a->pad_h;
     a->chunks = (a->N * NLI + WL_LINES - 1) / WL_LINES;
-    a->lds_bytes = (size_t)WL_NSTAGE * WL_STAGE;
-    const int GC = (WLn + pl + WL_GP - 1) / WL_GP;
+    a->lds_bytes = (size_t)WL_NSTAGE * wl_stage_bytes(WT, WT, GP);
     // Split count by the same estimate as wgrad_plan(): rounds of resident blocks (two per compute unit),
     // a block pays a prologue plus its stages, every split one write and one read of the partial tiles.
     const int out_tiles = a->ktiles * a->ctiles * a->tapgroups;
     const int slots = 512;
-    const double mfma_per_chunk = (double)QL * ST;   // per wave, a little less at the image border
-    const double t_chunk = GC * 0.45 + 0.014 * 2.0 * mfma_per_chunk;
+    const double stages_per_chunk = (double)(WLn + pl) / GP;
+    const double mfma_per_chunk = (double)QL * ST * WT * WT;   // per wave, a little less at the image border
+    const double t_chunk = stages_per_chunk * 0.45 + 0.014 * 2.0 * mfma_per_chunk;
     const double t_partial = (double)a->K * a->R * a->S * a->Cp * 8.0 / 4.0e6;
     int splits = 1;
     double best = 1e30;
@@ -252,16 +304,17 @@ void wgrad_plan_lines(WgradArgs* a) {
 
 hipError_t launch_wgrad_lines(const WgradArgs& a, dim3 grid, hipStream_t st) {
     KernelTimer kt(KID_WGRAD_LINES, st);
-#define LAUNCH(STv)                                                                                      \
+#define LAUNCH(STv, WTv, GPv)                                                                            \
     do {                                                                                                 \
         static std::atomic<unsigned long long> attr_done;                                                \
-        hipError_t ea = raise_dynamic_lds(reinterpret_cast<const void*>(wgrad_lines_kernel<STv>),        \
-                                          WL_NSTAGE * WL_STAGE, attr_done);                              \
+        hipError_t ea = raise_dynamic_lds(reinterpret_cast<const void*>(wgrad_lines_kernel<STv, WTv, WTv, GPv>), \
+                                          WL_NSTAGE * wl_stage_bytes(WTv, WTv, GPv), attr_done);         \
         if (ea != hipSuccess) return ea;                                                                 \
-        launch_timed(kt, (wgrad_lines_kernel<STv>), grid, dim3(256), a.lds_bytes, st, a);                \
+        launch_timed(kt, (wgrad_lines_kernel<STv, WTv, WTv, GPv>), grid, dim3(256), a.lds_bytes, st, a); \
     } while (0)
-    if (a.TB == 3) LAUNCH(3);
-    else if (a.TB == 7) LAUNCH(7);
+    if (a.TB == 3) LAUNCH(3, 1, 8);
+    else if (a.TB == 7) LAUNCH(7, 1, 8);
+    else if (a.TB == 1) LAUNCH(1, 2, 4);
     else return hipErrorInvalidValue;
 #undef LAUNCH
     return hipGetLastError();

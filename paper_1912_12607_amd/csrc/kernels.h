@@ -224,6 +224,8 @@ void wgrad_plan(WgradArgs* a);   // needs the geometry fields above the first co
 hipError_t launch_wgrad(const WgradArgs& a, hipStream_t st);
 // conv_wgrad_lines.hip: the kernel for stride-1 filters with 3 or 7 taps along an image axis
 bool wgrad_lines_applies(const WgradArgs& a);    // geometry as wgrad_plan() takes it (after wgrad_s2d())
+// lines are image rows and the taps of a block run along W (else: columns, along H)
+__host__ __device__ inline bool wgrad_lines_along_w(int R, int S) { return S > 1 || R == 1; }
 void wgrad_plan_lines(WgradArgs* a);
 hipError_t launch_wgrad_lines(const WgradArgs& a, dim3 grid, hipStream_t st);
 // which kernel VAR_AUTO stands for: true = wgrad_lines_kernel

@@ -733,7 +733,12 @@ def test_every_kernel_variant_is_exact():
               (3, 64, 14, 14, 128, 3, 3, (1, 1), (1, 1), 1), (2, 128, 17, 17, 192, 1, 7, (1, 1), (0, 3), 1),
               (2, 64, 17, 17, 64, 7, 1, (1, 1), (3, 0), 1), (5, 64, 9, 11, 64, 3, 3, (1, 1), (0, 0), 1),
               (2, 64, 8, 8, 64, 2, 2, (1, 1), (1, 1), 1), (3, 192, 6, 7, 64, 3, 5, (1, 1), (1, 0), 1),
-              (40, 64, 5, 5, 64, 3, 3, (1, 1), (1, 1), 1)]        # column tiles that span many small images
+              (40, 64, 5, 5, 64, 3, 3, (1, 1), (1, 1), 1),        # column tiles that span many small images
+              # backward-weight on image lines: ragged channel tiles, padding beyond the taps' reach, 7 taps
+              # along H on few lines, 1x1 on 128 x 128 tiles with ragged edges
+              (2, 40, 9, 13, 72, 3, 3, (1, 1), (1, 1), 1), (2, 64, 8, 8, 64, 3, 3, (1, 1), (2, 2), 1),
+              (2, 48, 6, 20, 80, 7, 1, (1, 1), (3, 0), 1), (3, 130, 10, 6, 200, 1, 1, (1, 1), (0, 0), 1),
+              (1, 256, 3, 37, 130, 1, 7, (1, 1), (0, 3), 1)]
     one = dev(np.array([1.0], np.float32))
     seen = set()
     for shape in shapes:
@@ -773,7 +778,8 @@ def test_every_kernel_variant_is_exact():
     # every variant ran at least once in each pass it exists for
     for v in (B.VARIANT_BAND, B.VARIANT_TILE, B.VARIANT_TILE_SPLIT, B.VARIANT_WIDE128, B.VARIANT_WIDE256):
         assert ("fwd", v) in seen and ("bwd_data", v) in seen, B.VARIANT_NAMES[v]
-    assert ("bwd_weight", B.VARIANT_WGRAD_FEWER) in seen and ("bwd_weight", B.VARIANT_WGRAD_MORE) in seen
+    for v in (B.VARIANT_WGRAD_FEWER, B.VARIANT_WGRAD_MORE, B.VARIANT_WGRAD_IMAGES, B.VARIANT_WGRAD_LINES):
+        assert ("bwd_weight", v) in seen, B.VARIANT_NAMES[v]
 
 
 def test_tuned_kernels_write_the_same_tensors():
