@@ -577,31 +577,35 @@ hipError_t launch_wgrad(const WgradArgs& a_in, hipStream_t st) {
 #undef LAUNCH
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    // Shape of the reducing blocks: the most taps (9, 7 or 3 where they divide R*S) and channels (64 or 16) per
-    // block that still give the chip 1024 blocks -- few fat blocks leave compute units idle and the loads of a
-    // small layer are latency, not bandwidth; one tap x 16 channels if nothing does.
+    // Shape of the reducing blocks: the most taps (9, 7 or 3 where they divide R*S) and channels (256, 64 or
+    // 16) per block that still give the chip 1024 blocks -- few fat blocks leave compute units idle and the
+    // loads of a small layer are latency, not bandwidth; one tap x 16 channels if nothing does.  A block's
+    // threads are (channels / 4) x (split lanes): 256 channels leave 4 split lanes, which is what few splits
+    // can keep busy.
     const int RS = a.R * a.S;
-    int rsc = 1;
-    bool wide = false;
+    int rsc = 1, qn = 4;
     {
         const int cand[3] = {9, 7, 3};
+        const int qns[3] = {64, 16, 4};
         bool found = false;
-        for (int w = 1; w >= 0 && !found; --w) {
-            if (w && a.Cp % 64 != 0) continue;
+        for (int w = 0; w < 3 && !found; ++w) {
+            if (a.Cp % (4 * qns[w]) != 0) continue;
+            if (qns[w] == 64 && a.splits > 6) continue;
             for (int i = 0; i < 4 && !found; ++i) {
                 const int r = i < 3 ? cand[i] : 1;
                 if (RS % r != 0) continue;
-                if ((long long)a.K * (a.Cp / (w ? 64 : 16)) * (RS / r) >= 1024) { rsc = r; wide = w != 0; found = true; }
+                if ((long long)a.K * (a.Cp / (4 * qns[w])) * (RS / r) >= 1024) { rsc = r; qn = qns[w]; found = true; }
             }
         }
     }
-    const unsigned rblocks = (unsigned)(a.K * (a.Cp / (wide ? 64 : 16)) * (RS / rsc));
+    const unsigned rblocks = (unsigned)(a.K * (a.Cp / (4 * qn)) * (RS / rsc));
     {
         KernelTimer kt(KID_WGRAD_REDUCE, st);
-#define REDUCE(RSCv)                                                                                      \
-    do {                                                                                                  \
-        if (wide) launch_timed(kt, (wgrad_reduce_kernel<16, RSCv>), dim3(rblocks), dim3(256), 0, st, a); \
-        else launch_timed(kt, (wgrad_reduce_kernel<4, RSCv>), dim3(rblocks), dim3(256), 0, st, a);       \
+#define REDUCE(RSCv)                                                                                         \
+    do {                                                                                                     \
+        if (qn == 64) launch_timed(kt, (wgrad_reduce_kernel<64, RSCv>), dim3(rblocks), dim3(256), 0, st, a); \
+        else if (qn == 16) launch_timed(kt, (wgrad_reduce_kernel<16, RSCv>), dim3(rblocks), dim3(256), 0, st, a); \
+        else launch_timed(kt, (wgrad_reduce_kernel<4, RSCv>), dim3(rblocks), dim3(256), 0, st, a);          \
     } while (0)
         if (rsc == 9) REDUCE(9);
         else if (rsc == 7) REDUCE(7);
