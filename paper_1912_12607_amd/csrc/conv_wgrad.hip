@@ -314,11 +314,12 @@ __global__ __launch_bounds__(256, 2) void wgrad_kernel(const WgradArgs a) {
 // splits z = lane, lane + 256/QN, ... of its quad at each tap (independent 16-byte loads, RSC of them in flight
 // per split), the lanes are combined through LDS, and the sums leave in the order of the result tensor -- with
 // all taps of a filter in the block (RSC = R*S) that is one contiguous run of 4*QN*RSC floats.  LDS holds
-// [split lane][channel][tap] with a lane pitch that is 1 mod 4 words: the stores of a wave (channel quads 4*RSC
-// words apart, lanes one pitch apart) and the final reads (consecutive words) both spread over the banks.
+// [split lane][channel quad][channel][tap] with an odd quad pitch of 4*RSC + 1 words: the stores of a wave
+// (one word per quad at a time) then land in different banks for any RSC, and the final reads walk
+// consecutive words with one word skipped per quad.
 template <int QN, int RSC>
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const WgradArgs a) {
-    constexpr int ZL = 256 / QN, CB = 4 * QN, PITCH = CB * RSC + 1;
+    constexpr int ZL = 256 / QN, CB = 4 * QN, QP = 4 * RSC + 1, PITCH = QN * QP;
     __shared__ int sred[ZL * PITCH];
     const int RS = a.R * a.S;
     const int ncolsp = RS * a.Cp;
@@ -355,7 +356,7 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const WgradArgs a) {
             s4[j].x += v.x; s4[j].y += v.y; s4[j].z += v.z; s4[j].w += v.w;
         }
     }
-    int* __restrict__ mine = sred + zl * PITCH + 4 * quad * RSC;
+    int* __restrict__ mine = sred + zl * PITCH + quad * QP;
 #pragma unroll
     for (int j = 0; j < RSC; ++j) {
         mine[j] = s4[j].x;
@@ -367,9 +368,9 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const WgradArgs a) {
     const int nz = a.splits < ZL ? a.splits : ZL;
     const float scale = __fmul_rn(a.sa[0], a.sb[0]);
     for (int t = threadIdx.x; t < CB * RSC; t += 256) {
-        int sum = 0;
-        for (int z = 0; z < nz; ++z) sum += sred[z * PITCH + t];
         const int cl = t / RSC;
+        int sum = 0;
+        for (int z = 0; z < nz; ++z) sum += sred[z * PITCH + t + (cl >> 2)];
         const int c = ct * CB + cl, rs = rg * RSC + (t - cl * RSC);
         if (c >= a.C) continue;
         size_t o = ((size_t)k * a.C + c) * RS + rs;
@@ -453,12 +454,13 @@ void wgrad_plan(WgradArgs* a) {
     a->TB = p.TB; a->CS = p.CS; a->BP = p.BP; a->BQ = p.BQ; a->ntp = p.ntp; a->ntq = p.ntq;
     a->ngrp = p.ngrp; a->chunks = p.chunks; a->splits = p.splits;
     a->ktiles = p.ktiles; a->ctiles = p.ctiles; a->tapgroups = p.tapgroups;
-    a->xt_slots = p.xt_slots; a->lds_bytes = p.lds_bytes; a->lines = p.lines;
+    a->xt_slots = p.xt_slots; a->lds_bytes = p.lds_bytes; a->lines = p.lines; a->xgk = p.xgk; a->xgc = p.xgc;
 }
 
 namespace {
 void wgrad_plan_uncached(WgradArgs* a) {
     a->lines = 0;
+    a->xgk = a->xgc = 0;
     if (a->variant == VAR_WGRAD_LINES || (a->variant != VAR_WGRAD_IMAGES && wgrad_auto_lines(*a))) {
         wgrad_plan_lines(a);
         return;
@@ -564,7 +566,7 @@ hipError_t launch_wgrad(const WgradArgs& a_in, hipStream_t st) {
         launch_timed(kt, (wgrad_kernel<TBv, CSv>), grid, dim3(256), a.lds_bytes, st, a);                \
     } while (0)
     if (a.lines) {
-        hipError_t el = launch_wgrad_lines(a, grid, st);
+        hipError_t el = launch_wgrad_lines(a, st);
         if (el != hipSuccess) return el;
     } else {
         KernelTimer kt(KID_WGRAD, st);

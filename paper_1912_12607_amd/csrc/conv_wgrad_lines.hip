@@ -52,22 +52,42 @@ __global__ __launch_bounds__(256, 2) void wgrad_lines_kernel(const WgradArgs a) 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int mt = wave & 1, ch = wave >> 1, half = lane >> 5, l32 = lane & 31;
 
-    // output tile and reduction share of this block: as in wgrad_kernel (shares of one XCD are neighbours)
+    // Output tile and reduction share of this block.  Workgroup b runs on XCD b % 8, and the blocks of an
+    // XCD should read as few different slices of the two tensors as possible, since each XCD fills its own
+    // L2.  With many output tiles (a.xgk > 0) an XCD owns a patch of the (filter tile, channel tile) grid
+    // -- xgk x xgc patches, all tap groups and shares of a patch on its XCD: a block reads one filter slice
+    // of the gradient and one channel slice of the input, so a patch of pk x pc tiles reads pk + pc slices
+    // instead of one pair per tile.  With few tiles and many shares, as in wgrad_kernel: the tiles of one
+    // share on one XCD.
     const int out_tiles = a.ktiles * a.ctiles * a.tapgroups;
-    int zshare, ot;
-    if (wgrad_xcd_mapping(a.splits)) {
-        const int wg_i = blockIdx.x >> 3;
-        zshare = ((wg_i / out_tiles) << 3) + (int)(blockIdx.x & 7);
-        if (zshare >= a.splits) return;
-        ot = wg_i % out_tiles;
+    int zshare, tg, ct, kt;
+    if (a.xgk > 0) {
+        const int xcd = (int)(blockIdx.x & 7), i = (int)(blockIdx.x >> 3);
+        const int pk = (a.ktiles + a.xgk - 1) / a.xgk, pc = (a.ctiles + a.xgc - 1) / a.xgc;
+        const int per_share = pk * pc * a.tapgroups;
+        zshare = i / per_share;
+        int l = i - zshare * per_share;
+        tg = l % a.tapgroups;
+        l /= a.tapgroups;
+        ct = (xcd % a.xgc) * pc + l % pc;
+        kt = (xcd / a.xgc) * pk + l / pc;
+        if (kt >= a.ktiles || ct >= a.ctiles) return;
     } else {
-        zshare = blockIdx.x / out_tiles;
-        ot = blockIdx.x - zshare * out_tiles;
+        int ot;
+        if (wgrad_xcd_mapping(a.splits)) {
+            const int wg_i = blockIdx.x >> 3;
+            zshare = ((wg_i / out_tiles) << 3) + (int)(blockIdx.x & 7);
+            if (zshare >= a.splits) return;
+            ot = wg_i % out_tiles;
+        } else {
+            zshare = blockIdx.x / out_tiles;
+            ot = blockIdx.x - zshare * out_tiles;
+        }
+        tg = ot % a.tapgroups;
+        ot /= a.tapgroups;
+        ct = ot % a.ctiles;
+        kt = ot / a.ctiles;
     }
-    const int tg = ot % a.tapgroups;
-    ot /= a.tapgroups;
-    const int ct = ot % a.ctiles;
-    const int kt = ot / a.ctiles;
 
     // Lines and positions.  along_w: a line is an image row, positions run along W, the block owns tap
     // row tg; otherwise (R x 1 filters) a line is an image column and positions run along H.
@@ -300,9 +320,30 @@ void wgrad_plan_lines(WgradArgs* a) {
     if (a->variant == VAR_WGRAD_FEWER) splits = splits > 1 ? splits / 2 : 1;
     if (a->variant == VAR_WGRAD_MORE) splits = (2 * splits <= a->chunks && 2 * splits <= 4096) ? 2 * splits : splits;
     a->splits = splits;
+    // XCD patches (see the kernel): the split of 8 into xgk x xgc whose patches read the fewest slices
+    a->xgk = a->xgc = 0;
+    if (a->ktiles * a->ctiles >= 16) {
+        int best = 1 << 30;
+        for (int gk = 1; gk <= 8; gk *= 2) {
+            const int gc = 8 / gk;
+            if (gk > a->ktiles || gc > a->ctiles) continue;
+            const int cost = (a->ktiles + gk - 1) / gk + (a->ctiles + gc - 1) / gc;
+            if (cost < best) { best = cost; a->xgk = gk; a->xgc = gc; }
+        }
+    }
 }
 
-hipError_t launch_wgrad_lines(const WgradArgs& a, dim3 grid, hipStream_t st) {
+unsigned wgrad_lines_grid(const WgradArgs& a) {
+    const unsigned out_tiles = (unsigned)(a.ktiles * a.ctiles * a.tapgroups);
+    if (a.xgk > 0) {
+        const unsigned pk = (unsigned)((a.ktiles + a.xgk - 1) / a.xgk), pc = (unsigned)((a.ctiles + a.xgc - 1) / a.xgc);
+        return 8u * pk * pc * (unsigned)a.tapgroups * (unsigned)a.splits;
+    }
+    return wgrad_xcd_mapping(a.splits) ? out_tiles * 8u * (unsigned)((a.splits + 7) / 8) : out_tiles * (unsigned)a.splits;
+}
+
+hipError_t launch_wgrad_lines(const WgradArgs& a, hipStream_t st) {
+    const dim3 grid(wgrad_lines_grid(a));
     KernelTimer kt(KID_WGRAD_LINES, st);
 #define LAUNCH(STv, WTv, GPv)                                                                            \
     do {                                                                                                 \

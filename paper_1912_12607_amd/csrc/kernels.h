@@ -216,6 +216,7 @@ struct WgradArgs {
     int8_t* xs;                  // scratch: the input codes in space-to-depth form, [N][H][W][16]
     int variant;                 // VAR_AUTO or a VAR_WGRAD_*: set before wgrad_plan()
     int lines;                   // filled by wgrad_plan(): 1 = wgrad_lines_kernel runs (TB = taps along the line)
+    int xgk, xgc;                // ... and its patches of output tiles per XCD: xgk x xgc = 8, or 0 0: tiles dealt by share
 };
 // Rewrites the geometry into the space-to-depth form (s2d.hip) when it applies.  Returns the bytes of
 // the rewritten input codes (0: does not apply, the geometry is left alone).  Call before wgrad_plan().
@@ -227,7 +228,7 @@ bool wgrad_lines_applies(const WgradArgs& a);    // geometry as wgrad_plan() tak
 // lines are image rows and the taps of a block run along W (else: columns, along H)
 __host__ __device__ inline bool wgrad_lines_along_w(int R, int S) { return S > 1 || R == 1; }
 void wgrad_plan_lines(WgradArgs* a);
-hipError_t launch_wgrad_lines(const WgradArgs& a, dim3 grid, hipStream_t st);
+hipError_t launch_wgrad_lines(const WgradArgs& a, hipStream_t st);
 // which kernel VAR_AUTO stands for: true = wgrad_lines_kernel
 bool wgrad_auto_lines(const WgradArgs& a);
 // reduction shares of one XCD are given neighbouring workgroups when there are enough of them
