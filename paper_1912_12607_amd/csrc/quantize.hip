@@ -467,15 +467,22 @@ static int quant_wgt_zsplit(int K, int Cg, int R, int S);
 // Channel tiles per block.  A filter's share of a block is one contiguous run of 16 * taps floats;
 // with one to three taps that is 64 to 192 bytes, a fraction of what a wave-wide load can fetch, and
 // a fully connected layer's 2 M weights would be 8000 blocks of 256 elements (44 us).  Few-tap
-// filters therefore take 64 or 32 channels per block.
-__host__ __device__ inline int quant_wgt_cm(int Cg, int R, int S) {
+// filters therefore take 64 or 32 channels per block.  So do filters of up to 16 taps when the tensor is
+// large enough to leave 512 blocks: the forward view's granules of a (filter, tap) are then written 64 or 32
+// bytes at a time instead of 16 (768 x 768 x 7 weights beside the activations of their layer: 33.0 -> 29.1 us).
+__host__ __device__ inline int quant_wgt_cm(int K, int Cg, int R, int S) {
     const int RS = R * S;
     int cm = RS == 1 ? 4 : RS <= 3 ? 2 : 1;
+    if (RS > 3 && RS <= 16) {
+        const long long ktiles = (K + QW_T - 1) / QW_T;
+        if (ktiles * ((Cg + 4 * QW_T - 1) / (4 * QW_T)) >= 512) cm = 4;
+        else if (ktiles * ((Cg + 2 * QW_T - 1) / (2 * QW_T)) >= 512) cm = 2;
+    }
     while (cm > 1 && Cg <= QW_T * (cm / 2)) cm /= 2;      // no wider than the tensor
     return cm;
 }
-static int quant_wgt_gx(int Cg, int R, int S) {
-    const int ct = QW_T * quant_wgt_cm(Cg, R, S);
+static int quant_wgt_gx(int K, int Cg, int R, int S) {
+    const int ct = QW_T * quant_wgt_cm(K, Cg, R, S);
     return (Cg + ct - 1) / ct;
 }
 
@@ -496,7 +503,7 @@ __device__ __forceinline__ void quantize_wgt_body(
     if (vb.x == 0 && vb.y == 0 && vb.z == 0 && threadIdx.x == 0) *scale_out = sc;
 
     const int RS = R * S;
-    const int CM = quant_wgt_cm(Cg, R, S), CT = QW_T * CM;      // channels per block
+    const int CM = quant_wgt_cm(K, Cg, R, S), CT = QW_T * CM;      // channels per block
     const int k0 = vb.y * QW_T, c0 = vb.x * CT;
     double A = 0.0, G = 0.0;
     unsigned long long B = 0;
@@ -516,19 +523,31 @@ __device__ __forceinline__ void quantize_wgt_body(
             for (int kk = 0; kk < 4; ++kk) {
                 const int k_l = wave * 4 + kk, k = k0 + k_l;
                 const size_t base = ((size_t)k * Cg + c0) * RS;
-                for (int rem = lane; rem < per_k; rem += 64) {
-                    int code = 0;
-                    if (k < K && rem < cvalid * RS) {
-                        const float g32 = w[base + rem];
-                        code = quantize_one<STOCH>(g32, inv, seed_lo, seed_hi_mul, (uint32_t)(base + rem));
-                        if (DEV) {
-                            const double g = (double)g32;
-                            A = fma(g, (double)code, A);
-                            G = fma(g, g, G);
-                            B += (unsigned)(code * code);
-                        }
+                // long runs: four loads in flight per lane; short ones (up to 256 floats): one trip each
+                const int step4 = per_k > 256 ? 4 : 1;
+                for (int rem0 = lane; rem0 < per_k; rem0 += 64 * step4) {
+                    float g32[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int rem = rem0 + 64 * u;
+                        g32[u] = (u < step4 && k < K && rem < cvalid * RS) ? w[base + rem] : 0.0f;
                     }
-                    tile[k_l * per_k + rem] = (int8_t)code;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int rem = rem0 + 64 * u;
+                        if (u >= step4 || rem >= per_k) break;
+                        int code = 0;
+                        if (k < K && rem < cvalid * RS) {
+                            code = quantize_one<STOCH>(g32[u], inv, seed_lo, seed_hi_mul, (uint32_t)(base + rem));
+                            if (DEV) {
+                                const double g = (double)g32[u];
+                                A = fma(g, (double)code, A);
+                                G = fma(g, g, G);
+                                B += (unsigned)(code * code);
+                            }
+                        }
+                        tile[k_l * per_k + rem] = (int8_t)code;
+                    }
                 }
             }
         } else {
@@ -653,7 +672,7 @@ void quant_grid(int kind, const int d[4], int* gx, int* gy, int* gz) {
         const int HW = d[2] * d[3], Cp = (d[1] + 15) & ~15;
         *gx = quant_act_gx(Cp, HW); *gy = (Cp + QA_CH - 1) / QA_CH; *gz = d[0];
     } else if (kind == 1) {
-        *gx = quant_wgt_gx(d[1], d[2], d[3]); *gy = (d[0] + QW_T - 1) / QW_T; *gz = quant_wgt_zsplit(d[0], d[1], d[2], d[3]);
+        *gx = quant_wgt_gx(d[0], d[1], d[2], d[3]); *gy = (d[0] + QW_T - 1) / QW_T; *gz = quant_wgt_zsplit(d[0], d[1], d[2], d[3]);
     } else {
         *gx = quant_blocks_planar((size_t)d[0] * d[1] * d[2] * d[3]); *gy = 1; *gz = 1;
     }
@@ -668,7 +687,7 @@ hipError_t launch_quantize_batch(const QuantBatch& b, int total_blocks, hipStrea
             need = sizeof(uint32_t) * QA_PIX * (QA_CH / 4 + 1);
         } else if (t.kind == 1) {
             const int tpb = (t.d2 * t.d3 + t.gz - 1) / t.gz;          // taps per block along z
-            need = (size_t)QW_T * QW_T * quant_wgt_cm(t.d1, t.d2, t.d3) * (tpb < QW_TAPS ? tpb : QW_TAPS);
+            need = (size_t)QW_T * QW_T * quant_wgt_cm(t.d0, t.d1, t.d2, t.d3) * (tpb < QW_TAPS ? tpb : QW_TAPS);
         }
         if (need > lds) lds = need;
     }
@@ -683,20 +702,20 @@ hipError_t launch_quantize_batch(const QuantBatch& b, int total_blocks, hipStrea
 
 // blocks along the taps: 1 for tensors with many 16 x 16 tiles, up to R*S for small ones
 static int quant_wgt_zsplit(int K, int Cg, int R, int S) {
-    const int tiles = ((K + QW_T - 1) / QW_T) * quant_wgt_gx(Cg, R, S);
+    const int tiles = ((K + QW_T - 1) / QW_T) * quant_wgt_gx(K, Cg, R, S);
     int z = (256 + tiles - 1) / tiles;
     if (z > R * S) z = R * S;
     return z < 1 ? 1 : z;
 }
 int quant_blocks_wgt(int K, int Cg, int R, int S) {
-    return ((K + QW_T - 1) / QW_T) * quant_wgt_gx(Cg, R, S) * quant_wgt_zsplit(K, Cg, R, S);
+    return ((K + QW_T - 1) / QW_T) * quant_wgt_gx(K, Cg, R, S) * quant_wgt_zsplit(K, Cg, R, S);
 }
 
 hipError_t launch_quantize_wgt(const QuantArgs& a, hipStream_t st) {
     const int K = a.d0, Cg = a.d1, R = a.d2, S = a.d3;
     const int Cp = (Cg + 15) & ~15, Kp = (K + 15) & ~15;
     const size_t off2 = (((size_t)K * R * S * Cp) + 255) & ~(size_t)255;
-    const dim3 grid(quant_wgt_gx(Cg, R, S), (K + QW_T - 1) / QW_T, quant_wgt_zsplit(K, Cg, R, S));
+    const dim3 grid(quant_wgt_gx(K, Cg, R, S), (K + QW_T - 1) / QW_T, quant_wgt_zsplit(K, Cg, R, S));
     const uint32_t slo = seed_key_x(a.seed), shi = seed_key_a(a.seed);
     KernelTimer kt(KID_QUANTIZE_WGT, st);
 #define LAUNCH(ST, DV)                                                                              \
