@@ -25,6 +25,7 @@ inline hipError_t raise_dynamic_lds(const void* fn, int bytes, std::atomic<unsig
 
 
 constexpr int kMaxPartials = 1024;   // per-block partial results of an absmax pass
+constexpr int kAbsmaxPartials = 256;  // ... of which an absmax pass writes at most this many (its block count)
 
 // Partial sums of Eq.6 left by one block: A = sum g*q, G = sum g^2, B = sum q^2.
 struct DevPartial {

@@ -23,14 +23,19 @@ struct VBlock {
     int gx, gy, gz;    // grid extents
 };
 
+constexpr int AM_THREADS = 1024;      // 16 waves per block
+constexpr int AM_MAX_BLOCKS = kAbsmaxPartials;    // the partials of a pass
+
 template <bool SUMSQ>
 __device__ __forceinline__ void absmax_body(const float* __restrict__ x, size_t n, float* __restrict__ part,
                                             double* __restrict__ sumsq, unsigned long long* __restrict__ zero,
                                             int nzero, const int bx, const int gx) {
-    __shared__ float lds4[4];
-    __shared__ double ldsd[4];
+    // AM_THREADS threads per block: few, fat blocks leave few partials, and every block of the passes that
+    // consume them reads all of them (a quantize pass of 3840 blocks spent 5 of its 21 us on 1024 partials)
+    __shared__ float ldsm[AM_THREADS / 64];
+    __shared__ double ldsd[AM_THREADS / 64];
     if (SUMSQ) {
-        for (int z = bx * 256 + threadIdx.x; z < nzero; z += gx * 256) zero[z] = 0ull;
+        for (int z = bx * AM_THREADS + threadIdx.x; z < nzero; z += gx * AM_THREADS) zero[z] = 0ull;
     }
     const size_t n4 = n >> 2;
     const float4* __restrict__ x4 = reinterpret_cast<const float4*>(x);
@@ -45,8 +50,8 @@ __device__ __forceinline__ void absmax_body(const float* __restrict__ x, size_t 
             q[3] = fma((double)a.w, (double)a.w, q[3]);
         }
     };
-    const size_t stride = (size_t)gx * 256;
-    size_t i = (size_t)bx * 256 + threadIdx.x;
+    const size_t stride = (size_t)gx * AM_THREADS;
+    size_t i = (size_t)bx * AM_THREADS + threadIdx.x;
     // four independent 16-byte loads in flight per thread
     for (; i + 3 * stride < n4; i += 4 * stride) {
         float4 a = x4[i], b = x4[i + stride], c = x4[i + 2 * stride], d = x4[i + 3 * stride];
@@ -61,25 +66,36 @@ __device__ __forceinline__ void absmax_body(const float* __restrict__ x, size_t 
         m = fmaxf(m, fabsf(v));
         if (SUMSQ) q[0] = fma((double)v, (double)v, q[0]);
     }
-    m = block_max_256(m, lds4);
-    if (threadIdx.x == 0) part[bx] = m;
-    if (SUMSQ) {
-        const double t = wave_sum((q[0] + q[1]) + (q[2] + q[3]));
-        if ((threadIdx.x & 63) == 0) ldsd[threadIdx.x >> 6] = t;
-        __syncthreads();
-        if (threadIdx.x == 0) sumsq[bx] = (ldsd[0] + ldsd[1]) + (ldsd[2] + ldsd[3]);
+    m = wave_max(m);
+    double t = 0.0;
+    if (SUMSQ) t = wave_sum((q[0] + q[1]) + (q[2] + q[3]));
+    if ((threadIdx.x & 63) == 0) {
+        ldsm[threadIdx.x >> 6] = m;
+        if (SUMSQ) ldsd[threadIdx.x >> 6] = t;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float mm = 0.0f;
+        double ss = 0.0;
+#pragma unroll
+        for (int w = 0; w < AM_THREADS / 64; ++w) {      // fixed order: the sum does not depend on timing
+            mm = fmaxf(mm, ldsm[w]);
+            if (SUMSQ) ss += ldsd[w];
+        }
+        part[bx] = mm;
+        if (SUMSQ) sumsq[bx] = ss;
     }
 }
 
 template <bool SUMSQ>
-__global__ __launch_bounds__(256) void absmax_kernel(const float* __restrict__ x, size_t n,
+__global__ __launch_bounds__(AM_THREADS) void absmax_kernel(const float* __restrict__ x, size_t n,
                                                      float* __restrict__ part, double* __restrict__ sumsq,
                                                      unsigned long long* __restrict__ zero, int nzero) {
     absmax_body<SUMSQ>(x, n, part, sumsq, zero, nzero, (int)blockIdx.x, (int)gridDim.x);
 }
 
 // several tensors in one launch: block b serves the tensor whose block range holds it
-__global__ __launch_bounds__(256) void absmax_batch_kernel(const AbsmaxBatch b) {
+__global__ __launch_bounds__(AM_THREADS) void absmax_batch_kernel(const AbsmaxBatch b) {
     int i = 0;
     while (i + 1 < b.count && (int)blockIdx.x >= b.it[i].block0 + b.it[i].nblocks) ++i;
     const AbsmaxBatchItem& t = b.it[i];
@@ -87,13 +103,13 @@ __global__ __launch_bounds__(256) void absmax_batch_kernel(const AbsmaxBatch b) 
 }
 
 int absmax_blocks(size_t n) {
-    size_t want = (n / 4 + 256 * 8 - 1) / (256 * 8);   // >= 8 float4 per thread before adding blocks
-    return (int)(want < 1 ? 1 : (want > (size_t)kMaxPartials ? (size_t)kMaxPartials : want));
+    size_t want = (n / 4 + AM_THREADS * 8 - 1) / (AM_THREADS * 8);   // >= 8 float4 per thread before adding blocks
+    return (int)(want < 1 ? 1 : (want > (size_t)AM_MAX_BLOCKS ? (size_t)AM_MAX_BLOCKS : want));
 }
 
 hipError_t launch_absmax_batch(const AbsmaxBatch& b, int total_blocks, hipStream_t st) {
     KernelTimer kt(KID_ABSMAX_BATCH, st);
-    launch_timed(kt, absmax_batch_kernel, dim3(total_blocks), dim3(256), 0, st, b);
+    launch_timed(kt, absmax_batch_kernel, dim3(total_blocks), dim3(AM_THREADS), 0, st, b);
     return hipGetLastError();
 }
 
@@ -102,8 +118,8 @@ hipError_t launch_absmax(const float* x, size_t n, float* part, int* nparts, hip
     const int blocks = absmax_blocks(n);
     *nparts = blocks;
     KernelTimer kt(KID_ABSMAX, st);
-    if (sumsq) launch_timed(kt, absmax_kernel<true>, dim3(blocks), dim3(256), 0, st, x, n, part, sumsq, zero, nzero);
-    else launch_timed(kt, absmax_kernel<false>, dim3(blocks), dim3(256), 0, st, x, n, part, sumsq, zero, 0);
+    if (sumsq) launch_timed(kt, absmax_kernel<true>, dim3(blocks), dim3(AM_THREADS), 0, st, x, n, part, sumsq, zero, nzero);
+    else launch_timed(kt, absmax_kernel<false>, dim3(blocks), dim3(AM_THREADS), 0, st, x, n, part, sumsq, zero, 0);
     return hipGetLastError();
 }
 
@@ -181,10 +197,13 @@ __device__ __forceinline__ void quantize_act_body(
     if (Cp == 16) {
         const int p = vb.x * QA_NARROW_PIX + (int)threadIdx.x;
         const bool pv = p < HW;
+        const float clip_in = clip ? *clip : 0.0f;
+        if (!clip) absmax_partials_begin(absmax_part, nparts, lds4);      // dealt with ahead of the pixels
         float v[16];
 #pragma unroll
         for (int c = 0; c < 16; ++c) v[c] = (pv && c < C) ? x[((size_t)n * C + c) * HW + p] : 0.0f;
-        const float cval = resolve_clip(clip, absmax_part, nparts, lds4);
+        float cval = clip_in;
+        if (!clip) cval = absmax_partials_end(lds4);
         float inv = inv_scale_of(cval);
         float sc = scale_of(cval);
         if (STOCH) {
@@ -219,6 +238,9 @@ __device__ __forceinline__ void quantize_act_body(
         return;
     }
     const int c0 = vb.y * QA_CH;
+    // the clip value: handed in (read now, a scalar load), or the absmax partials, dealt with ahead of the tile
+    const float clip_in = clip ? *clip : 0.0f;
+    if (!clip) absmax_partials_begin(absmax_part, nparts, lds4);
     const int nsub = quant_act_nsub(HW);
     const int lane = threadIdx.x & 63;
     const int wv = threadIdx.x >> 6;
@@ -235,26 +257,44 @@ __device__ __forceinline__ void quantize_act_body(
         // issue every global load of this thread before anything depends on them
         float v[4][4];
         if (VEC) {
+            // unconditional loads (lanes outside the tensor re-read its first floats and are zeroed afterwards):
+            // with a branch around each load the compiler has been seen to wait for one load before issuing the next
+            float4 f[4];
+            bool ok[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int c = c0 + 4 * cgp + j;
-                float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (p0 + 4 * pq < HW && c < C) f = *reinterpret_cast<const float4*>(x + ((size_t)n * C + c) * HW + p0 + 4 * pq);
-                v[j][0] = f.x; v[j][1] = f.y; v[j][2] = f.z; v[j][3] = f.w;     // v[channel][pixel]
+                ok[j] = p0 + 4 * pq < HW && c < C;
+                f[j] = *reinterpret_cast<const float4*>(x + (ok[j] ? ((size_t)n * C + c) * HW + p0 + 4 * pq : (size_t)0));
+            }
+            const bool whole = p0 + QA_PIX <= HW && c0 + QA_CH <= C;      // (uniform) nothing to zero in this tile
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (!whole && !ok[j]) f[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+                v[j][0] = f[j].x; v[j][1] = f[j].y; v[j][2] = f[j].z; v[j][3] = f[j].w;     // v[channel][pixel]
             }
         } else {
+            const bool whole = p0 + QA_PIX <= HW && c0 + QA_CH <= C;      // (uniform) nothing to zero in this tile
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int c = c0 + 4 * (wv + 4 * i) + j;
-                    v[i][j] = (pv && c < C) ? x[((size_t)n * C + c) * HW + p] : 0.0f;
+                    v[i][j] = x[(pv && c < C) ? ((size_t)n * C + c) * HW + p : (size_t)0];      // unconditional, as above
                 }
+            }
+            if (!whole) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (!(pv && c0 + 4 * (wv + 4 * i) + j < C)) v[i][j] = 0.0f;
             }
         }
 
         if (sub == 0) {
-            const float cval = resolve_clip(clip, absmax_part, nparts, lds4);
+            float cval = clip_in;
+            if (!clip) cval = absmax_partials_end(lds4);
             inv = inv_scale_of(cval);
             sc = scale_of(cval);
             if (STOCH) {
