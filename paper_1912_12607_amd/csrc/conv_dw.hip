@@ -113,6 +113,38 @@ __device__ __forceinline__ void dw_fill_plane(const int8_t* __restrict__ src, in
     }
 }
 
+// dw_fill_plane() in two halves for planes of a whole number of 16-byte chunks, at most CPT per thread:
+// the chunks of a thread fetched into registers, and written to LDS later -- so that the next image's
+// planes can be on their way while the current one is being worked on.
+template <int NT, int CPT>
+__device__ __forceinline__ void dw_plane_fetch(const int8_t* __restrict__ src, int IHW, uint4 (&regs)[CPT]) {
+#pragma unroll
+    for (int u = 0; u < CPT; ++u) {
+        const int i = (int)threadIdx.x + u * NT;
+        regs[u] = reinterpret_cast<const uint4*>(src)[i < (IHW >> 4) ? i : 0];     // (unconditional; the surplus is not stored)
+    }
+}
+template <int NT, int CPT>
+__device__ __forceinline__ void dw_plane_store(const uint4 (&regs)[CPT], int IHW, int IW, int8_t* dst, int pitch, int top,
+                                               int left) {
+#pragma unroll
+    for (int u = 0; u < CPT; ++u) {
+        const int i = (int)threadIdx.x + u * NT;
+        if (i < (IHW >> 4)) {
+            const uint32_t d[4] = {regs[u].x, regs[u].y, regs[u].z, regs[u].w};
+            int row = (16 * i) / IW, col = 16 * i - row * IW;
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                dst[(row + top) * pitch + col + left] = (int8_t)(d[k >> 2] >> (8 * (k & 3)));
+                if (++col == IW) {
+                    col = 0;
+                    ++row;
+                }
+            }
+        }
+    }
+}
+
 // Stage a plane with its zero border: `rows` x `pitch` bytes of LDS, the plane at (top, left).
 template <int NT>
 __device__ __forceinline__ void dw_stage_plane(const int8_t* __restrict__ src, int IH, int IW, int8_t* dst,
@@ -293,6 +325,26 @@ __device__ __forceinline__ void dw_block_sum_store(int v, int* red, int32_t* dst
     }
 }
 
+// The same for NV sums at once, behind ONE barrier (red: NT / 64 x NV ints of LDS that nothing else uses).
+template <int NT, int NV>
+__device__ __forceinline__ void dw_block_sums_store(int (&v)[NV], int* red, int32_t* dst) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) v[i] += __shfl_xor(v[i], o, kWave);
+    }
+    if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) red[(threadIdx.x >> 6) * NV + i] = v[i];
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < NV) {
+        int t = red[threadIdx.x];
+        for (int w = 1; w < (int)(NT >> 6); ++w) t += red[w * NV + threadIdx.x];
+        dst[threadIdx.x] = t;
+    }
+}
+
 template <int NT>
 __global__ __launch_bounds__(NT) void dw_wgrad_kernel(const DwArgs a) {
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
@@ -361,7 +413,7 @@ __global__ __launch_bounds__(NT) void dw_wgrad_kernel(const DwArgs a) {
 template <int R, int S, int NT>
 __global__ __launch_bounds__(NT) void dw_wgrad_fast_kernel(const DwArgs a, int pitch, int gpitch) {
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
-    __shared__ int red[4];
+    __shared__ int red[(NT / 64) * R * S];
     constexpr int SD = (S + 3) / 4;
     const int c = blockIdx.x, chunk = blockIdx.y;
     const int IHW = a.IH * a.IW, OHW = a.OH * a.OW;
@@ -381,13 +433,32 @@ __global__ __launch_bounds__(NT) void dw_wgrad_fast_kernel(const DwArgs a, int p
 #pragma unroll
         for (int sx = 0; sx < S; ++sx) acc[r][sx] = 0;
     const int QW = (a.OW + 3) >> 2;
+    // Planes of whole 16-byte chunks, at most 256 of them (DW_PF per thread): the next image's two planes are fetched
+    // into registers while this image's dot products run (a block otherwise waits out a round trip to memory
+    // per image: 56 x 56 planes, 144 channels, batch 64: 37.8 us of which little is arithmetic).
+    constexpr int DW_PF = 256 / NT;      // planes of up to 4 KB
+    const bool pf = (IHW & 15) == 0 && (OHW & 15) == 0 && (IHW >> 4) <= DW_PF * NT && (OHW >> 4) <= DW_PF * NT;
+    uint4 px[DW_PF], pg[DW_PF];
+    if (pf && n0 < n1) {
+        dw_plane_fetch<NT, DW_PF>(a.a + ((size_t)n0 * a.C + c) * IHW, IHW, px);
+        dw_plane_fetch<NT, DW_PF>(a.b + ((size_t)n0 * a.C + c) * OHW, OHW, pg);
+    }
     for (int n = n0; n < n1; ++n) {
         const int8_t* __restrict__ xsrc = a.a + ((size_t)n * a.C + c) * IHW;
         const int8_t* __restrict__ gsrc = a.b + ((size_t)n * a.C + c) * OHW;
         __syncthreads();   // the previous image's reads (and the zero fill) are done
-        dw_fill_plane<NT>(xsrc, a.IH, a.IW, xs, pitch, a.pad_h, a.pad_w);
-        dw_fill_plane<NT>(gsrc, a.OH, a.OW, gs, gpitch, 0, 0);
+        if (pf) {
+            dw_plane_store<NT, DW_PF>(px, IHW, a.IW, xs, pitch, a.pad_h, a.pad_w);
+            dw_plane_store<NT, DW_PF>(pg, OHW, a.OW, gs, gpitch, 0, 0);
+        } else {
+            dw_fill_plane<NT>(xsrc, a.IH, a.IW, xs, pitch, a.pad_h, a.pad_w);
+            dw_fill_plane<NT>(gsrc, a.OH, a.OW, gs, gpitch, 0, 0);
+        }
         __syncthreads();
+        if (pf && n + 1 < n1) {
+            dw_plane_fetch<NT, DW_PF>(xsrc + (size_t)a.C * IHW, IHW, px);
+            dw_plane_fetch<NT, DW_PF>(gsrc + (size_t)a.C * OHW, OHW, pg);
+        }
         for (int t = threadIdx.x; t < a.OH * QW; t += NT) {
             const int p = t / QW, q = (t - p * QW) << 2;
             const int g4 = *reinterpret_cast<const int*>(gs + p * gpitch + q);
@@ -405,10 +476,12 @@ __global__ __launch_bounds__(NT) void dw_wgrad_fast_kernel(const DwArgs a, int p
             }
         }
     }
+    int flat[R * S];
 #pragma unroll
     for (int r = 0; r < R; ++r)
 #pragma unroll
-        for (int sx = 0; sx < S; ++sx) dw_block_sum_store<NT>(acc[r][sx], red, part + r * S + sx);
+        for (int sx = 0; sx < S; ++sx) flat[r * S + sx] = acc[r][sx];
+    dw_block_sums_store<NT, R * S>(flat, red, part);
 }
 
 __global__ __launch_bounds__(256) void dw_wgrad_reduce_kernel(const DwArgs a) {
