@@ -333,9 +333,11 @@ typedef enum {
     INT8T_VARIANT_WGRAD_IMAGES = 8,  /* backward-weight: operands of 16 images per pixel, transposed in registers */
     INT8T_VARIANT_WGRAD_LINES = 9,   /* backward-weight, stride 1, 3 or 7 taps along an axis: operands of 32 image lines per
                                         position through transposing LDS reads, gradient operands in a sliding window */
+    INT8T_VARIANT_WIDE_SQ128 = 10,   /* forward / backward-data: 128 x 128 tiles from a 3-stage LDS ring, three blocks per
+                                        compute unit: layers that have too few of the larger tiles to go round */
     INT8T_VARIANT_MAX_ENUM = 0x7fffffff
 } int8t_variant;
-#define INT8T_VARIANT_COUNT 10
+#define INT8T_VARIANT_COUNT 11
 /* 1 when `variant` can run pass `op` (INT8T_OP_CONV_*) of the layer, else 0 (also on a bad descriptor). */
 int int8t_conv_variant_ok(int8t_op op, const int8t_conv_desc *desc, int8t_variant variant);
 /* INT8T_ERR_ARG when the variant cannot run that pass of that layer; then nothing changes. */

@@ -410,7 +410,11 @@ __global__ __launch_bounds__(NT) void dw_wgrad_kernel(const DwArgs a) {
 // LDS (the input with its zero border, so that tap (r,s) of output column q starts at LDS column
 // q + s), a thread owns four consecutive outputs of a row and adds, per tap, one 4-way int8 dot
 // product of the four gradient codes with the four input codes they meet.
-template <int R, int S, int NT>
+// PF: the planes are whole 16-byte chunks, at most 256 of them (host: dw_wgrad_prefetch()): the next image's
+// planes are fetched into registers while this image's dot products run.  A template flag, so that the
+// other instantiations do not carry the registers (64-thread blocks on 7 x 7 planes fell from many to two
+// waves per SIMD when it was a run-time choice).
+template <int R, int S, int NT, bool PF>
 __global__ __launch_bounds__(NT) void dw_wgrad_fast_kernel(const DwArgs a, int pitch, int gpitch) {
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
     __shared__ int red[(NT / 64) * R * S];
@@ -436,8 +440,8 @@ __global__ __launch_bounds__(NT) void dw_wgrad_fast_kernel(const DwArgs a, int p
     // Planes of whole 16-byte chunks, at most 256 of them (DW_PF per thread): the next image's two planes are fetched
     // into registers while this image's dot products run (a block otherwise waits out a round trip to memory
     // per image: 56 x 56 planes, 144 channels, batch 64: 37.8 us of which little is arithmetic).
-    constexpr int DW_PF = 256 / NT;      // planes of up to 4 KB
-    const bool pf = (IHW & 15) == 0 && (OHW & 15) == 0 && (IHW >> 4) <= DW_PF * NT && (OHW >> 4) <= DW_PF * NT;
+    constexpr int DW_PF = PF ? 256 / NT : 1;      // planes of up to 4 KB
+    constexpr bool pf = PF;
     uint4 px[DW_PF], pg[DW_PF];
     if (pf && n0 < n1) {
         dw_plane_fetch<NT, DW_PF>(a.a + ((size_t)n0 * a.C + c) * IHW, IHW, px);
@@ -624,13 +628,16 @@ hipError_t launch_dw_wgrad(const DwArgs& a, hipStream_t st) {
             const size_t ldsf = (((size_t)(a.OH + a.R - 1) * pitch + 15) & ~(size_t)15) + (size_t)a.OH * gpitch;
             if (ldsf <= 60 * 1024) {
                 fast = true;
-#define WFAST(Rv)                                                                                                   \
+#define WFAST(Rv, PFv)                                                                                                \
     do {                                                                                                            \
-        if (a.threads == 64) launch_timed(kt, (dw_wgrad_fast_kernel<Rv, Rv, 64>), dim3(a.C, a.chunks), dim3(64), ldsf, st, a, pitch, gpitch);        \
-        else if (a.threads == 128) launch_timed(kt, (dw_wgrad_fast_kernel<Rv, Rv, 128>), dim3(a.C, a.chunks), dim3(128), ldsf, st, a, pitch, gpitch); \
-        else launch_timed(kt, (dw_wgrad_fast_kernel<Rv, Rv, 256>), dim3(a.C, a.chunks), dim3(256), ldsf, st, a, pitch, gpitch);                      \
+        if (a.threads == 64) launch_timed(kt, (dw_wgrad_fast_kernel<Rv, Rv, 64, PFv>), dim3(a.C, a.chunks), dim3(64), ldsf, st, a, pitch, gpitch);        \
+        else if (a.threads == 128) launch_timed(kt, (dw_wgrad_fast_kernel<Rv, Rv, 128, PFv>), dim3(a.C, a.chunks), dim3(128), ldsf, st, a, pitch, gpitch); \
+        else launch_timed(kt, (dw_wgrad_fast_kernel<Rv, Rv, 256, PFv>), dim3(a.C, a.chunks), dim3(256), ldsf, st, a, pitch, gpitch);                      \
     } while (0)
-                if (a.R == 3) WFAST(3); else WFAST(5);
+                const int ihw = a.IH * a.IW, ohw = a.OH * a.OW;
+                const bool pf = (ihw & 15) == 0 && (ohw & 15) == 0 && ihw <= 4096 && ohw <= 4096;
+                if (pf) { if (a.R == 3) WFAST(3, true); else WFAST(5, true); }
+                else { if (a.R == 3) WFAST(3, false); else WFAST(5, false); }
 #undef WFAST
             }
         }

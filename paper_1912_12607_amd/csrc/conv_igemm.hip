@@ -381,18 +381,20 @@ __global__ __launch_bounds__(256) void igemm_reduce_kernel(const IgemmArgs a, si
 // buffer descriptor: the hardware then writes zeros.
 //   <WM=2, KG=4, NSTAGE=3>: 128 x 256, 72 KB of LDS, two blocks per compute unit
 //   <WM=4, KG=8, NSTAGE=2>: 256 x 256, 128 KB of LDS, one block of eight waves per compute unit
+//   <WM=2, KG=4, NSTAGE=3, BNT=128>: 128 x 128 (waves of 64 x 64), 48 KB of LDS, three blocks per compute unit: for
+//   layers whose larger tiles would leave most compute units without one
 // ---------------------------------------------------------------------------------------------
-template <bool DGRAD, int WM, int KG, int NSTAGE, bool CLS = false, bool CELL = false>
-__global__ __launch_bounds__(128 * WM, WM == 2 ? 2 : 1) void igemm_dma_kernel(const IgemmArgs a) {
+template <bool DGRAD, int WM, int KG, int NSTAGE, bool CLS = false, bool CELL = false, int BNT = IGD_BN>
+__global__ __launch_bounds__(128 * WM, WM == 2 ? (BNT == 128 ? 3 : 2) : 1) void igemm_dma_kernel(const IgemmArgs a) {
     static_assert(DGRAD || !CLS, "residue classes exist in the backward-data pass only");
     static_assert(CLS || !CELL, "the cell form is a residue-class form");
-    constexpr int BM = 64 * WM, BN = IGD_BN, MI = 2, NJ = 4, NW = 2 * WM;
+    constexpr int BM = 64 * WM, BN = BNT, MI = 2, NJ = BN / 64, NW = 2 * WM;
     constexpr int STAGE_SLOTS = (BM + BN) * KG;         // 16-byte slots per stage: A tile, then B tile
     constexpr int RPL = 64 / KG;                        // tile rows covered by one wave-wide load
     constexpr int NLA = BM * KG / 64 / NW;              // A loads per wave and stage
     constexpr int NLB = BN * KG / 64 / NW;              // B loads per wave and stage
     constexpr int NL = NLA + NLB;
-    static_assert(NSTAGE == 2 || NL == 6 || (NSTAGE == 4 && NL == 4), "vmcnt waits below are written for these");
+    static_assert(NSTAGE == 2 || NL == 6 || NL == 4, "vmcnt waits below are written for these");
     extern __shared__ __attribute__((aligned(16))) uint4 ring[];   // [NSTAGE][STAGE_SLOTS]
 
     const int tid = threadIdx.x;
@@ -575,7 +577,7 @@ __global__ __launch_bounds__(128 * WM, WM == 2 ? 2 : 1) void igemm_dma_kernel(co
             }
 #pragma unroll
             for (int j = 0; j < NJ; ++j) {
-                const uint4 t = sB[igd_slot<KG>(wn * 128 + j * 32 + (lane & 31), g)];
+                const uint4 t = sB[igd_slot<KG>(wn * (BN / 2) + j * 32 + (lane & 31), g)];
                 fb[j] = v4i{(int)t.x, (int)t.y, (int)t.z, (int)t.w};
             }
 #pragma unroll
@@ -591,7 +593,7 @@ __global__ __launch_bounds__(128 * WM, WM == 2 ? 2 : 1) void igemm_dma_kernel(co
     const float scale = __fmul_rn(a.sa[0], a.sb[0]);
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
-        const int col = colbase + wn * 128 + j * 32 + (lane & 31);
+        const int col = colbase + wn * (BN / 2) + j * 32 + (lane & 31);
         if (col >= ncols) continue;
         const int n = col / OHW;
         int opix = col - n * OHW;
@@ -677,25 +679,25 @@ bool igemm_wide(const IgemmArgs& a) {
 }
 }  // namespace
 
-template <bool DGRAD, int WM, int KG, int NSTAGE, bool CLS, bool CELL>
+template <bool DGRAD, int WM, int KG, int NSTAGE, bool CLS, bool CELL, int BNT = IGD_BN>
 static hipError_t launch_igemm_dma(const IgemmArgs& a, const IgemmShape& g, hipStream_t st, const KernelTimer& kt) {
-    const size_t lds = (size_t)NSTAGE * (64 * WM + IGD_BN) * KG * 16;
+    const size_t lds = (size_t)NSTAGE * (64 * WM + BNT) * KG * 16;
     static std::atomic<unsigned long long> attr_done;
     {
-        hipError_t e = raise_dynamic_lds(reinterpret_cast<const void*>(igemm_dma_kernel<DGRAD, WM, KG, NSTAGE, CLS, CELL>), (int)lds, attr_done);
+        hipError_t e = raise_dynamic_lds(reinterpret_cast<const void*>(igemm_dma_kernel<DGRAD, WM, KG, NSTAGE, CLS, CELL, BNT>), (int)lds, attr_done);
         if (e != hipSuccess) return e;
     }
-    const unsigned ctiles = (unsigned)((g.ncols + IGD_BN - 1) / IGD_BN), rtiles = (unsigned)((a.rows + 64 * WM - 1) / (64 * WM));
+    const unsigned ctiles = (unsigned)((g.ncols + BNT - 1) / BNT), rtiles = (unsigned)((a.rows + 64 * WM - 1) / (64 * WM));
     dim3 grid(((ctiles + 7) / 8) * 8 * rtiles * (unsigned)g.ncls);
-    launch_timed(kt, (igemm_dma_kernel<DGRAD, WM, KG, NSTAGE, CLS, CELL>), grid, dim3(128 * WM), lds, st, a);
+    launch_timed(kt, (igemm_dma_kernel<DGRAD, WM, KG, NSTAGE, CLS, CELL, BNT>), grid, dim3(128 * WM), lds, st, a);
     return hipGetLastError();
 }
-template <int WM, int KG, int NSTAGE>
+template <int WM, int KG, int NSTAGE, int BNT = IGD_BN>
 static hipError_t launch_igemm_dma_any(const IgemmArgs& a, const IgemmShape& g, hipStream_t st, const KernelTimer& kt) {
-    if (!a.dgrad) return launch_igemm_dma<false, WM, KG, NSTAGE, false, false>(a, g, st, kt);
-    if (g.cell) return launch_igemm_dma<true, WM, KG, NSTAGE, true, true>(a, g, st, kt);
-    if (g.cls) return launch_igemm_dma<true, WM, KG, NSTAGE, true, false>(a, g, st, kt);
-    return launch_igemm_dma<true, WM, KG, NSTAGE, false, false>(a, g, st, kt);
+    if (!a.dgrad) return launch_igemm_dma<false, WM, KG, NSTAGE, false, false, BNT>(a, g, st, kt);
+    if (g.cell) return launch_igemm_dma<true, WM, KG, NSTAGE, true, true, BNT>(a, g, st, kt);
+    if (g.cls) return launch_igemm_dma<true, WM, KG, NSTAGE, true, false, BNT>(a, g, st, kt);
+    return launch_igemm_dma<true, WM, KG, NSTAGE, false, false, BNT>(a, g, st, kt);
 }
 template <int BM, int BN>
 static void launch_igemm_generic(const IgemmArgs& a, const IgemmShape& g, int ksplit, hipStream_t st, const KernelTimer& kt) {
@@ -729,9 +731,13 @@ int igemm_auto_variant(const IgemmArgs& a) {
     if (igemm_wide(a)) {
         // 256-row tiles only where they are full (half-empty ones cost the short reductions of a
         // residue class a quarter of their time)
+        // ... and 128 x 128 tiles where even the 128 x 256 ones are too few to go round twice (14 x 14 images,
+        // 256 filters, batch 128: 196 of them; forward 36 -> 29 us)
         const IgemmShape g = igemm_shape(a);
-        const long long t256 = g.ncls * ((g.ncols + 255) / 256) * ((a.rows + 255) / 256);
-        return (t256 >= 192 && a.rows > 128) ? VAR_WIDE256 : VAR_WIDE128;
+        const long long ctiles = g.ncls * ((g.ncols + 255) / 256);
+        const long long t256 = ctiles * ((a.rows + 255) / 256);
+        if (t256 >= 192 && a.rows > 128) return VAR_WIDE256;
+        return ctiles * ((a.rows + 127) / 128) >= 512 ? VAR_WIDE128 : VAR_WIDE_SQ128;
     }
     return igemm_ksplit(a) > 1 ? VAR_TILE_SPLIT : VAR_TILE;
 }
@@ -739,7 +745,7 @@ int igemm_auto_variant(const IgemmArgs& a) {
 bool igemm_variant_ok(const IgemmArgs& a, int variant) {
     hipError_t e = hipSuccess;
     switch (variant) {
-        case VAR_AUTO: case VAR_TILE: case VAR_WIDE128: case VAR_WIDE256: return true;
+        case VAR_AUTO: case VAR_TILE: case VAR_WIDE128: case VAR_WIDE256: case VAR_WIDE_SQ128: return true;
         case VAR_BAND: return launch_band(a, nullptr, &e, true);
         case VAR_TILE_SPLIT: return igemm_ksplit(a) > 1;
         default: return false;
@@ -827,9 +833,10 @@ hipError_t launch_igemm(const IgemmArgs& a_in, hipStream_t st) {
         else launch_timed(kt, igemm_reduce_kernel<false>, rgrid, dim3(256), 0, st, a, total);
         return hipGetLastError();
     }
-    if (variant == VAR_WIDE128 || variant == VAR_WIDE256) {
+    if (variant == VAR_WIDE128 || variant == VAR_WIDE256 || variant == VAR_WIDE_SQ128) {
         KernelTimer kt(KID_IGEMM_DMA, st);
         if (variant == VAR_WIDE256) return launch_igemm_dma_any<4, 8, 2>(a, g, st, kt);
+        if (variant == VAR_WIDE_SQ128) return launch_igemm_dma_any<2, 4, 3, 128>(a, g, st, kt);
         return launch_igemm_dma_any<2, 4, 3>(a, g, st, kt);
     }
     KernelTimer kt(KID_IGEMM, st);
