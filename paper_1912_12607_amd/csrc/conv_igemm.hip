@@ -383,9 +383,11 @@ __global__ __launch_bounds__(256) void igemm_reduce_kernel(const IgemmArgs a, si
 //   <WM=4, KG=8, NSTAGE=2>: 256 x 256, 128 KB of LDS, one block of eight waves per compute unit
 //   <WM=2, KG=4, NSTAGE=3, BNT=128>: 128 x 128 (waves of 64 x 64), 48 KB of LDS, three blocks per compute unit: for
 //   layers whose larger tiles would leave most compute units without one
+//   <WM=2, KG=8, NSTAGE=2, BNT=128>: the same tile with 128-byte stages (64 KB, two blocks): half the barriers per MFMA,
+//   better where the reduction is long
 // ---------------------------------------------------------------------------------------------
 template <bool DGRAD, int WM, int KG, int NSTAGE, bool CLS = false, bool CELL = false, int BNT = IGD_BN>
-__global__ __launch_bounds__(128 * WM, WM == 2 ? (BNT == 128 ? 3 : 2) : 1) void igemm_dma_kernel(const IgemmArgs a) {
+__global__ __launch_bounds__(128 * WM, WM == 2 ? (BNT == 128 && KG == 4 ? 3 : 2) : 1) void igemm_dma_kernel(const IgemmArgs a) {
     static_assert(DGRAD || !CLS, "residue classes exist in the backward-data pass only");
     static_assert(CLS || !CELL, "the cell form is a residue-class form");
     constexpr int BM = 64 * WM, BN = BNT, MI = 2, NJ = BN / 64, NW = 2 * WM;
@@ -672,11 +674,6 @@ IgemmShape igemm_shape(const IgemmArgs& a) {
     }
     return g;
 }
-// long reduction and enough wide tiles to cover the chip
-bool igemm_wide(const IgemmArgs& a) {
-    const IgemmShape g = igemm_shape(a);
-    return a.rows > 64 && g.gran >= 32 && g.ncls * ((g.ncols + 255) / 256) * ((a.rows + 127) / 128) >= 256;
-}
 }  // namespace
 
 template <bool DGRAD, int WM, int KG, int NSTAGE, bool CLS, bool CELL, int BNT = IGD_BN>
@@ -728,24 +725,24 @@ int igemm_auto_variant(const IgemmArgs& a) {
     hipError_t e = hipSuccess;
     if (launch_band(a, nullptr, &e, true)) return VAR_BAND;
     if (a.rows <= 64) return VAR_TILE;
-    if (igemm_wide(a)) {
-        // 256-row tiles only where they are full (half-empty ones cost the short reductions of a
-        // residue class a quarter of their time)
-        // ... and 128 x 128 tiles where even the 128 x 256 ones are too few to go round twice (14 x 14 images,
-        // 256 filters, batch 128: 196 of them; forward 36 -> 29 us)
-        const IgemmShape g = igemm_shape(a);
-        const long long ctiles = g.ncls * ((g.ncols + 255) / 256);
-        const long long t256 = ctiles * ((a.rows + 255) / 256);
-        if (t256 >= 192 && a.rows > 128) return VAR_WIDE256;
-        return ctiles * ((a.rows + 127) / 128) >= 512 ? VAR_WIDE128 : VAR_WIDE_SQ128;
-    }
-    return igemm_ksplit(a) > 1 ? VAR_TILE_SPLIT : VAR_TILE;
+    // Above 64 rows the 128 x 128 tiles of the LDS-DMA kernel win on nearly every layer of the three networks
+    // (ResNet-50, batch 64: forward and backward-data 2.60 -> 2.11 ms in total; the best variant per layer would give 2.07):
+    //  - 128 x 256 tiles of 4 waves per row pair where they are full, many, unsplit and the reduction is at least
+    //    512 bytes (14 x 14, 256 channels, 3x3, batch 256: 41.6 against 46.3 us); the pixel classes of a strided
+    //    backward-data pass leave them ragged (28 x 28, 512 -> 1024 shortcut: 33.5 against 28.7)
+    //  - else 128 x 128: 128-byte stages (two blocks per compute unit) where a column's reduction is at least 1 KB, or 512 bytes
+    //    with fewer than 512 tiles; 64-byte stages (three blocks) below (35 x 35, 96 channels, 3x3: 20.9 against 25.1 us)
+    const IgemmShape g = igemm_shape(a);
+    const long long c256 = g.ncls * ((g.ncols + 255) / 256), c128 = g.ncls * ((g.ncols + 127) / 128);
+    if (!g.cls && c256 * ((a.rows + 255) / 256) >= 192 && a.rows > 128 && g.gran >= 32) return VAR_WIDE256;
+    const long long tiles = c128 * ((a.rows + 127) / 128);
+    return g.gran >= 64 || (g.gran >= 32 && tiles < 512) ? VAR_WIDE_SQ128_DEEP : VAR_WIDE_SQ128;
 }
 
 bool igemm_variant_ok(const IgemmArgs& a, int variant) {
     hipError_t e = hipSuccess;
     switch (variant) {
-        case VAR_AUTO: case VAR_TILE: case VAR_WIDE128: case VAR_WIDE256: case VAR_WIDE_SQ128: return true;
+        case VAR_AUTO: case VAR_TILE: case VAR_WIDE128: case VAR_WIDE256: case VAR_WIDE_SQ128: case VAR_WIDE_SQ128_DEEP: return true;
         case VAR_BAND: return launch_band(a, nullptr, &e, true);
         case VAR_TILE_SPLIT: return igemm_ksplit(a) > 1;
         default: return false;
@@ -833,10 +830,11 @@ hipError_t launch_igemm(const IgemmArgs& a_in, hipStream_t st) {
         else launch_timed(kt, igemm_reduce_kernel<false>, rgrid, dim3(256), 0, st, a, total);
         return hipGetLastError();
     }
-    if (variant == VAR_WIDE128 || variant == VAR_WIDE256 || variant == VAR_WIDE_SQ128) {
+    if (variant == VAR_WIDE128 || variant == VAR_WIDE256 || variant == VAR_WIDE_SQ128 || variant == VAR_WIDE_SQ128_DEEP) {
         KernelTimer kt(KID_IGEMM_DMA, st);
         if (variant == VAR_WIDE256) return launch_igemm_dma_any<4, 8, 2>(a, g, st, kt);
         if (variant == VAR_WIDE_SQ128) return launch_igemm_dma_any<2, 4, 3, 128>(a, g, st, kt);
+        if (variant == VAR_WIDE_SQ128_DEEP) return launch_igemm_dma_any<2, 8, 2, 128>(a, g, st, kt);
         return launch_igemm_dma_any<2, 4, 3>(a, g, st, kt);
     }
     KernelTimer kt(KID_IGEMM, st);
