@@ -731,12 +731,13 @@ int igemm_auto_variant(const IgemmArgs& a) {
     //    512 bytes (14 x 14, 256 channels, 3x3, batch 256: 41.6 against 46.3 us); the pixel classes of a strided
     //    backward-data pass leave them ragged (28 x 28, 512 -> 1024 shortcut: 33.5 against 28.7)
     //  - else 128 x 128: 128-byte stages (two blocks per compute unit) where a column's reduction is at least 1 KB, or 512 bytes
-    //    with fewer than 512 tiles; 64-byte stages (three blocks) below (35 x 35, 96 channels, 3x3: 20.9 against 25.1 us)
+    //    with fewer than 512 tiles or the tap classes of a strided backward-data pass (56 x 56, 128 channels, 3x3, stride 2:
+    //    44.7 against 53.9 us); 64-byte stages (three blocks) below (35 x 35, 96 channels, 3x3: 20.9 against 25.1 us)
     const IgemmShape g = igemm_shape(a);
     const long long c256 = g.ncls * ((g.ncols + 255) / 256), c128 = g.ncls * ((g.ncols + 127) / 128);
     if (!g.cls && c256 * ((a.rows + 255) / 256) >= 192 && a.rows > 128 && g.gran >= 32) return VAR_WIDE256;
     const long long tiles = c128 * ((a.rows + 127) / 128);
-    return g.gran >= 64 || (g.gran >= 32 && tiles < 512) ? VAR_WIDE_SQ128_DEEP : VAR_WIDE_SQ128;
+    return g.gran >= 64 || (g.gran >= 32 && (tiles < 512 || (g.cls && !g.cell))) ? VAR_WIDE_SQ128_DEEP : VAR_WIDE_SQ128;
 }
 
 bool igemm_variant_ok(const IgemmArgs& a, int variant) {
