@@ -74,10 +74,10 @@ def pass_algorithmic(L, n_cand):
         "absmax_xw": (4 * (n_x + n_w), 0, None),                 # one read of a and W
         "quantize_xw": (5 * n_x + 6 * n_w, 0, None),             # fp32 read + code write (W: two layouts)
         "absmax_gz": (4 * n_y, 0, None),                         # max|g_z| and sum g_z^2, one read
-        # One read of g_z.  Vector-ALU work of the sweep: 2.75 operations per element and candidate (round-down
-        # fused multiply-add, convert, 0.75 byte gather) + 30 per element and 32-candidate chunk (draw, fixed
-        # point, digit planes, LDS traffic); the products and sums themselves run on the matrix cores.
-        "dsgc_search": (4 * n_y, (2.75 * n_cand + 30 * ((n_cand + 31) // 32)) * n_y, "valu"),
+        # One read of g_z.  Vector-ALU work of the sweep: 2.5 operations per element and candidate (round-down
+        # fused multiply-add, convert-and-pack, a shift and a mask per four) + 31 per element and 32-candidate
+        # chunk (draw, fixed point, digit planes, LDS traffic); the products and sums themselves run on the matrix cores.
+        "dsgc_search": (4 * n_y, (2.5 * n_cand + 31 * ((n_cand + 31) // 32)) * n_y, "valu"),
         "quantize_gz": (5 * n_y, 0, None),
         "fwd": (n_x + n_w + 4 * n_y, 2 * macs, "mfma"),
         "bwd_data": (n_y + n_w + 4 * n_x, 2 * macs, "mfma"),

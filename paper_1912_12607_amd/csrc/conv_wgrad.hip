@@ -390,10 +390,11 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const WgradArgs a) {
 
 // The kernel VAR_AUTO runs: wgrad_lines_kernel wherever it applies (measured on the benchmark's 1x7, 7x1
 // and 3x3 layers it needs 0.6 - 0.85 of wgrad_kernel's time), except for 1x1 filters on few channels: its
-// 128 x 128 tile is mostly padding there (24 or 144 channels: 18 - 19 us against 17.5).
+// 128 x 128 tile is mostly padding there (24 or 144 channels: 18 - 19 us against 17.5); with 256 or more input
+// channels 64 filters are enough (56 x 56, 256 -> 64: 19.9 us against 27.5).
 bool wgrad_auto_lines(const WgradArgs& a) {
     if (!wgrad_lines_applies(a)) return false;
-    return !(a.R == 1 && a.S == 1) || (a.Cp >= 128 && a.Kp >= 128);
+    return !(a.R == 1 && a.S == 1) || (a.Cp >= 128 && a.Kp >= 128) || (a.Cp >= 256 && a.Kp >= 64);
 }
 
 size_t wgrad_s2d(WgradArgs* a) {

@@ -147,26 +147,28 @@ __device__ __forceinline__ int stoch_fixed_s(float x, float inv24_uniform, float
     return X;
 }
 
-// Four elements against one (uniform) scale: the four magnitudes floor((|x_e| * inv24 + u_e) / 2^24),
-// saturated at 127, packed as bytes [m0, m1, m2, m3].  One instruction block, so the eleven
-// instructions stay together and in this order (needs the round-down mode).
-__device__ __forceinline__ uint32_t stoch_codes4(const float x[4], float inv24_uniform, const float uf[4]) {
-    uint32_t a, b, c, d;
+// Four elements against one (uniform) scale: the four magnitudes min(127, floor(|x_e| * inv + u_e)), u_e in [0, 1),
+// packed as bytes [m0, m1, m2, m3].  The caller passes inv2 = 2 * inv and uf2 = 2 * u_e (both exact): in the
+// round-down mode the fused multiply-add never crosses an integer, the float -> byte convert-and-pack follows the
+// wave's rounding mode (so it floors) and saturates at 255, and floor(2t) >> 1 = floor(t) with 255 >> 1 = 127.
+// Ten instructions for four codes; one instruction block, so they stay together and in this order.
+__device__ __forceinline__ uint32_t stoch_codes4(const float x[4], float inv2_uniform, const float uf2[4]) {
+    uint32_t a;
+    float t0, t1, t2, t3;
     asm volatile(
-        "v_fma_f32 %0, |%4|, %8, %9\n\t"
-        "v_fma_f32 %1, |%5|, %8, %10\n\t"
-        "v_fma_f32 %2, |%6|, %8, %11\n\t"
-        "v_fma_f32 %3, |%7|, %8, %12\n\t"
-        "v_cvt_i32_f32 %0, %0\n\t"
-        "v_cvt_i32_f32 %1, %1\n\t"
-        "v_cvt_i32_f32 %2, %2\n\t"
-        "v_cvt_i32_f32 %3, %3\n\t"
-        "v_perm_b32 %0, %1, %0, %13\n\t"     // a.b3 b.b3 0 0
-        "v_perm_b32 %2, %3, %2, %14\n\t"     // 0 0 c.b3 d.b3
-        "v_or_b32 %0, %0, %2"
-        : "=&v"(a), "=&v"(b), "=&v"(c), "=&v"(d)
-        : "v"(x[0]), "v"(x[1]), "v"(x[2]), "v"(x[3]), "s"(inv24_uniform), "v"(uf[0]), "v"(uf[1]), "v"(uf[2]),
-          "v"(uf[3]), "s"(0x0c0c0703u), "s"(0x07030c0cu));
+        "v_fma_f32 %1, |%5|, %9, %10\n\t"
+        "v_fma_f32 %2, |%6|, %9, %11\n\t"
+        "v_fma_f32 %3, |%7|, %9, %12\n\t"
+        "v_fma_f32 %4, |%8|, %9, %13\n\t"
+        "v_cvt_pk_u8_f32 %0, %1, 0, 0\n\t"
+        "v_cvt_pk_u8_f32 %0, %2, 1, %0\n\t"
+        "v_cvt_pk_u8_f32 %0, %3, 2, %0\n\t"
+        "v_cvt_pk_u8_f32 %0, %4, 3, %0\n\t"
+        "v_lshrrev_b32 %0, 1, %0\n\t"
+        "v_and_b32 %0, %14, %0"
+        : "=&v"(a), "=&v"(t0), "=&v"(t1), "=&v"(t2), "=&v"(t3)
+        : "v"(x[0]), "v"(x[1]), "v"(x[2]), "v"(x[3]), "s"(inv2_uniform), "v"(uf2[0]), "v"(uf2[1]), "v"(uf2[2]),
+          "v"(uf2[3]), "s"(0x7f7f7f7fu));
     return a;
 }
 

@@ -11,9 +11,9 @@
 // operations per element AND candidate), so the arithmetic is arranged to need few instructions:
 //   * codes are sign(g) * m with m the rounded magnitude, so g*q = |g|*m and q^2 = m^2: the whole
 //     search runs on magnitudes and never looks at a sign;
-//   * m is the top byte of floor(|g| * inv24 + u), one round-down fused multiply-add and one
-//     saturating convert (see device_common.h); four elements' bytes are gathered into one dword
-//     by byte permutes.  These 2.75 instructions per element and candidate are all the vector ALU
+//   * m = floor(2 (|g| * inv + u)) >> 1: one round-down fused multiply-add and one convert that floors,
+//     saturates and drops its byte into the dword of four elements, then one shift and one mask per dword
+//     (see device_common.h).  These 2.5 instructions per element and candidate are all the vector ALU
 //     does per evaluation;
 //   * |g| is turned, once per element, into a 44-bit fixed-point integer relative to max|g|
 //     (H * 2^22 + L, H, L <= 2^22), and both halves into three balanced (signed) byte digits;
@@ -114,8 +114,8 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
     if (threadIdx.x < JC) {
         const int j = threadIdx.x;
         const float c = (j < jn) ? __fmul_rn(M, ratios[j0 + j]) : 0.0f;
-        // stochastic mode carries the scaled value with 24 fraction bits (exact power-of-two factor)
-        s_inv[j] = STOCH ? __fmul_rn(inv_scale_of(c), kTwo24) : inv_scale_of(c);
+        // the stochastic sweep works on twice the scaled value (exact power-of-two factor; stoch_codes4)
+        s_inv[j] = STOCH ? __fmul_rn(inv_scale_of(c), 2.0f) : inv_scale_of(c);
     }
     __syncthreads();
     // fixed point: max|g| < 2^e, |g| * 2^(22-e) <= 2^22
@@ -188,7 +188,7 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
         uint32_t H[4], L[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            if (STOCH) uf[e] = (float)rng24(seed_lo, seed_hi_mul, index0 + e);   // exact: 24 bits
+            if (STOCH) uf[e] = (float)rng24(seed_lo, seed_hi_mul, index0 + e) * 0x1p-23f;   // 2 u, u in [0, 1): exact
             const float xs = ldexpf(fabsf(x[e]), shift);     // exact, 0 .. 2^22
             const float h = floorf(xs);
             H[e] = (uint32_t)h;
