@@ -110,10 +110,19 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
 
     const int j0 = blockIdx.y * JC;
     const int jn = (n_cand - j0 < JC) ? (n_cand - j0) : JC;
-    const float M = reduce_absmax_partials(absmax_part, nparts, lds4);
+    // Everything the prologue fetches is requested before the first wait: the absmax partials, the ratios and
+    // the block's first 16 bytes per lane of g (one memory round trip instead of three in a row, about 1 us
+    // of a sweep that takes 10 us on a small tensor).
+    absmax_partials_begin(absmax_part, nparts, lds4);
+    const size_t n4 = n >> 2;
+    const float4* __restrict__ g4 = reinterpret_cast<const float4*>(g);
+    const size_t i_first = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const float4 f_first = (i_first < n4) ? g4[i_first] : make_float4(0.f, 0.f, 0.f, 0.f);
+    const float ratio_j = ratios[j0 + ((int)threadIdx.x < jn ? (int)threadIdx.x : 0)];
+    const float M = absmax_partials_end(lds4);
     if (threadIdx.x < JC) {
         const int j = threadIdx.x;
-        const float c = (j < jn) ? __fmul_rn(M, ratios[j0 + j]) : 0.0f;
+        const float c = (j < jn) ? __fmul_rn(M, ratio_j) : 0.0f;
         // the stochastic sweep works on twice the scaled value (exact power-of-two factor; stoch_codes4)
         s_inv[j] = STOCH ? __fmul_rn(inv_scale_of(c), 2.0f) : inv_scale_of(c);
     }
@@ -229,17 +238,15 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
         __builtin_amdgcn_wave_barrier();   // and the next iteration's stores behind these loads
     };
 
-    const size_t n4 = n >> 2;
-    const float4* __restrict__ g4 = reinterpret_cast<const float4*>(g);
     const size_t stride = (size_t)gridDim.x * 256;
     {
         // Wave-uniform trip count (the MFMAs need the whole wave): lanes beyond the end carry zeros,
         // which add nothing to A or B.  The next iteration's 16 bytes are requested before this
         // iteration's arithmetic starts.  The int32 tiles are turned into 64-bit totals after every
         // DSGC_FLUSH_ITERS iterations, outside the inner loop, so inside it only MFMAs touch them.
-        size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+        size_t i = i_first;
         size_t ibase = (size_t)blockIdx.x * 256 + 64 * w;      // the wave's first float4
-        float4 f = (i < n4) ? g4[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+        float4 f = f_first;
         while (ibase < n4) {
             for (int it = 0; it < DSGC_FLUSH_ITERS && ibase < n4; ++it) {
                 const size_t inext = i + stride;
@@ -306,8 +313,7 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
     // the largest clip value for decreasing ratios).  Every addition is in a fixed order. ----------
     long long (*const f_part)[DSGC_JPAD][3] = reinterpret_cast<long long (*)[DSGC_JPAD][3]>(&s_tile[0][0]);
     double* const f_g = reinterpret_cast<double*>(&s_tile[0][0] + sizeof(long long) * 4 * DSGC_JPAD * 3);
-    double* const f_dev = f_g + 4;
-    static_assert(sizeof(long long) * 4 * DSGC_JPAD * 3 + sizeof(double) * (4 + DSGC_JPAD) <= sizeof(s_tile), "fits the tiles");
+    static_assert(sizeof(long long) * 4 * DSGC_JPAD * 3 + sizeof(double) * 4 <= sizeof(s_tile), "fits the tiles");
     {
         const int j = threadIdx.x & 63, part = threadIdx.x >> 6;
         long long t[3] = {0, 0, 0};
@@ -349,21 +355,35 @@ __global__ __launch_bounds__(256) void dsgc_sweep_kernel(
             else d = 1.0 - At / (sqrt(Gt) * sqrt(Bt));
             if (dev_all_out) dev_all_out[j] = d;
         }
-        f_dev[j] = d;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int best = 0;
-        for (int k = 1; k < n_cand; ++k)
-            if (f_dev[k] < f_dev[best]) best = k;
-        if (Mn == 0.0f) best = 0;
-        *clip_out = __fmul_rn(Mn, ratios[best]);
-        *dev_out = f_dev[best];
+        // The winner, over the lanes: a candidate replaces the best so far only with a strictly smaller deviation,
+        // walking j upwards -- i.e. the smallest (d, j) in lexicographic order, where a deviation that is not
+        // a number never wins, except candidate 0's, which then is never replaced.
+        const double inf = __builtin_huge_val();
+        double bd = (j < n_cand && d == d) ? d : (j == 0 ? -inf : inf);
+        int bj = j;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const double od = __shfl_xor(bd, o, kWave);
+            const int oj = __shfl_xor(bj, o, kWave);
+            if (od < bd || (od == bd && oj < bj)) { bd = od; bj = oj; }
+        }
+        const int best = (Mn == 0.0f) ? 0 : bj;
+        const double dbest = __shfl(d, best, kWave);
+        if (j == 0) {
+            *clip_out = __fmul_rn(Mn, ratios[best]);
+            *dev_out = dbest;
+        }
     }
 }
 
+// Blocks of the sweep: one per 1024 elements up to one per compute unit, then a quarter of that up to three per
+// compute unit.  Every block ends with 96 device-scope atomic additions and a ticket, which the blocks of a
+// mid-sized tensor all issue at the same moment: with 768 blocks of one or two iterations each that hand-over
+// took 6 - 7 us of a 16 us sweep (0.8 M elements: 16.4 us with 768 blocks, 13.2 with 256; 1.6 M: 18.2 -> 16.7
+// with 392; from 3 M elements on the full grid is fastest).
 int dsgc_blocks(size_t n) {
-    size_t want = (n / 4 + 255) / 256;
+    const size_t units = (n / 4 + 255) / 256;
+    size_t want = units <= 256 ? units : (units / 4 < 256 ? 256 : units / 4);
     return (int)(want < 1 ? 1 : (want > (size_t)DSGC_MAX_BLOCKS ? (size_t)DSGC_MAX_BLOCKS : want));
 }
 
