@@ -336,9 +336,10 @@ typedef enum {
     INT8T_VARIANT_WIDE_SQ128 = 10,   /* forward / backward-data: 128 x 128 tiles from a 3-stage LDS ring, three blocks per
                                         compute unit: layers that have too few of the larger tiles to go round */
     INT8T_VARIANT_WIDE_SQ128_DEEP = 11,  /* ... with 2 stages of 128 reduction bytes: long reductions */
+    INT8T_VARIANT_WIDE_128X64 = 12,      /* ... 128 x 64 tiles with 128-byte stages: few columns (7 x 7 images) */
     INT8T_VARIANT_MAX_ENUM = 0x7fffffff
 } int8t_variant;
-#define INT8T_VARIANT_COUNT 12
+#define INT8T_VARIANT_COUNT 13
 /* 1 when `variant` can run pass `op` (INT8T_OP_CONV_*) of the layer, else 0 (also on a bad descriptor). */
 int int8t_conv_variant_ok(int8t_op op, const int8t_conv_desc *desc, int8t_variant variant);
 /* INT8T_ERR_ARG when the variant cannot run that pass of that layer; then nothing changes. */

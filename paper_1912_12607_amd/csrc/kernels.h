@@ -151,6 +151,7 @@ enum ConvVariant : int {
     VAR_WGRAD_LINES = 9,   // backward-weight: operands of 32 image lines per position, transposing LDS reads (conv_wgrad_lines.hip)
     VAR_WIDE_SQ128 = 10,   // forward / backward-data: 128 x 128 tiles, ring of 3 stages, three blocks per compute unit
     VAR_WIDE_SQ128_DEEP = 11,   // ... 2 stages of 128 reduction bytes, two blocks per compute unit
+    VAR_WIDE_128X64 = 12,       // ... 128 x 64 tiles: layers with few columns
     VAR_COUNT
 };
 int igemm_ksplit(const IgemmArgs& a);   // largest split a launch of this layer may use (1 = none): sizes the scratch

@@ -777,7 +777,7 @@ def test_every_kernel_variant_is_exact():
                 B.int8t_conv_select_variant(op, gd, B.VARIANT_AUTO)
     # every variant ran at least once in each pass it exists for
     for v in (B.VARIANT_BAND, B.VARIANT_TILE, B.VARIANT_TILE_SPLIT, B.VARIANT_WIDE128, B.VARIANT_WIDE256, B.VARIANT_WIDE_SQ128,
-              B.VARIANT_WIDE_SQ128_DEEP):
+              B.VARIANT_WIDE_SQ128_DEEP, B.VARIANT_WIDE_128X64):
         assert ("fwd", v) in seen and ("bwd_data", v) in seen, B.VARIANT_NAMES[v]
     for v in (B.VARIANT_WGRAD_FEWER, B.VARIANT_WGRAD_MORE, B.VARIANT_WGRAD_IMAGES, B.VARIANT_WGRAD_LINES):
         assert ("bwd_weight", v) in seen, B.VARIANT_NAMES[v]
