@@ -96,8 +96,22 @@ class _Int8ConvFn(torch.autograd.Function):
             layer.deviation = torch.zeros(1, dtype=torch.float64, device=dy.device)
         # Periodic Update (Sec.3.4): the clip value is searched every `dsgc_period` backward passes
         if layer.backward_calls % layer.dsgc_period == 0:
-            B.int8t_dsgc_clip(dy, n_y, layer.ratios, layer.ratios.numel(), B.ROUND_STOCHASTIC, seed,
-                              layer.clip, layer.deviation, None, buf.ws)
+            J = layer.ratios.numel()
+            refine = layer.dsgc_refine
+            B.int8t_dsgc_clip(dy, n_y, layer.ratios, J, B.ROUND_STOCHASTIC, seed,
+                              layer.clip, layer.deviation, layer.dev_all if refine else None, buf.ws)
+            # Refinement of the clip value (Sec.3.4 learns c by descending d_c; no step size is given): further
+            # sweeps over J candidates spaced geometrically around the last winner, the window shrinking by the
+            # factor J / 2 each time.  The winner itself is candidate J / 2, so d_c never rises.  The ratios are
+            # formed on the device (no host round trip): winner's ratio times 2^((j - J/2) * w / J), capped at 1.
+            ratios, width = layer.ratios, layer.ratio_step
+            for _ in range(refine):
+                best = torch.argmin(layer.dev_all[:J])
+                ratios = torch.clamp(ratios[best] * layer.refine_factors(width), max=1.0)
+                B.int8t_dsgc_clip(dy, n_y, ratios, J, B.ROUND_STOCHASTIC, seed,
+                                  layer.clip, layer.deviation, layer.dev_all, buf.ws)
+                width = 2.0 * width / J
+            layer.last_ratios = ratios          # the candidates of the last sweep (the grid itself without refinement)
             dev_out = None
         else:
             dev_out = layer.deviation          # Eq.6 of the codes actually produced with the kept clip
@@ -131,7 +145,9 @@ class Int8Conv2d(torch.nn.Module):
     to multiply this layer's learning rate with."""
 
     def __init__(self, in_channels, out_channels, kernel_size, stride=1, padding=0, groups=1, bias=False,
-                 n_candidates: int = 32, dsgc_period: int = 1, seed: int | None = None, device="cuda:0", name: str = ""):
+                 n_candidates: int = 32, dsgc_period: int = 1, dsgc_refine: int = 0, seed: int | None = None,
+                 device="cuda:0", name: str = ""):
+        """dsgc_refine: sweeps that refine the clip value around the winner of the candidate grid (0: the grid only)."""
         super().__init__()
         self.in_channels, self.out_channels = in_channels, out_channels
         self.kernel_size, self.stride, self.padding, self.groups = _pair(kernel_size), _pair(stride), _pair(padding), groups
@@ -143,7 +159,14 @@ class Int8Conv2d(torch.nn.Module):
         self.bias = torch.nn.Parameter(torch.zeros(out_channels, device=device)) if bias else None
         self.ratios = torch.from_numpy(np.ascontiguousarray(default_ratios(n_candidates))).to(device)
         self.dsgc_period = max(1, int(dsgc_period))
+        self.dsgc_refine = max(0, int(dsgc_refine))
+        # log2 of the spacing of the grid's neighbours around a winner: the first refinement spans one grid step each way
+        r = default_ratios(n_candidates)
+        self.ratio_step = 2.0 * float(np.log2(r[0] / r[1])) if n_candidates > 1 else 1.0
+        self.dev_all = torch.zeros(B.MAX_CANDIDATES, dtype=torch.float64, device=device) if self.dsgc_refine else None
+        self._j = torch.arange(n_candidates, dtype=torch.float32, device=device) - float(n_candidates // 2)
         self.backward_calls = 0
+        self.last_ratios = None
         self.clip = None
         self.deviation = None
         # Stream of seeds of the stochastic rounding (Eq.3): starts at a hash of the layer's name, so that
@@ -156,6 +179,10 @@ class Int8Conv2d(torch.nn.Module):
         if key not in self._buffers:
             self._buffers[key] = _LayerBuffers(self, x_shape, dev)
         return self._buffers[key]
+
+    def refine_factors(self, width: float) -> torch.Tensor:
+        """2^((j - J/2) * width / J), j = 0..J-1, fp32 on the layer's device (factor 1 at j = J/2)."""
+        return torch.exp2(self._j * (width / self._j.numel()))
 
     def next_seed(self) -> int:
         self._seed += 1
@@ -190,7 +217,7 @@ class Int8Linear(Int8Conv2d):
         return y.reshape(*lead, self.out_features)
 
 
-def replace_modules(model: torch.nn.Module, n_candidates: int = 32, dsgc_period: int = 1, skip=()) -> int:
+def replace_modules(model: torch.nn.Module, n_candidates: int = 32, dsgc_period: int = 1, skip=(), dsgc_refine: int = 0) -> int:
     """Swaps, in place, every `nn.Conv2d` the library covers (groups 1 or depthwise, dilation 1, zero
     padding) and every `nn.Linear` of `model` for its INT8 counterpart, keeping the parameters (the
     very Parameter objects, so optimizers and state dicts keep working) -- the automatic match and
@@ -209,11 +236,11 @@ def replace_modules(model: torch.nn.Module, n_candidates: int = 32, dsgc_period:
                       and (m.groups == 1 or m.groups == m.in_channels == m.out_channels))
                 if ok:
                     new = Int8Conv2d(m.in_channels, m.out_channels, m.kernel_size, m.stride, m.padding, m.groups,
-                                     bias=False, n_candidates=n_candidates, dsgc_period=dsgc_period,
+                                     bias=False, n_candidates=n_candidates, dsgc_period=dsgc_period, dsgc_refine=dsgc_refine,
                                      device=m.weight.device, name=full)
             elif isinstance(m, torch.nn.Linear):
                 new = Int8Linear(m.in_features, m.out_features, bias=False, n_candidates=n_candidates,
-                                 dsgc_period=dsgc_period, device=m.weight.device, name=full)
+                                 dsgc_period=dsgc_period, dsgc_refine=dsgc_refine, device=m.weight.device, name=full)
             if new is None:
                 continue
             new.weight = m.weight

@@ -105,6 +105,36 @@ def test_periodic_update_keeps_clip_between_searches():
     assert clips[3] != clips[0]                    # searched again at pass 3 (the gradients have grown)
 
 
+def test_clip_refinement_descends_and_matches_oracle():
+    """dsgc_refine: further sweeps around the winner of the grid (Sec.3.4 learns the clip by descending d_c).  Each
+    sweep keeps the previous winner as a candidate, so d_c cannot rise; the last sweep must equal the oracle's search
+    over the same candidates, and the candidates must sit inside one grid step around the grid's winner."""
+    r = np.random.default_rng(11)
+    x = r.standard_normal((2, 16, 10, 10)).astype(np.float32)
+    devs = {}
+    for refine in (0, 1, 2):
+        m = _layer(16, 24, (3, 3), (1, 1), (1, 1), 1, dsgc_refine=refine)
+        y = m(torch.from_numpy(x).cuda().requires_grad_(True))
+        if refine == 0:
+            dy = (r.standard_t(3, size=tuple(y.shape)) * 1e-3).astype(np.float32)
+        y.backward(torch.from_numpy(dy).cuda())
+        seed = m._seed
+        ratios = m.last_ratios.cpu().numpy()
+        o = oracle.dsgc(dy, ratios, STO, seed)
+        assert m.clip.item() == o["clip"]
+        assert abs(m.deviation.item() - o["deviation"]) <= DEV_TOL
+        devs[refine] = m.deviation.item()
+        if refine == 0:
+            grid = o
+            assert np.array_equal(ratios, inputs.default_ratios(32))
+        else:
+            centre = inputs.default_ratios(32)[grid["jstar"]]
+            assert ratios.max() <= min(1.0, centre * 2 ** 0.26) and ratios.min() >= centre * 2 ** -0.26
+            assert np.all(np.diff(ratios) >= 0)
+    assert devs[2] <= devs[1] <= devs[0]
+    assert devs[2] < devs[0]                       # a finer grid around the winner does find a better clip here
+
+
 def test_dclr_sgd_scales_each_layer_by_phi():
     """Eq.7: the update of an INT8 layer's weight is lr * phi(d_c) * gradient with that layer's own d_c;
     other parameters use the plain rate."""
