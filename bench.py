@@ -46,10 +46,12 @@ VALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 # (FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter reads for a copy kernel of known
 # size), keyed by (config, layer, kernel) -> (bytes, the profiles/ file that holds the run).
 TRAFFIC = {
-    (4, 0, "igemm_dma_kernel"): (int((50.5 + 80.9) * 1e6), "profiles/step_config4_inception_1x7_kernels_and_counters.md"),
-    (4, 0, "wgrad_lines_kernel"): (int((101.7 + 49.5) * 1e6), "profiles/step_config4_inception_1x7_kernels_and_counters.md"),
-    (2, 1, "igemm_kernel"): (int((20.6 + 34.5) * 1e6), "profiles/step_config2_resnet50_3x3_kernels_and_counters.md"),
-    (2, 0, "igemm_kernel"): (int((41.0 + 78.8) * 1e6), "profiles/step_config2_resnet50_1x1_reduce_kernels_and_counters.md"),
+    (4, 0, "igemm_dma_kernel"): (int((50.2 + 81.0) * 1e6), "profiles/step_config4_inception_1x7_kernels_and_counters.md"),
+    (4, 0, "wgrad_lines_kernel"): (int((101.6 + 49.5) * 1e6), "profiles/step_config4_inception_1x7_kernels_and_counters.md"),
+    (2, 1, "igemm_dma_kernel"): (int((12.8 + 33.6) * 1e6), "profiles/step_config2_resnet50_3x3_kernels_and_counters.md"),
+    (2, 1, "dsgc_sweep_kernel"): (int((25.9 + 0.6) * 1e6), "profiles/step_config2_resnet50_3x3_kernels_and_counters.md"),
+    (2, 0, "igemm_dma_kernel"): (int((20.9 + 72.8) * 1e6), "profiles/step_config2_resnet50_1x1_reduce_kernels_and_counters.md"),
+    (2, 0, "dsgc_sweep_kernel"): (int((25.9 + 0.6) * 1e6), "profiles/step_config2_resnet50_1x1_reduce_kernels_and_counters.md"),
     (1, 0, "dsgc_sweep_kernel"): (int((51.6 + 0.6) * 1e6), "profiles/step_config1_resnet18_3x3_kernels_and_counters.md"),
     (1, 0, "band_reg_kernel"): (int((13.3 + 51.4) * 1e6), "profiles/step_config1_resnet18_3x3_kernels_and_counters.md"),
 }
