@@ -265,9 +265,11 @@ size_t int8t_workspace_bytes(int8t_op op, const int8t_conv_desc* desc, size_t n,
         case INT8T_OP_CONV_BWD_WEIGHT: {
             Geo g;
             if (desc_ok(desc, &g) != INT8T_OK) return 0;
-            if (g.depthwise)
-                return align256((size_t)dw_wgrad_chunks(desc->N, desc->C, dw_wgrad_threads(g.P, g.Q, desc->R, desc->S, desc->stride_h, desc->stride_w)) *
-                                desc->C * desc->R * desc->S * 4);
+            if (g.depthwise) {
+                int threads, chunks, cg;
+                dw_wgrad_shape(desc->N, desc->C, desc->H, desc->W, g.P, g.Q, desc->R, desc->S, desc->stride_h, desc->stride_w, &threads, &chunks, &cg);
+                return align256((size_t)chunks * desc->C * desc->R * desc->S * 4);
+            }
             WgradArgs a{};
             fill_wgrad_geometry(&a, desc, g);
             const size_t s2d_bytes = wgrad_s2d(&a);
@@ -617,8 +619,7 @@ int8t_status int8t_conv_bwd_weight(const int8t_conv_desc* desc, const int8_t* xq
         DwArgs a{};
         a.a = xq_dev; a.b = dyq_dev; a.sa = sx_dev; a.sb = sdy_dev; a.out = dw_dev; a.acc = acc_dev;
         a.partial = (int32_t*)ws_dev;
-        a.threads = dw_wgrad_threads(g.P, g.Q, desc->R, desc->S, desc->stride_h, desc->stride_w);
-        a.chunks = dw_wgrad_chunks(desc->N, desc->C, a.threads);
+        dw_wgrad_shape(desc->N, desc->C, desc->H, desc->W, g.P, g.Q, desc->R, desc->S, desc->stride_h, desc->stride_w, &a.threads, &a.chunks, &a.cg);
         a.N = desc->N; a.C = desc->C; a.IH = desc->H; a.IW = desc->W; a.OH = g.P; a.OW = g.Q;
         a.R = desc->R; a.S = desc->S; a.stride_h = desc->stride_h; a.stride_w = desc->stride_w;
         a.pad_h = desc->pad_h; a.pad_w = desc->pad_w; a.dgrad = 0;

@@ -156,20 +156,106 @@ __device__ __forceinline__ void dw_stage_plane(const int8_t* __restrict__ src, i
     __syncthreads();
 }
 
+// t / d for 0 <= t < 2^15 and quotients below 2^10, d >= 1, with inv = 1.0f / d: (t + 0.5) / d is at least 0.5 / d away
+// from an integer and the fp32 product is off by less than 2^-13, so truncation gives the exact quotient -- four
+// instructions where the integer division takes some thirty-five.
+__device__ __forceinline__ int dw_div_small(int t, float inv) { return (int)(((float)t + 0.5f) * inv); }
+
+// Small planes (7 x 7, 14 x 14, 28 x 28): a block takes `np` consecutive planes -- they are one contiguous run of
+// np * IH * IW source bytes -- so that it has a few hundred results to form; one plane per block made a
+// 7 x 7 layer 61 440 blocks of 49 results, each living two memory round trips (960 channels, batch 64: 23 us per
+// pass for 15 MB of traffic).  Plane p is staged at dst + p * psize; 16-byte loads when the run is a whole number of
+// aligned chunks (`vec`, uniform over the block).
+// 16 bytes of the run starting at byte 16 * i, scattered to their planes' staged rows
+__device__ __forceinline__ void dw_scatter_chunk(const uint4& v, int i, int IH, int IW, int IHW, int8_t* dst, int psize,
+                                                 int pitch, int top, int left) {
+    const uint32_t d[4] = {v.x, v.y, v.z, v.w};
+    int pl = (16 * i) / IHW;
+    const int rem = 16 * i - pl * IHW;
+    int row = rem / IW, col = rem - row * IW;
+    int8_t* rowp = dst + pl * psize + (row + top) * pitch + left;
+    // (the byte loop is kept rolled: unrolled sixteen-fold in each of its callers it cost the kernels 100 registers)
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        uint32_t dw = d[w];
+#pragma unroll 1
+        for (int b = 0; b < 4; ++b) {
+            rowp[col] = (int8_t)dw;
+            dw >>= 8;
+            if (++col == IW) {
+                col = 0;
+                rowp += pitch;
+                if (++row == IH) {
+                    row = 0;
+                    rowp += psize - IH * pitch;
+                }
+            }
+        }
+    }
+}
+// The first two chunks of every thread are requested by dw_planes_fetch() at the top of the kernel, ahead of the
+// weights and of the zeroing of the staged area, and written by dw_planes_store(); blocks of at most
+// 32 * NT source bytes (every case with more than one plane but 28 x 28 planes by the dozen) need no further loads.
+template <int NT>
+__device__ __forceinline__ void dw_planes_fetch(const int8_t* __restrict__ src, int nch, uint4 (&regs)[2]) {
+    if (nch > 0) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int i = (int)threadIdx.x + u * NT;
+            regs[u] = reinterpret_cast<const uint4*>(src)[i < nch ? i : 0];     // (unconditional; the surplus is not stored)
+        }
+    }
+}
+template <int NT>
+__device__ __forceinline__ void dw_planes_store(const int8_t* __restrict__ src, int np, int nch, const uint4 (&regs)[2], int IH,
+                                                int IW, int8_t* dst, int rows, int pitch, int top, int left) {
+    const int psize = rows * pitch;
+    const int ndw = np * psize >> 2;          // pitch is a multiple of 4
+    for (int i = threadIdx.x; i < ndw; i += NT) reinterpret_cast<uint32_t*>(dst)[i] = 0u;
+    __syncthreads();
+    const int IHW = IH * IW, total = np * IHW;
+    if (nch > 0) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int i = (int)threadIdx.x + u * NT;
+            if (i < nch) dw_scatter_chunk(regs[u], i, IH, IW, IHW, dst, psize, pitch, top, left);
+        }
+        for (int i = (int)threadIdx.x + 2 * NT; i < nch; i += NT)
+            dw_scatter_chunk(reinterpret_cast<const uint4*>(src)[i], i, IH, IW, IHW, dst, psize, pitch, top, left);
+    } else {
+        for (int i = threadIdx.x; i < total; i += NT) {
+            const int pl = i / IHW, rem = i - pl * IHW;
+            const int row = rem / IW, col = rem - row * IW;
+            dst[pl * psize + (row + top) * pitch + col + left] = src[i];
+        }
+    }
+    __syncthreads();
+}
+
 // ST = 2 (forward only): the four outputs of a thread read windows that start two bytes apart, from
 // LDS row 2 * oh + r' and column 2 * ow; `rows` is the height of the staged area.
+constexpr int DW_MAX_PPB = 32;        // planes per block of the fast path, at most
+
 template <bool DGRAD, int SD, int NT, int ST = 1>    // SD = dwords of packed weights per filter row (S <= 4*SD)
-__global__ __launch_bounds__(NT) void dw_conv_fast_kernel(const DwArgs a, int pitch, int rows) {
+__global__ __launch_bounds__(NT) void dw_conv_fast_kernel(const DwArgs a, int pitch, int rows, int ppb) {
     static_assert(ST == 1 || (ST == 2 && !DGRAD), "the strided form is the forward pass at stride 2");
     extern __shared__ __attribute__((aligned(16))) int8_t plane[];
-    __shared__ uint32_t wrow[DW_FAST_MAXR][SD];
-    const int nc = blockIdx.x;
-    const int c = nc % a.C;
-    const int OHW = a.OH * a.OW, RS = a.R * a.S;
+    __shared__ uint32_t wrow[DW_MAX_PPB][DW_FAST_MAXR][SD];
+    const int nc0 = blockIdx.x * ppb;                            // the block's first plane (n * C + c)
+    const int np = a.N * a.C - nc0 < ppb ? a.N * a.C - nc0 : ppb;
+    const int OHW = a.OH * a.OW, RS = a.R * a.S, IHW = a.IH * a.IW;
+    const int psize = rows * pitch;
     const int top = DGRAD ? (a.R - 1 - a.pad_h) : a.pad_h;     // = -drmin
     const int left = DGRAD ? (a.S - 1 - a.pad_w) : a.pad_w;    // = -dsmin
-    if (threadIdx.x < a.R * SD) {
-        const int rp = threadIdx.x / SD, d = threadIdx.x - rp * SD;
+    const size_t src0 = (size_t)nc0 * IHW;
+    // 16-byte chunks of the block's source run, 0 when it is not a whole number of aligned chunks (uniform)
+    const int nch = (ppb > 1 && ((np * IHW) & 15) == 0 && (reinterpret_cast<uintptr_t>(a.a + src0) & 15) == 0) ? (np * IHW) >> 4 : 0;
+    uint4 pregs[2];
+    if (ppb > 1) dw_planes_fetch<NT>(a.a + src0, nch, pregs);
+    for (int i = threadIdx.x; i < np * a.R * SD; i += NT) {
+        const int pl = i / (a.R * SD), q = i - pl * (a.R * SD);
+        const int rp = q / SD, d = q - rp * SD;
+        const int c = (nc0 + pl) % a.C;
         uint32_t wv = 0;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
@@ -179,26 +265,32 @@ __global__ __launch_bounds__(NT) void dw_conv_fast_kernel(const DwArgs a, int pi
                 wv |= (uint32_t)(uint8_t)a.b[(size_t)c * RS + r * a.S + sx] << (8 * k);
             }
         }
-        wrow[rp][d] = wv;
+        wrow[pl][rp][d] = wv;
     }
-    dw_stage_plane<NT>(a.a + (size_t)nc * a.IH * a.IW, a.IH, a.IW, plane, rows, pitch, top, left);
+    if (ppb == 1) dw_stage_plane<NT>(a.a + src0, a.IH, a.IW, plane, rows, pitch, top, left);
+    else dw_planes_store<NT>(a.a + src0, np, nch, pregs, a.IH, a.IW, plane, rows, pitch, top, left);
 
     const float scale = __fmul_rn(a.sa[0], a.sb[0]);
     const int QW = (a.OW + 3) >> 2;
+    const int per = a.OH * QW;                                   // tasks of a plane: four results of a row each
     const bool vec = (a.OW & 3) == 0;
-    float* __restrict__ outp = a.out + (size_t)nc * OHW;
-    int32_t* __restrict__ accp = a.acc ? a.acc + (size_t)nc * OHW : nullptr;
-    for (int t = threadIdx.x; t < a.OH * QW; t += NT) {
-        const int oh = t / QW, ow = (t - oh * QW) << 2;
+    const bool small = per < 1024;                               // (then t < 32 * 1024 as well: dw_div_small is exact)
+    const float inv_per = 1.0f / (float)per, inv_qw = 1.0f / (float)QW;
+    for (int t = threadIdx.x; t < np * per; t += NT) {
+        const int pl = ppb == 1 ? 0 : small ? dw_div_small(t, inv_per) : t / per, tt = t - pl * per;
+        const int oh = small ? dw_div_small(tt, inv_qw) : tt / QW, ow = (tt - oh * QW) << 2;
+        const int8_t* __restrict__ pp = plane + pl * psize;
+        float* __restrict__ outp = a.out + (size_t)(nc0 + pl) * OHW;
+        int32_t* __restrict__ accp = a.acc ? a.acc + (size_t)(nc0 + pl) * OHW : nullptr;
         int sum[4] = {0, 0, 0, 0};
         for (int rp = 0; rp < a.R; ++rp) {
-            const uint32_t* __restrict__ rowp = reinterpret_cast<const uint32_t*>(plane + (ST * oh + rp) * pitch + ST * ow);
+            const uint32_t* __restrict__ rowp = reinterpret_cast<const uint32_t*>(pp + (ST * oh + rp) * pitch + ST * ow);
             uint32_t d[SD + ST];
 #pragma unroll
             for (int k = 0; k < SD + ST; ++k) d[k] = rowp[k];
 #pragma unroll
             for (int k = 0; k < SD; ++k) {
-                const uint32_t wv = wrow[rp][k];
+                const uint32_t wv = wrow[pl][rp][k];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     // output j's window starts ST * j bytes into the row segment
@@ -488,6 +580,113 @@ __global__ __launch_bounds__(NT) void dw_wgrad_fast_kernel(const DwArgs a, int p
     dw_block_sums_store<NT, R * S>(flat, red, part);
 }
 
+// Stride-1 backward-weight for small planes (14 x 14, 7 x 7): a block takes `cg` consecutive channels -- their planes
+// are one contiguous run of cg * IH * IW bytes per image -- and a share of the images; every thread owns one task (four
+// gradient codes of a row) of one channel for all images, the run of the next image is fetched into registers while
+// these images' dot products run (several images are staged per pass, see below); a channel's tasks sit in a group of `slot` lanes (a power of two, at most a wave), so
+// that its tap sums are reduced by lane exchanges (LDS atomics of 56 lanes on one address took longer than the pass).  With a block per
+// channel these planes are no whole 16-byte chunks (196, 49 bytes): each image cost eight memory round trips of
+// single-byte loads (384 channels at 14 x 14, batch 64: 23.7 us for 9.6 MB).
+// Host (dw_wgrad_shape): OH * ceil(OW / 4) <= slot <= 64, cg * slot <= 256 threads, cg * IH * IW and cg * OH * OW whole
+// 16-byte chunks and at most 512 of them together, cg <= 32 and a divisor of C.
+template <int R, int S>
+__global__ __launch_bounds__(256) void dw_wgrad_group_kernel(const DwArgs a, int pitch, int gpitch, int slot, int ni) {
+    constexpr int NT = 256, SD = (S + 3) / 4, RS = R * S;
+    extern __shared__ __attribute__((aligned(16))) int8_t lds[];
+    __shared__ int red[32 * RS];
+    const int cg = a.cg, c0 = blockIdx.x * cg, chunk = blockIdx.y;
+    const int IHW = a.IH * a.IW, OHW = a.OH * a.OW;
+    const int n0 = (int)(((long long)a.N * chunk) / a.chunks);
+    const int n1 = (int)(((long long)a.N * (chunk + 1)) / a.chunks);
+    const int xsize = ((a.OH + R - 1) * pitch + 15) & ~15, gsize = (a.OH * gpitch + 15) & ~15;
+    const int isize = cg * (xsize + gsize);                 // one image: cg input planes with zero borders, then cg gradient planes
+    for (int i = threadIdx.x; i < (ni * isize) >> 2; i += NT) reinterpret_cast<uint32_t*>(lds)[i] = 0u;
+    // `ni` images are staged per pass: their 2 * ni runs are ni * (nchx + nchg) chunks, at most two per thread
+    // (host), so that every thread takes part in the staging and a pass costs one memory round trip, not ni
+    const int nchx = (cg * IHW) >> 4, nchg = (cg * OHW) >> 4, nch = nchx + nchg;
+    const float inv_nch = 1.0f / (float)nch;
+    const int QW = (a.OW + 3) >> 2, per = a.OH * QW;
+    const int pl_raw = (int)threadIdx.x / slot, tt_raw = (int)threadIdx.x - pl_raw * slot;
+    const bool active = pl_raw < cg && tt_raw < per;
+    const int pl = active ? pl_raw : 0, tt = active ? tt_raw : 0;
+    const int p = tt / QW, q = (tt - p * QW) << 2;
+    int acc[R][S];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int sx = 0; sx < S; ++sx) acc[r][sx] = 0;
+    // chunk e of a pass that starts at image n: image n + e / nch, input chunk e % nch or gradient chunk e % nch - nchx
+    int ej[2], ei[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int e = (int)threadIdx.x + u * NT;
+        ej[u] = dw_div_small(e, inv_nch);
+        ei[u] = e - ej[u] * nch;
+    }
+    uint4 regs[2];
+    auto fetch = [&](int n) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const bool ok = ej[u] < ni && n + ej[u] < n1;
+            const size_t img = (size_t)(n + (ok ? ej[u] : 0)) * a.C + c0;
+            const uint4* src = ei[u] < nchx ? reinterpret_cast<const uint4*>(a.a + img * IHW) + ei[u]
+                                            : reinterpret_cast<const uint4*>(a.b + img * OHW) + (ei[u] - nchx);
+            regs[u] = *src;        // (unconditional: a chunk of the pass's first image when there is none; not stored)
+        }
+    };
+    if (n0 < n1) fetch(n0);
+    for (int n = n0; n < n1; n += ni) {
+        const int cnt = n1 - n < ni ? n1 - n : ni;
+        __syncthreads();   // the previous pass's reads (and the zero fill) are done
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            if (ej[u] < cnt) {
+                int8_t* base = lds + ej[u] * isize;
+                if (ei[u] < nchx) dw_scatter_chunk(regs[u], ei[u], a.IH, a.IW, IHW, base, xsize, pitch, a.pad_h, a.pad_w);
+                else dw_scatter_chunk(regs[u], ei[u] - nchx, a.OH, a.OW, OHW, base + cg * xsize, gsize, gpitch, 0, 0);
+            }
+        }
+        __syncthreads();
+        if (n + ni < n1) fetch(n + ni);
+        if (active) {
+            for (int j = 0; j < cnt; ++j) {
+                const int8_t* __restrict__ xs = lds + j * isize;
+                const int8_t* __restrict__ gs = xs + cg * xsize;
+                const int g4 = *reinterpret_cast<const int*>(gs + pl * gsize + p * gpitch + q);
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const uint32_t* __restrict__ rowp = reinterpret_cast<const uint32_t*>(xs + pl * xsize + (p + r) * pitch + q);
+                    uint32_t d[SD + 1];
+#pragma unroll
+                    for (int k = 0; k <= SD; ++k) d[k] = rowp[k];
+#pragma unroll
+                    for (int sx = 0; sx < S; ++sx) {
+                        const uint32_t win = (sx & 3) == 0 ? d[sx >> 2] : __builtin_amdgcn_alignbyte(d[(sx >> 2) + 1], d[sx >> 2], sx & 3);
+                        acc[r][sx] = __builtin_amdgcn_sdot4((int)win, g4, acc[r][sx], false);
+                    }
+                }
+            }
+        }
+    }
+    // sums over the lanes of a channel's group (inactive lanes hold zeros); its first lane leaves them in LDS
+    // (all R*S exchanges of a step are independent of each other: one LDS round trip per step, not per value)
+    for (int o = slot >> 1; o > 0; o >>= 1) {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int sx = 0; sx < S; ++sx) acc[r][sx] += __shfl_xor(acc[r][sx], o, kWave);
+    }
+    if (tt_raw == 0 && pl_raw < cg) {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int sx = 0; sx < S; ++sx) red[pl_raw * RS + r * S + sx] = acc[r][sx];
+    }
+    __syncthreads();
+    // [chunk][C][R*S]: the group's channels are consecutive
+    for (int i = threadIdx.x; i < cg * RS; i += NT) a.partial[((size_t)chunk * a.C + c0) * RS + i] = red[i];
+}
+
 __global__ __launch_bounds__(256) void dw_wgrad_reduce_kernel(const DwArgs a) {
     const int RS = a.R * a.S;
     const int total = a.C * RS;
@@ -516,11 +715,80 @@ int dw_wgrad_chunks(int N, int C, int threads) {
     return chunks;
 }
 
+static int dw_fast_pitch(int OW, int S);
+
+// lanes per channel in dw_wgrad_group_kernel: the tasks of a gradient plane, rounded up to a power of two
+static int dw_wgrad_slot(int P, int Q) {
+    const int per = P * ((Q + 3) / 4);
+    int slot = 4;
+    while (slot < per) slot *= 2;
+    return slot;
+}
+
+// consecutive channels per block of dw_wgrad_group_kernel, 1 where it does not apply
+static int dw_wgrad_group(int C, int IH, int IW, int P, int Q, int R, int S, int stride_h, int stride_w) {
+    if (stride_h != 1 || stride_w != 1 || R != S || (R != 3 && R != 5)) return 1;
+    const int per = P * ((Q + 3) / 4);
+    if (per > 64) return 1;
+    int cg = 256 / dw_wgrad_slot(P, Q);
+    if (cg > 32) cg = 32;
+    const int ihw = IH * IW, ohw = P * Q;
+    int m = 16;                          // smallest count that makes both runs whole 16-byte chunks
+    for (int g = ihw | ohw; m > 1 && g % 2 == 0; g /= 2) m /= 2;
+    cg = cg / m * m;
+    while (cg >= 2 && C % cg != 0) cg -= m;
+    if (cg < 2) return 1;
+    const size_t lds = (size_t)cg * ((((size_t)(P + R - 1) * dw_fast_pitch(Q, S) + 15) & ~(size_t)15) + (((size_t)P * ((Q + 3) & ~3) + 15) & ~(size_t)15));
+    if (lds > 32 * 1024 || (size_t)cg * (ihw + ohw) > 8192) return 1;      // (at most 512 chunks per image: two per thread)
+    return cg;
+}
+
+void dw_wgrad_shape(int N, int C, int IH, int IW, int P, int Q, int R, int S, int stride_h, int stride_w,
+                    int* threads, int* chunks, int* cg) {
+    *cg = dw_wgrad_group(C, IH, IW, P, Q, R, S, stride_h, stride_w);
+    if (*cg > 1) {
+        // about 1024 blocks of four waves: a block's fixed cost (staging set-up, the lane exchanges of its sums, its
+        // partial results) is paid once per share, and more shares than resident blocks add whole rounds of it
+        *threads = 256;
+        int ch = 1024 / (C / *cg);
+        *chunks = ch > N ? N : ch < 1 ? 1 : ch;
+    } else {
+        *threads = dw_wgrad_threads(P, Q, R, S, stride_h, stride_w);
+        *chunks = dw_wgrad_chunks(N, C, *threads);
+    }
+}
+
 // LDS row pitch of the fast path: the widest row read starts at column OW - 1 rounded down to 4 and
 // takes 4 * (SD + 1) bytes
 static int dw_fast_pitch(int OW, int S) {
     const int sd = (S + 3) / 4;
     return (((OW + 3) & ~3) + 4 * sd + 3) & ~3;
+}
+
+// Planes per block of the fast path: enough for about 256 tasks (four results of a row each) and, beyond that, for
+// the whole grid to be resident at once (2048 blocks of four waves: every block's loads are then on their way from
+// the start, instead of a second and third round of blocks each waiting out its own memory latency); a count that
+// makes the block's source bytes a whole number of 16-byte chunks where one of at most DW_MAX_PPB exists; at most
+// 48 KB of staged planes.
+static int dw_fast_ppb(int NC, int OH, int OW, int IH, int IW, size_t plane_lds) {
+    const int per = OH * ((OW + 3) / 4);
+    int ppb = (256 + per - 1) / per;
+    if (ppb > 1 || per < 512) {
+        const int resident = (NC + 2047) / 2048;
+        if (ppb < resident) ppb = resident;
+    }
+    if (ppb > DW_MAX_PPB) ppb = DW_MAX_PPB;
+    int g = IH * IW;                     // 16 / gcd(IH * IW, 16): planes per whole chunk run
+    int m = 16;
+    while (m > 1 && g % 2 == 0) { g /= 2; m /= 2; }
+    if (ppb > 1 && m <= DW_MAX_PPB) ppb = (ppb + m - 1) / m * m;
+    if (ppb > DW_MAX_PPB) ppb = DW_MAX_PPB;
+    while (ppb > 1 && (size_t)ppb * plane_lds > 48 * 1024) --ppb;
+    return ppb;
+}
+static int dw_fast_threads(int OH, int OW, int ppb) {
+    const long long tasks = (long long)ppb * OH * ((OW + 3) / 4);
+    return tasks <= 64 ? 64 : tasks <= 128 ? 128 : 256;
 }
 
 hipError_t launch_dw_conv(const DwArgs& a, hipStream_t st) {
@@ -558,14 +826,16 @@ hipError_t launch_dw_conv(const DwArgs& a, hipStream_t st) {
         pitch = (pitch + 3) & ~3;
         int rows = 2 * (a.OH - 1) + a.R;
         if (rows < a.pad_h + a.IH) rows = a.pad_h + a.IH;
-        const size_t lds = (size_t)rows * pitch;
-        if (lds <= 60 * 1024) {
-            const int nt = dw_threads(a.OH, a.OW, true);
+        const size_t lds1 = (size_t)rows * pitch;
+        if (lds1 <= 60 * 1024) {
+            const int ppb = dw_fast_ppb(a.N * a.C, a.OH, a.OW, a.IH, a.IW, lds1), nt = dw_fast_threads(a.OH, a.OW, ppb);
+            const size_t lds = lds1 * ppb;
+            const dim3 grid((unsigned)((a.N * a.C + ppb - 1) / ppb));
 #define FAST2(SDv)                                                                                                       \
     do {                                                                                                                 \
-        if (nt == 64) launch_timed(kt, (dw_conv_fast_kernel<false, SDv, 64, 2>), dim3(a.N * a.C), dim3(64), lds, st, a, pitch, rows);        \
-        else if (nt == 128) launch_timed(kt, (dw_conv_fast_kernel<false, SDv, 128, 2>), dim3(a.N * a.C), dim3(128), lds, st, a, pitch, rows); \
-        else launch_timed(kt, (dw_conv_fast_kernel<false, SDv, 256, 2>), dim3(a.N * a.C), dim3(256), lds, st, a, pitch, rows);               \
+        if (nt == 64) launch_timed(kt, (dw_conv_fast_kernel<false, SDv, 64, 2>), grid, dim3(64), lds, st, a, pitch, rows, ppb);        \
+        else if (nt == 128) launch_timed(kt, (dw_conv_fast_kernel<false, SDv, 128, 2>), grid, dim3(128), lds, st, a, pitch, rows, ppb); \
+        else launch_timed(kt, (dw_conv_fast_kernel<false, SDv, 256, 2>), grid, dim3(256), lds, st, a, pitch, rows, ppb);               \
     } while (0)
             if (a.S > 4) FAST2(2); else FAST2(1);
 #undef FAST2
@@ -575,15 +845,17 @@ hipError_t launch_dw_conv(const DwArgs& a, hipStream_t st) {
     if (a.stride_h == 1 && a.stride_w == 1 && a.S <= 8 && a.R <= DW_FAST_MAXR &&
         (a.dgrad ? (a.pad_h <= a.R - 1 && a.pad_w <= a.S - 1) : true)) {
         const int pitch = dw_fast_pitch(a.OW, a.S);
-        const size_t lds = (size_t)(a.OH + a.R - 1) * pitch;
-        if (lds <= 60 * 1024) {
+        const size_t lds1 = (size_t)(a.OH + a.R - 1) * pitch;
+        if (lds1 <= 60 * 1024) {
             const bool two = a.S > 4;
-            const int nt = dw_threads(a.OH, a.OW, true);
+            const int ppb = dw_fast_ppb(a.N * a.C, a.OH, a.OW, a.IH, a.IW, lds1), nt = dw_fast_threads(a.OH, a.OW, ppb);
+            const size_t lds = lds1 * ppb;
+            const dim3 grid((unsigned)((a.N * a.C + ppb - 1) / ppb));
 #define FAST(DG, SDv)                                                                                              \
     do {                                                                                                           \
-        if (nt == 64) launch_timed(kt, (dw_conv_fast_kernel<DG, SDv, 64>), dim3(a.N * a.C), dim3(64), lds, st, a, pitch, a.OH + a.R - 1);        \
-        else if (nt == 128) launch_timed(kt, (dw_conv_fast_kernel<DG, SDv, 128>), dim3(a.N * a.C), dim3(128), lds, st, a, pitch, a.OH + a.R - 1); \
-        else launch_timed(kt, (dw_conv_fast_kernel<DG, SDv, 256>), dim3(a.N * a.C), dim3(256), lds, st, a, pitch, a.OH + a.R - 1);               \
+        if (nt == 64) launch_timed(kt, (dw_conv_fast_kernel<DG, SDv, 64>), grid, dim3(64), lds, st, a, pitch, a.OH + a.R - 1, ppb);        \
+        else if (nt == 128) launch_timed(kt, (dw_conv_fast_kernel<DG, SDv, 128>), grid, dim3(128), lds, st, a, pitch, a.OH + a.R - 1, ppb); \
+        else launch_timed(kt, (dw_conv_fast_kernel<DG, SDv, 256>), grid, dim3(256), lds, st, a, pitch, a.OH + a.R - 1, ppb);               \
     } while (0)
             if (a.dgrad) {
                 if (two) FAST(true, 2); else FAST(true, 1);
@@ -622,7 +894,21 @@ hipError_t launch_dw_wgrad(const DwArgs& a, hipStream_t st) {
     {
         KernelTimer kt(KID_DW_WGRAD, st);
         bool fast = false;
-        if (a.stride_h == 1 && a.stride_w == 1 && a.R == a.S && (a.R == 3 || a.R == 5)) {
+        if (a.cg > 1) {
+            const int pitch = dw_fast_pitch(a.OW, a.S), gpitch = (a.OW + 3) & ~3;
+            const size_t ldsg = (size_t)a.cg * ((((size_t)(a.OH + a.R - 1) * pitch + 15) & ~(size_t)15) + (((size_t)a.OH * gpitch + 15) & ~(size_t)15));
+            const dim3 grid((unsigned)(a.C / a.cg), (unsigned)a.chunks);
+            const int slot = dw_wgrad_slot(a.OH, a.OW);
+            // images staged per pass: as many as two chunks per thread and 32 KB of LDS hold, at most 8
+            const int nch = (a.cg * a.IH * a.IW + a.cg * a.OH * a.OW) >> 4;
+            int ni = 512 / nch;
+            if (ni > 8) ni = 8;
+            while (ni > 1 && (size_t)ni * ldsg > 32 * 1024) --ni;
+            if (ni < 1) ni = 1;
+            if (a.R == 3) launch_timed(kt, (dw_wgrad_group_kernel<3, 3>), grid, dim3(256), ldsg * ni, st, a, pitch, gpitch, slot, ni);
+            else launch_timed(kt, (dw_wgrad_group_kernel<5, 5>), grid, dim3(256), ldsg * ni, st, a, pitch, gpitch, slot, ni);
+            fast = true;
+        } else if (a.stride_h == 1 && a.stride_w == 1 && a.R == a.S && (a.R == 3 || a.R == 5)) {
             // here IH x IW is the input plane and OH x OW the gradient plane
             const int pitch = dw_fast_pitch(a.OW, a.S), gpitch = (a.OW + 3) & ~3;
             const size_t ldsf = (((size_t)(a.OH + a.R - 1) * pitch + 15) & ~(size_t)15) + (size_t)a.OH * gpitch;

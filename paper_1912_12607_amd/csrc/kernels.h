@@ -247,8 +247,9 @@ struct DwArgs {
     float* out;
     int32_t* acc;                // nullable
     int32_t* partial;            // bwd-weight scratch [chunks][C*R*S]
-    int chunks;                  // bwd-weight: dw_wgrad_chunks(N, C, threads)
-    int threads;                 // bwd-weight: dw_wgrad_threads() of the layer
+    int chunks;                  // bwd-weight: shares of the batch, dw_wgrad_shape()
+    int threads;                 // bwd-weight: block size, dw_wgrad_shape()
+    int cg;                      // bwd-weight: consecutive channels per block (1: a block per channel), dw_wgrad_shape()
     int N, C, IH, IW, OH, OW, R, S;
     int stride_h, stride_w, pad_h, pad_w;
     int dgrad;
@@ -256,6 +257,9 @@ struct DwArgs {
 int dw_threads(int OH, int OW, bool quads);       // block size by plane size (quads: four results per task)
 int dw_wgrad_threads(int P, int Q, int R, int S, int stride_h, int stride_w);
 int dw_wgrad_chunks(int N, int C, int threads);
+// launch shape of the depthwise backward-weight pass (its scratch is chunks * C * R * S int32)
+void dw_wgrad_shape(int N, int C, int IH, int IW, int P, int Q, int R, int S, int stride_h, int stride_w,
+                    int* threads, int* chunks, int* cg);
 hipError_t launch_dw_conv(const DwArgs& a, hipStream_t st);
 hipError_t launch_dw_wgrad(const DwArgs& a, hipStream_t st);
 

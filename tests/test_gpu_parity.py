@@ -300,6 +300,18 @@ CONV_SHAPES = [
     (2, 6, 8, 12, 6, 3, 5, (1, 1), (1, 2), 6),         # depthwise stride 1, 5-wide filter, row length a multiple of 4
     (1, 4, 10, 11, 4, 3, 3, (1, 1), (0, 0), 4),        # depthwise stride 1, no padding
     (3, 5, 16, 16, 5, 3, 3, (1, 1), (1, 1), 5),        # depthwise, plane size a multiple of 16
+    # small depthwise planes: a block takes several consecutive planes (whole and partial groups, aligned and not)
+    (3, 20, 7, 7, 20, 3, 3, (1, 1), (1, 1), 20),
+    (2, 10, 14, 14, 10, 3, 3, (1, 1), (1, 1), 10),
+    (2, 10, 14, 14, 10, 3, 3, (2, 2), (1, 1), 10),
+    (2, 9, 7, 7, 9, 5, 5, (1, 1), (2, 2), 9),
+    (1, 7, 28, 28, 7, 3, 3, (1, 1), (1, 1), 7),
+    # ... backward-weight with several channels per block and several images per pass
+    (3, 32, 7, 7, 32, 3, 3, (1, 1), (1, 1), 32),
+    (2, 12, 14, 14, 12, 3, 3, (1, 1), (1, 1), 12),
+    (2, 16, 7, 7, 16, 5, 5, (1, 1), (2, 2), 16),
+    (2, 8, 12, 10, 8, 3, 3, (1, 1), (0, 1), 8),        # gradient plane smaller than the input plane
+    (64, 384, 14, 14, 384, 3, 3, (1, 1), (1, 1), 384), # a share of more images than one pass stages
     # small filter banks with an even number of channel granules (weights held in registers)
     (2, 64, 7, 20, 64, 3, 3, (1, 1), (1, 1), 1),
     (3, 32, 9, 13, 40, 3, 3, (1, 1), (1, 1), 1),
