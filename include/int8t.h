@@ -358,7 +358,7 @@ int8t_variant int8t_conv_selected_variant(int8t_op op, const int8t_conv_desc *de
  *            "deviation_finish_kernel", "igemm_kernel", "igemm_dma_kernel", "igemm_fused_kernel", "igemm_reduce_kernel",
  *            "band_kernel", "band_reg_kernel", "wgrad_kernel", "wgrad_lines_kernel", "wgrad_reduce_kernel", "s2d_repack_kernel",
  *            "s2d_weights_kernel", "dw_conv_kernel" (every depthwise forward / backward-data variant),
- *            "dw_wgrad_kernel" (both depthwise backward-weight variants), "dw_wgrad_reduce_kernel");
+ *            "dw_wgrad_kernel" (every depthwise backward-weight variant), "dw_wgrad_reduce_kernel");
  *            NULL or "" selects every kernel.
  *            An unknown name returns INT8T_ERR_ARG and leaves timing off.
  * int8t_profile_stop waits for the recorded events, writes one entry per kernel that was
