@@ -90,7 +90,23 @@ template <int NT>
 __device__ __forceinline__ void dw_fill_plane(const int8_t* __restrict__ src, int IH, int IW, int8_t* dst,
                                               int pitch, int top, int left) {
     const int IHW = IH * IW;
-    if ((IHW & 15) == 0) {
+    if ((IHW & 15) == 0 && ((IW | left | pitch) & 3) == 0) {
+        // rows of whole dwords at a dword-aligned place: four 4-byte stores per chunk (none straddles a row)
+        for (int i = threadIdx.x; i < (IHW >> 4); i += NT) {
+            const uint4 v = reinterpret_cast<const uint4*>(src)[i];
+            const uint32_t d[4] = {v.x, v.y, v.z, v.w};
+            int row = (16 * i) / IW, col = 16 * i - row * IW;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                *reinterpret_cast<uint32_t*>(dst + (row + top) * pitch + col + left) = d[w];
+                col += 4;
+                if (col == IW) {
+                    col = 0;
+                    ++row;
+                }
+            }
+        }
+    } else if ((IHW & 15) == 0) {
         // 16 source bytes per thread and pass; row / column advance without divisions
         for (int i = threadIdx.x; i < (IHW >> 4); i += NT) {
             const uint4 v = reinterpret_cast<const uint4*>(src)[i];
@@ -133,12 +149,24 @@ __device__ __forceinline__ void dw_plane_store(const uint4 (&regs)[CPT], int IHW
         if (i < (IHW >> 4)) {
             const uint32_t d[4] = {regs[u].x, regs[u].y, regs[u].z, regs[u].w};
             int row = (16 * i) / IW, col = 16 * i - row * IW;
+            if (((IW | left | pitch) & 3) == 0) {      // (uniform) whole dwords at a dword-aligned place
 #pragma unroll
-            for (int k = 0; k < 16; ++k) {
-                dst[(row + top) * pitch + col + left] = (int8_t)(d[k >> 2] >> (8 * (k & 3)));
-                if (++col == IW) {
-                    col = 0;
-                    ++row;
+                for (int w = 0; w < 4; ++w) {
+                    *reinterpret_cast<uint32_t*>(dst + (row + top) * pitch + col + left) = d[w];
+                    col += 4;
+                    if (col == IW) {
+                        col = 0;
+                        ++row;
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int k = 0; k < 16; ++k) {
+                    dst[(row + top) * pitch + col + left] = (int8_t)(d[k >> 2] >> (8 * (k & 3)));
+                    if (++col == IW) {
+                        col = 0;
+                        ++row;
+                    }
                 }
             }
         }
@@ -441,6 +469,7 @@ template <int NT>
 __global__ __launch_bounds__(NT) void dw_wgrad_kernel(const DwArgs a) {
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
     __shared__ int red[4];
+    __shared__ int red9[(NT / 64) * 9];
     const int c = blockIdx.x, chunk = blockIdx.y;
     const int IHW = a.IH * a.IW, OHW = a.OH * a.OW, RS = a.R * a.S;
     const int n0 = (int)(((long long)a.N * chunk) / a.chunks);
@@ -458,8 +487,18 @@ __global__ __launch_bounds__(NT) void dw_wgrad_kernel(const DwArgs a) {
             const int8_t* __restrict__ xsrc = a.a + ((size_t)n * a.C + c) * IHW;
             const int8_t* __restrict__ gsrc = a.b + ((size_t)n * a.C + c) * OHW;
             __syncthreads();
-            for (int i = threadIdx.x; i < IHW; i += NT) xs[i] = xsrc[i];
-            for (int i = threadIdx.x; i < OHW; i += NT) gs[i] = gsrc[i];
+            // (planes of whole 16-byte chunks -- the planes are 16-byte aligned then -- move as such: a 112 x 112 plane
+            // was 49 rounds of single-byte loads)
+            if ((IHW & 15) == 0) {
+                for (int i = threadIdx.x; i < (IHW >> 4); i += NT) reinterpret_cast<uint4*>(xs)[i] = reinterpret_cast<const uint4*>(xsrc)[i];
+            } else {
+                for (int i = threadIdx.x; i < IHW; i += NT) xs[i] = xsrc[i];
+            }
+            if ((OHW & 15) == 0) {
+                for (int i = threadIdx.x; i < (OHW >> 4); i += NT) reinterpret_cast<uint4*>(gs)[i] = reinterpret_cast<const uint4*>(gsrc)[i];
+            } else {
+                for (int i = threadIdx.x; i < OHW; i += NT) gs[i] = gsrc[i];
+            }
             __syncthreads();
             for (int o = threadIdx.x; o < OHW; o += NT) {
                 const int p = o / a.OW, q = o - p * a.OW;
@@ -476,8 +515,7 @@ __global__ __launch_bounds__(NT) void dw_wgrad_kernel(const DwArgs a) {
                 }
             }
         }
-#pragma unroll
-        for (int i = 0; i < 9; ++i) dw_block_sum_store<NT>(acc9[i], red, part + i);
+        dw_block_sums_store<NT, 9>(acc9, red9, part);
     } else {
         // other filter sizes: one tap at a time, straight from global memory
         for (int rs = 0; rs < RS; ++rs) {
@@ -506,7 +544,10 @@ __global__ __launch_bounds__(NT) void dw_wgrad_kernel(const DwArgs a) {
 // planes are fetched into registers while this image's dot products run.  A template flag, so that the
 // other instantiations do not carry the registers (64-thread blocks on 7 x 7 planes fell from many to two
 // waves per SIMD when it was a run-time choice).
-template <int R, int S, int NT, bool PF>
+// OFF: the input plane is staged OFF bytes further right than its padding asks (OFF = 4 - pad_w for rows of whole
+// dwords, else 0), so that its rows start on a dword of LDS and are written four bytes at a time: the byte-by-byte
+// scatter was most of this kernel's vector-ALU work.  Tap s of output column q then starts at LDS column q + OFF + s.
+template <int R, int S, int NT, bool PF, int OFF>
 __global__ __launch_bounds__(NT) void dw_wgrad_fast_kernel(const DwArgs a, int pitch, int gpitch) {
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
     __shared__ int red[(NT / 64) * R * S];
@@ -544,10 +585,10 @@ __global__ __launch_bounds__(NT) void dw_wgrad_fast_kernel(const DwArgs a, int p
         const int8_t* __restrict__ gsrc = a.b + ((size_t)n * a.C + c) * OHW;
         __syncthreads();   // the previous image's reads (and the zero fill) are done
         if (pf) {
-            dw_plane_store<NT, DW_PF>(px, IHW, a.IW, xs, pitch, a.pad_h, a.pad_w);
+            dw_plane_store<NT, DW_PF>(px, IHW, a.IW, xs, pitch, a.pad_h, a.pad_w + OFF);
             dw_plane_store<NT, DW_PF>(pg, OHW, a.OW, gs, gpitch, 0, 0);
         } else {
-            dw_fill_plane<NT>(xsrc, a.IH, a.IW, xs, pitch, a.pad_h, a.pad_w);
+            dw_fill_plane<NT>(xsrc, a.IH, a.IW, xs, pitch, a.pad_h, a.pad_w + OFF);
             dw_fill_plane<NT>(gsrc, a.OH, a.OW, gs, gpitch, 0, 0);
         }
         __syncthreads();
@@ -561,12 +602,14 @@ __global__ __launch_bounds__(NT) void dw_wgrad_fast_kernel(const DwArgs a, int p
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const uint32_t* __restrict__ rowp = reinterpret_cast<const uint32_t*>(xs + (p + r) * pitch + q);
-                uint32_t d[SD + 1];
+                constexpr int ND = ((OFF + S - 1) >> 2) + 2;      // dwords that hold the windows of the four outputs
+                uint32_t d[ND];
 #pragma unroll
-                for (int k = 0; k <= SD; ++k) d[k] = rowp[k];
+                for (int k = 0; k < ND; ++k) d[k] = rowp[k];
 #pragma unroll
                 for (int sx = 0; sx < S; ++sx) {
-                    const uint32_t win = (sx & 3) == 0 ? d[sx >> 2] : __builtin_amdgcn_alignbyte(d[(sx >> 2) + 1], d[sx >> 2], sx & 3);
+                    const int o = OFF + sx;
+                    const uint32_t win = (o & 3) == 0 ? d[o >> 2] : __builtin_amdgcn_alignbyte(d[(o >> 2) + 1], d[o >> 2], o & 3);
                     acc[r][sx] = __builtin_amdgcn_sdot4((int)win, g4, acc[r][sx], false);
                 }
             }
@@ -687,15 +730,21 @@ __global__ __launch_bounds__(256) void dw_wgrad_group_kernel(const DwArgs a, int
     for (int i = threadIdx.x; i < cg * RS; i += NT) a.partial[((size_t)chunk * a.C + c0) * RS + i] = red[i];
 }
 
+// 16 lanes per result: each adds every 16th share, then the lanes are summed (integer sums: any order is exact).
+// With one thread per result a layer of 32 channels and 64 shares was one block walking 64 dependent loads: 15.5 us.
 __global__ __launch_bounds__(256) void dw_wgrad_reduce_kernel(const DwArgs a) {
     const int RS = a.R * a.S;
     const int total = a.C * RS;
-    const int t = blockIdx.x * 256 + threadIdx.x;
-    if (t >= total) return;
+    const int t = (blockIdx.x * 256 + threadIdx.x) >> 4, sub = threadIdx.x & 15;
     int sum = 0;
-    for (int z = 0; z < a.chunks; ++z) sum += a.partial[(size_t)z * total + t];
-    a.out[t] = __fmul_rn((float)sum, __fmul_rn(a.sa[0], a.sb[0]));
-    if (a.acc) a.acc[t] = sum;
+    if (t < total)
+        for (int z = sub; z < a.chunks; z += 16) sum += a.partial[(size_t)z * total + t];
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) sum += __shfl_xor(sum, o, kWave);
+    if (t < total && sub == 0) {
+        a.out[t] = __fmul_rn((float)sum, __fmul_rn(a.sa[0], a.sb[0]));
+        if (a.acc) a.acc[t] = sum;
+    }
 }
 
 // Threads per block of the depthwise kernels: a plane of OH x OW results is OH * ceil(OW / 4) tasks in
@@ -910,20 +959,27 @@ hipError_t launch_dw_wgrad(const DwArgs& a, hipStream_t st) {
             fast = true;
         } else if (a.stride_h == 1 && a.stride_w == 1 && a.R == a.S && (a.R == 3 || a.R == 5)) {
             // here IH x IW is the input plane and OH x OW the gradient plane
-            const int pitch = dw_fast_pitch(a.OW, a.S), gpitch = (a.OW + 3) & ~3;
+            // rows of whole dwords under "same" padding: staged from a dword boundary (OFF = 4 - pad_w, one more dword per row)
+            const bool al = (a.IW & 3) == 0 && a.pad_w == a.S / 2 && a.pad_w > 0;
+            const int pitch = dw_fast_pitch(a.OW, a.S) + (al ? 4 : 0), gpitch = (a.OW + 3) & ~3;
             const size_t ldsf = (((size_t)(a.OH + a.R - 1) * pitch + 15) & ~(size_t)15) + (size_t)a.OH * gpitch;
             if (ldsf <= 60 * 1024) {
                 fast = true;
-#define WFAST(Rv, PFv)                                                                                                \
+#define WFAST(Rv, PFv, OFFv)                                                                                                \
     do {                                                                                                            \
-        if (a.threads == 64) launch_timed(kt, (dw_wgrad_fast_kernel<Rv, Rv, 64, PFv>), dim3(a.C, a.chunks), dim3(64), ldsf, st, a, pitch, gpitch);        \
-        else if (a.threads == 128) launch_timed(kt, (dw_wgrad_fast_kernel<Rv, Rv, 128, PFv>), dim3(a.C, a.chunks), dim3(128), ldsf, st, a, pitch, gpitch); \
-        else launch_timed(kt, (dw_wgrad_fast_kernel<Rv, Rv, 256, PFv>), dim3(a.C, a.chunks), dim3(256), ldsf, st, a, pitch, gpitch);                      \
+        if (a.threads == 64) launch_timed(kt, (dw_wgrad_fast_kernel<Rv, Rv, 64, PFv, OFFv>), dim3(a.C, a.chunks), dim3(64), ldsf, st, a, pitch, gpitch);        \
+        else if (a.threads == 128) launch_timed(kt, (dw_wgrad_fast_kernel<Rv, Rv, 128, PFv, OFFv>), dim3(a.C, a.chunks), dim3(128), ldsf, st, a, pitch, gpitch); \
+        else launch_timed(kt, (dw_wgrad_fast_kernel<Rv, Rv, 256, PFv, OFFv>), dim3(a.C, a.chunks), dim3(256), ldsf, st, a, pitch, gpitch);                      \
     } while (0)
                 const int ihw = a.IH * a.IW, ohw = a.OH * a.OW;
                 const bool pf = (ihw & 15) == 0 && (ohw & 15) == 0 && ihw <= 4096 && ohw <= 4096;
-                if (pf) { if (a.R == 3) WFAST(3, true); else WFAST(5, true); }
-                else { if (a.R == 3) WFAST(3, false); else WFAST(5, false); }
+                if (a.R == 3) {
+                    if (pf) { if (al) WFAST(3, true, 3); else WFAST(3, true, 0); }
+                    else { if (al) WFAST(3, false, 3); else WFAST(3, false, 0); }
+                } else {
+                    if (pf) { if (al) WFAST(5, true, 2); else WFAST(5, true, 0); }
+                    else { if (al) WFAST(5, false, 2); else WFAST(5, false, 0); }
+                }
 #undef WFAST
             }
         }
@@ -937,7 +993,7 @@ hipError_t launch_dw_wgrad(const DwArgs& a, hipStream_t st) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int total = a.C * a.R * a.S;
-    { KernelTimer kt(KID_DW_WGRAD_REDUCE, st); launch_timed(kt, dw_wgrad_reduce_kernel, dim3((total + 255) / 256), dim3(256), 0, st, a); }
+    { KernelTimer kt(KID_DW_WGRAD_REDUCE, st); launch_timed(kt, dw_wgrad_reduce_kernel, dim3((total * 16 + 255) / 256), dim3(256), 0, st, a); }
     return hipGetLastError();
 }
 
