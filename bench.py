@@ -157,6 +157,8 @@ def main():
                     help="also time the step of every ResNet-50 convolution and its classifier at this batch "
                          "(Fig.10's workload) and print the per-layer table and the network total (stderr)")
     ap.add_argument("--mobilenetv2", type=int, default=0, metavar="BATCH", help="the same for every convolution of MobileNetV2")
+    ap.add_argument("--fused-forward", action="store_true",
+                    help="also time quantize(a, W) + forward against the fused forward (int8t_conv_fwd_fused) on 1x1 layers (stderr)")
     ap.add_argument("--inceptionv3", type=int, default=0, metavar="BATCH",
                     help="the same for one layer of each kind in InceptionV3 (no network total: not every layer is listed)")
     args = ap.parse_args()
@@ -420,6 +422,47 @@ def main():
         print(json.dumps({"network": title, "batch": batch, "ms_per_iteration": round(total_ms, 3),
                           "TOPS": round(total_ops / total_ms / 1e9, 1),
                           "images_per_s": round(batch / total_ms * 1e3, 1)}), file=sys.stderr, flush=True)
+
+    if args.fused_forward:
+        # the quantization-convolution fused kernel (Suppl. "INT8 Convolution") against the separate passes:
+        # 1x1 stride-1 layers, one stream, wall clock over 300 repetitions after 150 untimed ones
+        def timeit(fn, reps=300):
+            for _ in range(150):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / reps * 1e6
+
+        def r50(C, HW, K):
+            return inputs.Layer("r50_1x1", 64, C, HW, HW, K, 1, 1, x_dist="relu", dy_scale=1e-4)
+        cases = [("config 3 layer 2 (MobileNetV2 144 -> 24, 56x56, N=64)", inputs.CONFIGS[3][2], 3, 2),
+                 ("config 3 layer 0 (MobileNetV2 24 -> 144, 56x56, N=64)", inputs.CONFIGS[3][0], 3, 0),
+                 ("config 2 layer 0 (ResNet-50 1024 -> 256, 14x14, N=128)", inputs.CONFIGS[2][0], 2, 0),
+                 ("config 2 layer 2 (ResNet-50 256 -> 1024, 14x14, N=128)", inputs.CONFIGS[2][2], 2, 2),
+                 ("ResNet-50 256 -> 64, 56x56, N=64", r50(256, 56, 64), 7, 0),
+                 ("ResNet-50 64 -> 64, 56x56, N=64", r50(64, 56, 64), 7, 1),
+                 ("ResNet-50 512 -> 128, 28x28, N=64", r50(512, 28, 128), 7, 2)]
+        for name, Lx, cfg_i, li_i in cases:
+            xx, ww, dd = inputs.make_x(Lx, cfg_i, li_i), inputs.make_w(Lx, cfg_i, li_i), inputs.make_dy(Lx, cfg_i, li_i)
+            res = {}
+            for fused in (False, True):
+                st = LayerStep(Lx, requantize_deviation=False, fused_fwd=fused)
+                st.upload(xx, ww, dd, ratios)
+                st.run(seed=0, overlap=False)
+                torch.cuda.synchronize()
+                sp = B.stream_pointer(None)
+                if fused:
+                    chain = lambda: (st._k_w(sp), st._k_fwd_fused(sp))
+                else:
+                    chain = lambda: (st._k_xw(sp), st._k_fwd(sp))
+                res[fused] = (timeit(chain), timeit(lambda: st.run(seed=1, overlap=False)))
+                del st
+            print(json.dumps({"layer": name, "quantize_aW_plus_fwd_us": round(res[False][0], 1), "fused_us": round(res[True][0], 1),
+                              "whole_step_us": round(res[False][1], 1), "whole_step_fused_fwd_us": round(res[True][1], 1)}),
+                  file=sys.stderr, flush=True)
 
     if args.resnet50 > 0:
         sweep("ResNet-50 convolutions + classifier", args.resnet50, inputs.resnet50_layers(args.resnet50), 50)
