@@ -547,8 +547,12 @@ __global__ __launch_bounds__(NT) void dw_wgrad_kernel(const DwArgs a) {
 // OFF: the input plane is staged OFF bytes further right than its padding asks (OFF = 4 - pad_w for rows of whole
 // dwords, else 0), so that its rows start on a dword of LDS and are written four bytes at a time: the byte-by-byte
 // scatter was most of this kernel's vector-ALU work.  Tap s of output column q then starts at LDS column q + OFF + s.
-template <int R, int S, int NT, bool PF, int OFF>
-__global__ __launch_bounds__(NT) void dw_wgrad_fast_kernel(const DwArgs a, int pitch, int gpitch) {
+// ST = 2: the four gradient codes of a task meet input codes two bytes apart (LDS row 2 p + r, columns 2 q + OFF + s + 2 j):
+// the seven bytes they span are cut out of the row's dwords by two byte-aligns and every other one picked by a byte
+// permute -- three instructions and a dot product per tap and four results, where the generic kernel spends some
+// seven per product on index arithmetic and bounds tests (96 channels at 112 x 112, batch 64: 62 us, compute-bound).
+template <int R, int S, int NT, bool PF, int OFF, int ST = 1>
+__global__ __launch_bounds__(NT) void dw_wgrad_fast_kernel(const DwArgs a, int pitch, int gpitch, int xrows) {
     extern __shared__ __attribute__((aligned(16))) int8_t lds[];
     __shared__ int red[(NT / 64) * R * S];
     constexpr int SD = (S + 3) / 4;
@@ -557,8 +561,7 @@ __global__ __launch_bounds__(NT) void dw_wgrad_fast_kernel(const DwArgs a, int p
     const int n0 = (int)(((long long)a.N * chunk) / a.chunks);
     const int n1 = (int)(((long long)a.N * (chunk + 1)) / a.chunks);
     int32_t* __restrict__ part = a.partial + ((size_t)chunk * a.C + c) * (R * S);
-    const int xrows = a.OH + R - 1;
-    int8_t* xs = lds;                                   // (OH + R - 1) x pitch, zero border
+    int8_t* xs = lds;                                   // xrows x pitch (stride 1: OH + R - 1 rows), zero border
     int8_t* gs = lds + ((xrows * pitch + 15) & ~15);    // OH x gpitch, zero tail columns
     {
         const int ndw = (((xrows * pitch + 15) & ~15) + a.OH * gpitch) >> 2;
@@ -601,15 +604,24 @@ __global__ __launch_bounds__(NT) void dw_wgrad_fast_kernel(const DwArgs a, int p
             const int g4 = *reinterpret_cast<const int*>(gs + p * gpitch + q);
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                const uint32_t* __restrict__ rowp = reinterpret_cast<const uint32_t*>(xs + (p + r) * pitch + q);
-                constexpr int ND = ((OFF + S - 1) >> 2) + 2;      // dwords that hold the windows of the four outputs
+                const uint32_t* __restrict__ rowp = reinterpret_cast<const uint32_t*>(xs + (ST * p + r) * pitch + ST * q);
+                constexpr int ND = ST == 2 ? 4 : ((OFF + S - 1) >> 2) + 2;      // dwords that hold the windows of the four outputs
+                static_assert(ST == 1 || ((OFF + S - 1) >> 2) + 2 <= 3, "stride 2: the windows end inside the fourth dword");
                 uint32_t d[ND];
 #pragma unroll
                 for (int k = 0; k < ND; ++k) d[k] = rowp[k];
 #pragma unroll
                 for (int sx = 0; sx < S; ++sx) {
                     const int o = OFF + sx;
-                    const uint32_t win = (o & 3) == 0 ? d[o >> 2] : __builtin_amdgcn_alignbyte(d[(o >> 2) + 1], d[o >> 2], o & 3);
+                    uint32_t win;
+                    if (ST == 1) {
+                        win = (o & 3) == 0 ? d[o >> 2] : __builtin_amdgcn_alignbyte(d[(o >> 2) + 1], d[o >> 2], o & 3);
+                    } else {
+                        const int k0 = o >> 2, sh = o & 3;
+                        const uint32_t lo = sh == 0 ? d[k0] : __builtin_amdgcn_alignbyte(d[k0 + 1], d[k0], sh);          // bytes o .. o + 3
+                        const uint32_t hi = sh == 0 ? d[k0 + 1] : __builtin_amdgcn_alignbyte(d[k0 + 2], d[k0 + 1], sh);  // bytes o + 4 .. o + 7
+                        win = __builtin_amdgcn_perm(hi, lo, 0x06040200u);                                                // bytes o, o + 2, o + 4, o + 6
+                    }
                     acc[r][sx] = __builtin_amdgcn_sdot4((int)win, g4, acc[r][sx], false);
                 }
             }
@@ -935,7 +947,7 @@ hipError_t launch_dw_conv(const DwArgs& a, hipStream_t st) {
 
 // block size of the backward-weight pass: its tasks are the gradient plane's results, in quads on the stride-1 path
 int dw_wgrad_threads(int P, int Q, int R, int S, int stride_h, int stride_w) {
-    const bool fast = stride_h == 1 && stride_w == 1 && R == S && (R == 3 || R == 5);
+    const bool fast = stride_h == stride_w && (stride_h == 1 || stride_h == 2) && R == S && (R == 3 || R == 5);
     return dw_threads(P, Q, fast);
 }
 
@@ -957,28 +969,46 @@ hipError_t launch_dw_wgrad(const DwArgs& a, hipStream_t st) {
             if (a.R == 3) launch_timed(kt, (dw_wgrad_group_kernel<3, 3>), grid, dim3(256), ldsg * ni, st, a, pitch, gpitch, slot, ni);
             else launch_timed(kt, (dw_wgrad_group_kernel<5, 5>), grid, dim3(256), ldsg * ni, st, a, pitch, gpitch, slot, ni);
             fast = true;
-        } else if (a.stride_h == 1 && a.stride_w == 1 && a.R == a.S && (a.R == 3 || a.R == 5)) {
+        } else if (a.stride_h == a.stride_w && (a.stride_h == 1 || a.stride_h == 2) && a.R == a.S && (a.R == 3 || a.R == 5)) {
             // here IH x IW is the input plane and OH x OW the gradient plane
             // rows of whole dwords under "same" padding: staged from a dword boundary (OFF = 4 - pad_w, one more dword per row)
+            const int stv = a.stride_h;
             const bool al = (a.IW & 3) == 0 && a.pad_w == a.S / 2 && a.pad_w > 0;
-            const int pitch = dw_fast_pitch(a.OW, a.S) + (al ? 4 : 0), gpitch = (a.OW + 3) & ~3;
-            const size_t ldsf = (((size_t)(a.OH + a.R - 1) * pitch + 15) & ~(size_t)15) + (size_t)a.OH * gpitch;
-            if (ldsf <= 60 * 1024) {
+            const int off = al ? 4 - a.pad_w : 0;
+            const int gpitch = (a.OW + 3) & ~3;
+            int pitch, xrows;
+            if (stv == 1) {
+                pitch = dw_fast_pitch(a.OW, a.S) + (al ? 4 : 0);
+                xrows = a.OH + a.R - 1;
+            } else {
+                // a task reads 16 bytes of row 2 p + r from column 2 q, q < OW rounded up to 4
+                pitch = 2 * (gpitch - 4) + 16;
+                if (pitch < a.pad_w + off + a.IW) pitch = a.pad_w + off + a.IW;
+                pitch = (pitch + 3) & ~3;
+                xrows = 2 * (a.OH - 1) + a.R;
+                if (xrows < a.pad_h + a.IH) xrows = a.pad_h + a.IH;
+            }
+            const size_t ldsf = (((size_t)xrows * pitch + 15) & ~(size_t)15) + (size_t)a.OH * gpitch;
+            // (stride 2 without the dword-aligned staging would need its own instantiations: the generic kernel serves it)
+            if (ldsf <= 60 * 1024 && (stv == 1 || al)) {
                 fast = true;
-#define WFAST(Rv, PFv, OFFv)                                                                                                \
+#define WFAST(Rv, PFv, OFFv, STv)                                                                                                \
     do {                                                                                                            \
-        if (a.threads == 64) launch_timed(kt, (dw_wgrad_fast_kernel<Rv, Rv, 64, PFv, OFFv>), dim3(a.C, a.chunks), dim3(64), ldsf, st, a, pitch, gpitch);        \
-        else if (a.threads == 128) launch_timed(kt, (dw_wgrad_fast_kernel<Rv, Rv, 128, PFv, OFFv>), dim3(a.C, a.chunks), dim3(128), ldsf, st, a, pitch, gpitch); \
-        else launch_timed(kt, (dw_wgrad_fast_kernel<Rv, Rv, 256, PFv, OFFv>), dim3(a.C, a.chunks), dim3(256), ldsf, st, a, pitch, gpitch);                      \
+        if (a.threads == 64) launch_timed(kt, (dw_wgrad_fast_kernel<Rv, Rv, 64, PFv, OFFv, STv>), dim3(a.C, a.chunks), dim3(64), ldsf, st, a, pitch, gpitch, xrows);        \
+        else if (a.threads == 128) launch_timed(kt, (dw_wgrad_fast_kernel<Rv, Rv, 128, PFv, OFFv, STv>), dim3(a.C, a.chunks), dim3(128), ldsf, st, a, pitch, gpitch, xrows); \
+        else launch_timed(kt, (dw_wgrad_fast_kernel<Rv, Rv, 256, PFv, OFFv, STv>), dim3(a.C, a.chunks), dim3(256), ldsf, st, a, pitch, gpitch, xrows);                      \
     } while (0)
                 const int ihw = a.IH * a.IW, ohw = a.OH * a.OW;
                 const bool pf = (ihw & 15) == 0 && (ohw & 15) == 0 && ihw <= 4096 && ohw <= 4096;
-                if (a.R == 3) {
-                    if (pf) { if (al) WFAST(3, true, 3); else WFAST(3, true, 0); }
-                    else { if (al) WFAST(3, false, 3); else WFAST(3, false, 0); }
+                if (stv == 2) {
+                    if (a.R == 3) { if (pf) WFAST(3, true, 3, 2); else WFAST(3, false, 3, 2); }
+                    else { if (pf) WFAST(5, true, 2, 2); else WFAST(5, false, 2, 2); }
+                } else if (a.R == 3) {
+                    if (pf) { if (al) WFAST(3, true, 3, 1); else WFAST(3, true, 0, 1); }
+                    else { if (al) WFAST(3, false, 3, 1); else WFAST(3, false, 0, 1); }
                 } else {
-                    if (pf) { if (al) WFAST(5, true, 2); else WFAST(5, true, 0); }
-                    else { if (al) WFAST(5, false, 2); else WFAST(5, false, 0); }
+                    if (pf) { if (al) WFAST(5, true, 2, 1); else WFAST(5, true, 0, 1); }
+                    else { if (al) WFAST(5, false, 2, 1); else WFAST(5, false, 0, 1); }
                 }
 #undef WFAST
             }
