@@ -202,6 +202,22 @@ __device__ __forceinline__ void dw_scatter_chunk(const uint4& v, int i, int IH, 
     const int rem = 16 * i - pl * IHW;
     int row = rem / IW, col = rem - row * IW;
     int8_t* rowp = dst + pl * psize + (row + top) * pitch + left;
+    if (((IW | left | pitch | psize) & 3) == 0) {      // (uniform) rows of whole dwords at a dword-aligned place
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            *reinterpret_cast<uint32_t*>(rowp + col) = d[w];
+            col += 4;
+            if (col == IW) {
+                col = 0;
+                rowp += pitch;
+                if (++row == IH) {
+                    row = 0;
+                    rowp += psize - IH * pitch;
+                }
+            }
+        }
+        return;
+    }
     // (the byte loop is kept rolled: unrolled sixteen-fold in each of its callers it cost the kernels 100 registers)
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
@@ -264,7 +280,10 @@ __device__ __forceinline__ void dw_planes_store(const int8_t* __restrict__ src, 
 // LDS row 2 * oh + r' and column 2 * ow; `rows` is the height of the staged area.
 constexpr int DW_MAX_PPB = 32;        // planes per block of the fast path, at most
 
-template <bool DGRAD, int SD, int NT, int ST = 1>    // SD = dwords of packed weights per filter row (S <= 4*SD)
+// OFF: the plane is staged OFF bytes further right than its border asks, so that its rows
+// start on a dword of LDS and are written four bytes at a time (see dw_fill_plane); the windows then start OFF bytes
+// further right as well.
+template <bool DGRAD, int SD, int NT, int ST = 1, int OFF = 0>    // SD = dwords of packed weights per filter row (S <= 4*SD)
 __global__ __launch_bounds__(NT) void dw_conv_fast_kernel(const DwArgs a, int pitch, int rows, int ppb) {
     static_assert(ST == 1 || (ST == 2 && !DGRAD), "the strided form is the forward pass at stride 2");
     extern __shared__ __attribute__((aligned(16))) int8_t plane[];
@@ -295,8 +314,8 @@ __global__ __launch_bounds__(NT) void dw_conv_fast_kernel(const DwArgs a, int pi
         }
         wrow[pl][rp][d] = wv;
     }
-    if (ppb == 1) dw_stage_plane<NT>(a.a + src0, a.IH, a.IW, plane, rows, pitch, top, left);
-    else dw_planes_store<NT>(a.a + src0, np, nch, pregs, a.IH, a.IW, plane, rows, pitch, top, left);
+    if (ppb == 1) dw_stage_plane<NT>(a.a + src0, a.IH, a.IW, plane, rows, pitch, top, left + OFF);
+    else dw_planes_store<NT>(a.a + src0, np, nch, pregs, a.IH, a.IW, plane, rows, pitch, top, left + OFF);
 
     const float scale = __fmul_rn(a.sa[0], a.sb[0]);
     const int QW = (a.OW + 3) >> 2;
@@ -313,16 +332,17 @@ __global__ __launch_bounds__(NT) void dw_conv_fast_kernel(const DwArgs a, int pi
         int sum[4] = {0, 0, 0, 0};
         for (int rp = 0; rp < a.R; ++rp) {
             const uint32_t* __restrict__ rowp = reinterpret_cast<const uint32_t*>(pp + (ST * oh + rp) * pitch + ST * ow);
-            uint32_t d[SD + ST];
+            constexpr int ND = ((OFF + 3 * ST + 3) >> 2) + SD;       // dwords the four windows reach into
+            uint32_t d[ND];
 #pragma unroll
-            for (int k = 0; k < SD + ST; ++k) d[k] = rowp[k];
+            for (int k = 0; k < ND; ++k) d[k] = rowp[k];
 #pragma unroll
             for (int k = 0; k < SD; ++k) {
                 const uint32_t wv = wrow[pl][rp][k];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    // output j's window starts ST * j bytes into the row segment
-                    const int dwi = k + (ST * j) / 4, sh = (ST * j) % 4;
+                    // output j's window starts OFF + ST * j bytes into the row segment
+                    const int dwi = k + (OFF + ST * j) / 4, sh = (OFF + ST * j) % 4;
                     const uint32_t win = sh == 0 ? d[dwi] : __builtin_amdgcn_alignbyte(d[dwi + 1], d[dwi], sh);
                     sum[j] = __builtin_amdgcn_sdot4((int)win, (int)wv, sum[j], false);
                 }
@@ -885,6 +905,7 @@ hipError_t launch_dw_conv(const DwArgs& a, hipStream_t st) {
         int pitch = 8 * ((a.OW + 3) / 4) + 4 * (sd + 2);
         if (pitch < a.pad_w + a.IW) pitch = a.pad_w + a.IW;
         pitch = (pitch + 3) & ~3;
+        if (pitch < a.pad_w + 3 + a.IW) pitch = (a.pad_w + 3 + a.IW + 3) & ~3;      // (room for the dword-aligned staging)
         int rows = 2 * (a.OH - 1) + a.R;
         if (rows < a.pad_h + a.IH) rows = a.pad_h + a.IH;
         const size_t lds1 = (size_t)rows * pitch;
@@ -892,36 +913,44 @@ hipError_t launch_dw_conv(const DwArgs& a, hipStream_t st) {
             const int ppb = dw_fast_ppb(a.N * a.C, a.OH, a.OW, a.IH, a.IW, lds1), nt = dw_fast_threads(a.OH, a.OW, ppb);
             const size_t lds = lds1 * ppb;
             const dim3 grid((unsigned)((a.N * a.C + ppb - 1) / ppb));
-#define FAST2(SDv)                                                                                                       \
+            // rows of whole dwords, a border of 1 (3-wide) or 2 (5-wide) columns: staged from a dword boundary
+            const bool al = (a.IW & 3) == 0 && a.pad_w == (sd == 1 ? 1 : 2);
+#define FAST2(SDv, OFFv)                                                                                                       \
     do {                                                                                                                 \
-        if (nt == 64) launch_timed(kt, (dw_conv_fast_kernel<false, SDv, 64, 2>), grid, dim3(64), lds, st, a, pitch, rows, ppb);        \
-        else if (nt == 128) launch_timed(kt, (dw_conv_fast_kernel<false, SDv, 128, 2>), grid, dim3(128), lds, st, a, pitch, rows, ppb); \
-        else launch_timed(kt, (dw_conv_fast_kernel<false, SDv, 256, 2>), grid, dim3(256), lds, st, a, pitch, rows, ppb);               \
+        if (nt == 64) launch_timed(kt, (dw_conv_fast_kernel<false, SDv, 64, 2, OFFv>), grid, dim3(64), lds, st, a, pitch, rows, ppb);        \
+        else if (nt == 128) launch_timed(kt, (dw_conv_fast_kernel<false, SDv, 128, 2, OFFv>), grid, dim3(128), lds, st, a, pitch, rows, ppb); \
+        else launch_timed(kt, (dw_conv_fast_kernel<false, SDv, 256, 2, OFFv>), grid, dim3(256), lds, st, a, pitch, rows, ppb);               \
     } while (0)
-            if (a.S > 4) FAST2(2); else FAST2(1);
+            if (a.S > 4) { if (al) FAST2(2, 2); else FAST2(2, 0); }
+            else { if (al) FAST2(1, 3); else FAST2(1, 0); }
 #undef FAST2
             return hipGetLastError();
         }
     }
     if (a.stride_h == 1 && a.stride_w == 1 && a.S <= 8 && a.R <= DW_FAST_MAXR &&
         (a.dgrad ? (a.pad_h <= a.R - 1 && a.pad_w <= a.S - 1) : true)) {
-        const int pitch = dw_fast_pitch(a.OW, a.S);
+        const int pitch = dw_fast_pitch(a.OW, a.S) + 4;      // (+ 4: room for the dword-aligned staging)
         const size_t lds1 = (size_t)(a.OH + a.R - 1) * pitch;
         if (lds1 <= 60 * 1024) {
             const bool two = a.S > 4;
             const int ppb = dw_fast_ppb(a.N * a.C, a.OH, a.OW, a.IH, a.IW, lds1), nt = dw_fast_threads(a.OH, a.OW, ppb);
             const size_t lds = lds1 * ppb;
             const dim3 grid((unsigned)((a.N * a.C + ppb - 1) / ppb));
-#define FAST(DG, SDv)                                                                                              \
+            // rows of whole dwords, a border of 1 (up to 4 wide) or 2 (wider) columns: staged from a dword boundary
+            const int left = a.dgrad ? (a.S - 1 - a.pad_w) : a.pad_w;
+            const bool al = (a.IW & 3) == 0 && left == (two ? 2 : 1);
+#define FAST(DG, SDv, OFFv)                                                                                              \
     do {                                                                                                           \
-        if (nt == 64) launch_timed(kt, (dw_conv_fast_kernel<DG, SDv, 64>), grid, dim3(64), lds, st, a, pitch, a.OH + a.R - 1, ppb);        \
-        else if (nt == 128) launch_timed(kt, (dw_conv_fast_kernel<DG, SDv, 128>), grid, dim3(128), lds, st, a, pitch, a.OH + a.R - 1, ppb); \
-        else launch_timed(kt, (dw_conv_fast_kernel<DG, SDv, 256>), grid, dim3(256), lds, st, a, pitch, a.OH + a.R - 1, ppb);               \
+        if (nt == 64) launch_timed(kt, (dw_conv_fast_kernel<DG, SDv, 64, 1, OFFv>), grid, dim3(64), lds, st, a, pitch, a.OH + a.R - 1, ppb);        \
+        else if (nt == 128) launch_timed(kt, (dw_conv_fast_kernel<DG, SDv, 128, 1, OFFv>), grid, dim3(128), lds, st, a, pitch, a.OH + a.R - 1, ppb); \
+        else launch_timed(kt, (dw_conv_fast_kernel<DG, SDv, 256, 1, OFFv>), grid, dim3(256), lds, st, a, pitch, a.OH + a.R - 1, ppb);               \
     } while (0)
             if (a.dgrad) {
-                if (two) FAST(true, 2); else FAST(true, 1);
+                if (two) { if (al) FAST(true, 2, 2); else FAST(true, 2, 0); }
+                else { if (al) FAST(true, 1, 3); else FAST(true, 1, 0); }
             } else {
-                if (two) FAST(false, 2); else FAST(false, 1);
+                if (two) { if (al) FAST(false, 2, 2); else FAST(false, 2, 0); }
+                else { if (al) FAST(false, 1, 3); else FAST(false, 1, 0); }
             }
 #undef FAST
             return hipGetLastError();
