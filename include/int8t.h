@@ -315,10 +315,11 @@ int8t_status int8t_conv_bwd_weight(const int8t_conv_desc *desc,
  * the layer's own buffers and selects the fastest.  The selection is kept in a process-wide table
  * keyed by (pass, descriptor) until it is changed; INT8T_VARIANT_AUTO (the default for every layer)
  * restores the library's own rules.  Thread-safe; not device-specific.
- *   forward / backward-data:  BAND, TILE, TILE_SPLIT, WIDE128, WIDE256
- *   backward-weight:          WGRAD_FEWER, WGRAD_MORE (half / twice the reduction shares of the
- *                             cost model's choice; query int8t_workspace_bytes() again afterwards)
- * Depthwise layers have one kernel per pass.  A variant that needs scratch (TILE_SPLIT) and is not
+ *   forward / backward-data:  BAND, TILE, TILE_SPLIT, WIDE128, WIDE256, WIDE_SQ128, WIDE_SQ128_DEEP, WIDE_128X64
+ *   backward-weight:          WGRAD_IMAGES, WGRAD_LINES (the two kernels), WGRAD_FEWER, WGRAD_MORE (half / twice the
+ *                             reduction shares of the cost model's choice); query int8t_workspace_bytes() again
+ *                             after selecting any of them
+ * Depthwise layers are served by the library's own choice among their kernels only.  A variant that needs scratch (TILE_SPLIT) and is not
  * given enough falls back to TILE.
  */
 typedef enum {
