@@ -157,6 +157,9 @@ def main():
                     help="also time the step of every ResNet-50 convolution and its classifier at this batch "
                          "(Fig.10's workload) and print the per-layer table and the network total (stderr)")
     ap.add_argument("--mobilenetv2", type=int, default=0, metavar="BATCH", help="the same for every convolution of MobileNetV2")
+    ap.add_argument("--variant-table", action="store_true",
+                    help="in the network sweeps, also time every kernel variant of every layer and pass (stderr; the sweep itself "
+                         "keeps the library's own choice)")
     ap.add_argument("--fused-forward", action="store_true",
                     help="also time quantize(a, W) + forward against the fused forward (int8t_conv_fwd_fused) on 1x1 layers (stderr)")
     ap.add_argument("--inceptionv3", type=int, default=0, metavar="BATCH",
@@ -407,6 +410,14 @@ def main():
                 st.run(seed=k, overlap=overlap)
             if overlap is None and period == 1:
                 st.tune()                # one or two streams for this layer, by measurement (untimed)
+            if args.variant_table:
+                # every variant the library admits, per pass (microseconds); the library's own rule is restored afterwards
+                table = st.tune_kernels()
+                for op in (B.OP_CONV_FWD, B.OP_CONV_BWD_DATA, B.OP_CONV_BWD_WEIGHT):
+                    B.int8t_conv_select_variant(op, st.desc, B.VARIANT_AUTO)
+                st.refresh_scratch()
+                if table:
+                    print(json.dumps({"variants": Lx.name, **{k: v[1] for k, v in table.items()}}), file=sys.stderr, flush=True)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             for k in range(nst):
