@@ -55,9 +55,16 @@ __host__ __device__ inline void tap_extent(int t0, int nt, int S, int* rmin, int
 constexpr int W2_MAXSTEPS = 16;        // MFMA steps per chunk: at most 32 tile pixels
 
 
-template <int TB, int CS>
+// PK (tensors of 16 channels -- the space-to-depth image of a stem: TB = 4, CS = 1): the block's 64 columns are its
+// four taps x 16 channels, not 64 channels of which 48 do not exist: a column's operand is the channel granule of the
+// window pixel its tap points at, so one MFMA per step serves four taps, and a window pixel is one granule to stage,
+// not four (7x7 stem of ResNet-50, batch 64: the 4 x 4 taps of the rewritten layer took 16 blocks of a quarter-full
+// tile each).
+template <int TB, int CS, bool PK = false>
 __global__ __launch_bounds__(256, 2) void wgrad_kernel(const WgradArgs a) {
-    constexpr int CT = 64 * CS;                   // channels per block
+    static_assert(!PK || (TB == 4 && CS == 1), "packed taps: four taps of 16 channels");
+    constexpr int CT = PK ? 16 : 64 * CS;         // channels staged per pixel
+    constexpr int TBA = PK ? 1 : TB;              // accumulator tiles per wave along the taps
     constexpr int XP = CT + W2_PAD;               // pixel pitch of the input window tile
     constexpr int YP = W2_BM + W2_PAD;            // pixel pitch of the gradient tile
     static_assert(CS == 1 || CS == 4, "channel tile is 64 or 256");
@@ -124,10 +131,15 @@ __global__ __launch_bounds__(256, 2) void wgrad_kernel(const WgradArgs a) {
     int x_ch[CS];                                   // this lane's channel positions inside the block's tile
 #pragma unroll
     for (int i = 0; i < CS; ++i) x_ch[i] = swz_ch((ch * CS + i) * 32 + l32);
+    if (PK) {
+        // column 32 * ch + l32 = tap 2 * ch + l32 / 16 of the block's four, channel l32 % 16 (a single group of 16: no xor)
+        const int tlo = ch ? tpix[2 % TB] : tpix[0], thi = ch ? tpix[3 % TB] : tpix[1 % TB];
+        x_ch[0] = ((l32 >> 4) ? thi : tlo) + (l32 & 15);
+    }
 
-    v16i acc[TB][CS];
+    v16i acc[TBA][CS];
 #pragma unroll
-    for (int j = 0; j < TB; ++j)
+    for (int j = 0; j < TBA; ++j)
 #pragma unroll
         for (int i = 0; i < CS; ++i)
 #pragma unroll
@@ -137,7 +149,7 @@ __global__ __launch_bounds__(256, 2) void wgrad_kernel(const WgradArgs a) {
     // that the operand reads of a step depend on nothing that is read in that step
     // (only the variants with few accumulators have the registers for this and for the operand
     // prefetch below; the others look the position up in LDS step by step)
-    constexpr bool PF = TB * CS <= 3;
+    constexpr bool PF = TBA * CS <= 3;
     __syncthreads();
     int wpix[PF ? W2_MAXSTEPS : 1];
     if (PF) {
@@ -256,14 +268,14 @@ __global__ __launch_bounds__(256, 2) void wgrad_kernel(const WgradArgs a) {
         // The operands of step s+1 are requested before the MFMAs of step s are issued (two register
         // sets), so the LDS latency of a step hides behind the previous step's matrix work.
         constexpr int NSET = PF ? 2 : 1;
-        uint4 ra[NSET], rb[NSET][TB][CS];
+        uint4 ra[NSET], rb[NSET][TBA][CS];
         auto fetch = [&](int s, int set) {
             ra[set] = dyT[a_ch + 2 * s * YP];
             const int wp = PF ? wpix[PF ? s : 0] : stab_h[2 * s].y;
 #pragma unroll
-            for (int j = 0; j < TB; ++j)   // TB divides R*S: every tap of the group exists
+            for (int j = 0; j < TBA; ++j)   // TB divides R*S: every tap of the group exists
 #pragma unroll
-                for (int i = 0; i < CS; ++i) rb[set][j][i] = xT[wp + tpix[j] + x_ch[i]];
+                for (int i = 0; i < CS; ++i) rb[set][j][i] = xT[wp + (PK ? 0 : tpix[j]) + x_ch[i]];
         };
         if (PF) fetch(0, 0);
 #pragma unroll
@@ -277,7 +289,7 @@ __global__ __launch_bounds__(256, 2) void wgrad_kernel(const WgradArgs a) {
                 const uint4 ta = ra[s & (NSET - 1)];
                 const v4i fa = v4i{(int)ta.x, (int)ta.y, (int)ta.z, (int)ta.w};
 #pragma unroll
-                for (int j = 0; j < TB; ++j) {
+                for (int j = 0; j < TBA; ++j) {
 #pragma unroll
                     for (int i = 0; i < CS; ++i) {
                         const uint4 tb = rb[s & (NSET - 1)][j][i];
@@ -293,12 +305,13 @@ __global__ __launch_bounds__(256, 2) void wgrad_kernel(const WgradArgs a) {
     const int ncolsp = RS * a.Cp;
     int32_t* __restrict__ part = a.partial + (size_t)zshare * a.K * ncolsp;
 #pragma unroll
-    for (int j = 0; j < TB; ++j) {
+    for (int j = 0; j < TBA; ++j) {
         if (j >= nt) continue;
 #pragma unroll
         for (int i = 0; i < CS; ++i) {
-            const int c = ct * CT + (ch * CS + i) * 32 + l32;
-            if (c >= a.Cp) continue;
+            // (PK: the 64 columns are taps t0 .. t0 + 3 x 16 channels, which is their order in the partial tile as well)
+            const int c = PK ? ch * 32 + l32 : ct * CT + (ch * CS + i) * 32 + l32;
+            if (!PK && c >= a.Cp) continue;
             const int col = (t0 + j) * a.Cp + c;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
@@ -455,7 +468,7 @@ void wgrad_plan(WgradArgs* a) {
     a->TB = p.TB; a->CS = p.CS; a->BP = p.BP; a->BQ = p.BQ; a->ntp = p.ntp; a->ntq = p.ntq;
     a->ngrp = p.ngrp; a->chunks = p.chunks; a->splits = p.splits;
     a->ktiles = p.ktiles; a->ctiles = p.ctiles; a->tapgroups = p.tapgroups;
-    a->xt_slots = p.xt_slots; a->lds_bytes = p.lds_bytes; a->lines = p.lines; a->xgk = p.xgk; a->xgc = p.xgc;
+    a->xt_slots = p.xt_slots; a->lds_bytes = p.lds_bytes; a->lines = p.lines; a->xgk = p.xgk; a->xgc = p.xgc; a->pk = p.pk;
 }
 
 namespace {
@@ -469,12 +482,14 @@ void wgrad_plan_uncached(WgradArgs* a) {
     const int RS = a->R * a->S;
     // taps per block / channel slabs per wave: one filter row of a 3-wide filter, a whole 1x7 or
     // 7x1 filter, a wide channel tile for 1x1, one tap at a time otherwise
-    if (RS == 1) { a->TB = 1; a->CS = (a->Cp >= 256) ? 4 : 1; }
+    a->pk = 0;
+    if (a->Cp == 16 && RS % 4 == 0) { a->TB = 4; a->CS = 1; a->pk = 1; }      // four taps side by side in the 64 columns
+    else if (RS == 1) { a->TB = 1; a->CS = (a->Cp >= 256) ? 4 : 1; }
     else if (RS % 3 == 0 && a->S == 3) { a->TB = 3; a->CS = 1; }
     else if (RS == 7) { a->TB = 7; a->CS = 1; }
     else { a->TB = 1; a->CS = 1; }
     // TB divides R*S in every case, so a tap group is never ragged
-    const int CT = 64 * a->CS;
+    const int CT = a->pk ? 16 : 64 * a->CS;          // channels staged per window pixel
     a->tapgroups = (RS + a->TB - 1) / a->TB;
     a->ktiles = (a->K + W2_BM - 1) / W2_BM;
     a->ctiles = (a->Cp + CT - 1) / CT;
@@ -526,11 +541,12 @@ void wgrad_plan_uncached(WgradArgs* a) {
     // (blocks resident on the chip: registers allow two per compute unit for the narrow tiles, one
     // for the wide ones); a block pays a prologue plus its chunks; every split adds one write and
     // one read of the int32 partial tile set.  The constants are rough measurements in microseconds.
-    const int per_cu_regs = (a->TB == 1 && a->CS == 1) ? 3 : 2;   // by register count of the variants
+    const int acc_tiles = a->pk ? 1 : a->TB * a->CS;
+    const int per_cu_regs = acc_tiles == 1 ? 3 : 2;   // by register count of the variants
     int per_cu_lds = (int)((160 * 1024) / a->lds_bytes);
     if (per_cu_lds < 1) per_cu_lds = 1;
     const int slots = 256 * (per_cu_regs < per_cu_lds ? per_cu_regs : per_cu_lds);
-    const double t_chunk = 1.2 * per_cu_regs + 0.014 * (BP * BQ + 1) / 2 * a->TB * a->CS;
+    const double t_chunk = 1.2 * per_cu_regs + 0.014 * (BP * BQ + 1) / 2 * acc_tiles;
     const double t_partial = (double)a->K * RS * a->Cp * 8.0 / 4.0e6;
     int splits = 1;
     double best = 1e30;
@@ -558,23 +574,24 @@ hipError_t launch_wgrad(const WgradArgs& a_in, hipStream_t st) {
     const unsigned out_tiles = (unsigned)(a.ktiles * a.ctiles * a.tapgroups);
     dim3 grid(wgrad_xcd_mapping(a.splits) ? out_tiles * 8u * (unsigned)((a.splits + 7) / 8) : out_tiles * (unsigned)a.splits);
     // the staged tiles may exceed the default 64 KB of dynamic LDS: raise the limit once per variant
-#define LAUNCH(TBv, CSv)                                                                                  \
+#define LAUNCH(TBv, CSv, PKv)                                                                                  \
     do {                                                                                                  \
         static std::atomic<unsigned long long> attr_done;                                                 \
-        hipError_t ea = raise_dynamic_lds(reinterpret_cast<const void*>(wgrad_kernel<TBv, CSv>), W2_LDS_BUDGET, \
+        hipError_t ea = raise_dynamic_lds(reinterpret_cast<const void*>(wgrad_kernel<TBv, CSv, PKv>), W2_LDS_BUDGET, \
                                           attr_done);                                                     \
         if (ea != hipSuccess) return ea;                                                                  \
-        launch_timed(kt, (wgrad_kernel<TBv, CSv>), grid, dim3(256), a.lds_bytes, st, a);                \
+        launch_timed(kt, (wgrad_kernel<TBv, CSv, PKv>), grid, dim3(256), a.lds_bytes, st, a);                \
     } while (0)
     if (a.lines) {
         hipError_t el = launch_wgrad_lines(a, st);
         if (el != hipSuccess) return el;
     } else {
         KernelTimer kt(KID_WGRAD, st);
-        if (a.TB == 1 && a.CS == 1) LAUNCH(1, 1);
-        else if (a.TB == 1 && a.CS == 4) LAUNCH(1, 4);
-        else if (a.TB == 3) LAUNCH(3, 1);
-        else if (a.TB == 7) LAUNCH(7, 1);
+        if (a.pk) LAUNCH(4, 1, true);
+        else if (a.TB == 1 && a.CS == 1) LAUNCH(1, 1, false);
+        else if (a.TB == 1 && a.CS == 4) LAUNCH(1, 4, false);
+        else if (a.TB == 3) LAUNCH(3, 1, false);
+        else if (a.TB == 7) LAUNCH(7, 1, false);
         else return hipErrorInvalidValue;
     }
 #undef LAUNCH

@@ -209,6 +209,7 @@ struct WgradArgs {
     int stride_h, stride_w, pad_h, pad_w;
     // filled by wgrad_plan():
     int TB, CS;                  // taps per block, 32-channel slabs per wave
+    int pk;                      // 1: a tensor of 16 channels, four taps per block packed side by side into the 64 columns
     int BP, BQ, ntp, ntq;        // output-pixel tile and tiles per image
     int ngrp, chunks, splits;    // groups of 16 images, reduction chunks, split-K factor
     int ktiles, ctiles, tapgroups;
