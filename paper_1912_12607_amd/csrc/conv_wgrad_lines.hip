@@ -94,15 +94,18 @@ __global__ __launch_bounds__(256, 2) void wgrad_lines_kernel(const WgradArgs a) 
     const bool along_w = wgrad_lines_along_w(a.R, a.S);
     const int NLI = along_w ? a.P : a.Q;          // gradient lines per image
     const int QL = along_w ? a.Q : a.P;           // gradient positions on a line
-    const int WLn = along_w ? a.W : a.H;          // input positions on a line
+    // A strided 1x1 filter without padding (the shortcut of a residual stage) reads the sub-image of every stride_h-th
+    // row and stride_w-th pixel: the same pass on an input of P x Q positions whose lines and positions lie further apart.
+    const bool strided = a.stride_h != 1 || a.stride_w != 1;          // (1x1, no padding: wgrad_lines_applies)
+    const int WLn = strided ? QL : along_w ? a.W : a.H;          // input positions on a line
     const int pl = along_w ? a.pad_w : a.pad_h;   // padding along the line
-    const int XC = along_w ? a.H : a.W;           // input lines per image
+    const int XC = strided ? NLI : along_w ? a.H : a.W;           // input lines per image
     const int xshift = along_w ? tg - a.pad_h : -a.pad_w;   // gradient line l pairs with input line l + xshift
     const int t0 = along_w ? tg * a.S : 0;        // first tap of the block (taps numbered r*S + s)
     const uint32_t dy_ls = along_w ? (uint32_t)a.Q * a.Kp : (uint32_t)a.Kp;
     const uint32_t dy_ps = along_w ? (uint32_t)a.Kp : (uint32_t)a.Q * a.Kp;
-    const uint32_t x_ls = along_w ? (uint32_t)a.W * a.Cp : (uint32_t)a.Cp;
-    const uint32_t x_ps = along_w ? (uint32_t)a.Cp : (uint32_t)a.W * a.Cp;
+    const uint32_t x_ls = along_w ? (uint32_t)a.W * a.Cp * a.stride_h : (uint32_t)a.Cp;
+    const uint32_t x_ps = along_w ? (uint32_t)a.Cp * a.stride_w : (uint32_t)a.W * a.Cp;
     // Step u of a line: the gradient position u enters the window, the input position u - pl is
     // multiplied with the gradient positions u, u-1, .., u-ST+1 (taps 0 .. ST-1).  A ring stage holds GP
     // steps of one chunk.  (Letting the stages run on across chunk ends saves the idle steps of a chunk's last
@@ -271,8 +274,10 @@ __global__ __launch_bounds__(256, 2) void wgrad_lines_kernel(const WgradArgs a) 
 }
 
 bool wgrad_lines_applies(const WgradArgs& a) {
-    if (a.s2d || a.stride_h != 1 || a.stride_w != 1) return false;
     const bool one = a.R == 1 && a.S == 1;
+    if (a.s2d) return false;
+    // strides: 1x1 filters without padding only (the pass then runs on every stride-th row and pixel)
+    if ((a.stride_h != 1 || a.stride_w != 1) && !(one && a.pad_h == 0 && a.pad_w == 0)) return false;
     const bool along_w = a.S == 3 || a.S == 7;
     const bool along_h = a.S == 1 && (a.R == 3 || a.R == 7);
     if (!one && !along_w && !along_h) return false;
@@ -296,7 +301,7 @@ void wgrad_plan_lines(WgradArgs* a) {
     a->ctiles = (a->Cp + 64 * WT - 1) / (64 * WT);
     const int NLI = along_w ? a->P : a->Q;
     const int QL = along_w ? a->Q : a->P;
-    const int WLn = along_w ? a->W : a->H;
+    const int WLn = (a->stride_h != 1 || a->stride_w != 1) ? QL : along_w ? a->W : a->H;
     const int pl = along_w ? a->pad_w : a->pad_h;
     a->chunks = (a->N * NLI + WL_LINES - 1) / WL_LINES;
     a->lds_bytes = (size_t)WL_NSTAGE * wl_stage_bytes(WT, WT, GP);
