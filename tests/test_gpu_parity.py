@@ -446,22 +446,22 @@ def test_conv_three_passes_random_shapes():
             assert np.array_equal(out.cpu().numpy(), want32.astype(np.float32)), (name, shape)   # scales are 1
 
 
-# Layers just over the threshold from which forward / backward-data run the wide-tile kernel
-# (igemm_dma_kernel: more than 64 rows, at least 32 reduction granules, at least 256 tiles of 128 x 256),
-# one per instantiation; every accumulator and every fp32 result is compared.
+# Layers large enough for the 128-row and the 256 x 256 tiles of igemm_dma_kernel (forward / backward-data
+# of every layer with more than 64 output rows run it; 256 x 256 from 192 such tiles up), plain, split by
+# pixel classes and in the cell form; every accumulator and every fp32 result is compared.
 # (N, C, H, W, K, R, S, stride, pad, groups), passes that must run the wide kernel
 WIDE_SHAPES = [
-    # forward and plain backward-data, 128 x 256 tiles (192 rows: one full and one half row tile; ragged columns)
+    # forward and plain backward-data, 128-row tiles (192 rows: one full and one half row tile; ragged columns)
     ((4, 192, 95, 97, 192, 1, 3, (1, 1), (0, 1), 1), ("fwd", "bwd_data")),
-    # ... 256 x 256 tiles (at least 192 of them)
+    # ... a larger batch: at least 192 tiles of 256 x 256, which the plain passes then take
     ((6, 192, 95, 97, 192, 1, 3, (1, 1), (0, 1), 1), ("fwd", "bwd_data")),
-    # backward-data by residue classes (3 x 3, stride 2: four classes with 4, 2, 2, 1 taps), 128 x 256 tiles
+    # backward-data by residue classes (3 x 3, stride 2: four classes with 4, 2, 2, 1 taps)
     ((2, 192, 127, 129, 128, 3, 3, (2, 2), (1, 1), 1), ("bwd_data",)),
-    # ... 256 x 256 tiles
+    # ... a larger batch
     ((3, 192, 127, 129, 128, 3, 3, (2, 2), (1, 1), 1), ("bwd_data",)),
-    # backward-data in the cell form (1 x 1, stride 2, even row length, odd height), 128 x 256 tiles
+    # backward-data in the cell form (1 x 1, stride 2, even row length, odd height)
     ((32, 192, 63, 64, 512, 1, 1, (2, 2), (0, 0), 1), ("bwd_data",)),
-    # ... 256 x 256 tiles
+    # ... a larger batch
     ((48, 192, 63, 64, 512, 1, 1, (2, 2), (0, 0), 1), ("bwd_data",)),
 ]
 
