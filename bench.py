@@ -408,7 +408,7 @@ def main():
             nst = max(20, args.steps // 10)
             for k in range(80):          # the first few dozen steps on fresh buffers run at up to twice the steady time
                 st.run(seed=k, overlap=overlap)
-            if overlap is None and period == 1:
+            if overlap is None:
                 st.tune()                # one or two streams for this layer, by measurement (untimed)
             if args.variant_table:
                 # every variant the library admits, per pass (microseconds); the library's own rule is restored afterwards

@@ -108,6 +108,7 @@ class LayerStep:
             self.xw_items + [(self.dy, L.y_shape, self.act_kind, self.clip, self.dyq, self.sdy)]), dtype=u8, device=d)
         self._side = None
         self._tuned_overlap = None
+        self._tuned_fork = None
         self.ws_fwd = torch.empty(nf, dtype=u8, device=d) if nf else None
         self.ws_bwd_data = torch.empty(nb, dtype=u8, device=d) if nb else None
 
@@ -193,21 +194,39 @@ class LayerStep:
         B.int8t_conv_bwd_weight(self.desc, self.xq, self.sx, self.dyq, self.sdy, self.dw, self.dw_acc,
                                 self.ws, stream)
 
-    def run(self, seed: int = 0, stream=None, search: bool = True, overlap: bool | None = False):
+    def run(self, seed: int = 0, stream=None, search: bool = True, overlap: bool | int | None = False):
         """The whole hot path once.  search=False keeps the clip value of the last search (the
         paper's Periodic Update, Sec.3.4 / Table 2: the clip is refreshed every P iterations only);
         the caller decides the period.
 
-        overlap=True puts the quantization of a and W and the forward convolution on a second stream
-        beside the clip search: the two chains are independent until the backward convolutions, the
-        search is bound by the vector ALUs and the other kernels by HBM.  Both streams have the
-        default priority.  Outputs are complete once the main stream is.  overlap=None decides by the
-        layer (two_stream_default) and only in steps that search."""
+        overlap chooses the schedule of the same calls on the caller's stream and a second one (both
+        of the default priority; outputs are complete once the caller's stream is):
+          False / 0  everything on one stream;
+          True / 1   the quantization of a and W and the forward convolution on the second stream
+                     beside the clip search: the two chains are independent until the backward
+                     convolutions, the search is bound by the vector ALUs and the other kernels by HBM;
+          2          one stream up to the codes, then backward-weight on the second stream beside the
+                     forward and backward-data convolutions: the three passes depend only on the codes,
+                     and on layers whose tiles do not fill the chip they run beside each other;
+          3          both: backward-weight follows the forward pass on the second stream, and backward-data
+                     starts as soon as the codes of W are there, beside the forward pass if that is still running;
+          4          as 1, but the backward passes wait for the codes of a and W only, not for the forward pass
+                     behind them (with 1 each convolution has the chip to itself).
+        A step that keeps the clip has no search to hide anything behind: any non-zero value means 2.
+        overlap=None follows tune() if it has run, else two_stream_default() in steps that search
+        and one stream in steps that do not."""
         if overlap is None:
-            overlap = search and (self._tuned_overlap if self._tuned_overlap is not None else two_stream_default(self.L))
-        if not overlap:
+            if search:
+                overlap = self._tuned_overlap if self._tuned_overlap is not None else two_stream_default(self.L)
+            else:
+                overlap = self._tuned_fork or 0
+        mode = int(overlap)
+        batched = not search and not self.requantize_deviation and not self.fused_fwd
+        if mode and batched:
+            mode = 2
+        if not mode:
             sp = B.stream_pointer(stream)
-            if not search and not self.requantize_deviation and not self.fused_fwd:
+            if batched:
                 # the clip value is known: a, W and g_z in one batched call (one launch fewer)
                 self._items_xwg[2].seed = seed
                 self._k_xwg(sp)
@@ -232,11 +251,31 @@ class LayerStep:
         main = stream if stream is not None else torch.cuda.current_stream()
         if self._side is None:
             self._side = side_stream(self.dev)
-            self._ev_side = torch.cuda.Event()
-            self._ev_main = torch.cuda.Event()
+            self._ev_main, self._ev_main2, self._ev_side, self._ev_side2 = (torch.cuda.Event() for _ in range(4))
         side = self._side
         mp, sp = B.stream_pointer(main), B.stream_pointer(side)
-        # main stream: clip search, quantize g_z, then the two backward convolutions.
+        if mode == 2:
+            if batched:
+                self._items_xwg[2].seed = seed
+                self._k_xwg(mp)
+            else:
+                (self._k_w if self.fused_fwd else self._k_xw)(mp)
+                if search:
+                    self._k_clip(seed, mp)
+                self._k_qdy(seed, mp)
+                if self.fused_fwd:
+                    self._k_fwd_fused(mp)       # writes the codes of a, which backward-weight reads
+            self._ev_main.record(main)
+            side.wait_event(self._ev_main)
+            self._k_bwd_weight(sp)
+            self._ev_side.record(side)
+            if not self.fused_fwd:
+                self._k_fwd(mp)
+            if self.input_grad:
+                self._k_bwd_data(mp)
+            main.wait_event(self._ev_side)
+            return
+        # main stream: clip search, quantize g_z, then backward-data (and backward-weight, unless it is forked).
         # side stream: quantize a and W, forward convolution (needs nothing from the gradient chain).
         # It starts behind whatever is queued on the main stream up to the search's first pass (the
         # previous step's backward passes still read the codes that are about to be overwritten, and
@@ -246,42 +285,57 @@ class LayerStep:
             self._k_prepare(mp)
         self._ev_main.record(main)
         side.wait_event(self._ev_main)
+        early = mode >= 3 and not self.fused_fwd
         if self.fused_fwd:
             self._k_w(sp)
-            self._k_fwd_fused(sp)
+            self._k_fwd_fused(sp)               # writes the codes of a
+            self._ev_side.record(side)
         else:
             self._k_xw(sp)
+            if early:
+                self._ev_side.record(side)      # the codes of a and W are there
             self._k_fwd(sp)
-        self._ev_side.record(side)
+            if not early:
+                self._ev_side.record(side)
         if search:
             self._k_search(seed, mp)
         self._k_qdy(seed, mp)
+        if mode == 3:
+            # backward-weight follows the forward pass on the side stream once g_z has its codes
+            self._ev_main2.record(main)
+            side.wait_event(self._ev_main2)
+            self._k_bwd_weight(sp)
+        if early or mode == 3:
+            self._ev_side2.record(side)
         main.wait_event(self._ev_side)
         if self.input_grad:
             self._k_bwd_data(mp)
-        self._k_bwd_weight(mp)
+        if mode != 3:
+            self._k_bwd_weight(mp)
+        if early or mode == 3:
+            main.wait_event(self._ev_side2)
 
-    def tune(self, steps: int = 40) -> bool:
-        """Choose between the one-stream and the two-stream arrangement of a searching step by timing both
-        on this layer's own buffers (the per-layer choice "before training" of the paper's Suppl. "INT8
-        Convolution", here between two schedules of the same kernels).  run(overlap=None) then follows the
-        measurement instead of two_stream_default().  Returns the choice.  The buffers must hold data
-        (upload() first); their contents are what a step leaves."""
+    def tune(self, steps: int = 40) -> int:
+        """Choose the schedule (run()'s overlap values) by timing them on this layer's own buffers (the
+        per-layer choice "before training" of the paper's Suppl. "INT8 Convolution", here between schedules of
+        the same kernels): once for steps that search the clip and once for steps that keep it.
+        run(overlap=None) then follows the measurement.  Returns the choice for searching steps.  The buffers
+        must hold data (upload() first; the steps that keep the clip quantize with whatever the clip buffer
+        holds, so a searching step should have run); their contents are what a step leaves."""
         import time
-        if self.depthwise:
-            self._tuned_overlap = False
-            return False
-        best = []
-        for overlap in (False, True):
+
+        def timed(search, overlap):
             for k in range(steps):
-                self.run(seed=k, overlap=overlap)
+                self.run(seed=k, search=search, overlap=overlap)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             for k in range(steps):
-                self.run(seed=k, overlap=overlap)
+                self.run(seed=k, search=search, overlap=overlap)
             torch.cuda.synchronize()
-            best.append(time.perf_counter() - t0)
-        self._tuned_overlap = best[1] < best[0]
+            return time.perf_counter() - t0
+
+        self._tuned_fork = min((0, 2), key=lambda m: timed(False, m))
+        self._tuned_overlap = min((0, 1, 2, 3, 4), key=lambda m: timed(True, m))
         return self._tuned_overlap
 
     def refresh_scratch(self):

@@ -626,11 +626,12 @@ def test_full_size_layers(cfg, li):
 
 @pytest.mark.parametrize("cfg,li", [(0, 0), (1, 0), (3, 1)])
 def test_two_stream_step_equals_one_stream_step(cfg, li):
-    """The step with the a / W chain and the forward pass on a second stream writes exactly what the
-    one-stream step writes (several steps in a row, so that the streams' hand-overs are exercised)."""
+    """Every two-stream schedule of the step (the a / W chain and the forward pass beside the search,
+    backward-weight beside the other convolutions, both) writes exactly what the one-stream step writes
+    (several steps in a row, so that the streams' hand-overs are exercised)."""
     L, x, w, dy = inputs.make_layer_inputs(cfg, li)
     outs = []
-    for overlap in (False, True):
+    for overlap in (False, True, 2, 3, 4):
         st = LayerStep(L, n_cand=32, keep_acc=True)
         st.upload(x, w, dy, inputs.default_ratios(32))
         for seed in (5, 6, 7):
@@ -638,8 +639,9 @@ def test_two_stream_step_equals_one_stream_step(cfg, li):
         torch.cuda.synchronize()
         outs.append([t.clone() for t in (st.xq, st.wq, st.dyq, st.sx, st.sw, st.sdy, st.clip, st.dev_search,
                                           st.y, st.dx, st.dw, st.y_acc, st.dx_acc, st.dw_acc)])
-    for a, b in zip(*outs):
-        assert torch.equal(a, b)
+    for other in outs[1:]:
+        for a, b in zip(outs[0], other):
+            assert torch.equal(a, b)
 
 
 @pytest.mark.parametrize("cfg,li", [(0, 0), (3, 1), (5, 0)])
@@ -660,6 +662,27 @@ def test_step_that_keeps_the_clip_equals_step_that_searches(cfg, li):
         assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("cfg,li", [(0, 0), (2, 1), (3, 1)])
+def test_forked_step_that_keeps_the_clip_equals_one_stream_step(cfg, li):
+    """A step that keeps the clip with backward-weight on the second stream writes what the one-stream step
+    writes (several steps in a row with changing seeds, so that each step's hand-overs are exercised)."""
+    L, x, w, dy = inputs.make_layer_inputs(cfg, li)
+    outs = []
+    for overlap in (False, True):
+        st = LayerStep(L, n_cand=32, keep_acc=True, requantize_deviation=False)
+        st.upload(x, w, dy, inputs.default_ratios(32))
+        st.run(seed=5, overlap=False)
+        for t in (st.xq, st.wq, st.dyq, st.y, st.dx, st.dw):
+            t.zero_()
+        for seed in (6, 7, 8):
+            st.run(seed=seed, search=False, overlap=overlap)
+        torch.cuda.synchronize()
+        outs.append([t.clone() for t in (st.xq, st.wq, st.dyq, st.sx, st.sw, st.sdy, st.clip,
+                                          st.y, st.dx, st.dw, st.y_acc, st.dx_acc, st.dw_acc)])
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
 def test_tuned_schedule_writes_the_same_tensors():
     L, x, w, dy = inputs.make_layer_inputs(1, 0)
     st = LayerStep(L, n_cand=32, requantize_deviation=False)
@@ -668,8 +691,14 @@ def test_tuned_schedule_writes_the_same_tensors():
     torch.cuda.synchronize()
     want = [t.clone() for t in (st.dyq, st.y, st.dx, st.dw, st.clip)]
     choice = st.tune(steps=5)
-    assert choice in (True, False)
+    assert choice in (0, 1, 2, 3, 4)
     st.run(seed=4)                      # overlap=None: the tuned schedule
+    torch.cuda.synchronize()
+    for a, b in zip(want, (st.dyq, st.y, st.dx, st.dw, st.clip)):
+        assert torch.equal(a, b)
+    for t in (st.dyq, st.y, st.dx, st.dw):
+        t.zero_()
+    st.run(seed=4, search=False)        # ... and the tuned schedule of a step that keeps the clip
     torch.cuda.synchronize()
     for a, b in zip(want, (st.dyq, st.y, st.dx, st.dw, st.clip)):
         assert torch.equal(a, b)
@@ -717,7 +746,7 @@ def test_step_with_fused_forward_equals_plain_step():
     L, x, w, dy = inputs.make_layer_inputs(3, 2)
     outs = []
     for fused in (False, True):
-        for overlap in (False, True):
+        for overlap in (False, True, 2, 3, 4):
             st = LayerStep(L, n_cand=32, keep_acc=True, fused_fwd=fused)
             st.upload(x, w, dy, inputs.default_ratios(32))
             st.wq.zero_()                  # (the alignment gap between the two weight layouts is never written)
