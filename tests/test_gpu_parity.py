@@ -668,8 +668,9 @@ def test_forked_step_that_keeps_the_clip_equals_one_stream_step(cfg, li):
     writes (several steps in a row with changing seeds, so that each step's hand-overs are exercised)."""
     L, x, w, dy = inputs.make_layer_inputs(cfg, li)
     outs = []
-    for overlap in (False, True):
-        st = LayerStep(L, n_cand=32, keep_acc=True, requantize_deviation=False)
+    # (schedule, deviation of the final codes asked for: the step then quantizes g_z in a call of its own)
+    for overlap, requant in ((False, False), (True, False), (False, True), (2, True), (3, True), (4, True)):
+        st = LayerStep(L, n_cand=32, keep_acc=True, requantize_deviation=requant)
         st.upload(x, w, dy, inputs.default_ratios(32))
         st.run(seed=5, overlap=False)
         for t in (st.xq, st.wq, st.dyq, st.y, st.dx, st.dw):
@@ -679,8 +680,9 @@ def test_forked_step_that_keeps_the_clip_equals_one_stream_step(cfg, li):
         torch.cuda.synchronize()
         outs.append([t.clone() for t in (st.xq, st.wq, st.dyq, st.sx, st.sw, st.sdy, st.clip,
                                           st.y, st.dx, st.dw, st.y_acc, st.dx_acc, st.dw_acc)])
-    for a, b in zip(*outs):
-        assert torch.equal(a, b)
+    for other in outs[1:]:
+        for a, b in zip(outs[0], other):
+            assert torch.equal(a, b)
 
 
 def test_tuned_schedule_writes_the_same_tensors():
