@@ -332,9 +332,9 @@ typedef enum {
     INT8T_VARIANT_WGRAD_FEWER = 6,
     INT8T_VARIANT_WGRAD_MORE = 7,
     INT8T_VARIANT_WGRAD_IMAGES = 8,  /* backward-weight: operands of 16 images per pixel, transposed in registers */
-    INT8T_VARIANT_WGRAD_LINES = 9,   /* backward-weight, stride 1 with 1, 3 or 7 taps along an axis, or 1x1 at any stride without
-                                        padding: operands of 32 image lines per position through transposing LDS reads,
-                                        gradient operands in a sliding window */
+    INT8T_VARIANT_WGRAD_LINES = 9,   /* backward-weight, stride 1 with 1, 3 or 7 taps along an axis, 1x1 at any stride without
+                                        padding, or 3x3 at stride 2 x 2: operands of 32 image lines per position through
+                                        transposing LDS reads, gradient operands in a sliding window */
     INT8T_VARIANT_WIDE_SQ128 = 10,   /* forward / backward-data: 128 x 128 tiles from a 3-stage LDS ring, three blocks per
                                         compute unit: layers that have too few of the larger tiles to go round */
     INT8T_VARIANT_WIDE_SQ128_DEEP = 11,  /* ... with 2 stages of 128 reduction bytes: long reductions */

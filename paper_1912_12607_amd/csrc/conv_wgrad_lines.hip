@@ -1,5 +1,5 @@
-// Dense backward-weight convolution (Sec.3.4: g_W = g_z^T a) for stride-1 filters with 3 or 7 taps along
-// one image axis, on int8 MFMA with int32 accumulation.  Same result, partial-tile format and final
+// Dense backward-weight convolution (Sec.3.4: g_W = g_z^T a) for stride-1 filters with 1, 3 or 7 taps along
+// one image axis, strided 1x1 filters and 3x3 filters under stride 2, on int8 MFMA with int32 accumulation.  Same result, partial-tile format and final
 // reduction as conv_wgrad.hip; what differs is how the operands reach the matrix cores.
 //
 // GEMM view:  D[k][(tap,c)] = sum over (n,p,q) of  Gz[(n,p,q)][k] * A[(n, p+r-ph, q+s-pw)][c].
@@ -17,6 +17,10 @@
 // input operand and ONE gradient operand and feeds up to 7 MFMAs -- the gradient operands of the last 7
 // positions stay in registers (a sliding window), each tap has its own accumulator.  Positions in the zero
 // padding are never multiplied at all.  (The kernel in conv_wgrad.hip reads 8 operands for 7 MFMAs.)
+// A 3x3 filter under stride 2 x 2 walks the same way with two input positions per gradient position: with
+// pl the padding along the line, gradient position u meets the inputs 2u - pl (tap 0) and 2u - pl + 1 (tap 1),
+// and the first of them is also what tap 2 of gradient position u - 1 meets -- three MFMAs per step for one
+// gradient operand and two input operands, the previous gradient operand kept in registers.
 #include "device_common.h"
 #include "kernels.h"
 #include "lds_dma.h"
@@ -31,21 +35,26 @@ constexpr int WL_LINES = 32;                     // lines per chunk: the reducti
 constexpr int WL_SUB = WL_LINES * 64;            // bytes of one position of 64 channels of one tensor
 constexpr int WL_NSTAGE = 2;
 // ring stage of a variant: GP positions, each the input's WN and the gradient's WM 64-channel slabs
-__host__ __device__ constexpr int wl_stage_bytes(int WM, int WN, int GP) { return GP * (WM + WN) * WL_SUB; }
+// (XPS input positions per step: 2 under stride 2)
+__host__ __device__ constexpr int wl_stage_bytes(int WM, int WN, int GP, int XPS = 1) { return GP * (WM + XPS * WN) * WL_SUB; }
 
 typedef __attribute__((address_space(3))) wl_v2i* wl_lds_ptr;
 
 // ST taps along the line; a wave owns WM x WN MFMA tiles (32 filters x 32 channels each) per tap, the block's
 // four waves (2 x 2) a tile of 64 WM filters x 64 WN channels; GP positions per ring stage.
-template <int ST, int WM, int WN, int GP>
+// S2: stride 2 x 2 (3 taps along the line, one MFMA tile per wave and tap).
+template <int ST, int WM, int WN, int GP, bool S2 = false>
 __global__ __launch_bounds__(256, 2) void wgrad_lines_kernel(const WgradArgs a) {
-    constexpr int NSLOT = ST + 1;                // gradient operands kept: the window of ST plus the one being fetched
+    // gradient operands kept: the window (ST positions; 2 under stride 2) plus the one being fetched
+    constexpr int NSLOT = S2 ? 3 : ST + 1;
     static_assert(GP % NSLOT == 0, "the window slot of a position must not depend on the stage");
     static_assert((WM == 1 && WN == 1) || (WM == 2 && WN == 2), "loader roles below");
+    static_assert(!S2 || (ST == 3 && WM == 1 && WN == 1), "stride 2: 3 taps, one tile per wave and tap");
     constexpr bool BOTH = WM + WN == 4;          // every wave loads both tensors (else waves 0,1 the input, 2,3 the gradient)
-    constexpr int STAGE = wl_stage_bytes(WM, WN, GP);
+    constexpr int XPS = S2 ? 2 : 1;              // input positions per step
+    constexpr int STAGE = wl_stage_bytes(WM, WN, GP, XPS);
     constexpr int XPOS = WN * WL_SUB, YPOS = WM * WL_SUB;   // bytes per position
-    constexpr int YOFF = GP * XPOS;                        // gradient slabs follow the input slabs
+    constexpr int YOFF = GP * XPS * XPOS;                  // gradient slabs follow the input slabs
     extern __shared__ __attribute__((aligned(1024))) unsigned char lsm[];
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -96,7 +105,7 @@ __global__ __launch_bounds__(256, 2) void wgrad_lines_kernel(const WgradArgs a) 
     const int QL = along_w ? a.Q : a.P;           // gradient positions on a line
     // A strided 1x1 filter without padding (the shortcut of a residual stage) reads the sub-image of every stride_h-th
     // row and stride_w-th pixel: the same pass on an input of P x Q positions whose lines and positions lie further apart.
-    const bool strided = a.stride_h != 1 || a.stride_w != 1;          // (1x1, no padding: wgrad_lines_applies)
+    const bool strided = !S2 && (a.stride_h != 1 || a.stride_w != 1);   // (1x1, no padding: wgrad_lines_applies)
     const int WLn = strided ? QL : along_w ? a.W : a.H;          // input positions on a line
     const int pl = along_w ? a.pad_w : a.pad_h;   // padding along the line
     const int XC = strided ? NLI : along_w ? a.H : a.W;           // input lines per image
@@ -104,13 +113,14 @@ __global__ __launch_bounds__(256, 2) void wgrad_lines_kernel(const WgradArgs a) 
     const int t0 = along_w ? tg * a.S : 0;        // first tap of the block (taps numbered r*S + s)
     const uint32_t dy_ls = along_w ? (uint32_t)a.Q * a.Kp : (uint32_t)a.Kp;
     const uint32_t dy_ps = along_w ? (uint32_t)a.Kp : (uint32_t)a.Q * a.Kp;
-    const uint32_t x_ls = along_w ? (uint32_t)a.W * a.Cp * a.stride_h : (uint32_t)a.Cp;
-    const uint32_t x_ps = along_w ? (uint32_t)a.Cp * a.stride_w : (uint32_t)a.W * a.Cp;
+    const uint32_t x_ls = S2 ? (uint32_t)a.W * a.Cp : along_w ? (uint32_t)a.W * a.Cp * a.stride_h : (uint32_t)a.Cp;
+    const uint32_t x_ps = S2 ? (uint32_t)a.Cp : along_w ? (uint32_t)a.Cp * a.stride_w : (uint32_t)a.W * a.Cp;
     // Step u of a line: the gradient position u enters the window, the input position u - pl is
     // multiplied with the gradient positions u, u-1, .., u-ST+1 (taps 0 .. ST-1).  A ring stage holds GP
     // steps of one chunk.  (Letting the stages run on across chunk ends saves the idle steps of a chunk's last
     // stage, but the bookkeeping per step costs more than they do: measured 26 -> 28 us on 14 x 14 images.)
-    const int U = WLn + pl;
+    // Stride 2: step u brings gradient position u and the input positions 2u - pl, 2u - pl + 1; steps 0 .. QL.
+    const int U = S2 ? QL + 1 : WLn + pl;
     const int GC = (U + GP - 1) / GP;             // ring stages per chunk
     const int total_lines = a.N * NLI;
     const int c_begin = (int)(((uint32_t)a.chunks * (uint32_t)zshare) / (uint32_t)a.splits);
@@ -130,6 +140,8 @@ __global__ __launch_bounds__(256, 2) void wgrad_lines_kernel(const WgradArgs a) 
     uint32_t ld_ps[NLD], ld_img[NLD], ld_ls[NLD], ld_dst[NLD], ld_pitch[NLD], ld_base[NLD];
     int ld_npos[NLD], ld_poff[NLD], ld_lshift[NLD], ld_nlines[NLD], ld_chan[NLD];
     bool ld_chan_ok[NLD];
+    const bool ld_input = !BOTH && (wave >> 1) == 0;        // (stride 2) this wave fetches the input
+    const int ld_lmul = (S2 && ld_input) ? 2 : 1;           // gradient line l of an image pairs with input line 2l + xshift
 #pragma unroll
     for (int e = 0; e < NLD; ++e) {
         const int tensor = BOTH ? e : (wave >> 1);              // 0: input codes, 1: gradient codes
@@ -154,7 +166,7 @@ __global__ __launch_bounds__(256, 2) void wgrad_lines_kernel(const WgradArgs a) 
         const int L = chunk * WL_LINES + myline;
         if (chunk >= c_end || L >= total_lines || !ld_chan_ok[e]) return IGD_OOB;
         const int n = L / NLI;
-        const int l = L - n * NLI + ld_lshift[e];
+        const int l = (L - n * NLI) * ld_lmul + ld_lshift[e];
         if ((unsigned)l >= (unsigned)ld_nlines[e]) return IGD_OOB;
         return (uint32_t)n * ld_img[e] + (uint32_t)l * ld_ls[e] + (uint32_t)ld_chan[e];
     };
@@ -164,6 +176,23 @@ __global__ __launch_bounds__(256, 2) void wgrad_lines_kernel(const WgradArgs a) 
     auto issue = [&](int slot) {
 #pragma unroll
         for (int j = 0; j < GP; ++j) {
+            if (S2) {
+                if (ld_input) {
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const int pos = 2 * (lg * GP + j) - pl + h;
+                        const bool ok = ld_base[0] != IGD_OOB && (unsigned)pos < (unsigned)ld_npos[0];
+                        igd_load_lds(rsrc[0], ld_dst[0] + (uint32_t)slot * STAGE + (uint32_t)(2 * j + h) * XPOS,
+                                     ok ? ld_base[0] + (uint32_t)pos * ld_ps[0] : IGD_OOB);
+                    }
+                } else {
+                    const int pos = lg * GP + j;
+                    const bool ok = ld_base[0] != IGD_OOB && (unsigned)pos < (unsigned)ld_npos[0];
+                    igd_load_lds(rsrc[0], ld_dst[0] + (uint32_t)slot * STAGE + (uint32_t)j * YPOS,
+                                 ok ? ld_base[0] + (uint32_t)pos * ld_ps[0] : IGD_OOB);
+                }
+                continue;
+            }
 #pragma unroll
             for (int e = 0; e < NLD; ++e) {
                 const int pos = lg * GP + j - ld_poff[e];
@@ -219,6 +248,29 @@ __global__ __launch_bounds__(256, 2) void wgrad_lines_kernel(const WgradArgs a) 
             const wl_v2i r1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32(p + (bytes + 512) / 8);
             return wl_v4i{r0.x, r0.y, r1.x, r1.y};
         };
+        if constexpr (S2) {
+            wl_v4i Ba_n = fetch(offB[0], 0), Bb_n = fetch(offB[0], XPOS);
+            A[0][0] = fetch(offA[0], 0);
+#pragma unroll
+            for (int j = 0; j < GP; ++j) {
+                const wl_v4i Ba = Ba_n, Bb = Bb_n;
+                if (j + 1 < GP) {
+                    A[(j + 1) % NSLOT][0] = fetch(offA[0], (j + 1) * YPOS);
+                    Ba_n = fetch(offB[0], (2 * j + 2) * XPOS);
+                    Bb_n = fetch(offB[0], (2 * j + 3) * XPOS);
+                }
+                const int u = g * GP + j;
+                if (__builtin_expect(u < QL, 1)) {
+                    acc[0][0][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[j % NSLOT][0], Ba, acc[0][0][0], 0, 0, 0);
+                    acc[1][0][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[j % NSLOT][0], Bb, acc[1][0][0], 0, 0, 0);
+                }
+                // tap 2 of the previous gradient position (none at the start of a line; the last step has only this)
+                if (__builtin_expect(u >= 1 && u <= QL, 1))
+                    acc[2][0][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[(j + NSLOT - 1) % NSLOT][0], Ba, acc[2][0][0], 0, 0, 0);
+            }
+            if (++g == GC) g = 0;
+            continue;
+        }
         wl_v4i Bn[WN], Bc[WN];
 #pragma unroll
         for (int k = 0; k < WN; ++k) Bn[k] = fetch(offB[k], 0);
@@ -273,11 +325,17 @@ __global__ __launch_bounds__(256, 2) void wgrad_lines_kernel(const WgradArgs a) 
     }
 }
 
+// the stride-2 form of the kernel: 3x3 filters, stride 2 x 2
+bool wgrad_lines_s2(const WgradArgs& a) {
+    return a.R == 3 && a.S == 3 && a.stride_h == 2 && a.stride_w == 2 && a.pad_h <= 2 && a.pad_w <= 2;
+}
+
 bool wgrad_lines_applies(const WgradArgs& a) {
     const bool one = a.R == 1 && a.S == 1;
     if (a.s2d) return false;
-    // strides: 1x1 filters without padding only (the pass then runs on every stride-th row and pixel)
-    if ((a.stride_h != 1 || a.stride_w != 1) && !(one && a.pad_h == 0 && a.pad_w == 0)) return false;
+    // strides: 1x1 filters without padding (the pass then runs on every stride-th row and pixel), and 3x3 filters
+    // under stride 2 x 2
+    if ((a.stride_h != 1 || a.stride_w != 1) && !(one && a.pad_h == 0 && a.pad_w == 0) && !wgrad_lines_s2(a)) return false;
     const bool along_w = a.S == 3 || a.S == 7;
     const bool along_h = a.S == 1 && (a.R == 3 || a.R == 7);
     if (!one && !along_w && !along_h) return false;
@@ -290,7 +348,8 @@ void wgrad_plan_lines(WgradArgs* a) {
     const bool along_w = wgrad_lines_along_w(a->R, a->S);
     const int ST = along_w ? a->S : a->R;
     const int WT = ST == 1 ? 2 : 1;              // MFMA tiles per wave and tap in each direction
-    const int GP = ST == 1 ? 4 : 8;
+    const bool s2 = wgrad_lines_s2(*a);
+    const int GP = ST == 1 ? 4 : s2 ? 3 : 8;
     a->lines = 1;
     a->TB = ST;
     a->CS = WT;
@@ -302,9 +361,9 @@ void wgrad_plan_lines(WgradArgs* a) {
     const int NLI = along_w ? a->P : a->Q;
     const int QL = along_w ? a->Q : a->P;
     const int WLn = (a->stride_h != 1 || a->stride_w != 1) ? QL : along_w ? a->W : a->H;
-    const int pl = along_w ? a->pad_w : a->pad_h;
+    const int pl = s2 ? 1 : along_w ? a->pad_w : a->pad_h;      // (stride 2: QL + 1 steps per chunk)
     a->chunks = (a->N * NLI + WL_LINES - 1) / WL_LINES;
-    a->lds_bytes = (size_t)WL_NSTAGE * wl_stage_bytes(WT, WT, GP);
+    a->lds_bytes = (size_t)WL_NSTAGE * wl_stage_bytes(WT, WT, GP, s2 ? 2 : 1);
     // Split count by the same estimate as wgrad_plan(): rounds of resident blocks (two per compute unit),
     // a block pays a prologue plus its stages, every split one write and one read of the partial tiles.
     const int out_tiles = a->ktiles * a->ctiles * a->tapgroups;
@@ -350,17 +409,18 @@ unsigned wgrad_lines_grid(const WgradArgs& a) {
 hipError_t launch_wgrad_lines(const WgradArgs& a, hipStream_t st) {
     const dim3 grid(wgrad_lines_grid(a));
     KernelTimer kt(KID_WGRAD_LINES, st);
-#define LAUNCH(STv, WTv, GPv)                                                                            \
+#define LAUNCH(STv, WTv, GPv, S2v)                                                                       \
     do {                                                                                                 \
         static std::atomic<unsigned long long> attr_done;                                                \
-        hipError_t ea = raise_dynamic_lds(reinterpret_cast<const void*>(wgrad_lines_kernel<STv, WTv, WTv, GPv>), \
-                                          WL_NSTAGE * wl_stage_bytes(WTv, WTv, GPv), attr_done);         \
+        hipError_t ea = raise_dynamic_lds(reinterpret_cast<const void*>(wgrad_lines_kernel<STv, WTv, WTv, GPv, S2v>), \
+                                          WL_NSTAGE * wl_stage_bytes(WTv, WTv, GPv, S2v ? 2 : 1), attr_done); \
         if (ea != hipSuccess) return ea;                                                                 \
-        launch_timed(kt, (wgrad_lines_kernel<STv, WTv, WTv, GPv>), grid, dim3(256), a.lds_bytes, st, a); \
+        launch_timed(kt, (wgrad_lines_kernel<STv, WTv, WTv, GPv, S2v>), grid, dim3(256), a.lds_bytes, st, a); \
     } while (0)
-    if (a.TB == 3) LAUNCH(3, 1, 8);
-    else if (a.TB == 7) LAUNCH(7, 1, 8);
-    else if (a.TB == 1) LAUNCH(1, 2, 4);
+    if (a.TB == 3 && wgrad_lines_s2(a)) LAUNCH(3, 1, 3, true);
+    else if (a.TB == 3) LAUNCH(3, 1, 8, false);
+    else if (a.TB == 7) LAUNCH(7, 1, 8, false);
+    else if (a.TB == 1) LAUNCH(1, 2, 4, false);
     else return hipErrorInvalidValue;
 #undef LAUNCH
     return hipGetLastError();

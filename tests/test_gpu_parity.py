@@ -330,6 +330,10 @@ CONV_SHAPES = [
     (2, 40, 9, 10, 72, 3, 3, (2, 2), (1, 1), 1),
     (1, 16, 13, 11, 24, 5, 3, (3, 2), (2, 1), 1),
     (1, 16, 7, 7, 16, 2, 2, (3, 3), (0, 0), 1),        # stride larger than the filter: pixels no tap reaches
+    # 3x3 under stride 2: backward-weight walks image rows with two input positions per gradient position
+    (3, 40, 23, 12, 72, 3, 3, (2, 2), (0, 2), 1),      # no padding along H, 2 along W; even row length
+    (5, 130, 21, 11, 70, 3, 3, (2, 2), (2, 0), 1),     # 60 gradient rows: two chunks of 32 lines; odd row length
+    (2, 16, 8, 35, 16, 3, 3, (2, 2), (1, 1), 1),       # 18 steps per line: exactly three ring stages
     # strided backward-data split into residue classes of the pixels: rows of at least 24 pixels, or a
     # reduction of at least 2048 bytes per pixel
     (1, 16, 9, 26, 24, 3, 3, (2, 2), (1, 1), 1),
