@@ -315,7 +315,8 @@ int8t_status int8t_conv_bwd_weight(const int8t_conv_desc *desc,
  * the layer's own buffers and selects the fastest.  The selection is kept in a process-wide table
  * keyed by (pass, descriptor) until it is changed; INT8T_VARIANT_AUTO (the default for every layer)
  * restores the library's own rules.  Thread-safe; not device-specific.
- *   forward / backward-data:  BAND, TILE, TILE_SPLIT, WIDE128, WIDE256, WIDE_SQ128, WIDE_SQ128_DEEP, WIDE_128X64
+ *   forward / backward-data:  BAND, TILE, TILE_SPLIT, WIDE128, WIDE256, WIDE_SQ128, WIDE_SQ128_DEEP, WIDE_128X64;
+ *   backward-data only:       WIDE_CELLS
  *   backward-weight:          WGRAD_IMAGES, WGRAD_LINES (the two kernels), WGRAD_FEWER, WGRAD_MORE (half / twice the
  *                             reduction shares of the cost model's choice); query int8t_workspace_bytes() again
  *                             after selecting any of them
@@ -339,9 +340,12 @@ typedef enum {
                                         compute unit: layers that have too few of the larger tiles to go round */
     INT8T_VARIANT_WIDE_SQ128_DEEP = 11,  /* ... with 2 stages of 128 reduction bytes: long reductions */
     INT8T_VARIANT_WIDE_128X64 = 12,      /* ... 128 x 64 tiles with 128-byte stages: few columns (7 x 7 images) */
+    INT8T_VARIANT_WIDE_CELLS = 13,       /* backward-data of a layer with stride 2 x 2 and a filter of at least 2 x 2: tiles of 128
+                                            rows x 64 cells of 2 x 2 pixels; a block runs the four pixel classes in turn and
+                                            writes whole cells */
     INT8T_VARIANT_MAX_ENUM = 0x7fffffff
 } int8t_variant;
-#define INT8T_VARIANT_COUNT 13
+#define INT8T_VARIANT_COUNT 14
 /* 1 when `variant` can run pass `op` (INT8T_OP_CONV_*) of the layer, else 0 (also on a bad descriptor). */
 int int8t_conv_variant_ok(int8t_op op, const int8t_conv_desc *desc, int8t_variant variant);
 /* INT8T_ERR_ARG when the variant cannot run that pass of that layer; then nothing changes. */

@@ -19,9 +19,9 @@ ACT, WGT, ACT_PLANAR, WGT_PLANAR = 0, 1, 2, 3
 OP_QUANTIZE, OP_DSGC, OP_CONV_FWD, OP_CONV_BWD_DATA, OP_CONV_BWD_WEIGHT = range(5)
 (VARIANT_AUTO, VARIANT_BAND, VARIANT_TILE, VARIANT_TILE_SPLIT, VARIANT_WIDE128, VARIANT_WIDE256,
  VARIANT_WGRAD_FEWER, VARIANT_WGRAD_MORE, VARIANT_WGRAD_IMAGES, VARIANT_WGRAD_LINES, VARIANT_WIDE_SQ128,
- VARIANT_WIDE_SQ128_DEEP, VARIANT_WIDE_128X64) = range(13)
+ VARIANT_WIDE_SQ128_DEEP, VARIANT_WIDE_128X64, VARIANT_WIDE_CELLS) = range(14)
 VARIANT_NAMES = ["auto", "band", "tile", "tile_split", "wide128", "wide256", "wgrad_fewer", "wgrad_more", "wgrad_images",
-                 "wgrad_lines", "wide_sq128", "wide_sq128_deep", "wide_128x64"]
+                 "wgrad_lines", "wide_sq128", "wide_sq128_deep", "wide_128x64", "wide_cells"]
 MAX_CANDIDATES = 64
 MAX_BATCH = 8
 

@@ -388,11 +388,17 @@ __global__ __launch_bounds__(256) void igemm_reduce_kernel(const IgemmArgs a, si
 //   <WM=2, KG=8, NSTAGE=2, BNT=64>: 128 x 64 (waves of 64 x 32), 48 KB: twice the tiles for layers with few columns
 //   (7 x 7 and 8 x 8 images), which otherwise leave more than half of the compute units idle
 // ---------------------------------------------------------------------------------------------
-template <bool DGRAD, int WM, int KG, int NSTAGE, bool CLS = false, bool CELL = false, int BNT = IGD_BN>
-__global__ __launch_bounds__(128 * WM, WM == 2 ? ((BNT == 128 && KG == 4) || BNT == 64 ? 3 : 2) : 1) void igemm_dma_kernel(const IgemmArgs a) {
+//   ALLC (with CLS and CELL, stride 2 x 2, every class with taps): the columns are the 2 x 2 cells of pixels and the
+//   block runs the four classes one after the other, each into accumulators of its own, then writes every cell
+//   whole -- two neighbouring floats per lane and image row, whole cache lines per wave -- where the per-class
+//   form writes every other float of a line from four different blocks and pays a block's fixed cost per class.
+template <bool DGRAD, int WM, int KG, int NSTAGE, bool CLS = false, bool CELL = false, int BNT = IGD_BN, bool ALLC = false>
+__global__ __launch_bounds__(128 * WM, WM == 2 ? (ALLC ? 2 : (BNT == 128 && KG == 4) || BNT == 64 ? 3 : 2) : 1) void igemm_dma_kernel(const IgemmArgs a) {
     static_assert(DGRAD || !CLS, "residue classes exist in the backward-data pass only");
     static_assert(CLS || !CELL, "the cell form is a residue-class form");
+    static_assert(!ALLC || (CLS && CELL && BNT == 64), "all classes per block: cell columns, 64 of them");
     constexpr int BM = 64 * WM, BN = BNT, MI = 2, NJ = BN / 64, NW = 2 * WM;
+    constexpr int NC = ALLC ? 4 : 1;                    // classes a block runs
     constexpr int STAGE_SLOTS = (BM + BN) * KG;         // 16-byte slots per stage: A tile, then B tile
     constexpr int RPL = 64 / KG;                        // tile rows covered by one wave-wide load
     constexpr int NLA = BM * KG / 64 / NW;              // A loads per wave and stage
@@ -420,7 +426,7 @@ __global__ __launch_bounds__(128 * WM, WM == 2 ? ((BNT == 128 && KG == 4) || BNT
     DgradClass dc;
     if (CLS) {
         if (CELL) {
-            dc = dgrad_class(a, a.cell - 1);
+            dc = dgrad_class(a, ALLC ? 0 : a.cell - 1);
             dc.OHc = (a.OH + a.cls_h - 1) / a.cls_h;      // cells, not pixels of the class
             dc.OWc = (a.OW + a.cls_w - 1) / a.cls_w;
         } else {
@@ -433,9 +439,9 @@ __global__ __launch_bounds__(128 * WM, WM == 2 ? ((BNT == 128 && KG == 4) || BNT
     const int OWc = CLS ? dc.OWc : a.OW;
     const int OHW = CLS ? dc.OHc * dc.OWc : OHWfull;     // columns per image
     const int ncols = a.N * OHW;
-    const int nr = CLS ? dc.nr : a.R, ns = CLS ? dc.ns : a.S;
-    const int gtot = nr * ns * Cg16;
-    const int nsteps = (gtot + KG - 1) / KG;
+    int nr = CLS ? dc.nr : a.R, ns = CLS ? dc.ns : a.S;  // (ALLC: of the class being run)
+    int gtot = nr * ns * Cg16;
+    int nsteps = (gtot + KG - 1) / KG;
     const int ctile = (cgroup << 3) + (int)(blockIdx.x & 7);
     if (ctile * BN >= ncols) return;
     const int rowbase = (wg_i % rtiles) * BM;
@@ -462,6 +468,7 @@ __global__ __launch_bounds__(128 * WM, WM == 2 ? ((BNT == 128 && KG == 4) || BNT
         aoff[i] = row < a.rows ? (uint32_t)row * (uint32_t)gfull * 16u : IGD_OOB;
     }
     int bh[NLB], bw[NLB];
+    int boh[NLB], bow[NLB];                                  // (ALLC) the column's cell, to which each class adds its offset
     uint32_t bimg[NLB];                                      // byte offset of the column's image or OOB
 #pragma unroll
     for (int i = 0; i < NLB; ++i) {
@@ -470,19 +477,23 @@ __global__ __launch_bounds__(128 * WM, WM == 2 ? ((BNT == 128 && KG == 4) || BNT
         const int cc = cv ? col : 0;
         const int n = cc / OHW, rem = cc - n * OHW;
         const int oh = rem / OWc, ow = rem - oh * OWc;
+        boh[i] = oh;
+        bow[i] = ow;
         bh[i] = CLS ? (oh + dc.bh) : DGRAD ? (oh + a.pad_h) : (oh * a.stride_h - a.pad_h);
         bw[i] = CLS ? (ow + dc.bw) : DGRAD ? (ow + a.pad_w) : (ow * a.stride_w - a.pad_w);
         bimg[i] = cv ? (uint32_t)n * (uint32_t)(a.IH * a.IW * a.Ca) : IGD_OOB;
     }
     // reduction position of this lane's granule: filter tap (r,s) and channel granule cg
     int r, s, cg;
-    {
+    int qnext;                                               // granule index of the next stage to issue
+    auto first_granule = [&]() {
         const int tap = gsw / Cg16;
         cg = gsw - tap * Cg16;
         r = tap / (ns > 0 ? ns : 1);
         s = tap - r * ns;
-    }
-    int qnext = gsw;                                         // granule index of the next stage to issue
+        qnext = gsw;
+    };
+    first_granule();
 
     auto issue_a = [&](int buf) {
         const uint32_t boff = (uint32_t)buf * (STAGE_SLOTS * 16u);
@@ -534,14 +545,33 @@ __global__ __launch_bounds__(128 * WM, WM == 2 ? ((BNT == 128 && KG == 4) || BNT
         }
     };
 
-    v16i acc[MI][NJ];
+    v16i acc[NC][MI][NJ];
 #pragma unroll
-    for (int i = 0; i < MI; ++i)
+    for (int c = 0; c < NC; ++c)
 #pragma unroll
-        for (int j = 0; j < NJ; ++j)
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+            for (int j = 0; j < NJ; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[c][i][j][v] = 0;
 
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+    if (ALLC && c > 0) {
+        // the next class: its taps and offsets; the ring is free once every wave has read the last stage
+        dc = dgrad_class(a, c);
+        nr = dc.nr;
+        ns = dc.ns;
+        gtot = nr * ns * Cg16;
+        nsteps = (gtot + KG - 1) / KG;
+#pragma unroll
+        for (int i = 0; i < NLB; ++i) {
+            bh[i] = boh[i] + dc.bh;
+            bw[i] = bow[i] + dc.bw;
+        }
+        first_granule();
+        __syncthreads();
+    }
     // prologue: the first NSTAGE-1 stages on their way
     if (nsteps > 0) {     // (a class without taps has nothing to load: its pixels get zeros)
         issue_a(0);
@@ -588,10 +618,11 @@ __global__ __launch_bounds__(128 * WM, WM == 2 ? ((BNT == 128 && KG == 4) || BNT
             for (int i = 0; i < MI; ++i)
 #pragma unroll
                 for (int j = 0; j < NJ; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                    acc[c][i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[c][i][j], 0, 0, 0);
             if (kk == (KG >= 8 ? KG / 4 - 1 : 0) && more) issue_b(nbuf);
         }
     }
+    }   // classes
 
     // ---- epilogue: Eq.2, straight into N,C,H,W ----------------------------------------------
     const float scale = __fmul_rn(a.sa[0], a.sb[0]);
@@ -614,8 +645,38 @@ __global__ __launch_bounds__(128 * WM, WM == 2 ? ((BNT == 128 && KG == 4) || BNT
                 const int row = rowbase + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
                 if (row < a.rows) {
                     const size_t idx = ((size_t)n * a.rows + row) * OHWfull + opix;
-                    const int val = acc[i][j][v];
-                    if (CELL) {
+                    const int val = acc[0][i][j][v];
+                    if (ALLC) {
+                        // the cell's four pixels, classes (row parity, column parity) = 0 .. 3; the last cell row / column
+                        // of an odd image holds one row / column only
+                        const size_t o = ((size_t)n * a.rows + row) * OHWfull + (size_t)(2 * ci) * a.OW + 2 * cj;
+                        const bool two = 2 * ci + 1 < a.OH, right = 2 * cj + 1 < a.OW;
+                        const int v00 = val, v01 = acc[NC > 1 ? 1 : 0][i][j][v], v10 = acc[NC > 2 ? 2 : 0][i][j][v],
+                                  v11 = acc[NC > 3 ? 3 : 0][i][j][v];
+                        if (!(a.OW & 1)) {          // every cell starts on an 8-byte boundary
+                            *reinterpret_cast<float2*>(a.out + o) = make_float2(__fmul_rn((float)v00, scale), __fmul_rn((float)v01, scale));
+                            if (two) *reinterpret_cast<float2*>(a.out + o + a.OW) = make_float2(__fmul_rn((float)v10, scale), __fmul_rn((float)v11, scale));
+                            if (a.acc) {
+                                *reinterpret_cast<int2*>(a.acc + o) = make_int2(v00, v01);
+                                if (two) *reinterpret_cast<int2*>(a.acc + o + a.OW) = make_int2(v10, v11);
+                            }
+                        } else {
+                            a.out[o] = __fmul_rn((float)v00, scale);
+                            if (right) a.out[o + 1] = __fmul_rn((float)v01, scale);
+                            if (two) {
+                                a.out[o + a.OW] = __fmul_rn((float)v10, scale);
+                                if (right) a.out[o + a.OW + 1] = __fmul_rn((float)v11, scale);
+                            }
+                            if (a.acc) {
+                                a.acc[o] = v00;
+                                if (right) a.acc[o + 1] = v01;
+                                if (two) {
+                                    a.acc[o + a.OW] = v10;
+                                    if (right) a.acc[o + a.OW + 1] = v11;
+                                }
+                            }
+                        }
+                    } else if (CELL) {
                         const size_t o = ((size_t)n * a.rows + row) * OHWfull + (size_t)(2 * ci) * a.OW + 2 * cj;
                         const bool two = 2 * ci + 1 < a.OH;
                         store_cell<float, float2>(a.out, o, a.OW, two, dc.ch, dc.cw, __fmul_rn((float)val, scale));
@@ -678,17 +739,17 @@ IgemmShape igemm_shape(const IgemmArgs& a) {
 }
 }  // namespace
 
-template <bool DGRAD, int WM, int KG, int NSTAGE, bool CLS, bool CELL, int BNT = IGD_BN>
+template <bool DGRAD, int WM, int KG, int NSTAGE, bool CLS, bool CELL, int BNT = IGD_BN, bool ALLC = false>
 static hipError_t launch_igemm_dma(const IgemmArgs& a, const IgemmShape& g, hipStream_t st, const KernelTimer& kt) {
     const size_t lds = (size_t)NSTAGE * (64 * WM + BNT) * KG * 16;
     static std::atomic<unsigned long long> attr_done;
     {
-        hipError_t e = raise_dynamic_lds(reinterpret_cast<const void*>(igemm_dma_kernel<DGRAD, WM, KG, NSTAGE, CLS, CELL, BNT>), (int)lds, attr_done);
+        hipError_t e = raise_dynamic_lds(reinterpret_cast<const void*>(igemm_dma_kernel<DGRAD, WM, KG, NSTAGE, CLS, CELL, BNT, ALLC>), (int)lds, attr_done);
         if (e != hipSuccess) return e;
     }
     const unsigned ctiles = (unsigned)((g.ncols + BNT - 1) / BNT), rtiles = (unsigned)((a.rows + 64 * WM - 1) / (64 * WM));
     dim3 grid(((ctiles + 7) / 8) * 8 * rtiles * (unsigned)g.ncls);
-    launch_timed(kt, (igemm_dma_kernel<DGRAD, WM, KG, NSTAGE, CLS, CELL, BNT>), grid, dim3(128 * WM), lds, st, a);
+    launch_timed(kt, (igemm_dma_kernel<DGRAD, WM, KG, NSTAGE, CLS, CELL, BNT, ALLC>), grid, dim3(128 * WM), lds, st, a);
     return hipGetLastError();
 }
 template <int WM, int KG, int NSTAGE, int BNT = IGD_BN>
@@ -721,6 +782,11 @@ int igemm_ksplit(const IgemmArgs& a) {
     return ks < 2 ? 1 : (int)ks;
 }
 
+// the form that runs the four pixel classes of a stride-2 backward-data pass in one block: every class needs a tap
+static bool igemm_cells_ok(const IgemmArgs& a) {
+    return a.dgrad && a.stride_h == 2 && a.stride_w == 2 && a.R >= 2 && a.S >= 2;
+}
+
 // The variant the library picks on its own (rules from measurements over the layers of ResNet-50,
 // MobileNetV2 and InceptionV3); a caller may overrule it per layer (include/int8t.h).
 int igemm_auto_variant(const IgemmArgs& a) {
@@ -736,6 +802,11 @@ int igemm_auto_variant(const IgemmArgs& a) {
     //    with fewer than 512 tiles or the tap classes of a strided backward-data pass (56 x 56, 128 channels, 3x3, stride 2:
     //    44.7 against 53.9 us); 64-byte stages (three blocks) below (35 x 35, 96 channels, 3x3: 20.9 against 25.1 us)
     const IgemmShape g = igemm_shape(a);
+    //  - backward-data under stride 2 x 2 on images of at least 28 pixels a row, even row length: the four pixel classes in
+    //    one block, whole 2 x 2 cells written (56 x 56, 128 channels, 3x3: 43.7 -> 37.0 us; 28 x 28, 256 channels: 36.4 ->
+    //    28.1); on smaller images the four short reductions in a row cost more than the stores gain (14 x 14, 512 channels:
+    //    28.8 against 32.9), and with odd rows the cells no longer start on 8-byte boundaries (35 x 35: 39.6 against 40.4)
+    if (igemm_cells_ok(a) && g.cls && !g.cell && a.rows >= 128 && !(a.OW & 1) && a.OW >= 28) return VAR_WIDE_CELLS;
     const long long c256 = g.ncls * ((g.ncols + 255) / 256), c128 = g.ncls * ((g.ncols + 127) / 128);
     if (!g.cls && c256 * ((a.rows + 255) / 256) >= 192 && a.rows > 128 && g.gran >= 32) return VAR_WIDE256;
     const long long rt = (a.rows + 127) / 128, tiles = c128 * rt;
@@ -756,6 +827,7 @@ bool igemm_variant_ok(const IgemmArgs& a, int variant) {
         case VAR_AUTO: case VAR_TILE: case VAR_WIDE128: case VAR_WIDE256: case VAR_WIDE_SQ128: case VAR_WIDE_SQ128_DEEP: case VAR_WIDE_128X64: return true;
         case VAR_BAND: return launch_band(a, nullptr, &e, true);
         case VAR_TILE_SPLIT: return igemm_ksplit(a) > 1;
+        case VAR_WIDE_CELLS: return igemm_cells_ok(a);
         default: return false;
     }
 }
@@ -840,6 +912,18 @@ hipError_t launch_igemm(const IgemmArgs& a_in, hipStream_t st) {
         if ((total & 3) == 0) launch_timed(kt, igemm_reduce_kernel<true>, rgrid, dim3(256), 0, st, a, total);
         else launch_timed(kt, igemm_reduce_kernel<false>, rgrid, dim3(256), 0, st, a, total);
         return hipGetLastError();
+    }
+    if (variant == VAR_WIDE_CELLS) {
+        IgemmShape gc = g;
+        gc.cls = true;
+        gc.cell = 0;
+        gc.cls_h = gc.cls_w = 2;
+        gc.ncls = 1;
+        gc.ncols = (long long)a.N * ((a.OH + 1) / 2) * ((a.OW + 1) / 2);
+        a.cls_h = a.cls_w = 2;
+        a.cell = 0;
+        KernelTimer kt(KID_IGEMM_DMA, st);
+        return launch_igemm_dma<true, 2, 8, 2, true, true, 64, true>(a, gc, st, kt);
     }
     if (variant == VAR_WIDE128 || variant == VAR_WIDE256 || variant == VAR_WIDE_SQ128 || variant == VAR_WIDE_SQ128_DEEP ||
         variant == VAR_WIDE_128X64) {

@@ -152,6 +152,7 @@ enum ConvVariant : int {
     VAR_WIDE_SQ128 = 10,   // forward / backward-data: 128 x 128 tiles, ring of 3 stages, three blocks per compute unit
     VAR_WIDE_SQ128_DEEP = 11,   // ... 2 stages of 128 reduction bytes, two blocks per compute unit
     VAR_WIDE_128X64 = 12,       // ... 128 x 64 tiles: layers with few columns
+    VAR_WIDE_CELLS = 13,        // backward-data under stride 2 x 2: 128 rows x 64 cells of 2 x 2 pixels, the four pixel classes in one block
     VAR_COUNT
 };
 int igemm_ksplit(const IgemmArgs& a);   // largest split a launch of this layer may use (1 = none): sizes the scratch

@@ -467,6 +467,9 @@ WIDE_SHAPES = [
     ((32, 192, 63, 64, 512, 1, 1, (2, 2), (0, 0), 1), ("bwd_data",)),
     # ... a larger batch
     ((48, 192, 63, 64, 512, 1, 1, (2, 2), (0, 0), 1), ("bwd_data",)),
+    # backward-data with the four pixel classes of stride 2 in one block (rows of at least 28 pixels, even length):
+    # odd height, so that the last cell row is half empty
+    ((2, 130, 57, 60, 64, 3, 3, (2, 2), (1, 1), 1), ("bwd_data",)),
 ]
 
 
@@ -785,7 +788,12 @@ def test_every_kernel_variant_is_exact():
               # along H on few lines, 1x1 on 128 x 128 tiles with ragged edges
               (2, 40, 9, 13, 72, 3, 3, (1, 1), (1, 1), 1), (2, 64, 8, 8, 64, 3, 3, (1, 1), (2, 2), 1),
               (2, 48, 6, 20, 80, 7, 1, (1, 1), (3, 0), 1), (3, 130, 10, 6, 200, 1, 1, (1, 1), (0, 0), 1),
-              (1, 256, 3, 37, 130, 1, 7, (1, 1), (0, 3), 1)]
+              (1, 256, 3, 37, 130, 1, 7, (1, 1), (0, 3), 1),
+              # stride 2 x 2: backward-data on 2 x 2 cells with all four pixel classes in one block -- odd and even
+              # images (the last cell row / column half empty), 5- and 2-tap filters, ragged rows, several column tiles
+              (2, 40, 9, 10, 72, 3, 3, (2, 2), (1, 1), 1), (1, 16, 11, 13, 24, 5, 3, (2, 2), (2, 1), 1),
+              (2, 130, 8, 8, 70, 2, 2, (2, 2), (0, 0), 1), (3, 200, 17, 17, 48, 3, 3, (2, 2), (0, 0), 1),
+              (5, 24, 14, 15, 130, 3, 5, (2, 2), (1, 2), 1)]
     one = dev(np.array([1.0], np.float32))
     seen = set()
     for shape in shapes:
@@ -826,6 +834,7 @@ def test_every_kernel_variant_is_exact():
     for v in (B.VARIANT_BAND, B.VARIANT_TILE, B.VARIANT_TILE_SPLIT, B.VARIANT_WIDE128, B.VARIANT_WIDE256, B.VARIANT_WIDE_SQ128,
               B.VARIANT_WIDE_SQ128_DEEP, B.VARIANT_WIDE_128X64):
         assert ("fwd", v) in seen and ("bwd_data", v) in seen, B.VARIANT_NAMES[v]
+    assert ("bwd_data", B.VARIANT_WIDE_CELLS) in seen and ("fwd", B.VARIANT_WIDE_CELLS) not in seen
     for v in (B.VARIANT_WGRAD_FEWER, B.VARIANT_WGRAD_MORE, B.VARIANT_WGRAD_IMAGES, B.VARIANT_WGRAD_LINES):
         assert ("bwd_weight", v) in seen, B.VARIANT_NAMES[v]
 
