@@ -808,7 +808,11 @@ int igemm_auto_variant(const IgemmArgs& a) {
     //    28.8 against 32.9), and with odd rows the cells no longer start on 8-byte boundaries (35 x 35: 39.6 against 40.4)
     if (igemm_cells_ok(a) && g.cls && !g.cell && a.rows >= 128 && !(a.OW & 1) && a.OW >= 28) return VAR_WIDE_CELLS;
     const long long c256 = g.ncls * ((g.ncols + 255) / 256), c128 = g.ncls * ((g.ncols + 127) / 128);
-    if (!g.cls && c256 * ((a.rows + 255) / 256) >= 192 && a.rows > 128 && g.gran >= 32) return VAR_WIDE256;
+    // (a column tile's row tiles all run on XCD (column tile) mod 8, one block per compute unit: 243 tiles that put 33 blocks
+    // on an XCD of 32 compute units take two turns -- 1x1, 768 channels, 18 x 18, batch 64: 41.5 us against 29.8 on 128 x 128
+    // tiles -- so the 256 x 256 tiles must fill at least 0.7 of the turns they take)
+    const long long r256 = (a.rows + 255) / 256, t256 = c256 * r256, turns = (((c256 + 7) / 8) * r256 + 31) / 32;
+    if (!g.cls && t256 >= 192 && a.rows > 128 && g.gran >= 32 && 10 * t256 >= 7 * turns * 256) return VAR_WIDE256;
     const long long rt = (a.rows + 127) / 128, tiles = c128 * rt;
     const bool deep = g.gran >= 64 || (g.gran >= 32 && (tiles < 512 || (g.cls && !g.cell)));
     //  - 128 x 64 tiles where they go round the chip's block slots (three per compute unit; two for the 128-byte
