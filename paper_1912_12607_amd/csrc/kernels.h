@@ -237,8 +237,13 @@ void wgrad_plan_lines(WgradArgs* a);
 hipError_t launch_wgrad_lines(const WgradArgs& a, hipStream_t st);
 // which kernel VAR_AUTO stands for: true = wgrad_lines_kernel
 bool wgrad_auto_lines(const WgradArgs& a);
-// reduction shares of one XCD are given neighbouring workgroups when there are enough of them
-__host__ __device__ inline bool wgrad_xcd_mapping(int splits) { return splits >= 64 || (splits >= 8 && (splits & 7) == 0); }
+// Share z runs on XCD z mod 8 with all its output tiles (they read the same lines of both tensors, and every XCD fills
+// its own L2) when the shares go round the XCDs evenly enough: the grid holds a multiple of 8 shares, the extra ones
+// exit at once, and the XCDs with one share more take 8 / splits longer (at most 1/7 here).  Without it the tiles of a
+// share land on all 8 XCDs and each L2 fetches the share's lines again (256 x 128 -> 128 3x3 at 28 x 28: 68 -> 47 us).
+__host__ __device__ inline bool wgrad_xcd_mapping(int splits) {
+    return splits >= 8 && (((splits + 7) & ~7) - splits) * 7 <= splits;
+}
 
 // ---- conv_dw.hip (depthwise, planar codes) ----------------------------------------------------
 struct DwArgs {
