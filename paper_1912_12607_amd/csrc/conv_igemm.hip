@@ -789,10 +789,12 @@ static bool igemm_cells_ok(const IgemmArgs& a) {
 
 // The variant the library picks on its own (rules from measurements over the layers of ResNet-50,
 // MobileNetV2 and InceptionV3); a caller may overrule it per layer (include/int8t.h).
-int igemm_auto_variant(const IgemmArgs& a) {
+int igemm_auto_variant(const IgemmArgs& a, bool allow_split) {
     hipError_t e = hipSuccess;
     if (launch_band(a, nullptr, &e, true)) return VAR_BAND;
-    if (a.rows <= 64) return VAR_TILE;
+    // At most 64 rows and no band kernel (strides, filter banks too large for the chip): none of the three networks has
+    // such a pass; on 25 random ones the 128 x 64 LDS-DMA tile, half empty, took 0.5 - 0.85 of the 64-row tile's time.
+    if (a.rows <= 64) return VAR_WIDE_128X64;
     // Above 64 rows the 128 x 128 tiles of the LDS-DMA kernel win on nearly every layer of the three networks
     // (ResNet-50, batch 64: forward and backward-data 2.60 -> 2.11 ms in total; the best variant per layer would give 2.07):
     //  - 128 x 256 tiles of 4 waves per row pair where they are full, many, unsplit and the reduction is at least
@@ -802,11 +804,21 @@ int igemm_auto_variant(const IgemmArgs& a) {
     //    with fewer than 512 tiles or the tap classes of a strided backward-data pass (56 x 56, 128 channels, 3x3, stride 2:
     //    44.7 against 53.9 us); 64-byte stages (three blocks) below (35 x 35, 96 channels, 3x3: 20.9 against 25.1 us)
     const IgemmShape g = igemm_shape(a);
+    //  - few tiles and a very long reduction (5x5 and 7x7 filters on 1024 channels at 4 x 4 to 10 x 10, small batches): the
+    //    split reduction of igemm_kernel, when the caller gave the scratch for it.  Over 40 such layers it won from about
+    //    40 + 0.4 x (number of 128 x 64 tiles) stages of 128 bytes on, by up to 6.5x (16 tiles, 392 stages: 204 -> 31 us);
+    //    no layer of the three networks is that shape (their closest: 7 x 7, 512 channels, 3x3 with 196 tiles and 36
+    //    stages, 23 us on the LDS-DMA tiles against 35 split)
+    {
+        const long long t64s = g.ncls * ((g.ncols + 63) / 64) * ((a.rows + 127) / 128), stages = (g.gran + 7) / 8;
+        if (allow_split && 5 * stages >= 200 + 2 * t64s && igemm_ksplit(a) > 1) return VAR_TILE_SPLIT;
+    }
     //  - backward-data under stride 2 x 2 on images of at least 28 pixels a row, even row length: the four pixel classes in
     //    one block, whole 2 x 2 cells written (56 x 56, 128 channels, 3x3: 43.7 -> 37.0 us; 28 x 28, 256 channels: 36.4 ->
     //    28.1); on smaller images the four short reductions in a row cost more than the stores gain (14 x 14, 512 channels:
     //    28.8 against 32.9), and with odd rows the cells no longer start on 8-byte boundaries (35 x 35: 39.6 against 40.4)
-    if (igemm_cells_ok(a) && g.cls && !g.cell && a.rows >= 128 && !(a.OW & 1) && a.OW >= 28) return VAR_WIDE_CELLS;
+    //    (and with long reductions the block count matters more: 5x5 on 1024 channels, 141 against 82 us)
+    if (igemm_cells_ok(a) && g.cls && !g.cell && a.rows >= 128 && !(a.OW & 1) && a.OW >= 28 && g.gran <= 128) return VAR_WIDE_CELLS;
     const long long c256 = g.ncls * ((g.ncols + 255) / 256), c128 = g.ncls * ((g.ncols + 127) / 128);
     // (a column tile's row tiles all run on XCD (column tile) mod 8, one block per compute unit: 243 tiles that put 33 blocks
     // on an XCD of 32 compute units take two turns -- 1x1, 768 channels, 18 x 18, batch 64: 41.5 us against 29.8 on 128 x 128
@@ -889,7 +901,8 @@ hipError_t launch_igemm(const IgemmArgs& a_in, hipStream_t st) {
         }
     }
     int variant = a.variant;
-    if (variant == VAR_AUTO || !igemm_variant_ok(a, variant)) variant = igemm_auto_variant(a);
+    if (variant == VAR_AUTO || !igemm_variant_ok(a, variant))
+        variant = igemm_auto_variant(a, a.partial != nullptr && a.partial_bytes >= (size_t)igemm_ksplit(a) * a.rows * a.N * a.OH * a.OW * 4);
     if (variant == VAR_BAND) {
         hipError_t berr = hipSuccess;
         if (launch_band(a, st, &berr)) return berr;   // small filter bank: LDS-resident kernel

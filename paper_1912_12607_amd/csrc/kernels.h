@@ -158,7 +158,7 @@ enum ConvVariant : int {
 int igemm_ksplit(const IgemmArgs& a);   // largest split a launch of this layer may use (1 = none): sizes the scratch
 // whether `variant` can run this layer (VAR_AUTO always can); resolved = the variant VAR_AUTO stands for
 bool igemm_variant_ok(const IgemmArgs& a, int variant);
-int igemm_auto_variant(const IgemmArgs& a);
+int igemm_auto_variant(const IgemmArgs& a, bool allow_split = true);   // allow_split: the caller's scratch holds the partial sums of a split reduction
 // Forward pass of a layer s2d.hip covers: rewrites the geometry and returns the scratch bytes of the
 // rewritten input and filter codes (0: does not apply, the geometry is left alone).
 size_t igemm_s2d(IgemmArgs* a);
