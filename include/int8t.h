@@ -217,6 +217,20 @@ int8t_status int8t_dsgc_clip(const float *g_dev, size_t n, const float *ratios_d
  * n and ws_dev left it.  int8t_dsgc_clip is the two calls in a row; arguments as there.
  */
 int8t_status int8t_dsgc_prepare(const float *g_dev, size_t n, void *ws_dev, size_t ws_bytes, void *stream);
+/*
+ * int8t_quantize_batch and int8t_dsgc_prepare in one call: the pass over g shares the launch of the items'
+ * absmax passes (a step on one stream then has one launch fewer; Sec.3.4: max|.| of a, W and g_z are
+ * independent of each other).  Writes what the two calls write, bit for bit; int8t_dsgc_search follows it
+ * as it follows int8t_dsgc_prepare.
+ *   count, items, ws_dev, ws_bytes   as for int8t_quantize_batch
+ *   g_dev, n                         as for int8t_dsgc_prepare (required)
+ *   dsgc_ws_dev, dsgc_ws_bytes       the search's scratch: int8t_workspace_bytes(INT8T_OP_DSGC, NULL, n, n_cand) bytes,
+ *                                    16-byte aligned, not overlapping ws_dev
+ * Errors as for the two calls; nothing is launched then.
+ */
+int8t_status int8t_quantize_batch_prepare(int count, const int8t_quantize_item *items, void *ws_dev, size_t ws_bytes,
+                                          const float *g_dev, size_t n, void *dsgc_ws_dev, size_t dsgc_ws_bytes,
+                                          void *stream);
 int8t_status int8t_dsgc_search(const float *g_dev, size_t n, const float *ratios_dev, int n_cand,
                                int8t_round mode, uint64_t seed,
                                float *clip_dev, double *deviation_dev, double *deviation_all_dev,

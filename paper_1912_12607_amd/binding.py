@@ -27,7 +27,7 @@ MAX_BATCH = 8
 
 EXPORTS = ["int8t_status_string", "int8t_code_bytes", "int8t_unpack_codes", "int8t_workspace_bytes",
            "int8t_quantize_workspace_bytes", "int8t_quantize", "int8t_quantize_batch_workspace_bytes",
-           "int8t_quantize_batch", "int8t_dsgc_clip", "int8t_dsgc_clip_static", "int8t_dsgc_prepare", "int8t_dsgc_search", "int8t_conv_fwd", "int8t_conv_fwd_fused",
+           "int8t_quantize_batch", "int8t_quantize_batch_prepare", "int8t_dsgc_clip", "int8t_dsgc_clip_static", "int8t_dsgc_prepare", "int8t_dsgc_search", "int8t_conv_fwd", "int8t_conv_fwd_fused",
            "int8t_conv_bwd_data", "int8t_conv_bwd_weight", "int8t_dclr_scale",
            "int8t_conv_variant_ok", "int8t_conv_select_variant", "int8t_conv_selected_variant",
            "int8t_profile_start", "int8t_profile_start_sampled", "int8t_profile_stop", "int8t_profile_mfma_ceiling"]
@@ -75,6 +75,8 @@ def _load():
     L.int8t_quantize_batch_workspace_bytes.argtypes = [i32, C.POINTER(QuantizeItem)]
     L.int8t_quantize_batch.restype = i32
     L.int8t_quantize_batch.argtypes = [i32, C.POINTER(QuantizeItem), vp, sz, vp]
+    L.int8t_quantize_batch_prepare.restype = i32
+    L.int8t_quantize_batch_prepare.argtypes = [i32, C.POINTER(QuantizeItem), vp, sz, vp, sz, vp, sz, vp]
     L.int8t_dsgc_clip.restype = i32
     L.int8t_dsgc_clip.argtypes = [vp, sz, vp, i32, i32, u64, vp, vp, vp, vp, sz, vp]
     L.int8t_dsgc_clip_static.restype = i32
@@ -216,6 +218,11 @@ def int8t_quantize_batch_workspace_bytes(items) -> int:
 
 def int8t_quantize_batch(items, ws=None, stream=None):
     _check(lib.int8t_quantize_batch(len(items), _items(items), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def int8t_quantize_batch_prepare(items, ws, g, n, dsgc_ws, stream=None):
+    _check(lib.int8t_quantize_batch_prepare(len(items), _items(items), _ptr(ws), _nbytes(ws), _ptr(g), n, _ptr(dsgc_ws),
+                                            _nbytes(dsgc_ws), _stream(stream)))
 
 
 def int8t_dsgc_clip(g, n, ratios, n_cand, mode, seed, clip, deviation, deviation_all=None, ws=None,

@@ -343,10 +343,21 @@ size_t int8t_quantize_batch_workspace_bytes(int count, const int8t_quantize_item
     return (size_t)count * align256(kMaxPartials * sizeof(float));
 }
 
-int8t_status int8t_quantize_batch(int count, const int8t_quantize_item* items, void* ws_dev, size_t ws_bytes,
-                                  void* stream) {
+}  // extern "C"
+
+namespace {
+DsgcWs dsgc_ws_layout(void* ws_dev);
+// int8t_quantize_batch, and with g_dev also the first phase of a clip search on g in the same absmax launch
+int8t_status quantize_batch_impl(int count, const int8t_quantize_item* items, void* ws_dev, size_t ws_bytes,
+                                 const float* g_dev, size_t g_n, void* dsgc_ws_dev, size_t dsgc_ws_size, void* stream) {
     if (!items) return INT8T_ERR_NULL;
     if (count < 1 || count > INT8T_MAX_BATCH) return INT8T_ERR_ARG;
+    if (g_dev) {
+        if (!dsgc_ws_dev) return INT8T_ERR_NULL;
+        if (g_n == 0 || g_n > kMaxElems) return INT8T_ERR_SHAPE;
+        if (!aligned16(g_dev) || !aligned16(dsgc_ws_dev)) return INT8T_ERR_ARG;
+        if (dsgc_ws_size < dsgc_ws_bytes(g_n)) return INT8T_ERR_WORKSPACE;
+    }
     AbsmaxBatch ab{};
     QuantBatch qb{};
     qb.count = count;
@@ -405,10 +416,32 @@ int8t_status int8t_quantize_batch(int count, const int8t_quantize_item* items, v
         qblocks += (long long)q.gx * q.gy * q.gz;
         if (qblocks > 0x7FFFFFFFll) return INT8T_ERR_SHAPE;
     }
+    if (g_dev) {
+        const DsgcWs dws = dsgc_ws_layout(dsgc_ws_dev);
+        AbsmaxBatchItem& a = ab.it[ab.count++];
+        a.x = g_dev; a.n = g_n; a.part = dws.absmax_part; a.block0 = (int)ablocks; a.nblocks = absmax_blocks(g_n);
+        a.sumsq = dws.partG; a.zero = dws.acc; a.nzero = (int)dsgc_acc_words() + 1;
+        ablocks += a.nblocks;
+    }
     hipStream_t st = (hipStream_t)stream;
     if (ab.count && launch_absmax_batch(ab, (int)ablocks, st) != hipSuccess) return INT8T_ERR_RUNTIME;
     if (launch_quantize_batch(qb, (int)qblocks, st) != hipSuccess) return INT8T_ERR_RUNTIME;
     return INT8T_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int8t_status int8t_quantize_batch(int count, const int8t_quantize_item* items, void* ws_dev, size_t ws_bytes,
+                                  void* stream) {
+    return quantize_batch_impl(count, items, ws_dev, ws_bytes, nullptr, 0, nullptr, 0, stream);
+}
+
+int8t_status int8t_quantize_batch_prepare(int count, const int8t_quantize_item* items, void* ws_dev, size_t ws_bytes,
+                                          const float* g_dev, size_t n, void* dsgc_ws_dev, size_t dsgc_ws_size,
+                                          void* stream) {
+    if (!g_dev) return INT8T_ERR_NULL;
+    return quantize_batch_impl(count, items, ws_dev, ws_bytes, g_dev, n, dsgc_ws_dev, dsgc_ws_size, stream);
 }
 
 namespace {

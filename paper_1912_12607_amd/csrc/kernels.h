@@ -60,10 +60,15 @@ struct AbsmaxBatchItem {
     size_t n;
     float* part;                 // this tensor's partials
     int block0, nblocks;         // its block range inside the launch (nblocks = 0: clip supplied)
+    // the tensor of a clip search (at most one, the last item): its blocks also leave the sums of squares and clear
+    // the search's accumulators, as absmax_kernel<true> does
+    double* sumsq;
+    unsigned long long* zero;
+    int nzero;
 };
 struct AbsmaxBatch {
     int count;
-    AbsmaxBatchItem it[kMaxBatch];
+    AbsmaxBatchItem it[kMaxBatch + 1];
 };
 struct QuantBatchItem {
     const float* x;

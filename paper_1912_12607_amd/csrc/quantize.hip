@@ -99,7 +99,8 @@ __global__ __launch_bounds__(AM_THREADS) void absmax_batch_kernel(const AbsmaxBa
     int i = 0;
     while (i + 1 < b.count && (int)blockIdx.x >= b.it[i].block0 + b.it[i].nblocks) ++i;
     const AbsmaxBatchItem& t = b.it[i];
-    absmax_body<false>(t.x, t.n, t.part, nullptr, nullptr, 0, (int)blockIdx.x - t.block0, t.nblocks);
+    if (t.sumsq) absmax_body<true>(t.x, t.n, t.part, t.sumsq, t.zero, t.nzero, (int)blockIdx.x - t.block0, t.nblocks);
+    else absmax_body<false>(t.x, t.n, t.part, nullptr, nullptr, 0, (int)blockIdx.x - t.block0, t.nblocks);
 }
 
 int absmax_blocks(size_t n) {

@@ -131,6 +131,8 @@ class LayerStep:
         self._k_fwd_fused = B.bind(lib.int8t_conv_fwd_fused, C.byref(self.desc), p(self.x), None, p(self.wq), p(self.sw), p(self.y),
                                    p(self.y_acc), p(self.xq), p(self.sx), p(self.ws_x), nb(self.ws_x))
         self._k_prepare = B.bind(lib.int8t_dsgc_prepare, p(self.dy), n_y, p(self.ws_dy), nb(self.ws_dy))
+        self._k_xw_prepare = B.bind(lib.int8t_quantize_batch_prepare, 2, self._items_xw, p(self.ws_xw), nb(self.ws_xw),
+                                    p(self.dy), n_y, p(self.ws_dy), nb(self.ws_dy))
         d = C.byref(self.desc)
         self._k_fwd = B.bind(lib.int8t_conv_fwd, d, p(self.xq), p(self.sx), p(self.wq), p(self.sw), p(self.y), p(self.y_acc),
                              p(self.ws_fwd), nb(self.ws_fwd))
@@ -235,10 +237,13 @@ class LayerStep:
                 if search:
                     self._k_clip(seed, sp)
                 self._k_qdy(seed, sp)
+            elif search:
+                # max|.| of a, W and g_z (with the sums the search needs) in one launch, then the sweep
+                self._k_xw_prepare(sp)
+                self._k_search(seed, sp)
+                self._k_qdy(seed, sp)
             else:
                 self._k_xw(sp)
-                if search:
-                    self._k_clip(seed, sp)
                 self._k_qdy(seed, sp)
             if self.fused_fwd:
                 self._k_fwd_fused(sp)
@@ -259,9 +264,13 @@ class LayerStep:
                 self._items_xwg[2].seed = seed
                 self._k_xwg(mp)
             else:
-                (self._k_w if self.fused_fwd else self._k_xw)(mp)
-                if search:
-                    self._k_clip(seed, mp)
+                if search and not self.fused_fwd:
+                    self._k_xw_prepare(mp)
+                    self._k_search(seed, mp)
+                else:
+                    (self._k_w if self.fused_fwd else self._k_xw)(mp)
+                    if search:
+                        self._k_clip(seed, mp)
                 self._k_qdy(seed, mp)
                 if self.fused_fwd:
                     self._k_fwd_fused(mp)       # writes the codes of a, which backward-weight reads

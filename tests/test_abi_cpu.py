@@ -186,6 +186,20 @@ def test_quantize_batch_argument_errors(lib):
     items[1].dims[2] = 4
     items[0].q_dev = 0x2004
     assert f(2, items, 0x4000, 1 << 20, None) == 3                 # alignment
+    items[0].q_dev = 0x2000
+    # ... with the first phase of a clip search in the same launch
+    lib.int8t_workspace_bytes.restype = C.c_size_t
+    lib.int8t_workspace_bytes.argtypes = [C.c_int, C.c_void_p, C.c_size_t, C.c_int]
+    need = lib.int8t_workspace_bytes(1, None, 1000, 32)            # INT8T_OP_DSGC
+    g = lib.int8t_quantize_batch_prepare
+    g.restype = C.c_int
+    g.argtypes = [C.c_int, C.POINTER(Item), C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_void_p]
+    assert g(2, items, 0x4000, 1 << 20, None, 1000, 0x100000, need, None) == 1       # g is required
+    assert g(2, items, 0x4000, 1 << 20, 0x8000, 1000, None, 0, None) == 1            # ... and the search's scratch
+    assert g(2, items, 0x4000, 1 << 20, 0x8000, 0, 0x100000, need, None) == 2        # n == 0
+    assert g(2, items, 0x4000, 1 << 20, 0x8004, 1000, 0x100000, need, None) == 3     # alignment of g
+    assert g(2, items, 0x4000, 1 << 20, 0x8000, 1000, 0x100000, need - 1, None) == 4
+    assert g(0, items, 0x4000, 1 << 20, 0x8000, 1000, 0x100000, need, None) == 3     # the batch's own checks still apply
 
 
 def test_dsgc_two_phase_argument_errors(lib):

@@ -229,6 +229,40 @@ def test_dsgc_candidate_counts_and_degenerate():
     assert clip == np.float32(127 * 2.0 ** -12) and abs(d) < 1e-15
 
 
+def test_quantize_batch_prepare_equals_the_two_calls():
+    """The batched quantize call that also runs the first phase of a clip search, followed by the sweep, writes
+    what int8t_quantize_batch and int8t_dsgc_clip write: codes, scales, clip value and every deviation."""
+    r = np.random.RandomState(12)
+    x = r.standard_normal((3, 20, 9, 9)).astype(np.float32)
+    w = (r.standard_normal((24, 20, 3, 3)) * 0.1).astype(np.float32)
+    for n in (5, 4099, 300000):
+        g = (r.standard_t(3, n) * 1e-3).astype(np.float32)
+        gd, ratios = dev(g), dev(inputs.default_ratios(32))
+        outs = []
+        for merged in (False, True):
+            items = []
+            for t, kind in ((x, B.ACT), (w, B.WGT)):
+                items.append((dev(t), t.shape, kind, None, torch.full((B.int8t_code_bytes(t.shape, kind),), 77, dtype=torch.int8, device=DEV),
+                              torch.zeros(1, dtype=torch.float32, device=DEV), RTN, 0))
+            ws = torch.empty(B.int8t_quantize_batch_workspace_bytes(items), dtype=torch.uint8, device=DEV)
+            dws = torch.full((B.int8t_workspace_bytes(B.OP_DSGC, None, n, 32),), 0x5A, dtype=torch.uint8, device=DEV)
+            clip = torch.zeros(1, dtype=torch.float32, device=DEV)
+            d = torch.zeros(1, dtype=torch.float64, device=DEV)
+            da = torch.zeros(32, dtype=torch.float64, device=DEV)
+            if merged:
+                B.int8t_quantize_batch_prepare(items, ws, gd, n, dws)
+                B.int8t_dsgc_search(gd, n, ratios, 32, STO, 9, clip, d, da, dws)
+            else:
+                B.int8t_quantize_batch(items, ws)
+                B.int8t_dsgc_clip(gd, n, ratios, 32, STO, 9, clip, d, da, dws)
+            torch.cuda.synchronize()
+            outs.append([items[0][4], items[0][5], items[1][4], items[1][5], clip, d, da])
+        for a, b in zip(*outs):
+            assert torch.equal(a, b)
+        want = oracle.dsgc(g, inputs.default_ratios(32), mode=STO, seed=9)
+        assert np.float32(outs[1][4].item()) == want["clip"] and abs(outs[1][5].item() - want["deviation"]) < DEV_TOL
+
+
 def test_quantize_batch_equals_single_calls_and_oracle():
     """One batched call = the per-tensor calls, bit for bit (codes, scales), for every layout, with and
     without a supplied clip value."""
